@@ -1,0 +1,165 @@
+/* pb.h -- C ABI of the batch-1 Pipelined Backpropagation (PB) tick engine for
+ * AMD MI355X (gfx950).
+ *
+ * One context simulates an S-stage pipeline on one GPU.  One call of pb_tick
+ * is one time step of the pipeline described in the paper's appendix
+ * "Pipelined Backpropagation": every stage performs the forward pass of one
+ * in-flight sample and the backward pass of another, then every stage that
+ * produced a gradient is updated, without ever draining the pipeline
+ * (Eq. sgdpb).  Stage s sees, on its forward pass, weights that are
+ * D^s = 2(S-1-s) updates older than those its backward pass sees (Eq. wf).
+ * The forward pass runs on Linear-Weight-Predicted weights
+ * w_hat = w - lr*T*v, T = D^s (Eq. lwp_v_form); the update is the
+ * Spike-Compensated momentum step  v <- m v + g ; w <- w - lr (a v + b g)
+ * with a = m^D, b = (1-m^D)/(1-m) (Eqs. gscv, gscw, scd; combination in
+ * Section "Combined Mitigation").
+ *
+ * All functions return 0 (or a non-negative count) on success and a negative
+ * PB_E* code on failure; pb_last_error() then describes the failure.  No
+ * function throws.  Unless said otherwise pointers are HOST pointers.  The
+ * library is not thread-safe per context.
+ */
+#ifndef PB_H_
+#define PB_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pb_ctx pb_ctx;
+
+enum {
+  PB_OK = 0,
+  PB_E_INVALID = -1,      /* bad descriptor / argument                     */
+  PB_E_UNSUPPORTED = -2,  /* valid request the GPU path does not implement  */
+  PB_E_NOMEM = -3,        /* arena too small or device allocation failed    */
+  PB_E_HIP = -4           /* a HIP runtime call failed                      */
+};
+
+/* Operations a pipeline stage is composed of.  A stage holds exactly one
+ * weight layer (LINEAR or CONV2D) -- the paper assigns one layer per stage
+ * and fuses its normalisation, activation and the residual sum into it
+ * (Section "Experiments").  Accepted op order inside a stage:
+ *   [GROUPNORM] [RELU] [GLOBAL_AVGPOOL] (CONV2D|LINEAR)
+ *   [GROUPNORM RELU [MAXPOOL]] [ADD_SKIP] [SOFTMAX_CE]
+ * with at most one GROUPNORM per stage; SOFTMAX_CE only as the last op of the
+ * last stage, where it is mandatory. */
+typedef enum {
+  PB_OP_LINEAR = 0,         /* y = W x + b; x is the flattened (C,H,W) input; cin, cout, has_bias */
+  PB_OP_CONV2D = 1,         /* square kernel k, stride, pad; weight [cout][cin][k][k]; has_bias   */
+  PB_OP_GROUPNORM = 2,      /* groups; cin = cout = channels; biased variance, eps 1e-5, affine   */
+  PB_OP_RELU = 3,           /* max(x,0); derivative 0 at 0                                        */
+  PB_OP_MAXPOOL = 4,        /* window k, stride, pad; gradient to the first maximum (row-major)   */
+  PB_OP_GLOBAL_AVGPOOL = 5, /* mean over H*W                                                      */
+  PB_OP_ADD_SKIP = 6,       /* y += tensor that entered stage skip_from_stage (same sample);      *
+                             * has_proj: through a 1x1 conv cin->cout with the given stride first, *
+                             * whose weight [cout][cin] belongs to this stage                      */
+  PB_OP_SOFTMAX_CE = 7      /* loss = -log softmax(x)[label]; dlogits = softmax - onehot           */
+} pb_op_kind;
+
+typedef struct {
+  int32_t kind;             /* pb_op_kind */
+  int32_t cin, cout;
+  int32_t k, stride, pad;
+  int32_t groups;
+  int32_t has_bias;
+  int32_t skip_from_stage;  /* ADD_SKIP only; must be < index of the stage holding the op */
+  int32_t has_proj;         /* ADD_SKIP only */
+} pb_op;
+
+typedef struct {
+  int32_t n_ops;
+  const pb_op* ops;
+} pb_stage;
+
+typedef struct {
+  int32_t n_stages;
+  const pb_stage* stages;
+  int32_t in_c, in_h, in_w;   /* one sample is in_c*in_h*in_w floats, CHW order */
+  int32_t n_classes;
+  int32_t mitigation;         /* 0 plain delayed SGDM, 1 SC_D, 2 LWP^v_D, 3 SC_D + LWP^v_D */
+  int32_t bwd_weights;        /* 0 backward pass uses current weights (the paper's PB)      */
+  int32_t act_dtype;          /* 0 fp32 activations                                         */
+  int32_t loss_capacity;      /* losses kept (most recent); 0 = 1<<20                       */
+  void* device_arena;         /* DEVICE memory owned by the caller (>= pb_arena_bytes, 256-byte
+                                 aligned) that must outlive the context, or NULL: the library
+                                 allocates and frees its own */
+  size_t arena_bytes;
+  void* stream;               /* hipStream_t to launch on, NULL = the null stream */
+} pb_net_desc;
+
+/* Device bytes pb_init needs for this network (0 on an invalid descriptor). */
+size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays);
+
+/* Build a context.  delays: n_stages entries or NULL for the pipeline's own
+ * D^s = 2(S-1-s) (Eq. wf); other values are rejected with PB_E_UNSUPPORTED
+ * (they cannot be produced by a pipeline that never stalls).  Weights are
+ * initialised on the host from `seed` (Kaiming normal, std sqrt(2/fan_in),
+ * biases 0, GroupNorm scale 1 / shift 0) and uploaded; velocity starts at 0.
+ * The descriptor is copied; the caller may free it afterwards. */
+int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float lr, float momentum,
+            uint64_t seed);
+
+/* One pipeline time step: feeds `sample` (host, in_c*in_h*in_w floats) with
+ * its class label, runs every stage's forward and backward work and the fused
+ * update.  The sample is copied before the call returns; GPU work is
+ * asynchronous on the context's stream. */
+int pb_tick(pb_ctx* ctx, const float* sample, int32_t label);
+
+/* n_ticks time steps fed from a pool resident in DEVICE memory: tick j of
+ * this call consumes item (first_index + j) mod n_pool of samples_dev
+ * ([n_pool][in_c*in_h*in_w] floats) / labels_dev ([n_pool] int32).  Nothing
+ * crosses the host-device boundary.  Asynchronous. */
+int pb_run_resident(pb_ctx* ctx, const float* samples_dev, const int32_t* labels_dev,
+                    int32_t n_pool, int64_t first_index, int64_t n_ticks);
+
+/* Master weights w (not the predicted ones) in canonical order: stage-major;
+ * within a stage: layer weight [cout][cin][kh][kw], bias, projection weight,
+ * GroupNorm scale, shift.  Synchronises the stream.  dst == NULL returns the
+ * number of floats; otherwise at most cap floats are written and the count
+ * returned.  After K ticks stage s has received max(0, K - 2(S-1) + s)
+ * updates. */
+int64_t pb_read_weights(pb_ctx* ctx, float* dst, int64_t cap);
+
+/* Same layout, the velocity v. */
+int64_t pb_read_velocity(pb_ctx* ctx, float* dst, int64_t cap);
+
+/* Loss of sample i at entry i (the sample fed by the i-th tick); after K
+ * ticks max(0, K-S+1) losses exist.  Returns the most recent
+ * min(count, loss_capacity, cap) of them in sample order.  dst == NULL
+ * returns the number available.  Synchronises the stream. */
+int64_t pb_loss_history(pb_ctx* ctx, float* dst, int64_t cap);
+
+int64_t pb_num_params(const pb_ctx* ctx);
+int64_t pb_num_ticks(const pb_ctx* ctx);
+
+/* Launch policy: 0 = one launch per pipeline phase (default), 1 = one launch
+ * per step of every stage (debugging aid; same arithmetic, same results). */
+int pb_set_launch_mode(pb_ctx* ctx, int32_t mode);
+
+/* Kernel timing with HIP events on the context's stream.  pb_profile_begin
+ * starts recording every launch of the following ticks (at most `max_events`
+ * launches), pb_profile_end synchronises and returns, for kernel class
+ * `which` (0 stage phases, 1 fused update, 2 ingest), the number of launches
+ * recorded and their total milliseconds. */
+int pb_profile_begin(pb_ctx* ctx, int32_t max_events);
+int pb_profile_end(pb_ctx* ctx, int32_t which, int64_t* n_launches, double* total_ms);
+
+/* Stand-alone launch of the fused update kernel over caller-provided DEVICE
+ * arrays of n floats (n a multiple of 1024) with one set of coefficients:
+ * v <- m v + g; w <- w - lr (a v + b g); w_hat <- w - lrT v (skipped when
+ * w_hat == NULL).  Used to measure the kernel at sizes beyond the caches. */
+int pb_update_standalone(float* w_dev, float* v_dev, const float* g_dev, float* what_dev, int64_t n,
+                         float lr, float m, float a, float b, float lrT, void* stream);
+
+int pb_sync(pb_ctx* ctx);
+void pb_destroy(pb_ctx* ctx);
+const char* pb_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PB_H_ */

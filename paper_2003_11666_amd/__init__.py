@@ -1,0 +1,3 @@
+"""Batch-1 Pipelined Backpropagation tick engine for MI355X: thin Python
+binding over the C ABI of libpb_hip.so (see include/pb.h)."""
+from .binding import PBEngine, PBError, lib_path, load_library, update_standalone  # noqa: F401

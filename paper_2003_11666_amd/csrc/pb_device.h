@@ -1,0 +1,115 @@
+// Shared between the host runtime and the kernels of the PB tick engine:
+// the step table that describes, once at pb_init, every piece of work a
+// pipeline tick consists of.  Plain data only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pb {
+
+constexpr int BLK = 256;          // threads per workgroup (4 wavefronts of 64)
+constexpr int UPD_CHUNK = 1024;   // floats per workgroup in the update kernel
+constexpr float GN_EPS = 1e-5f;
+
+// A tensor that lives in a ring of `depth` slots.  At tick t the slot in use
+// is (t - lag) mod depth: lag 0 = the slot of the sample handled now, lag D =
+// the sample whose forward pass ran D ticks ago, lag -1 = the slot the next
+// tick will read.  depth 1 = plain buffer.
+struct TRef {
+  float* base;
+  int32_t depth;
+  int32_t stride;   // floats per slot
+  int32_t lag;
+  int32_t pad_;
+};
+
+enum StepKind : int32_t {
+  K_GN_STATS = 0,    // group mean / rstd and per-channel scale, shift
+  K_GAP_FWD = 1,     // mean over H*W of relu(affine(x))
+  K_CONV_FWD = 2,    // convolution / linear forward with fused input transform and skip add
+  K_POST_FWD = 3,    // relu(affine(z)) [+ max-pool]
+  K_CE = 4,          // softmax cross-entropy + dlogits
+  K_GNB_REDUCE = 5,  // GroupNorm backward: per-channel sums (dgamma, dbeta)
+  K_GNB_APPLY = 6,   // GroupNorm backward: elementwise dx
+  K_CONV_BWD_X = 7,  // backward data
+  K_CONV_BWD_W = 8,  // backward weights (+ bias)
+  K_COPY = 9
+};
+
+enum StepFlags : int32_t {
+  F_PRE_AFFINE = 1,   // input is sc[c]*x + sh[c] (GroupNorm folded into the load)
+  F_PRE_RELU = 2,     // then max(.,0)
+  F_BIAS = 4,
+  F_SKIP = 8,         // epilogue adds the skip tensor
+  F_PROJ = 16,        // ... through a 1x1 projection
+  F_POOL = 32,        // max-pool after relu(affine(z))
+  F_DU_BUF = 64,      // GN backward: incoming gradient is a plain buffer
+  F_DU_GAP = 128,     // ... is dpooled[c] / (H*W)
+  F_DU_POOL = 256,    // ... is dY routed through the max-pool
+  F_ADD_SKG = 512,    // epilogue adds the skip-path gradient
+  F_MASK_X = 1024,    // backward data: multiply by [x > 0] (ReLU directly on the stage input)
+  F_GN_RELU = 2048    // GN backward: a ReLU follows the normalisation
+};
+
+struct StepDesc {
+  int32_t kind, stage, first_tick, ntiles;
+  int32_t flags;
+  int32_t C, H, W;          // input tensor of the op
+  int32_t K, OH, OW;        // output tensor of the op
+  int32_t k, stride, pad;
+  int32_t G;                // GroupNorm groups
+  int32_t pk, ps, pp, PH, PW;   // max-pool window / stride / pad / output size
+  int32_t sC, sH, sW, sstride;  // skip tensor dims and projection stride
+  int32_t n;                // generic element count (CE: classes, COPY: floats)
+  int32_t loss_cap, n_stages;
+  TRef x;        // op input (forward) / saved input (backward)
+  TRef st;       // statistics slot: mean[G], rstd[G], sc[C], sh[C]
+  TRef y;        // op output
+  TRef dy;       // incoming gradient
+  TRef dx;       // outgoing gradient
+  TRef skip;     // skip tensor (forward epilogue / projection weight gradient)
+  TRef skg;      // skip-path gradient
+  const float* w;      // weight used by this step (predicted on forward, current on backward)
+  const float* b;
+  const float* wp;
+  const float* gamma;
+  const float* beta;
+  float* gw;           // gradient outputs
+  float* gb;
+  float* ggamma;
+  float* gbeta;
+  float* part;         // per-channel partial sums of the GN backward
+  float* loss_log;
+  int32_t* labels;     // label ring [n_stages]
+};
+
+// State that changes from tick to tick lives in device memory so that a
+// recorded launch sequence can be replayed unchanged.
+struct Globals {
+  int32_t t_base;      // tick index = t_base + k (k = launch argument)
+  int32_t idx_base;    // pool item = (idx_base + k) mod n_pool
+  int32_t n_pool;
+  int32_t pad_;
+  const float* pool;
+  const int32_t* pool_labels;
+};
+
+struct UpdSeg {       // per stage constants of the fused update
+  float a, b, lrT;
+  int32_t first_tick;
+};
+
+// ---- launch wrappers implemented in pb_kernels.hip ----
+void launch_phase(const StepDesc* steps_dev, const int32_t* tile_prefix_dev, int n_steps,
+                  int total_tiles, const Globals* G, int k, hipStream_t s);
+void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,
+                   int n_stages, const Globals* G, int k, hipStream_t s);
+void launch_update(float* w, float* v, const float* g, float* what, const int32_t* chunk_stage,
+                   const UpdSeg* segs, int n_chunks, float lr, float m, const Globals* G, int k,
+                   hipStream_t s);
+void launch_update_flat(float* w, float* v, const float* g, float* what, int64_t n, float lr, float m,
+                        float a, float b, float lrT, hipStream_t s);
+void launch_advance(Globals* G, int dt, int didx, hipStream_t s);
+void launch_set_globals(Globals* G, Globals val, hipStream_t s);
+
+}  // namespace pb

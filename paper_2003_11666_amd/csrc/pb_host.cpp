@@ -1,0 +1,964 @@
+// Host runtime of the PB tick engine: descriptor validation, arena planning,
+// step-table compilation, the C ABI declared in include/pb.h.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <string>
+#include <vector>
+
+#include "../../include/pb.h"
+#include "pb_device.h"
+
+using namespace pb;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                    \
+  do {                                                                                   \
+    hipError_t e_ = (expr);                                                              \
+    if (e_ != hipSuccess)                                                                \
+      return fail(PB_E_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+  } while (0)
+
+// ---------------------------------------------------------------- stage model
+struct Stage {
+  bool pre_gn = false, pre_relu = false, gap = false, post_gn = false, pool = false, add = false,
+       proj = false, ce = false, is_conv = false, has_bias = false;
+  int G = 0;                       // GroupNorm groups
+  int Cin = 0, Hin = 0, Win = 0;   // stage input
+  int C = 0, H = 0, W = 0;         // main op input (after optional GAP / flatten)
+  int K = 0, OH = 0, OW = 0;       // main op output
+  int k = 1, stride = 1, pad = 0;
+  int pk = 0, ps = 0, pp = 0, PH = 0, PW = 0;
+  int Cout = 0, Hout = 0, Wout = 0;   // stage output
+  int skip_from = -1, sstride = 1, sC = 0, sH = 0, sW = 0;
+  int tap_dist = 0;                // >0: a later stage (this + tap_dist) adds this stage's input
+  int D = 0;
+  // parameter offsets in the padded flat arena (floats), -1 = absent
+  int64_t off = 0, padded = 0, n_params = 0;
+  int64_t o_w = -1, o_b = -1, o_wp = -1, o_gamma = -1, o_beta = -1;
+  int64_t n_w = 0, n_b = 0, n_wp = 0, n_gn = 0;
+  int fan_w = 0, fan_wp = 0;
+  int in_elems() const { return Cin * Hin * Win; }
+  int out_elems() const { return Cout * Hout * Wout; }
+  int z_elems() const { return K * OH * OW; }
+  int gnC() const { return pre_gn ? Cin : K; }
+};
+
+int parse_net(const pb_net_desc* net, std::vector<Stage>& out) {
+  if (!net || net->n_stages <= 0 || !net->stages) return fail(PB_E_INVALID, "empty network");
+  if (net->in_c <= 0 || net->in_h <= 0 || net->in_w <= 0 || net->n_classes <= 0)
+    return fail(PB_E_INVALID, "bad input dimensions");
+  if (net->mitigation < 0 || net->mitigation > 3) return fail(PB_E_INVALID, "mitigation must be 0..3");
+  if (net->bwd_weights != 0) return fail(PB_E_UNSUPPORTED, "bwd_weights=%d (weight stashing) not implemented", net->bwd_weights);
+  if (net->act_dtype != 0) return fail(PB_E_UNSUPPORTED, "act_dtype=%d not implemented", net->act_dtype);
+  const int S = net->n_stages;
+  out.assign(S, Stage());
+  int C = net->in_c, H = net->in_h, W = net->in_w;
+  for (int s = 0; s < S; ++s) {
+    Stage& st = out[s];
+    const pb_stage& ps = net->stages[s];
+    if (ps.n_ops <= 0 || !ps.ops) return fail(PB_E_INVALID, "stage %d has no ops", s);
+    st.Cin = C; st.Hin = H; st.Win = W;
+    st.D = 2 * (S - 1 - s);
+    int i = 0;
+    const int n = ps.n_ops;
+    auto kind = [&](int j) { return j < n ? ps.ops[j].kind : -1; };
+    if (kind(i) == PB_OP_GROUPNORM) {
+      const pb_op& o = ps.ops[i];
+      if (o.cin != C || o.groups <= 0 || C % o.groups) return fail(PB_E_INVALID, "stage %d: GroupNorm channels/groups mismatch", s);
+      st.pre_gn = true; st.G = o.groups; ++i;
+    }
+    if (kind(i) == PB_OP_RELU) { st.pre_relu = true; ++i; }
+    if (kind(i) == PB_OP_GLOBAL_AVGPOOL) {
+      if (!st.pre_gn) return fail(PB_E_UNSUPPORTED, "stage %d: global average pool needs a GroupNorm before it", s);
+      st.gap = true; ++i;
+    }
+    if (kind(i) != PB_OP_CONV2D && kind(i) != PB_OP_LINEAR)
+      return fail(PB_E_INVALID, "stage %d: expected the weight layer at op %d", s, i);
+    {
+      const pb_op& o = ps.ops[i];
+      st.is_conv = (o.kind == PB_OP_CONV2D);
+      st.has_bias = o.has_bias != 0;
+      if (st.is_conv) {
+        if (st.gap) return fail(PB_E_UNSUPPORTED, "stage %d: conv after global average pool", s);
+        if (o.cin != C || o.cout <= 0 || o.k <= 0 || o.stride <= 0 || o.pad < 0 || o.pad >= o.k)
+          return fail(PB_E_INVALID, "stage %d: bad conv parameters", s);
+        st.C = C; st.H = H; st.W = W; st.K = o.cout; st.k = o.k; st.stride = o.stride; st.pad = o.pad;
+        st.OH = (H + 2 * o.pad - o.k) / o.stride + 1;
+        st.OW = (W + 2 * o.pad - o.k) / o.stride + 1;
+        if (st.OH <= 0 || st.OW <= 0) return fail(PB_E_INVALID, "stage %d: conv output is empty", s);
+      } else {
+        const int flat = st.gap ? C : C * H * W;
+        if (o.cin != flat || o.cout <= 0) return fail(PB_E_INVALID, "stage %d: linear cin %d != input size %d", s, o.cin, flat);
+        if (st.pre_gn && !st.gap && H * W > 1)
+          return fail(PB_E_UNSUPPORTED, "stage %d: GroupNorm before a flattening linear layer", s);
+        st.C = flat; st.H = 1; st.W = 1; st.K = o.cout; st.k = 1; st.stride = 1; st.pad = 0;
+        st.OH = st.OW = 1;
+      }
+      st.fan_w = st.C * st.k * st.k;
+      ++i;
+    }
+    st.Cout = st.K; st.Hout = st.OH; st.Wout = st.OW;
+    if (kind(i) == PB_OP_GROUPNORM) {
+      if (st.pre_gn) return fail(PB_E_UNSUPPORTED, "stage %d: two GroupNorms in one stage", s);
+      const pb_op& o = ps.ops[i];
+      if (o.cin != st.K || o.groups <= 0 || st.K % o.groups) return fail(PB_E_INVALID, "stage %d: GroupNorm channels/groups mismatch", s);
+      if (kind(i + 1) != PB_OP_RELU) return fail(PB_E_UNSUPPORTED, "stage %d: GroupNorm after the layer must be followed by ReLU", s);
+      st.post_gn = true; st.G = o.groups; i += 2;
+      if (kind(i) == PB_OP_MAXPOOL) {
+        const pb_op& p = ps.ops[i];
+        if (p.k <= 0 || p.stride <= 0 || p.pad < 0 || 2 * p.pad > p.k) return fail(PB_E_INVALID, "stage %d: bad max-pool", s);
+        st.pool = true; st.pk = p.k; st.ps = p.stride; st.pp = p.pad;
+        st.PH = (st.OH + 2 * p.pad - p.k) / p.stride + 1;
+        st.PW = (st.OW + 2 * p.pad - p.k) / p.stride + 1;
+        if (st.PH <= 0 || st.PW <= 0) return fail(PB_E_INVALID, "stage %d: pool output is empty", s);
+        st.Hout = st.PH; st.Wout = st.PW;
+        ++i;
+      }
+    }
+    if (kind(i) == PB_OP_ADD_SKIP) {
+      const pb_op& o = ps.ops[i];
+      if (st.post_gn) return fail(PB_E_UNSUPPORTED, "stage %d: skip add after a post-layer GroupNorm", s);
+      const int a = o.skip_from_stage;
+      if (a < 0 || a >= s) return fail(PB_E_INVALID, "stage %d: skip_from_stage %d out of range", s, a);
+      if (out[a].tap_dist) return fail(PB_E_UNSUPPORTED, "stage %d tapped twice", a);
+      if (s - a > out[a].D) return fail(PB_E_INVALID, "stage %d: skip source too far", s);
+      st.add = true; st.skip_from = a; st.proj = o.has_proj != 0;
+      st.sC = out[a].Cin; st.sH = out[a].Hin; st.sW = out[a].Win;
+      st.sstride = st.proj ? std::max(1, (int)o.stride) : 1;
+      if (st.proj) {
+        if (o.cin != st.sC || o.cout != st.K) return fail(PB_E_INVALID, "stage %d: projection channels mismatch", s);
+        if ((st.sH - 1) / st.sstride + 1 != st.OH || (st.sW - 1) / st.sstride + 1 != st.OW)
+          return fail(PB_E_INVALID, "stage %d: projection output size mismatch", s);
+        st.fan_wp = st.sC;
+      } else if (st.sC != st.K || st.sH != st.OH || st.sW != st.OW) {
+        return fail(PB_E_INVALID, "stage %d: identity skip shape mismatch", s);
+      }
+      out[a].tap_dist = s - a;
+      ++i;
+    }
+    if (kind(i) == PB_OP_SOFTMAX_CE) {
+      if (s != S - 1) return fail(PB_E_INVALID, "stage %d: loss only in the last stage", s);
+      if (st.post_gn || st.add) return fail(PB_E_UNSUPPORTED, "loss stage with post-norm or skip");
+      if (st.K != net->n_classes || st.OH * st.OW != 1) return fail(PB_E_INVALID, "logits size %d != n_classes %d", st.K * st.OH * st.OW, net->n_classes);
+      st.ce = true; ++i;
+    }
+    if (i != n) return fail(PB_E_UNSUPPORTED, "stage %d: op %d (kind %d) does not fit the stage pattern", s, i, kind(i));
+    if (s == S - 1 && !st.ce) return fail(PB_E_INVALID, "last stage must end with the loss");
+    if (s == 0 && st.pre_gn) return fail(PB_E_UNSUPPORTED, "GroupNorm directly on the network input");
+    C = st.Cout; H = st.Hout; W = st.Wout;
+  }
+  // parameter layout, canonical order inside a stage, stages padded to UPD_CHUNK
+  int64_t off = 0;
+  for (Stage& st : out) {
+    st.off = off;
+    int64_t o = 0;
+    st.n_w = (int64_t)st.K * st.C * st.k * st.k; st.o_w = o; o += st.n_w;
+    if (st.has_bias) { st.n_b = st.K; st.o_b = o; o += st.n_b; }
+    if (st.proj) { st.n_wp = (int64_t)st.K * st.sC; st.o_wp = o; o += st.n_wp; }
+    if (st.pre_gn || st.post_gn) { st.n_gn = st.gnC(); st.o_gamma = o; o += st.n_gn; st.o_beta = o; o += st.n_gn; }
+    st.n_params = o;
+    st.padded = (o + UPD_CHUNK - 1) / UPD_CHUNK * UPD_CHUNK;
+    off += st.padded;
+  }
+  return PB_OK;
+}
+
+int check_delays(const std::vector<Stage>& st, const int32_t* delays) {
+  if (!delays) return PB_OK;
+  for (size_t s = 0; s < st.size(); ++s) {
+    if (delays[s] < 0) return fail(PB_E_INVALID, "delay of stage %zu is negative", s);
+    if (delays[s] != st[s].D)
+      return fail(PB_E_UNSUPPORTED, "delay %d of stage %zu differs from the pipeline's 2(S-1-s)=%d", delays[s], s, st[s].D);
+  }
+  return PB_OK;
+}
+
+// ------------------------------------------------------------------ arena
+struct Plan {
+  int64_t total = 0;   // floats
+  int64_t alloc(int64_t n) {
+    int64_t o = total;
+    total += (n + 63) / 64 * 64;
+    return o;
+  }
+};
+
+struct StageBufs {
+  int64_t xring = -1, prest = -1, pooled = -1, zring = -1, postst = -1, gradbox = -1, skg = -1,
+          da = -1, dz = -1, part = -1, logits = -1, dlogits = -1;
+  int st_stride = 0;
+};
+
+struct Layout {
+  int64_t P = 0;                      // padded parameter count
+  int64_t w = 0, v = 0, g = 0, what = -1;
+  std::vector<StageBufs> sb;
+  int64_t staging = 0, labels = 0, loss = 0, globals = 0, zero = 0;
+  int64_t steps = 0, prefix = 0, chunk_stage = 0, segs = 0;   // filled after step compilation
+  int64_t total = 0;
+};
+
+int st_stride_of(const Stage& s) { return (2 * s.G + 2 * s.gnC() + 63) / 64 * 64; }
+
+void plan_arena(const std::vector<Stage>& st, bool lwp, int loss_cap, Layout& L, Plan& pl) {
+  const int S = (int)st.size();
+  L.P = 0;
+  for (const Stage& s : st) L.P += s.padded;
+  L.w = pl.alloc(L.P); L.v = pl.alloc(L.P); L.g = pl.alloc(L.P);
+  L.what = lwp ? pl.alloc(L.P) : -1;
+  L.sb.assign(S, StageBufs());
+  for (int s = 0; s < S; ++s) {
+    const Stage& a = st[s];
+    StageBufs& b = L.sb[s];
+    b.xring = pl.alloc((int64_t)(a.D + 2) * a.in_elems());
+    if (a.pre_gn || a.post_gn) b.st_stride = st_stride_of(a);
+    if (a.pre_gn) b.prest = pl.alloc((int64_t)(a.D + 1) * b.st_stride);
+    if (a.gap) b.pooled = pl.alloc((int64_t)(a.D + 1) * a.C);
+    if (a.post_gn) {
+      b.zring = pl.alloc((int64_t)(a.D + 1) * a.z_elems());
+      b.postst = pl.alloc((int64_t)(a.D + 1) * b.st_stride);
+      b.dz = pl.alloc(a.z_elems());
+    }
+    if (a.pre_gn || a.post_gn) b.part = pl.alloc(2 * a.gnC());
+    if (a.pre_gn) b.da = pl.alloc(a.gap ? a.C : a.in_elems());
+    if (s < S - 1) b.gradbox = pl.alloc(2 * (int64_t)a.out_elems());
+    if (a.tap_dist) b.skg = pl.alloc((int64_t)(a.tap_dist + 1) * a.in_elems());
+    if (a.ce) { b.logits = pl.alloc(a.K); b.dlogits = pl.alloc(a.K); }
+  }
+  L.staging = pl.alloc(st[0].in_elems());
+  L.labels = pl.alloc(S);
+  L.loss = pl.alloc(loss_cap);
+  L.globals = pl.alloc(64);
+  L.zero = pl.alloc(64);
+}
+
+// ---------------------------------------------------------------- context
+struct Phase {
+  std::vector<int> step_idx;       // indices into steps, in launch order
+  int first = 0, count = 0, tiles = 0;
+};
+
+}  // namespace
+
+struct pb_ctx {
+  std::vector<Stage> st;
+  int S = 0;
+  int mitigation = 3;
+  float lr = 0, m = 0;
+  int loss_cap = 0;
+  int64_t n_params = 0;
+  Layout L;
+  float* arena = nullptr;
+  bool own_arena = false;
+  hipStream_t stream = nullptr;
+  int64_t ticks = 0;
+  int launch_mode = 0;
+  std::vector<StepDesc> steps;         // sorted by phase
+  std::vector<int32_t> prefix;         // per step: first tile within its phase
+  std::vector<Phase> phases;
+  int n_chunks = 0;
+  // device views
+  StepDesc* steps_dev = nullptr;
+  int32_t* prefix_dev = nullptr;
+  int32_t* chunk_stage_dev = nullptr;
+  UpdSeg* segs_dev = nullptr;
+  Globals* globals_dev = nullptr;
+  int32_t* zero_dev = nullptr;
+  int32_t* labels_dev = nullptr;
+  // resident-pool bookkeeping
+  const float* pool = nullptr;
+  const int32_t* pool_labels = nullptr;
+  int n_pool = 0;
+  int idx_base = 0;
+  // profiling
+  bool profiling = false;
+  int max_events = 0;
+  struct Ev { hipEvent_t a, b; int cls; };
+  std::vector<Ev> evs;
+  std::vector<Ev> ev_pool;
+  float* f(int64_t off) const { return arena + off; }
+};
+
+namespace {
+
+TRef ring(const pb_ctx* c, int64_t off, int depth, int stride, int lag) {
+  TRef r;
+  r.base = c->f(off); r.depth = depth; r.stride = stride; r.lag = lag; r.pad_ = 0;
+  return r;
+}
+
+StepDesc blank(int kind, int stage, int first_tick) {
+  StepDesc d;
+  memset(&d, 0, sizeof d);
+  d.kind = kind; d.stage = stage; d.first_tick = first_tick;
+  d.x.depth = d.st.depth = d.y.depth = d.dy.depth = d.dx.depth = d.skip.depth = d.skg.depth = 1;
+  return d;
+}
+
+int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+int bwd_w_tiles(int K, int C, int k, int P, bool bias) {
+  const int64_t nW = (int64_t)K * C * k * k;
+  const int per = P > 16 ? BLK / 64 : BLK;
+  return cdiv(nW, per) + (bias ? cdiv(K, per) : 0);
+}
+
+// Compile the network into the step table.  Every step carries the phase it
+// may run in: steps of one stage's forward (or backward) chain depend on each
+// other and get consecutive phases; different stages and the two passes of
+// one stage are independent inside a tick (they work on different samples and
+// read the start-of-tick weights), except for the last stage whose backward
+// pass consumes the loss gradient of the same tick.
+void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
+  const int S = c->S;
+  const Layout& L = c->L;
+  const bool lwp = L.what >= 0;
+  for (int s = 0; s < S; ++s) {
+    const Stage& a = c->st[s];
+    const StageBufs& b = L.sb[s];
+    const int D = a.D;
+    const float* wf = c->f((lwp ? L.what : L.w) + a.off);   // forward (predicted) parameters
+    const float* wb = c->f(L.w + a.off);                    // backward (current) parameters
+    float* gr = c->f(L.g + a.off);
+    const int t_f = s, t_b = 2 * (S - 1) - s;
+    const TRef x_f = ring(c, b.xring, D + 2, a.in_elems(), 0);
+    const TRef x_b = ring(c, b.xring, D + 2, a.in_elems(), D);
+    TRef y_out;   // where the stage output goes
+    if (s < S - 1) y_out = ring(c, L.sb[s + 1].xring, c->st[s + 1].D + 2, a.out_elems(), -1);
+    else y_out = ring(c, b.logits, 1, a.K, 0);
+    int ph = 0;
+    // ------------------------------------------------------------ forward
+    if (a.pre_gn) {
+      StepDesc d = blank(K_GN_STATS, s, t_f);
+      d.C = a.Cin; d.H = a.Hin; d.W = a.Win; d.G = a.G;
+      d.x = x_f; d.st = ring(c, b.prest, D + 1, b.st_stride, 0);
+      d.gamma = wf + a.o_gamma; d.beta = wf + a.o_beta;
+      d.ntiles = a.G;
+      out.push_back({ph++, d});
+    }
+    if (a.gap) {
+      StepDesc d = blank(K_GAP_FWD, s, t_f);
+      d.C = a.Cin; d.H = a.Hin; d.W = a.Win; d.G = a.G;
+      d.flags = F_PRE_AFFINE | (a.pre_relu ? F_PRE_RELU : 0);
+      d.x = x_f; d.st = ring(c, b.prest, D + 1, b.st_stride, 0);
+      d.y = ring(c, b.pooled, D + 1, a.C, 0);
+      d.ntiles = a.Cin;
+      out.push_back({ph++, d});
+    }
+    {
+      StepDesc d = blank(K_CONV_FWD, s, t_f);
+      d.C = a.C; d.H = a.H; d.W = a.W; d.K = a.K; d.OH = a.OH; d.OW = a.OW;
+      d.k = a.k; d.stride = a.stride; d.pad = a.pad; d.G = a.G;
+      if (a.gap) {
+        d.x = ring(c, b.pooled, D + 1, a.C, 0);
+      } else {
+        d.x = x_f;
+        if (a.pre_gn) { d.flags |= F_PRE_AFFINE; d.st = ring(c, b.prest, D + 1, b.st_stride, 0); }
+        if (a.pre_relu) d.flags |= F_PRE_RELU;
+      }
+      d.w = wf + a.o_w;
+      if (a.has_bias) { d.flags |= F_BIAS; d.b = wf + a.o_b; }
+      if (a.post_gn) {
+        d.y = ring(c, b.zring, D + 1, a.z_elems(), 0);
+      } else {
+        d.y = y_out;
+        if (a.add) {
+          const int A = a.skip_from;
+          d.flags |= F_SKIP;
+          d.skip = ring(c, L.sb[A].xring, c->st[A].D + 2, c->st[A].in_elems(), s - A);
+          d.sC = a.sC; d.sH = a.sH; d.sW = a.sW; d.sstride = a.sstride;
+          if (a.proj) { d.flags |= F_PROJ; d.wp = wf + a.o_wp; }
+        }
+      }
+      d.ntiles = cdiv((int64_t)a.K * a.OH * a.OW, BLK);
+      out.push_back({ph++, d});
+    }
+    if (a.post_gn) {
+      StepDesc d = blank(K_GN_STATS, s, t_f);
+      d.C = a.K; d.H = a.OH; d.W = a.OW; d.G = a.G;
+      d.x = ring(c, b.zring, D + 1, a.z_elems(), 0);
+      d.st = ring(c, b.postst, D + 1, b.st_stride, 0);
+      d.gamma = wf + a.o_gamma; d.beta = wf + a.o_beta;
+      d.ntiles = a.G;
+      out.push_back({ph++, d});
+      StepDesc e = blank(K_POST_FWD, s, t_f);
+      e.C = a.K; e.H = a.OH; e.W = a.OW; e.G = a.G;
+      e.x = d.x; e.st = d.st; e.y = y_out;
+      if (a.pool) { e.flags |= F_POOL; e.pk = a.pk; e.ps = a.ps; e.pp = a.pp; e.PH = a.PH; e.PW = a.PW; }
+      e.ntiles = cdiv(a.out_elems(), BLK);
+      out.push_back({ph++, e});
+    }
+    if (a.ce) {
+      StepDesc d = blank(K_CE, s, t_f);
+      d.n = a.K; d.n_stages = S; d.loss_cap = c->loss_cap;
+      d.x = ring(c, b.logits, 1, a.K, 0);
+      d.dx = ring(c, b.dlogits, 1, a.K, 0);
+      d.loss_log = c->f(L.loss);
+      d.labels = c->labels_dev;
+      d.ntiles = 1;
+      out.push_back({ph++, d});
+    }
+    // ----------------------------------------------------------- backward
+    int pb = (s == S - 1) ? ph : 0;
+    const TRef dy_src = (s == S - 1) ? ring(c, b.dlogits, 1, a.K, 0)
+                                     : ring(c, b.gradbox, 2, a.out_elems(), 0);
+    TRef dz_src = dy_src;
+    if (a.post_gn) {
+      StepDesc d = blank(K_GNB_REDUCE, s, t_b);
+      d.C = a.K; d.H = a.OH; d.W = a.OW; d.G = a.G;
+      d.flags = F_GN_RELU | (a.pool ? F_DU_POOL : F_DU_BUF);
+      if (a.pool) { d.pk = a.pk; d.ps = a.ps; d.pp = a.pp; d.PH = a.PH; d.PW = a.PW; }
+      d.x = ring(c, b.zring, D + 1, a.z_elems(), D);
+      d.st = ring(c, b.postst, D + 1, b.st_stride, D);
+      d.dy = dy_src;
+      d.gamma = wb + a.o_gamma;
+      d.ggamma = gr + a.o_gamma; d.gbeta = gr + a.o_beta;
+      d.part = c->f(b.part);
+      d.ntiles = a.K;
+      out.push_back({pb++, d});
+      StepDesc e = d;
+      e.kind = K_GNB_APPLY;
+      e.dx = ring(c, b.dz, 1, a.z_elems(), 0);
+      e.ntiles = cdiv(a.z_elems(), BLK);
+      out.push_back({pb++, e});
+      dz_src = e.dx;
+    }
+    {   // weight gradient of the main layer
+      StepDesc d = blank(K_CONV_BWD_W, s, t_b);
+      d.C = a.C; d.H = a.H; d.W = a.W; d.K = a.K; d.OH = a.OH; d.OW = a.OW;
+      d.k = a.k; d.stride = a.stride; d.pad = a.pad; d.G = a.G;
+      if (a.gap) {
+        d.x = ring(c, b.pooled, D + 1, a.C, D);
+      } else {
+        d.x = x_b;
+        if (a.pre_gn) { d.flags |= F_PRE_AFFINE; d.st = ring(c, b.prest, D + 1, b.st_stride, D); }
+        if (a.pre_relu) d.flags |= F_PRE_RELU;
+      }
+      d.dy = dz_src;
+      d.gw = gr + a.o_w;
+      if (a.has_bias) { d.flags |= F_BIAS; d.gb = gr + a.o_b; }
+      d.ntiles = bwd_w_tiles(a.K, a.C, a.k, a.OH * a.OW, a.has_bias);
+      out.push_back({pb, d});
+    }
+    if (s > 0) {   // data gradient of the main layer
+      StepDesc d = blank(K_CONV_BWD_X, s, t_b);
+      d.C = a.C; d.H = a.H; d.W = a.W; d.K = a.K; d.OH = a.OH; d.OW = a.OW;
+      d.k = a.k; d.stride = a.stride; d.pad = a.pad;
+      d.dy = dz_src;
+      d.w = wb + a.o_w;
+      if (a.pre_gn) {
+        d.dx = ring(c, b.da, 1, a.gap ? a.C : a.in_elems(), 0);
+      } else {
+        d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
+        if (a.pre_relu) { d.flags |= F_MASK_X; d.x = x_b; }
+        if (a.tap_dist) { d.flags |= F_ADD_SKG; d.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
+      }
+      d.ntiles = cdiv((int64_t)a.C * a.H * a.W, BLK);
+      out.push_back({pb, d});
+    }
+    if (a.add) {   // skip path: projection weight gradient and the gradient sent to the tap stage
+      const int A = a.skip_from;
+      const Stage& ta = c->st[A];
+      const TRef skg_w = ring(c, L.sb[A].skg, ta.tap_dist + 1, ta.in_elems(), 0);
+      if (a.proj) {
+        StepDesc d = blank(K_CONV_BWD_W, s, t_b);
+        d.C = a.sC; d.H = a.sH; d.W = a.sW; d.K = a.K; d.OH = a.OH; d.OW = a.OW;
+        d.k = 1; d.stride = a.sstride; d.pad = 0;
+        d.x = ring(c, L.sb[A].xring, ta.D + 2, ta.in_elems(), D + (s - A));
+        d.dy = dy_src;
+        d.gw = gr + a.o_wp;
+        d.ntiles = bwd_w_tiles(a.K, a.sC, 1, a.OH * a.OW, false);
+        out.push_back({pb, d});
+        StepDesc e = blank(K_CONV_BWD_X, s, t_b);
+        e.C = a.sC; e.H = a.sH; e.W = a.sW; e.K = a.K; e.OH = a.OH; e.OW = a.OW;
+        e.k = 1; e.stride = a.sstride; e.pad = 0;
+        e.dy = dy_src;
+        e.w = wb + a.o_wp;
+        e.dx = skg_w;
+        e.ntiles = cdiv(ta.in_elems(), BLK);
+        out.push_back({pb, e});
+      } else {
+        StepDesc d = blank(K_COPY, s, t_b);
+        d.n = ta.in_elems();
+        d.dy = dy_src; d.dx = skg_w;
+        d.ntiles = cdiv(d.n, BLK);
+        out.push_back({pb, d});
+      }
+    }
+    ++pb;
+    if (a.pre_gn) {
+      StepDesc d = blank(K_GNB_REDUCE, s, t_b);
+      d.C = a.Cin; d.H = a.Hin; d.W = a.Win; d.G = a.G;
+      d.flags = (a.pre_relu ? F_GN_RELU : 0) | (a.gap ? F_DU_GAP : F_DU_BUF);
+      d.x = x_b;
+      d.st = ring(c, b.prest, D + 1, b.st_stride, D);
+      d.dy = ring(c, b.da, 1, a.gap ? a.C : a.in_elems(), 0);
+      d.gamma = wb + a.o_gamma;
+      d.ggamma = gr + a.o_gamma; d.gbeta = gr + a.o_beta;
+      d.part = c->f(b.part);
+      d.ntiles = a.Cin;
+      out.push_back({pb++, d});
+      if (s > 0) {
+        StepDesc e = d;
+        e.kind = K_GNB_APPLY;
+        e.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
+        if (a.tap_dist) { e.flags |= F_ADD_SKG; e.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
+        e.ntiles = cdiv(a.in_elems(), BLK);
+        out.push_back({pb++, e});
+      }
+    }
+  }
+}
+
+// Host-side audit of the step table: every tensor reference a kernel will
+// dereference must hold at least the elements that kernel's indexing reaches
+// and must lie inside the arena.  Runs at pb_init and pb_arena_bytes, i.e.
+// before anything is launched.
+int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>& steps, int64_t arena_floats) {
+  const float* lo = c->f(0);
+  const float* hi = c->f(arena_floats);
+  auto ref_ok = [&](const TRef& r, int64_t need) {
+    if (r.depth < 1 || r.stride < need) return false;
+    return r.base >= lo && r.base + (int64_t)r.depth * r.stride <= hi;
+  };
+  auto ptr_ok = [&](const float* p, int64_t need) { return p >= lo && p + need <= hi; };
+  int idx = 0;
+  for (const auto& pr : steps) {
+    const StepDesc& d = pr.second;
+    const int64_t in = (int64_t)d.C * d.H * d.W, outn = (int64_t)d.K * d.OH * d.OW;
+    const int64_t stn = 2 * d.G + 2 * d.C;
+    bool ok = d.ntiles > 0;
+    switch (d.kind) {
+      case K_GN_STATS:
+        ok = ok && d.G > 0 && d.C % d.G == 0 && d.ntiles == d.G && ref_ok(d.x, in) && ref_ok(d.st, stn) &&
+             ptr_ok(d.gamma, d.C) && ptr_ok(d.beta, d.C);
+        break;
+      case K_GAP_FWD:
+        ok = ok && d.ntiles == d.C && ref_ok(d.x, in) && ref_ok(d.y, d.C) &&
+             (!(d.flags & F_PRE_AFFINE) || ref_ok(d.st, stn));
+        break;
+      case K_CONV_FWD:
+        ok = ok && (int64_t)d.ntiles * BLK >= outn && ref_ok(d.x, in) && ref_ok(d.y, outn) &&
+             ptr_ok(d.w, outn / (d.OH * d.OW) * d.C * d.k * d.k) &&
+             (!(d.flags & F_PRE_AFFINE) || ref_ok(d.st, stn)) && (!(d.flags & F_BIAS) || ptr_ok(d.b, d.K));
+        if (d.flags & F_SKIP) {
+          if (d.flags & F_PROJ)
+            ok = ok && ref_ok(d.skip, (int64_t)d.sC * d.sH * d.sW) && ptr_ok(d.wp, (int64_t)d.K * d.sC) &&
+                 (d.OH - 1) * d.sstride < d.sH && (d.OW - 1) * d.sstride < d.sW;
+          else
+            ok = ok && ref_ok(d.skip, outn);
+        }
+        break;
+      case K_POST_FWD:
+        ok = ok && ref_ok(d.x, in) && ref_ok(d.st, stn) &&
+             ref_ok(d.y, (d.flags & F_POOL) ? (int64_t)d.C * d.PH * d.PW : in);
+        break;
+      case K_CE:
+        ok = ok && d.n > 0 && ref_ok(d.x, d.n) && ref_ok(d.dx, d.n) && ptr_ok(d.loss_log, d.loss_cap) &&
+             ptr_ok((const float*)d.labels, d.n_stages);
+        break;
+      case K_GNB_REDUCE:
+      case K_GNB_APPLY: {
+        const int64_t dyn = (d.flags & F_DU_BUF) ? in : (d.flags & F_DU_GAP) ? d.C : (int64_t)d.C * d.PH * d.PW;
+        ok = ok && d.G > 0 && d.C % d.G == 0 && ref_ok(d.x, in) && ref_ok(d.st, stn) && ref_ok(d.dy, dyn) &&
+             ptr_ok(d.part, 2 * d.C) && ptr_ok(d.gamma, d.C);
+        if (d.kind == K_GNB_REDUCE) ok = ok && d.ntiles == d.C && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C);
+        else ok = ok && (int64_t)d.ntiles * BLK >= in && ref_ok(d.dx, in) && (!(d.flags & F_ADD_SKG) || ref_ok(d.skg, in));
+        break;
+      }
+      case K_CONV_BWD_X:
+        ok = ok && (int64_t)d.ntiles * BLK >= in && ref_ok(d.dy, outn) && ref_ok(d.dx, in) &&
+             ptr_ok(d.w, (int64_t)d.K * d.C * d.k * d.k) && (!(d.flags & F_MASK_X) || ref_ok(d.x, in)) &&
+             (!(d.flags & F_ADD_SKG) || ref_ok(d.skg, in));
+        break;
+      case K_CONV_BWD_W:
+        ok = ok && d.ntiles == bwd_w_tiles(d.K, d.C, d.k, d.OH * d.OW, d.flags & F_BIAS) && ref_ok(d.x, in) &&
+             ref_ok(d.dy, outn) && ptr_ok(d.gw, (int64_t)d.K * d.C * d.k * d.k) &&
+             (!(d.flags & F_BIAS) || ptr_ok(d.gb, d.K)) && (!(d.flags & F_PRE_AFFINE) || ref_ok(d.st, stn));
+        break;
+      case K_COPY:
+        ok = ok && (int64_t)d.ntiles * BLK >= d.n && ref_ok(d.dy, d.n) && ref_ok(d.dx, d.n);
+        break;
+      default:
+        ok = false;
+    }
+    if (!ok) return fail(PB_E_INVALID, "internal: step %d (kind %d, stage %d) fails the bounds audit", idx, d.kind, d.stage);
+    ++idx;
+  }
+  return PB_OK;
+}
+
+// ------------------------------------------------- initial weights (host)
+inline uint64_t mix64(uint64_t z) {
+  z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ULL;
+  z ^= z >> 27; z *= 0x94D049BB133111EBULL;
+  z ^= z >> 31;
+  return z;
+}
+
+// Element e of parameter tensor `tensor`: outputs 2e and 2e+1 of a splitmix64
+// stream started at seed ^ (GOLD*(tensor+1)); Box-Muller (cosine branch) in
+// double; scaled by std and rounded once to float.
+void fill_normal(float* dst, int64_t n, uint64_t seed, int tensor, double std_) {
+  const uint64_t GOLD = 0x9E3779B97F4A7C15ULL;
+  const uint64_t key = seed ^ (GOLD * (uint64_t)(tensor + 1));
+  const double two_pi = 6.283185307179586476925286766559;
+  for (int64_t e = 0; e < n; ++e) {
+    const uint64_t r1 = mix64(key + GOLD * (2 * (uint64_t)e + 1));
+    const uint64_t r2 = mix64(key + GOLD * (2 * (uint64_t)e + 2));
+    const double u1 = ((double)(r1 >> 11) + 1.0) * 0x1.0p-53;
+    const double u2 = (double)(r2 >> 11) * 0x1.0p-53;
+    dst[e] = (float)(sqrt(-2.0 * log(u1)) * cos(two_pi * u2) * std_);
+  }
+}
+
+void init_weights_host(const std::vector<Stage>& st, uint64_t seed, std::vector<float>& w) {
+  int tensor = 0;
+  for (const Stage& a : st) {
+    float* p = w.data() + a.off;
+    fill_normal(p + a.o_w, a.n_w, seed, tensor++, sqrt(2.0 / a.fan_w));
+    if (a.has_bias) tensor++;                       // zeros
+    if (a.proj) fill_normal(p + a.o_wp, a.n_wp, seed, tensor++, sqrt(2.0 / a.fan_wp));
+    if (a.n_gn) {
+      for (int64_t i = 0; i < a.n_gn; ++i) p[a.o_gamma + i] = 1.0f;
+      tensor += 2;
+    }
+  }
+}
+
+void sc_coeffs(double m, int D, double* a, double* b) {
+  *a = (D == 0) ? 1.0 : pow(m, (double)D);
+  *b = (m == 1.0) ? (double)D : (1.0 - *a) / (1.0 - m);
+}
+
+int64_t copy_params_out(pb_ctx* c, int64_t arena_off, float* dst, int64_t cap) {
+  if (!dst) return c->n_params;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(PB_E_HIP, "stream synchronize failed");
+  std::vector<float> tmp(c->L.P);
+  if (hipMemcpy(tmp.data(), c->f(arena_off), sizeof(float) * c->L.P, hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(PB_E_HIP, "device to host copy failed");
+  int64_t n = 0;
+  for (const Stage& a : c->st) {
+    const int64_t take = std::min<int64_t>(a.n_params, cap - n);
+    if (take <= 0) break;
+    memcpy(dst + n, tmp.data() + a.off, sizeof(float) * take);
+    n += take;
+  }
+  return n;
+}
+
+struct ScopedEv {
+  pb_ctx* c; int idx = -1;
+  ScopedEv(pb_ctx* c_, int cls) : c(c_) {
+    if (!c->profiling || (int)c->evs.size() >= c->max_events) return;
+    pb_ctx::Ev e;
+    if (!c->ev_pool.empty()) { e = c->ev_pool.back(); c->ev_pool.pop_back(); }
+    else { if (hipEventCreate(&e.a) != hipSuccess || hipEventCreate(&e.b) != hipSuccess) return; }
+    e.cls = cls;
+    (void)hipEventRecord(e.a, c->stream);
+    c->evs.push_back(e);
+    idx = (int)c->evs.size() - 1;
+  }
+  ~ScopedEv() { if (idx >= 0) (void)hipEventRecord(c->evs[idx].b, c->stream); }
+};
+
+int run_one_tick(pb_ctx* c, const float* staging, int label) {
+  const int k = (int)c->ticks;   // t_base stays 0 on this path
+  {
+    ScopedEv ev(c, 2);
+    launch_ingest(ring(c, c->L.sb[0].xring, c->st[0].D + 2, c->st[0].in_elems(), 0), c->st[0].in_elems(),
+                  staging, label, c->labels_dev, c->S, c->globals_dev, k, c->stream);
+  }
+  if (c->launch_mode == 0) {
+    for (const Phase& p : c->phases) {
+      ScopedEv ev(c, 0);
+      launch_phase(c->steps_dev + p.first, c->prefix_dev + p.first, p.count, p.tiles, c->globals_dev, k,
+                   c->stream);
+    }
+  } else {
+    for (const Phase& p : c->phases)
+      for (int i = 0; i < p.count; ++i) {
+        ScopedEv ev(c, 0);
+        launch_phase(c->steps_dev + p.first + i, c->zero_dev, 1, c->steps[p.first + i].ntiles,
+                     c->globals_dev, k, c->stream);
+      }
+  }
+  {
+    ScopedEv ev(c, 1);
+    launch_update(c->f(c->L.w), c->f(c->L.v), c->f(c->L.g), c->L.what >= 0 ? c->f(c->L.what) : nullptr,
+                  c->chunk_stage_dev, c->segs_dev, c->n_chunks, c->lr, c->m, c->globals_dev, k, c->stream);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PB_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+  c->ticks++;
+  return PB_OK;
+}
+
+}  // namespace
+
+// =============================================================== the C ABI
+extern "C" {
+
+const char* pb_last_error(void) { return g_err.c_str(); }
+
+size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays) {
+  std::vector<Stage> st;
+  if (parse_net(net, st) != PB_OK || check_delays(st, delays) != PB_OK) return 0;
+  pb_ctx tmp;
+  tmp.st = st; tmp.S = (int)st.size();
+  const int cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
+  Plan pl;
+  Layout L;
+  plan_arena(st, net->mitigation >= 2, cap, L, pl);
+  // step table, prefix, chunk map and segment table live in the arena too
+  tmp.L = L; tmp.loss_cap = cap; tmp.arena = nullptr;
+  tmp.labels_dev = (int32_t*)tmp.f(L.labels);
+  std::vector<std::pair<int, StepDesc>> steps;
+  compile_steps(&tmp, steps);
+  if (validate_steps(&tmp, steps, pl.total) != PB_OK) return 0;
+  pl.alloc((int64_t)steps.size() * sizeof(StepDesc) / 4 + 64);
+  pl.alloc((int64_t)steps.size() + 64);
+  pl.alloc(L.P / UPD_CHUNK + 64);
+  pl.alloc((int64_t)st.size() * sizeof(UpdSeg) / 4 + 64);
+  return (size_t)pl.total * sizeof(float) + 256;
+}
+
+int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float lr, float momentum,
+            uint64_t seed) {
+  if (!out) return fail(PB_E_INVALID, "out is NULL");
+  *out = nullptr;
+  std::vector<Stage> st;
+  int rc = parse_net(net, st);
+  if (rc != PB_OK) return rc;
+  rc = check_delays(st, delays);
+  if (rc != PB_OK) return rc;
+  if (!(momentum >= 0.f && momentum <= 1.f)) return fail(PB_E_INVALID, "momentum must be in [0,1]");
+  if (!(lr >= 0.f)) return fail(PB_E_INVALID, "learning rate must be >= 0");
+  const size_t need = pb_arena_bytes(net, delays);
+  if (!need) return PB_E_INVALID;
+
+  pb_ctx* c = new pb_ctx();
+  c->st = st; c->S = (int)st.size();
+  c->mitigation = net->mitigation; c->lr = lr; c->m = momentum;
+  c->loss_cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
+  c->stream = (hipStream_t)net->stream;
+  for (const Stage& a : st) c->n_params += a.n_params;
+  void* base = net->device_arena;
+  if (base) {
+    if (net->arena_bytes < need) { delete c; return fail(PB_E_NOMEM, "arena has %zu bytes, %zu needed", net->arena_bytes, need); }
+    if ((uintptr_t)base % 256) { delete c; return fail(PB_E_INVALID, "arena must be 256-byte aligned"); }
+  } else {
+    if (hipMalloc(&base, need) != hipSuccess) { delete c; return fail(PB_E_NOMEM, "hipMalloc of %zu bytes failed", need); }
+    c->own_arena = true;
+  }
+  c->arena = (float*)base;
+#define INIT_TRY(expr)                                                                  \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess) {                                                             \
+      fail(PB_E_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));                    \
+      pb_destroy(c);                                                                    \
+      return PB_E_HIP;                                                                  \
+    }                                                                                   \
+  } while (0)
+  INIT_TRY(hipMemsetAsync(base, 0, need, c->stream));
+
+  Plan pl;
+  plan_arena(st, net->mitigation >= 2, c->loss_cap, c->L, pl);
+  c->labels_dev = (int32_t*)c->f(c->L.labels);
+  c->globals_dev = (Globals*)c->f(c->L.globals);
+  c->zero_dev = (int32_t*)c->f(c->L.zero);
+
+  std::vector<std::pair<int, StepDesc>> tagged;
+  compile_steps(c, tagged);
+  if (validate_steps(c, tagged, pl.total) != PB_OK) { pb_destroy(c); return PB_E_INVALID; }
+  std::stable_sort(tagged.begin(), tagged.end(),
+                   [](const std::pair<int, StepDesc>& x, const std::pair<int, StepDesc>& y) { return x.first < y.first; });
+  const int n_steps = (int)tagged.size();
+  c->steps.resize(n_steps);
+  c->prefix.resize(n_steps);
+  int n_ph = 0;
+  for (auto& p : tagged) n_ph = std::max(n_ph, p.first + 1);
+  c->phases.assign(n_ph, Phase());
+  for (int i = 0, cur = -1, acc = 0; i < n_steps; ++i) {
+    const int ph = tagged[i].first;
+    if (ph != cur) { cur = ph; acc = 0; c->phases[ph].first = i; }
+    c->steps[i] = tagged[i].second;
+    c->prefix[i] = acc;
+    acc += tagged[i].second.ntiles;
+    c->phases[ph].count++;
+    c->phases[ph].tiles = acc;
+  }
+  const int64_t o_steps = pl.alloc((int64_t)n_steps * sizeof(StepDesc) / 4 + 64);
+  const int64_t o_prefix = pl.alloc(n_steps + 64);
+  c->n_chunks = (int)(c->L.P / UPD_CHUNK);
+  const int64_t o_chunk = pl.alloc(c->n_chunks + 64);
+  const int64_t o_segs = pl.alloc((int64_t)c->S * sizeof(UpdSeg) / 4 + 64);
+  if ((size_t)pl.total * sizeof(float) > need) { pb_destroy(c); return fail(PB_E_NOMEM, "internal: arena plan mismatch"); }
+  c->steps_dev = (StepDesc*)c->f(o_steps);
+  c->prefix_dev = (int32_t*)c->f(o_prefix);
+  c->chunk_stage_dev = (int32_t*)c->f(o_chunk);
+  c->segs_dev = (UpdSeg*)c->f(o_segs);
+
+  // host-side tables
+  std::vector<int32_t> chunk_stage(c->n_chunks);
+  std::vector<UpdSeg> segs(c->S);
+  for (int s = 0; s < c->S; ++s) {
+    const Stage& a = st[s];
+    for (int64_t ch = a.off / UPD_CHUNK; ch < (a.off + a.padded) / UPD_CHUNK; ++ch) chunk_stage[ch] = s;
+    double ca = 1.0, cb = 0.0;
+    if (net->mitigation == 1 || net->mitigation == 3) sc_coeffs((double)momentum, a.D, &ca, &cb);
+    const double T = (net->mitigation >= 2) ? (double)a.D : 0.0;
+    segs[s].a = (float)ca; segs[s].b = (float)cb; segs[s].lrT = (float)((double)lr * T);
+    segs[s].first_tick = 2 * (c->S - 1) - s;
+  }
+  std::vector<float> w(c->L.P, 0.f);
+  init_weights_host(st, seed, w);
+  Globals g0;
+  memset(&g0, 0, sizeof g0);
+  g0.n_pool = 1;
+  INIT_TRY(hipMemcpyAsync(c->f(c->L.w), w.data(), sizeof(float) * c->L.P, hipMemcpyHostToDevice, c->stream));
+  if (c->L.what >= 0)
+    INIT_TRY(hipMemcpyAsync(c->f(c->L.what), w.data(), sizeof(float) * c->L.P, hipMemcpyHostToDevice, c->stream));
+  INIT_TRY(hipMemcpyAsync(c->steps_dev, c->steps.data(), sizeof(StepDesc) * n_steps, hipMemcpyHostToDevice, c->stream));
+  INIT_TRY(hipMemcpyAsync(c->prefix_dev, c->prefix.data(), sizeof(int32_t) * n_steps, hipMemcpyHostToDevice, c->stream));
+  INIT_TRY(hipMemcpyAsync(c->chunk_stage_dev, chunk_stage.data(), sizeof(int32_t) * c->n_chunks, hipMemcpyHostToDevice, c->stream));
+  INIT_TRY(hipMemcpyAsync(c->segs_dev, segs.data(), sizeof(UpdSeg) * c->S, hipMemcpyHostToDevice, c->stream));
+  INIT_TRY(hipMemcpyAsync(c->globals_dev, &g0, sizeof g0, hipMemcpyHostToDevice, c->stream));
+  INIT_TRY(hipStreamSynchronize(c->stream));
+#undef INIT_TRY
+  *out = c;
+  return PB_OK;
+}
+
+int pb_tick(pb_ctx* c, const float* sample, int32_t label) {
+  if (!c || !sample) return fail(PB_E_INVALID, "NULL argument");
+  if (label < 0 || label >= c->st.back().K) return fail(PB_E_INVALID, "label %d out of range", label);
+  float* staging = c->f(c->L.staging);
+  HIP_TRY(hipMemcpyAsync(staging, sample, sizeof(float) * c->st[0].in_elems(), hipMemcpyHostToDevice, c->stream));
+  return run_one_tick(c, staging, label);
+}
+
+int pb_run_resident(pb_ctx* c, const float* samples_dev, const int32_t* labels_dev, int32_t n_pool,
+                    int64_t first_index, int64_t n_ticks) {
+  if (!c || !samples_dev || !labels_dev || n_pool <= 0 || first_index < 0 || n_ticks < 0)
+    return fail(PB_E_INVALID, "bad argument");
+  // tick t consumes item (idx_base + t) mod n_pool
+  const int64_t t0 = c->ticks;
+  int64_t ib = (first_index - t0) % n_pool;
+  if (ib < 0) ib += n_pool;
+  if (c->pool != samples_dev || c->pool_labels != labels_dev || c->n_pool != n_pool || c->idx_base != (int)ib) {
+    Globals g;
+    memset(&g, 0, sizeof g);
+    g.t_base = 0; g.idx_base = (int)ib; g.n_pool = n_pool; g.pool = samples_dev; g.pool_labels = labels_dev;
+    launch_set_globals(c->globals_dev, g, c->stream);
+    c->pool = samples_dev; c->pool_labels = labels_dev; c->n_pool = n_pool; c->idx_base = (int)ib;
+  }
+  for (int64_t j = 0; j < n_ticks; ++j) {
+    int rc = run_one_tick(c, nullptr, 0);
+    if (rc != PB_OK) return rc;
+  }
+  return PB_OK;
+}
+
+int64_t pb_read_weights(pb_ctx* c, float* dst, int64_t cap) {
+  if (!c) return fail(PB_E_INVALID, "NULL context");
+  return copy_params_out(c, c->L.w, dst, cap);
+}
+
+int64_t pb_read_velocity(pb_ctx* c, float* dst, int64_t cap) {
+  if (!c) return fail(PB_E_INVALID, "NULL context");
+  return copy_params_out(c, c->L.v, dst, cap);
+}
+
+int64_t pb_loss_history(pb_ctx* c, float* dst, int64_t cap) {
+  if (!c) return fail(PB_E_INVALID, "NULL context");
+  const int64_t count = std::max<int64_t>(0, c->ticks - c->S + 1);
+  const int64_t avail = std::min<int64_t>(count, c->loss_cap);
+  if (!dst) return avail;
+  const int64_t n = std::min(avail, cap);
+  if (n <= 0) return 0;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  std::vector<float> ring_(c->loss_cap);
+  HIP_TRY(hipMemcpy(ring_.data(), c->f(c->L.loss), sizeof(float) * c->loss_cap, hipMemcpyDeviceToHost));
+  for (int64_t i = 0; i < n; ++i) dst[i] = ring_[(count - n + i) % c->loss_cap];
+  return n;
+}
+
+int64_t pb_num_params(const pb_ctx* c) { return c ? c->n_params : 0; }
+int64_t pb_num_ticks(const pb_ctx* c) { return c ? c->ticks : 0; }
+
+int pb_set_launch_mode(pb_ctx* c, int32_t mode) {
+  if (!c || mode < 0 || mode > 1) return fail(PB_E_INVALID, "bad launch mode");
+  c->launch_mode = mode;
+  return PB_OK;
+}
+
+int pb_profile_begin(pb_ctx* c, int32_t max_events) {
+  if (!c || max_events <= 0) return fail(PB_E_INVALID, "bad argument");
+  for (auto& e : c->evs) c->ev_pool.push_back(e);
+  c->evs.clear();
+  c->profiling = true;
+  c->max_events = max_events;
+  return PB_OK;
+}
+
+int pb_profile_end(pb_ctx* c, int32_t which, int64_t* n_launches, double* total_ms) {
+  if (!c || !n_launches || !total_ms) return fail(PB_E_INVALID, "NULL argument");
+  c->profiling = false;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  int64_t n = 0;
+  double ms = 0;
+  for (auto& e : c->evs) {
+    if (e.cls != which) continue;
+    float x = 0;
+    HIP_TRY(hipEventElapsedTime(&x, e.a, e.b));
+    ms += x; ++n;
+  }
+  *n_launches = n; *total_ms = ms;
+  return PB_OK;
+}
+
+int pb_update_standalone(float* w, float* v, const float* g, float* what, int64_t n, float lr, float m,
+                         float a, float b, float lrT, void* stream) {
+  if (!w || !v || !g || n <= 0 || n % UPD_CHUNK) return fail(PB_E_INVALID, "n must be a positive multiple of %d", UPD_CHUNK);
+  if (n / UPD_CHUNK > 0x7fffffff) return fail(PB_E_INVALID, "n too large");
+  launch_update_flat(w, v, g, what, n, lr, m, a, b, lrT, (hipStream_t)stream);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PB_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+  return PB_OK;
+}
+
+int pb_sync(pb_ctx* c) {
+  if (!c) return fail(PB_E_INVALID, "NULL context");
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  return PB_OK;
+}
+
+void pb_destroy(pb_ctx* c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->stream);
+  for (auto& e : c->evs) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+  for (auto& e : c->ev_pool) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+  if (c->own_arena && c->arena) (void)hipFree(c->arena);
+  delete c;
+}
+
+}  // extern "C"

@@ -1,0 +1,520 @@
+// HIP kernels of the PB tick engine (gfx950).
+//
+// One kernel, k_phase, executes every step of one pipeline phase: each
+// workgroup looks up which step of the step table its block index falls in
+// and runs that step's tile.  All stages' forward and backward work of a tick
+// therefore goes out as a handful of launches (Appendix "GPU Bottlenecks for
+// Fine-Grained Pipelined Training" names the launch rate as the limit for
+// small networks).  Reductions use fixed trees: results are bit-reproducible.
+#include "pb_device.h"
+
+namespace pb {
+
+// ------------------------------------------------------------------ helpers
+__device__ __forceinline__ float* at(const TRef& r, int t) {
+  int u = t - r.lag;
+  int slot = u % r.depth;
+  if (slot < 0) slot += r.depth;
+  return r.base + (size_t)slot * (size_t)r.stride;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  return v;   // valid in lane 0
+}
+
+// Sum over the workgroup, same value returned to every thread.
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) red[wv] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__device__ __forceinline__ float block_max(float v, float* red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_down(v, o, 64));
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) red[wv] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+// ------------------------------------------------------------ forward steps
+// GroupNorm statistics of one group (biased variance, two passes) and the
+// folded per-channel scale/shift built from the forward (predicted) affine
+// parameters; kept for the backward pass of the same sample.
+__device__ void step_gn_stats(const StepDesc& d, int tile, int t, float* red) {
+  const int g = tile, HW = d.H * d.W, cpg = d.C / d.G, n = cpg * HW;
+  const float* xp = at(d.x, t) + (size_t)g * n;
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += BLK) s += xp[i];
+  const float mean = block_sum(s, red) / (float)n;
+  float q = 0.f;
+  for (int i = threadIdx.x; i < n; i += BLK) { float dl = xp[i] - mean; q = fmaf(dl, dl, q); }
+  const float var = block_sum(q, red) / (float)n;
+  const float rstd = 1.0f / sqrtf(var + GN_EPS);
+  float* st = at(d.st, t);
+  if (threadIdx.x == 0) { st[g] = mean; st[d.G + g] = rstd; }
+  for (int c = threadIdx.x; c < cpg; c += BLK) {
+    const int ch = g * cpg + c;
+    const float sc = d.gamma[ch] * rstd;
+    st[2 * d.G + ch] = sc;
+    st[2 * d.G + d.C + ch] = fmaf(-mean, sc, d.beta[ch]);
+  }
+}
+
+// pooled[c] = mean_hw relu(sc*x+sh)
+__device__ void step_gap_fwd(const StepDesc& d, int tile, int t, float* red) {
+  const int c = tile, HW = d.H * d.W;
+  const float* xp = at(d.x, t) + (size_t)c * HW;
+  const bool aff = d.flags & F_PRE_AFFINE, rl = d.flags & F_PRE_RELU;
+  const float* st = aff ? at(d.st, t) : nullptr;
+  const float sc = aff ? st[2 * d.G + c] : 1.f, sh = aff ? st[2 * d.G + d.C + c] : 0.f;
+  float s = 0.f;
+  for (int i = threadIdx.x; i < HW; i += BLK) {
+    float v = fmaf(sc, xp[i], sh);
+    if (rl) v = fmaxf(v, 0.f);
+    s += v;
+  }
+  s = block_sum(s, red);
+  if (threadIdx.x == 0) at(d.y, t)[c] = s / (float)HW;
+}
+
+// Direct convolution / linear forward, one thread per output element.
+__device__ void step_conv_fwd(const StepDesc& d, int tile, int t) {
+  const int P = d.OH * d.OW;
+  const int o = tile * BLK + threadIdx.x;
+  if (o >= d.K * P) return;
+  const int co = o / P, p = o - co * P, oh = p / d.OW, ow = p - oh * d.OW;
+  const float* x = at(d.x, t);
+  const float* st = (d.flags & F_PRE_AFFINE) ? at(d.st, t) : nullptr;
+  const bool aff = d.flags & F_PRE_AFFINE, rl = d.flags & F_PRE_RELU;
+  const int HW = d.H * d.W, kk = d.k * d.k;
+  float acc = (d.flags & F_BIAS) ? d.b[co] : 0.f;
+  const float* wr = d.w + (size_t)co * d.C * kk;
+  for (int ci = 0; ci < d.C; ++ci) {
+    const float sc = aff ? st[2 * d.G + ci] : 1.f, sh = aff ? st[2 * d.G + d.C + ci] : 0.f;
+    const float* xc = x + (size_t)ci * HW;
+    for (int kh = 0; kh < d.k; ++kh) {
+      const int ih = oh * d.stride - d.pad + kh;
+      if (ih < 0 || ih >= d.H) continue;
+      for (int kw = 0; kw < d.k; ++kw) {
+        const int iw = ow * d.stride - d.pad + kw;
+        if (iw < 0 || iw >= d.W) continue;
+        float v = xc[ih * d.W + iw];
+        if (aff) v = fmaf(sc, v, sh);
+        if (rl) v = fmaxf(v, 0.f);
+        acc = fmaf(wr[ci * kk + kh * d.k + kw], v, acc);
+      }
+    }
+  }
+  if (d.flags & F_SKIP) {
+    const float* sk = at(d.skip, t);
+    if (d.flags & F_PROJ) {
+      const int sHW = d.sH * d.sW;
+      const float* s0 = sk + (size_t)(oh * d.sstride) * d.sW + ow * d.sstride;
+      float a2 = 0.f;
+      for (int ci = 0; ci < d.sC; ++ci) a2 = fmaf(d.wp[(size_t)co * d.sC + ci], s0[(size_t)ci * sHW], a2);
+      acc += a2;
+    } else {
+      acc += sk[o];
+    }
+  }
+  at(d.y, t)[o] = acc;
+}
+
+// y = [maxpool] relu(sc*z+sh), one thread per output element.
+__device__ void step_post_fwd(const StepDesc& d, int tile, int t) {
+  const float* z = at(d.x, t);
+  const float* st = at(d.st, t);
+  float* y = at(d.y, t);
+  const int HW = d.H * d.W;
+  if (d.flags & F_POOL) {
+    const int PP = d.PH * d.PW;
+    const int o = tile * BLK + threadIdx.x;
+    if (o >= d.C * PP) return;
+    const int c = o / PP, p = o - c * PP, ph = p / d.PW, pw = p - ph * d.PW;
+    const float sc = st[2 * d.G + c], sh = st[2 * d.G + d.C + c];
+    const float* zc = z + (size_t)c * HW;
+    float best = -1.f;
+    for (int kh = 0; kh < d.pk; ++kh) {
+      const int ih = ph * d.ps - d.pp + kh;
+      if (ih < 0 || ih >= d.H) continue;
+      for (int kw = 0; kw < d.pk; ++kw) {
+        const int iw = pw * d.ps - d.pp + kw;
+        if (iw < 0 || iw >= d.W) continue;
+        best = fmaxf(best, fmaxf(fmaf(sc, zc[ih * d.W + iw], sh), 0.f));
+      }
+    }
+    y[o] = best;
+  } else {
+    const int o = tile * BLK + threadIdx.x;
+    if (o >= d.C * HW) return;
+    const int c = o / HW;
+    y[o] = fmaxf(fmaf(st[2 * d.G + c], z[o], st[2 * d.G + d.C + c]), 0.f);
+  }
+}
+
+// Softmax cross-entropy of the sample that reaches the last stage at tick t
+// (sample index t-(S-1)); writes dlogits = softmax - onehot.
+__device__ void step_ce(const StepDesc& d, int tile, int t, float* red) {
+  const float* z = at(d.x, t);
+  float* dz = at(d.dx, t);
+  const int n = d.n;
+  const int sample = t - (d.n_stages - 1);
+  const int label = d.labels[sample % d.n_stages];
+  float mx = -3.0e38f;
+  for (int i = threadIdx.x; i < n; i += BLK) mx = fmaxf(mx, z[i]);
+  mx = block_max(mx, red);
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += BLK) s += expf(z[i] - mx);
+  s = block_sum(s, red);
+  for (int i = threadIdx.x; i < n; i += BLK) {
+    float p = expf(z[i] - mx) / s;
+    dz[i] = p - (i == label ? 1.f : 0.f);
+  }
+  if (threadIdx.x == 0) d.loss_log[sample % d.loss_cap] = logf(s) + mx - z[label];
+}
+
+// ----------------------------------------------------------- backward steps
+// Gradient arriving at element (h,w) of channel c of the tensor u = relu(affine(z))
+// that feeds a max-pool: the sum of dY over the windows whose first maximum
+// (row-major scan, strict >) sits at (h,w).
+__device__ __forceinline__ float pool_routed(const StepDesc& d, const float* zc, float sc, float sh,
+                                             int h, int w, const float* dyc) {
+  float sum = 0.f;
+  int ph_lo = h + d.pp - d.pk + 1;
+  ph_lo = ph_lo <= 0 ? 0 : (ph_lo + d.ps - 1) / d.ps;
+  int ph_hi = (h + d.pp) / d.ps;
+  if (ph_hi >= d.PH) ph_hi = d.PH - 1;
+  int pw_lo = w + d.pp - d.pk + 1;
+  pw_lo = pw_lo <= 0 ? 0 : (pw_lo + d.ps - 1) / d.ps;
+  int pw_hi = (w + d.pp) / d.ps;
+  if (pw_hi >= d.PW) pw_hi = d.PW - 1;
+  for (int ph = ph_lo; ph <= ph_hi; ++ph)
+    for (int pw = pw_lo; pw <= pw_hi; ++pw) {
+      float best = -1.f;
+      int bh = -1, bw = -1;
+      for (int kh = 0; kh < d.pk; ++kh) {
+        const int ih = ph * d.ps - d.pp + kh;
+        if (ih < 0 || ih >= d.H) continue;
+        for (int kw = 0; kw < d.pk; ++kw) {
+          const int iw = pw * d.ps - d.pp + kw;
+          if (iw < 0 || iw >= d.W) continue;
+          const float v = fmaxf(fmaf(sc, zc[ih * d.W + iw], sh), 0.f);
+          if (v > best) { best = v; bh = ih; bw = iw; }
+        }
+      }
+      if (bh == h && bw == w) sum += dyc[ph * d.PW + pw];
+    }
+  return sum;
+}
+
+__device__ __forceinline__ float gn_du(const StepDesc& d, const float* dy, const float* xc, float sc,
+                                       float sh, int c, int i, int HW) {
+  if (d.flags & F_DU_BUF) return dy[(size_t)c * HW + i];
+  if (d.flags & F_DU_GAP) return dy[c] / (float)HW;
+  const int h = i / d.W, w = i - h * d.W;
+  return pool_routed(d, xc, sc, sh, h, w, dy + (size_t)c * d.PH * d.PW);
+}
+
+// Per channel: dgamma = sum dyv*xh, dbeta = sum dyv (dyv = gradient after the
+// ReLU mask); also gamma_b*dbeta and gamma_b*dgamma for the group sums.
+__device__ void step_gnb_reduce(const StepDesc& d, int tile, int t, float* red) {
+  const int c = tile, HW = d.H * d.W, cpg = d.C / d.G, g = c / cpg;
+  const float* st = at(d.st, t);
+  const float mean = st[g], rstd = st[d.G + g], sc = st[2 * d.G + c], sh = st[2 * d.G + d.C + c];
+  const float* xc = at(d.x, t) + (size_t)c * HW;
+  const float* dy = at(d.dy, t);
+  const bool rl = d.flags & F_GN_RELU;
+  float sg = 0.f, sb = 0.f;
+  for (int i = threadIdx.x; i < HW; i += BLK) {
+    const float xv = xc[i];
+    const float yv = fmaf(sc, xv, sh);
+    float du = gn_du(d, dy, xc, sc, sh, c, i, HW);
+    if (rl && !(yv > 0.f)) du = 0.f;
+    sg = fmaf(du, (xv - mean) * rstd, sg);
+    sb += du;
+  }
+  sg = block_sum(sg, red);
+  sb = block_sum(sb, red);
+  if (threadIdx.x == 0) {
+    d.ggamma[c] = sg;
+    d.gbeta[c] = sb;
+    const float gm = d.gamma[c];
+    d.part[c] = gm * sb;
+    d.part[d.C + c] = gm * sg;
+  }
+}
+
+// dx = rstd * (dxh - mean(dxh) - xh * mean(dxh*xh)), dxh = dyv * gamma_b
+__device__ void step_gnb_apply(const StepDesc& d, int tile, int t) {
+  const int HW = d.H * d.W, cpg = d.C / d.G, n = cpg * HW;
+  const int o = tile * BLK + threadIdx.x;
+  if (o >= d.C * HW) return;
+  const int c = o / HW, i = o - c * HW, g = c / cpg;
+  const float* st = at(d.st, t);
+  const float mean = st[g], rstd = st[d.G + g], sc = st[2 * d.G + c], sh = st[2 * d.G + d.C + c];
+  float S1 = 0.f, S2 = 0.f;
+  for (int j = 0; j < cpg; ++j) { S1 += d.part[g * cpg + j]; S2 += d.part[d.C + g * cpg + j]; }
+  const float* xc = at(d.x, t) + (size_t)c * HW;
+  const float xv = xc[i];
+  const float yv = fmaf(sc, xv, sh);
+  float du = gn_du(d, at(d.dy, t), xc, sc, sh, c, i, HW);
+  if ((d.flags & F_GN_RELU) && !(yv > 0.f)) du = 0.f;
+  const float xh = (xv - mean) * rstd;
+  const float inv_n = 1.0f / (float)n;
+  float r = rstd * (du * d.gamma[c] - S1 * inv_n - xh * (S2 * inv_n));
+  if (d.flags & F_ADD_SKG) r += at(d.skg, t)[o];
+  at(d.dx, t)[o] = r;
+}
+
+// Backward data: dX = W^T dZ (transposed convolution), one thread per input
+// element, gathering.
+__device__ void step_conv_bwd_x(const StepDesc& d, int tile, int t) {
+  const int HW = d.H * d.W, P = d.OH * d.OW, kk = d.k * d.k;
+  const int o = tile * BLK + threadIdx.x;
+  if (o >= d.C * HW) return;
+  const int ci = o / HW, r = o - ci * HW, ih = r / d.W, iw = r - ih * d.W;
+  const float* dz = at(d.dy, t);
+  float acc = 0.f;
+  for (int kh = 0; kh < d.k; ++kh) {
+    const int th = ih + d.pad - kh;
+    if (th < 0 || th % d.stride) continue;
+    const int oh = th / d.stride;
+    if (oh >= d.OH) continue;
+    for (int kw = 0; kw < d.k; ++kw) {
+      const int tw = iw + d.pad - kw;
+      if (tw < 0 || tw % d.stride) continue;
+      const int ow = tw / d.stride;
+      if (ow >= d.OW) continue;
+      const float* wq = d.w + (size_t)ci * kk + kh * d.k + kw;
+      const float* dq = dz + oh * d.OW + ow;
+      for (int co = 0; co < d.K; ++co) acc = fmaf(wq[(size_t)co * d.C * kk], dq[(size_t)co * P], acc);
+    }
+  }
+  if (d.flags & F_MASK_X) { if (!(at(d.x, t)[o] > 0.f)) acc = 0.f; }
+  if (d.flags & F_ADD_SKG) acc += at(d.skg, t)[o];
+  at(d.dx, t)[o] = acc;
+}
+
+// Backward weights: dW[co,ci,kh,kw] = sum_p dZ[co,p] * a[ci, p*s-pad+k],
+// a = the forward's transformed input recomputed from the saved input.
+// Large maps: one wavefront per weight element; small maps: one thread.
+__device__ void step_conv_bwd_w(const StepDesc& d, int tile, int t) {
+  const int HW = d.H * d.W, P = d.OH * d.OW, kk = d.k * d.k;
+  const int nW = d.K * d.C * kk;
+  const bool wave_mode = P > 16;
+  const int per_tile = wave_mode ? BLK / 64 : BLK;
+  const int w_tiles = (nW + per_tile - 1) / per_tile;
+  const float* dz = at(d.dy, t);
+  if (tile >= w_tiles) {                      // bias tiles
+    const int lane = threadIdx.x & 63;
+    if (wave_mode) {
+      const int co = (tile - w_tiles) * per_tile + (threadIdx.x >> 6);
+      if (co >= d.K) return;
+      float s = 0.f;
+      for (int p = lane; p < P; p += 64) s += dz[(size_t)co * P + p];
+      s = wave_sum(s);
+      if (lane == 0) d.gb[co] = s;
+    } else {
+      const int co = (tile - w_tiles) * per_tile + threadIdx.x;
+      if (co >= d.K) return;
+      float s = 0.f;
+      for (int p = 0; p < P; ++p) s += dz[(size_t)co * P + p];
+      d.gb[co] = s;
+    }
+    return;
+  }
+  const float* x = at(d.x, t);
+  const bool aff = d.flags & F_PRE_AFFINE, rl = d.flags & F_PRE_RELU;
+  const float* st = aff ? at(d.st, t) : nullptr;
+  const int e = wave_mode ? tile * per_tile + (threadIdx.x >> 6) : tile * per_tile + threadIdx.x;
+  if (e >= nW) return;
+  const int co = e / (d.C * kk), r = e - co * d.C * kk, ci = r / kk, q = r - ci * kk;
+  const int kh = q / d.k, kw = q - kh * d.k;
+  const float sc = aff ? st[2 * d.G + ci] : 1.f, sh = aff ? st[2 * d.G + d.C + ci] : 0.f;
+  const float* xc = x + (size_t)ci * HW;
+  const float* dzc = dz + (size_t)co * P;
+  float acc = 0.f;
+  const int p0 = wave_mode ? (threadIdx.x & 63) : 0, dp = wave_mode ? 64 : 1;
+  for (int p = p0; p < P; p += dp) {
+    const int oh = p / d.OW, ow = p - oh * d.OW;
+    const int ih = oh * d.stride - d.pad + kh, iw = ow * d.stride - d.pad + kw;
+    if (ih < 0 || ih >= d.H || iw < 0 || iw >= d.W) continue;
+    float v = xc[ih * d.W + iw];
+    if (aff) v = fmaf(sc, v, sh);
+    if (rl) v = fmaxf(v, 0.f);
+    acc = fmaf(dzc[p], v, acc);
+  }
+  if (wave_mode) {
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) d.gw[e] = acc;
+  } else {
+    d.gw[e] = acc;
+  }
+}
+
+__device__ void step_copy(const StepDesc& d, int tile, int t) {
+  const int o = tile * BLK + threadIdx.x;
+  if (o < d.n) at(d.dx, t)[o] = at(d.dy, t)[o];
+}
+
+// ------------------------------------------------------------------ kernels
+__global__ void __launch_bounds__(BLK)
+k_phase(const StepDesc* __restrict__ steps, const int32_t* __restrict__ prefix, int n_steps,
+        const Globals* __restrict__ G, int k) {
+  __shared__ float red[8];
+  const int t = G->t_base + k;
+  // which step does this workgroup belong to (prefix[i] = first tile of step i)
+  int lo = 0, hi = n_steps - 1;
+  const int bid = blockIdx.x;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (prefix[mid] <= bid) lo = mid; else hi = mid - 1;
+  }
+  const StepDesc& d = steps[lo];
+  if (t < d.first_tick) return;
+  const int tile = bid - prefix[lo];
+  switch (d.kind) {
+    case K_GN_STATS: step_gn_stats(d, tile, t, red); break;
+    case K_GAP_FWD: step_gap_fwd(d, tile, t, red); break;
+    case K_CONV_FWD: step_conv_fwd(d, tile, t); break;
+    case K_POST_FWD: step_post_fwd(d, tile, t); break;
+    case K_CE: step_ce(d, tile, t, red); break;
+    case K_GNB_REDUCE: step_gnb_reduce(d, tile, t, red); break;
+    case K_GNB_APPLY: step_gnb_apply(d, tile, t); break;
+    case K_CONV_BWD_X: step_conv_bwd_x(d, tile, t); break;
+    case K_CONV_BWD_W: step_conv_bwd_w(d, tile, t); break;
+    case K_COPY: step_copy(d, tile, t); break;
+    default: break;
+  }
+}
+
+// Copies the tick's sample into the first stage's input ring and its label
+// into the label ring.  staging != nullptr: sample/label were handed over by
+// the host call; otherwise they come from the resident pool.
+__global__ void __launch_bounds__(BLK)
+k_ingest(TRef ring0, int n_elems, const float* __restrict__ staging, int label,
+         int32_t* __restrict__ label_ring, int n_stages, const Globals* __restrict__ G, int k) {
+  const int t = G->t_base + k;
+  const float* src = staging;
+  int lab = label;
+  if (!src) {
+    const int item = (int)(((int64_t)G->idx_base + k) % G->n_pool);
+    src = G->pool + (size_t)item * n_elems;
+    lab = G->pool_labels[item];
+  }
+  float* dst = at(ring0, t);
+  const int i = blockIdx.x * BLK + threadIdx.x;
+  if (i < n_elems) dst[i] = src[i];
+  if (i == 0) label_ring[t % n_stages] = lab;
+}
+
+// Fused Spike-Compensated momentum update with Linear Weight Prediction over
+// the flat parameter arena: v <- m v + g; w <- w - lr (a v + b g);
+// w_hat <- w - lr T v.  Each workgroup owns UPD_CHUNK consecutive floats,
+// which belong to exactly one stage (stages are padded to the chunk size).
+__global__ void __launch_bounds__(BLK)
+k_update(float* __restrict__ w, float* __restrict__ v, const float* __restrict__ g,
+         float* __restrict__ what, const int32_t* __restrict__ chunk_stage,
+         const UpdSeg* __restrict__ segs, float lr, float m, const Globals* __restrict__ G, int k) {
+  const int t = G->t_base + k;
+  const UpdSeg sg = segs[chunk_stage[blockIdx.x]];
+  if (t < sg.first_tick) return;
+  const size_t i = (size_t)blockIdx.x * UPD_CHUNK / 4 + threadIdx.x;
+  const float4 gv = reinterpret_cast<const float4*>(g)[i];
+  float4 vv = reinterpret_cast<float4*>(v)[i];
+  float4 wv = reinterpret_cast<float4*>(w)[i];
+  vv.x = fmaf(m, vv.x, gv.x); vv.y = fmaf(m, vv.y, gv.y);
+  vv.z = fmaf(m, vv.z, gv.z); vv.w = fmaf(m, vv.w, gv.w);
+  wv.x = fmaf(-lr, fmaf(sg.a, vv.x, sg.b * gv.x), wv.x);
+  wv.y = fmaf(-lr, fmaf(sg.a, vv.y, sg.b * gv.y), wv.y);
+  wv.z = fmaf(-lr, fmaf(sg.a, vv.z, sg.b * gv.z), wv.z);
+  wv.w = fmaf(-lr, fmaf(sg.a, vv.w, sg.b * gv.w), wv.w);
+  reinterpret_cast<float4*>(v)[i] = vv;
+  reinterpret_cast<float4*>(w)[i] = wv;
+  if (what) {
+    float4 p;
+    p.x = fmaf(-sg.lrT, vv.x, wv.x); p.y = fmaf(-sg.lrT, vv.y, wv.y);
+    p.z = fmaf(-sg.lrT, vv.z, wv.z); p.w = fmaf(-sg.lrT, vv.w, wv.w);
+    reinterpret_cast<float4*>(what)[i] = p;
+  }
+}
+
+// Same arithmetic over plain arrays with one coefficient set.
+__global__ void __launch_bounds__(BLK)
+k_update_flat(float* __restrict__ w, float* __restrict__ v, const float* __restrict__ g,
+              float* __restrict__ what, float lr, float m, float a, float b, float lrT) {
+  const size_t i = (size_t)blockIdx.x * UPD_CHUNK / 4 + threadIdx.x;
+  const float4 gv = reinterpret_cast<const float4*>(g)[i];
+  float4 vv = reinterpret_cast<float4*>(v)[i];
+  float4 wv = reinterpret_cast<float4*>(w)[i];
+  vv.x = fmaf(m, vv.x, gv.x); vv.y = fmaf(m, vv.y, gv.y);
+  vv.z = fmaf(m, vv.z, gv.z); vv.w = fmaf(m, vv.w, gv.w);
+  wv.x = fmaf(-lr, fmaf(a, vv.x, b * gv.x), wv.x);
+  wv.y = fmaf(-lr, fmaf(a, vv.y, b * gv.y), wv.y);
+  wv.z = fmaf(-lr, fmaf(a, vv.z, b * gv.z), wv.z);
+  wv.w = fmaf(-lr, fmaf(a, vv.w, b * gv.w), wv.w);
+  reinterpret_cast<float4*>(v)[i] = vv;
+  reinterpret_cast<float4*>(w)[i] = wv;
+  if (what) {
+    float4 p;
+    p.x = fmaf(-lrT, vv.x, wv.x); p.y = fmaf(-lrT, vv.y, wv.y);
+    p.z = fmaf(-lrT, vv.z, wv.z); p.w = fmaf(-lrT, vv.w, wv.w);
+    reinterpret_cast<float4*>(what)[i] = p;
+  }
+}
+
+__global__ void k_set_globals(Globals* G, Globals val) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *G = val;
+}
+
+__global__ void k_advance(Globals* G, int dt, int didx) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    G->t_base += dt;
+    G->idx_base = (int)(((int64_t)G->idx_base + didx) % G->n_pool);
+  }
+}
+
+// --------------------------------------------------------- launch wrappers
+void launch_phase(const StepDesc* steps_dev, const int32_t* tile_prefix_dev, int n_steps,
+                  int total_tiles, const Globals* G, int k, hipStream_t s) {
+  if (total_tiles <= 0) return;
+  hipLaunchKernelGGL(k_phase, dim3(total_tiles), dim3(BLK), 0, s, steps_dev, tile_prefix_dev, n_steps,
+                     G, k);
+}
+
+void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,
+                   int n_stages, const Globals* G, int k, hipStream_t s) {
+  hipLaunchKernelGGL(k_ingest, dim3((n_elems + BLK - 1) / BLK), dim3(BLK), 0, s, ring0, n_elems,
+                     staging, label, label_ring, n_stages, G, k);
+}
+
+void launch_update(float* w, float* v, const float* g, float* what, const int32_t* chunk_stage,
+                   const UpdSeg* segs, int n_chunks, float lr, float m, const Globals* G, int k,
+                   hipStream_t s) {
+  hipLaunchKernelGGL(k_update, dim3(n_chunks), dim3(BLK), 0, s, w, v, g, what, chunk_stage, segs, lr,
+                     m, G, k);
+}
+
+void launch_update_flat(float* w, float* v, const float* g, float* what, int64_t n, float lr, float m,
+                        float a, float b, float lrT, hipStream_t s) {
+  hipLaunchKernelGGL(k_update_flat, dim3((unsigned)(n / UPD_CHUNK)), dim3(BLK), 0, s, w, v, g, what,
+                     lr, m, a, b, lrT);
+}
+
+void launch_set_globals(Globals* G, Globals val, hipStream_t s) {
+  hipLaunchKernelGGL(k_set_globals, dim3(1), dim3(64), 0, s, G, val);
+}
+
+void launch_advance(Globals* G, int dt, int didx, hipStream_t s) {
+  hipLaunchKernelGGL(k_advance, dim3(1), dim3(64), 0, s, G, dt, didx);
+}
+
+}  // namespace pb

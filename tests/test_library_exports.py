@@ -1,0 +1,52 @@
+"""The C-ABI library loads and exports every symbol include/pb.h declares
+(no compute calls: this runs without a GPU)."""
+import ctypes
+import os
+import re
+
+import pb_workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "pb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pb_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    from paper_2003_11666_amd import binding as B
+    if not os.path.exists(B.lib_path()):
+        from paper_2003_11666_amd import build
+        build.build(verbose=False)
+    lib = B.load_library()
+    names = _declared()
+    assert "pb_init" in names and "pb_tick" in names and "pb_read_weights" in names \
+        and "pb_loss_history" in names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_descriptor_validation_on_host():
+    from paper_2003_11666_amd import binding as B
+    lib = B.load_library()
+    for name in ("mlp", "vgg11", "resnet20", "wide"):
+        d, keep = B.marshal_net(W.config(name))
+        assert lib.pb_arena_bytes(ctypes.byref(d), None) > 0, name
+    # natural delays accepted, others refused
+    net = W.config("tiny_resnet")
+    S = len(net["stages"])
+    d, keep = B.marshal_net(net)
+    nat = (ctypes.c_int32 * S)(*[2 * (S - 1 - s) for s in range(S)])
+    assert lib.pb_arena_bytes(ctypes.byref(d), nat) > 0
+    zero = (ctypes.c_int32 * S)(*([0] * S))
+    assert lib.pb_arena_bytes(ctypes.byref(d), zero) == 0
+    assert b"differs" in lib.pb_last_error()
+    # broken descriptor: loss op missing
+    bad = dict(net)
+    bad["stages"] = [list(st) for st in net["stages"]]
+    bad["stages"][-1] = bad["stages"][-1][:-1]
+    d, keep = B.marshal_net(bad)
+    assert lib.pb_arena_bytes(ctypes.byref(d), None) == 0
