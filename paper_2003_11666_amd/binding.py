@@ -49,6 +49,10 @@ def load_library():
     global _LIB
     if _LIB is not None:
         return _LIB
+    # PyTorch ships its own HIP runtime; it must be in the process first so that
+    # the library binds to the same runtime instance that owns the tensors and
+    # streams handed to it.
+    import torch  # noqa: F401
     path = lib_path()
     if not os.path.exists(path):
         raise PBError(f"{path} is missing: build it with `python -m paper_2003_11666_amd.build`")

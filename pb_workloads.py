@@ -195,3 +195,41 @@ def sample_pool(net, n=None, seed=None):
     x = rng.standard_normal((n, net["in_c"], net["in_h"], net["in_w"]), dtype=np.float32)
     y = rng.integers(0, net["n_classes"], size=n, dtype=np.int32)
     return x, y
+
+
+def stage_shapes(net):
+    """[(in_shape, out_shape)] per stage, (C,H,W) tuples; structure only."""
+    c, h, w = net["in_c"], net["in_h"], net["in_w"]
+    out = []
+    for st in net["stages"]:
+        cin = (c, h, w)
+        for o in st:
+            k = o["kind"]
+            if k == "conv":
+                c = o["cout"]
+                h = (h + 2 * o["pad"] - o["k"]) // o["stride"] + 1
+                w = (w + 2 * o["pad"] - o["k"]) // o["stride"] + 1
+            elif k == "linear":
+                c, h, w = o["cout"], 1, 1
+            elif k == "maxpool":
+                h = (h + 2 * o["pad"] - o["k"]) // o["stride"] + 1
+                w = (w + 2 * o["pad"] - o["k"]) // o["stride"] + 1
+            elif k == "gap":
+                h = w = 1
+        out.append((cin, (c, h, w)))
+    return out
+
+
+def count_params(net):
+    n = 0
+    for st in net["stages"]:
+        for o in st:
+            if o["kind"] == "conv":
+                n += o["cout"] * o["cin"] * o["k"] * o["k"] + (o["cout"] if o["bias"] else 0)
+            elif o["kind"] == "linear":
+                n += o["cout"] * o["cin"] + (o["cout"] if o["bias"] else 0)
+            elif o["kind"] == "gn":
+                n += 2 * o["cin"]
+            elif o["kind"] == "add" and o["proj"]:
+                n += o["cout"] * o["cin"]
+    return n
