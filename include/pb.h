@@ -84,6 +84,7 @@ typedef struct {
   int32_t bwd_weights;        /* 0 backward pass uses current weights (the paper's PB)      */
   int32_t act_dtype;          /* 0 fp32 activations                                         */
   int32_t loss_capacity;      /* losses kept (most recent); 0 = 1<<20                       */
+  int32_t kernel_set;         /* 0 tiled MFMA kernels (default), 1 plain direct kernels     */
   void* device_arena;         /* DEVICE memory owned by the caller (>= pb_arena_bytes, 256-byte
                                  aligned) that must outlive the context, or NULL: the library
                                  allocates and frees its own */
@@ -154,6 +155,11 @@ int pb_profile_end(pb_ctx* ctx, int32_t which, int64_t* n_launches, double* tota
  * w_hat == NULL).  Used to measure the kernel at sizes beyond the caches. */
 int pb_update_standalone(float* w_dev, float* v_dev, const float* g_dev, float* what_dev, int64_t n,
                          float lr, float m, float a, float b, float lrT, void* stream);
+
+/* Human-readable table of the steps one tick consists of (stage, phase, kernel
+ * kind, tiles, GEMM tiling), one line per step.  Returns the bytes needed
+ * including the terminator; writes at most cap bytes into buf (may be NULL). */
+int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap);
 
 int pb_sync(pb_ctx* ctx);
 void pb_destroy(pb_ctx* ctx);

@@ -15,7 +15,7 @@ OP_KIND = {"linear": 0, "conv": 1, "gn": 2, "relu": 3, "maxpool": 4, "gap": 5, "
 
 EXPORTS = ["pb_arena_bytes", "pb_init", "pb_tick", "pb_run_resident", "pb_read_weights",
            "pb_read_velocity", "pb_loss_history", "pb_num_params", "pb_num_ticks",
-           "pb_set_launch_mode", "pb_profile_begin", "pb_profile_end", "pb_update_standalone",
+           "pb_set_launch_mode", "pb_plan_summary", "pb_profile_begin", "pb_profile_end", "pb_update_standalone",
            "pb_sync", "pb_destroy", "pb_last_error"]
 
 
@@ -36,7 +36,7 @@ class _NetDesc(C.Structure):
     _fields_ = [("n_stages", C.c_int32), ("stages", C.POINTER(_Stage)),
                 ("in_c", C.c_int32), ("in_h", C.c_int32), ("in_w", C.c_int32),
                 ("n_classes", C.c_int32), ("mitigation", C.c_int32), ("bwd_weights", C.c_int32),
-                ("act_dtype", C.c_int32), ("loss_capacity", C.c_int32),
+                ("act_dtype", C.c_int32), ("loss_capacity", C.c_int32), ("kernel_set", C.c_int32),
                 ("device_arena", C.c_void_p), ("arena_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
 
@@ -83,6 +83,8 @@ def load_library():
     lib.pb_update_standalone.restype = C.c_int
     lib.pb_update_standalone.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                          C.c_float, C.c_float, C.c_float, C.c_float, C.c_float, C.c_void_p]
+    lib.pb_plan_summary.restype = C.c_int64
+    lib.pb_plan_summary.argtypes = [C.POINTER(_NetDesc), C.c_char_p, C.c_int64]
     lib.pb_sync.restype = C.c_int
     lib.pb_sync.argtypes = [C.c_void_p]
     lib.pb_destroy.restype = None
@@ -99,7 +101,7 @@ def _check(lib, rc):
     return rc
 
 
-def marshal_net(net, mitigation=3, bwd_weights=0, loss_capacity=0):
+def marshal_net(net, mitigation=3, bwd_weights=0, loss_capacity=0, kernel_set=0):
     """dict descriptor (pb_workloads) -> pb_net_desc; returns (desc, keepalive)."""
     keep = []
     stages = (_Stage * len(net["stages"]))()
@@ -119,17 +121,29 @@ def marshal_net(net, mitigation=3, bwd_weights=0, loss_capacity=0):
     d.mitigation, d.bwd_weights = mitigation, bwd_weights
     d.act_dtype = {"fp32": 0, "bf16": 1}[net.get("act_dtype", "fp32")]
     d.loss_capacity = loss_capacity
+    d.kernel_set = kernel_set
     return d, keep
+
+
+def plan_summary(net, **kw):
+    lib = load_library()
+    desc, keep = marshal_net(net, **kw)
+    n = lib.pb_plan_summary(C.byref(desc), None, 0)
+    if n < 0:
+        raise PBError(lib.pb_last_error().decode())
+    buf = C.create_string_buffer(n)
+    lib.pb_plan_summary(C.byref(desc), buf, n)
+    return buf.value.decode()
 
 
 class PBEngine:
     """pb_init / pb_tick / pb_run_resident / pb_read_weights / pb_loss_history."""
 
     def __init__(self, net, lr=None, momentum=None, seed=42, mitigation=3, delays=None,
-                 bwd_weights=0, loss_capacity=0, torch_arena=True):
+                 bwd_weights=0, loss_capacity=0, torch_arena=True, kernel_set=0):
         self.lib = load_library()
         self.net = net
-        desc, self._keep = marshal_net(net, mitigation, bwd_weights, loss_capacity)
+        desc, self._keep = marshal_net(net, mitigation, bwd_weights, loss_capacity, kernel_set)
         dl = None
         if delays is not None:
             dl = (C.c_int32 * len(delays))(*delays)

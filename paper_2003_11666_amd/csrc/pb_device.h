@@ -33,7 +33,29 @@ enum StepKind : int32_t {
   K_GNB_APPLY = 6,   // GroupNorm backward: elementwise dx
   K_CONV_BWD_X = 7,  // backward data
   K_CONV_BWD_W = 8,  // backward weights (+ bias)
-  K_COPY = 9
+  K_COPY = 9,
+  K_GEMM = 10,       // conv / linear forward, backward data or backward weights as an MFMA implicit GEMM
+  K_BIAS_GRAD = 11   // db[co] = sum_p dZ[co,p]
+};
+
+constexpr int LDS_FLOATS = 12288;   // 48 KB of LDS per workgroup for the GEMM steps
+
+// Tiling of one implicit-GEMM operand set: C[M x N] += A[M x Q] * B[Q x N] with
+// B[q][n] = patch[offq(q) + offn(n)], the patch being a zero-padded window of
+// the activation (or of the dilated output gradient) staged in LDS.
+struct GemmCfg {
+  int32_t gm;             // 0 = none, 1 = forward, 2 = backward data, 3 = backward weights
+  int32_t M, N, Q;
+  int32_t wm, wn, wk, ni; // 4 waves = wm x wn x wk (split of the reduction); ni 16-column subtiles per wave
+  int32_t MT, NT, tiles_n, tiles;
+  int32_t QC;             // reduction elements per chunk
+  int32_t QCpad;          // rounded up to a multiple of 4
+  int32_t CC;             // channels per patch
+  int32_t rows_c;         // backward weights: output rows per chunk
+  int32_t PR, Wp;         // patch rows / width
+  int32_t LDA;
+  int32_t o_offq, o_patch;   // LDS offsets (floats); the A chunk sits at 0
+  int32_t n_chunks;
 };
 
 enum StepFlags : int32_t {
@@ -62,6 +84,8 @@ struct StepDesc {
   int32_t sC, sH, sW, sstride;  // skip tensor dims and projection stride
   int32_t n;                // generic element count (CE: classes, COPY: floats)
   int32_t loss_cap, n_stages;
+  GemmCfg g;     // main operand set of a K_GEMM step
+  GemmCfg gp;    // projection of the skip tensor accumulated into the same tile (forward only)
   TRef x;        // op input (forward) / saved input (backward)
   TRef st;       // statistics slot: mean[G], rstd[G], sc[C], sh[C]
   TRef y;        // op output

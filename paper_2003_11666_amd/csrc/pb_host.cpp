@@ -3,6 +3,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -67,6 +68,7 @@ int parse_net(const pb_net_desc* net, std::vector<Stage>& out) {
   if (net->mitigation < 0 || net->mitigation > 3) return fail(PB_E_INVALID, "mitigation must be 0..3");
   if (net->bwd_weights != 0) return fail(PB_E_UNSUPPORTED, "bwd_weights=%d (weight stashing) not implemented", net->bwd_weights);
   if (net->act_dtype != 0) return fail(PB_E_UNSUPPORTED, "act_dtype=%d not implemented", net->act_dtype);
+  if (net->kernel_set < 0 || net->kernel_set > 1) return fail(PB_E_INVALID, "kernel_set must be 0 or 1");
   const int S = net->n_stages;
   out.assign(S, Stage());
   int C = net->in_c, H = net->in_h, W = net->in_w;
@@ -270,6 +272,7 @@ struct pb_ctx {
   hipStream_t stream = nullptr;
   int64_t ticks = 0;
   int launch_mode = 0;
+  int kernel_set = 0;
   std::vector<StepDesc> steps;         // sorted by phase
   std::vector<int32_t> prefix;         // per step: first tile within its phase
   std::vector<Phase> phases;
@@ -320,6 +323,86 @@ int bwd_w_tiles(int K, int C, int k, int P, bool bias) {
   return cdiv(nW, per) + (bias ? cdiv(K, per) : 0);
 }
 
+// ---------------------------------------------------------- GEMM tiling
+int pow2_floor(int x) { int p = 1; while (p * 2 <= x) p *= 2; return p; }
+
+// Choose the tiling of one implicit-GEMM operand set.  mode 1 forward, 2
+// backward data, 3 backward weights.  `like` != nullptr forces the wave
+// arrangement of an existing configuration (projection accumulated into the
+// same tile).  Returns false if no chunking fits the LDS budget.
+int g_tile_target = 8;   // workgroups a step is split into at least, when its shape allows
+
+bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int s, int pad,
+               const GemmCfg* like, GemmCfg* out) {
+  const int target = g_tile_target;
+  GemmCfg g;
+  memset(&g, 0, sizeof g);
+  g.gm = mode;
+  const int kk = k * k, P = OH * OW, HWi = H * W;
+  if (mode == 1) { g.M = K; g.N = P; g.Q = C * kk; }
+  else if (mode == 2) { g.M = C; g.N = HWi; g.Q = K * kk; }
+  else { g.M = K; g.N = C * kk; g.Q = P; }
+  if (like) {
+    g.wm = like->wm; g.wn = like->wn; g.wk = like->wk; g.ni = like->ni;
+  } else {
+    const int mt = cdiv(g.M, 16), n16 = cdiv(g.N, 16);
+    g.wm = mt >= 4 ? 4 : mt >= 2 ? 2 : 1;
+    const int rest = 4 / g.wm;
+    if (mode == 3 && g.Q >= 256) { g.wk = rest; g.wn = 1; }
+    else { g.wn = std::min(rest, pow2_floor(n16)); g.wk = rest / g.wn; }
+    g.ni = std::min(4, cdiv(n16, g.wn));
+    auto tiles = [&]() { return cdiv(g.M, 16 * g.wm) * cdiv(g.N, 16 * g.ni * g.wn); };
+    while (tiles() < target && g.ni > 1) g.ni = (g.ni + 1) / 2;
+    while (tiles() < target && g.wm > 1 && g.Q >= 64 * g.wk * 2) { g.wm /= 2; g.wk *= 2; }
+    while (tiles() < target && g.wn > 1 && g.Q >= 64 * g.wk * 2) { g.wn /= 2; g.wk *= 2; }
+  }
+  g.MT = 16 * g.wm; g.NT = 16 * g.ni * g.wn;
+  g.tiles_n = cdiv(g.N, g.NT);
+  g.tiles = cdiv(g.M, g.MT) * g.tiles_n;
+  auto fits = [&](int QC, int CC, int PR, int Wp) {
+    const int QCpad = (QC + 3) / 4 * 4, LDA = QCpad + 2;
+    const int64_t need = (int64_t)g.MT * LDA + QCpad + (int64_t)CC * PR * Wp + 64;
+    return need <= LDS_FLOATS;
+  };
+  if (mode == 1 || mode == 2) {
+    const int rowlen = mode == 1 ? OW : W, nrows = mode == 1 ? OH : H;
+    const int rows_max = std::min(nrows, (g.NT + rowlen - 2) / rowlen + 1);
+    g.PR = mode == 1 ? (rows_max - 1) * s + k : rows_max + k - 1;
+    g.Wp = mode == 1 ? W + 2 * pad : W + k - 1;
+    const int nch = mode == 1 ? C : K;
+    int CC = nch;
+    while (CC > 1 && !fits(CC * kk, CC, g.PR, g.Wp)) CC = (CC + 1) / 2;
+    if (!fits(CC * kk, CC, g.PR, g.Wp)) return false;
+    g.CC = CC; g.QC = CC * kk; g.n_chunks = cdiv(nch, CC); g.rows_c = 0;
+  } else {
+    g.CC = std::min(C, (g.NT + kk - 2) / kk + 1);
+    g.Wp = W + 2 * pad;
+    auto pr = [&](int r) { return (r - 1) * s + k; };
+    // one chunk holding every output row, else the largest row count whose
+    // pixel count is a multiple of 4 (chunks in the middle must not be padded)
+    int rows = 0;
+    if (fits(OH * OW, g.CC, pr(OH), g.Wp)) {
+      rows = OH;
+    } else {
+      int step = 1;
+      while ((step * OW) % 4) ++step;
+      for (int r = step; r < OH; r += step) {
+        if (!fits(r * OW, g.CC, pr(r), g.Wp)) break;
+        rows = r;
+      }
+    }
+    if (!rows) return false;
+    g.rows_c = rows; g.QC = rows * OW; g.PR = pr(rows); g.n_chunks = cdiv(OH, rows);
+  }
+  g.QCpad = (g.QC + 3) / 4 * 4;
+  g.LDA = g.QCpad + 2;
+  g.o_offq = (g.MT * g.LDA + 3) / 4 * 4;
+  g.o_patch = (g.o_offq + g.QCpad + 3) / 4 * 4;
+  if (g.o_patch + g.CC * g.PR * g.Wp > LDS_FLOATS) return false;
+  *out = g;
+  return true;
+}
+
 // Compile the network into the step table.  Every step carries the phase it
 // may run in: steps of one stage's forward (or backward) chain depend on each
 // other and get consecutive phases; different stages and the two passes of
@@ -328,6 +411,10 @@ int bwd_w_tiles(int K, int C, int k, int P, bool bias) {
 // pass consumes the loss gradient of the same tick.
 void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   const int S = c->S;
+  // all stages run concurrently: aim at a few workgroups per compute unit over
+  // the whole phase rather than per step
+  g_tile_target = std::max(4, std::min(32, 1024 / (3 * S)));
+  if (const char* e = getenv("PB_TILE_TARGET")) g_tile_target = std::max(1, atoi(e));
   const Layout& L = c->L;
   const bool lwp = L.what >= 0;
   for (int s = 0; s < S; ++s) {
@@ -388,6 +475,13 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         }
       }
       d.ntiles = cdiv((int64_t)a.K * a.OH * a.OW, BLK);
+      if (c->kernel_set == 0) {
+        GemmCfg g, gp;
+        memset(&gp, 0, sizeof gp);
+        bool ok = make_gemm(1, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g);
+        if (ok && (d.flags & F_PROJ)) ok = make_gemm(1, d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, 0, &g, &gp);
+        if (ok) { d.kind = K_GEMM; d.g = g; d.gp = gp; d.ntiles = g.tiles; }
+      }
       out.push_back({ph++, d});
     }
     if (a.post_gn) {
@@ -455,6 +549,16 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       d.gw = gr + a.o_w;
       if (a.has_bias) { d.flags |= F_BIAS; d.gb = gr + a.o_b; }
       d.ntiles = bwd_w_tiles(a.K, a.C, a.k, a.OH * a.OW, a.has_bias);
+      GemmCfg g;
+      if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g)) {
+        if (a.has_bias) {
+          StepDesc e = blank(K_BIAS_GRAD, s, t_b);
+          e.K = a.K; e.OH = a.OH; e.OW = a.OW; e.dy = dz_src; e.gb = gr + a.o_b;
+          e.ntiles = cdiv(a.K, BLK / 64);
+          out.push_back({pb, e});
+        }
+        d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles; d.flags &= ~F_BIAS;
+      }
       out.push_back({pb, d});
     }
     if (s > 0) {   // data gradient of the main layer
@@ -471,6 +575,10 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         if (a.tap_dist) { d.flags |= F_ADD_SKG; d.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
       }
       d.ntiles = cdiv((int64_t)a.C * a.H * a.W, BLK);
+      GemmCfg g;
+      if (c->kernel_set == 0 && make_gemm(2, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g)) {
+        d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
+      }
       out.push_back({pb, d});
     }
     if (a.add) {   // skip path: projection weight gradient and the gradient sent to the tap stage
@@ -485,6 +593,10 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         d.dy = dy_src;
         d.gw = gr + a.o_wp;
         d.ntiles = bwd_w_tiles(a.K, a.sC, 1, a.OH * a.OW, false);
+        GemmCfg g;
+        if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, 1, d.stride, 0, nullptr, &g)) {
+          d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
+        }
         out.push_back({pb, d});
         StepDesc e = blank(K_CONV_BWD_X, s, t_b);
         e.C = a.sC; e.H = a.sH; e.W = a.sW; e.K = a.K; e.OH = a.OH; e.OW = a.OW;
@@ -493,6 +605,10 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         e.w = wb + a.o_wp;
         e.dx = skg_w;
         e.ntiles = cdiv(ta.in_elems(), BLK);
+        GemmCfg g2;
+        if (c->kernel_set == 0 && make_gemm(2, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, 0, nullptr, &g2)) {
+          e.kind = K_GEMM; e.g = g2; e.ntiles = g2.tiles;
+        }
         out.push_back({pb, e});
       } else {
         StepDesc d = blank(K_COPY, s, t_b);
@@ -596,6 +712,56 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
       case K_COPY:
         ok = ok && (int64_t)d.ntiles * BLK >= d.n && ref_ok(d.dy, d.n) && ref_ok(d.dx, d.n);
         break;
+      case K_BIAS_GRAD:
+        ok = ok && d.ntiles * (BLK / 64) >= d.K && ref_ok(d.dy, outn) && ptr_ok(d.gb, d.K);
+        break;
+      case K_GEMM: {
+        auto cfg_ok = [&](const GemmCfg& g, int C, int H, int W, int k, int s, int pad) {
+          const int kk = k * k;
+          bool o = g.wm * g.wn * g.wk == 4 && g.ni >= 1 && g.ni <= 4 && g.MT == 16 * g.wm && g.NT == 16 * g.ni * g.wn &&
+                   g.tiles_n == cdiv(g.N, g.NT) && g.tiles == cdiv(g.M, g.MT) * g.tiles_n && g.QCpad % 4 == 0 &&
+                   g.QCpad >= g.QC && g.LDA >= g.QCpad && g.o_offq >= g.MT * g.LDA && g.o_patch >= g.o_offq + g.QCpad &&
+                   (int64_t)g.o_patch + (int64_t)g.CC * g.PR * g.Wp <= LDS_FLOATS && LDS_FLOATS >= 4096 &&
+                   (int64_t)g.n_chunks * g.QC >= g.Q;
+          if (g.gm == 1) {
+            const int rows_max = std::min(d.OH, (g.NT + d.OW - 2) / d.OW + 1);
+            o = o && g.M == d.K && g.N == d.OH * d.OW && g.Q == C * kk && g.QC == g.CC * kk &&
+                g.PR >= (rows_max - 1) * s + k && g.Wp >= W + 2 * pad && g.Wp >= (d.OW - 1) * s + k;
+          } else if (g.gm == 2) {
+            const int rows_max = std::min(H, (g.NT + W - 2) / W + 1);
+            o = o && g.M == C && g.N == H * W && g.Q == d.K * kk && g.QC == g.CC * kk && g.PR >= rows_max + k - 1 &&
+                g.Wp >= W + k - 1 && pad <= k - 1;
+          } else if (g.gm == 3) {
+            o = o && g.M == d.K && g.N == C * kk && g.Q == d.OH * d.OW && g.QC == g.rows_c * d.OW &&
+                g.CC >= std::min(C, (g.NT + kk - 2) / kk + 1) && g.PR >= (g.rows_c - 1) * s + k && g.Wp >= W + 2 * pad &&
+                g.Wp >= (d.OW - 1) * s + k && (g.n_chunks == 1 || g.QC % 4 == 0);
+          } else {
+            o = false;
+          }
+          return o;
+        };
+        ok = ok && d.ntiles == d.g.tiles && cfg_ok(d.g, d.C, d.H, d.W, d.k, d.stride, d.pad);
+        const int64_t wn_ = (int64_t)d.K * d.C * d.k * d.k;
+        if (d.g.gm == 1) {
+          ok = ok && ref_ok(d.x, in) && ref_ok(d.y, outn) && ptr_ok(d.w, wn_) &&
+               (!(d.flags & F_PRE_AFFINE) || ref_ok(d.st, stn)) && (!(d.flags & F_BIAS) || ptr_ok(d.b, d.K));
+          if (d.flags & F_SKIP) {
+            if (d.flags & F_PROJ)
+              ok = ok && d.gp.gm == 1 && d.gp.wm == d.g.wm && d.gp.wn == d.g.wn && d.gp.wk == d.g.wk && d.gp.ni == d.g.ni &&
+                   cfg_ok(d.gp, d.sC, d.sH, d.sW, 1, d.sstride, 0) && ref_ok(d.skip, (int64_t)d.sC * d.sH * d.sW) &&
+                   ptr_ok(d.wp, (int64_t)d.K * d.sC) && (d.OH - 1) * d.sstride < d.sH && (d.OW - 1) * d.sstride < d.sW;
+            else
+              ok = ok && ref_ok(d.skip, outn);
+          }
+        } else if (d.g.gm == 2) {
+          ok = ok && ref_ok(d.dy, outn) && ref_ok(d.dx, in) && ptr_ok(d.w, wn_) &&
+               (!(d.flags & F_MASK_X) || ref_ok(d.x, in)) && (!(d.flags & F_ADD_SKG) || ref_ok(d.skg, in));
+        } else {
+          ok = ok && ref_ok(d.x, in) && ref_ok(d.dy, outn) && ptr_ok(d.gw, wn_) &&
+               (!(d.flags & F_PRE_AFFINE) || ref_ok(d.st, stn)) && !(d.flags & F_BIAS);
+        }
+        break;
+      }
       default:
         ok = false;
     }
@@ -723,6 +889,7 @@ size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays) {
   if (parse_net(net, st) != PB_OK || check_delays(st, delays) != PB_OK) return 0;
   pb_ctx tmp;
   tmp.st = st; tmp.S = (int)st.size();
+  tmp.kernel_set = net->kernel_set;
   const int cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   Plan pl;
   Layout L;
@@ -738,6 +905,43 @@ size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays) {
   pl.alloc(L.P / UPD_CHUNK + 64);
   pl.alloc((int64_t)st.size() * sizeof(UpdSeg) / 4 + 64);
   return (size_t)pl.total * sizeof(float) + 256;
+}
+
+int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
+  std::vector<Stage> st;
+  if (parse_net(net, st) != PB_OK) return PB_E_INVALID;
+  pb_ctx tmp;
+  tmp.st = st; tmp.S = (int)st.size(); tmp.kernel_set = net->kernel_set;
+  const int lcap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
+  Plan pl;
+  plan_arena(st, net->mitigation >= 2, lcap, tmp.L, pl);
+  tmp.loss_cap = lcap;
+  std::vector<std::pair<int, StepDesc>> steps;
+  compile_steps(&tmp, steps);
+  static const char* names[] = {"gn_stats", "gap_fwd", "conv_fwd", "post_fwd", "ce", "gnb_reduce", "gnb_apply",
+                                "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad"};
+  std::string o;
+  char line[400];
+  for (auto& pr : steps) {
+    const StepDesc& d = pr.second;
+    snprintf(line, sizeof line, "stage %2d phase %d %-10s tiles %6d first_tick %3d C%dx%dx%d K%dx%dx%d k%d s%d", d.stage,
+             pr.first, names[d.kind], d.ntiles, d.first_tick, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride);
+    o += line;
+    if (d.kind == K_GEMM) {
+      const GemmCfg& g = d.g;
+      snprintf(line, sizeof line, " | gm%d M%d N%d Q%d waves %dx%dx%d ni%d tile %dx%d chunks %d QC%d CC%d PR%d Wp%d lds %d",
+               g.gm, g.M, g.N, g.Q, g.wm, g.wn, g.wk, g.ni, g.MT, g.NT, g.n_chunks, g.QC, g.CC, g.PR, g.Wp,
+               g.o_patch + g.CC * g.PR * g.Wp);
+      o += line;
+    }
+    o += "\n";
+  }
+  if (buf && cap > 0) {
+    const int64_t n = std::min<int64_t>(cap - 1, (int64_t)o.size());
+    memcpy(buf, o.data(), n);
+    buf[n] = 0;
+  }
+  return (int64_t)o.size() + 1;
 }
 
 int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float lr, float momentum,
@@ -757,6 +961,7 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   pb_ctx* c = new pb_ctx();
   c->st = st; c->S = (int)st.size();
   c->mitigation = net->mitigation; c->lr = lr; c->m = momentum;
+  c->kernel_set = net->kernel_set;
   c->loss_cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   c->stream = (hipStream_t)net->stream;
   for (const Stage& a : st) c->n_params += a.n_params;

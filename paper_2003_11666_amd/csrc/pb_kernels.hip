@@ -44,6 +44,10 @@ __device__ __forceinline__ float block_max(float v, float* red) {
   return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
+}  // namespace pb
+#include "pb_gemm.h"
+namespace pb {
+
 // ------------------------------------------------------------ forward steps
 // GroupNorm statistics of one group (biased variance, two passes) and the
 // folded per-channel scale/shift built from the forward (predicted) affine
@@ -370,6 +374,7 @@ __global__ void __launch_bounds__(BLK)
 k_phase(const StepDesc* __restrict__ steps, const int32_t* __restrict__ prefix, int n_steps,
         const Globals* __restrict__ G, int k) {
   __shared__ float red[8];
+  __shared__ __attribute__((aligned(16))) float smem[LDS_FLOATS];
   const int t = G->t_base + k;
   // which step does this workgroup belong to (prefix[i] = first tile of step i)
   int lo = 0, hi = n_steps - 1;
@@ -392,6 +397,8 @@ k_phase(const StepDesc* __restrict__ steps, const int32_t* __restrict__ prefix, 
     case K_CONV_BWD_X: step_conv_bwd_x(d, tile, t); break;
     case K_CONV_BWD_W: step_conv_bwd_w(d, tile, t); break;
     case K_COPY: step_copy(d, tile, t); break;
+    case K_GEMM: step_gemm(d, tile, t, smem); break;
+    case K_BIAS_GRAD: step_bias_grad(d, tile, t); break;
     default: break;
   }
 }
