@@ -65,6 +65,7 @@ def main():
     ap.add_argument("--config", default="resnet20")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-standalone", action="store_true")
+    ap.add_argument("--launch-mode", type=int, default=0, help="1 = one launch per step (profiling aid)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the pipeline on ONE GPU only; --gpus must be 1 "
@@ -83,6 +84,8 @@ def main():
     xd = torch.from_numpy(xs).to(dev)
     yd = torch.from_numpy(ys).to(dev)
     eng = PBEngine(net, mitigation=3)
+    if args.launch_mode:
+        eng.set_launch_mode(args.launch_mode)
     n_params = eng.n_params
 
     warm = max(args.warmup, 2 * (S - 1) + 1)      # steady state: every stage busy

@@ -56,6 +56,7 @@ struct GemmCfg {
   int32_t LDA;
   int32_t o_offq, o_patch;   // LDS offsets (floats); the A chunk sits at 0
   int32_t n_chunks;
+  int32_t lgA, lgP;        // log2 of the padded row lengths used by the staging thread maps
 };
 
 enum StepFlags : int32_t {
@@ -75,6 +76,7 @@ enum StepFlags : int32_t {
 
 struct StepDesc {
   int32_t kind, stage, first_tick, ntiles;
+  int32_t tile;             // per-workgroup records: which tile of the step this workgroup runs
   int32_t flags;
   int32_t C, H, W;          // input tensor of the op
   int32_t K, OH, OW;        // output tensor of the op
@@ -124,8 +126,7 @@ struct UpdSeg {       // per stage constants of the fused update
 };
 
 // ---- launch wrappers implemented in pb_kernels.hip ----
-void launch_phase(const StepDesc* steps_dev, const int32_t* tile_prefix_dev, int n_steps,
-                  int total_tiles, const Globals* G, int k, hipStream_t s);
+void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, hipStream_t s);
 void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,
                    int n_stages, const Globals* G, int k, hipStream_t s);
 void launch_update(float* w, float* v, const float* g, float* what, const int32_t* chunk_stage,

@@ -8,7 +8,13 @@
 // B is never materialised: B[q][n] = patch[offq(q) + offn(n)], where the patch
 // is a zero-padded window of the (normalised, rectified) input -- or of the
 // output gradient placed at stride spacing -- staged in LDS per chunk of the
-// reduction, and offq / offn are separable offsets into it.
+// reduction, and offq / offn are separable offsets into it.  A goes from
+// global memory straight into the MFMA operand registers.
+//
+// The code is kept small on purpose: a tile's work is a few hundred MFMAs, so
+// instruction fetch of a long unrolled path costs more than it saves.
+//
+// Included by pb_kernels.hip after its address-space helpers.
 #pragma once
 #include "pb_device.h"
 
@@ -16,188 +22,268 @@ namespace pb {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-struct Geo { int C, H, W, K, OH, OW, k, s, pad; };
-
-// Accumulate one operand set into acc[0..ni).  Aglob: weights (forward,
-// backward data) or dZ (backward weights); src: activation (forward, backward
-// weights) or dZ (backward data); st != nullptr applies sc[c]*x+sh[c], relu
-// then max(.,0), while staging.
-__device__ __forceinline__ void gemm_accumulate(const Geo& ge, const GemmCfg& g, const float* __restrict__ Aglob,
-                                                const float* __restrict__ src, const float* __restrict__ st,
-                                                int stG, int stC, bool relu, int m0, int n0, float* smem,
-                                                v4f acc[4]) {
+// One tile of a K_GEMM step, GM = 1 forward, 2 backward data, 3 backward
+// weights.  A forward step may carry a second operand set (the 1x1 projection
+// of the skip tensor) that accumulates into the same tile.
+template <int GM>
+__device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfloat* smem) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int wk_id = wv % g.wk, wn_id = (wv / g.wk) % g.wn, wm_id = wv / (g.wk * g.wn);
-  float* As = smem;
-  int* offq = reinterpret_cast<int*>(smem + g.o_offq);
-  float* patch = smem + g.o_patch;
-  const int kk = ge.k * ge.k, PRW = g.PR * g.Wp;
-  const int HW = ge.H * ge.W, P = ge.OH * ge.OW;
-
-  // first row (of the output map for forward / backward weights, of the input
-  // map for backward data) this tile touches, and per-lane column offsets
-  int tile_row0 = 0, c_lo = 0;
-  if (g.gm == 1) tile_row0 = n0 / ge.OW;
-  else if (g.gm == 2) tile_row0 = n0 / ge.W;
-  else c_lo = n0 / kk;
-  int offn[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int n = n0 + (wn_id * g.ni + j) * 16 + (lane & 15);
-    int o = 0;
-    if (j < g.ni && n < g.N) {
-      if (g.gm == 1) { const int oh = n / ge.OW, ow = n - oh * ge.OW; o = (oh - tile_row0) * ge.s * g.Wp + ow * ge.s; }
-      else if (g.gm == 2) { const int ih = n / ge.W, iw = n - ih * ge.W; o = (ih - tile_row0) * g.Wp + iw; }
-      else { const int ci = n / kk, tap = n - ci * kk, kh = tap / ge.k, kw = tap - kh * ge.k; o = (ci - c_lo) * PRW + kh * g.Wp + kw; }
-    }
-    offn[j] = o;
-  }
-  __syncthreads();   // LDS may still be in use by a previous operand set
-  for (int i = tid; i < g.QCpad; i += BLK) {
-    int o = 0;
-    if (i < g.QC) {
-      if (g.gm == 3) { const int r = i / ge.OW, ow = i - r * ge.OW; o = r * ge.s * g.Wp + ow * ge.s; }
-      else {
-        const int c = i / kk, tap = i - c * kk, kh = tap / ge.k, kw = tap - kh * ge.k;
-        o = (g.gm == 1) ? c * PRW + kh * g.Wp + kw : c * PRW + (ge.k - 1 - kh) * g.Wp + (ge.k - 1 - kw);
-      }
-    }
-    offq[i] = o;
-  }
-  const int a_row = (wm_id * 16 + (lane & 15)) * g.LDA + (lane >> 4);
-  const int nsteps = g.QCpad >> 2;
-  const int patch_elems = g.CC * PRW;
-  for (int ch = 0; ch < g.n_chunks; ++ch) {
-    if (ch) __syncthreads();
-    const int q0 = ch * g.QC;
-    // ---- A chunk: As[m][qr]
-    for (int idx = tid; idx < g.MT * g.QCpad; idx += BLK) {
-      const int m = idx / g.QCpad, qr = idx - m * g.QCpad, q = q0 + qr;
-      float v = 0.f;
-      if (m0 + m < g.M && qr < g.QC && q < g.Q) {
-        if (g.gm == 2) { const int co = q / kk, tap = q - co * kk; v = Aglob[(size_t)co * ge.C * kk + (size_t)(m0 + m) * kk + tap]; }
-        else v = Aglob[(size_t)(m0 + m) * g.Q + q];
-      }
-      As[m * g.LDA + qr] = v;
-    }
-    // ---- patch
-    int chan0, row0;
-    if (g.gm == 1) { chan0 = ch * g.CC; row0 = tile_row0 * ge.s - ge.pad; }
-    else if (g.gm == 2) { chan0 = ch * g.CC; row0 = tile_row0; }
-    else { chan0 = c_lo; row0 = ch * g.rows_c * ge.s - ge.pad; }
-    for (int idx = tid; idx < patch_elems; idx += BLK) {
-      const int c = idx / PRW, rem = idx - c * PRW, y = rem / g.Wp, x = rem - y * g.Wp;
-      const int chn = chan0 + c;
-      float v = 0.f;
-      if (g.gm == 2) {
-        // output gradient placed at stride spacing with a (k-1-pad) border
-        const int ty = row0 + y - (ge.k - 1 - ge.pad), tx = x - (ge.k - 1 - ge.pad);
-        if (chn < ge.K && ty >= 0 && tx >= 0 && ty % ge.s == 0 && tx % ge.s == 0) {
-          const int oh = ty / ge.s, ow = tx / ge.s;
-          if (oh < ge.OH && ow < ge.OW) v = src[(size_t)chn * P + oh * ge.OW + ow];
-        }
-      } else {
-        const int ih = row0 + y, iw = x - ge.pad;
-        if (chn < ge.C && ih >= 0 && ih < ge.H && iw >= 0 && iw < ge.W) {
-          v = src[(size_t)chn * HW + ih * ge.W + iw];
-          if (st) v = fmaf(st[2 * stG + chn], v, st[2 * stG + stC + chn]);
-          if (relu) v = fmaxf(v, 0.f);
-        }
-      }
-      patch[idx] = v;
-    }
-    __syncthreads();
-    // ---- MFMA loop: lane holds A[i = lane%16][k = lane/16] and B[k = lane/16][j = lane%16]
-    for (int ks = wk_id; ks < nsteps; ks += g.wk) {
-      const float a = As[a_row + ks * 4];
-      const int oq = offq[ks * 4 + (lane >> 4)];
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (j < g.ni) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, patch[oq + offn[j]], acc[j], 0, 0, 0);
-    }
-  }
-}
-
-// One tile of a K_GEMM step.
-__device__ void step_gemm(const StepDesc& d, int tile, int t, float* smem) {
-  const GemmCfg& g = d.g;
-  const int tm = tile / g.tiles_n, tn = tile - tm * g.tiles_n;
-  const int m0 = tm * g.MT, n0 = tn * g.NT;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int wk_id = wv % g.wk, wn_id = (wv / g.wk) % g.wn, wm_id = wv / (g.wk * g.wn);
+  const int wk = UNI(d.g.wk), wn = UNI(d.g.wn), ni = UNI(d.g.ni);
+  const int wk_id = wv % wk, wn_id = (wv / wk) % wn, wm_id = wv / (wk * wn);
+  const int tiles_n = UNI(d.g.tiles_n);
+  const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
+  const int m0 = tm * UNI(d.g.MT), n0 = tn * UNI(d.g.NT);
+  const int flags = UNI(d.flags);
   v4f acc[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
-  const Geo ge{d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad};
-  const float* st = (d.flags & F_PRE_AFFINE) ? at(d.st, t) : nullptr;
-  if (g.gm == 1) {
-    gemm_accumulate(ge, g, d.w, at(d.x, t), st, d.G, d.C, d.flags & F_PRE_RELU, m0, n0, smem, acc);
-    if (d.flags & F_PROJ) {
-      const Geo gs{d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, 0};
-      gemm_accumulate(gs, d.gp, d.wp, at(d.skip, t), nullptr, 0, 0, false, m0, n0, smem, acc);
+  const int nops = (GM == 1 && (flags & F_PROJ)) ? 2 : 1;
+  // what the epilogue adds or masks with is fetched now, together with the
+  // operands, instead of after the MFMA loop
+  float e_add[4][4], e_msk[4][4];
+  {
+    const int M = UNI(d.g.M), N = UNI(d.g.N);
+    const gfloat* skip = (GM == 1 && (flags & F_SKIP) && !(flags & F_PROJ)) ? (const gfloat*)at(d.skip, t) : nullptr;
+    const gfloat* xm = (GM == 2 && (flags & F_MASK_X)) ? (const gfloat*)at(d.x, t) : nullptr;
+    const gfloat* skg = (GM == 2 && (flags & F_ADD_SKG)) ? (const gfloat*)at(d.skg, t) : nullptr;
+    const gfloat* bias = (GM == 1 && (flags & F_BIAS)) ? GP(d.b) : nullptr;
+    const int mrow = m0 + wm_id * 16 + 4 * (lane >> 4);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        e_add[j][r] = 0.f; e_msk[j][r] = 1.f;
+        if (wk_id == 0 && j < ni && n < N && mrow + r < M) {
+          const size_t o = (size_t)(mrow + r) * N + n;
+          if (GM == 1 && bias) e_add[j][r] = bias[mrow + r];
+          if (GM == 1 && skip) e_add[j][r] += skip[o];
+          if (GM == 2 && skg) e_add[j][r] = skg[o];
+          if (GM == 2 && xm) e_msk[j][r] = xm[o];
+        }
+      }
     }
-  } else if (g.gm == 2) {
-    gemm_accumulate(ge, g, d.w, at(d.dy, t), nullptr, 0, 0, false, m0, n0, smem, acc);
-  } else {
-    gemm_accumulate(ge, g, at(d.dy, t), at(d.x, t), st, d.G, d.C, d.flags & F_PRE_RELU, m0, n0, smem, acc);
   }
+
+  for (int op = 0; op < nops; ++op) {
+    const bool second = GM == 1 && op == 1;
+    const LGemmCfg& g = second ? d.gp : d.g;
+    const int gC = UNI(second ? d.sC : d.C), gH = UNI(second ? d.sH : d.H), gW = UNI(second ? d.sW : d.W);
+    const int gK = UNI(d.K), gOH = UNI(d.OH), gOW = UNI(d.OW);
+    const int gk = second ? 1 : UNI(d.k), gs = UNI(second ? d.sstride : d.stride), gpad = second ? 0 : UNI(d.pad);
+    // A: weights (forward, backward data) or dZ (backward weights);
+    // src: activation (forward, backward weights) or dZ (backward data)
+    const gfloat* Aglob = second ? GP(d.wp) : (GM == 3 ? (const gfloat*)at(d.dy, t) : GP(d.w));
+    const gfloat* src = second ? (const gfloat*)at(d.skip, t)
+                               : (GM == 2 ? (const gfloat*)at(d.dy, t) : (const gfloat*)at(d.x, t));
+    const gfloat* st = (GM != 2 && !second && (flags & F_PRE_AFFINE)) ? (const gfloat*)at(d.st, t) : nullptr;
+    const bool relu = GM != 2 && !second && (flags & F_PRE_RELU);
+    const int stG = UNI(d.G), stC = UNI(d.C);
+
+    lint* offq = (lint*)(smem + UNI(g.o_offq));
+    lfloat* patch = smem + UNI(g.o_patch);
+    const int kk = gk * gk, Wp = UNI(g.Wp), PR = UNI(g.PR), PRW = PR * Wp;
+    const int HW = gH * gW, P = gOH * gOW;
+    const int QC = UNI(g.QC), QCpad = UNI(g.QCpad), CC = UNI(g.CC), M = UNI(g.M), N = UNI(g.N), Q = UNI(g.Q);
+    const int n_chunks = UNI(g.n_chunks), rows_c = UNI(g.rows_c);
+
+    // first row (of the output map for forward / backward weights, of the input
+    // map for backward data) this tile touches, and per-lane column offsets
+    int tile_row0 = 0, c_lo = 0;
+    if (GM == 1) tile_row0 = n0 / gOW;
+    else if (GM == 2) tile_row0 = n0 / gW;
+    else c_lo = n0 / kk;
+    int offn[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
+      int o = 0;
+      if (j < ni && n < N) {
+        if (GM == 1) { const int oh = n / gOW, ow = n - oh * gOW; o = (oh - tile_row0) * gs * Wp + ow * gs; }
+        else if (GM == 2) { const int ih = n / gW, iw = n - ih * gW; o = (ih - tile_row0) * Wp + iw; }
+        else { const int ci = n / kk, tap = n - ci * kk, kh = tap / gk, kw = tap - kh * gk; o = (ci - c_lo) * PRW + kh * Wp + kw; }
+      }
+      offn[j] = o;
+    }
+    __syncthreads();   // LDS may still be in use by the previous operand set
+    for (int i = tid; i < QCpad; i += BLK) {
+      int o = 0;
+      if (i < QC) {
+        if (GM == 3) { const int r = i / gOW, ow = i - r * gOW; o = r * gs * Wp + ow * gs; }
+        else {
+          const int c = i / kk, tap = i - c * kk, kh = tap / gk, kw = tap - kh * gk;
+          o = (GM == 1) ? c * PRW + kh * Wp + kw : c * PRW + (gk - 1 - kh) * Wp + (gk - 1 - kw);
+        }
+      }
+      offq[i] = o;
+    }
+    const int nsteps = QCpad >> 2;
+    const int patch_elems = CC * PRW;
+    // Patch staging walks flat element indices tid, tid+BLK, ... keeping their
+    // (channel, row, column) decomposition incrementally; loads are issued SU
+    // at a time before any is consumed, so that their latencies overlap.
+    constexpr int SU = 16;
+    const int p_c0 = tid / PRW, p_rem = tid - p_c0 * PRW, p_y0 = p_rem / Wp, p_x0 = p_rem - p_y0 * Wp;
+    const int p_dc = BLK / PRW, p_r2 = BLK - p_dc * PRW, p_dy = p_r2 / Wp, p_dx = p_r2 - p_dy * Wp;
+    const int border = gk - 1 - gpad;
+    // lane (i = lane%16, kq = lane/16) needs A[m][4*ks + kq] for its k-steps ks.
+    // A round trip to memory costs far more than a tile's MFMAs, so the loads
+    // run two register batches ahead of their use.
+    constexpr int KB = 16;                       // k-steps per register batch
+    const int am = m0 + wm_id * 16 + (lane & 15);
+    const bool am_ok = am < M;
+    const int dq = 4 * wk, dq_co = dq / kk, dq_tap = dq - dq_co * kk;
+    const gfloat* arow = Aglob + (GM == 2 ? (size_t)am * kk : (size_t)am * Q);
+
+    for (int ch = 0; ch < n_chunks; ++ch) {
+      const int q0 = ch * QC;
+      float a0[KB], a1[KB];
+      int qr = 4 * wk_id + (lane >> 4);          // chunk-relative reduction index of the lane's next k-step
+      int a_co = 0, a_tap = 0;
+      if (GM == 2) { a_co = (q0 + qr) / kk; a_tap = q0 + qr - a_co * kk; }
+      auto load_batch = [&](float (&a)[KB]) {
+#pragma unroll
+        for (int u = 0; u < KB; ++u) {
+          a[u] = 0.f;
+          if (am_ok && qr < QC && q0 + qr < Q) a[u] = (GM == 2) ? arow[(size_t)a_co * gC * kk + a_tap] : arow[q0 + qr];
+          qr += dq;
+          if (GM == 2) { a_tap += dq_tap; a_co += dq_co; if (a_tap >= kk) { a_tap -= kk; ++a_co; } }
+        }
+      };
+      auto mfma_batch = [&](const float (&a)[KB], int kb) {
+#pragma unroll
+        for (int u = 0; u < KB; ++u) {
+          const int ks = kb + u * wk;
+          if (ks < nsteps) {
+            const int oq = offq[ks * 4 + (lane >> 4)];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (j < ni) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u], patch[oq + offn[j]], acc[j], 0, 0, 0);
+          }
+        }
+      };
+      // ---- first two batches of A loads (in flight while the patch is staged)
+      load_batch(a0);
+      load_batch(a1);
+      if (ch) __syncthreads();
+      // ---- patch
+      int chan0, row0;
+      if (GM == 1) { chan0 = ch * CC; row0 = tile_row0 * gs - gpad; }
+      else if (GM == 2) { chan0 = ch * CC; row0 = tile_row0; }
+      else { chan0 = c_lo; row0 = ch * rows_c * gs - gpad; }
+      {
+        int c = p_c0, y = p_y0, x = p_x0;
+        for (int base = tid; base < patch_elems; base += BLK * SU) {
+          float v[SU], sc[SU], sh[SU];
+#pragma unroll
+          for (int u = 0; u < SU; ++u) {
+            v[u] = 0.f; sc[u] = 0.f; sh[u] = 0.f;     // sc = sh = 0: the zero padding
+            if (base + u * BLK < patch_elems) {
+              const int chn = chan0 + c;
+              if (GM == 2) {
+                // output gradient placed at stride spacing with a (k-1-pad) border
+                const int ty = row0 + y - border, tx = x - border;
+                if (chn < gK && ty >= 0 && tx >= 0 && ty % gs == 0 && tx % gs == 0) {
+                  const int oh = ty / gs, ow = tx / gs;
+                  if (oh < gOH && ow < gOW) v[u] = src[(size_t)chn * P + oh * gOW + ow];
+                }
+              } else {
+                const int ih = row0 + y, iw = x - gpad;
+                if (chn < gC && ih >= 0 && ih < gH && iw >= 0 && iw < gW) {
+                  v[u] = src[(size_t)chn * HW + ih * gW + iw];
+                  sc[u] = 1.f;
+                  if (st) { sc[u] = st[2 * stG + chn]; sh[u] = st[2 * stG + stC + chn]; }
+                }
+              }
+            }
+            x += p_dx; y += p_dy; c += p_dc;
+            if (x >= Wp) { x -= Wp; ++y; }
+            if (y >= PR) { y -= PR; ++c; }
+          }
+#pragma unroll
+          for (int u = 0; u < SU; ++u) {
+            if (base + u * BLK < patch_elems) {
+              float r = v[u];
+              if (GM != 2) {
+                r = fmaf(sc[u], r, sh[u]);
+                if (relu) r = fmaxf(r, 0.f);
+              }
+              patch[base + u * BLK] = r;
+            }
+          }
+        }
+      }
+      __syncthreads();
+      // ---- MFMA loop: lane holds A[i = lane%16][k = lane/16] and B[k = lane/16][j = lane%16]
+      for (int kb = wk_id; kb < nsteps; kb += 2 * KB * wk) {
+        mfma_batch(a0, kb);
+        if (kb + 2 * KB * wk < nsteps) load_batch(a0);
+        if (kb + KB * wk < nsteps) mfma_batch(a1, kb + KB * wk);
+        if (kb + 3 * KB * wk < nsteps) load_batch(a1);
+      }
+    }
+  }
+
   // ---- reduce the split of the reduction across waves (fixed order)
-  if (g.wk > 1) {
+  if (wk > 1) {
     __syncthreads();
-    float* red = smem;   // [wave][j][lane] float4
+    lfloat* red = smem;   // [wave][j][lane] float4
     if (wk_id > 0) {
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        if (j < g.ni) *reinterpret_cast<v4f*>(red + ((wv * 4 + j) * 64 + lane) * 4) = acc[j];
+        if (j < ni) {
+          lfloat* r = red + ((wv * 4 + j) * 64 + lane) * 4;
+          r[0] = acc[j][0]; r[1] = acc[j][1]; r[2] = acc[j][2]; r[3] = acc[j][3];
+        }
     }
     __syncthreads();
     if (wk_id == 0) {
-      for (int w2 = 1; w2 < g.wk; ++w2)
+      for (int w2 = 1; w2 < wk; ++w2)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-          if (j < g.ni) acc[j] += *reinterpret_cast<const v4f*>(red + (((wv + w2) * 4 + j) * 64 + lane) * 4);
+          if (j < ni) {
+            const lfloat* r = red + (((wv + w2) * 4 + j) * 64 + lane) * 4;
+            acc[j][0] += r[0]; acc[j][1] += r[1]; acc[j][2] += r[2]; acc[j][3] += r[3];
+          }
     }
   }
   if (wk_id != 0) return;
   // ---- epilogue: lane holds C[i = 4*(lane/16) + r][j = lane%16]
-  float* out = (g.gm == 1) ? at(d.y, t) : (g.gm == 2) ? at(d.dx, t) : d.gw;
-  const float* skip = (g.gm == 1 && (d.flags & F_SKIP) && !(d.flags & F_PROJ)) ? at(d.skip, t) : nullptr;
-  const float* xm = (g.gm == 2 && (d.flags & F_MASK_X)) ? at(d.x, t) : nullptr;
-  const float* skg = (g.gm == 2 && (d.flags & F_ADD_SKG)) ? at(d.skg, t) : nullptr;
+  const int M = UNI(d.g.M), N = UNI(d.g.N);
+  gfloat* out = (GM == 1) ? at(d.y, t) : (GM == 2) ? at(d.dx, t) : GP(d.gw);
+  const int mrow = m0 + wm_id * 16 + 4 * (lane >> 4);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    if (j >= g.ni) continue;
-    const int n = n0 + (wn_id * g.ni + j) * 16 + (lane & 15);
-    if (n >= g.N) continue;
+    const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
+    if (j >= ni || n >= N) continue;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int m = m0 + wm_id * 16 + 4 * (lane >> 4) + r;
-      if (m >= g.M) continue;
-      const size_t o = (size_t)m * g.N + n;
-      float v = acc[j][r];
-      if (g.gm == 1) {
-        if (d.flags & F_BIAS) v += d.b[m];
-        if (skip) v += skip[o];
-      } else if (g.gm == 2) {
-        if (xm && !(xm[o] > 0.f)) v = 0.f;
-        if (skg) v += skg[o];
+    for (int r = 0; r < 4; ++r)
+      if (mrow + r < M) {
+        float v = acc[j][r];
+        if (GM == 2 && !(e_msk[j][r] > 0.f)) v = 0.f;
+        out[(size_t)(mrow + r) * N + n] = v + e_add[j][r];
       }
-      out[o] = v;
-    }
   }
 }
 
+__device__ __forceinline__ void step_gemm(const LDesc& d, int tile, int t, lfloat* smem) {
+  const int gm = UNI(d.g.gm);
+  if (gm == 1) step_gemm_t<1>(d, tile, t, smem);
+  else if (gm == 2) step_gemm_t<2>(d, tile, t, smem);
+  else step_gemm_t<3>(d, tile, t, smem);
+}
+
 // db[co] = sum_p dZ[co,p], one wavefront per channel.
-__device__ void step_bias_grad(const StepDesc& d, int tile, int t) {
+__device__ void step_bias_grad(const LDesc& d, int tile, int t) {
   const int co = tile * (BLK / 64) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (co >= d.K) return;
   const int P = d.OH * d.OW;
-  const float* dz = at(d.dy, t) + (size_t)co * P;
+  const gfloat* dz = at(d.dy, t) + (size_t)co * P;
   float s = 0.f;
   for (int p = lane; p < P; p += 64) s += dz[p];
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o, 64);
-  if (lane == 0) d.gb[co] = s;
+  if (lane == 0) GP(d.gb)[co] = s;
 }
 
 }  // namespace pb

@@ -274,12 +274,11 @@ struct pb_ctx {
   int launch_mode = 0;
   int kernel_set = 0;
   std::vector<StepDesc> steps;         // sorted by phase
-  std::vector<int32_t> prefix;         // per step: first tile within its phase
+  std::vector<int64_t> rec_first;      // per step: index of its first per-workgroup record
   std::vector<Phase> phases;
   int n_chunks = 0;
   // device views
-  StepDesc* steps_dev = nullptr;
-  int32_t* prefix_dev = nullptr;
+  StepDesc* recs_dev = nullptr;        // one descriptor copy per workgroup, in launch order
   int32_t* chunk_stage_dev = nullptr;
   UpdSeg* segs_dev = nullptr;
   Globals* globals_dev = nullptr;
@@ -360,8 +359,8 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
   g.tiles_n = cdiv(g.N, g.NT);
   g.tiles = cdiv(g.M, g.MT) * g.tiles_n;
   auto fits = [&](int QC, int CC, int PR, int Wp) {
-    const int QCpad = (QC + 3) / 4 * 4, LDA = QCpad + 2;
-    const int64_t need = (int64_t)g.MT * LDA + QCpad + (int64_t)CC * PR * Wp + 64;
+    const int QCpad = (QC + 3) / 4 * 4;
+    const int64_t need = QCpad + (int64_t)CC * PR * Wp + 64;
     return need <= LDS_FLOATS;
   };
   if (mode == 1 || mode == 2) {
@@ -395,10 +394,13 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
     g.rows_c = rows; g.QC = rows * OW; g.PR = pr(rows); g.n_chunks = cdiv(OH, rows);
   }
   g.QCpad = (g.QC + 3) / 4 * 4;
-  g.LDA = g.QCpad + 2;
-  g.o_offq = (g.MT * g.LDA + 3) / 4 * 4;
+  g.LDA = 0;
+  g.o_offq = 0;
   g.o_patch = (g.o_offq + g.QCpad + 3) / 4 * 4;
   if (g.o_patch + g.CC * g.PR * g.Wp > LDS_FLOATS) return false;
+  auto lg_ceil = [](int x) { int l = 0; while ((1 << l) < x && l < 8) ++l; return l; };
+  g.lgA = lg_ceil(mode == 2 ? g.MT * kk : g.QCpad);
+  g.lgP = lg_ceil(g.Wp);
   *out = g;
   return true;
 }
@@ -720,9 +722,9 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
           const int kk = k * k;
           bool o = g.wm * g.wn * g.wk == 4 && g.ni >= 1 && g.ni <= 4 && g.MT == 16 * g.wm && g.NT == 16 * g.ni * g.wn &&
                    g.tiles_n == cdiv(g.N, g.NT) && g.tiles == cdiv(g.M, g.MT) * g.tiles_n && g.QCpad % 4 == 0 &&
-                   g.QCpad >= g.QC && g.LDA >= g.QCpad && g.o_offq >= g.MT * g.LDA && g.o_patch >= g.o_offq + g.QCpad &&
+                   g.QCpad >= g.QC && g.o_offq >= 0 && g.o_patch >= g.o_offq + g.QCpad &&
                    (int64_t)g.o_patch + (int64_t)g.CC * g.PR * g.Wp <= LDS_FLOATS && LDS_FLOATS >= 4096 &&
-                   (int64_t)g.n_chunks * g.QC >= g.Q;
+                   (int64_t)g.n_chunks * g.QC >= g.Q && g.lgA >= 0 && g.lgA <= 8 && g.lgP >= 0 && g.lgP <= 8;
           if (g.gm == 1) {
             const int rows_max = std::min(d.OH, (g.NT + d.OW - 2) / d.OW + 1);
             o = o && g.M == d.K && g.N == d.OH * d.OW && g.Q == C * kk && g.QC == g.CC * kk &&
@@ -855,15 +857,14 @@ int run_one_tick(pb_ctx* c, const float* staging, int label) {
   if (c->launch_mode == 0) {
     for (const Phase& p : c->phases) {
       ScopedEv ev(c, 0);
-      launch_phase(c->steps_dev + p.first, c->prefix_dev + p.first, p.count, p.tiles, c->globals_dev, k,
-                   c->stream);
+      launch_phase(c->recs_dev + c->rec_first[p.first], p.tiles, c->globals_dev, k, c->stream);
     }
   } else {
     for (const Phase& p : c->phases)
       for (int i = 0; i < p.count; ++i) {
         ScopedEv ev(c, 0);
-        launch_phase(c->steps_dev + p.first + i, c->zero_dev, 1, c->steps[p.first + i].ntiles,
-                     c->globals_dev, k, c->stream);
+        launch_phase(c->recs_dev + c->rec_first[p.first + i], c->steps[p.first + i].ntiles, c->globals_dev, k,
+                     c->stream);
       }
   }
   {
@@ -900,8 +901,9 @@ size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays) {
   std::vector<std::pair<int, StepDesc>> steps;
   compile_steps(&tmp, steps);
   if (validate_steps(&tmp, steps, pl.total) != PB_OK) return 0;
-  pl.alloc((int64_t)steps.size() * sizeof(StepDesc) / 4 + 64);
-  pl.alloc((int64_t)steps.size() + 64);
+  int64_t total_tiles = 0;
+  for (auto& pr : steps) total_tiles += pr.second.ntiles;
+  pl.alloc(total_tiles * (int64_t)sizeof(StepDesc) / 4 + 64);
   pl.alloc(L.P / UPD_CHUNK + 64);
   pl.alloc((int64_t)st.size() * sizeof(UpdSeg) / 4 + 64);
   return (size_t)pl.total * sizeof(float) + 256;
@@ -998,27 +1000,30 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
                    [](const std::pair<int, StepDesc>& x, const std::pair<int, StepDesc>& y) { return x.first < y.first; });
   const int n_steps = (int)tagged.size();
   c->steps.resize(n_steps);
-  c->prefix.resize(n_steps);
   int n_ph = 0;
   for (auto& p : tagged) n_ph = std::max(n_ph, p.first + 1);
   c->phases.assign(n_ph, Phase());
+  c->rec_first.assign(n_steps, 0);
+  std::vector<StepDesc> recs;
   for (int i = 0, cur = -1, acc = 0; i < n_steps; ++i) {
     const int ph = tagged[i].first;
     if (ph != cur) { cur = ph; acc = 0; c->phases[ph].first = i; }
     c->steps[i] = tagged[i].second;
-    c->prefix[i] = acc;
+    c->rec_first[i] = (int64_t)recs.size();
+    for (int tl = 0; tl < tagged[i].second.ntiles; ++tl) {
+      recs.push_back(tagged[i].second);
+      recs.back().tile = tl;
+    }
     acc += tagged[i].second.ntiles;
     c->phases[ph].count++;
     c->phases[ph].tiles = acc;
   }
-  const int64_t o_steps = pl.alloc((int64_t)n_steps * sizeof(StepDesc) / 4 + 64);
-  const int64_t o_prefix = pl.alloc(n_steps + 64);
+  const int64_t o_recs = pl.alloc((int64_t)recs.size() * sizeof(StepDesc) / 4 + 64);
   c->n_chunks = (int)(c->L.P / UPD_CHUNK);
   const int64_t o_chunk = pl.alloc(c->n_chunks + 64);
   const int64_t o_segs = pl.alloc((int64_t)c->S * sizeof(UpdSeg) / 4 + 64);
   if ((size_t)pl.total * sizeof(float) > need) { pb_destroy(c); return fail(PB_E_NOMEM, "internal: arena plan mismatch"); }
-  c->steps_dev = (StepDesc*)c->f(o_steps);
-  c->prefix_dev = (int32_t*)c->f(o_prefix);
+  c->recs_dev = (StepDesc*)c->f(o_recs);
   c->chunk_stage_dev = (int32_t*)c->f(o_chunk);
   c->segs_dev = (UpdSeg*)c->f(o_segs);
 
@@ -1042,8 +1047,7 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   INIT_TRY(hipMemcpyAsync(c->f(c->L.w), w.data(), sizeof(float) * c->L.P, hipMemcpyHostToDevice, c->stream));
   if (c->L.what >= 0)
     INIT_TRY(hipMemcpyAsync(c->f(c->L.what), w.data(), sizeof(float) * c->L.P, hipMemcpyHostToDevice, c->stream));
-  INIT_TRY(hipMemcpyAsync(c->steps_dev, c->steps.data(), sizeof(StepDesc) * n_steps, hipMemcpyHostToDevice, c->stream));
-  INIT_TRY(hipMemcpyAsync(c->prefix_dev, c->prefix.data(), sizeof(int32_t) * n_steps, hipMemcpyHostToDevice, c->stream));
+  INIT_TRY(hipMemcpyAsync(c->recs_dev, recs.data(), sizeof(StepDesc) * recs.size(), hipMemcpyHostToDevice, c->stream));
   INIT_TRY(hipMemcpyAsync(c->chunk_stage_dev, chunk_stage.data(), sizeof(int32_t) * c->n_chunks, hipMemcpyHostToDevice, c->stream));
   INIT_TRY(hipMemcpyAsync(c->segs_dev, segs.data(), sizeof(UpdSeg) * c->S, hipMemcpyHostToDevice, c->stream));
   INIT_TRY(hipMemcpyAsync(c->globals_dev, &g0, sizeof g0, hipMemcpyHostToDevice, c->stream));

@@ -11,11 +11,36 @@
 namespace pb {
 
 // ------------------------------------------------------------------ helpers
-__device__ __forceinline__ float* at(const TRef& r, int t) {
+// Pointers read out of the step table are generic to the compiler; accesses
+// through generic pointers become flat loads whose completion has to be
+// awaited conservatively.  Every buffer of the engine lives in global memory
+// (address space 1) and every staging array in LDS (address space 3): say so.
+typedef __attribute__((address_space(1))) float gfloat;
+typedef __attribute__((address_space(1))) int32_t gint;
+typedef __attribute__((address_space(3))) float lfloat;
+typedef __attribute__((address_space(3))) int lint;
+
+__device__ __forceinline__ gfloat* GP(float* p) { return (gfloat*)p; }
+__device__ __forceinline__ const gfloat* GP(const float* p) { return (const gfloat*)p; }
+
+// the workgroup's step descriptor lives in LDS
+typedef __attribute__((address_space(3))) StepDesc LDesc;
+typedef __attribute__((address_space(3))) TRef LTRef;
+typedef __attribute__((address_space(3))) GemmCfg LGemmCfg;
+#define UNI(x) __builtin_amdgcn_readfirstlane(x)   /* value is the same in every lane: keep it scalar */
+
+__device__ __forceinline__ gfloat* at(const LTRef& r, int t) {
+  const int depth = UNI(r.depth), stride = UNI(r.stride), lag = UNI(r.lag);
+  int slot = (t - lag) % depth;
+  if (slot < 0) slot += depth;
+  return (gfloat*)r.base + (size_t)slot * (size_t)stride;
+}
+
+__device__ __forceinline__ gfloat* at(const TRef& r, int t) {
   int u = t - r.lag;
   int slot = u % r.depth;
   if (slot < 0) slot += r.depth;
-  return r.base + (size_t)slot * (size_t)r.stride;
+  return (gfloat*)r.base + (size_t)slot * (size_t)r.stride;
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -25,7 +50,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // Sum over the workgroup, same value returned to every thread.
-__device__ __forceinline__ float block_sum(float v, float* red) {
+__device__ __forceinline__ float block_sum(float v, lfloat* red) {
   v = wave_sum(v);
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   __syncthreads();
@@ -34,7 +59,7 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-__device__ __forceinline__ float block_max(float v, float* red) {
+__device__ __forceinline__ float block_max(float v, lfloat* red) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_down(v, o, 64));
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -52,9 +77,9 @@ namespace pb {
 // GroupNorm statistics of one group (biased variance, two passes) and the
 // folded per-channel scale/shift built from the forward (predicted) affine
 // parameters; kept for the backward pass of the same sample.
-__device__ void step_gn_stats(const StepDesc& d, int tile, int t, float* red) {
+__device__ void step_gn_stats(const LDesc& d, int tile, int t, lfloat* red) {
   const int g = tile, HW = d.H * d.W, cpg = d.C / d.G, n = cpg * HW;
-  const float* xp = at(d.x, t) + (size_t)g * n;
+  const gfloat* xp = at(d.x, t) + (size_t)g * n;
   float s = 0.f;
   for (int i = threadIdx.x; i < n; i += BLK) s += xp[i];
   const float mean = block_sum(s, red) / (float)n;
@@ -62,22 +87,22 @@ __device__ void step_gn_stats(const StepDesc& d, int tile, int t, float* red) {
   for (int i = threadIdx.x; i < n; i += BLK) { float dl = xp[i] - mean; q = fmaf(dl, dl, q); }
   const float var = block_sum(q, red) / (float)n;
   const float rstd = 1.0f / sqrtf(var + GN_EPS);
-  float* st = at(d.st, t);
+  gfloat* st = at(d.st, t);
   if (threadIdx.x == 0) { st[g] = mean; st[d.G + g] = rstd; }
   for (int c = threadIdx.x; c < cpg; c += BLK) {
     const int ch = g * cpg + c;
-    const float sc = d.gamma[ch] * rstd;
+    const float sc = GP(d.gamma)[ch] * rstd;
     st[2 * d.G + ch] = sc;
-    st[2 * d.G + d.C + ch] = fmaf(-mean, sc, d.beta[ch]);
+    st[2 * d.G + d.C + ch] = fmaf(-mean, sc, GP(d.beta)[ch]);
   }
 }
 
 // pooled[c] = mean_hw relu(sc*x+sh)
-__device__ void step_gap_fwd(const StepDesc& d, int tile, int t, float* red) {
+__device__ void step_gap_fwd(const LDesc& d, int tile, int t, lfloat* red) {
   const int c = tile, HW = d.H * d.W;
-  const float* xp = at(d.x, t) + (size_t)c * HW;
+  const gfloat* xp = at(d.x, t) + (size_t)c * HW;
   const bool aff = d.flags & F_PRE_AFFINE, rl = d.flags & F_PRE_RELU;
-  const float* st = aff ? at(d.st, t) : nullptr;
+  const gfloat* st = aff ? at(d.st, t) : nullptr;
   const float sc = aff ? st[2 * d.G + c] : 1.f, sh = aff ? st[2 * d.G + d.C + c] : 0.f;
   float s = 0.f;
   for (int i = threadIdx.x; i < HW; i += BLK) {
@@ -90,20 +115,20 @@ __device__ void step_gap_fwd(const StepDesc& d, int tile, int t, float* red) {
 }
 
 // Direct convolution / linear forward, one thread per output element.
-__device__ void step_conv_fwd(const StepDesc& d, int tile, int t) {
+__device__ void step_conv_fwd(const LDesc& d, int tile, int t) {
   const int P = d.OH * d.OW;
   const int o = tile * BLK + threadIdx.x;
   if (o >= d.K * P) return;
   const int co = o / P, p = o - co * P, oh = p / d.OW, ow = p - oh * d.OW;
-  const float* x = at(d.x, t);
-  const float* st = (d.flags & F_PRE_AFFINE) ? at(d.st, t) : nullptr;
+  const gfloat* x = at(d.x, t);
+  const gfloat* st = (d.flags & F_PRE_AFFINE) ? at(d.st, t) : nullptr;
   const bool aff = d.flags & F_PRE_AFFINE, rl = d.flags & F_PRE_RELU;
   const int HW = d.H * d.W, kk = d.k * d.k;
-  float acc = (d.flags & F_BIAS) ? d.b[co] : 0.f;
-  const float* wr = d.w + (size_t)co * d.C * kk;
+  float acc = (d.flags & F_BIAS) ? GP(d.b)[co] : 0.f;
+  const gfloat* wr = GP(d.w) + (size_t)co * d.C * kk;
   for (int ci = 0; ci < d.C; ++ci) {
     const float sc = aff ? st[2 * d.G + ci] : 1.f, sh = aff ? st[2 * d.G + d.C + ci] : 0.f;
-    const float* xc = x + (size_t)ci * HW;
+    const gfloat* xc = x + (size_t)ci * HW;
     for (int kh = 0; kh < d.k; ++kh) {
       const int ih = oh * d.stride - d.pad + kh;
       if (ih < 0 || ih >= d.H) continue;
@@ -118,12 +143,12 @@ __device__ void step_conv_fwd(const StepDesc& d, int tile, int t) {
     }
   }
   if (d.flags & F_SKIP) {
-    const float* sk = at(d.skip, t);
+    const gfloat* sk = at(d.skip, t);
     if (d.flags & F_PROJ) {
       const int sHW = d.sH * d.sW;
-      const float* s0 = sk + (size_t)(oh * d.sstride) * d.sW + ow * d.sstride;
+      const gfloat* s0 = sk + (size_t)(oh * d.sstride) * d.sW + ow * d.sstride;
       float a2 = 0.f;
-      for (int ci = 0; ci < d.sC; ++ci) a2 = fmaf(d.wp[(size_t)co * d.sC + ci], s0[(size_t)ci * sHW], a2);
+      for (int ci = 0; ci < d.sC; ++ci) a2 = fmaf(GP(d.wp)[(size_t)co * d.sC + ci], s0[(size_t)ci * sHW], a2);
       acc += a2;
     } else {
       acc += sk[o];
@@ -133,10 +158,10 @@ __device__ void step_conv_fwd(const StepDesc& d, int tile, int t) {
 }
 
 // y = [maxpool] relu(sc*z+sh), one thread per output element.
-__device__ void step_post_fwd(const StepDesc& d, int tile, int t) {
-  const float* z = at(d.x, t);
-  const float* st = at(d.st, t);
-  float* y = at(d.y, t);
+__device__ void step_post_fwd(const LDesc& d, int tile, int t) {
+  const gfloat* z = at(d.x, t);
+  const gfloat* st = at(d.st, t);
+  gfloat* y = at(d.y, t);
   const int HW = d.H * d.W;
   if (d.flags & F_POOL) {
     const int PP = d.PH * d.PW;
@@ -144,7 +169,7 @@ __device__ void step_post_fwd(const StepDesc& d, int tile, int t) {
     if (o >= d.C * PP) return;
     const int c = o / PP, p = o - c * PP, ph = p / d.PW, pw = p - ph * d.PW;
     const float sc = st[2 * d.G + c], sh = st[2 * d.G + d.C + c];
-    const float* zc = z + (size_t)c * HW;
+    const gfloat* zc = z + (size_t)c * HW;
     float best = -1.f;
     for (int kh = 0; kh < d.pk; ++kh) {
       const int ih = ph * d.ps - d.pp + kh;
@@ -166,12 +191,12 @@ __device__ void step_post_fwd(const StepDesc& d, int tile, int t) {
 
 // Softmax cross-entropy of the sample that reaches the last stage at tick t
 // (sample index t-(S-1)); writes dlogits = softmax - onehot.
-__device__ void step_ce(const StepDesc& d, int tile, int t, float* red) {
-  const float* z = at(d.x, t);
-  float* dz = at(d.dx, t);
+__device__ void step_ce(const LDesc& d, int tile, int t, lfloat* red) {
+  const gfloat* z = at(d.x, t);
+  gfloat* dz = at(d.dx, t);
   const int n = d.n;
   const int sample = t - (d.n_stages - 1);
-  const int label = d.labels[sample % d.n_stages];
+  const int label = ((const gint*)d.labels)[sample % d.n_stages];
   float mx = -3.0e38f;
   for (int i = threadIdx.x; i < n; i += BLK) mx = fmaxf(mx, z[i]);
   mx = block_max(mx, red);
@@ -182,15 +207,15 @@ __device__ void step_ce(const StepDesc& d, int tile, int t, float* red) {
     float p = expf(z[i] - mx) / s;
     dz[i] = p - (i == label ? 1.f : 0.f);
   }
-  if (threadIdx.x == 0) d.loss_log[sample % d.loss_cap] = logf(s) + mx - z[label];
+  if (threadIdx.x == 0) GP(d.loss_log)[sample % d.loss_cap] = logf(s) + mx - z[label];
 }
 
 // ----------------------------------------------------------- backward steps
 // Gradient arriving at element (h,w) of channel c of the tensor u = relu(affine(z))
 // that feeds a max-pool: the sum of dY over the windows whose first maximum
 // (row-major scan, strict >) sits at (h,w).
-__device__ __forceinline__ float pool_routed(const StepDesc& d, const float* zc, float sc, float sh,
-                                             int h, int w, const float* dyc) {
+__device__ __forceinline__ float pool_routed(const LDesc& d, const gfloat* zc, float sc, float sh,
+                                             int h, int w, const gfloat* dyc) {
   float sum = 0.f;
   int ph_lo = h + d.pp - d.pk + 1;
   ph_lo = ph_lo <= 0 ? 0 : (ph_lo + d.ps - 1) / d.ps;
@@ -219,7 +244,7 @@ __device__ __forceinline__ float pool_routed(const StepDesc& d, const float* zc,
   return sum;
 }
 
-__device__ __forceinline__ float gn_du(const StepDesc& d, const float* dy, const float* xc, float sc,
+__device__ __forceinline__ float gn_du(const LDesc& d, const gfloat* dy, const gfloat* xc, float sc,
                                        float sh, int c, int i, int HW) {
   if (d.flags & F_DU_BUF) return dy[(size_t)c * HW + i];
   if (d.flags & F_DU_GAP) return dy[c] / (float)HW;
@@ -229,12 +254,12 @@ __device__ __forceinline__ float gn_du(const StepDesc& d, const float* dy, const
 
 // Per channel: dgamma = sum dyv*xh, dbeta = sum dyv (dyv = gradient after the
 // ReLU mask); also gamma_b*dbeta and gamma_b*dgamma for the group sums.
-__device__ void step_gnb_reduce(const StepDesc& d, int tile, int t, float* red) {
+__device__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red) {
   const int c = tile, HW = d.H * d.W, cpg = d.C / d.G, g = c / cpg;
-  const float* st = at(d.st, t);
+  const gfloat* st = at(d.st, t);
   const float mean = st[g], rstd = st[d.G + g], sc = st[2 * d.G + c], sh = st[2 * d.G + d.C + c];
-  const float* xc = at(d.x, t) + (size_t)c * HW;
-  const float* dy = at(d.dy, t);
+  const gfloat* xc = at(d.x, t) + (size_t)c * HW;
+  const gfloat* dy = at(d.dy, t);
   const bool rl = d.flags & F_GN_RELU;
   float sg = 0.f, sb = 0.f;
   for (int i = threadIdx.x; i < HW; i += BLK) {
@@ -248,44 +273,44 @@ __device__ void step_gnb_reduce(const StepDesc& d, int tile, int t, float* red) 
   sg = block_sum(sg, red);
   sb = block_sum(sb, red);
   if (threadIdx.x == 0) {
-    d.ggamma[c] = sg;
-    d.gbeta[c] = sb;
-    const float gm = d.gamma[c];
-    d.part[c] = gm * sb;
-    d.part[d.C + c] = gm * sg;
+    GP(d.ggamma)[c] = sg;
+    GP(d.gbeta)[c] = sb;
+    const float gm = GP(d.gamma)[c];
+    GP(d.part)[c] = gm * sb;
+    GP(d.part)[d.C + c] = gm * sg;
   }
 }
 
 // dx = rstd * (dxh - mean(dxh) - xh * mean(dxh*xh)), dxh = dyv * gamma_b
-__device__ void step_gnb_apply(const StepDesc& d, int tile, int t) {
+__device__ void step_gnb_apply(const LDesc& d, int tile, int t) {
   const int HW = d.H * d.W, cpg = d.C / d.G, n = cpg * HW;
   const int o = tile * BLK + threadIdx.x;
   if (o >= d.C * HW) return;
   const int c = o / HW, i = o - c * HW, g = c / cpg;
-  const float* st = at(d.st, t);
+  const gfloat* st = at(d.st, t);
   const float mean = st[g], rstd = st[d.G + g], sc = st[2 * d.G + c], sh = st[2 * d.G + d.C + c];
   float S1 = 0.f, S2 = 0.f;
-  for (int j = 0; j < cpg; ++j) { S1 += d.part[g * cpg + j]; S2 += d.part[d.C + g * cpg + j]; }
-  const float* xc = at(d.x, t) + (size_t)c * HW;
+  for (int j = 0; j < cpg; ++j) { S1 += GP(d.part)[g * cpg + j]; S2 += GP(d.part)[d.C + g * cpg + j]; }
+  const gfloat* xc = at(d.x, t) + (size_t)c * HW;
   const float xv = xc[i];
   const float yv = fmaf(sc, xv, sh);
   float du = gn_du(d, at(d.dy, t), xc, sc, sh, c, i, HW);
   if ((d.flags & F_GN_RELU) && !(yv > 0.f)) du = 0.f;
   const float xh = (xv - mean) * rstd;
   const float inv_n = 1.0f / (float)n;
-  float r = rstd * (du * d.gamma[c] - S1 * inv_n - xh * (S2 * inv_n));
+  float r = rstd * (du * GP(d.gamma)[c] - S1 * inv_n - xh * (S2 * inv_n));
   if (d.flags & F_ADD_SKG) r += at(d.skg, t)[o];
   at(d.dx, t)[o] = r;
 }
 
 // Backward data: dX = W^T dZ (transposed convolution), one thread per input
 // element, gathering.
-__device__ void step_conv_bwd_x(const StepDesc& d, int tile, int t) {
+__device__ void step_conv_bwd_x(const LDesc& d, int tile, int t) {
   const int HW = d.H * d.W, P = d.OH * d.OW, kk = d.k * d.k;
   const int o = tile * BLK + threadIdx.x;
   if (o >= d.C * HW) return;
   const int ci = o / HW, r = o - ci * HW, ih = r / d.W, iw = r - ih * d.W;
-  const float* dz = at(d.dy, t);
+  const gfloat* dz = at(d.dy, t);
   float acc = 0.f;
   for (int kh = 0; kh < d.k; ++kh) {
     const int th = ih + d.pad - kh;
@@ -297,8 +322,8 @@ __device__ void step_conv_bwd_x(const StepDesc& d, int tile, int t) {
       if (tw < 0 || tw % d.stride) continue;
       const int ow = tw / d.stride;
       if (ow >= d.OW) continue;
-      const float* wq = d.w + (size_t)ci * kk + kh * d.k + kw;
-      const float* dq = dz + oh * d.OW + ow;
+      const gfloat* wq = GP(d.w) + (size_t)ci * kk + kh * d.k + kw;
+      const gfloat* dq = dz + oh * d.OW + ow;
       for (int co = 0; co < d.K; ++co) acc = fmaf(wq[(size_t)co * d.C * kk], dq[(size_t)co * P], acc);
     }
   }
@@ -310,13 +335,13 @@ __device__ void step_conv_bwd_x(const StepDesc& d, int tile, int t) {
 // Backward weights: dW[co,ci,kh,kw] = sum_p dZ[co,p] * a[ci, p*s-pad+k],
 // a = the forward's transformed input recomputed from the saved input.
 // Large maps: one wavefront per weight element; small maps: one thread.
-__device__ void step_conv_bwd_w(const StepDesc& d, int tile, int t) {
+__device__ void step_conv_bwd_w(const LDesc& d, int tile, int t) {
   const int HW = d.H * d.W, P = d.OH * d.OW, kk = d.k * d.k;
   const int nW = d.K * d.C * kk;
   const bool wave_mode = P > 16;
   const int per_tile = wave_mode ? BLK / 64 : BLK;
   const int w_tiles = (nW + per_tile - 1) / per_tile;
-  const float* dz = at(d.dy, t);
+  const gfloat* dz = at(d.dy, t);
   if (tile >= w_tiles) {                      // bias tiles
     const int lane = threadIdx.x & 63;
     if (wave_mode) {
@@ -325,26 +350,26 @@ __device__ void step_conv_bwd_w(const StepDesc& d, int tile, int t) {
       float s = 0.f;
       for (int p = lane; p < P; p += 64) s += dz[(size_t)co * P + p];
       s = wave_sum(s);
-      if (lane == 0) d.gb[co] = s;
+      if (lane == 0) GP(d.gb)[co] = s;
     } else {
       const int co = (tile - w_tiles) * per_tile + threadIdx.x;
       if (co >= d.K) return;
       float s = 0.f;
       for (int p = 0; p < P; ++p) s += dz[(size_t)co * P + p];
-      d.gb[co] = s;
+      GP(d.gb)[co] = s;
     }
     return;
   }
-  const float* x = at(d.x, t);
+  const gfloat* x = at(d.x, t);
   const bool aff = d.flags & F_PRE_AFFINE, rl = d.flags & F_PRE_RELU;
-  const float* st = aff ? at(d.st, t) : nullptr;
+  const gfloat* st = aff ? at(d.st, t) : nullptr;
   const int e = wave_mode ? tile * per_tile + (threadIdx.x >> 6) : tile * per_tile + threadIdx.x;
   if (e >= nW) return;
   const int co = e / (d.C * kk), r = e - co * d.C * kk, ci = r / kk, q = r - ci * kk;
   const int kh = q / d.k, kw = q - kh * d.k;
   const float sc = aff ? st[2 * d.G + ci] : 1.f, sh = aff ? st[2 * d.G + d.C + ci] : 0.f;
-  const float* xc = x + (size_t)ci * HW;
-  const float* dzc = dz + (size_t)co * P;
+  const gfloat* xc = x + (size_t)ci * HW;
+  const gfloat* dzc = dz + (size_t)co * P;
   float acc = 0.f;
   const int p0 = wave_mode ? (threadIdx.x & 63) : 0, dp = wave_mode ? 64 : 1;
   for (int p = p0; p < P; p += dp) {
@@ -358,35 +383,44 @@ __device__ void step_conv_bwd_w(const StepDesc& d, int tile, int t) {
   }
   if (wave_mode) {
     acc = wave_sum(acc);
-    if ((threadIdx.x & 63) == 0) d.gw[e] = acc;
+    if ((threadIdx.x & 63) == 0) GP(d.gw)[e] = acc;
   } else {
-    d.gw[e] = acc;
+    GP(d.gw)[e] = acc;
   }
 }
 
-__device__ void step_copy(const StepDesc& d, int tile, int t) {
+__device__ void step_copy(const LDesc& d, int tile, int t) {
   const int o = tile * BLK + threadIdx.x;
   if (o < d.n) at(d.dx, t)[o] = at(d.dy, t)[o];
 }
 
 // ------------------------------------------------------------------ kernels
+// One workgroup = one tile of one step.  recs[] holds, per workgroup of the
+// phase, a full copy of its step descriptor with the tile index filled in, so
+// that a single burst of scalar loads (one memory round trip) delivers all a
+// workgroup needs to know.
 __global__ void __launch_bounds__(BLK)
-k_phase(const StepDesc* __restrict__ steps, const int32_t* __restrict__ prefix, int n_steps,
-        const Globals* __restrict__ G, int k) {
-  __shared__ float red[8];
-  __shared__ __attribute__((aligned(16))) float smem[LDS_FLOATS];
+k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k) {
+  __shared__ float red_[8];
+  __shared__ __attribute__((aligned(16))) float smem_[LDS_FLOATS];
+  lfloat* red = (lfloat*)red_;
+  lfloat* smem = (lfloat*)smem_;
   const int t = G->t_base + k;
-  // which step does this workgroup belong to (prefix[i] = first tile of step i)
-  int lo = 0, hi = n_steps - 1;
-  const int bid = blockIdx.x;
-  while (lo < hi) {
-    const int mid = (lo + hi + 1) >> 1;
-    if (prefix[mid] <= bid) lo = mid; else hi = mid - 1;
+  // The descriptor arrives through the vector memory path (one coalesced
+  // request) and is parked in LDS; a burst of scalar loads of data no other
+  // workgroup shares would miss the scalar cache line after line.
+  constexpr int NW = (int)(sizeof(StepDesc) / 4);
+  static_assert(sizeof(StepDesc) % 4 == 0 && NW <= BLK, "descriptor must fit one word per thread");
+  __shared__ StepDesc sd_;
+  {
+    const gint* dp = (const gint*)(recs + blockIdx.x);
+    if (threadIdx.x < NW) ((lint*)&sd_)[threadIdx.x] = dp[threadIdx.x];
   }
-  const StepDesc& d = steps[lo];
-  if (t < d.first_tick) return;
-  const int tile = bid - prefix[lo];
-  switch (d.kind) {
+  __syncthreads();
+  const LDesc& d = *(const LDesc*)&sd_;
+  const int tile = UNI(d.tile);
+  if (t < UNI(d.first_tick)) return;
+  switch (UNI(d.kind)) {
     case K_GN_STATS: step_gn_stats(d, tile, t, red); break;
     case K_GAP_FWD: step_gap_fwd(d, tile, t, red); break;
     case K_CONV_FWD: step_conv_fwd(d, tile, t); break;
@@ -410,14 +444,14 @@ __global__ void __launch_bounds__(BLK)
 k_ingest(TRef ring0, int n_elems, const float* __restrict__ staging, int label,
          int32_t* __restrict__ label_ring, int n_stages, const Globals* __restrict__ G, int k) {
   const int t = G->t_base + k;
-  const float* src = staging;
+  const gfloat* src = (const gfloat*)staging;
   int lab = label;
-  if (!src) {
+  if (!staging) {
     const int item = (int)(((int64_t)G->idx_base + k) % G->n_pool);
-    src = G->pool + (size_t)item * n_elems;
-    lab = G->pool_labels[item];
+    src = (const gfloat*)G->pool + (size_t)item * n_elems;
+    lab = ((const gint*)G->pool_labels)[item];
   }
-  float* dst = at(ring0, t);
+  gfloat* dst = at(ring0, t);
   const int i = blockIdx.x * BLK + threadIdx.x;
   if (i < n_elems) dst[i] = src[i];
   if (i == 0) label_ring[t % n_stages] = lab;
@@ -490,11 +524,9 @@ __global__ void k_advance(Globals* G, int dt, int didx) {
 }
 
 // --------------------------------------------------------- launch wrappers
-void launch_phase(const StepDesc* steps_dev, const int32_t* tile_prefix_dev, int n_steps,
-                  int total_tiles, const Globals* G, int k, hipStream_t s) {
+void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, hipStream_t s) {
   if (total_tiles <= 0) return;
-  hipLaunchKernelGGL(k_phase, dim3(total_tiles), dim3(BLK), 0, s, steps_dev, tile_prefix_dev, n_steps,
-                     G, k);
+  hipLaunchKernelGGL(k_phase, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, G, k);
 }
 
 void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,
