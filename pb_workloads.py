@@ -176,6 +176,16 @@ def config(name):
     if name == "tiny_bottleneck":
         st = preact_resnet_bottleneck(layers=(1, 1), base=4, groups=2, in_c=3, n_classes=6)
         return _net("tiny_bottleneck", st, 3, 16, 16, 6, 0.01, 0.9, 16, 14, 64)
+    if name == "resnet50_64":
+        # the ResNet-50 stage structure at full channel widths on 64x64 inputs with
+        # fp32 activations: exercises the 7x7/2 stem, the 3x3/2 max-pool, 1x1
+        # convolutions, stride-2 3x3 convolutions and skips over two stages at a size
+        # the float64 oracle handles in a test
+        st = preact_resnet_bottleneck()
+        return _net("resnet50_64", st, 3, 64, 64, 1000, 0.001, 0.9, 64, 1240, 200)
+    if name == "resnet50_fp32":
+        st = preact_resnet_bottleneck()
+        return _net("resnet50_fp32", st, 3, 224, 224, 1000, 0.001, 0.9, 256, 1238, 5000)
     if name == "small_resnet":
         # ragged sizes: spans several tiles with tails in every kernel
         st = preact_resnet_basic((12, 20), 2, 4, in_c=3, n_classes=7)

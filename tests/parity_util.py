@@ -18,7 +18,7 @@ TOL = 1e-5   # per-tick relative weight tolerance for fp32 (stated by the task's
 # ticks is SENS_FACTOR times the oracles' own disagreement.
 PERTURB = (3e-7, 1e-6)
 SENS_FACTOR = 4.0
-WELL_CONDITIONED = 3e-6    # oracle-vs-perturbed-oracle disagreement below which TOL applies
+WELL_CONDITIONED = 1e-5   # oracle-vs-perturbed-oracle disagreement up to which TOL applies (the perturbation itself reaches ~5e-6 on large tensors)
 
 
 def tensor_slices(net):
@@ -30,6 +30,18 @@ def tensor_slices(net):
             out.append((s, name, off, off + n))
             off += n
     return out
+
+
+def median_rel_error(a, b, slices):
+    """Median over tensors of max|d|/max|ref|: robust against the few tensors a
+    ReLU-mask tie touches."""
+    errs = []
+    for s, name, lo, hi in slices:
+        r = b[lo:hi]
+        mx = np.abs(r).max()
+        if mx > 0:
+            errs.append(np.abs(a[lo:hi].astype(np.float64) - r).max() / mx)
+    return float(np.median(errs)) if errs else 0.0
 
 
 def rel_errors(a, b, slices):
@@ -50,9 +62,9 @@ def rel_errors(a, b, slices):
     return worst_inf, worst_l2, where
 
 
-def perturbed_oracle(net, seed, mitigation, eps, gen_seed=12345):
+def perturbed_oracle(net, seed, mitigation, eps, gen_seed=12345, lr=None):
     import torch
-    orc = O.PBOracle(net, seed=seed, mitigation=mitigation)
+    orc = O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr)
     g = torch.Generator().manual_seed(gen_seed)
     for p in orc.w:
         for k in p:
@@ -60,11 +72,11 @@ def perturbed_oracle(net, seed, mitigation, eps, gen_seed=12345):
     return orc
 
 
-def run_parity(engine_cls, net, K, mitigation=3, seed=42, every=1, engine_kwargs=None, verbose=False):
+def run_parity(engine_cls, net, K, mitigation=3, seed=42, every=1, engine_kwargs=None, verbose=False, lr=None):
     xs, ys = W.sample_pool(net)
-    orc = O.PBOracle(net, seed=seed, mitigation=mitigation)
-    orcs = [perturbed_oracle(net, seed, mitigation, e, 12345 + i) for i, e in enumerate(PERTURB)]
-    eng = engine_cls(net, seed=seed, mitigation=mitigation, **(engine_kwargs or {}))
+    orc = O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr)
+    orcs = [perturbed_oracle(net, seed, mitigation, e, 12345 + i, lr=lr) for i, e in enumerate(PERTURB)]
+    eng = engine_cls(net, seed=seed, mitigation=mitigation, lr=lr, **(engine_kwargs or {}))
     slices = tensor_slices(net)
     w0 = eng.read_weights()
     assert w0.size == orc.read_weights().size
@@ -91,11 +103,13 @@ def run_parity(engine_cls, net, K, mitigation=3, seed=42, every=1, engine_kwargs
                 violations.append((t, e_inf, e_l2, where, tol))
             if e_inf > worst[0]:
                 worst = (e_inf, max(e_l2, worst[1]), where, t)
+    med = median_rel_error(eng.read_weights(), orc.read_weights(), slices)
     lg, lo = eng.loss_history(), orc.loss_history()
     ev, ov = eng.read_velocity(), orc.read_velocity()
+    l_sens = max(np.abs(o2.loss_history() - lo).max() for o2 in orcs) if len(lo) else 0.0
     v_sens = max(np.abs(o2.read_velocity() - ov).max() for o2 in orcs) / np.abs(ov).max()
     v_err = np.abs(ev - ov).max() / np.abs(ov).max()
     eng.close()
     return dict(worst_inf=worst[0], worst_l2=worst[1], where=worst[2], tick=worst[3],
-                violations=violations, strict_ticks=strict_ticks, checked=checked,
-                loss_gpu=lg, loss_cpu=lo, v_err=v_err, v_tol=max(10 * TOL, SENS_FACTOR * v_sens))
+                violations=violations, strict_ticks=strict_ticks, checked=checked, median_final=med,
+                loss_gpu=lg, loss_cpu=lo, loss_tol=max(1e-4, SENS_FACTOR * l_sens), v_err=v_err, v_tol=max(10 * TOL, SENS_FACTOR * v_sens))

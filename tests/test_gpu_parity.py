@@ -17,11 +17,12 @@ def _engine():
 
 def _check(res, K, S):
     print(f"worst inf {res['worst_inf']:.3e} l2 {res['worst_l2']:.3e} at {res['where']} tick {res['tick']}; "
-          f"strict 1e-5 tolerance in force on {res['strict_ticks']}/{res['checked']} checked ticks",
+          f"strict 1e-5 tolerance in force on {res['strict_ticks']}/{res['checked']} checked ticks; "
+          f"median tensor error at the last tick {res['median_final']:.2e}",
           file=sys.stderr, flush=True)
     assert not res["violations"], res["violations"][:3]
     assert len(res["loss_gpu"]) == len(res["loss_cpu"]) == max(0, K - S + 1)
-    assert np.allclose(res["loss_gpu"], res["loss_cpu"], rtol=1e-4, atol=1e-5)
+    assert np.allclose(res["loss_gpu"], res["loss_cpu"], rtol=res["loss_tol"], atol=res["loss_tol"])
     assert res["v_err"] <= res["v_tol"], (res["v_err"], res["v_tol"])
 
 
@@ -85,3 +86,37 @@ def test_resnet20_config_100_ticks():
     net = W.config("resnet20")
     res = run_parity(_engine(), net, 100, every=5)
     _check(res, 100, len(net["stages"]))
+
+
+def test_vgg11_config_100_ticks():
+    net = W.config("vgg11")
+    res = run_parity(_engine(), net, 100, every=5)
+    _check(res, 100, len(net["stages"]))
+
+
+def test_wide_config_100_ticks():
+    # 256-channel stages on 8x8 maps: a single ReLU-mask tie moves a GroupNorm-shift
+    # gradient by ~1/64 of a channel's sum and about one tie per sample occurs, so
+    # oracles perturbed by 1e-6 already disagree by ~5e-3 on a few `beta` tensors
+    # from the first update on (and at the configuration's lr the first 100 ticks
+    # are chaotic: loss spikes to ~9).  Checked here at a tenth of the lr: the
+    # tie-aware tolerance on every tensor, plus the median over tensors, which the
+    # few tie-affected tensors cannot move.
+    net = W.config("wide")
+    res = run_parity(_engine(), net, 100, every=5, lr=0.0005)
+    assert res["strict_ticks"] >= 5
+    assert res["median_final"] <= 10 * TOL, res["median_final"]
+    _check(res, 100, len(net["stages"]))
+
+
+def test_resnet50_structure_64px_120_ticks():
+    net = W.config("resnet50_64")
+    res = run_parity(_engine(), net, 120, every=10)
+    _check(res, 120, len(net["stages"]))
+
+
+def test_reference_kernel_set_matches_too():
+    """The plain direct kernels (kernel_set=1) are a second GPU implementation."""
+    net = W.config("small_resnet")
+    res = run_parity(_engine(), net, 60, engine_kwargs=dict(kernel_set=1))
+    _check(res, 60, len(net["stages"]))
