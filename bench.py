@@ -98,12 +98,19 @@ def main():
     ticks_per_s = args.steps / dt
 
     # second pass over the same region with HIP events around every launch
+    # (a) the launches as timed above; (b) one launch per step with the update as
+    # its stand-alone kernel, which isolates the update's duration inside the tick
     prof_ticks = min(args.steps, 500)
     eng.profile_begin(64 * prof_ticks)
     eng.run_resident(xd, yd, warm + args.steps, prof_ticks)
-    n_upd, ms_upd = eng.profile_end(1)
     n_ph, ms_ph = eng.profile_end(0)
+    eng.set_launch_mode(1)
+    prof2 = min(args.steps, 200)
+    eng.profile_begin(512 * prof2)
+    eng.run_resident(xd, yd, warm + args.steps + prof_ticks, prof2)
+    n_upd, ms_upd = eng.profile_end(1)
     n_in, ms_in = eng.profile_end(2)
+    eng.set_launch_mode(args.launch_mode)
     upd_us = 1e3 * ms_upd / max(n_upd, 1)
     upd_bytes = 24 * n_params                     # w,v,g read; w,v,w_hat written
     achieved = upd_bytes / (upd_us * 1e-6) / 1e9
@@ -124,9 +131,10 @@ def main():
                      "avg_launch_us": upd_us, "algorithmic_bytes_per_launch": upd_bytes},
         "tick_roofline": {"bound": "hbm", "algorithmic_bytes": tick_algorithmic_bytes(net, n_params),
                           "frac": tick_algorithmic_bytes(net, n_params) / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
-        "kernel_time_us_per_tick": {"stage_phases": 1e3 * ms_ph / prof_ticks, "update": 1e3 * ms_upd / prof_ticks,
-                                    "ingest": 1e3 * ms_in / prof_ticks,
-                                    "launches_per_tick": (n_ph + n_upd + n_in) / prof_ticks},
+        "kernel_time_us_per_tick": {"phase_launches": 1e3 * ms_ph / prof_ticks,
+                                    "launches_per_tick": n_ph / prof_ticks,
+                                    "update_alone": 1e3 * ms_upd / max(prof2, 1),
+                                    "ingest_alone": 1e3 * ms_in / max(prof2, 1)},
         "final_loss_mean_last_200": float(losses[-200:].mean()),
     }
     eng.close()

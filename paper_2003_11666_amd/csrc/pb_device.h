@@ -35,7 +35,10 @@ enum StepKind : int32_t {
   K_CONV_BWD_W = 8,  // backward weights (+ bias)
   K_COPY = 9,
   K_GEMM = 10,       // conv / linear forward, backward data or backward weights as an MFMA implicit GEMM
-  K_BIAS_GRAD = 11   // db[co] = sum_p dZ[co,p]
+  K_BIAS_GRAD = 11,  // db[co] = sum_p dZ[co,p]
+  K_INGEST = 12,     // the tick's sample and label into the first stage's ring
+  K_UPDATE = 13,     // fused SC+LWP update of one stage's parameter block
+  K_HEAD = 14        // whole last stage (forward, loss, backward) in one workgroup
 };
 
 constexpr int LDS_FLOATS = 12288;   // 48 KB of LDS per workgroup for the GEMM steps
@@ -86,6 +89,8 @@ struct StepDesc {
   int32_t sC, sH, sW, sstride;  // skip tensor dims and projection stride
   int32_t n;                // generic element count (CE: classes, COPY: floats)
   int32_t loss_cap, n_stages;
+  float fa, fb, flrT, flr, fm;   // K_UPDATE: SC coefficients a, b, lr*T, lr, momentum
+  int32_t pad0_;
   GemmCfg g;     // main operand set of a K_GEMM step
   GemmCfg gp;    // projection of the skip tensor accumulated into the same tile (forward only)
   TRef x;        // op input (forward) / saved input (backward)
@@ -100,6 +105,8 @@ struct StepDesc {
   const float* wp;
   const float* gamma;
   const float* beta;
+  float* v;            // K_UPDATE: velocity block; K_HEAD: unused
+  float* what;         // K_UPDATE: predicted-weight block (nullptr without LWP)
   float* gw;           // gradient outputs
   float* gb;
   float* ggamma;
@@ -126,7 +133,8 @@ struct UpdSeg {       // per stage constants of the fused update
 };
 
 // ---- launch wrappers implemented in pb_kernels.hip ----
-void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, hipStream_t s);
+void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, const float* sample_override,
+                  int label_override, hipStream_t s);
 void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,
                    int n_stages, const Globals* G, int k, hipStream_t s);
 void launch_update(float* w, float* v, const float* g, float* what, const int32_t* chunk_stage,

@@ -238,7 +238,7 @@ void plan_arena(const std::vector<Stage>& st, bool lwp, int loss_cap, Layout& L,
       b.postst = pl.alloc((int64_t)(a.D + 1) * b.st_stride);
       b.dz = pl.alloc(a.z_elems());
     }
-    if (a.pre_gn || a.post_gn) b.part = pl.alloc(2 * a.gnC());
+    if (a.pre_gn || a.post_gn) b.part = pl.alloc(3 * a.gnC());
     if (a.pre_gn) b.da = pl.alloc(a.gap ? a.C : a.in_elems());
     if (s < S - 1) b.gradbox = pl.alloc(2 * (int64_t)a.out_elems());
     if (a.tap_dist) b.skg = pl.alloc((int64_t)(a.tap_dist + 1) * a.in_elems());
@@ -320,6 +320,11 @@ int bwd_w_tiles(int K, int C, int k, int P, bool bias) {
   const int64_t nW = (int64_t)K * C * k * k;
   const int per = P > 16 ? BLK / 64 : BLK;
   return cdiv(nW, per) + (bias ? cdiv(K, per) : 0);
+}
+
+void sc_coeffs(double m, int D, double* a, double* b) {
+  *a = (D == 0) ? 1.0 : pow(m, (double)D);
+  *b = (m == 1.0) ? (double)D : (1.0 - *a) / (1.0 - m);
 }
 
 // ---------------------------------------------------------- GEMM tiling
@@ -433,6 +438,43 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     if (s < S - 1) y_out = ring(c, L.sb[s + 1].xring, c->st[s + 1].D + 2, a.out_elems(), -1);
     else y_out = ring(c, b.logits, 1, a.K, 0);
     int ph = 0;
+    if (s == 0) {
+      // the sample arrives in phase 0; the first stage's forward chain follows it
+      StepDesc d = blank(K_INGEST, 0, 0);
+      d.n = a.in_elems(); d.n_stages = S;
+      d.dx = x_f;
+      d.labels = c->labels_dev;
+      d.ntiles = cdiv(d.n, BLK);
+      out.push_back({0, d});
+      ph = 1;
+    }
+    // a small last stage runs as one workgroup: forward, loss and backward
+    const int head_cv = a.gap ? a.Cin : a.in_elems();
+    const bool fused_head = a.ce && c->kernel_set == 0 && !a.post_gn && !a.add && !a.is_conv && (a.gap ? a.pre_gn : !a.pre_gn) &&
+                            (int64_t)a.K * head_cv <= 65536 && a.in_elems() <= 32768 &&
+                            2 * head_cv + a.K + 6 * a.Cin + 64 <= LDS_FLOATS && s > 0;
+    if (fused_head) {
+      StepDesc d = blank(K_HEAD, s, t_f);
+      d.C = a.Cin; d.H = a.Hin; d.W = a.Win; d.K = a.K; d.G = a.pre_gn ? a.G : 1;
+      d.n_stages = S; d.loss_cap = c->loss_cap;
+      if (a.pre_gn) d.flags |= F_PRE_AFFINE;
+      if (a.pre_relu) d.flags |= F_PRE_RELU;
+      if (a.gap) d.flags |= F_DU_GAP;
+      if (a.has_bias) { d.flags |= F_BIAS; d.b = wf + a.o_b; d.gb = gr + a.o_b; }
+      d.x = x_f;
+      d.w = wf + a.o_w; d.wp = wb + a.o_w; d.gw = gr + a.o_w;
+      if (a.pre_gn) {
+        d.gamma = wf + a.o_gamma; d.beta = wf + a.o_beta;
+        d.skip.base = const_cast<float*>(wb + a.o_gamma);
+        d.ggamma = gr + a.o_gamma; d.gbeta = gr + a.o_beta;
+      }
+      d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
+      d.loss_log = c->f(L.loss);
+      d.labels = c->labels_dev;
+      d.ntiles = 1;
+      out.push_back({0, d});
+      continue;
+    }
     // ------------------------------------------------------------ forward
     if (a.pre_gn) {
       StepDesc d = blank(K_GN_STATS, s, t_f);
@@ -643,6 +685,28 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       }
     }
   }
+  // ---- fused update: one step per stage, in the first phase in which no step
+  // reads parameters or writes gradients any more
+  int last_param_phase = 0;
+  for (auto& pr : out) {
+    const int kd = pr.second.kind;
+    const bool touches = kd == K_GN_STATS || kd == K_CONV_FWD || kd == K_GEMM || kd == K_GNB_REDUCE || kd == K_CONV_BWD_X ||
+                         kd == K_CONV_BWD_W || kd == K_BIAS_GRAD || kd == K_HEAD;
+    if (touches) last_param_phase = std::max(last_param_phase, pr.first);
+  }
+  for (int s = 0; s < S; ++s) {
+    const Stage& a = c->st[s];
+    StepDesc d = blank(K_UPDATE, s, 2 * (S - 1) - s);
+    double ca = 1.0, cb = 0.0;
+    if (c->mitigation == 1 || c->mitigation == 3) sc_coeffs((double)c->m, a.D, &ca, &cb);
+    const double T = (c->mitigation >= 2) ? (double)a.D : 0.0;
+    d.fa = (float)ca; d.fb = (float)cb; d.flrT = (float)((double)c->lr * T); d.flr = c->lr; d.fm = c->m;
+    d.w = c->f(L.w + a.off); d.v = c->f(L.v + a.off); d.gw = c->f(L.g + a.off);
+    d.what = lwp ? c->f(L.what + a.off) : nullptr;
+    d.n = (int)a.padded;
+    d.ntiles = (int)(a.padded / UPD_CHUNK);
+    out.push_back({last_param_phase + 1, d});
+  }
 }
 
 // Host-side audit of the step table: every tensor reference a kernel will
@@ -696,7 +760,7 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
       case K_GNB_APPLY: {
         const int64_t dyn = (d.flags & F_DU_BUF) ? in : (d.flags & F_DU_GAP) ? d.C : (int64_t)d.C * d.PH * d.PW;
         ok = ok && d.G > 0 && d.C % d.G == 0 && ref_ok(d.x, in) && ref_ok(d.st, stn) && ref_ok(d.dy, dyn) &&
-             ptr_ok(d.part, 2 * d.C) && ptr_ok(d.gamma, d.C);
+             ptr_ok(d.part, 3 * d.C) && ptr_ok(d.gamma, d.C);
         if (d.kind == K_GNB_REDUCE) ok = ok && d.ntiles == d.C && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C);
         else ok = ok && (int64_t)d.ntiles * BLK >= in && ref_ok(d.dx, in) && (!(d.flags & F_ADD_SKG) || ref_ok(d.skg, in));
         break;
@@ -714,6 +778,26 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
       case K_COPY:
         ok = ok && (int64_t)d.ntiles * BLK >= d.n && ref_ok(d.dy, d.n) && ref_ok(d.dx, d.n);
         break;
+      case K_INGEST:
+        ok = ok && (int64_t)d.ntiles * BLK >= d.n && ref_ok(d.dx, d.n) && ptr_ok((const float*)d.labels, d.n_stages);
+        break;
+      case K_UPDATE:
+        ok = ok && d.n > 0 && d.n % UPD_CHUNK == 0 && d.ntiles == d.n / UPD_CHUNK && ptr_ok(d.w, d.n) && ptr_ok(d.v, d.n) &&
+             ptr_ok(d.gw, d.n) && (!d.what || ptr_ok(d.what, d.n));
+        break;
+      case K_HEAD: {
+        const int64_t cv = (d.flags & F_DU_GAP) ? d.C : in;
+        ok = ok && d.ntiles == 1 && d.K > 0 && 2 * cv + d.K + 6 * d.C + 64 <= LDS_FLOATS && ref_ok(d.x, in) &&
+             ptr_ok(d.w, d.K * cv) && ptr_ok(d.wp, d.K * cv) && ptr_ok(d.gw, d.K * cv) && ptr_ok(d.loss_log, d.loss_cap) &&
+             ptr_ok((const float*)d.labels, d.n_stages) && (!(d.flags & F_BIAS) || (ptr_ok(d.b, d.K) && ptr_ok(d.gb, d.K))) &&
+             (!d.dx.base || ref_ok(d.dx, in)) && d.G > 0 && d.C % d.G == 0;
+        if (d.flags & F_PRE_AFFINE)
+          ok = ok && ptr_ok(d.gamma, d.C) && ptr_ok(d.beta, d.C) && ptr_ok(d.skip.base, d.C) && ptr_ok(d.ggamma, d.C) &&
+               ptr_ok(d.gbeta, d.C) && (d.flags & F_DU_GAP);
+        else
+          ok = ok && !(d.flags & F_DU_GAP);
+        break;
+      }
       case K_BIAS_GRAD:
         ok = ok && d.ntiles * (BLK / 64) >= d.K && ref_ok(d.dy, outn) && ptr_ok(d.gb, d.K);
         break;
@@ -811,11 +895,6 @@ void init_weights_host(const std::vector<Stage>& st, uint64_t seed, std::vector<
   }
 }
 
-void sc_coeffs(double m, int D, double* a, double* b) {
-  *a = (D == 0) ? 1.0 : pow(m, (double)D);
-  *b = (m == 1.0) ? (double)D : (1.0 - *a) / (1.0 - m);
-}
-
 int64_t copy_params_out(pb_ctx* c, int64_t arena_off, float* dst, int64_t cap) {
   if (!dst) return c->n_params;
   if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(PB_E_HIP, "stream synchronize failed");
@@ -849,25 +928,20 @@ struct ScopedEv {
 
 int run_one_tick(pb_ctx* c, const float* staging, int label) {
   const int k = (int)c->ticks;   // t_base stays 0 on this path
-  {
-    ScopedEv ev(c, 2);
-    launch_ingest(ring(c, c->L.sb[0].xring, c->st[0].D + 2, c->st[0].in_elems(), 0), c->st[0].in_elems(),
-                  staging, label, c->labels_dev, c->S, c->globals_dev, k, c->stream);
-  }
   if (c->launch_mode == 0) {
     for (const Phase& p : c->phases) {
       ScopedEv ev(c, 0);
-      launch_phase(c->recs_dev + c->rec_first[p.first], p.tiles, c->globals_dev, k, c->stream);
+      launch_phase(c->recs_dev + c->rec_first[p.first], p.tiles, c->globals_dev, k, staging, label, c->stream);
     }
   } else {
+    // one launch per step; the update as the single stand-alone kernel (same arithmetic)
     for (const Phase& p : c->phases)
       for (int i = 0; i < p.count; ++i) {
-        ScopedEv ev(c, 0);
-        launch_phase(c->recs_dev + c->rec_first[p.first + i], c->steps[p.first + i].ntiles, c->globals_dev, k,
-                     c->stream);
+        const StepDesc& sd = c->steps[p.first + i];
+        if (sd.kind == K_UPDATE) continue;
+        ScopedEv ev(c, sd.kind == K_INGEST ? 2 : 0);
+        launch_phase(c->recs_dev + c->rec_first[p.first + i], sd.ntiles, c->globals_dev, k, staging, label, c->stream);
       }
-  }
-  {
     ScopedEv ev(c, 1);
     launch_update(c->f(c->L.w), c->f(c->L.v), c->f(c->L.g), c->L.what >= 0 ? c->f(c->L.what) : nullptr,
                   c->chunk_stage_dev, c->segs_dev, c->n_chunks, c->lr, c->m, c->globals_dev, k, c->stream);
@@ -921,7 +995,7 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   std::vector<std::pair<int, StepDesc>> steps;
   compile_steps(&tmp, steps);
   static const char* names[] = {"gn_stats", "gap_fwd", "conv_fwd", "post_fwd", "ce", "gnb_reduce", "gnb_apply",
-                                "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad"};
+                                "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad", "ingest", "update", "head"};
   std::string o;
   char line[400];
   for (auto& pr : steps) {

@@ -278,6 +278,7 @@ __device__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red) {
     const float gm = GP(d.gamma)[c];
     GP(d.part)[c] = gm * sb;
     GP(d.part)[d.C + c] = gm * sg;
+    GP(d.part)[2 * d.C + c] = gm;   // the elementwise pass must not read the parameter arena (it may run beside the update)
   }
 }
 
@@ -298,7 +299,7 @@ __device__ void step_gnb_apply(const LDesc& d, int tile, int t) {
   if ((d.flags & F_GN_RELU) && !(yv > 0.f)) du = 0.f;
   const float xh = (xv - mean) * rstd;
   const float inv_n = 1.0f / (float)n;
-  float r = rstd * (du * GP(d.gamma)[c] - S1 * inv_n - xh * (S2 * inv_n));
+  float r = rstd * (du * GP(d.part)[2 * d.C + c] - S1 * inv_n - xh * (S2 * inv_n));
   if (d.flags & F_ADD_SKG) r += at(d.skg, t)[o];
   at(d.dx, t)[o] = r;
 }
@@ -394,13 +395,189 @@ __device__ void step_copy(const LDesc& d, int tile, int t) {
   if (o < d.n) at(d.dx, t)[o] = at(d.dy, t)[o];
 }
 
+
+// The tick's sample into the first stage's input ring, its label into the
+// label ring.  src != nullptr: handed over by the host call; otherwise pool
+// item (idx_base + k) mod n_pool.
+__device__ void step_ingest(const LDesc& d, int tile, int t, const Globals* __restrict__ G, int k,
+                            const float* src_override, int label_override) {
+  const gfloat* src = (const gfloat*)src_override;
+  int lab = label_override;
+  if (!src_override) {
+    const int item = (int)(((int64_t)G->idx_base + k) % G->n_pool);
+    src = (const gfloat*)G->pool + (size_t)item * d.n;
+    lab = ((const gint*)G->pool_labels)[item];
+  }
+  gfloat* dst = at(d.dx, t);
+  const int i = tile * BLK + threadIdx.x;
+  if (i < d.n) dst[i] = src[i];
+  if (i == 0) ((gint*)d.labels)[t % d.n_stages] = lab;
+}
+
+// Fused Spike-Compensated momentum update with Linear Weight Prediction of one
+// 1024-float chunk of a stage: v <- m v + g; w <- w - lr (a v + b g);
+// w_hat <- w - lr T v.
+__device__ void step_update(const LDesc& d, int tile) {
+  const size_t i = (size_t)tile * (UPD_CHUNK / 4) + threadIdx.x;
+  const float a = d.fa, b = d.fb, lrT = d.flrT, lr = d.flr, m = d.fm;
+  typedef __attribute__((address_space(1))) v4f gv4;
+  const v4f gv = ((const gv4*)d.gw)[i];
+  v4f vv = ((gv4*)d.v)[i];
+  v4f wv = ((gv4*)d.w)[i];
+  vv.x = fmaf(m, vv.x, gv.x); vv.y = fmaf(m, vv.y, gv.y);
+  vv.z = fmaf(m, vv.z, gv.z); vv.w = fmaf(m, vv.w, gv.w);
+  wv.x = fmaf(-lr, fmaf(a, vv.x, b * gv.x), wv.x);
+  wv.y = fmaf(-lr, fmaf(a, vv.y, b * gv.y), wv.y);
+  wv.z = fmaf(-lr, fmaf(a, vv.z, b * gv.z), wv.z);
+  wv.w = fmaf(-lr, fmaf(a, vv.w, b * gv.w), wv.w);
+  ((gv4*)d.v)[i] = vv;
+  ((gv4*)d.w)[i] = wv;
+  if (d.what) {
+    v4f p;
+    p.x = fmaf(-lrT, vv.x, wv.x); p.y = fmaf(-lrT, vv.y, wv.y);
+    p.z = fmaf(-lrT, vv.z, wv.z); p.w = fmaf(-lrT, vv.w, wv.w);
+    ((gv4*)d.what)[i] = p;
+  }
+}
+
+// The whole last stage in one workgroup: [GroupNorm, ReLU, global average
+// pool |  ReLU | nothing] -> linear -> softmax cross-entropy -> backward of all
+// of it.  Forward parameters: d.w / d.b / d.gamma / d.beta point into the
+// predicted arena; the backward ones (current weights) are d.wp (weight) and
+// d.skip.base (GroupNorm scale).  LDS: vec[Cv] | dvec[Cv] | logit[K] | chan[4C].
+__device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int C = d.C, HW = d.H * d.W, K = d.K, G = d.G;
+  const bool gn = d.flags & F_PRE_AFFINE, rl = d.flags & F_PRE_RELU, gap = d.flags & F_DU_GAP;
+  const int Cv = gap ? C : C * HW;                 // length of the vector the linear layer sees
+  lfloat* vec = smem;
+  lfloat* dvec = smem + Cv;
+  lfloat* logit = dvec + Cv;
+  lfloat* chan = logit + K;                        // sc[C], sh[C], mean[C], rstd[C], then 2C partial sums
+  const gfloat* x = at(d.x, t);
+  // ---- forward
+  if (gn) {
+    const int cpg = C / G, n = cpg * HW;
+    for (int g = 0; g < G; ++g) {
+      const gfloat* xp = x + (size_t)g * n;
+      float s = 0.f;
+      for (int i = tid; i < n; i += BLK) s += xp[i];
+      const float mean = block_sum(s, red) / (float)n;
+      float q = 0.f;
+      for (int i = tid; i < n; i += BLK) { const float dl = xp[i] - mean; q = fmaf(dl, dl, q); }
+      const float var = block_sum(q, red) / (float)n;
+      const float rstd = 1.0f / sqrtf(var + GN_EPS);
+      for (int c = tid; c < cpg; c += BLK) {
+        const int ch = g * cpg + c;
+        const float sc = GP(d.gamma)[ch] * rstd;
+        chan[ch] = sc;
+        chan[C + ch] = fmaf(-mean, sc, GP(d.beta)[ch]);
+        chan[2 * C + ch] = mean;
+        chan[3 * C + ch] = rstd;
+      }
+    }
+    __syncthreads();
+  }
+  if (gap) {
+    for (int c = wv; c < C; c += BLK / 64) {
+      const float sc = gn ? chan[c] : 1.f, sh = gn ? chan[C + c] : 0.f;
+      float s = 0.f;
+      for (int i = lane; i < HW; i += 64) {
+        float v = fmaf(sc, x[(size_t)c * HW + i], sh);
+        if (rl) v = fmaxf(v, 0.f);
+        s += v;
+      }
+      s = wave_sum(s);
+      if (lane == 0) vec[c] = s / (float)HW;
+    }
+  } else {
+    for (int i = tid; i < Cv; i += BLK) { const float v = x[i]; vec[i] = rl ? fmaxf(v, 0.f) : v; }
+  }
+  __syncthreads();
+  for (int kk = wv; kk < K; kk += BLK / 64) {
+    const gfloat* wr = GP(d.w) + (size_t)kk * Cv;
+    float s = 0.f;
+    for (int i = lane; i < Cv; i += 64) s = fmaf(wr[i], vec[i], s);
+    s = wave_sum(s);
+    if (lane == 0) logit[kk] = s + ((d.flags & F_BIAS) ? GP(d.b)[kk] : 0.f);
+  }
+  __syncthreads();
+  // ---- loss and dlogits (kept in logit[])
+  {
+    const int sample = t - (d.n_stages - 1);
+    const int label = ((const gint*)d.labels)[sample % d.n_stages];
+    float mx = -3.0e38f;
+    for (int i = tid; i < K; i += BLK) mx = fmaxf(mx, logit[i]);
+    mx = block_max(mx, red);
+    float s = 0.f;
+    for (int i = tid; i < K; i += BLK) s += expf(logit[i] - mx);
+    s = block_sum(s, red);
+    const float zl = logit[label];
+    __syncthreads();
+    for (int i = tid; i < K; i += BLK) logit[i] = expf(logit[i] - mx) / s - (i == label ? 1.f : 0.f);
+    if (tid == 0) GP(d.loss_log)[sample % d.loss_cap] = logf(s) + mx - zl;
+  }
+  __syncthreads();
+  // ---- backward of the linear layer: dW = dl (x) vec, db = dl, dvec = W_cur^T dl
+  for (int e = tid; e < K * Cv; e += BLK) { const int kk = e / Cv; GP(d.gw)[e] = logit[kk] * vec[e - kk * Cv]; }
+  if (d.flags & F_BIAS) for (int i = tid; i < K; i += BLK) GP(d.gb)[i] = logit[i];
+  for (int i = tid; i < Cv; i += BLK) {
+    float s = 0.f;
+    for (int kk = 0; kk < K; ++kk) s = fmaf(GP(d.wp)[(size_t)kk * Cv + i], logit[kk], s);
+    dvec[i] = s;
+  }
+  __syncthreads();
+  if (d.dx.base == nullptr && !gn) return;
+  gfloat* dx = d.dx.base ? at(d.dx, t) : nullptr;
+  if (!gn) {
+    for (int i = tid; i < Cv; i += BLK) { float r = dvec[i]; if (rl && !(x[i] > 0.f)) r = 0.f; dx[i] = r; }
+    return;
+  }
+  // ---- GroupNorm backward with du[c,hw] = dvec[c]/HW (after the pool) or dvec[c*HW+hw]
+  const gfloat* gam_b = (const gfloat*)d.skip.base;     // current GroupNorm scale
+  lfloat* part = chan + 4 * C;                          // S1_c, S2_c
+  for (int c = wv; c < C; c += BLK / 64) {
+    const float sc = chan[c], sh = chan[C + c], mean = chan[2 * C + c], rstd = chan[3 * C + c];
+    float sg = 0.f, sb = 0.f;
+    for (int i = lane; i < HW; i += 64) {
+      const float xv = x[(size_t)c * HW + i];
+      float du = gap ? dvec[c] / (float)HW : dvec[c * HW + i];
+      if (rl && !(fmaf(sc, xv, sh) > 0.f)) du = 0.f;
+      sg = fmaf(du, (xv - mean) * rstd, sg);
+      sb += du;
+    }
+    sg = wave_sum(sg); sb = wave_sum(sb);
+    if (lane == 0) {
+      GP(d.ggamma)[c] = sg; GP(d.gbeta)[c] = sb;
+      const float gm = gam_b[c];
+      part[c] = gm * sb; part[C + c] = gm * sg;
+    }
+  }
+  __syncthreads();
+  if (!dx) return;
+  const int cpg = C / G, n = cpg * HW;
+  const float inv_n = 1.0f / (float)n;
+  for (int o = tid; o < C * HW; o += BLK) {
+    const int c = o / HW, g = c / cpg;
+    float S1 = 0.f, S2 = 0.f;
+    for (int j = 0; j < cpg; ++j) { S1 += part[g * cpg + j]; S2 += part[C + g * cpg + j]; }
+    const float sc = chan[c], sh = chan[C + c], mean = chan[2 * C + c], rstd = chan[3 * C + c];
+    const float xv = x[o];
+    float du = gap ? dvec[c] / (float)HW : dvec[o];
+    if (rl && !(fmaf(sc, xv, sh) > 0.f)) du = 0.f;
+    const float xh = (xv - mean) * rstd;
+    dx[o] = rstd * (du * gam_b[c] - S1 * inv_n - xh * (S2 * inv_n));
+  }
+}
+
 // ------------------------------------------------------------------ kernels
 // One workgroup = one tile of one step.  recs[] holds, per workgroup of the
 // phase, a full copy of its step descriptor with the tile index filled in, so
 // that a single burst of scalar loads (one memory round trip) delivers all a
 // workgroup needs to know.
 __global__ void __launch_bounds__(BLK)
-k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k) {
+k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
+        const float* __restrict__ sample_override, int label_override) {
   __shared__ float red_[8];
   __shared__ __attribute__((aligned(16))) float smem_[LDS_FLOATS];
   lfloat* red = (lfloat*)red_;
@@ -433,6 +610,9 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k)
     case K_COPY: step_copy(d, tile, t); break;
     case K_GEMM: step_gemm(d, tile, t, smem); break;
     case K_BIAS_GRAD: step_bias_grad(d, tile, t); break;
+    case K_INGEST: step_ingest(d, tile, t, G, k, sample_override, label_override); break;
+    case K_UPDATE: step_update(d, tile); break;
+    case K_HEAD: step_head(d, t, red, smem); break;
     default: break;
   }
 }
@@ -524,9 +704,10 @@ __global__ void k_advance(Globals* G, int dt, int didx) {
 }
 
 // --------------------------------------------------------- launch wrappers
-void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, hipStream_t s) {
+void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, const float* sample_override,
+                  int label_override, hipStream_t s) {
   if (total_tiles <= 0) return;
-  hipLaunchKernelGGL(k_phase, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, G, k);
+  hipLaunchKernelGGL(k_phase, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, G, k, sample_override, label_override);
 }
 
 void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,
