@@ -60,6 +60,8 @@ struct GemmCfg {
   int32_t o_offq, o_patch;   // LDS offsets (floats); the A chunk sits at 0
   int32_t n_chunks;
   int32_t lgA, lgP;        // log2 of the padded row lengths used by the staging thread maps
+  int32_t vec;             // 1: patch rows are staged with 16-byte copies (source rows a multiple of 4 wide, no transform)
+  int32_t xoff;            // LDS column of logical patch column 0
 };
 
 enum StepFlags : int32_t {

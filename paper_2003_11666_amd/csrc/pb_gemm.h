@@ -103,8 +103,9 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
         else if (GM == 2) { const int ih = n / gW, iw = n - ih * gW; o = (ih - tile_row0) * Wp + iw; }
         else { const int ci = n / kk, tap = n - ci * kk, kh = tap / gk, kw = tap - kh * gk; o = (ci - c_lo) * PRW + kh * Wp + kw; }
       }
-      offn[j] = o;
+      offn[j] = o + UNI(g.xoff);
     }
+    const int vec = UNI(g.vec);
     __syncthreads();   // LDS may still be in use by the previous operand set
     for (int i = tid; i < QCpad; i += BLK) {
       int o = 0;
@@ -171,6 +172,45 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
       if (GM == 1) { chan0 = ch * CC; row0 = tile_row0 * gs - gpad; }
       else if (GM == 2) { chan0 = ch * CC; row0 = tile_row0; }
       else { chan0 = c_lo; row0 = ch * rows_c * gs - gpad; }
+      if (vec) {
+        // rows of the source map go to LDS with 16-byte copies; the interior of a
+        // patch row starts at column 4, columns 0..3 and Wsrc+4..Wsrc+7 are halo
+        typedef __attribute__((address_space(1))) v4f gv4;
+        typedef __attribute__((address_space(3))) v4f lv4;
+        const int Wsrc = (GM == 2) ? gOW : gW, Hsrc = (GM == 2) ? gOH : gH, Cred = (GM == 2) ? gK : gC;
+        const int W4 = Wsrc >> 2, nrow = CC * PR, nslot = nrow * W4;
+        const int rshift = (GM == 2) ? border : 0;
+        constexpr int VU = 8;
+        int r = tid / W4, xs = tid - r * W4;
+        int c = r / PR, y = r - c * PR;
+        const int dr = BLK / W4, dxs = BLK - dr * W4, dc = dr / PR, dy = dr - dc * PR;
+        for (int base = tid; base < nslot; base += BLK * VU) {
+          v4f v[VU];
+          int dst[VU];
+#pragma unroll
+          for (int u = 0; u < VU; ++u) {
+            v[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+            dst[u] = -1;
+            if (base + u * BLK < nslot) {
+              const int chn = chan0 + c, srow = row0 + y - rshift;
+              dst[u] = c * PRW + y * Wp + 4 + 4 * xs;
+              if (chn < Cred && srow >= 0 && srow < Hsrc)
+                v[u] = *(const gv4*)(src + ((size_t)chn * Hsrc + srow) * Wsrc + 4 * xs);
+            }
+            xs += dxs; y += dy; c += dc;
+            if (xs >= W4) { xs -= W4; ++y; }
+            if (y >= PR) { y -= PR; ++c; }
+            if (y >= PR) { y -= PR; ++c; }
+          }
+#pragma unroll
+          for (int u = 0; u < VU; ++u)
+            if (dst[u] >= 0) *(lv4*)(patch + dst[u]) = v[u];
+        }
+        for (int h = tid; h < 2 * nrow; h += BLK) {
+          const int rr = h >> 1;
+          *(lv4*)(patch + rr * Wp + ((h & 1) ? Wsrc + 4 : 0)) = (v4f){0.f, 0.f, 0.f, 0.f};
+        }
+      } else
       {
         int c = p_c0, y = p_y0, x = p_x0;
         for (int base = tid; base < patch_elems; base += BLK * SU) {

@@ -203,6 +203,7 @@ struct Plan {
 };
 
 struct StageBufs {
+  int64_t aring = -1;   // normalised + rectified stage input (pre-norm conv stages)
   int64_t xring = -1, prest = -1, pooled = -1, zring = -1, postst = -1, gradbox = -1, skg = -1,
           da = -1, dz = -1, part = -1, logits = -1, dlogits = -1;
   int st_stride = 0;
@@ -219,7 +220,7 @@ struct Layout {
 
 int st_stride_of(const Stage& s) { return (2 * s.G + 2 * s.gnC() + 63) / 64 * 64; }
 
-void plan_arena(const std::vector<Stage>& st, bool lwp, int loss_cap, Layout& L, Plan& pl) {
+void plan_arena(const std::vector<Stage>& st, bool lwp, int loss_cap, Layout& L, Plan& pl, bool use_aring) {
   const int S = (int)st.size();
   L.P = 0;
   for (const Stage& s : st) L.P += s.padded;
@@ -232,6 +233,7 @@ void plan_arena(const std::vector<Stage>& st, bool lwp, int loss_cap, Layout& L,
     b.xring = pl.alloc((int64_t)(a.D + 2) * a.in_elems());
     if (a.pre_gn || a.post_gn) b.st_stride = st_stride_of(a);
     if (a.pre_gn) b.prest = pl.alloc((int64_t)(a.D + 1) * b.st_stride);
+    if (a.pre_gn && !a.gap && use_aring) b.aring = pl.alloc((int64_t)(a.D + 1) * a.in_elems());
     if (a.gap) b.pooled = pl.alloc((int64_t)(a.D + 1) * a.C);
     if (a.post_gn) {
       b.zring = pl.alloc((int64_t)(a.D + 1) * a.z_elems());
@@ -337,7 +339,7 @@ int pow2_floor(int x) { int p = 1; while (p * 2 <= x) p *= 2; return p; }
 int g_tile_target = 8;   // workgroups a step is split into at least, when its shape allows
 
 bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int s, int pad,
-               const GemmCfg* like, GemmCfg* out) {
+               const GemmCfg* like, GemmCfg* out, bool allow_vec = false) {
   const int target = g_tile_target;
   GemmCfg g;
   memset(&g, 0, sizeof g);
@@ -363,6 +365,15 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
   g.MT = 16 * g.wm; g.NT = 16 * g.ni * g.wn;
   g.tiles_n = cdiv(g.N, g.NT);
   g.tiles = cdiv(g.M, g.MT) * g.tiles_n;
+  // 16-byte row copies: source rows a multiple of 4 floats wide, no transform
+  // while staging, and (backward data) unit stride so that no zeros interleave
+  const int hl = (mode == 2) ? k - 1 - pad : pad;
+  g.vec = 0;
+  if (allow_vec && hl <= 4) {
+    if (mode == 2) g.vec = (s == 1 && OW % 4 == 0) ? 1 : 0;
+    else g.vec = (W % 4 == 0) ? 1 : 0;
+  }
+  g.xoff = g.vec ? 4 - hl : 0;
   auto fits = [&](int QC, int CC, int PR, int Wp) {
     const int QCpad = (QC + 3) / 4 * 4;
     const int64_t need = QCpad + (int64_t)CC * PR * Wp + 64;
@@ -373,6 +384,7 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
     const int rows_max = std::min(nrows, (g.NT + rowlen - 2) / rowlen + 1);
     g.PR = mode == 1 ? (rows_max - 1) * s + k : rows_max + k - 1;
     g.Wp = mode == 1 ? W + 2 * pad : W + k - 1;
+    if (g.vec) g.Wp = (mode == 1 ? W : OW) + 8;
     const int nch = mode == 1 ? C : K;
     int CC = nch;
     while (CC > 1 && !fits(CC * kk, CC, g.PR, g.Wp)) CC = (CC + 1) / 2;
@@ -380,7 +392,7 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
     g.CC = CC; g.QC = CC * kk; g.n_chunks = cdiv(nch, CC); g.rows_c = 0;
   } else {
     g.CC = std::min(C, (g.NT + kk - 2) / kk + 1);
-    g.Wp = W + 2 * pad;
+    g.Wp = g.vec ? W + 8 : W + 2 * pad;
     auto pr = [&](int r) { return (r - 1) * s + k; };
     // one chunk holding every output row, else the largest row count whose
     // pixel count is a multiple of 4 (chunks in the middle must not be padded)
@@ -481,6 +493,10 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       d.C = a.Cin; d.H = a.Hin; d.W = a.Win; d.G = a.G;
       d.x = x_f; d.st = ring(c, b.prest, D + 1, b.st_stride, 0);
       d.gamma = wf + a.o_gamma; d.beta = wf + a.o_beta;
+      if (b.aring >= 0) {
+        d.y = ring(c, b.aring, D + 1, a.in_elems(), 0);
+        if (a.pre_relu) d.flags |= F_PRE_RELU;
+      }
       d.ntiles = a.G;
       out.push_back({ph++, d});
     }
@@ -501,8 +517,12 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         d.x = ring(c, b.pooled, D + 1, a.C, 0);
       } else {
         d.x = x_f;
-        if (a.pre_gn) { d.flags |= F_PRE_AFFINE; d.st = ring(c, b.prest, D + 1, b.st_stride, 0); }
-        if (a.pre_relu) d.flags |= F_PRE_RELU;
+        if (b.aring >= 0) {
+          d.x = ring(c, b.aring, D + 1, a.in_elems(), 0);     // already normalised and rectified
+        } else {
+          if (a.pre_gn) { d.flags |= F_PRE_AFFINE; d.st = ring(c, b.prest, D + 1, b.st_stride, 0); }
+          if (a.pre_relu) d.flags |= F_PRE_RELU;
+        }
       }
       d.w = wf + a.o_w;
       if (a.has_bias) { d.flags |= F_BIAS; d.b = wf + a.o_b; }
@@ -522,8 +542,9 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       if (c->kernel_set == 0) {
         GemmCfg g, gp;
         memset(&gp, 0, sizeof gp);
-        bool ok = make_gemm(1, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g);
-        if (ok && (d.flags & F_PROJ)) ok = make_gemm(1, d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, 0, &g, &gp);
+        const bool plain_src = !(d.flags & (F_PRE_AFFINE | F_PRE_RELU));
+        bool ok = make_gemm(1, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, plain_src);
+        if (ok && (d.flags & F_PROJ)) ok = make_gemm(1, d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, 0, &g, &gp, true);
         if (ok) { d.kind = K_GEMM; d.g = g; d.gp = gp; d.ntiles = g.tiles; }
       }
       out.push_back({ph++, d});
@@ -586,15 +607,20 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         d.x = ring(c, b.pooled, D + 1, a.C, D);
       } else {
         d.x = x_b;
-        if (a.pre_gn) { d.flags |= F_PRE_AFFINE; d.st = ring(c, b.prest, D + 1, b.st_stride, D); }
-        if (a.pre_relu) d.flags |= F_PRE_RELU;
+        if (b.aring >= 0) {
+          d.x = ring(c, b.aring, D + 1, a.in_elems(), D);
+        } else {
+          if (a.pre_gn) { d.flags |= F_PRE_AFFINE; d.st = ring(c, b.prest, D + 1, b.st_stride, D); }
+          if (a.pre_relu) d.flags |= F_PRE_RELU;
+        }
       }
       d.dy = dz_src;
       d.gw = gr + a.o_w;
       if (a.has_bias) { d.flags |= F_BIAS; d.gb = gr + a.o_b; }
       d.ntiles = bwd_w_tiles(a.K, a.C, a.k, a.OH * a.OW, a.has_bias);
       GemmCfg g;
-      if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g)) {
+      if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g,
+                                          !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)))) {
         if (a.has_bias) {
           StepDesc e = blank(K_BIAS_GRAD, s, t_b);
           e.K = a.K; e.OH = a.OH; e.OW = a.OW; e.dy = dz_src; e.gb = gr + a.o_b;
@@ -620,7 +646,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       }
       d.ntiles = cdiv((int64_t)a.C * a.H * a.W, BLK);
       GemmCfg g;
-      if (c->kernel_set == 0 && make_gemm(2, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g)) {
+      if (c->kernel_set == 0 && make_gemm(2, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, true)) {
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
       }
       out.push_back({pb, d});
@@ -638,7 +664,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         d.gw = gr + a.o_wp;
         d.ntiles = bwd_w_tiles(a.K, a.sC, 1, a.OH * a.OW, false);
         GemmCfg g;
-        if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, 1, d.stride, 0, nullptr, &g)) {
+        if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, 1, d.stride, 0, nullptr, &g, true)) {
           d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
         }
         out.push_back({pb, d});
@@ -650,7 +676,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         e.dx = skg_w;
         e.ntiles = cdiv(ta.in_elems(), BLK);
         GemmCfg g2;
-        if (c->kernel_set == 0 && make_gemm(2, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, 0, nullptr, &g2)) {
+        if (c->kernel_set == 0 && make_gemm(2, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, 0, nullptr, &g2, true)) {
           e.kind = K_GEMM; e.g = g2; e.ntiles = g2.tiles;
         }
         out.push_back({pb, e});
@@ -730,7 +756,7 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
     switch (d.kind) {
       case K_GN_STATS:
         ok = ok && d.G > 0 && d.C % d.G == 0 && d.ntiles == d.G && ref_ok(d.x, in) && ref_ok(d.st, stn) &&
-             ptr_ok(d.gamma, d.C) && ptr_ok(d.beta, d.C);
+             ptr_ok(d.gamma, d.C) && ptr_ok(d.beta, d.C) && (!d.y.base || ref_ok(d.y, in));
         break;
       case K_GAP_FWD:
         ok = ok && d.ntiles == d.C && ref_ok(d.x, in) && ref_ok(d.y, d.C) &&
@@ -809,18 +835,26 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
                    g.QCpad >= g.QC && g.o_offq >= 0 && g.o_patch >= g.o_offq + g.QCpad &&
                    (int64_t)g.o_patch + (int64_t)g.CC * g.PR * g.Wp <= LDS_FLOATS && LDS_FLOATS >= 4096 &&
                    (int64_t)g.n_chunks * g.QC >= g.Q && g.lgA >= 0 && g.lgA <= 8 && g.lgP >= 0 && g.lgP <= 8;
+          const int hl_ = (g.gm == 2) ? k - 1 - pad : pad;
+          if (g.vec) {
+            const int wsrc = (g.gm == 2) ? d.OW : W;
+            o = o && wsrc % 4 == 0 && g.Wp == wsrc + 8 && g.xoff == 4 - hl_ && hl_ <= 4 && (g.gm != 2 || s == 1) &&
+                (g.o_patch % 4) == 0 && !(d.flags & (F_PRE_AFFINE | F_PRE_RELU) && g.gm != 2);
+          } else {
+            o = o && g.xoff == 0;
+          }
           if (g.gm == 1) {
             const int rows_max = std::min(d.OH, (g.NT + d.OW - 2) / d.OW + 1);
             o = o && g.M == d.K && g.N == d.OH * d.OW && g.Q == C * kk && g.QC == g.CC * kk &&
-                g.PR >= (rows_max - 1) * s + k && g.Wp >= W + 2 * pad && g.Wp >= (d.OW - 1) * s + k;
+                g.PR >= (rows_max - 1) * s + k && g.Wp >= W + 2 * pad && g.Wp >= (d.OW - 1) * s + k + g.xoff;
           } else if (g.gm == 2) {
             const int rows_max = std::min(H, (g.NT + W - 2) / W + 1);
             o = o && g.M == C && g.N == H * W && g.Q == d.K * kk && g.QC == g.CC * kk && g.PR >= rows_max + k - 1 &&
-                g.Wp >= W + k - 1 && pad <= k - 1;
+                g.Wp >= W + k - 1 + g.xoff && pad <= k - 1;
           } else if (g.gm == 3) {
             o = o && g.M == d.K && g.N == C * kk && g.Q == d.OH * d.OW && g.QC == g.rows_c * d.OW &&
                 g.CC >= std::min(C, (g.NT + kk - 2) / kk + 1) && g.PR >= (g.rows_c - 1) * s + k && g.Wp >= W + 2 * pad &&
-                g.Wp >= (d.OW - 1) * s + k && (g.n_chunks == 1 || g.QC % 4 == 0);
+                g.Wp >= (d.OW - 1) * s + k + g.xoff && (g.n_chunks == 1 || g.QC % 4 == 0);
           } else {
             o = false;
           }
@@ -968,7 +1002,7 @@ size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays) {
   const int cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   Plan pl;
   Layout L;
-  plan_arena(st, net->mitigation >= 2, cap, L, pl);
+  plan_arena(st, net->mitigation >= 2, cap, L, pl, net->kernel_set == 0);
   // step table, prefix, chunk map and segment table live in the arena too
   tmp.L = L; tmp.loss_cap = cap; tmp.arena = nullptr;
   tmp.labels_dev = (int32_t*)tmp.f(L.labels);
@@ -990,7 +1024,7 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   tmp.st = st; tmp.S = (int)st.size(); tmp.kernel_set = net->kernel_set;
   const int lcap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   Plan pl;
-  plan_arena(st, net->mitigation >= 2, lcap, tmp.L, pl);
+  plan_arena(st, net->mitigation >= 2, lcap, tmp.L, pl, net->kernel_set == 0);
   tmp.loss_cap = lcap;
   std::vector<std::pair<int, StepDesc>> steps;
   compile_steps(&tmp, steps);
@@ -1062,7 +1096,7 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   INIT_TRY(hipMemsetAsync(base, 0, need, c->stream));
 
   Plan pl;
-  plan_arena(st, net->mitigation >= 2, c->loss_cap, c->L, pl);
+  plan_arena(st, net->mitigation >= 2, c->loss_cap, c->L, pl, net->kernel_set == 0);
   c->labels_dev = (int32_t*)c->f(c->L.labels);
   c->globals_dev = (Globals*)c->f(c->L.globals);
   c->zero_dev = (int32_t*)c->f(c->L.zero);

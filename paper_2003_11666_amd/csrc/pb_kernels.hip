@@ -95,6 +95,19 @@ __device__ void step_gn_stats(const LDesc& d, int tile, int t, lfloat* red) {
     st[2 * d.G + ch] = sc;
     st[2 * d.G + d.C + ch] = fmaf(-mean, sc, GP(d.beta)[ch]);
   }
+  if (d.y.base) {
+    // the normalised (and rectified) group, kept for the convolution of this
+    // tick and for the weight gradient of the same sample D ticks later
+    gfloat* yo = at(d.y, t) + (size_t)g * n;
+    const bool rl = d.flags & F_PRE_RELU;
+    for (int i = threadIdx.x; i < n; i += BLK) {
+      const int ch = g * cpg + i / HW;
+      const float sc = GP(d.gamma)[ch] * rstd;
+      float v = fmaf(sc, xp[i], fmaf(-mean, sc, GP(d.beta)[ch]));
+      if (rl) v = fmaxf(v, 0.f);
+      yo[i] = v;
+    }
+  }
 }
 
 // pooled[c] = mean_hw relu(sc*x+sh)
