@@ -116,6 +116,10 @@ struct StepDesc {
   float* part;         // per-channel partial sums of the GN backward
   float* loss_log;
   int32_t* labels;     // label ring [n_stages]
+  const int32_t* tq;   // K_GEMM: reduction index (chunk-relative) -> patch offset, QCpad entries
+  const int32_t* tn;   // K_GEMM: column index -> patch offset, N entries
+  const int32_t* tq2;  // the same for the projection operand set
+  const int32_t* tn2;
 };
 
 // State that changes from tick to tick lives in device memory so that a

@@ -25,6 +25,9 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 // One tile of a K_GEMM step, GM = 1 forward, 2 backward data, 3 backward
 // weights.  A forward step may carry a second operand set (the 1x1 projection
 // of the skip tensor) that accumulates into the same tile.
+//
+// The per-step offset tables (tq: reduction index -> patch offset, tn: column
+// -> patch offset) are built on the host, so the tile does no index division.
 template <int GM>
 __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfloat* smem) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -34,36 +37,11 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
   const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
   const int m0 = tm * UNI(d.g.MT), n0 = tn * UNI(d.g.NT);
   const int flags = UNI(d.flags);
+  const int kq = lane >> 4;
   v4f acc[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
   const int nops = (GM == 1 && (flags & F_PROJ)) ? 2 : 1;
-  // what the epilogue adds or masks with is fetched now, together with the
-  // operands, instead of after the MFMA loop
-  float e_add[4][4], e_msk[4][4];
-  {
-    const int M = UNI(d.g.M), N = UNI(d.g.N);
-    const gfloat* skip = (GM == 1 && (flags & F_SKIP) && !(flags & F_PROJ)) ? (const gfloat*)at(d.skip, t) : nullptr;
-    const gfloat* xm = (GM == 2 && (flags & F_MASK_X)) ? (const gfloat*)at(d.x, t) : nullptr;
-    const gfloat* skg = (GM == 2 && (flags & F_ADD_SKG)) ? (const gfloat*)at(d.skg, t) : nullptr;
-    const gfloat* bias = (GM == 1 && (flags & F_BIAS)) ? GP(d.b) : nullptr;
-    const int mrow = m0 + wm_id * 16 + 4 * (lane >> 4);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        e_add[j][r] = 0.f; e_msk[j][r] = 1.f;
-        if (wk_id == 0 && j < ni && n < N && mrow + r < M) {
-          const size_t o = (size_t)(mrow + r) * N + n;
-          if (GM == 1 && bias) e_add[j][r] = bias[mrow + r];
-          if (GM == 1 && skip) e_add[j][r] += skip[o];
-          if (GM == 2 && skg) e_add[j][r] = skg[o];
-          if (GM == 2 && xm) e_msk[j][r] = xm[o];
-        }
-      }
-    }
-  }
 
   for (int op = 0; op < nops; ++op) {
     const bool second = GM == 1 && op == 1;
@@ -79,6 +57,8 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
     const gfloat* st = (GM != 2 && !second && (flags & F_PRE_AFFINE)) ? (const gfloat*)at(d.st, t) : nullptr;
     const bool relu = GM != 2 && !second && (flags & F_PRE_RELU);
     const int stG = UNI(d.G), stC = UNI(d.C);
+    const gint* tq = (const gint*)(second ? d.tq2 : d.tq);
+    const gint* tnb = (const gint*)(second ? d.tn2 : d.tn);
 
     lint* offq = (lint*)(smem + UNI(g.o_offq));
     lfloat* patch = smem + UNI(g.o_patch);
@@ -86,86 +66,64 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
     const int HW = gH * gW, P = gOH * gOW;
     const int QC = UNI(g.QC), QCpad = UNI(g.QCpad), CC = UNI(g.CC), M = UNI(g.M), N = UNI(g.N), Q = UNI(g.Q);
     const int n_chunks = UNI(g.n_chunks), rows_c = UNI(g.rows_c);
+    const int vec = UNI(g.vec);
+    const int border = gk - 1 - gpad;
 
     // first row (of the output map for forward / backward weights, of the input
-    // map for backward data) this tile touches, and per-lane column offsets
-    int tile_row0 = 0, c_lo = 0;
-    if (GM == 1) tile_row0 = n0 / gOW;
-    else if (GM == 2) tile_row0 = n0 / gW;
-    else c_lo = n0 / kk;
+    // map for backward data) this tile touches; per-lane column offsets
+    int tile_row0 = 0, c_lo = 0, adj;
+    if (GM == 1) { tile_row0 = n0 / gOW; adj = tile_row0 * gs * Wp; }
+    else if (GM == 2) { tile_row0 = n0 / gW; adj = tile_row0 * Wp; }
+    else { c_lo = n0 / kk; adj = c_lo * PRW; }
+    adj -= UNI(g.xoff);
     int offn[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
-      int o = 0;
-      if (j < ni && n < N) {
-        if (GM == 1) { const int oh = n / gOW, ow = n - oh * gOW; o = (oh - tile_row0) * gs * Wp + ow * gs; }
-        else if (GM == 2) { const int ih = n / gW, iw = n - ih * gW; o = (ih - tile_row0) * Wp + iw; }
-        else { const int ci = n / kk, tap = n - ci * kk, kh = tap / gk, kw = tap - kh * gk; o = (ci - c_lo) * PRW + kh * Wp + kw; }
-      }
-      offn[j] = o + UNI(g.xoff);
+      offn[j] = (j < ni && n < N) ? tnb[n] - adj : 0;
     }
-    const int vec = UNI(g.vec);
     __syncthreads();   // LDS may still be in use by the previous operand set
-    for (int i = tid; i < QCpad; i += BLK) {
-      int o = 0;
-      if (i < QC) {
-        if (GM == 3) { const int r = i / gOW, ow = i - r * gOW; o = r * gs * Wp + ow * gs; }
-        else {
-          const int c = i / kk, tap = i - c * kk, kh = tap / gk, kw = tap - kh * gk;
-          o = (GM == 1) ? c * PRW + kh * Wp + kw : c * PRW + (gk - 1 - kh) * Wp + (gk - 1 - kw);
-        }
-      }
-      offq[i] = o;
-    }
-    const int nsteps = QCpad >> 2;
+    for (int i = tid; i < QCpad; i += BLK) offq[i] = tq[i];
     const int patch_elems = CC * PRW;
-    // Patch staging walks flat element indices tid, tid+BLK, ... keeping their
-    // (channel, row, column) decomposition incrementally; loads are issued SU
-    // at a time before any is consumed, so that their latencies overlap.
-    constexpr int SU = 16;
+    constexpr int SU = 8;
     const int p_c0 = tid / PRW, p_rem = tid - p_c0 * PRW, p_y0 = p_rem / Wp, p_x0 = p_rem - p_y0 * Wp;
     const int p_dc = BLK / PRW, p_r2 = BLK - p_dc * PRW, p_dy = p_r2 / Wp, p_dx = p_r2 - p_dy * Wp;
-    const int border = gk - 1 - gpad;
-    // lane (i = lane%16, kq = lane/16) needs A[m][4*ks + kq] for its k-steps ks.
-    // A round trip to memory costs far more than a tile's MFMAs, so the loads
-    // run two register batches ahead of their use.
-    constexpr int KB = 16;                       // k-steps per register batch
-    const int am = m0 + wm_id * 16 + (lane & 15);
-    const bool am_ok = am < M;
+    // ---- A operand: lane (row i = lane%16, kq = lane/16) needs A[m][4*ks + kq] for
+    // the k-steps ks = wk_id, wk_id + wk, ... of its wave.  Rows beyond M are
+    // clamped (their results are never stored), so only the last, partial
+    // k-step of a chunk needs a predicate.
+    constexpr int KB = 8;
+    int am = m0 + wm_id * 16 + (lane & 15);
+    if (am >= M) am = M - 1;
     const int dq = 4 * wk, dq_co = dq / kk, dq_tap = dq - dq_co * kk;
     const gfloat* arow = Aglob + (GM == 2 ? (size_t)am * kk : (size_t)am * Q);
+    const size_t co_stride = (size_t)gC * kk;
 
     for (int ch = 0; ch < n_chunks; ++ch) {
       const int q0 = ch * QC;
-      float a0[KB], a1[KB];
-      int qr = 4 * wk_id + (lane >> 4);          // chunk-relative reduction index of the lane's next k-step
+      const int qc_eff = (Q - q0 < QC) ? Q - q0 : QC;       // valid reduction entries in this chunk
+      const int nfull = qc_eff >> 2;                        // k-steps in which all 4 lane groups are valid
+      const int nk = (nfull > wk_id) ? (nfull - wk_id + wk - 1) / wk : 0;   // ... that belong to this wave
+      int qr = 4 * wk_id + kq;
       int a_co = 0, a_tap = 0;
       if (GM == 2) { a_co = (q0 + qr) / kk; a_tap = q0 + qr - a_co * kk; }
-      auto load_batch = [&](float (&a)[KB]) {
-#pragma unroll
-        for (int u = 0; u < KB; ++u) {
-          a[u] = 0.f;
-          if (am_ok && qr < QC && q0 + qr < Q) a[u] = (GM == 2) ? arow[(size_t)a_co * gC * kk + a_tap] : arow[q0 + qr];
-          qr += dq;
-          if (GM == 2) { a_tap += dq_tap; a_co += dq_co; if (a_tap >= kk) { a_tap -= kk; ++a_co; } }
-        }
+      float a0[KB], a1[KB];
+      auto load1 = [&]() -> float {
+        const float v = (GM == 2) ? arow[a_co * co_stride + a_tap] : arow[q0 + qr];
+        qr += dq;
+        if (GM == 2) { a_tap += dq_tap; a_co += dq_co; if (a_tap >= kk) { a_tap -= kk; ++a_co; } }
+        return v;
       };
-      auto mfma_batch = [&](const float (&a)[KB], int kb) {
+      int issued = 0;                                       // k-steps of this wave whose A load has been issued
+      if (nk >= KB) {
 #pragma unroll
-        for (int u = 0; u < KB; ++u) {
-          const int ks = kb + u * wk;
-          if (ks < nsteps) {
-            const int oq = offq[ks * 4 + (lane >> 4)];
+        for (int u = 0; u < KB; ++u) a0[u] = load1();
+        issued = KB;
+      } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-              if (j < ni) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u], patch[oq + offn[j]], acc[j], 0, 0, 0);
-          }
-        }
-      };
-      // ---- first two batches of A loads (in flight while the patch is staged)
-      load_batch(a0);
-      load_batch(a1);
+        for (int u = 0; u < KB; ++u)
+          if (u < nk) a1[u] = load1();
+      }
       if (ch) __syncthreads();
       // ---- patch
       int chan0, row0;
@@ -180,7 +138,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
         const int Wsrc = (GM == 2) ? gOW : gW, Hsrc = (GM == 2) ? gOH : gH, Cred = (GM == 2) ? gK : gC;
         const int W4 = Wsrc >> 2, nrow = CC * PR, nslot = nrow * W4;
         const int rshift = (GM == 2) ? border : 0;
-        constexpr int VU = 8;
+        constexpr int VU = 4;
         int r = tid / W4, xs = tid - r * W4;
         int c = r / PR, y = r - c * PR;
         const int dr = BLK / W4, dxs = BLK - dr * W4, dc = dr / PR, dy = dr - dc * PR;
@@ -255,11 +213,57 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
       }
       __syncthreads();
       // ---- MFMA loop: lane holds A[i = lane%16][k = lane/16] and B[k = lane/16][j = lane%16]
-      for (int kb = wk_id; kb < nsteps; kb += 2 * KB * wk) {
-        mfma_batch(a0, kb);
-        if (kb + 2 * KB * wk < nsteps) load_batch(a0);
-        if (kb + KB * wk < nsteps) mfma_batch(a1, kb + KB * wk);
-        if (kb + 3 * KB * wk < nsteps) load_batch(a1);
+      const lint* oqp = offq + 4 * wk_id + kq;
+      int done = 0;
+      while (done + KB <= nk) {
+        // a0 holds the A values of k-steps done..done+KB-1; fetch the next batch first
+        const bool more = issued + KB <= nk;
+        if (more) {
+#pragma unroll
+          for (int u = 0; u < KB; ++u) a1[u] = load1();
+          issued += KB;
+        }
+#pragma unroll
+        for (int u = 0; u < KB; ++u) {
+          const int oq = oqp[(done + u) * dq];
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (j < ni) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0[u], patch[oq + offn[j]], acc[j], 0, 0, 0);
+        }
+        done += KB;
+        if (more) {
+#pragma unroll
+          for (int u = 0; u < KB; ++u) a0[u] = a1[u];
+        }
+      }
+      // remaining full k-steps of this wave (fewer than KB), then the chunk's partial k-step
+      {
+        const int rem = nk - done;
+        if (nk >= KB) {
+#pragma unroll
+          for (int u = 0; u < KB; ++u)
+            if (u < rem) a1[u] = load1();
+        }
+#pragma unroll
+        for (int u = 0; u < KB; ++u)
+          if (u < rem) {
+            const int oq = oqp[(done + u) * dq];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (j < ni) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[u], patch[oq + offn[j]], acc[j], 0, 0, 0);
+          }
+      }
+      if ((qc_eff & 3) && (nfull % wk) == wk_id) {
+        const int qt = 4 * nfull + kq;
+        float av = 0.f;
+        if (qt < qc_eff) {
+          if (GM == 2) { const int co = (q0 + qt) / kk; av = arow[co * co_stride + (q0 + qt - co * kk)]; }
+          else av = arow[q0 + qt];
+        }
+        const int oq = offq[qt];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (j < ni) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, patch[oq + offn[j]], acc[j], 0, 0, 0);
       }
     }
   }
@@ -291,17 +295,46 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
   // ---- epilogue: lane holds C[i = 4*(lane/16) + r][j = lane%16]
   const int M = UNI(d.g.M), N = UNI(d.g.N);
   gfloat* out = (GM == 1) ? at(d.y, t) : (GM == 2) ? at(d.dx, t) : GP(d.gw);
-  const int mrow = m0 + wm_id * 16 + 4 * (lane >> 4);
+  const int mrow = m0 + wm_id * 16 + 4 * kq;
+  const bool extras = (GM == 1 && (flags & (F_BIAS | F_SKIP))) || (GM == 2 && (flags & (F_MASK_X | F_ADD_SKG)));
+  if (!extras) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
+      if (j < ni && n < N) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (mrow + r < M) out[(size_t)(mrow + r) * N + n] = acc[j][r];
+      }
+    }
+    return;
+  }
+  const gfloat* skip = (GM == 1 && (flags & F_SKIP) && !(flags & F_PROJ)) ? (const gfloat*)at(d.skip, t) : nullptr;
+  const gfloat* xm = (GM == 2 && (flags & F_MASK_X)) ? (const gfloat*)at(d.x, t) : nullptr;
+  const gfloat* skg = (GM == 2 && (flags & F_ADD_SKG)) ? (const gfloat*)at(d.skg, t) : nullptr;
+  const gfloat* bias = (GM == 1 && (flags & F_BIAS)) ? GP(d.b) : nullptr;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
     if (j >= ni || n >= N) continue;
+    float add[4], msk[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      add[r] = 0.f; msk[r] = 1.f;
+      if (mrow + r < M) {
+        const size_t o = (size_t)(mrow + r) * N + n;
+        if (bias) add[r] = bias[mrow + r];
+        if (skip) add[r] += skip[o];
+        if (skg) add[r] = skg[o];
+        if (xm) msk[r] = xm[o];
+      }
+    }
 #pragma unroll
     for (int r = 0; r < 4; ++r)
       if (mrow + r < M) {
         float v = acc[j][r];
-        if (GM == 2 && !(e_msk[j][r] > 0.f)) v = 0.f;
-        out[(size_t)(mrow + r) * N + n] = v + e_add[j][r];
+        if (GM == 2 && !(msk[r] > 0.f)) v = 0.f;
+        out[(size_t)(mrow + r) * N + n] = v + add[r];
       }
   }
 }

@@ -277,6 +277,8 @@ struct pb_ctx {
   int kernel_set = 0;
   std::vector<StepDesc> steps;         // sorted by phase
   std::vector<int64_t> rec_first;      // per step: index of its first per-workgroup record
+  Plan* plan = nullptr;                // arena allocator while the step table is compiled
+  std::vector<std::pair<int64_t, std::vector<int32_t>>> tables;   // (arena offset, contents) of the GEMM offset tables
   std::vector<Phase> phases;
   int n_chunks = 0;
   // device views
@@ -422,6 +424,33 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
   return true;
 }
 
+// Offset tables of one GEMM operand set (see pb_gemm.h): tq maps the
+// chunk-relative reduction index, tn the column index, to offsets into the
+// LDS patch.  They depend on the step only, not on the tile.
+void gemm_tables(pb_ctx* c, const GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int s,
+                 const int32_t** tq, const int32_t** tn) {
+  const int kk = k * k, PRW = g.PR * g.Wp;
+  std::vector<int32_t> q(g.QCpad, 0), n(g.N, 0);
+  for (int i = 0; i < g.QC; ++i) {
+    if (g.gm == 3) { const int r = i / OW, ow = i % OW; q[i] = r * s * g.Wp + ow * s; }
+    else {
+      const int cc = i / kk, tap = i % kk, kh = tap / k, kw = tap % k;
+      q[i] = (g.gm == 1) ? cc * PRW + kh * g.Wp + kw : cc * PRW + (k - 1 - kh) * g.Wp + (k - 1 - kw);
+    }
+  }
+  for (int i = 0; i < g.N; ++i) {
+    if (g.gm == 1) { const int oh = i / OW, ow = i % OW; n[i] = oh * s * g.Wp + ow * s; }
+    else if (g.gm == 2) { const int ih = i / W, iw = i % W; n[i] = ih * g.Wp + iw; }
+    else { const int ci = i / kk, tap = i % kk, kh = tap / k, kw = tap % k; n[i] = ci * PRW + kh * g.Wp + kw; }
+  }
+  const int64_t oq = c->plan->alloc((int64_t)q.size()), on = c->plan->alloc((int64_t)n.size());
+  *tq = (const int32_t*)c->f(oq);
+  *tn = (const int32_t*)c->f(on);
+  c->tables.push_back({oq, std::move(q)});
+  c->tables.push_back({on, std::move(n)});
+  (void)C; (void)H; (void)K; (void)OH;
+}
+
 // Compile the network into the step table.  Every step carries the phase it
 // may run in: steps of one stage's forward (or backward) chain depend on each
 // other and get consecutive phases; different stages and the two passes of
@@ -545,7 +574,11 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         const bool plain_src = !(d.flags & (F_PRE_AFFINE | F_PRE_RELU));
         bool ok = make_gemm(1, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, plain_src);
         if (ok && (d.flags & F_PROJ)) ok = make_gemm(1, d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, 0, &g, &gp, true);
-        if (ok) { d.kind = K_GEMM; d.g = g; d.gp = gp; d.ntiles = g.tiles; }
+        if (ok) {
+          d.kind = K_GEMM; d.g = g; d.gp = gp; d.ntiles = g.tiles;
+          gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, &d.tq, &d.tn);
+          if (d.flags & F_PROJ) gemm_tables(c, gp, d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, &d.tq2, &d.tn2);
+        }
       }
       out.push_back({ph++, d});
     }
@@ -628,6 +661,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
           out.push_back({pb, e});
         }
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles; d.flags &= ~F_BIAS;
+        gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, &d.tq, &d.tn);
       }
       out.push_back({pb, d});
     }
@@ -648,6 +682,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       GemmCfg g;
       if (c->kernel_set == 0 && make_gemm(2, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, true)) {
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
+        gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, &d.tq, &d.tn);
       }
       out.push_back({pb, d});
     }
@@ -666,6 +701,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         GemmCfg g;
         if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, 1, d.stride, 0, nullptr, &g, true)) {
           d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
+          gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, 1, d.stride, &d.tq, &d.tn);
         }
         out.push_back({pb, d});
         StepDesc e = blank(K_CONV_BWD_X, s, t_b);
@@ -678,6 +714,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         GemmCfg g2;
         if (c->kernel_set == 0 && make_gemm(2, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, 0, nullptr, &g2, true)) {
           e.kind = K_GEMM; e.g = g2; e.ntiles = g2.tiles;
+          gemm_tables(c, g2, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, &e.tq, &e.tn);
         }
         out.push_back({pb, e});
       } else {
@@ -860,7 +897,9 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
           }
           return o;
         };
-        ok = ok && d.ntiles == d.g.tiles && cfg_ok(d.g, d.C, d.H, d.W, d.k, d.stride, d.pad);
+        ok = ok && d.ntiles == d.g.tiles && cfg_ok(d.g, d.C, d.H, d.W, d.k, d.stride, d.pad) &&
+             ptr_ok((const float*)d.tq, d.g.QCpad) && ptr_ok((const float*)d.tn, d.g.N) &&
+             (!(d.flags & F_PROJ) || d.g.gm != 1 || (ptr_ok((const float*)d.tq2, d.gp.QCpad) && ptr_ok((const float*)d.tn2, d.gp.N)));
         const int64_t wn_ = (int64_t)d.K * d.C * d.k * d.k;
         if (d.g.gm == 1) {
           ok = ok && ref_ok(d.x, in) && ref_ok(d.y, outn) && ptr_ok(d.w, wn_) &&
@@ -1007,6 +1046,7 @@ size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays) {
   tmp.L = L; tmp.loss_cap = cap; tmp.arena = nullptr;
   tmp.labels_dev = (int32_t*)tmp.f(L.labels);
   std::vector<std::pair<int, StepDesc>> steps;
+  tmp.plan = &pl;
   compile_steps(&tmp, steps);
   if (validate_steps(&tmp, steps, pl.total) != PB_OK) return 0;
   int64_t total_tiles = 0;
@@ -1027,6 +1067,7 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   plan_arena(st, net->mitigation >= 2, lcap, tmp.L, pl, net->kernel_set == 0);
   tmp.loss_cap = lcap;
   std::vector<std::pair<int, StepDesc>> steps;
+  tmp.plan = &pl;
   compile_steps(&tmp, steps);
   static const char* names[] = {"gn_stats", "gap_fwd", "conv_fwd", "post_fwd", "ce", "gnb_reduce", "gnb_apply",
                                 "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad", "ingest", "update", "head"};
@@ -1102,6 +1143,7 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   c->zero_dev = (int32_t*)c->f(c->L.zero);
 
   std::vector<std::pair<int, StepDesc>> tagged;
+  c->plan = &pl;
   compile_steps(c, tagged);
   if (validate_steps(c, tagged, pl.total) != PB_OK) { pb_destroy(c); return PB_E_INVALID; }
   std::stable_sort(tagged.begin(), tagged.end(),
@@ -1159,6 +1201,8 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   INIT_TRY(hipMemcpyAsync(c->chunk_stage_dev, chunk_stage.data(), sizeof(int32_t) * c->n_chunks, hipMemcpyHostToDevice, c->stream));
   INIT_TRY(hipMemcpyAsync(c->segs_dev, segs.data(), sizeof(UpdSeg) * c->S, hipMemcpyHostToDevice, c->stream));
   INIT_TRY(hipMemcpyAsync(c->globals_dev, &g0, sizeof g0, hipMemcpyHostToDevice, c->stream));
+  for (auto& tb : c->tables)
+    INIT_TRY(hipMemcpyAsync(c->f(tb.first), tb.second.data(), sizeof(int32_t) * tb.second.size(), hipMemcpyHostToDevice, c->stream));
   INIT_TRY(hipStreamSynchronize(c->stream));
 #undef INIT_TRY
   *out = c;
