@@ -41,7 +41,7 @@ enum StepKind : int32_t {
   K_HEAD = 14        // whole last stage (forward, loss, backward) in one workgroup
 };
 
-constexpr int LDS_FLOATS = 12288;   // 48 KB of LDS per workgroup for the GEMM steps
+constexpr int LDS_FLOATS = 15872;   // 62 KB of LDS per workgroup for the GEMM steps (two workgroups per compute unit)
 
 // Tiling of one implicit-GEMM operand set: C[M x N] += A[M x Q] * B[Q x N] with
 // B[q][n] = patch[offq(q) + offn(n)], the patch being a zero-padded window of
@@ -52,15 +52,16 @@ struct GemmCfg {
   int32_t wm, wn, wk, ni; // 4 waves = wm x wn x wk (split of the reduction); ni 16-column subtiles per wave
   int32_t MT, NT, tiles_n, tiles;
   int32_t QC;             // reduction elements per chunk
-  int32_t QCpad;          // rounded up to a multiple of 4
+  int32_t QCpad;          // rounded up to a multiple of 16
   int32_t CC;             // channels per patch
   int32_t rows_c;         // backward weights: output rows per chunk
   int32_t PR, Wp;         // patch rows / width
-  int32_t LDA;
-  int32_t o_offq, o_patch;   // LDS offsets (floats); the A chunk sits at 0
+  int32_t avec;           // 1: the A block is fetched with 16-byte loads (segments 16-byte aligned, lengths multiples of 4)
+  int32_t o_offq, o_patch;   // LDS offsets (floats)
   int32_t n_chunks;
-  int32_t lgA, lgP;        // log2 of the padded row lengths used by the staging thread maps
-  int32_t vec;             // 1: patch rows are staged with 16-byte copies (source rows a multiple of 4 wide, no transform)
+  int32_t LDA, o_A;        // row stride of the A block in LDS (forward, backward weights) and its LDS offset
+  int32_t vec;             // 1: patch rows are staged with 16-byte copies (source rows a multiple of 4 wide, no transform);
+                           // 2: backward data of a strided layer: patch cleared, then the gradient scattered into it
   int32_t xoff;            // LDS column of logical patch column 0
 };
 

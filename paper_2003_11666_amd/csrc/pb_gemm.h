@@ -7,12 +7,15 @@
 //   backward weights  M = cout,  N = (cin, kh, kw), q = output pixels
 // B is never materialised: B[q][n] = patch[offq(q) + offn(n)], where the patch
 // is a zero-padded window of the (normalised, rectified) input -- or of the
-// output gradient placed at stride spacing -- staged in LDS per chunk of the
-// reduction, and offq / offn are separable offsets into it.  A goes from
-// global memory straight into the MFMA operand registers.
+// output gradient placed at stride spacing -- and offq / offn are separable
+// offsets into it (tables built on the host).
 //
-// The code is kept small on purpose: a tile's work is a few hundred MFMAs, so
-// instruction fetch of a long unrolled path costs more than it saves.
+// A batch-1 tile is a few hundred MFMAs, so what bounds it is the latency of
+// memory, not its bandwidth and not the matrix cores: the data a tile reads
+// was written by other workgroups one launch earlier and comes from beyond the
+// L2.  Everything a chunk of the reduction needs -- the A block and the patch
+// -- is therefore requested with coalesced loads that are all in flight
+// together, parked in LDS, and only then contracted.
 //
 // Included by pb_kernels.hip after its address-space helpers.
 #pragma once
@@ -21,26 +24,39 @@
 namespace pb {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) v4f gv4;
+typedef __attribute__((address_space(3))) v4f lv4;
 
 // One tile of a K_GEMM step, GM = 1 forward, 2 backward data, 3 backward
-// weights.  A forward step may carry a second operand set (the 1x1 projection
-// of the skip tensor) that accumulates into the same tile.
+// weights; NI = 16-column subtiles per wave.  A forward step may carry a second
+// operand set (the 1x1 projection of the skip tensor) that accumulates into the
+// same tile.
 //
-// The per-step offset tables (tq: reduction index -> patch offset, tn: column
-// -> patch offset) are built on the host, so the tile does no index division.
-template <int GM>
+// LDS per chunk: offq[QCpad] | A block | patch.
+//   A block, GM 1 and 3: MT rows of the chunk's reduction range, row stride LDA
+//   A block, GM 2:       one segment of MT*k*k floats per output channel of the
+//                        chunk -- the layout the weights have in memory
+template <int GM, int NI>
 __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfloat* smem) {
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int wk = UNI(d.g.wk), wn = UNI(d.g.wn), ni = UNI(d.g.ni);
-  const int wk_id = wv % wk, wn_id = (wv / wk) % wn, wm_id = wv / (wk * wn);
+  PB_TS(1);
+  const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);   // wave index: scalar
+  const int wk = UNI(d.g.wk), wn = UNI(d.g.wn);
+  constexpr int ni = NI;
+  // wk, wn are powers of two (4 waves = wm x wn x wk)
+  auto lg = [](int x) { return x == 1 ? 0 : (x == 2 ? 1 : 2); };
+  const int wk_id = wv & (wk - 1), wn_id = (wv >> lg(wk)) & (wn - 1), wm_id = wv >> (lg(wk) + lg(wn));
   const int tiles_n = UNI(d.g.tiles_n);
-  const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
-  const int m0 = tm * UNI(d.g.MT), n0 = tn * UNI(d.g.NT);
+  const int tm = UNI(fdiv(tile, frcp(tiles_n))), tn = tile - tm * tiles_n;
+  const int MT = UNI(d.g.MT);
+  const int m0 = tm * MT, n0 = tn * UNI(d.g.NT);
   const int flags = UNI(d.flags);
   const int kq = lane >> 4;
-  v4f acc[4];
+  // with one or two subtiles per wave consecutive MFMAs would wait for each other's
+  // result: odd k-steps of the unrolled loop go to a second accumulator set
+  constexpr bool DUAL = NI <= 2;
+  v4f acc[NI], acc2[NI];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
+  for (int j = 0; j < NI; ++j) { acc[j] = (v4f){0.f, 0.f, 0.f, 0.f}; acc2[j] = (v4f){0.f, 0.f, 0.f, 0.f}; }
   const int nops = (GM == 1 && (flags & F_PROJ)) ? 2 : 1;
 
   for (int op = 0; op < nops; ++op) {
@@ -61,87 +77,114 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
     const gint* tnb = (const gint*)(second ? d.tn2 : d.tn);
 
     lint* offq = (lint*)(smem + UNI(g.o_offq));
+    lfloat* Alds = smem + UNI(g.o_A);
     lfloat* patch = smem + UNI(g.o_patch);
     const int kk = gk * gk, Wp = UNI(g.Wp), PR = UNI(g.PR), PRW = PR * Wp;
     const int HW = gH * gW, P = gOH * gOW;
     const int QC = UNI(g.QC), QCpad = UNI(g.QCpad), CC = UNI(g.CC), M = UNI(g.M), N = UNI(g.N), Q = UNI(g.Q);
-    const int n_chunks = UNI(g.n_chunks), rows_c = UNI(g.rows_c);
-    const int vec = UNI(g.vec);
+    const int n_chunks = UNI(g.n_chunks), rows_c = UNI(g.rows_c), LDA = UNI(g.LDA);
+    const int vec = UNI(g.vec), avec = UNI(g.avec);
     const int border = gk - 1 - gpad;
 
     // first row (of the output map for forward / backward weights, of the input
     // map for backward data) this tile touches; per-lane column offsets
     int tile_row0 = 0, c_lo = 0, adj;
-    if (GM == 1) { tile_row0 = n0 / gOW; adj = tile_row0 * gs * Wp; }
-    else if (GM == 2) { tile_row0 = n0 / gW; adj = tile_row0 * Wp; }
-    else { c_lo = n0 / kk; adj = c_lo * PRW; }
+    if (GM == 1) { tile_row0 = UNI(fdiv(n0, frcp(gOW))); adj = tile_row0 * gs * Wp; }
+    else if (GM == 2) { tile_row0 = UNI(fdiv(n0, frcp(gW))); adj = tile_row0 * Wp; }
+    else { c_lo = UNI(fdiv(n0, frcp(kk))); adj = c_lo * PRW; }
     adj -= UNI(g.xoff);
-    int offn[4];
+    int offn[NI];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NI; ++j) {
       const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
-      offn[j] = (j < ni && n < N) ? tnb[n] - adj : 0;
+      offn[j] = (n < N) ? tnb[n] - adj : 0;
     }
+    if (!op) PB_TS(2);
     __syncthreads();   // LDS may still be in use by the previous operand set
-    for (int i = tid; i < QCpad; i += BLK) offq[i] = tq[i];
+    if (!op) PB_TS(9);
     const int patch_elems = CC * PRW;
-    constexpr int SU = 8;
-    const int p_c0 = tid / PRW, p_rem = tid - p_c0 * PRW, p_y0 = p_rem / Wp, p_x0 = p_rem - p_y0 * Wp;
-    const int p_dc = BLK / PRW, p_r2 = BLK - p_dc * PRW, p_dy = p_r2 / Wp, p_dx = p_r2 - p_dy * Wp;
-    // ---- A operand: lane (row i = lane%16, kq = lane/16) needs A[m][4*ks + kq] for
-    // the k-steps ks = wk_id, wk_id + wk, ... of its wave.  Rows beyond M are
-    // clamped (their results are never stored), so only the last, partial
-    // k-step of a chunk needs a predicate.
-    constexpr int KB = 8;
-    int am = m0 + wm_id * 16 + (lane & 15);
-    if (am >= M) am = M - 1;
-    const int dq = 4 * wk, dq_co = dq / kk, dq_tap = dq - dq_co * kk;
-    const gfloat* arow = Aglob + (GM == 2 ? (size_t)am * kk : (size_t)am * Q);
-    const size_t co_stride = (size_t)gC * kk;
+    const int mte = (M - m0 < MT) ? M - m0 : MT;        // rows of the tile that exist
+    const size_t co_stride = (size_t)gC * kk;           // GM 2: floats between the weights of consecutive output channels
+    const int i_row = wm_id * 16 + (lane & 15);
 
     for (int ch = 0; ch < n_chunks; ++ch) {
       const int q0 = ch * QC;
       const int qc_eff = (Q - q0 < QC) ? Q - q0 : QC;       // valid reduction entries in this chunk
-      const int nfull = qc_eff >> 2;                        // k-steps in which all 4 lane groups are valid
-      const int nk = (nfull > wk_id) ? (nfull - wk_id + wk - 1) / wk : 0;   // ... that belong to this wave
-      int qr = 4 * wk_id + kq;
-      int a_co = 0, a_tap = 0;
-      if (GM == 2) { a_co = (q0 + qr) / kk; a_tap = q0 + qr - a_co * kk; }
-      float a0[KB], a1[KB];
-      auto load1 = [&]() -> float {
-        const float v = (GM == 2) ? arow[a_co * co_stride + a_tap] : arow[q0 + qr];
-        qr += dq;
-        if (GM == 2) { a_tap += dq_tap; a_co += dq_co; if (a_tap >= kk) { a_tap -= kk; ++a_co; } }
-        return v;
-      };
-      int issued = 0;                                       // k-steps of this wave whose A load has been issued
-      if (nk >= KB) {
+      const int qc4 = (qc_eff + 3) & ~3;
+      if (ch) __syncthreads();                              // the previous chunk has been contracted
+      if (ch == 1 && !op) PB_TS(12);
+      // ---- requests: offset table (first chunk), A block, then the patch
+      int tv[4];
+      if (ch == 0) {
 #pragma unroll
-        for (int u = 0; u < KB; ++u) a0[u] = load1();
-        issued = KB;
-      } else {
-#pragma unroll
-        for (int u = 0; u < KB; ++u)
-          if (u < nk) a1[u] = load1();
+        for (int u = 0; u < 4; ++u) tv[u] = (tid + u * BLK < QCpad) ? tq[tid + u * BLK] : 0;
       }
-      if (ch) __syncthreads();
+      // A block as a 2-D copy: nseg segments of seg_pad floats, of which the first
+      // seg_len of the first nvalid segments come from memory and the rest is zero
+      int nseg, nvalid, seg_len, seg_pad, lstride;
+      if (GM == 2) {
+        const float ikk = frcp(kk);
+        nseg = UNI(fdiv(qc4 + kk - 1, ikk)); nvalid = UNI(fdiv(qc_eff, ikk)); seg_len = mte * kk; seg_pad = MT * kk; lstride = MT * kk;
+      } else {
+        nseg = MT; nvalid = MT; seg_len = qc_eff; seg_pad = qc4; lstride = LDA;
+      }
+      auto a_src = [&](int r, int c) -> const gfloat* {
+        if (GM == 2) return Aglob + (size_t)(ch * CC + r) * co_stride + (size_t)m0 * kk + c;
+        int rr = m0 + r;
+        if (rr >= M) rr = M - 1;                            // rows beyond M repeat the last one; never stored
+        return Aglob + (size_t)rr * Q + q0 + c;
+      };
+      constexpr int AU = 8;
+      const int av = avec ? 4 : 1;                          // floats per request
+      const int spr = avec ? (seg_pad + 3) >> 2 : seg_pad;  // requests per segment
+      const float ispr = frcp(spr);
+      const int a_slots = nseg * spr;
+      const int a_dr = UNI(fdiv(BLK, ispr)), a_dc = BLK - a_dr * spr;
+      int a_r = fdiv(tid, ispr), a_c = tid - a_r * spr;     // iterator over this thread's requests
+      v4f ra[AU];
+      auto a_issue = [&](int first_slot) {
+        int r = a_r, c = a_c;
+#pragma unroll
+        for (int u = 0; u < AU; ++u) {
+          ra[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+          if (first_slot + u * BLK < a_slots && r < nvalid && c * av < seg_len) {
+            if (avec) ra[u] = *(const gv4*)a_src(r, 4 * c);
+            else ra[u][0] = *a_src(r, c);
+          }
+          c += a_dc; r += a_dr;
+          if (c >= spr) { c -= spr; ++r; }
+        }
+      };
+      auto a_commit = [&](int first_slot) {
+#pragma unroll
+        for (int u = 0; u < AU; ++u) {
+          if (first_slot + u * BLK < a_slots) {
+            if (avec) *(lv4*)(Alds + a_r * lstride + 4 * a_c) = ra[u];
+            else Alds[a_r * lstride + a_c] = ra[u][0];
+          }
+          a_c += a_dc; a_r += a_dr;
+          if (a_c >= spr) { a_c -= spr; ++a_r; }
+        }
+      };
+      a_issue(tid);
+      if (!ch && !op) PB_TS(10);
+      if (ch == 1 && !op) PB_TS(13);
       // ---- patch
       int chan0, row0;
       if (GM == 1) { chan0 = ch * CC; row0 = tile_row0 * gs - gpad; }
       else if (GM == 2) { chan0 = ch * CC; row0 = tile_row0; }
       else { chan0 = c_lo; row0 = ch * rows_c * gs - gpad; }
-      if (vec) {
+      if (vec == 1) {
         // rows of the source map go to LDS with 16-byte copies; the interior of a
         // patch row starts at column 4, columns 0..3 and Wsrc+4..Wsrc+7 are halo
-        typedef __attribute__((address_space(1))) v4f gv4;
-        typedef __attribute__((address_space(3))) v4f lv4;
         const int Wsrc = (GM == 2) ? gOW : gW, Hsrc = (GM == 2) ? gOH : gH, Cred = (GM == 2) ? gK : gC;
         const int W4 = Wsrc >> 2, nrow = CC * PR, nslot = nrow * W4;
         const int rshift = (GM == 2) ? border : 0;
-        constexpr int VU = 4;
-        int r = tid / W4, xs = tid - r * W4;
-        int c = r / PR, y = r - c * PR;
-        const int dr = BLK / W4, dxs = BLK - dr * W4, dc = dr / PR, dy = dr - dc * PR;
+        constexpr int VU = 8;
+        const float iW4 = frcp(W4), iPR = frcp(PR);
+        int r = fdiv(tid, iW4), xs = tid - r * W4;
+        int c = fdiv(r, iPR), y = r - c * PR;
+        const int dr = UNI(fdiv(BLK, iW4)), dxs = BLK - dr * W4, dc = UNI(fdiv(dr, iPR)), dy = dr - dc * PR;
         for (int base = tid; base < nslot; base += BLK * VU) {
           v4f v[VU];
           int dst[VU];
@@ -168,9 +211,51 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
           const int rr = h >> 1;
           *(lv4*)(patch + rr * Wp + ((h & 1) ? Wsrc + 4 : 0)) = (v4f){0.f, 0.f, 0.f, 0.f};
         }
-      } else
-      {
-        int c = p_c0, y = p_y0, x = p_x0;
+      } else if (GM == 2 && vec == 2) {
+        // strided layer: the output gradient sits at stride spacing inside a patch
+        // of zeros.  Request its rows, clear the patch, then scatter them.
+        const float igs = frcp(gs);
+        const int nrow_src = UNI(fdiv(PR + gs - 1, igs)) + 1;   // source rows that can fall into the patch
+        const int oh0 = (row0 - border + gs - 1 >= 0) ? UNI(fdiv(row0 - border + gs - 1, igs)) : 0;
+        const int rowlen = nrow_src * gOW, nslot = CC * rowlen;
+        constexpr int DU = 8;
+        const float irl = frcp(rowlen), iow = frcp(gOW);
+        int c = fdiv(tid, irl), rem = tid - c * rowlen, yr = fdiv(rem, iow), x = rem - yr * gOW;
+        const int dc = UNI(fdiv(BLK, irl)), drem = BLK - dc * rowlen, dyr = UNI(fdiv(drem, iow)), dx = drem - dyr * gOW;
+        float v[DU];
+        int dst[DU];
+        auto d_issue = [&](int first_slot) {
+#pragma unroll
+          for (int u = 0; u < DU; ++u) {
+            dst[u] = -1; v[u] = 0.f;
+            if (first_slot + u * BLK < nslot) {
+              const int chn = chan0 + c, oh = oh0 + yr;
+              const int py = oh * gs + border - row0, px = x * gs + border;
+              if (chn < gK && oh < gOH && py >= 0 && py < PR) {
+                dst[u] = c * PRW + py * Wp + px;
+                v[u] = src[(size_t)chn * P + oh * gOW + x];
+              }
+            }
+            x += dx; yr += dyr; c += dc;
+            if (x >= gOW) { x -= gOW; ++yr; }
+            if (yr >= nrow_src) { yr -= nrow_src; ++c; }
+          }
+        };
+        auto d_commit = [&]() {
+#pragma unroll
+          for (int u = 0; u < DU; ++u)
+            if (dst[u] >= 0) patch[dst[u]] = v[u];
+        };
+        d_issue(tid);
+        for (int i = tid; i < ((patch_elems + 3) >> 2); i += BLK) *(lv4*)(patch + 4 * i) = (v4f){0.f, 0.f, 0.f, 0.f};
+        __syncthreads();                                    // the patch has been cleared
+        d_commit();
+        for (int s0 = tid + DU * BLK; s0 < nslot; s0 += DU * BLK) { d_issue(s0); d_commit(); }
+      } else {
+        constexpr int SU = 8;
+        const float iprw = frcp(PRW), iwp = frcp(Wp);
+        int c = fdiv(tid, iprw), rem = tid - c * PRW, y = fdiv(rem, iwp), x = rem - y * Wp;
+        const int p_dc = UNI(fdiv(BLK, iprw)), p_r2 = BLK - p_dc * PRW, p_dy = UNI(fdiv(p_r2, iwp)), p_dx = p_r2 - p_dy * Wp;
         for (int base = tid; base < patch_elems; base += BLK * SU) {
           float v[SU], sc[SU], sh[SU];
 #pragma unroll
@@ -211,86 +296,104 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
           }
         }
       }
+      if (!ch && !op) PB_TS(3);
+      if (ch == 1 && !op) PB_TS(14);
+      // ---- park the offset table and the A block
+      if (ch == 0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (tid + u * BLK < QCpad) offq[tid + u * BLK] = tv[u];
+        for (int i = tid + 4 * BLK; i < QCpad; i += BLK) offq[i] = tq[i];
+      }
+      a_commit(tid);
+      for (int s0 = tid + AU * BLK; s0 < a_slots; s0 += AU * BLK) { a_issue(s0); a_commit(s0); }
+      if (!ch && !op) PB_TS(4);
+      if (ch == 1 && !op) PB_TS(15);
       __syncthreads();
-      // ---- MFMA loop: lane holds A[i = lane%16][k = lane/16] and B[k = lane/16][j = lane%16]
-      const lint* oqp = offq + 4 * wk_id + kq;
-      int done = 0;
-      while (done + KB <= nk) {
-        // a0 holds the A values of k-steps done..done+KB-1; fetch the next batch first
-        const bool more = issued + KB <= nk;
-        if (more) {
-#pragma unroll
-          for (int u = 0; u < KB; ++u) a1[u] = load1();
-          issued += KB;
-        }
-#pragma unroll
-        for (int u = 0; u < KB; ++u) {
-          const int oq = oqp[(done + u) * dq];
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (j < ni) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0[u], patch[oq + offn[j]], acc[j], 0, 0, 0);
-        }
-        done += KB;
-        if (more) {
-#pragma unroll
-          for (int u = 0; u < KB; ++u) a0[u] = a1[u];
-        }
-      }
-      // remaining full k-steps of this wave (fewer than KB), then the chunk's partial k-step
+      if (!ch && !op) PB_TS(5);
+      if (ch == 1 && !op) PB_TS(16);
+      // ---- MFMA loop: lane holds A[i = lane%16][k = lane/16] and B[k = lane/16][j = lane%16];
+      // the waves of a reduction split take k-steps wk_id, wk_id + wk, ...
       {
-        const int rem = nk - done;
-        if (nk >= KB) {
-#pragma unroll
-          for (int u = 0; u < KB; ++u)
-            if (u < rem) a1[u] = load1();
+        const int nsteps = qc4 >> 2;
+        const int nk = (nsteps > wk_id) ? (nsteps - wk_id + wk - 1) >> lg(wk) : 0;
+        const int dq = 4 * wk;
+        const lint* oqp = offq + 4 * wk_id + kq;
+        const lfloat* ap;
+        int a_tap = 0, dq_co = 0, dq_tap = 0;
+        if (GM == 2) {
+          const float ikk = frcp(kk);
+          const int q = 4 * wk_id + kq, co = fdiv(q, ikk);
+          a_tap = q - co * kk;
+          ap = Alds + co * lstride + i_row * kk + a_tap;
+          dq_co = UNI(fdiv(dq, ikk)); dq_tap = dq - dq_co * kk;
+        } else {
+          ap = Alds + i_row * LDA + 4 * wk_id + kq;
         }
+        const int a_adv = (GM == 2) ? dq_co * lstride + dq_tap : dq;
+        const int a_wrap = (GM == 2) ? lstride - kk : 0;    // extra advance when the tap index wraps into the next channel
+        auto fetch = [&](float& a, int& oq) {
+          a = *ap; oq = *oqp;
+          ap += a_adv; oqp += dq;
+          if (GM == 2) { a_tap += dq_tap; if (a_tap >= kk) { a_tap -= kk; ap += a_wrap; } }
+        };
+        int s = 0;
+        for (; s + 8 <= nk; s += 8) {
+          float a[8];
+          int oq[8];
 #pragma unroll
-        for (int u = 0; u < KB; ++u)
-          if (u < rem) {
-            const int oq = oqp[(done + u) * dq];
+          for (int u = 0; u < 8; ++u) fetch(a[u], oq[u]);
+          float b[8][NI];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-              if (j < ni) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[u], patch[oq + offn[j]], acc[j], 0, 0, 0);
-          }
-      }
-      if ((qc_eff & 3) && (nfull % wk) == wk_id) {
-        const int qt = 4 * nfull + kq;
-        float av = 0.f;
-        if (qt < qc_eff) {
-          if (GM == 2) { const int co = (q0 + qt) / kk; av = arow[co * co_stride + (q0 + qt - co * kk)]; }
-          else av = arow[q0 + qt];
+          for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) b[u][j] = patch[oq[u] + offn[j]];
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+              if (DUAL && (u & 1)) acc2[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u], b[u][j], acc2[j], 0, 0, 0);
+              else acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u], b[u][j], acc[j], 0, 0, 0);
+            }
         }
-        const int oq = offq[qt];
+        for (; s < nk; ++s) {
+          float a;
+          int oq;
+          fetch(a, oq);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          if (j < ni) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, patch[oq + offn[j]], acc[j], 0, 0, 0);
+          for (int j = 0; j < NI; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, patch[oq + offn[j]], acc[j], 0, 0, 0);
+        }
       }
+      if (!ch && !op) PB_TS(6);
+      if (ch == 1 && !op) PB_TS(17);
     }
   }
 
+  if (DUAL) {
+#pragma unroll
+    for (int j = 0; j < NI; ++j) acc[j] += acc2[j];
+  }
+  PB_TS(7);
   // ---- reduce the split of the reduction across waves (fixed order)
   if (wk > 1) {
     __syncthreads();
     lfloat* red = smem;   // [wave][j][lane] float4
     if (wk_id > 0) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (j < ni) {
-          lfloat* r = red + ((wv * 4 + j) * 64 + lane) * 4;
-          r[0] = acc[j][0]; r[1] = acc[j][1]; r[2] = acc[j][2]; r[3] = acc[j][3];
-        }
+      for (int j = 0; j < NI; ++j) *(lv4*)(red + ((wv * 4 + j) * 64 + lane) * 4) = acc[j];
     }
     __syncthreads();
     if (wk_id == 0) {
       for (int w2 = 1; w2 < wk; ++w2)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          if (j < ni) {
-            const lfloat* r = red + (((wv + w2) * 4 + j) * 64 + lane) * 4;
-            acc[j][0] += r[0]; acc[j][1] += r[1]; acc[j][2] += r[2]; acc[j][3] += r[3];
-          }
+        for (int j = 0; j < NI; ++j) {
+          const v4f r = *(const lv4*)(red + (((wv + w2) * 4 + j) * 64 + lane) * 4);
+          acc[j][0] += r[0]; acc[j][1] += r[1]; acc[j][2] += r[2]; acc[j][3] += r[3];
+        }
     }
   }
+  PB_TS(8);
   if (wk_id != 0) return;
   // ---- epilogue: lane holds C[i = 4*(lane/16) + r][j = lane%16]
   const int M = UNI(d.g.M), N = UNI(d.g.N);
@@ -299,9 +402,9 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
   const bool extras = (GM == 1 && (flags & (F_BIAS | F_SKIP))) || (GM == 2 && (flags & (F_MASK_X | F_ADD_SKG)));
   if (!extras) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NI; ++j) {
       const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
-      if (j < ni && n < N) {
+      if (n < N) {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
           if (mrow + r < M) out[(size_t)(mrow + r) * N + n] = acc[j][r];
@@ -314,9 +417,9 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
   const gfloat* skg = (GM == 2 && (flags & F_ADD_SKG)) ? (const gfloat*)at(d.skg, t) : nullptr;
   const gfloat* bias = (GM == 1 && (flags & F_BIAS)) ? GP(d.b) : nullptr;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < NI; ++j) {
     const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
-    if (j >= ni || n >= N) continue;
+    if (n >= N) continue;
     float add[4], msk[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -340,10 +443,22 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
 }
 
 __device__ __forceinline__ void step_gemm(const LDesc& d, int tile, int t, lfloat* smem) {
-  const int gm = UNI(d.g.gm);
-  if (gm == 1) step_gemm_t<1>(d, tile, t, smem);
-  else if (gm == 2) step_gemm_t<2>(d, tile, t, smem);
-  else step_gemm_t<3>(d, tile, t, smem);
+  // the number of column subtiles per wave (1, 2 or 4) is a compile-time
+  // constant so that the accumulators stay in fixed registers
+  const int gm = UNI(d.g.gm), ni = UNI(d.g.ni);
+  if (gm == 1) {
+    if (ni == 1) step_gemm_t<1, 1>(d, tile, t, smem);
+    else if (ni == 2) step_gemm_t<1, 2>(d, tile, t, smem);
+    else step_gemm_t<1, 4>(d, tile, t, smem);
+  } else if (gm == 2) {
+    if (ni == 1) step_gemm_t<2, 1>(d, tile, t, smem);
+    else if (ni == 2) step_gemm_t<2, 2>(d, tile, t, smem);
+    else step_gemm_t<2, 4>(d, tile, t, smem);
+  } else {
+    if (ni == 1) step_gemm_t<3, 1>(d, tile, t, smem);
+    else if (ni == 2) step_gemm_t<3, 2>(d, tile, t, smem);
+    else step_gemm_t<3, 4>(d, tile, t, smem);
+  }
 }
 
 // db[co] = sum_p dZ[co,p], one wavefront per channel.

@@ -360,7 +360,8 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
     else { g.wn = std::min(rest, pow2_floor(n16)); g.wk = rest / g.wn; }
     g.ni = std::min(4, cdiv(n16, g.wn));
     auto tiles = [&]() { return cdiv(g.M, 16 * g.wm) * cdiv(g.N, 16 * g.ni * g.wn); };
-    while (tiles() < target && g.ni > 1) g.ni = (g.ni + 1) / 2;
+    if (g.ni == 3) g.ni = 4;   // the kernels are instantiated for 1, 2 and 4 subtiles
+    while (tiles() < target && g.ni > 1) g.ni /= 2;
     while (tiles() < target && g.wm > 1 && g.Q >= 64 * g.wk * 2) { g.wm /= 2; g.wk *= 2; }
     while (tiles() < target && g.wn > 1 && g.Q >= 64 * g.wk * 2) { g.wn /= 2; g.wk *= 2; }
   }
@@ -375,10 +376,17 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
     if (mode == 2) g.vec = (s == 1 && OW % 4 == 0) ? 1 : 0;
     else g.vec = (W % 4 == 0) ? 1 : 0;
   }
-  g.xoff = g.vec ? 4 - hl : 0;
+  if (mode == 2 && s > 1) g.vec = 2;
+  g.xoff = g.vec == 1 ? 4 - hl : 0;
+  // LDS per chunk: offset table, A block, patch
+  auto a_size = [&](int QC) -> int64_t {
+    const int QCpad = (QC + 15) / 16 * 16;
+    if (mode == 2) return (int64_t)((QCpad + kk - 1) / kk + 1) * g.MT * kk;
+    return (int64_t)g.MT * (QCpad + 4);
+  };
   auto fits = [&](int QC, int CC, int PR, int Wp) {
-    const int QCpad = (QC + 3) / 4 * 4;
-    const int64_t need = QCpad + (int64_t)CC * PR * Wp + 64;
+    const int QCpad = (QC + 15) / 16 * 16;
+    const int64_t need = QCpad + a_size(QC) + ((int64_t)CC * PR * Wp + 3) / 4 * 4 + 16;
     return need <= LDS_FLOATS;
   };
   if (mode == 1 || mode == 2) {
@@ -386,10 +394,11 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
     const int rows_max = std::min(nrows, (g.NT + rowlen - 2) / rowlen + 1);
     g.PR = mode == 1 ? (rows_max - 1) * s + k : rows_max + k - 1;
     g.Wp = mode == 1 ? W + 2 * pad : W + k - 1;
-    if (g.vec) g.Wp = (mode == 1 ? W : OW) + 8;
+    if (g.vec == 1) g.Wp = (mode == 1 ? W : OW) + 8;
     const int nch = mode == 1 ? C : K;
     int CC = nch;
     while (CC > 1 && !fits(CC * kk, CC, g.PR, g.Wp)) CC = (CC + 1) / 2;
+    if (CC > 4) CC = CC / 4 * 4;   // keeps the chunks of a row 16-byte aligned
     if (!fits(CC * kk, CC, g.PR, g.Wp)) return false;
     g.CC = CC; g.QC = CC * kk; g.n_chunks = cdiv(nch, CC); g.rows_c = 0;
   } else {
@@ -412,14 +421,18 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
     if (!rows) return false;
     g.rows_c = rows; g.QC = rows * OW; g.PR = pr(rows); g.n_chunks = cdiv(OH, rows);
   }
-  g.QCpad = (g.QC + 3) / 4 * 4;
-  g.LDA = 0;
+  g.QCpad = (g.QC + 15) / 16 * 16;
+  // 16-byte fetches of the A block: every segment starts on a 16-byte boundary and
+  // has a length that is a multiple of 4 (the caller withdraws this if the operand's
+  // address does not allow it).  Forward / backward weights: segments are rows of the
+  // reduction range; backward data: the MT x k x k weights of one output channel.
+  if (mode == 2) g.avec = (C % 4 == 0) ? 1 : 0;
+  else g.avec = (g.Q % 4 == 0 && (g.n_chunks == 1 || g.QC % 4 == 0)) ? 1 : 0;
+  g.LDA = (mode == 2) ? g.MT * kk : g.QCpad + 4;   // QCpad + 4 = 4 * odd: the 16 rows of a wave fall into different banks
   g.o_offq = 0;
-  g.o_patch = (g.o_offq + g.QCpad + 3) / 4 * 4;
-  if (g.o_patch + g.CC * g.PR * g.Wp > LDS_FLOATS) return false;
-  auto lg_ceil = [](int x) { int l = 0; while ((1 << l) < x && l < 8) ++l; return l; };
-  g.lgA = lg_ceil(mode == 2 ? g.MT * kk : g.QCpad);
-  g.lgP = lg_ceil(g.Wp);
+  g.o_A = g.QCpad;
+  g.o_patch = (int)(g.o_A + a_size(g.QC));
+  if (g.o_patch % 4 || g.o_patch + (g.CC * g.PR * g.Wp + 3) / 4 * 4 > LDS_FLOATS) return false;
   *out = g;
   return true;
 }
@@ -449,6 +462,23 @@ void gemm_tables(pb_ctx* c, const GemmCfg& g, int C, int H, int W, int K, int OH
   c->tables.push_back({oq, std::move(q)});
   c->tables.push_back({on, std::move(n)});
   (void)C; (void)H; (void)K; (void)OH;
+}
+
+// Whether the A operand of a GEMM step (of its projection operand set if
+// `second`) starts on a 16-byte boundary in every ring slot.
+bool a_aligned(const pb_ctx* c, const StepDesc& d, bool second) {
+  const float* p = second ? d.wp : (d.g.gm == 3 ? d.dy.base : d.w);
+  if (!p || (p - c->f(0)) % 4) return false;
+  return second || d.g.gm != 3 || d.dy.stride % 4 == 0;
+}
+
+// Limits of the fused last stage (one workgroup; see step_head): sizes of its
+// register and LDS arrays.
+constexpr int HEAD_MAX_IN = 8192, HEAD_MAX_CV = 512, HEAD_MAX_K = 16;
+bool head_fits(int C, int HW, int K, bool gap, int G) {
+  const int64_t n_in = (int64_t)C * HW, cv = gap ? C : n_in;
+  if (n_in > HEAD_MAX_IN || cv > HEAD_MAX_CV || K > HEAD_MAX_K || C > 2 * BLK || G > BLK || G < 1 || C % G) return false;
+  return (n_in + 3) / 4 * 4 + 2 * HEAD_MAX_CV + 2 * HEAD_MAX_K + 9 * (int64_t)C + 2 * G <= LDS_FLOATS;
 }
 
 // Compile the network into the step table.  Every step carries the phase it
@@ -490,10 +520,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       ph = 1;
     }
     // a small last stage runs as one workgroup: forward, loss and backward
-    const int head_cv = a.gap ? a.Cin : a.in_elems();
     const bool fused_head = a.ce && c->kernel_set == 0 && !a.post_gn && !a.add && !a.is_conv && (a.gap ? a.pre_gn : !a.pre_gn) &&
-                            (int64_t)a.K * head_cv <= 65536 && a.in_elems() <= 32768 &&
-                            2 * head_cv + a.K + 6 * a.Cin + 64 <= LDS_FLOATS && s > 0;
+                            head_fits(a.Cin, a.Hin * a.Win, a.K, a.gap, a.pre_gn ? a.G : 1) && s > 0;
     if (fused_head) {
       StepDesc d = blank(K_HEAD, s, t_f);
       d.C = a.Cin; d.H = a.Hin; d.W = a.Win; d.K = a.K; d.G = a.pre_gn ? a.G : 1;
@@ -748,6 +776,13 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       }
     }
   }
+  // 16-byte loads of the A operand need a 16-byte aligned operand (the arena is)
+  for (auto& pr : out) {
+    StepDesc& d = pr.second;
+    if (d.kind != K_GEMM) continue;
+    if (d.g.avec && !a_aligned(c, d, false)) d.g.avec = 0;
+    if (d.gp.gm && d.gp.avec && !a_aligned(c, d, true)) d.gp.avec = 0;
+  }
   // ---- fused update: one step per stage, in the first phase in which no step
   // reads parameters or writes gradients any more
   int last_param_phase = 0;
@@ -770,6 +805,26 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     d.ntiles = (int)(a.padded / UPD_CHUNK);
     out.push_back({last_param_phase + 1, d});
   }
+}
+
+// Launch order: by phase; inside a phase the steps are independent of each
+// other, and as its longest workgroups bound the phase they go first in the grid.
+void order_steps(std::vector<std::pair<int, StepDesc>>& tagged) {
+  auto step_cost = [](const StepDesc& d) -> int64_t {
+    if (d.kind == K_HEAD) return (int64_t)1 << 40;
+    if (d.kind == K_GEMM) {
+      const GemmCfg& g = d.g;
+      return ((int64_t)1 << 20) + (int64_t)g.Q * g.ni / g.wk + ((int64_t)g.MT * g.Q + (int64_t)g.n_chunks * g.CC * g.PR * g.Wp) / 64;
+    }
+    if (d.kind == K_GN_STATS) return (int64_t)d.C / std::max(1, d.G) * d.H * d.W / 64 + 1000;
+    if (d.kind == K_GNB_REDUCE) return (int64_t)d.H * d.W / 64 + 500;
+    return 0;
+  };
+  std::stable_sort(tagged.begin(), tagged.end(),
+                   [&](const std::pair<int, StepDesc>& x, const std::pair<int, StepDesc>& y) {
+                     if (x.first != y.first) return x.first < y.first;
+                     return step_cost(x.second) > step_cost(y.second);
+                   });
 }
 
 // Host-side audit of the step table: every tensor reference a kernel will
@@ -850,7 +905,7 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
         break;
       case K_HEAD: {
         const int64_t cv = (d.flags & F_DU_GAP) ? d.C : in;
-        ok = ok && d.ntiles == 1 && d.K > 0 && 2 * cv + d.K + 6 * d.C + 64 <= LDS_FLOATS && ref_ok(d.x, in) &&
+        ok = ok && d.ntiles == 1 && d.K > 0 && d.G > 0 && head_fits(d.C, d.H * d.W, d.K, (d.flags & F_DU_GAP) != 0, d.G) && ref_ok(d.x, in) &&
              ptr_ok(d.w, d.K * cv) && ptr_ok(d.wp, d.K * cv) && ptr_ok(d.gw, d.K * cv) && ptr_ok(d.loss_log, d.loss_cap) &&
              ptr_ok((const float*)d.labels, d.n_stages) && (!(d.flags & F_BIAS) || (ptr_ok(d.b, d.K) && ptr_ok(d.gb, d.K))) &&
              (!d.dx.base || ref_ok(d.dx, in)) && d.G > 0 && d.C % d.G == 0;
@@ -867,13 +922,23 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
       case K_GEMM: {
         auto cfg_ok = [&](const GemmCfg& g, int C, int H, int W, int k, int s, int pad) {
           const int kk = k * k;
-          bool o = g.wm * g.wn * g.wk == 4 && g.ni >= 1 && g.ni <= 4 && g.MT == 16 * g.wm && g.NT == 16 * g.ni * g.wn &&
-                   g.tiles_n == cdiv(g.N, g.NT) && g.tiles == cdiv(g.M, g.MT) * g.tiles_n && g.QCpad % 4 == 0 &&
-                   g.QCpad >= g.QC && g.o_offq >= 0 && g.o_patch >= g.o_offq + g.QCpad &&
-                   (int64_t)g.o_patch + (int64_t)g.CC * g.PR * g.Wp <= LDS_FLOATS && LDS_FLOATS >= 4096 &&
-                   (int64_t)g.n_chunks * g.QC >= g.Q && g.lgA >= 0 && g.lgA <= 8 && g.lgP >= 0 && g.lgP <= 8;
+          bool o = g.wm * g.wn * g.wk == 4 && (g.ni == 1 || g.ni == 2 || g.ni == 4) && g.MT == 16 * g.wm && g.NT == 16 * g.ni * g.wn &&
+                   g.tiles_n == cdiv(g.N, g.NT) && g.tiles == cdiv(g.M, g.MT) * g.tiles_n && g.QCpad % 16 == 0 &&
+                   g.QCpad >= g.QC && g.o_offq >= 0 && g.o_A >= g.o_offq + g.QCpad && g.o_A % 4 == 0 && g.o_patch % 4 == 0 &&
+                   (int64_t)g.o_patch + ((int64_t)g.CC * g.PR * g.Wp + 3) / 4 * 4 <= LDS_FLOATS && LDS_FLOATS >= 4096 &&
+                   (int64_t)g.n_chunks * g.QC >= g.Q;
+          // the A block: MT rows of LDA floats, or (backward data) one MT*k*k segment per channel of the
+          // chunk plus the zero segments the last k-step can reach
+          if (g.gm == 2)
+            o = o && g.LDA == g.MT * kk && (int64_t)g.o_A + (int64_t)((g.QCpad + kk - 1) / kk + 1) * g.MT * kk <= g.o_patch &&
+                (!g.avec || C % 4 == 0);
+          else
+            o = o && g.LDA >= g.QCpad + 4 && g.LDA % 4 == 0 && (int64_t)g.o_A + (int64_t)g.MT * g.LDA <= g.o_patch &&
+                (!g.avec || (g.Q % 4 == 0 && (g.n_chunks == 1 || g.QC % 4 == 0)));
           const int hl_ = (g.gm == 2) ? k - 1 - pad : pad;
-          if (g.vec) {
+          if (g.vec == 2) {
+            o = o && g.gm == 2 && s > 1 && g.xoff == 0;
+          } else if (g.vec) {
             const int wsrc = (g.gm == 2) ? d.OW : W;
             o = o && wsrc % 4 == 0 && g.Wp == wsrc + 8 && g.xoff == 4 - hl_ && hl_ <= 4 && (g.gm != 2 || s == 1) &&
                 (g.o_patch % 4) == 0 && !(d.flags & (F_PRE_AFFINE | F_PRE_RELU) && g.gm != 2);
@@ -897,6 +962,7 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
           }
           return o;
         };
+        ok = ok && (!d.g.avec || a_aligned(c, d, false)) && (!(d.flags & F_PROJ) || !d.gp.avec || a_aligned(c, d, true));
         ok = ok && d.ntiles == d.g.tiles && cfg_ok(d.g, d.C, d.H, d.W, d.k, d.stride, d.pad) &&
              ptr_ok((const float*)d.tq, d.g.QCpad) && ptr_ok((const float*)d.tn, d.g.N) &&
              (!(d.flags & F_PROJ) || d.g.gm != 1 || (ptr_ok((const float*)d.tq2, d.gp.QCpad) && ptr_ok((const float*)d.tn2, d.gp.N)));
@@ -1069,6 +1135,7 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   std::vector<std::pair<int, StepDesc>> steps;
   tmp.plan = &pl;
   compile_steps(&tmp, steps);
+  order_steps(steps);
   static const char* names[] = {"gn_stats", "gap_fwd", "conv_fwd", "post_fwd", "ce", "gnb_reduce", "gnb_apply",
                                 "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad", "ingest", "update", "head"};
   std::string o;
@@ -1146,8 +1213,7 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   c->plan = &pl;
   compile_steps(c, tagged);
   if (validate_steps(c, tagged, pl.total) != PB_OK) { pb_destroy(c); return PB_E_INVALID; }
-  std::stable_sort(tagged.begin(), tagged.end(),
-                   [](const std::pair<int, StepDesc>& x, const std::pair<int, StepDesc>& y) { return x.first < y.first; });
+  order_steps(tagged);
   const int n_steps = (int)tagged.size();
   c->steps.resize(n_steps);
   int n_ph = 0;

@@ -28,6 +28,20 @@ typedef __attribute__((address_space(3))) StepDesc LDesc;
 typedef __attribute__((address_space(3))) TRef LTRef;
 typedef __attribute__((address_space(3))) GemmCfg LGemmCfg;
 #define UNI(x) __builtin_amdgcn_readfirstlane(x)   /* value is the same in every lane: keep it scalar */
+#ifdef PB_TIMING
+__shared__ long long ts_sh[4][24];
+__device__ long long pb_ts_out[16384 * 100];
+__device__ int pb_ts_n;
+__device__ int pb_ts_tick;
+#define PB_TS(i) do { if ((threadIdx.x & 63) == 0) ts_sh[threadIdx.x >> 6][i] = (long long)__builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define PB_TS(i)
+#endif
+
+// floor(n / d) for 0 <= n < 2^21, d >= 1, with inv = rcp(d): a few instructions
+// instead of the long expansion of an integer division
+__device__ __forceinline__ float frcp(int d) { return __builtin_amdgcn_rcpf((float)d); }
+__device__ __forceinline__ int fdiv(int n, float inv) { return (int)(((float)n + 0.5f) * inv); }
 
 __device__ __forceinline__ gfloat* at(const LTRef& r, int t) {
   const int depth = UNI(r.depth), stride = UNI(r.stride), lag = UNI(r.lag);
@@ -453,38 +467,126 @@ __device__ void step_update(const LDesc& d, int tile) {
   }
 }
 
+// Sum over the wavefront, same value returned to every lane.
+__device__ __forceinline__ float wave_sum_all(float v) {
+  return __shfl(wave_sum(v), 0, 64);
+}
+
+// Limits of the fused last stage (checked on the host): its input, the vector
+// the linear layer sees and the logits live in LDS / registers of one workgroup.
+constexpr int HEAD_MAX_IN = 8192;   // C*H*W
+constexpr int HEAD_MAX_CV = 512;    // inputs of the linear layer
+constexpr int HEAD_MAX_K = 16;      // classes
+
 // The whole last stage in one workgroup: [GroupNorm, ReLU, global average
 // pool |  ReLU | nothing] -> linear -> softmax cross-entropy -> backward of all
 // of it.  Forward parameters: d.w / d.b / d.gamma / d.beta point into the
 // predicted arena; the backward ones (current weights) are d.wp (weight) and
-// d.skip.base (GroupNorm scale).  LDS: vec[Cv] | dvec[Cv] | logit[K] | chan[4C].
+// d.skip.base (GroupNorm scale).
+//
+// A single workgroup cannot hide memory latency behind other work, so every
+// global read of the step is requested in one burst at the start (the input
+// goes to LDS, the weights stay in registers) and everything after that runs
+// out of LDS and registers.
+// LDS: xs[C*H*W] | vec[512] | dvec[512] | logit[16] | bias[16] | chan[9*C] | grp[2*G]
 __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int C = d.C, HW = d.H * d.W, K = d.K, G = d.G;
-  const bool gn = d.flags & F_PRE_AFFINE, rl = d.flags & F_PRE_RELU, gap = d.flags & F_DU_GAP;
-  const int Cv = gap ? C : C * HW;                 // length of the vector the linear layer sees
-  lfloat* vec = smem;
-  lfloat* dvec = smem + Cv;
-  lfloat* logit = dvec + Cv;
-  lfloat* chan = logit + K;                        // sc[C], sh[C], mean[C], rstd[C], then 2C partial sums
+  (void)red;
+  const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);
+  const int C = UNI(d.C), HW = UNI(d.H) * UNI(d.W), K = UNI(d.K), G = UNI(d.G), flags = UNI(d.flags);
+  const bool gn = flags & F_PRE_AFFINE, rl = flags & F_PRE_RELU, gap = flags & F_DU_GAP, has_b = flags & F_BIAS;
+  const int n_in = C * HW;
+  const int Cv = gap ? C : n_in;                   // length of the vector the linear layer sees
+  lfloat* xs = smem;
+  lfloat* vec = xs + ((n_in + 3) & ~3);
+  lfloat* dvec = vec + HEAD_MAX_CV;
+  lfloat* logit = dvec + HEAD_MAX_CV;
+  lfloat* bias = logit + HEAD_MAX_K;
+  lfloat* chan = bias + HEAD_MAX_K;                // sc, sh, mean, rstd, gamma_f, beta_f, gamma_b, S1 part, S2 part
+  lfloat* grp = chan + 9 * C;                      // S1[G], S2[G]
   const gfloat* x = at(d.x, t);
+  // ---- all global reads
+  constexpr int XU = HEAD_MAX_IN / (4 * BLK);
+  v4f xr[XU];
+  const bool x4 = (n_in & 3) == 0;
+#pragma unroll
+  for (int u = 0; u < XU; ++u) {
+    xr[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+    if (x4) {
+      const int i = (tid + u * BLK) * 4;
+      if (i < n_in) xr[u] = *(const gv4*)(x + i);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = tid + (4 * u + e) * BLK;
+        if (i < n_in) xr[u][e] = x[i];
+      }
+    }
+  }
+  constexpr int KU = HEAD_MAX_K / 4, IU = HEAD_MAX_CV / 64, JU = HEAD_MAX_CV / BLK;
+  float wf[KU][IU];      // forward weights: wave wv holds rows wv, wv + 4, ...
+#pragma unroll
+  for (int ku = 0; ku < KU; ++ku)
+#pragma unroll
+    for (int iu = 0; iu < IU; ++iu) {
+      const int k = wv + 4 * ku, i = lane + 64 * iu;
+      wf[ku][iu] = (k < K && i < Cv) ? GP(d.w)[(size_t)k * Cv + i] : 0.f;
+    }
+  float wb[JU][HEAD_MAX_K];   // backward (current) weights: thread holds columns tid, tid + 256
+#pragma unroll
+  for (int ju = 0; ju < JU; ++ju)
+#pragma unroll
+    for (int k = 0; k < HEAD_MAX_K; ++k) {
+      const int i = tid + ju * BLK;
+      wb[ju][k] = (k < K && i < Cv) ? GP(d.wp)[(size_t)k * Cv + i] : 0.f;
+    }
+  float pg[JU][3];
+#pragma unroll
+  for (int ju = 0; ju < JU; ++ju) {
+    const int c = tid + ju * BLK;
+    pg[ju][0] = pg[ju][1] = pg[ju][2] = 0.f;
+    if (gn && c < C) { pg[ju][0] = GP(d.gamma)[c]; pg[ju][1] = GP(d.beta)[c]; pg[ju][2] = ((const gfloat*)d.skip.base)[c]; }
+  }
+  const float bz = (has_b && tid < K) ? GP(d.b)[tid] : 0.f;
+  const int sample = t - (UNI(d.n_stages) - 1);
+  const int label = ((const gint*)d.labels)[sample % UNI(d.n_stages)];
+  // ---- park them
+#pragma unroll
+  for (int u = 0; u < XU; ++u) {
+    if (x4) {
+      const int i = (tid + u * BLK) * 4;
+      if (i < n_in) *(lv4*)(xs + i) = xr[u];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = tid + (4 * u + e) * BLK;
+        if (i < n_in) xs[i] = xr[u][e];
+      }
+    }
+  }
+#pragma unroll
+  for (int ju = 0; ju < JU; ++ju) {
+    const int c = tid + ju * BLK;
+    if (gn && c < C) { chan[4 * C + c] = pg[ju][0]; chan[5 * C + c] = pg[ju][1]; chan[6 * C + c] = pg[ju][2]; }
+  }
+  if (tid < K) bias[tid] = bz;
+  __syncthreads();
   // ---- forward
+  const int cpg = gn ? C / G : 1, n = cpg * HW;
   if (gn) {
-    const int cpg = C / G, n = cpg * HW;
-    for (int g = 0; g < G; ++g) {
-      const gfloat* xp = x + (size_t)g * n;
-      float s = 0.f;
-      for (int i = tid; i < n; i += BLK) s += xp[i];
-      const float mean = block_sum(s, red) / (float)n;
+    for (int g = wv; g < G; g += BLK / 64) {          // one wavefront per group
+      const lfloat* xp = xs + g * n;
+      float sm = 0.f;
+      for (int i = lane; i < n; i += 64) sm += xp[i];
+      const float mean = wave_sum_all(sm) / (float)n;
       float q = 0.f;
-      for (int i = tid; i < n; i += BLK) { const float dl = xp[i] - mean; q = fmaf(dl, dl, q); }
-      const float var = block_sum(q, red) / (float)n;
+      for (int i = lane; i < n; i += 64) { const float dl = xp[i] - mean; q = fmaf(dl, dl, q); }
+      const float var = wave_sum_all(q) / (float)n;
       const float rstd = 1.0f / sqrtf(var + GN_EPS);
-      for (int c = tid; c < cpg; c += BLK) {
+      for (int c = lane; c < cpg; c += 64) {
         const int ch = g * cpg + c;
-        const float sc = GP(d.gamma)[ch] * rstd;
+        const float sc = chan[4 * C + ch] * rstd;
         chan[ch] = sc;
-        chan[C + ch] = fmaf(-mean, sc, GP(d.beta)[ch]);
+        chan[C + ch] = fmaf(-mean, sc, chan[5 * C + ch]);
         chan[2 * C + ch] = mean;
         chan[3 * C + ch] = rstd;
       }
@@ -494,66 +596,82 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
   if (gap) {
     for (int c = wv; c < C; c += BLK / 64) {
       const float sc = gn ? chan[c] : 1.f, sh = gn ? chan[C + c] : 0.f;
-      float s = 0.f;
+      float sm = 0.f;
       for (int i = lane; i < HW; i += 64) {
-        float v = fmaf(sc, x[(size_t)c * HW + i], sh);
+        float v = fmaf(sc, xs[c * HW + i], sh);
         if (rl) v = fmaxf(v, 0.f);
-        s += v;
+        sm += v;
       }
-      s = wave_sum(s);
-      if (lane == 0) vec[c] = s / (float)HW;
+      sm = wave_sum(sm);
+      if (lane == 0) vec[c] = sm / (float)HW;
     }
   } else {
-    for (int i = tid; i < Cv; i += BLK) { const float v = x[i]; vec[i] = rl ? fmaxf(v, 0.f) : v; }
+    for (int i = tid; i < Cv; i += BLK) { const float v = xs[i]; vec[i] = rl ? fmaxf(v, 0.f) : v; }
   }
   __syncthreads();
-  for (int kk = wv; kk < K; kk += BLK / 64) {
-    const gfloat* wr = GP(d.w) + (size_t)kk * Cv;
-    float s = 0.f;
-    for (int i = lane; i < Cv; i += 64) s = fmaf(wr[i], vec[i], s);
-    s = wave_sum(s);
-    if (lane == 0) logit[kk] = s + ((d.flags & F_BIAS) ? GP(d.b)[kk] : 0.f);
+#pragma unroll
+  for (int ku = 0; ku < KU; ++ku) {
+    const int k = wv + 4 * ku;
+    if (k < K) {
+      float sm = 0.f;
+#pragma unroll
+      for (int iu = 0; iu < IU; ++iu) {
+        const int i = lane + 64 * iu;
+        if (i < Cv) sm = fmaf(wf[ku][iu], vec[i], sm);
+      }
+      sm = wave_sum(sm);
+      if (lane == 0) logit[k] = sm + bias[k];
+    }
   }
   __syncthreads();
-  // ---- loss and dlogits (kept in logit[])
+  // ---- loss and dlogits: K is small, every thread computes them
+  float dl[HEAD_MAX_K];
   {
-    const int sample = t - (d.n_stages - 1);
-    const int label = ((const gint*)d.labels)[sample % d.n_stages];
     float mx = -3.0e38f;
-    for (int i = tid; i < K; i += BLK) mx = fmaxf(mx, logit[i]);
-    mx = block_max(mx, red);
-    float s = 0.f;
-    for (int i = tid; i < K; i += BLK) s += expf(logit[i] - mx);
-    s = block_sum(s, red);
-    const float zl = logit[label];
-    __syncthreads();
-    for (int i = tid; i < K; i += BLK) logit[i] = expf(logit[i] - mx) / s - (i == label ? 1.f : 0.f);
-    if (tid == 0) GP(d.loss_log)[sample % d.loss_cap] = logf(s) + mx - zl;
+#pragma unroll
+    for (int k = 0; k < HEAD_MAX_K; ++k) { dl[k] = (k < K) ? logit[k] : -3.0e38f; mx = fmaxf(mx, dl[k]); }
+    float sm = 0.f;
+#pragma unroll
+    for (int k = 0; k < HEAD_MAX_K; ++k) { dl[k] = (k < K) ? expf(dl[k] - mx) : 0.f; sm += dl[k]; }
+    if (tid == 0) GP(d.loss_log)[sample % UNI(d.loss_cap)] = logf(sm) + mx - logit[label];
+#pragma unroll
+    for (int k = 0; k < HEAD_MAX_K; ++k) dl[k] = dl[k] / sm - (k == label ? 1.f : 0.f);
   }
-  __syncthreads();
   // ---- backward of the linear layer: dW = dl (x) vec, db = dl, dvec = W_cur^T dl
-  for (int e = tid; e < K * Cv; e += BLK) { const int kk = e / Cv; GP(d.gw)[e] = logit[kk] * vec[e - kk * Cv]; }
-  if (d.flags & F_BIAS) for (int i = tid; i < K; i += BLK) GP(d.gb)[i] = logit[i];
-  for (int i = tid; i < Cv; i += BLK) {
-    float s = 0.f;
-    for (int kk = 0; kk < K; ++kk) s = fmaf(GP(d.wp)[(size_t)kk * Cv + i], logit[kk], s);
-    dvec[i] = s;
+#pragma unroll
+  for (int ju = 0; ju < JU; ++ju) {
+    const int i = tid + ju * BLK;
+    if (i < Cv) {
+      const float vi = vec[i];
+      float sm = 0.f;
+#pragma unroll
+      for (int k = 0; k < HEAD_MAX_K; ++k)
+        if (k < K) {
+          GP(d.gw)[(size_t)k * Cv + i] = dl[k] * vi;
+          sm = fmaf(wb[ju][k], dl[k], sm);
+        }
+      dvec[i] = sm;
+    }
   }
-  __syncthreads();
+  if (has_b) {
+#pragma unroll
+    for (int k = 0; k < HEAD_MAX_K; ++k)
+      if (k < K && tid == k) GP(d.gb)[k] = dl[k];
+  }
   if (d.dx.base == nullptr && !gn) return;
   gfloat* dx = d.dx.base ? at(d.dx, t) : nullptr;
   if (!gn) {
-    for (int i = tid; i < Cv; i += BLK) { float r = dvec[i]; if (rl && !(x[i] > 0.f)) r = 0.f; dx[i] = r; }
+    // dvec[i] was written by this thread
+    for (int i = tid; i < Cv; i += BLK) { float r = dvec[i]; if (rl && !(xs[i] > 0.f)) r = 0.f; dx[i] = r; }
     return;
   }
+  __syncthreads();
   // ---- GroupNorm backward with du[c,hw] = dvec[c]/HW (after the pool) or dvec[c*HW+hw]
-  const gfloat* gam_b = (const gfloat*)d.skip.base;     // current GroupNorm scale
-  lfloat* part = chan + 4 * C;                          // S1_c, S2_c
   for (int c = wv; c < C; c += BLK / 64) {
     const float sc = chan[c], sh = chan[C + c], mean = chan[2 * C + c], rstd = chan[3 * C + c];
     float sg = 0.f, sb = 0.f;
     for (int i = lane; i < HW; i += 64) {
-      const float xv = x[(size_t)c * HW + i];
+      const float xv = xs[c * HW + i];
       float du = gap ? dvec[c] / (float)HW : dvec[c * HW + i];
       if (rl && !(fmaf(sc, xv, sh) > 0.f)) du = 0.f;
       sg = fmaf(du, (xv - mean) * rstd, sg);
@@ -562,24 +680,28 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
     sg = wave_sum(sg); sb = wave_sum(sb);
     if (lane == 0) {
       GP(d.ggamma)[c] = sg; GP(d.gbeta)[c] = sb;
-      const float gm = gam_b[c];
-      part[c] = gm * sb; part[C + c] = gm * sg;
+      const float gm = chan[6 * C + c];
+      chan[7 * C + c] = gm * sb; chan[8 * C + c] = gm * sg;
     }
   }
   __syncthreads();
   if (!dx) return;
-  const int cpg = C / G, n = cpg * HW;
-  const float inv_n = 1.0f / (float)n;
-  for (int o = tid; o < C * HW; o += BLK) {
-    const int c = o / HW, g = c / cpg;
+  if (tid < G) {
     float S1 = 0.f, S2 = 0.f;
-    for (int j = 0; j < cpg; ++j) { S1 += part[g * cpg + j]; S2 += part[C + g * cpg + j]; }
+    for (int j = 0; j < cpg; ++j) { S1 += chan[7 * C + tid * cpg + j]; S2 += chan[8 * C + tid * cpg + j]; }
+    grp[tid] = S1; grp[G + tid] = S2;
+  }
+  __syncthreads();
+  const float inv_n = 1.0f / (float)n;
+  const float ihw = frcp(HW), icpg = frcp(cpg);
+  for (int o = tid; o < n_in; o += BLK) {
+    const int c = fdiv(o, ihw), g = fdiv(c, icpg);
     const float sc = chan[c], sh = chan[C + c], mean = chan[2 * C + c], rstd = chan[3 * C + c];
-    const float xv = x[o];
+    const float xv = xs[o];
     float du = gap ? dvec[c] / (float)HW : dvec[o];
     if (rl && !(fmaf(sc, xv, sh) > 0.f)) du = 0.f;
     const float xh = (xv - mean) * rstd;
-    dx[o] = rstd * (du * gam_b[c] - S1 * inv_n - xh * (S2 * inv_n));
+    dx[o] = rstd * (du * chan[6 * C + c] - grp[g] * inv_n - xh * (grp[G + g] * inv_n));
   }
 }
 
@@ -596,6 +718,11 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
   lfloat* red = (lfloat*)red_;
   lfloat* smem = (lfloat*)smem_;
   const int t = G->t_base + k;
+#ifdef PB_TIMING
+  if (threadIdx.x < 96) ts_sh[threadIdx.x / 24][threadIdx.x % 24] = 0;
+  __syncthreads();
+  PB_TS(0);
+#endif
   // The descriptor arrives through the vector memory path (one coalesced
   // request) and is parked in LDS; a burst of scalar loads of data no other
   // workgroup shares would miss the scalar cache line after line.
@@ -628,6 +755,23 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     case K_HEAD: step_head(d, t, red, smem); break;
     default: break;
   }
+#ifdef PB_TIMING
+  PB_TS(11);
+  __syncthreads();
+  if (t == pb_ts_tick) {
+    __shared__ int slot_;
+    if (threadIdx.x == 0) slot_ = atomicAdd(&pb_ts_n, 1);
+    __syncthreads();
+    const int slot = slot_;
+    if (slot < 16384) {
+      if (threadIdx.x < 96) pb_ts_out[slot * 100 + 4 + threadIdx.x] = ts_sh[threadIdx.x / 24][threadIdx.x % 24];
+      if (threadIdx.x == 0) {
+        pb_ts_out[slot * 100 + 0] = d.kind; pb_ts_out[slot * 100 + 1] = d.stage;
+        pb_ts_out[slot * 100 + 2] = d.g.gm; pb_ts_out[slot * 100 + 3] = tile;
+      }
+    }
+  }
+#endif
 }
 
 // Copies the tick's sample into the first stage's input ring and its label
@@ -751,3 +895,20 @@ void launch_advance(Globals* G, int dt, int didx, hipStream_t s) {
 }
 
 }  // namespace pb
+
+#ifdef PB_TIMING
+extern "C" int pb_debug_set_tick(int t) {
+  int z = 0;
+  hipMemcpyToSymbol(HIP_SYMBOL(pb::pb_ts_n), &z, sizeof(int));
+  return (int)hipMemcpyToSymbol(HIP_SYMBOL(pb::pb_ts_tick), &t, sizeof(int));
+}
+extern "C" int pb_debug_dump(long long* host, int max_recs) {
+  int n = 0;
+  hipDeviceSynchronize();
+  hipMemcpyFromSymbol(&n, HIP_SYMBOL(pb::pb_ts_n), sizeof(int));
+  if (n > max_recs) n = max_recs;
+  if (n > 16384) n = 16384;
+  hipMemcpyFromSymbol(host, HIP_SYMBOL(pb::pb_ts_out), (size_t)n * 100 * sizeof(long long));
+  return n;
+}
+#endif
