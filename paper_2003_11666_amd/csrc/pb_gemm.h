@@ -469,8 +469,7 @@ __device__ void step_bias_grad(const LDesc& d, int tile, int t) {
   const gfloat* dz = at(d.dy, t) + (size_t)co * P;
   float s = 0.f;
   for (int p = lane; p < P; p += 64) s += dz[p];
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o, 64);
+  s = wave_sum(s);
   if (lane == 0) GP(d.gb)[co] = s;
 }
 

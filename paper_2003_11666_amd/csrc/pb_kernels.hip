@@ -57,10 +57,29 @@ __device__ __forceinline__ gfloat* at(const TRef& r, int t) {
   return (gfloat*)r.base + (size_t)slot * (size_t)r.stride;
 }
 
+// Cross-lane operand through the data-parallel-primitive path of the vector
+// ALU (no LDS round trip): lanes without a source, or in rows masked out,
+// read 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_src(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+
+// Sum over the wavefront, returned to every lane (fixed order).
 __device__ __forceinline__ float wave_sum(float v) {
+  v += dpp_src<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+  v += dpp_src<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+  v += dpp_src<0x141, 0xF>(v);   // row_half_mirror
+  v += dpp_src<0x140, 0xF>(v);   // row_mirror: every lane holds the sum of its row of 16
+  v += dpp_src<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+  v += dpp_src<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3: lane 63 holds the total
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+__device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
-  return v;   // valid in lane 0
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
 }
 
 // Sum over the workgroup, same value returned to every thread.
@@ -74,8 +93,7 @@ __device__ __forceinline__ float block_sum(float v, lfloat* red) {
 }
 
 __device__ __forceinline__ float block_max(float v, lfloat* red) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_down(v, o, 64));
+  v = wave_max(v);
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   __syncthreads();
   if (lane == 0) red[wv] = v;
@@ -91,30 +109,87 @@ namespace pb {
 // GroupNorm statistics of one group (biased variance, two passes) and the
 // folded per-channel scale/shift built from the forward (predicted) affine
 // parameters; kept for the backward pass of the same sample.
-__device__ void step_gn_stats(const LDesc& d, int tile, int t, lfloat* red) {
-  const int g = tile, HW = d.H * d.W, cpg = d.C / d.G, n = cpg * HW;
+__device__ void step_gn_stats(const LDesc& d, int tile, int t, lfloat* red, lfloat* smem) {
+  const int tid = threadIdx.x;
+  const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W);
+  const int g = tile, cpg = UNI(fdiv(C, frcp(G))), n = cpg * HW;
   const gfloat* xp = at(d.x, t) + (size_t)g * n;
+  gfloat* st = at(d.st, t);
+  const bool rl = UNI(d.flags) & F_PRE_RELU;
+  constexpr int GU = 8;   // 16-byte registers per thread: groups of up to 8192 elements stay in registers
+  if ((n & 3) == 0 && n <= GU * 4 * BLK && cpg <= BLK) {
+    // one burst of reads: the group, and its channels' affine parameters
+    v4f xr[GU];
+#pragma unroll
+    for (int u = 0; u < GU; ++u) {
+      const int i = (tid + u * BLK) * 4;
+      xr[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+      if (i < n) xr[u] = *(const gv4*)(xp + i);
+    }
+    float gam = 0.f, bet = 0.f;
+    if (tid < cpg) { gam = GP(d.gamma)[g * cpg + tid]; bet = GP(d.beta)[g * cpg + tid]; }
+    float s = 0.f;
+#pragma unroll
+    for (int u = 0; u < GU; ++u) s += (xr[u][0] + xr[u][1]) + (xr[u][2] + xr[u][3]);
+    const float mean = block_sum(s, red) / (float)n;
+    float q = 0.f;
+#pragma unroll
+    for (int u = 0; u < GU; ++u)
+      if ((tid + u * BLK) * 4 < n) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { const float dl = xr[u][e] - mean; q = fmaf(dl, dl, q); }
+      }
+    const float var = block_sum(q, red) / (float)n;
+    const float rstd = 1.0f / sqrtf(var + GN_EPS);
+    if (tid == 0) { st[g] = mean; st[G + g] = rstd; }
+    if (tid < cpg) {
+      const int ch = g * cpg + tid;
+      const float sc = gam * rstd, sh = fmaf(-mean, sc, bet);
+      st[2 * G + ch] = sc;
+      st[2 * G + C + ch] = sh;
+      smem[tid] = sc; smem[cpg + tid] = sh;
+    }
+    if (d.y.base) {
+      // the normalised (and rectified) group, kept for the convolution of this
+      // tick and for the weight gradient of the same sample D ticks later
+      __syncthreads();
+      gfloat* yo = at(d.y, t) + (size_t)g * n;
+      const float ihw = frcp(HW);
+#pragma unroll
+      for (int u = 0; u < GU; ++u) {
+        const int i = (tid + u * BLK) * 4;
+        if (i < n) {
+          v4f o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int c = fdiv(i + e, ihw);
+            float v = fmaf(smem[c], xr[u][e], smem[cpg + c]);
+            if (rl) v = fmaxf(v, 0.f);
+            o[e] = v;
+          }
+          *(gv4*)(yo + i) = o;
+        }
+      }
+    }
+    return;
+  }
   float s = 0.f;
-  for (int i = threadIdx.x; i < n; i += BLK) s += xp[i];
+  for (int i = tid; i < n; i += BLK) s += xp[i];
   const float mean = block_sum(s, red) / (float)n;
   float q = 0.f;
-  for (int i = threadIdx.x; i < n; i += BLK) { float dl = xp[i] - mean; q = fmaf(dl, dl, q); }
+  for (int i = tid; i < n; i += BLK) { float dl = xp[i] - mean; q = fmaf(dl, dl, q); }
   const float var = block_sum(q, red) / (float)n;
   const float rstd = 1.0f / sqrtf(var + GN_EPS);
-  gfloat* st = at(d.st, t);
-  if (threadIdx.x == 0) { st[g] = mean; st[d.G + g] = rstd; }
-  for (int c = threadIdx.x; c < cpg; c += BLK) {
+  if (tid == 0) { st[g] = mean; st[G + g] = rstd; }
+  for (int c = tid; c < cpg; c += BLK) {
     const int ch = g * cpg + c;
     const float sc = GP(d.gamma)[ch] * rstd;
-    st[2 * d.G + ch] = sc;
-    st[2 * d.G + d.C + ch] = fmaf(-mean, sc, GP(d.beta)[ch]);
+    st[2 * G + ch] = sc;
+    st[2 * G + C + ch] = fmaf(-mean, sc, GP(d.beta)[ch]);
   }
   if (d.y.base) {
-    // the normalised (and rectified) group, kept for the convolution of this
-    // tick and for the weight gradient of the same sample D ticks later
     gfloat* yo = at(d.y, t) + (size_t)g * n;
-    const bool rl = d.flags & F_PRE_RELU;
-    for (int i = threadIdx.x; i < n; i += BLK) {
+    for (int i = tid; i < n; i += BLK) {
       const int ch = g * cpg + i / HW;
       const float sc = GP(d.gamma)[ch] * rstd;
       float v = fmaf(sc, xp[i], fmaf(-mean, sc, GP(d.beta)[ch]));
@@ -282,20 +357,51 @@ __device__ __forceinline__ float gn_du(const LDesc& d, const gfloat* dy, const g
 // Per channel: dgamma = sum dyv*xh, dbeta = sum dyv (dyv = gradient after the
 // ReLU mask); also gamma_b*dbeta and gamma_b*dgamma for the group sums.
 __device__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red) {
-  const int c = tile, HW = d.H * d.W, cpg = d.C / d.G, g = c / cpg;
+  const int c = tile, HW = UNI(d.H) * UNI(d.W), cpg = UNI(fdiv(UNI(d.C), frcp(UNI(d.G)))), g = UNI(fdiv(c, frcp(cpg)));
   const gfloat* st = at(d.st, t);
   const float mean = st[g], rstd = st[d.G + g], sc = st[2 * d.G + c], sh = st[2 * d.G + d.C + c];
   const gfloat* xc = at(d.x, t) + (size_t)c * HW;
   const gfloat* dy = at(d.dy, t);
   const bool rl = d.flags & F_GN_RELU;
   float sg = 0.f, sb = 0.f;
-  for (int i = threadIdx.x; i < HW; i += BLK) {
-    const float xv = xc[i];
-    const float yv = fmaf(sc, xv, sh);
-    float du = gn_du(d, dy, xc, sc, sh, c, i, HW);
-    if (rl && !(yv > 0.f)) du = 0.f;
-    sg = fmaf(du, (xv - mean) * rstd, sg);
-    sb += du;
+  if ((d.flags & (F_DU_BUF | F_DU_GAP)) && (HW & 3) == 0) {
+    // plain gradient buffer (or a pooled one): both operands with 16-byte loads, all in flight
+    const float dug = (d.flags & F_DU_GAP) ? dy[c] / (float)HW : 0.f;
+    constexpr int RU = 4;
+    for (int base = threadIdx.x * 4; base < HW; base += RU * 4 * BLK) {
+      v4f xv[RU], dv[RU];
+#pragma unroll
+      for (int u = 0; u < RU; ++u) {
+        const int i = base + u * 4 * BLK;
+        xv[u] = (v4f){0.f, 0.f, 0.f, 0.f}; dv[u] = xv[u];
+        if (i < HW) {
+          xv[u] = *(const gv4*)(xc + i);
+          if (d.flags & F_DU_BUF) dv[u] = *(const gv4*)(dy + (size_t)c * HW + i);
+          else dv[u] = (v4f){dug, dug, dug, dug};
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < RU; ++u)
+        if (base + u * 4 * BLK < HW) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float yv = fmaf(sc, xv[u][e], sh);
+            float du = dv[u][e];
+            if (rl && !(yv > 0.f)) du = 0.f;
+            sg = fmaf(du, (xv[u][e] - mean) * rstd, sg);
+            sb += du;
+          }
+        }
+    }
+  } else {
+    for (int i = threadIdx.x; i < HW; i += BLK) {
+      const float xv = xc[i];
+      const float yv = fmaf(sc, xv, sh);
+      float du = gn_du(d, dy, xc, sc, sh, c, i, HW);
+      if (rl && !(yv > 0.f)) du = 0.f;
+      sg = fmaf(du, (xv - mean) * rstd, sg);
+      sb += du;
+    }
   }
   sg = block_sum(sg, red);
   sb = block_sum(sb, red);
@@ -311,14 +417,23 @@ __device__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red) {
 
 // dx = rstd * (dxh - mean(dxh) - xh * mean(dxh*xh)), dxh = dyv * gamma_b
 __device__ void step_gnb_apply(const LDesc& d, int tile, int t) {
-  const int HW = d.H * d.W, cpg = d.C / d.G, n = cpg * HW;
+  const int HW = UNI(d.H) * UNI(d.W), cpg = UNI(fdiv(UNI(d.C), frcp(UNI(d.G)))), n = cpg * HW;
   const int o = tile * BLK + threadIdx.x;
   if (o >= d.C * HW) return;
-  const int c = o / HW, i = o - c * HW, g = c / cpg;
+  const int c = fdiv(o, frcp(HW)), i = o - c * HW, g = fdiv(c, frcp(cpg));
   const gfloat* st = at(d.st, t);
   const float mean = st[g], rstd = st[d.G + g], sc = st[2 * d.G + c], sh = st[2 * d.G + d.C + c];
   float S1 = 0.f, S2 = 0.f;
-  for (int j = 0; j < cpg; ++j) { S1 += GP(d.part)[g * cpg + j]; S2 += GP(d.part)[d.C + g * cpg + j]; }
+  for (int j0 = 0; j0 < cpg; j0 += 8) {           // 16 reads in flight per round trip
+    float p1[8], p2[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      p1[u] = 0.f; p2[u] = 0.f;
+      if (j0 + u < cpg) { p1[u] = GP(d.part)[g * cpg + j0 + u]; p2[u] = GP(d.part)[d.C + g * cpg + j0 + u]; }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { S1 += p1[u]; S2 += p2[u]; }
+  }
   const gfloat* xc = at(d.x, t) + (size_t)c * HW;
   const float xv = xc[i];
   const float yv = fmaf(sc, xv, sh);
@@ -467,16 +582,267 @@ __device__ void step_update(const LDesc& d, int tile) {
   }
 }
 
-// Sum over the wavefront, same value returned to every lane.
-__device__ __forceinline__ float wave_sum_all(float v) {
-  return __shfl(wave_sum(v), 0, 64);
-}
-
 // Limits of the fused last stage (checked on the host): its input, the vector
 // the linear layer sees and the logits live in LDS / registers of one workgroup.
 constexpr int HEAD_MAX_IN = 8192;   // C*H*W
 constexpr int HEAD_MAX_CV = 512;    // inputs of the linear layer
 constexpr int HEAD_MAX_K = 16;      // classes
+
+// Last stage of the form GroupNorm -> ReLU -> global average pool -> linear ->
+// cross-entropy with H*W a multiple of 4: the input stays in registers (thread
+// holds the 4-element slots tid, tid + 256, ...; a slot lies inside one
+// channel) and every reduction over a group or a channel goes through one
+// array of per-slot partial sums in LDS.
+// LDS: psum[n/4] | psum2[n/4] | vec[512] | dvec[512] | logit[16] | ebuf[16] | chan[9*C] | grp[2*G]
+__device__ void step_head_gap4(const LDesc& d, int t, lfloat* smem) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);
+  const int C = UNI(d.C), HW = UNI(d.H) * UNI(d.W), K = UNI(d.K), G = UNI(d.G), flags = UNI(d.flags);
+  const bool rl = flags & F_PRE_RELU, has_b = flags & F_BIAS;
+  const int n_in = C * HW, nslot = n_in >> 2, HW4 = HW >> 2;
+  const int cpg = UNI(fdiv(C, frcp(G))), n = cpg * HW, ns = n >> 2;      // per group: channels, elements, slots
+  const float ihw4 = frcp(HW4), ins = frcp(ns);
+  lfloat* psum = smem;
+  lfloat* psum2 = psum + nslot;
+  lfloat* vec = psum2 + nslot;
+  lfloat* dvec = vec + HEAD_MAX_CV;
+  lfloat* logit = dvec + HEAD_MAX_CV;
+  lfloat* ebuf = logit + HEAD_MAX_K;
+  lfloat* chan = ebuf + HEAD_MAX_K;                // sc, sh, mean, rstd, gamma_f, beta_f, gamma_b, gm*sb, gm*sg
+  lfloat* grp = chan + 9 * C;
+  const gfloat* x = at(d.x, t);
+  // ---- all global reads in one burst
+  constexpr int XU = HEAD_MAX_IN / (4 * BLK);
+  v4f xr[XU];
+#pragma unroll
+  for (int u = 0; u < XU; ++u) {
+    xr[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+    if (u * BLK < nslot) {
+      const int sl = tid + u * BLK;
+      if (sl < nslot) xr[u] = *(const gv4*)(x + 4 * sl);
+    }
+  }
+  constexpr int KU = HEAD_MAX_K / 4, IU = HEAD_MAX_CV / 64, JU = HEAD_MAX_CV / BLK;
+  float wf[KU][IU];      // forward weights: wave wv holds rows wv, wv + 4, ...
+#pragma unroll
+  for (int ku = 0; ku < KU; ++ku)
+#pragma unroll
+    for (int iu = 0; iu < IU; ++iu) {
+      const int k = wv + 4 * ku, i = lane + 64 * iu;
+      wf[ku][iu] = 0.f;
+      if (4 * ku < K && 64 * iu < C) {
+        if (k < K && i < C) wf[ku][iu] = GP(d.w)[k * C + i];
+      }
+    }
+  float wb[JU][HEAD_MAX_K];   // backward (current) weights: thread holds columns tid, tid + 256
+#pragma unroll
+  for (int ju = 0; ju < JU; ++ju)
+#pragma unroll
+    for (int k = 0; k < HEAD_MAX_K; ++k) {
+      const int i = tid + ju * BLK;
+      wb[ju][k] = 0.f;
+      if (k < K && ju * BLK < C) {
+        if (i < C) wb[ju][k] = GP(d.wp)[k * C + i];
+      }
+    }
+  float pg[JU][3];
+#pragma unroll
+  for (int ju = 0; ju < JU; ++ju) {
+    const int c = tid + ju * BLK;
+    pg[ju][0] = pg[ju][1] = pg[ju][2] = 0.f;
+    if (ju * BLK < C && c < C) { pg[ju][0] = GP(d.gamma)[c]; pg[ju][1] = GP(d.beta)[c]; pg[ju][2] = ((const gfloat*)d.skip.base)[c]; }
+  }
+  const float bz = (has_b && tid < K) ? GP(d.b)[tid] : 0.f;
+  const int sample = t - (UNI(d.n_stages) - 1);
+  const int label = ((const gint*)d.labels)[sample % UNI(d.n_stages)];
+  // ---- GroupNorm statistics: per-slot partial sums, one wavefront per group
+#pragma unroll
+  for (int u = 0; u < XU; ++u)
+    if (u * BLK < nslot) {
+      const int sl = tid + u * BLK;
+      if (sl < nslot) psum[sl] = (xr[u][0] + xr[u][1]) + (xr[u][2] + xr[u][3]);
+    }
+#pragma unroll
+  for (int ju = 0; ju < JU; ++ju) {
+    const int c = tid + ju * BLK;
+    if (ju * BLK < C && c < C) { chan[4 * C + c] = pg[ju][0]; chan[5 * C + c] = pg[ju][1]; chan[6 * C + c] = pg[ju][2]; }
+  }
+  __syncthreads();
+  for (int g = wv; g < G; g += BLK / 64) {
+    float sm = 0.f;
+    for (int j = lane; j < ns; j += 64) sm += psum[g * ns + j];
+    sm = wave_sum(sm);
+    if (lane == 0) grp[g] = sm / (float)n;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < XU; ++u)
+    if (u * BLK < nslot) {
+      const int sl = tid + u * BLK;
+      if (sl < nslot) {
+        const float m = grp[fdiv(sl, ins)];
+        float q = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { const float dl = xr[u][e] - m; q = fmaf(dl, dl, q); }
+        psum2[sl] = q;
+      }
+    }
+  __syncthreads();
+  for (int g = wv; g < G; g += BLK / 64) {
+    float q = 0.f;
+    for (int j = lane; j < ns; j += 64) q += psum2[g * ns + j];
+    q = wave_sum(q);
+    const float mean = grp[g];
+    const float rstd = 1.0f / sqrtf(q / (float)n + GN_EPS);
+    for (int c = lane; c < cpg; c += 64) {
+      const int ch = g * cpg + c;
+      const float sc = chan[4 * C + ch] * rstd;
+      chan[ch] = sc;
+      chan[C + ch] = fmaf(-mean, sc, chan[5 * C + ch]);
+      chan[2 * C + ch] = mean;
+      chan[3 * C + ch] = rstd;
+    }
+  }
+  __syncthreads();
+  // ---- ReLU and average pool: per-slot partial sums, then 4 lanes per channel
+#pragma unroll
+  for (int u = 0; u < XU; ++u)
+    if (u * BLK < nslot) {
+      const int sl = tid + u * BLK;
+      if (sl < nslot) {
+        const int c = fdiv(sl, ihw4);
+        const float sc = chan[c], sh = chan[C + c];
+        float sm = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { float v = fmaf(sc, xr[u][e], sh); if (rl) v = fmaxf(v, 0.f); sm += v; }
+        psum[sl] = sm;
+      }
+    }
+  __syncthreads();
+  for (int j = tid; j < 4 * C; j += BLK) {           // lanes 4c..4c+3 share channel c
+    const int c = j >> 2, p = j & 3;
+    float sm = 0.f;
+    for (int i = p; i < HW4; i += 4) sm += psum[c * HW4 + i];
+    sm += dpp_src<0xB1, 0xF>(sm);
+    sm += dpp_src<0x4E, 0xF>(sm);
+    if (p == 0) vec[c] = sm / (float)HW;
+  }
+  if (tid < K) ebuf[tid] = bz;
+  __syncthreads();
+#pragma unroll
+  for (int ku = 0; ku < KU; ++ku) {
+    const int k = wv + 4 * ku;
+    if (k < K) {
+      float sm = 0.f;
+#pragma unroll
+      for (int iu = 0; iu < IU; ++iu) {
+        const int i = lane + 64 * iu;
+        if (64 * iu < C && i < C) sm = fmaf(wf[ku][iu], vec[i], sm);
+      }
+      sm = wave_sum(sm);
+      if (lane == 0) logit[k] = sm + ebuf[k];
+    }
+  }
+  __syncthreads();
+  // ---- loss and dlogits
+  float mx = -3.0e38f;
+#pragma unroll
+  for (int k = 0; k < HEAD_MAX_K; ++k)
+    if (k < K) mx = fmaxf(mx, logit[k]);
+  const float zl = logit[label];
+  __syncthreads();
+  if (tid < K) ebuf[tid] = expf(logit[tid] - mx);
+  __syncthreads();
+  float dl[HEAD_MAX_K];
+  float sm = 0.f;
+#pragma unroll
+  for (int k = 0; k < HEAD_MAX_K; ++k) { dl[k] = (k < K) ? ebuf[k] : 0.f; sm += dl[k]; }
+  if (tid == 0) GP(d.loss_log)[sample % UNI(d.loss_cap)] = logf(sm) + mx - zl;
+#pragma unroll
+  for (int k = 0; k < HEAD_MAX_K; ++k) dl[k] = dl[k] / sm - (k == label ? 1.f : 0.f);
+  // ---- backward of the linear layer: dW = dl (x) vec, db = dl, dvec = W_cur^T dl
+#pragma unroll
+  for (int ju = 0; ju < JU; ++ju) {
+    const int i = tid + ju * BLK;
+    if (ju * BLK < C && i < C) {
+      const float vi = vec[i];
+      float a = 0.f;
+#pragma unroll
+      for (int k = 0; k < HEAD_MAX_K; ++k)
+        if (k < K) {
+          GP(d.gw)[k * C + i] = dl[k] * vi;
+          a = fmaf(wb[ju][k], dl[k], a);
+        }
+      dvec[i] = a / (float)HW;                      // gradient of every element under the pool
+    }
+  }
+  if (has_b) {
+#pragma unroll
+    for (int k = 0; k < HEAD_MAX_K; ++k)
+      if (k < K && tid == k) GP(d.gb)[k] = dl[k];
+  }
+  __syncthreads();
+  // ---- GroupNorm backward: per-slot partial sums of du*xh and du
+#pragma unroll
+  for (int u = 0; u < XU; ++u)
+    if (u * BLK < nslot) {
+      const int sl = tid + u * BLK;
+      if (sl < nslot) {
+        const int c = fdiv(sl, ihw4);
+        const float sc = chan[c], sh = chan[C + c], mean = chan[2 * C + c], rstd = chan[3 * C + c], du0 = dvec[c];
+        float sg = 0.f, sb = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float du = du0;
+          if (rl && !(fmaf(sc, xr[u][e], sh) > 0.f)) du = 0.f;
+          sg = fmaf(du, (xr[u][e] - mean) * rstd, sg);
+          sb += du;
+        }
+        psum[sl] = sg; psum2[sl] = sb;
+      }
+    }
+  __syncthreads();
+  for (int j = tid; j < 4 * C; j += BLK) {
+    const int c = j >> 2, p = j & 3;
+    float sg = 0.f, sb = 0.f;
+    for (int i = p; i < HW4; i += 4) { sg += psum[c * HW4 + i]; sb += psum2[c * HW4 + i]; }
+    sg += dpp_src<0xB1, 0xF>(sg); sb += dpp_src<0xB1, 0xF>(sb);
+    sg += dpp_src<0x4E, 0xF>(sg); sb += dpp_src<0x4E, 0xF>(sb);
+    if (p == 0) {
+      GP(d.ggamma)[c] = sg; GP(d.gbeta)[c] = sb;
+      const float gm = chan[6 * C + c];
+      chan[7 * C + c] = gm * sb; chan[8 * C + c] = gm * sg;
+    }
+  }
+  __syncthreads();
+  if (d.dx.base == nullptr) return;
+  if (tid < G) {
+    float S1 = 0.f, S2 = 0.f;
+    for (int j = 0; j < cpg; ++j) { S1 += chan[7 * C + tid * cpg + j]; S2 += chan[8 * C + tid * cpg + j]; }
+    const float inv_n = 1.0f / (float)n;
+    grp[tid] = S1 * inv_n; grp[G + tid] = S2 * inv_n;
+  }
+  __syncthreads();
+  gfloat* dx = at(d.dx, t);
+#pragma unroll
+  for (int u = 0; u < XU; ++u)
+    if (u * BLK < nslot) {
+      const int sl = tid + u * BLK;
+      if (sl < nslot) {
+        const int c = fdiv(sl, ihw4), g = fdiv(sl, ins);
+        const float sc = chan[c], sh = chan[C + c], mean = chan[2 * C + c], rstd = chan[3 * C + c];
+        const float dug = dvec[c] * chan[6 * C + c], m1 = grp[g], m2 = grp[G + g];
+        v4f o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float du = dug;
+          if (rl && !(fmaf(sc, xr[u][e], sh) > 0.f)) du = 0.f;
+          const float xh = (xr[u][e] - mean) * rstd;
+          o[e] = rstd * (du - m1 - xh * m2);
+        }
+        *(gv4*)(dx + 4 * sl) = o;
+      }
+    }
+}
 
 // The whole last stage in one workgroup: [GroupNorm, ReLU, global average
 // pool |  ReLU | nothing] -> linear -> softmax cross-entropy -> backward of all
@@ -491,6 +857,10 @@ constexpr int HEAD_MAX_K = 16;      // classes
 // LDS: xs[C*H*W] | vec[512] | dvec[512] | logit[16] | bias[16] | chan[9*C] | grp[2*G]
 __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
   (void)red;
+  if ((UNI(d.flags) & F_PRE_AFFINE) && (UNI(d.flags) & F_DU_GAP) && ((UNI(d.H) * UNI(d.W)) & 3) == 0) {
+    step_head_gap4(d, t, smem);
+    return;
+  }
   const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);
   const int C = UNI(d.C), HW = UNI(d.H) * UNI(d.W), K = UNI(d.K), G = UNI(d.G), flags = UNI(d.flags);
   const bool gn = flags & F_PRE_AFFINE, rl = flags & F_PRE_RELU, gap = flags & F_DU_GAP, has_b = flags & F_BIAS;
@@ -529,7 +899,10 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
 #pragma unroll
     for (int iu = 0; iu < IU; ++iu) {
       const int k = wv + 4 * ku, i = lane + 64 * iu;
-      wf[ku][iu] = (k < K && i < Cv) ? GP(d.w)[(size_t)k * Cv + i] : 0.f;
+      wf[ku][iu] = 0.f;
+      if (4 * ku < K && 64 * iu < Cv) {            // scalar test first: whole blocks are skipped
+        if (k < K && i < Cv) wf[ku][iu] = GP(d.w)[k * Cv + i];
+      }
     }
   float wb[JU][HEAD_MAX_K];   // backward (current) weights: thread holds columns tid, tid + 256
 #pragma unroll
@@ -537,7 +910,10 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
 #pragma unroll
     for (int k = 0; k < HEAD_MAX_K; ++k) {
       const int i = tid + ju * BLK;
-      wb[ju][k] = (k < K && i < Cv) ? GP(d.wp)[(size_t)k * Cv + i] : 0.f;
+      wb[ju][k] = 0.f;
+      if (k < K && ju * BLK < Cv) {
+        if (i < Cv) wb[ju][k] = GP(d.wp)[k * Cv + i];
+      }
     }
   float pg[JU][3];
 #pragma unroll
@@ -549,6 +925,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
   const float bz = (has_b && tid < K) ? GP(d.b)[tid] : 0.f;
   const int sample = t - (UNI(d.n_stages) - 1);
   const int label = ((const gint*)d.labels)[sample % UNI(d.n_stages)];
+  PB_TS(1);
   // ---- park them
 #pragma unroll
   for (int u = 0; u < XU; ++u) {
@@ -570,6 +947,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
   }
   if (tid < K) bias[tid] = bz;
   __syncthreads();
+  PB_TS(2);
   // ---- forward
   const int cpg = gn ? C / G : 1, n = cpg * HW;
   if (gn) {
@@ -577,10 +955,10 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
       const lfloat* xp = xs + g * n;
       float sm = 0.f;
       for (int i = lane; i < n; i += 64) sm += xp[i];
-      const float mean = wave_sum_all(sm) / (float)n;
+      const float mean = wave_sum(sm) / (float)n;
       float q = 0.f;
       for (int i = lane; i < n; i += 64) { const float dl = xp[i] - mean; q = fmaf(dl, dl, q); }
-      const float var = wave_sum_all(q) / (float)n;
+      const float var = wave_sum(q) / (float)n;
       const float rstd = 1.0f / sqrtf(var + GN_EPS);
       for (int c = lane; c < cpg; c += 64) {
         const int ch = g * cpg + c;
@@ -593,6 +971,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
     }
     __syncthreads();
   }
+  PB_TS(3);
   if (gap) {
     for (int c = wv; c < C; c += BLK / 64) {
       const float sc = gn ? chan[c] : 1.f, sh = gn ? chan[C + c] : 0.f;
@@ -609,6 +988,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
     for (int i = tid; i < Cv; i += BLK) { const float v = xs[i]; vec[i] = rl ? fmaxf(v, 0.f) : v; }
   }
   __syncthreads();
+  PB_TS(4);
 #pragma unroll
   for (int ku = 0; ku < KU; ++ku) {
     const int k = wv + 4 * ku;
@@ -624,6 +1004,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
     }
   }
   __syncthreads();
+  PB_TS(5);
   // ---- loss and dlogits: K is small, every thread computes them
   float dl[HEAD_MAX_K];
   {
@@ -637,6 +1018,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
 #pragma unroll
     for (int k = 0; k < HEAD_MAX_K; ++k) dl[k] = dl[k] / sm - (k == label ? 1.f : 0.f);
   }
+  PB_TS(6);
   // ---- backward of the linear layer: dW = dl (x) vec, db = dl, dvec = W_cur^T dl
 #pragma unroll
   for (int ju = 0; ju < JU; ++ju) {
@@ -666,6 +1048,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
     return;
   }
   __syncthreads();
+  PB_TS(7);
   // ---- GroupNorm backward with du[c,hw] = dvec[c]/HW (after the pool) or dvec[c*HW+hw]
   for (int c = wv; c < C; c += BLK / 64) {
     const float sc = chan[c], sh = chan[C + c], mean = chan[2 * C + c], rstd = chan[3 * C + c];
@@ -685,6 +1068,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
     }
   }
   __syncthreads();
+  PB_TS(8);
   if (!dx) return;
   if (tid < G) {
     float S1 = 0.f, S2 = 0.f;
@@ -738,7 +1122,7 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
   const int tile = UNI(d.tile);
   if (t < UNI(d.first_tick)) return;
   switch (UNI(d.kind)) {
-    case K_GN_STATS: step_gn_stats(d, tile, t, red); break;
+    case K_GN_STATS: step_gn_stats(d, tile, t, red, smem); break;
     case K_GAP_FWD: step_gap_fwd(d, tile, t, red); break;
     case K_CONV_FWD: step_conv_fwd(d, tile, t); break;
     case K_POST_FWD: step_post_fwd(d, tile, t); break;

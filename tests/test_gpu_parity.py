@@ -26,7 +26,7 @@ def _check(res, K, S):
     assert res["v_err"] <= res["v_tol"], (res["v_err"], res["v_tol"])
 
 
-@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_vgg", "tiny_resnet", "small_resnet"])
+@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_vgg", "tiny_resnet", "small_resnet", "odd_resnet", "tiny_bottleneck"])
 @pytest.mark.parametrize("mit", [3, 0])
 def test_small_nets_100_ticks(name, mit):
     net = W.config(name)
