@@ -38,7 +38,8 @@ enum StepKind : int32_t {
   K_BIAS_GRAD = 11,  // db[co] = sum_p dZ[co,p]
   K_INGEST = 12,     // the tick's sample and label into the first stage's ring
   K_UPDATE = 13,     // fused SC+LWP update of one stage's parameter block
-  K_HEAD = 14        // whole last stage (forward, loss, backward) in one workgroup
+  K_HEAD = 14,       // whole last stage (forward, loss, backward) in one workgroup
+  K_GN_BWD = 15      // GroupNorm backward of one group in one workgroup: channel sums and dx together
 };
 
 constexpr int LDS_FLOATS = 15872;   // 62 KB of LDS per workgroup for the GEMM steps (two workgroups per compute unit)

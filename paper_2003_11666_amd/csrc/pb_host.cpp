@@ -481,6 +481,16 @@ bool head_fits(int C, int HW, int K, bool gap, int G) {
   return (n_in + 3) / 4 * 4 + 2 * HEAD_MAX_CV + 2 * HEAD_MAX_K + 9 * (int64_t)C + 2 * G <= LDS_FLOATS;
 }
 
+// Whether the GroupNorm backward of a C x HW map in G groups can run as one
+// workgroup per group (see step_gn_bwd): group in registers, slots inside a channel.
+constexpr int GNB_MAX_N = 8192;
+bool gn_bwd_fits(int C, int HW, int G) {
+  if (G < 1 || C % G || HW % 4) return false;
+  const int cpg = C / G;
+  const int64_t n = (int64_t)cpg * HW;
+  return n <= GNB_MAX_N && cpg <= BLK && n / 2 + 5 * cpg + 2 <= LDS_FLOATS;
+}
+
 // Compile the network into the step table.  Every step carries the phase it
 // may run in: steps of one stage's forward (or backward) chain depend on each
 // other and get consecutive phases; different stages and the two passes of
@@ -651,14 +661,22 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       d.gamma = wb + a.o_gamma;
       d.ggamma = gr + a.o_gamma; d.gbeta = gr + a.o_beta;
       d.part = c->f(b.part);
-      d.ntiles = a.K;
-      out.push_back({pb++, d});
-      StepDesc e = d;
-      e.kind = K_GNB_APPLY;
-      e.dx = ring(c, b.dz, 1, a.z_elems(), 0);
-      e.ntiles = cdiv(a.z_elems(), BLK);
-      out.push_back({pb++, e});
-      dz_src = e.dx;
+      if (c->kernel_set == 0 && !a.pool && gn_bwd_fits(d.C, d.H * d.W, d.G)) {
+        d.kind = K_GN_BWD;
+        d.dx = ring(c, b.dz, 1, a.z_elems(), 0);
+        d.ntiles = a.G;
+        out.push_back({pb++, d});
+        dz_src = d.dx;
+      } else {
+        d.ntiles = a.K;
+        out.push_back({pb++, d});
+        StepDesc e = d;
+        e.kind = K_GNB_APPLY;
+        e.dx = ring(c, b.dz, 1, a.z_elems(), 0);
+        e.ntiles = cdiv(a.z_elems(), BLK);
+        out.push_back({pb++, e});
+        dz_src = e.dx;
+      }
     }
     {   // weight gradient of the main layer
       StepDesc d = blank(K_CONV_BWD_W, s, t_b);
@@ -764,15 +782,25 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       d.gamma = wb + a.o_gamma;
       d.ggamma = gr + a.o_gamma; d.gbeta = gr + a.o_beta;
       d.part = c->f(b.part);
-      d.ntiles = a.Cin;
-      out.push_back({pb++, d});
-      if (s > 0) {
-        StepDesc e = d;
-        e.kind = K_GNB_APPLY;
-        e.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
-        if (a.tap_dist) { e.flags |= F_ADD_SKG; e.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
-        e.ntiles = cdiv(a.in_elems(), BLK);
-        out.push_back({pb++, e});
+      if (c->kernel_set == 0 && gn_bwd_fits(d.C, d.H * d.W, d.G)) {
+        d.kind = K_GN_BWD;
+        if (s > 0) {
+          d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
+          if (a.tap_dist) { d.flags |= F_ADD_SKG; d.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
+        }
+        d.ntiles = a.G;
+        out.push_back({pb++, d});
+      } else {
+        d.ntiles = a.Cin;
+        out.push_back({pb++, d});
+        if (s > 0) {
+          StepDesc e = d;
+          e.kind = K_GNB_APPLY;
+          e.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
+          if (a.tap_dist) { e.flags |= F_ADD_SKG; e.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
+          e.ntiles = cdiv(a.in_elems(), BLK);
+          out.push_back({pb++, e});
+        }
       }
     }
   }
@@ -789,7 +817,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   for (auto& pr : out) {
     const int kd = pr.second.kind;
     const bool touches = kd == K_GN_STATS || kd == K_CONV_FWD || kd == K_GEMM || kd == K_GNB_REDUCE || kd == K_CONV_BWD_X ||
-                         kd == K_CONV_BWD_W || kd == K_BIAS_GRAD || kd == K_HEAD;
+                         kd == K_CONV_BWD_W || kd == K_BIAS_GRAD || kd == K_HEAD || kd == K_GN_BWD;
     if (touches) last_param_phase = std::max(last_param_phase, pr.first);
   }
   for (int s = 0; s < S; ++s) {
@@ -818,6 +846,7 @@ void order_steps(std::vector<std::pair<int, StepDesc>>& tagged) {
     }
     if (d.kind == K_GN_STATS) return (int64_t)d.C / std::max(1, d.G) * d.H * d.W / 64 + 1000;
     if (d.kind == K_GNB_REDUCE) return (int64_t)d.H * d.W / 64 + 500;
+    if (d.kind == K_GN_BWD) return (int64_t)d.C / std::max(1, d.G) * d.H * d.W / 32 + 1000;
     return 0;
   };
   std::stable_sort(tagged.begin(), tagged.end(),
@@ -881,6 +910,14 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
              ptr_ok(d.part, 3 * d.C) && ptr_ok(d.gamma, d.C);
         if (d.kind == K_GNB_REDUCE) ok = ok && d.ntiles == d.C && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C);
         else ok = ok && (int64_t)d.ntiles * BLK >= in && ref_ok(d.dx, in) && (!(d.flags & F_ADD_SKG) || ref_ok(d.skg, in));
+        break;
+      }
+      case K_GN_BWD: {
+        const int64_t dyn = (d.flags & F_DU_BUF) ? in : d.C;
+        ok = ok && gn_bwd_fits(d.C, d.H * d.W, d.G) && d.ntiles == d.G && !(d.flags & F_DU_POOL) &&
+             ((d.flags & F_DU_BUF) || (d.flags & F_DU_GAP)) && ref_ok(d.x, in) && ref_ok(d.st, stn) && ref_ok(d.dy, dyn) &&
+             ptr_ok(d.gamma, d.C) && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C) && (!d.dx.base || ref_ok(d.dx, in)) &&
+             (!(d.flags & F_ADD_SKG) || (d.dx.base && ref_ok(d.skg, in)));
         break;
       }
       case K_CONV_BWD_X:
@@ -1137,7 +1174,7 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   compile_steps(&tmp, steps);
   order_steps(steps);
   static const char* names[] = {"gn_stats", "gap_fwd", "conv_fwd", "post_fwd", "ce", "gnb_reduce", "gnb_apply",
-                                "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad", "ingest", "update", "head"};
+                                "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad", "ingest", "update", "head", "gn_bwd"};
   std::string o;
   char line[400];
   for (auto& pr : steps) {

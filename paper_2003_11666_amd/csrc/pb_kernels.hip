@@ -446,6 +446,118 @@ __device__ void step_gnb_apply(const LDesc& d, int tile, int t) {
   at(d.dx, t)[o] = r;
 }
 
+// Limit of the one-workgroup GroupNorm backward: elements of a group (they
+// stay in registers together with their gradients).
+constexpr int GNB_MAX_N = 8192;
+
+// GroupNorm (+ReLU) backward of one group in one workgroup: the group and its
+// incoming gradient are read once, in one burst, and stay in registers (thread
+// holds the 4-element slots tid, tid + 256, ...; H*W is a multiple of 4, so a
+// slot lies inside one channel).  Per-channel sums (dgamma, dbeta) go through
+// per-slot partial sums in LDS, then the group sums, then dx.
+// LDS: psum[n/4] | psum2[n/4] | cs[2*cpg] | cs2[3*cpg] | grp[2]
+__device__ void step_gn_bwd(const LDesc& d, int tile, int t, lfloat* smem) {
+  const int tid = threadIdx.x;
+  const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W), flags = UNI(d.flags);
+  const int g = tile, cpg = UNI(fdiv(C, frcp(G))), n = cpg * HW, ns = n >> 2, HW4 = HW >> 2;
+  const bool rl = flags & F_GN_RELU, gapd = flags & F_DU_GAP, has_skg = flags & F_ADD_SKG;
+  const float ihw4 = frcp(HW4);
+  lfloat* psum = smem;
+  lfloat* psum2 = psum + ns;
+  lfloat* cs = psum2 + ns;            // sc, sh per channel of the group
+  lfloat* cs2 = cs + 2 * cpg;         // gm*sb, gm*sg, gm per channel
+  lfloat* grp = cs2 + 3 * cpg;
+  const gfloat* st = at(d.st, t);
+  const gfloat* xg = at(d.x, t) + (size_t)g * n;
+  const gfloat* dy = at(d.dy, t);
+  const bool has_dx = d.dx.base != nullptr;
+  const gfloat* skg = (has_skg && has_dx) ? at(d.skg, t) + (size_t)g * n : nullptr;
+  constexpr int GU = GNB_MAX_N / (4 * BLK);
+  // ---- all reads
+  v4f xr[GU], du[GU], sk[GU];
+#pragma unroll
+  for (int u = 0; u < GU; ++u) {
+    xr[u] = (v4f){0.f, 0.f, 0.f, 0.f}; du[u] = xr[u]; sk[u] = xr[u];
+    if (u * BLK < ns) {
+      const int sl = tid + u * BLK;
+      if (sl < ns) {
+        xr[u] = *(const gv4*)(xg + 4 * sl);
+        if (gapd) { const float v = dy[g * cpg + fdiv(sl, ihw4)]; du[u] = (v4f){v, v, v, v}; }
+        else du[u] = *(const gv4*)(dy + (size_t)g * n + 4 * sl);
+        if (skg) sk[u] = *(const gv4*)(skg + 4 * sl);
+      }
+    }
+  }
+  const float mean = st[g], rstd = st[G + g];
+  float sc_c = 0.f, sh_c = 0.f, gm_c = 0.f;         // thread c < cpg holds its channel's constants
+  if (tid < cpg) {
+    sc_c = st[2 * G + g * cpg + tid]; sh_c = st[2 * G + C + g * cpg + tid]; gm_c = GP(d.gamma)[g * cpg + tid];
+  }
+  if (tid < cpg) { cs[tid] = sc_c; cs[cpg + tid] = sh_c; }
+  __syncthreads();
+  // ---- mask by the ReLU, per-slot partial sums of du*xh and du
+#pragma unroll
+  for (int u = 0; u < GU; ++u)
+    if (u * BLK < ns) {
+      const int sl = tid + u * BLK;
+      if (sl < ns) {
+        const int c = fdiv(sl, ihw4);
+        const float sc = cs[c], sh = cs[cpg + c];
+        const float dpool = gapd ? du[u][0] / (float)HW : 0.f;   // gradient of every element under an average pool
+        float sg = 0.f, sb = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float dv = gapd ? dpool : du[u][e];
+          if (rl && !(fmaf(sc, xr[u][e], sh) > 0.f)) dv = 0.f;
+          du[u][e] = dv;
+          sg = fmaf(dv, (xr[u][e] - mean) * rstd, sg);
+          sb += dv;
+        }
+        psum[sl] = sg; psum2[sl] = sb;
+      }
+    }
+  __syncthreads();
+  for (int j = tid; j < 4 * cpg; j += BLK) {          // lanes 4c..4c+3 share channel c
+    const int c = j >> 2, p = j & 3;
+    float sg = 0.f, sb = 0.f;
+    for (int i = p; i < HW4; i += 4) { sg += psum[c * HW4 + i]; sb += psum2[c * HW4 + i]; }
+    sg += dpp_src<0xB1, 0xF>(sg); sb += dpp_src<0xB1, 0xF>(sb);
+    sg += dpp_src<0x4E, 0xF>(sg); sb += dpp_src<0x4E, 0xF>(sb);
+    if (p == 0) {
+      GP(d.ggamma)[g * cpg + c] = sg; GP(d.gbeta)[g * cpg + c] = sb;
+      cs2[c] = sb; cs2[cpg + c] = sg;
+    }
+  }
+  __syncthreads();
+  if (tid < cpg) { cs2[tid] *= gm_c; cs2[cpg + tid] *= gm_c; cs2[2 * cpg + tid] = gm_c; }
+  __syncthreads();
+  if (!has_dx) return;
+  if (tid < 64) {
+    float s1 = 0.f, s2 = 0.f;
+    for (int c = tid; c < cpg; c += 64) { s1 += cs2[c]; s2 += cs2[cpg + c]; }
+    s1 = wave_sum(s1); s2 = wave_sum(s2);
+    if (tid == 0) { grp[0] = s1 / (float)n; grp[1] = s2 / (float)n; }
+  }
+  __syncthreads();
+  const float m1 = grp[0], m2 = grp[1];
+  gfloat* dx = at(d.dx, t) + (size_t)g * n;
+#pragma unroll
+  for (int u = 0; u < GU; ++u)
+    if (u * BLK < ns) {
+      const int sl = tid + u * BLK;
+      if (sl < ns) {
+        const float gm = cs2[2 * cpg + fdiv(sl, ihw4)];
+        v4f o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float xh = (xr[u][e] - mean) * rstd;
+          o[e] = rstd * (du[u][e] * gm - m1 - xh * m2) + sk[u][e];
+        }
+        *(gv4*)(dx + 4 * sl) = o;
+      }
+    }
+}
+
 // Backward data: dX = W^T dZ (transposed convolution), one thread per input
 // element, gathering.
 __device__ void step_conv_bwd_x(const LDesc& d, int tile, int t) {
@@ -1137,6 +1249,7 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     case K_INGEST: step_ingest(d, tile, t, G, k, sample_override, label_override); break;
     case K_UPDATE: step_update(d, tile); break;
     case K_HEAD: step_head(d, t, red, smem); break;
+    case K_GN_BWD: step_gn_bwd(d, tile, t, smem); break;
     default: break;
   }
 #ifdef PB_TIMING
