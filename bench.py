@@ -98,8 +98,8 @@ def main():
     ticks_per_s = args.steps / dt
 
     # second pass over the same region with HIP events around every launch
-    # (a) the launches as timed above; (b) one launch per step with the update as
-    # its stand-alone kernel, which isolates the update's duration inside the tick
+    # (a) the launches as timed above; (b) one launch per step, which isolates the
+    # duration of the update steps inside the tick
     prof_ticks = min(args.steps, 500)
     eng.profile_begin(64 * prof_ticks)
     eng.run_resident(xd, yd, warm + args.steps, prof_ticks)
@@ -111,9 +111,16 @@ def main():
     n_upd, ms_upd = eng.profile_end(1)
     n_in, ms_in = eng.profile_end(2)
     eng.set_launch_mode(args.launch_mode)
-    upd_us = 1e3 * ms_upd / max(n_upd, 1)
-    upd_bytes = 24 * n_params                     # w,v,g read; w,v,w_hat written
-    achieved = upd_bytes / (upd_us * 1e-6) / 1e9
+    # update steps of one tick (one launch per stage in this mode): 24 B per parameter
+    # (w, v, g read; w, v, w_hat written)
+    upd_us_tick = 1e3 * ms_upd / max(prof2, 1)
+    upd_bytes = 24 * n_params
+    upd_gbs = upd_bytes / (upd_us_tick * 1e-6) / 1e9
+    # the dominant kernel: k_phase, all steps of a phase in one launch
+    tick_bytes = tick_algorithmic_bytes(net, n_params)
+    ph_us_tick = 1e3 * ms_ph / prof_ticks
+    launches = n_ph / prof_ticks
+    achieved = tick_bytes / (ph_us_tick * 1e-6) / 1e9
     losses = eng.loss_history()
     assert len(losses) and all(l == l for l in losses[-100:]), "non-finite loss"
 
@@ -125,15 +132,19 @@ def main():
         "config": {"workload": f"{net['name']}: {S} pipeline stages, input {net['in_c']}x{net['in_h']}x{net['in_w']}, "
                                f"{n_params} parameters, batch 1, SC_D+LWP_D, lr {net['lr']}, momentum {net['momentum']}, "
                                f"pool of {len(ys)} resident samples"},
-        "roofline": {"kernel": "k_update (fused SC+LWP momentum update)", "bound": "hbm",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "roofline": {"kernel": "k_phase (every step of a tick: forward, backward and update of all stages)",
+                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "avg_launch_us": upd_us, "algorithmic_bytes_per_launch": upd_bytes},
-        "tick_roofline": {"bound": "hbm", "algorithmic_bytes": tick_algorithmic_bytes(net, n_params),
-                          "frac": tick_algorithmic_bytes(net, n_params) / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
-        "kernel_time_us_per_tick": {"phase_launches": 1e3 * ms_ph / prof_ticks,
-                                    "launches_per_tick": n_ph / prof_ticks,
-                                    "update_alone": 1e3 * ms_upd / max(prof2, 1),
+                     "avg_launch_us": ph_us_tick / launches, "launches_per_tick": launches,
+                     "algorithmic_bytes_per_launch": tick_bytes / launches},
+        "update_in_tick": {"kernel": "k_phase, update steps only (one launch per stage)", "bound": "hbm",
+                           "achieved": upd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": upd_gbs / HBM_PEAK_GBS,
+                           "us_per_tick": upd_us_tick, "launches_per_tick": n_upd / max(prof2, 1),
+                           "algorithmic_bytes_per_tick": upd_bytes},
+        "tick_roofline": {"bound": "hbm", "algorithmic_bytes": tick_bytes,
+                          "frac": tick_bytes / (dt / args.steps) / 1e9 / HBM_PEAK_GBS},
+        "kernel_time_us_per_tick": {"phase_launches": ph_us_tick, "launches_per_tick": launches,
+                                    "update_steps_alone": upd_us_tick,
                                     "ingest_alone": 1e3 * ms_in / max(prof2, 1)},
         "final_loss_mean_last_200": float(losses[-200:].mean()),
     }

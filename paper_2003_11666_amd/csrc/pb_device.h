@@ -8,7 +8,8 @@
 namespace pb {
 
 constexpr int BLK = 256;          // threads per workgroup (4 wavefronts of 64)
-constexpr int UPD_CHUNK = 1024;   // floats per workgroup in the update kernel
+constexpr int UPD_CHUNK = 1024;   // stages are padded to this many floats
+constexpr int UPD_TILE = 8192;    // floats per workgroup of an update step (8 float4 per thread and array in flight)
 constexpr float GN_EPS = 1e-5f;
 
 // A tensor that lives in a ring of `depth` slots.  At tick t the slot in use
@@ -37,7 +38,7 @@ enum StepKind : int32_t {
   K_GEMM = 10,       // conv / linear forward, backward data or backward weights as an MFMA implicit GEMM
   K_BIAS_GRAD = 11,  // db[co] = sum_p dZ[co,p]
   K_INGEST = 12,     // the tick's sample and label into the first stage's ring
-  K_UPDATE = 13,     // fused SC+LWP update of one stage's parameter block
+  K_UPDATE = 13,     // fused SC+LWP update of one stage's parameter block (reads one copy of w, v; writes the other)
   K_HEAD = 14,       // whole last stage (forward, loss, backward) in one workgroup
   K_GN_BWD = 15      // GroupNorm backward of one group in one workgroup: channel sums and dx together
 };
@@ -78,7 +79,9 @@ enum StepFlags : int32_t {
   F_DU_POOL = 256,    // ... is dY routed through the max-pool
   F_ADD_SKG = 512,    // epilogue adds the skip-path gradient
   F_MASK_X = 1024,    // backward data: multiply by [x > 0] (ReLU directly on the stage input)
-  F_GN_RELU = 2048    // GN backward: a ReLU follows the normalisation
+  F_GN_RELU = 2048,   // GN backward: a ReLU follows the normalisation
+  F_UPD_GN = 4096,    // K_GN_BWD also applies the update of the GroupNorm scale / shift it has the gradients of
+  F_ALWAYS = 8192     // the step runs before its first_tick too (then it only carries parameters over)
 };
 
 struct StepDesc {
@@ -109,8 +112,8 @@ struct StepDesc {
   const float* wp;
   const float* gamma;
   const float* beta;
-  float* v;            // K_UPDATE: velocity block; K_HEAD: unused
-  float* what;         // K_UPDATE: predicted-weight block (nullptr without LWP)
+  float* v;            // K_UPDATE / fused GroupNorm update: velocity read
+  float* what;         // ... predicted weights written (nullptr without LWP)
   float* gw;           // gradient outputs
   float* gb;
   float* ggamma;
@@ -135,19 +138,11 @@ struct Globals {
   const int32_t* pool_labels;
 };
 
-struct UpdSeg {       // per stage constants of the fused update
-  float a, b, lrT;
-  int32_t first_tick;
-};
-
 // ---- launch wrappers implemented in pb_kernels.hip ----
-void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, const float* sample_override,
-                  int label_override, hipStream_t s);
+void launch_phase(const StepDesc* recs_dev, int rec_stride, int total_tiles, const Globals* G, int k,
+                  const float* sample_override, int label_override, hipStream_t s);
 void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,
                    int n_stages, const Globals* G, int k, hipStream_t s);
-void launch_update(float* w, float* v, const float* g, float* what, const int32_t* chunk_stage,
-                   const UpdSeg* segs, int n_chunks, float lr, float m, const Globals* G, int k,
-                   hipStream_t s);
 void launch_update_flat(float* w, float* v, const float* g, float* what, int64_t n, float lr, float m,
                         float a, float b, float lrT, hipStream_t s);
 void launch_advance(Globals* G, int dt, int didx, hipStream_t s);

@@ -51,7 +51,7 @@ struct Stage {
   int tap_dist = 0;                // >0: a later stage (this + tap_dist) adds this stage's input
   int D = 0;
   // parameter offsets in the padded flat arena (floats), -1 = absent
-  int64_t off = 0, padded = 0, n_params = 0;
+  int64_t off = 0, padded = 0, n_params = 0, n_head = 0;
   int64_t o_w = -1, o_b = -1, o_wp = -1, o_gamma = -1, o_beta = -1;
   int64_t n_w = 0, n_b = 0, n_wp = 0, n_gn = 0;
   int fan_w = 0, fan_wp = 0;
@@ -174,8 +174,14 @@ int parse_net(const pb_net_desc* net, std::vector<Stage>& out) {
     st.n_w = (int64_t)st.K * st.C * st.k * st.k; st.o_w = o; o += st.n_w;
     if (st.has_bias) { st.n_b = st.K; st.o_b = o; o += st.n_b; }
     if (st.proj) { st.n_wp = (int64_t)st.K * st.sC; st.o_wp = o; o += st.n_wp; }
-    if (st.pre_gn || st.post_gn) { st.n_gn = st.gnC(); st.o_gamma = o; o += st.n_gn; st.o_beta = o; o += st.n_gn; }
-    st.n_params = o;
+    st.n_head = o;                                   // weight, bias, projection: contiguous, canonical order
+    if (st.pre_gn || st.post_gn) {
+      // GroupNorm scale and shift start on a 16-byte boundary: the vectorised update of the
+      // tensors before them must not touch them when another step updates them (F_UPD_GN)
+      o = (o + 3) / 4 * 4;
+      st.n_gn = st.gnC(); st.o_gamma = o; o += st.n_gn; st.o_beta = o; o += st.n_gn;
+    }
+    st.n_params = st.n_head + 2 * st.n_gn;
     st.padded = (o + UPD_CHUNK - 1) / UPD_CHUNK * UPD_CHUNK;
     off += st.padded;
   }
@@ -214,7 +220,6 @@ struct Layout {
   int64_t w = 0, v = 0, g = 0, what = -1;
   std::vector<StageBufs> sb;
   int64_t staging = 0, labels = 0, loss = 0, globals = 0, zero = 0;
-  int64_t steps = 0, prefix = 0, chunk_stage = 0, segs = 0;   // filled after step compilation
   int64_t total = 0;
 };
 
@@ -224,8 +229,14 @@ void plan_arena(const std::vector<Stage>& st, bool lwp, int loss_cap, Layout& L,
   const int S = (int)st.size();
   L.P = 0;
   for (const Stage& s : st) L.P += s.padded;
+  // The forward (predicted) weights exist twice: copy p is read by the forward passes of ticks of
+  // parity p while the updates of that tick write the other copy, so an update may run beside
+  // forward work of its own tick.  Master weights and velocity are updated in place: their only
+  // readers in a tick (the stage's backward steps) come before the stage's update.  Without weight
+  // prediction the forward copy simply equals the master weights.
   L.w = pl.alloc(L.P); L.v = pl.alloc(L.P); L.g = pl.alloc(L.P);
-  L.what = lwp ? pl.alloc(L.P) : -1;
+  L.what = pl.alloc(2 * L.P);
+  (void)lwp;
   L.sb.assign(S, StageBufs());
   for (int s = 0; s < S; ++s) {
     const Stage& a = st[s];
@@ -279,12 +290,12 @@ struct pb_ctx {
   std::vector<int64_t> rec_first;      // per step: index of its first per-workgroup record
   Plan* plan = nullptr;                // arena allocator while the step table is compiled
   std::vector<std::pair<int64_t, std::vector<int32_t>>> tables;   // (arena offset, contents) of the GEMM offset tables
+  std::vector<std::pair<int64_t, int64_t>> table_offs;            // per gemm_tables call: offsets of its two tables
+  size_t table_cursor = 0;
   std::vector<Phase> phases;
-  int n_chunks = 0;
+  int rec_stride = 0;   // records per step table (there are two, one per tick parity)
   // device views
   StepDesc* recs_dev = nullptr;        // one descriptor copy per workgroup, in launch order
-  int32_t* chunk_stage_dev = nullptr;
-  UpdSeg* segs_dev = nullptr;
   Globals* globals_dev = nullptr;
   int32_t* zero_dev = nullptr;
   int32_t* labels_dev = nullptr;
@@ -456,11 +467,18 @@ void gemm_tables(pb_ctx* c, const GemmCfg& g, int C, int H, int W, int K, int OH
     else if (g.gm == 2) { const int ih = i / W, iw = i % W; n[i] = ih * g.Wp + iw; }
     else { const int ci = i / kk, tap = i % kk, kh = tap / k, kw = tap % k; n[i] = ci * PRW + kh * g.Wp + kw; }
   }
-  const int64_t oq = c->plan->alloc((int64_t)q.size()), on = c->plan->alloc((int64_t)n.size());
+  int64_t oq, on;
+  if (c->table_cursor < c->table_offs.size()) {          // second record table: the tables exist already
+    oq = c->table_offs[c->table_cursor].first; on = c->table_offs[c->table_cursor].second;
+  } else {
+    oq = c->plan->alloc((int64_t)q.size()); on = c->plan->alloc((int64_t)n.size());
+    c->table_offs.push_back({oq, on});
+    c->tables.push_back({oq, std::move(q)});
+    c->tables.push_back({on, std::move(n)});
+  }
+  ++c->table_cursor;
   *tq = (const int32_t*)c->f(oq);
   *tn = (const int32_t*)c->f(on);
-  c->tables.push_back({oq, std::move(q)});
-  c->tables.push_back({on, std::move(n)});
   (void)C; (void)H; (void)K; (void)OH;
 }
 
@@ -481,9 +499,17 @@ bool head_fits(int C, int HW, int K, bool gap, int G) {
   return (n_in + 3) / 4 * 4 + 2 * HEAD_MAX_CV + 2 * HEAD_MAX_K + 9 * (int64_t)C + 2 * G <= LDS_FLOATS;
 }
 
+// Coefficients of the stage's update (Eqs. gscv, gscw, scd, lwp_v_form) by mitigation mode.
+void set_update_coeffs(const pb_ctx* c, const Stage& a, StepDesc* d) {
+  double ca = 1.0, cb = 0.0;
+  if (c->mitigation == 1 || c->mitigation == 3) sc_coeffs((double)c->m, a.D, &ca, &cb);
+  const double T = (c->mitigation >= 2) ? (double)a.D : 0.0;
+  d->fa = (float)ca; d->fb = (float)cb; d->flrT = (float)((double)c->lr * T); d->flr = c->lr; d->fm = c->m;
+}
+
 // Whether the GroupNorm backward of a C x HW map in G groups can run as one
 // workgroup per group (see step_gn_bwd): group in registers, slots inside a channel.
-constexpr int GNB_MAX_N = 8192;
+constexpr int GNB_MAX_N = 4096;
 bool gn_bwd_fits(int C, int HW, int G) {
   if (G < 1 || C % G || HW % 4) return false;
   const int cpg = C / G;
@@ -497,19 +523,21 @@ bool gn_bwd_fits(int C, int HW, int G) {
 // one stage are independent inside a tick (they work on different samples and
 // read the start-of-tick weights), except for the last stage whose backward
 // pass consumes the loss gradient of the same tick.
-void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
+void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int parity) {
   const int S = c->S;
+  c->table_cursor = 0;
   // all stages run concurrently: aim at a few workgroups per compute unit over
   // the whole phase rather than per step
   g_tile_target = std::max(4, std::min(32, 1024 / (3 * S)));
   if (const char* e = getenv("PB_TILE_TARGET")) g_tile_target = std::max(1, atoi(e));
   const Layout& L = c->L;
-  const bool lwp = L.what >= 0;
   for (int s = 0; s < S; ++s) {
     const Stage& a = c->st[s];
     const StageBufs& b = L.sb[s];
     const int D = a.D;
-    const float* wf = c->f((lwp ? L.what : L.w) + a.off);   // forward (predicted) parameters
+    // the copy of the forward parameters that ticks of this parity read, and the one their updates write
+    const int64_t rd = parity * L.P + a.off, wr = (1 - parity) * L.P + a.off;
+    const float* wf = c->f(L.what + rd);                    // forward (predicted) parameters
     const float* wb = c->f(L.w + a.off);                    // backward (current) parameters
     float* gr = c->f(L.g + a.off);
     const int t_f = s, t_b = 2 * (S - 1) - s;
@@ -665,7 +693,11 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         d.kind = K_GN_BWD;
         d.dx = ring(c, b.dz, 1, a.z_elems(), 0);
         d.ntiles = a.G;
-        out.push_back({pb++, d});
+        out.push_back({pb, d});
+        // keep the backward GEMMs of every post-norm stage in the same phase as those of the stages
+        // that need the two-step GroupNorm backward: a phase lasts as long as its longest tile, so
+        // heavy steps spread over more phases cost more, not less
+        pb += 2;
         dz_src = d.dx;
       } else {
         d.ntiles = a.K;
@@ -788,6 +820,15 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
           d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
           if (a.tap_dist) { d.flags |= F_ADD_SKG; d.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
         }
+        // this step ends the stage's backward chain and is the only producer of the scale / shift
+        // gradients: it updates those two tensors itself, so that the rest of the stage can be
+        // updated one phase earlier and no phase is left that holds nothing but updates
+        d.flags |= F_UPD_GN | F_ALWAYS;
+        set_update_coeffs(c, a, &d);
+        d.v = c->f(L.v + a.off + a.o_gamma);
+        d.w = wb + a.o_gamma;                         // in place (d.gamma)
+        d.b = d.v;
+        d.what = c->f(L.what + wr + a.o_gamma);
         d.ntiles = a.G;
         out.push_back({pb++, d});
       } else {
@@ -811,27 +852,30 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     if (d.g.avec && !a_aligned(c, d, false)) d.g.avec = 0;
     if (d.gp.gm && d.gp.avec && !a_aligned(c, d, true)) d.gp.avec = 0;
   }
-  // ---- fused update: one step per stage, in the first phase in which no step
-  // reads parameters or writes gradients any more
-  int last_param_phase = 0;
-  for (auto& pr : out) {
-    const int kd = pr.second.kind;
-    const bool touches = kd == K_GN_STATS || kd == K_CONV_FWD || kd == K_GEMM || kd == K_GNB_REDUCE || kd == K_CONV_BWD_X ||
-                         kd == K_CONV_BWD_W || kd == K_BIAS_GRAD || kd == K_HEAD || kd == K_GN_BWD;
-    if (touches) last_param_phase = std::max(last_param_phase, pr.first);
-  }
+  // ---- fused update: one step per stage, in the phase after the last one that writes a gradient
+  // of the stage (its readers use the other copy of the parameters, so they need not be waited for).
+  // It runs from the first tick on: before the stage's first backward pass its gradient and
+  // velocity are zero and the update only carries the parameters over to the other copy.
   for (int s = 0; s < S; ++s) {
     const Stage& a = c->st[s];
-    StepDesc d = blank(K_UPDATE, s, 2 * (S - 1) - s);
-    double ca = 1.0, cb = 0.0;
-    if (c->mitigation == 1 || c->mitigation == 3) sc_coeffs((double)c->m, a.D, &ca, &cb);
-    const double T = (c->mitigation >= 2) ? (double)a.D : 0.0;
-    d.fa = (float)ca; d.fb = (float)cb; d.flrT = (float)((double)c->lr * T); d.flr = c->lr; d.fm = c->m;
+    int last_grad_phase = 0;
+    bool gn_fused = false;
+    for (auto& pr : out) {
+      const StepDesc& e = pr.second;
+      if (e.stage != s) continue;
+      if (e.kind == K_GN_BWD && (e.flags & F_UPD_GN)) { gn_fused = true; continue; }
+      const bool writes_grad = (e.kind == K_GEMM && e.g.gm == 3) || e.kind == K_CONV_BWD_W || e.kind == K_BIAS_GRAD ||
+                               e.kind == K_GNB_REDUCE || e.kind == K_GN_BWD || e.kind == K_HEAD;
+      if (writes_grad) last_grad_phase = std::max(last_grad_phase, pr.first);
+    }
+    StepDesc d = blank(K_UPDATE, s, 0);
+    set_update_coeffs(c, a, &d);
     d.w = c->f(L.w + a.off); d.v = c->f(L.v + a.off); d.gw = c->f(L.g + a.off);
-    d.what = lwp ? c->f(L.what + a.off) : nullptr;
-    d.n = (int)a.padded;
-    d.ntiles = (int)(a.padded / UPD_CHUNK);
-    out.push_back({last_param_phase + 1, d});
+    d.wp = d.w; d.b = d.v;                             // master weights and velocity in place
+    d.what = c->f(L.what + (1 - parity) * L.P + a.off);
+    d.n = (int)(gn_fused ? a.o_gamma : a.padded);      // o_gamma is a multiple of 4
+    d.ntiles = (int)cdiv(d.n, UPD_TILE);
+    if (d.n > 0) out.push_back({last_grad_phase + 1, d});
   }
 }
 
@@ -918,6 +962,9 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
              ((d.flags & F_DU_BUF) || (d.flags & F_DU_GAP)) && ref_ok(d.x, in) && ref_ok(d.st, stn) && ref_ok(d.dy, dyn) &&
              ptr_ok(d.gamma, d.C) && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C) && (!d.dx.base || ref_ok(d.dx, in)) &&
              (!(d.flags & F_ADD_SKG) || (d.dx.base && ref_ok(d.skg, in)));
+        if (d.flags & F_UPD_GN)
+          ok = ok && ptr_ok(d.v, 2 * d.C) && ptr_ok(d.w, 2 * d.C) && ptr_ok(d.b, 2 * d.C) && ptr_ok(d.gamma, 2 * d.C) &&
+               d.what && ptr_ok(d.what, 2 * d.C);
         break;
       }
       case K_CONV_BWD_X:
@@ -937,8 +984,9 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
         ok = ok && (int64_t)d.ntiles * BLK >= d.n && ref_ok(d.dx, d.n) && ptr_ok((const float*)d.labels, d.n_stages);
         break;
       case K_UPDATE:
-        ok = ok && d.n > 0 && d.n % UPD_CHUNK == 0 && d.ntiles == d.n / UPD_CHUNK && ptr_ok(d.w, d.n) && ptr_ok(d.v, d.n) &&
-             ptr_ok(d.gw, d.n) && (!d.what || ptr_ok(d.what, d.n));
+        ok = ok && d.n > 0 && d.n % 4 == 0 && d.ntiles == cdiv(d.n, UPD_TILE) && ptr_ok(d.w, d.n) && ptr_ok(d.v, d.n) &&
+             ptr_ok(d.gw, d.n) && ptr_ok(d.wp, d.n) && ptr_ok(d.b, d.n) && (!d.what || ptr_ok(d.what, d.n)) &&
+             d.what != nullptr;
         break;
       case K_HEAD: {
         const int64_t cv = (d.flags & F_DU_GAP) ? d.C : in;
@@ -1078,11 +1126,13 @@ int64_t copy_params_out(pb_ctx* c, int64_t arena_off, float* dst, int64_t cap) {
   if (hipMemcpy(tmp.data(), c->f(arena_off), sizeof(float) * c->L.P, hipMemcpyDeviceToHost) != hipSuccess)
     return fail(PB_E_HIP, "device to host copy failed");
   int64_t n = 0;
+  auto put = [&](const float* src, int64_t cnt) {
+    const int64_t take = std::min<int64_t>(cnt, cap - n);
+    if (take > 0) { memcpy(dst + n, src, sizeof(float) * take); n += take; }
+  };
   for (const Stage& a : c->st) {
-    const int64_t take = std::min<int64_t>(a.n_params, cap - n);
-    if (take <= 0) break;
-    memcpy(dst + n, tmp.data() + a.off, sizeof(float) * take);
-    n += take;
+    put(tmp.data() + a.off, a.n_head);
+    if (a.n_gn) put(tmp.data() + a.off + a.o_gamma, 2 * a.n_gn);
   }
   return n;
 }
@@ -1107,20 +1157,17 @@ int run_one_tick(pb_ctx* c, const float* staging, int label) {
   if (c->launch_mode == 0) {
     for (const Phase& p : c->phases) {
       ScopedEv ev(c, 0);
-      launch_phase(c->recs_dev + c->rec_first[p.first], p.tiles, c->globals_dev, k, staging, label, c->stream);
+      launch_phase(c->recs_dev + c->rec_first[p.first], c->rec_stride, p.tiles, c->globals_dev, k, staging, label, c->stream);
     }
   } else {
-    // one launch per step; the update as the single stand-alone kernel (same arithmetic)
+    // one launch per step (same records, same arithmetic); event classes: 1 = update steps, 2 = ingest
     for (const Phase& p : c->phases)
       for (int i = 0; i < p.count; ++i) {
         const StepDesc& sd = c->steps[p.first + i];
-        if (sd.kind == K_UPDATE) continue;
-        ScopedEv ev(c, sd.kind == K_INGEST ? 2 : 0);
-        launch_phase(c->recs_dev + c->rec_first[p.first + i], sd.ntiles, c->globals_dev, k, staging, label, c->stream);
+        ScopedEv ev(c, sd.kind == K_INGEST ? 2 : sd.kind == K_UPDATE ? 1 : 0);
+        launch_phase(c->recs_dev + c->rec_first[p.first + i], c->rec_stride, sd.ntiles, c->globals_dev, k, staging, label,
+                     c->stream);
       }
-    ScopedEv ev(c, 1);
-    launch_update(c->f(c->L.w), c->f(c->L.v), c->f(c->L.g), c->L.what >= 0 ? c->f(c->L.what) : nullptr,
-                  c->chunk_stage_dev, c->segs_dev, c->n_chunks, c->lr, c->m, c->globals_dev, k, c->stream);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PB_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
@@ -1150,13 +1197,11 @@ size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays) {
   tmp.labels_dev = (int32_t*)tmp.f(L.labels);
   std::vector<std::pair<int, StepDesc>> steps;
   tmp.plan = &pl;
-  compile_steps(&tmp, steps);
+  compile_steps(&tmp, steps, 0);
   if (validate_steps(&tmp, steps, pl.total) != PB_OK) return 0;
   int64_t total_tiles = 0;
   for (auto& pr : steps) total_tiles += pr.second.ntiles;
-  pl.alloc(total_tiles * (int64_t)sizeof(StepDesc) / 4 + 64);
-  pl.alloc(L.P / UPD_CHUNK + 64);
-  pl.alloc((int64_t)st.size() * sizeof(UpdSeg) / 4 + 64);
+  pl.alloc(2 * total_tiles * (int64_t)sizeof(StepDesc) / 4 + 64);
   return (size_t)pl.total * sizeof(float) + 256;
 }
 
@@ -1171,7 +1216,7 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   tmp.loss_cap = lcap;
   std::vector<std::pair<int, StepDesc>> steps;
   tmp.plan = &pl;
-  compile_steps(&tmp, steps);
+  compile_steps(&tmp, steps, 0);
   order_steps(steps);
   static const char* names[] = {"gn_stats", "gap_fwd", "conv_fwd", "post_fwd", "ce", "gnb_reduce", "gnb_apply",
                                 "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad", "ingest", "update", "head", "gn_bwd"};
@@ -1246,63 +1291,56 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   c->globals_dev = (Globals*)c->f(c->L.globals);
   c->zero_dev = (int32_t*)c->f(c->L.zero);
 
-  std::vector<std::pair<int, StepDesc>> tagged;
+  // two step tables that differ only in which copy of the parameters they read and write:
+  // ticks of parity p run table p
+  std::vector<std::pair<int, StepDesc>> tagged, tagged1;
   c->plan = &pl;
-  compile_steps(c, tagged);
-  if (validate_steps(c, tagged, pl.total) != PB_OK) { pb_destroy(c); return PB_E_INVALID; }
+  compile_steps(c, tagged, 0);
+  compile_steps(c, tagged1, 1);
+  if (validate_steps(c, tagged, pl.total) != PB_OK || validate_steps(c, tagged1, pl.total) != PB_OK) { pb_destroy(c); return PB_E_INVALID; }
   order_steps(tagged);
+  order_steps(tagged1);
   const int n_steps = (int)tagged.size();
+  if ((int)tagged1.size() != n_steps) { pb_destroy(c); return fail(PB_E_INVALID, "internal: step tables differ"); }
   c->steps.resize(n_steps);
   int n_ph = 0;
   for (auto& p : tagged) n_ph = std::max(n_ph, p.first + 1);
   c->phases.assign(n_ph, Phase());
   c->rec_first.assign(n_steps, 0);
-  std::vector<StepDesc> recs;
+  std::vector<StepDesc> recs, recs1;
   for (int i = 0, cur = -1, acc = 0; i < n_steps; ++i) {
     const int ph = tagged[i].first;
+    if (tagged1[i].first != ph || tagged1[i].second.kind != tagged[i].second.kind || tagged1[i].second.ntiles != tagged[i].second.ntiles) {
+      pb_destroy(c);
+      return fail(PB_E_INVALID, "internal: step tables differ");
+    }
     if (ph != cur) { cur = ph; acc = 0; c->phases[ph].first = i; }
     c->steps[i] = tagged[i].second;
     c->rec_first[i] = (int64_t)recs.size();
     for (int tl = 0; tl < tagged[i].second.ntiles; ++tl) {
       recs.push_back(tagged[i].second);
       recs.back().tile = tl;
+      recs1.push_back(tagged1[i].second);
+      recs1.back().tile = tl;
     }
     acc += tagged[i].second.ntiles;
     c->phases[ph].count++;
     c->phases[ph].tiles = acc;
   }
+  c->rec_stride = (int)recs.size();
+  recs.insert(recs.end(), recs1.begin(), recs1.end());
   const int64_t o_recs = pl.alloc((int64_t)recs.size() * sizeof(StepDesc) / 4 + 64);
-  c->n_chunks = (int)(c->L.P / UPD_CHUNK);
-  const int64_t o_chunk = pl.alloc(c->n_chunks + 64);
-  const int64_t o_segs = pl.alloc((int64_t)c->S * sizeof(UpdSeg) / 4 + 64);
   if ((size_t)pl.total * sizeof(float) > need) { pb_destroy(c); return fail(PB_E_NOMEM, "internal: arena plan mismatch"); }
   c->recs_dev = (StepDesc*)c->f(o_recs);
-  c->chunk_stage_dev = (int32_t*)c->f(o_chunk);
-  c->segs_dev = (UpdSeg*)c->f(o_segs);
 
-  // host-side tables
-  std::vector<int32_t> chunk_stage(c->n_chunks);
-  std::vector<UpdSeg> segs(c->S);
-  for (int s = 0; s < c->S; ++s) {
-    const Stage& a = st[s];
-    for (int64_t ch = a.off / UPD_CHUNK; ch < (a.off + a.padded) / UPD_CHUNK; ++ch) chunk_stage[ch] = s;
-    double ca = 1.0, cb = 0.0;
-    if (net->mitigation == 1 || net->mitigation == 3) sc_coeffs((double)momentum, a.D, &ca, &cb);
-    const double T = (net->mitigation >= 2) ? (double)a.D : 0.0;
-    segs[s].a = (float)ca; segs[s].b = (float)cb; segs[s].lrT = (float)((double)lr * T);
-    segs[s].first_tick = 2 * (c->S - 1) - s;
-  }
   std::vector<float> w(c->L.P, 0.f);
   init_weights_host(st, seed, w);
   Globals g0;
   memset(&g0, 0, sizeof g0);
   g0.n_pool = 1;
   INIT_TRY(hipMemcpyAsync(c->f(c->L.w), w.data(), sizeof(float) * c->L.P, hipMemcpyHostToDevice, c->stream));
-  if (c->L.what >= 0)
-    INIT_TRY(hipMemcpyAsync(c->f(c->L.what), w.data(), sizeof(float) * c->L.P, hipMemcpyHostToDevice, c->stream));
+  INIT_TRY(hipMemcpyAsync(c->f(c->L.what), w.data(), sizeof(float) * c->L.P, hipMemcpyHostToDevice, c->stream));
   INIT_TRY(hipMemcpyAsync(c->recs_dev, recs.data(), sizeof(StepDesc) * recs.size(), hipMemcpyHostToDevice, c->stream));
-  INIT_TRY(hipMemcpyAsync(c->chunk_stage_dev, chunk_stage.data(), sizeof(int32_t) * c->n_chunks, hipMemcpyHostToDevice, c->stream));
-  INIT_TRY(hipMemcpyAsync(c->segs_dev, segs.data(), sizeof(UpdSeg) * c->S, hipMemcpyHostToDevice, c->stream));
   INIT_TRY(hipMemcpyAsync(c->globals_dev, &g0, sizeof g0, hipMemcpyHostToDevice, c->stream));
   for (auto& tb : c->tables)
     INIT_TRY(hipMemcpyAsync(c->f(tb.first), tb.second.data(), sizeof(int32_t) * tb.second.size(), hipMemcpyHostToDevice, c->stream));

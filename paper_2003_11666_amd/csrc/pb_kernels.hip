@@ -27,7 +27,8 @@ __device__ __forceinline__ const gfloat* GP(const float* p) { return (const gflo
 typedef __attribute__((address_space(3))) StepDesc LDesc;
 typedef __attribute__((address_space(3))) TRef LTRef;
 typedef __attribute__((address_space(3))) GemmCfg LGemmCfg;
-#define UNI(x) __builtin_amdgcn_readfirstlane(x)   /* value is the same in every lane: keep it scalar */
+#define UNI(x) __builtin_amdgcn_readfirstlane(x)   /* integer value that is the same in every lane: keep it scalar */
+#define UNIF(x) __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x)))   /* the same for a float */
 #ifdef PB_TIMING
 __shared__ long long ts_sh[4][24];
 __device__ long long pb_ts_out[16384 * 100];
@@ -446,9 +447,20 @@ __device__ void step_gnb_apply(const LDesc& d, int tile, int t) {
   at(d.dx, t)[o] = r;
 }
 
+// The same update for one parameter (GroupNorm scale or shift updated by the
+// step that produced its gradient): w, v at index i in place, w_hat into the other copy.
+__device__ __forceinline__ void update_one(const LDesc& d, int i, float g) {
+  float vv = GP(d.v)[i], wv = GP(d.gamma)[i];
+  vv = fmaf(UNIF(d.fm), vv, g);
+  wv = fmaf(-UNIF(d.flr), fmaf(UNIF(d.fa), vv, UNIF(d.fb) * g), wv);
+  GP((float*)d.b)[i] = vv;
+  GP((float*)d.w)[i] = wv;
+  if (d.what) GP(d.what)[i] = fmaf(-UNIF(d.flrT), vv, wv);
+}
+
 // Limit of the one-workgroup GroupNorm backward: elements of a group (they
 // stay in registers together with their gradients).
-constexpr int GNB_MAX_N = 8192;
+constexpr int GNB_MAX_N = 4096;
 
 // GroupNorm (+ReLU) backward of one group in one workgroup: the group and its
 // incoming gradient are read once, in one burst, and stay in registers (thread
@@ -456,10 +468,15 @@ constexpr int GNB_MAX_N = 8192;
 // slot lies inside one channel).  Per-channel sums (dgamma, dbeta) go through
 // per-slot partial sums in LDS, then the group sums, then dx.
 // LDS: psum[n/4] | psum2[n/4] | cs[2*cpg] | cs2[3*cpg] | grp[2]
-__device__ void step_gn_bwd(const LDesc& d, int tile, int t, lfloat* smem) {
+__device__ void step_gn_bwd(const LDesc& d, int tile, int t, bool live, lfloat* smem) {
   const int tid = threadIdx.x;
   const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W), flags = UNI(d.flags);
   const int g = tile, cpg = UNI(fdiv(C, frcp(G))), n = cpg * HW, ns = n >> 2, HW4 = HW >> 2;
+  if (!live) {
+    // no gradient has reached this stage yet: carry scale and shift over to the other forward copy
+    if ((flags & F_UPD_GN) && tid < cpg) { update_one(d, g * cpg + tid, 0.f); update_one(d, C + g * cpg + tid, 0.f); }
+    return;
+  }
   const bool rl = flags & F_GN_RELU, gapd = flags & F_DU_GAP, has_skg = flags & F_ADD_SKG;
   const float ihw4 = frcp(HW4);
   lfloat* psum = smem;
@@ -526,6 +543,7 @@ __device__ void step_gn_bwd(const LDesc& d, int tile, int t, lfloat* smem) {
     if (p == 0) {
       GP(d.ggamma)[g * cpg + c] = sg; GP(d.gbeta)[g * cpg + c] = sb;
       cs2[c] = sb; cs2[cpg + c] = sg;
+      if (flags & F_UPD_GN) { update_one(d, g * cpg + c, sg); update_one(d, C + g * cpg + c, sb); }
     }
   }
   __syncthreads();
@@ -669,28 +687,50 @@ __device__ void step_ingest(const LDesc& d, int tile, int t, const Globals* __re
 }
 
 // Fused Spike-Compensated momentum update with Linear Weight Prediction of one
-// 1024-float chunk of a stage: v <- m v + g; w <- w - lr (a v + b g);
-// w_hat <- w - lr T v.
+// tile of a stage: v' = m v + g; w' = w - lr (a v' + b g);
+// w_hat' = w' - lr T v'.  The predicted weights are double-buffered by tick
+// parity: the tick's forward passes read one copy while the update writes the
+// other (d.what), so the update may run beside forward work of the same tick
+// as soon as the stage's gradients are complete.  Master weights and velocity
+// (read d.w, d.v; written d.wp, d.b) are updated in place.
 __device__ void step_update(const LDesc& d, int tile) {
-  const size_t i = (size_t)tile * (UPD_CHUNK / 4) + threadIdx.x;
-  const float a = d.fa, b = d.fb, lrT = d.flrT, lr = d.flr, m = d.fm;
-  typedef __attribute__((address_space(1))) v4f gv4;
-  const v4f gv = ((const gv4*)d.gw)[i];
-  v4f vv = ((gv4*)d.v)[i];
-  v4f wv = ((gv4*)d.w)[i];
-  vv.x = fmaf(m, vv.x, gv.x); vv.y = fmaf(m, vv.y, gv.y);
-  vv.z = fmaf(m, vv.z, gv.z); vv.w = fmaf(m, vv.w, gv.w);
-  wv.x = fmaf(-lr, fmaf(a, vv.x, b * gv.x), wv.x);
-  wv.y = fmaf(-lr, fmaf(a, vv.y, b * gv.y), wv.y);
-  wv.z = fmaf(-lr, fmaf(a, vv.z, b * gv.z), wv.z);
-  wv.w = fmaf(-lr, fmaf(a, vv.w, b * gv.w), wv.w);
-  ((gv4*)d.v)[i] = vv;
-  ((gv4*)d.w)[i] = wv;
-  if (d.what) {
-    v4f p;
-    p.x = fmaf(-lrT, vv.x, wv.x); p.y = fmaf(-lrT, vv.y, wv.y);
-    p.z = fmaf(-lrT, vv.z, wv.z); p.w = fmaf(-lrT, vv.w, wv.w);
-    ((gv4*)d.what)[i] = p;
+  // the step streams 24 bytes per parameter and nothing else: what it needs is bytes in
+  // flight, so every thread requests its 8 vectors of all three arrays before using any
+  constexpr int UU = UPD_TILE / (4 * BLK);
+  const int n4 = UNI(d.n) >> 2;
+  const int i0 = tile * (UPD_TILE / 4) + threadIdx.x;
+  const float a = UNIF(d.fa), b = UNIF(d.fb), lrT = UNIF(d.flrT), lr = UNIF(d.flr), m = UNIF(d.fm);
+  const gv4* gp = (const gv4*)d.gw;
+  const gv4* vp = (const gv4*)d.v;
+  const gv4* wp = (const gv4*)d.w;
+  v4f gv[UU], vv[UU], wv[UU];
+#pragma unroll
+  for (int u = 0; u < UU; ++u) {
+    const int i = i0 + u * BLK;
+    if (i < n4) { gv[u] = gp[i]; vv[u] = vp[i]; wv[u] = wp[i]; }
+  }
+  gv4* vo = (gv4*)(float*)d.b;
+  gv4* wo = (gv4*)(float*)d.wp;
+  gv4* ho = (gv4*)d.what;
+#pragma unroll
+  for (int u = 0; u < UU; ++u) {
+    const int i = i0 + u * BLK;
+    if (i < n4) {
+      v4f v2, w2;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v2[e] = fmaf(m, vv[u][e], gv[u][e]);
+        w2[e] = fmaf(-lr, fmaf(a, v2[e], b * gv[u][e]), wv[u][e]);
+      }
+      vo[i] = v2;
+      wo[i] = w2;
+      if (ho) {
+        v4f p;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) p[e] = fmaf(-lrT, v2[e], w2[e]);
+        ho[i] = p;
+      }
+    }
   }
 }
 
@@ -1207,7 +1247,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
 // that a single burst of scalar loads (one memory round trip) delivers all a
 // workgroup needs to know.
 __global__ void __launch_bounds__(BLK)
-k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
+k_phase(const StepDesc* __restrict__ recs, int rec_stride, const Globals* __restrict__ G, int k,
         const float* __restrict__ sample_override, int label_override) {
   __shared__ float red_[8];
   __shared__ __attribute__((aligned(16))) float smem_[LDS_FLOATS];
@@ -1226,13 +1266,15 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
   static_assert(sizeof(StepDesc) % 4 == 0 && NW <= BLK, "descriptor must fit one word per thread");
   __shared__ StepDesc sd_;
   {
-    const gint* dp = (const gint*)(recs + blockIdx.x);
+    // two record tables: parameter pointers of even and of odd ticks
+    const gint* dp = (const gint*)(recs + (size_t)(t & 1) * rec_stride + blockIdx.x);
     if (threadIdx.x < NW) ((lint*)&sd_)[threadIdx.x] = dp[threadIdx.x];
   }
   __syncthreads();
   const LDesc& d = *(const LDesc*)&sd_;
   const int tile = UNI(d.tile);
-  if (t < UNI(d.first_tick)) return;
+  const bool live = t >= UNI(d.first_tick);
+  if (!live && !(UNI(d.flags) & F_ALWAYS)) return;
   switch (UNI(d.kind)) {
     case K_GN_STATS: step_gn_stats(d, tile, t, red, smem); break;
     case K_GAP_FWD: step_gap_fwd(d, tile, t, red); break;
@@ -1249,7 +1291,7 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     case K_INGEST: step_ingest(d, tile, t, G, k, sample_override, label_override); break;
     case K_UPDATE: step_update(d, tile); break;
     case K_HEAD: step_head(d, t, red, smem); break;
-    case K_GN_BWD: step_gn_bwd(d, tile, t, smem); break;
+    case K_GN_BWD: step_gn_bwd(d, tile, t, live, smem); break;
     default: break;
   }
 #ifdef PB_TIMING
@@ -1291,36 +1333,6 @@ k_ingest(TRef ring0, int n_elems, const float* __restrict__ staging, int label,
   if (i == 0) label_ring[t % n_stages] = lab;
 }
 
-// Fused Spike-Compensated momentum update with Linear Weight Prediction over
-// the flat parameter arena: v <- m v + g; w <- w - lr (a v + b g);
-// w_hat <- w - lr T v.  Each workgroup owns UPD_CHUNK consecutive floats,
-// which belong to exactly one stage (stages are padded to the chunk size).
-__global__ void __launch_bounds__(BLK)
-k_update(float* __restrict__ w, float* __restrict__ v, const float* __restrict__ g,
-         float* __restrict__ what, const int32_t* __restrict__ chunk_stage,
-         const UpdSeg* __restrict__ segs, float lr, float m, const Globals* __restrict__ G, int k) {
-  const int t = G->t_base + k;
-  const UpdSeg sg = segs[chunk_stage[blockIdx.x]];
-  if (t < sg.first_tick) return;
-  const size_t i = (size_t)blockIdx.x * UPD_CHUNK / 4 + threadIdx.x;
-  const float4 gv = reinterpret_cast<const float4*>(g)[i];
-  float4 vv = reinterpret_cast<float4*>(v)[i];
-  float4 wv = reinterpret_cast<float4*>(w)[i];
-  vv.x = fmaf(m, vv.x, gv.x); vv.y = fmaf(m, vv.y, gv.y);
-  vv.z = fmaf(m, vv.z, gv.z); vv.w = fmaf(m, vv.w, gv.w);
-  wv.x = fmaf(-lr, fmaf(sg.a, vv.x, sg.b * gv.x), wv.x);
-  wv.y = fmaf(-lr, fmaf(sg.a, vv.y, sg.b * gv.y), wv.y);
-  wv.z = fmaf(-lr, fmaf(sg.a, vv.z, sg.b * gv.z), wv.z);
-  wv.w = fmaf(-lr, fmaf(sg.a, vv.w, sg.b * gv.w), wv.w);
-  reinterpret_cast<float4*>(v)[i] = vv;
-  reinterpret_cast<float4*>(w)[i] = wv;
-  if (what) {
-    float4 p;
-    p.x = fmaf(-sg.lrT, vv.x, wv.x); p.y = fmaf(-sg.lrT, vv.y, wv.y);
-    p.z = fmaf(-sg.lrT, vv.z, wv.z); p.w = fmaf(-sg.lrT, vv.w, wv.w);
-    reinterpret_cast<float4*>(what)[i] = p;
-  }
-}
 
 // Same arithmetic over plain arrays with one coefficient set.
 __global__ void __launch_bounds__(BLK)
@@ -1358,10 +1370,11 @@ __global__ void k_advance(Globals* G, int dt, int didx) {
 }
 
 // --------------------------------------------------------- launch wrappers
-void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, const float* sample_override,
-                  int label_override, hipStream_t s) {
+void launch_phase(const StepDesc* recs_dev, int rec_stride, int total_tiles, const Globals* G, int k,
+                  const float* sample_override, int label_override, hipStream_t s) {
   if (total_tiles <= 0) return;
-  hipLaunchKernelGGL(k_phase, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, G, k, sample_override, label_override);
+  hipLaunchKernelGGL(k_phase, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, rec_stride, G, k, sample_override,
+                     label_override);
 }
 
 void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,
@@ -1370,12 +1383,6 @@ void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int
                      staging, label, label_ring, n_stages, G, k);
 }
 
-void launch_update(float* w, float* v, const float* g, float* what, const int32_t* chunk_stage,
-                   const UpdSeg* segs, int n_chunks, float lr, float m, const Globals* G, int k,
-                   hipStream_t s) {
-  hipLaunchKernelGGL(k_update, dim3(n_chunks), dim3(BLK), 0, s, w, v, g, what, chunk_stage, segs, lr,
-                     m, G, k);
-}
 
 void launch_update_flat(float* w, float* v, const float* g, float* what, int64_t n, float lr, float m,
                         float a, float b, float lrT, hipStream_t s) {
