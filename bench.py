@@ -17,6 +17,8 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# measured HBM bytes per algorithmic byte of the update kernel (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)
+UPDATE_TRAFFIC_PER_ALGORITHMIC_BYTE = 1.0
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 
 
@@ -66,6 +68,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-standalone", action="store_true")
     ap.add_argument("--launch-mode", type=int, default=0, help="1 = one launch per step (profiling aid)")
+    ap.add_argument("--no-step-profile", action="store_true",
+                    help="skip the pass that launches every step on its own (keeps a kernel trace of this run clean)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the pipeline on ONE GPU only; --gpus must be 1 "
@@ -104,18 +108,21 @@ def main():
     eng.profile_begin(64 * prof_ticks)
     eng.run_resident(xd, yd, warm + args.steps, prof_ticks)
     n_ph, ms_ph = eng.profile_end(0)
-    eng.set_launch_mode(1)
-    prof2 = min(args.steps, 200)
-    eng.profile_begin(512 * prof2)
-    eng.run_resident(xd, yd, warm + args.steps + prof_ticks, prof2)
-    n_upd, ms_upd = eng.profile_end(1)
-    n_in, ms_in = eng.profile_end(2)
+    prof2 = 0 if args.no_step_profile else min(args.steps, 200)
+    n_upd = n_in = 0
+    ms_upd = ms_in = 0.0
+    if prof2:
+        eng.set_launch_mode(1)
+        eng.profile_begin(512 * prof2)
+        eng.run_resident(xd, yd, warm + args.steps + prof_ticks, prof2)
+        n_upd, ms_upd = eng.profile_end(1)
+        n_in, ms_in = eng.profile_end(2)
     eng.set_launch_mode(args.launch_mode)
     # update steps of one tick (one launch per stage in this mode): 24 B per parameter
     # (w, v, g read; w, v, w_hat written)
     upd_us_tick = 1e3 * ms_upd / max(prof2, 1)
     upd_bytes = 24 * n_params
-    upd_gbs = upd_bytes / (upd_us_tick * 1e-6) / 1e9
+    upd_gbs = upd_bytes / (upd_us_tick * 1e-6) / 1e9 if prof2 else None
     # the dominant kernel: k_phase, all steps of a phase in one launch
     tick_bytes = tick_algorithmic_bytes(net, n_params)
     ph_us_tick = 1e3 * ms_ph / prof_ticks
@@ -138,7 +145,8 @@ def main():
                      "avg_launch_us": ph_us_tick / launches, "launches_per_tick": launches,
                      "algorithmic_bytes_per_launch": tick_bytes / launches},
         "update_in_tick": {"kernel": "k_phase, update steps only (one launch per stage)", "bound": "hbm",
-                           "achieved": upd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": upd_gbs / HBM_PEAK_GBS,
+                           "achieved": upd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": upd_gbs / HBM_PEAK_GBS if prof2 else None,
                            "us_per_tick": upd_us_tick, "launches_per_tick": n_upd / max(prof2, 1),
                            "algorithmic_bytes_per_tick": upd_bytes},
         "tick_roofline": {"bound": "hbm", "algorithmic_bytes": tick_bytes,
@@ -165,8 +173,13 @@ def main():
         torch.cuda.synchronize()
         us = 1e3 * e0.elapsed_time(e1) / reps
         gbs = 24 * n / (us * 1e-6) / 1e9
-        out["update_standalone"] = {"elements": n, "bytes": 24 * n, "avg_launch_us": us, "achieved_GBs": gbs,
-                                    "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+        out["update_standalone"] = {"kernel": "k_update_flat (the update step's arithmetic over plain arrays)",
+                                    "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                    "frac": gbs / HBM_PEAK_GBS, "elements": n, "avg_launch_us": us,
+                                    "algorithmic_bytes_per_launch": 24 * n,
+                                    # FETCH_SIZE + WRITE_SIZE of this kernel at this size, each scaled by what the
+                                    # counter reads for a plain copy: profiles/k_update_flat_1GiB_arrays.md
+                                    "traffic": UPDATE_TRAFFIC_PER_ALGORITHMIC_BYTE * 24 * n}
         del w, v, g, wh
 
     if not args.no_cpu_baseline:

@@ -138,14 +138,17 @@ int64_t pb_num_params(const pb_ctx* ctx);
 int64_t pb_num_ticks(const pb_ctx* ctx);
 
 /* Launch policy: 0 = one launch per pipeline phase (default), 1 = one launch
- * per step of every stage (debugging aid; same arithmetic, same results). */
+ * per step of every stage, update steps included (profiling and debugging
+ * aid; same records, same arithmetic, bit-identical results). */
 int pb_set_launch_mode(pb_ctx* ctx, int32_t mode);
 
 /* Kernel timing with HIP events on the context's stream.  pb_profile_begin
  * starts recording every launch of the following ticks (at most `max_events`
  * launches), pb_profile_end synchronises and returns, for kernel class
- * `which` (0 stage phases, 1 fused update, 2 ingest), the number of launches
- * recorded and their total milliseconds. */
+ * `which`, the number of launches recorded and their total milliseconds.
+ * Classes: 0 = phase launches (launch mode 0) or forward / backward steps
+ * (launch mode 1); 1 = update steps and 2 = ingest, both recorded separately
+ * only in launch mode 1. */
 int pb_profile_begin(pb_ctx* ctx, int32_t max_events);
 int pb_profile_end(pb_ctx* ctx, int32_t which, int64_t* n_launches, double* total_ms);
 
