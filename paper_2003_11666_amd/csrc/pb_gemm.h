@@ -399,7 +399,8 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
   const int M = UNI(d.g.M), N = UNI(d.g.N);
   gfloat* out = (GM == 1) ? at(d.y, t) : (GM == 2) ? at(d.dx, t) : GP(d.gw);
   const int mrow = m0 + wm_id * 16 + 4 * kq;
-  const bool extras = (GM == 1 && (flags & (F_BIAS | F_SKIP))) || (GM == 2 && (flags & (F_MASK_X | F_ADD_SKG)));
+  const bool extras = (GM == 1 && (flags & (F_BIAS | F_SKIP))) || (GM == 2 && (flags & (F_MASK_X | F_ADD_SKG))) ||
+                      (GM != 3 && (flags & F_BF16_OUT));
   if (!extras) {
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
@@ -437,7 +438,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
       if (mrow + r < M) {
         float v = acc[j][r];
         if (GM == 2 && !(msk[r] > 0.f)) v = 0.f;
-        out[(size_t)(mrow + r) * N + n] = v + add[r];
+        out[(size_t)(mrow + r) * N + n] = rbf_if(GM != 3 && (flags & F_BF16_OUT), v + add[r]);
       }
   }
 }

@@ -67,7 +67,8 @@ int parse_net(const pb_net_desc* net, std::vector<Stage>& out) {
     return fail(PB_E_INVALID, "bad input dimensions");
   if (net->mitigation < 0 || net->mitigation > 3) return fail(PB_E_INVALID, "mitigation must be 0..3");
   if (net->bwd_weights != 0) return fail(PB_E_UNSUPPORTED, "bwd_weights=%d (weight stashing) not implemented", net->bwd_weights);
-  if (net->act_dtype != 0) return fail(PB_E_UNSUPPORTED, "act_dtype=%d not implemented", net->act_dtype);
+  if (net->act_dtype != 0 && net->act_dtype != 1) return fail(PB_E_INVALID, "act_dtype=%d", net->act_dtype);
+  if (net->act_dtype == 1 && net->kernel_set != 0) return fail(PB_E_UNSUPPORTED, "bf16 activations need kernel_set 0");
   if (net->kernel_set < 0 || net->kernel_set > 1) return fail(PB_E_INVALID, "kernel_set must be 0 or 1");
   const int S = net->n_stages;
   out.assign(S, Stage());
@@ -286,6 +287,7 @@ struct pb_ctx {
   int64_t ticks = 0;
   int launch_mode = 0;
   int kernel_set = 0;
+  bool bf16 = false;   // bf16 activation mode: tensors that cross a stage boundary are rounded to bf16
   std::vector<StepDesc> steps;         // sorted by phase
   std::vector<int64_t> rec_first;      // per step: index of its first per-workgroup record
   Plan* plan = nullptr;                // arena allocator while the step table is compiled
@@ -554,6 +556,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
       d.dx = x_f;
       d.labels = c->labels_dev;
       d.ntiles = cdiv(d.n, BLK);
+      if (c->bf16) d.flags |= F_BF16_OUT;
       out.push_back({0, d});
       ph = 1;
     }
@@ -579,6 +582,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
       d.loss_log = c->f(L.loss);
       d.labels = c->labels_dev;
       d.ntiles = 1;
+      if (c->bf16) d.flags |= F_BF16_OUT;
       out.push_back({0, d});
       continue;
     }
@@ -634,6 +638,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
         }
       }
       d.ntiles = cdiv((int64_t)a.K * a.OH * a.OW, BLK);
+      if (c->bf16 && !a.ce) d.flags |= F_BF16_OUT;   // the logits of the loss stage stay unrounded
       if (c->kernel_set == 0) {
         GemmCfg g, gp;
         memset(&gp, 0, sizeof gp);
@@ -661,6 +666,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
       e.x = d.x; e.st = d.st; e.y = y_out;
       if (a.pool) { e.flags |= F_POOL; e.pk = a.pk; e.ps = a.ps; e.pp = a.pp; e.PH = a.PH; e.PW = a.PW; }
       e.ntiles = cdiv(a.out_elems(), BLK);
+      if (c->bf16) e.flags |= F_BF16_OUT;
       out.push_back({ph++, e});
     }
     if (a.ce) {
@@ -755,6 +761,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
         d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
         if (a.pre_relu) { d.flags |= F_MASK_X; d.x = x_b; }
         if (a.tap_dist) { d.flags |= F_ADD_SKG; d.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
+        if (c->bf16) d.flags |= F_BF16_OUT;          // this gradient leaves the stage
       }
       d.ntiles = cdiv((int64_t)a.C * a.H * a.W, BLK);
       GemmCfg g;
@@ -788,6 +795,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
         e.dy = dy_src;
         e.w = wb + a.o_wp;
         e.dx = skg_w;
+        if (c->bf16) e.flags |= F_BF16_OUT;
         e.ntiles = cdiv(ta.in_elems(), BLK);
         GemmCfg g2;
         if (c->kernel_set == 0 && make_gemm(2, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, 0, nullptr, &g2, true)) {
@@ -816,6 +824,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
       d.part = c->f(b.part);
       if (c->kernel_set == 0 && gn_bwd_fits(d.C, d.H * d.W, d.G)) {
         d.kind = K_GN_BWD;
+        if (c->bf16) d.flags |= F_BF16_OUT;
         if (s > 0) {
           d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
           if (a.tap_dist) { d.flags |= F_ADD_SKG; d.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
@@ -837,6 +846,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
         if (s > 0) {
           StepDesc e = d;
           e.kind = K_GNB_APPLY;
+          if (c->bf16) e.flags |= F_BF16_OUT;
           e.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
           if (a.tap_dist) { e.flags |= F_ADD_SKG; e.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
           e.ntiles = cdiv(a.in_elems(), BLK);
@@ -915,6 +925,8 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
   int idx = 0;
   for (const auto& pr : steps) {
     const StepDesc& d = pr.second;
+    if (c->bf16 && (d.kind == K_CONV_FWD || d.kind == K_CONV_BWD_X))
+      return fail(PB_E_UNSUPPORTED, "bf16 activations: stage %d has a layer the GEMM tiling cannot place", d.stage);
     const int64_t in = (int64_t)d.C * d.H * d.W, outn = (int64_t)d.K * d.OH * d.OW;
     const int64_t stn = 2 * d.G + 2 * d.C;
     bool ok = d.ntiles > 0;
@@ -1188,6 +1200,7 @@ size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays) {
   pb_ctx tmp;
   tmp.st = st; tmp.S = (int)st.size();
   tmp.kernel_set = net->kernel_set;
+  tmp.bf16 = net->act_dtype == 1;
   const int cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   Plan pl;
   Layout L;
@@ -1209,7 +1222,7 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   std::vector<Stage> st;
   if (parse_net(net, st) != PB_OK) return PB_E_INVALID;
   pb_ctx tmp;
-  tmp.st = st; tmp.S = (int)st.size(); tmp.kernel_set = net->kernel_set;
+  tmp.st = st; tmp.S = (int)st.size(); tmp.kernel_set = net->kernel_set; tmp.bf16 = net->act_dtype == 1;
   const int lcap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   Plan pl;
   plan_arena(st, net->mitigation >= 2, lcap, tmp.L, pl, net->kernel_set == 0);
@@ -1262,6 +1275,7 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   c->st = st; c->S = (int)st.size();
   c->mitigation = net->mitigation; c->lr = lr; c->m = momentum;
   c->kernel_set = net->kernel_set;
+  c->bf16 = net->act_dtype == 1;
   c->loss_cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   c->stream = (hipStream_t)net->stream;
   for (const Stage& a : st) c->n_params += a.n_params;

@@ -44,6 +44,15 @@ __device__ int pb_ts_tick;
 __device__ __forceinline__ float frcp(int d) { return __builtin_amdgcn_rcpf((float)d); }
 __device__ __forceinline__ int fdiv(int n, float inv) { return (int)(((float)n + 0.5f) * inv); }
 
+// Round to the nearest bf16 value (ties to even), kept in a float.  bf16 activation mode rounds
+// every tensor that crosses a stage boundary or is kept for the backward pass.
+__device__ __forceinline__ float rbf(float x) {
+  unsigned u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return __uint_as_float(u & 0xFFFF0000u);
+}
+__device__ __forceinline__ float rbf_if(bool on, float x) { return on ? rbf(x) : x; }
+
 __device__ __forceinline__ gfloat* at(const LTRef& r, int t) {
   const int depth = UNI(r.depth), stride = UNI(r.stride), lag = UNI(r.lag);
   int slot = (t - lag) % depth;
@@ -283,12 +292,12 @@ __device__ void step_post_fwd(const LDesc& d, int tile, int t) {
         best = fmaxf(best, fmaxf(fmaf(sc, zc[ih * d.W + iw], sh), 0.f));
       }
     }
-    y[o] = best;
+    y[o] = rbf_if(d.flags & F_BF16_OUT, best);
   } else {
     const int o = tile * BLK + threadIdx.x;
     if (o >= d.C * HW) return;
     const int c = o / HW;
-    y[o] = fmaxf(fmaf(st[2 * d.G + c], z[o], st[2 * d.G + d.C + c]), 0.f);
+    y[o] = rbf_if(d.flags & F_BF16_OUT, fmaxf(fmaf(st[2 * d.G + c], z[o], st[2 * d.G + d.C + c]), 0.f));
   }
 }
 
@@ -444,7 +453,7 @@ __device__ void step_gnb_apply(const LDesc& d, int tile, int t) {
   const float inv_n = 1.0f / (float)n;
   float r = rstd * (du * GP(d.part)[2 * d.C + c] - S1 * inv_n - xh * (S2 * inv_n));
   if (d.flags & F_ADD_SKG) r += at(d.skg, t)[o];
-  at(d.dx, t)[o] = r;
+  at(d.dx, t)[o] = rbf_if(d.flags & F_BF16_OUT, r);
 }
 
 // The same update for one parameter (GroupNorm scale or shift updated by the
@@ -569,7 +578,7 @@ __device__ void step_gn_bwd(const LDesc& d, int tile, int t, bool live, lfloat* 
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float xh = (xr[u][e] - mean) * rstd;
-          o[e] = rstd * (du[u][e] * gm - m1 - xh * m2) + sk[u][e];
+          o[e] = rbf_if(flags & F_BF16_OUT, rstd * (du[u][e] * gm - m1 - xh * m2) + sk[u][e]);
         }
         *(gv4*)(dx + 4 * sl) = o;
       }
@@ -682,7 +691,7 @@ __device__ void step_ingest(const LDesc& d, int tile, int t, const Globals* __re
   }
   gfloat* dst = at(d.dx, t);
   const int i = tile * BLK + threadIdx.x;
-  if (i < d.n) dst[i] = src[i];
+  if (i < d.n) dst[i] = rbf_if(d.flags & F_BF16_OUT, src[i]);
   if (i == 0) ((gint*)d.labels)[t % d.n_stages] = lab;
 }
 
@@ -989,7 +998,7 @@ __device__ void step_head_gap4(const LDesc& d, int t, lfloat* smem) {
           float du = dug;
           if (rl && !(fmaf(sc, xr[u][e], sh) > 0.f)) du = 0.f;
           const float xh = (xr[u][e] - mean) * rstd;
-          o[e] = rstd * (du - m1 - xh * m2);
+          o[e] = rbf_if(flags & F_BF16_OUT, rstd * (du - m1 - xh * m2));
         }
         *(gv4*)(dx + 4 * sl) = o;
       }
@@ -1196,7 +1205,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
   gfloat* dx = d.dx.base ? at(d.dx, t) : nullptr;
   if (!gn) {
     // dvec[i] was written by this thread
-    for (int i = tid; i < Cv; i += BLK) { float r = dvec[i]; if (rl && !(xs[i] > 0.f)) r = 0.f; dx[i] = r; }
+    for (int i = tid; i < Cv; i += BLK) { float r = dvec[i]; if (rl && !(xs[i] > 0.f)) r = 0.f; dx[i] = rbf_if(flags & F_BF16_OUT, r); }
     return;
   }
   __syncthreads();
@@ -1237,7 +1246,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
     float du = gap ? dvec[c] / (float)HW : dvec[o];
     if (rl && !(fmaf(sc, xv, sh) > 0.f)) du = 0.f;
     const float xh = (xv - mean) * rstd;
-    dx[o] = rstd * (du * chan[6 * C + c] - grp[g] * inv_n - xh * (grp[G + g] * inv_n));
+    dx[o] = rbf_if(flags & F_BF16_OUT, rstd * (du * chan[6 * C + c] - grp[g] * inv_n - xh * (grp[G + g] * inv_n)));
   }
 }
 

@@ -72,10 +72,11 @@ def perturbed_oracle(net, seed, mitigation, eps, gen_seed=12345, lr=None):
     return orc
 
 
-def run_parity(engine_cls, net, K, mitigation=3, seed=42, every=1, engine_kwargs=None, verbose=False, lr=None):
+def run_parity(engine_cls, net, K, mitigation=3, seed=42, every=1, engine_kwargs=None, verbose=False, lr=None,
+               perturb=PERTURB):
     xs, ys = W.sample_pool(net)
     orc = O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr)
-    orcs = [perturbed_oracle(net, seed, mitigation, e, 12345 + i, lr=lr) for i, e in enumerate(PERTURB)]
+    orcs = [perturbed_oracle(net, seed, mitigation, e, 12345 + i, lr=lr) for i, e in enumerate(perturb)]
     eng = engine_cls(net, seed=seed, mitigation=mitigation, lr=lr, **(engine_kwargs or {}))
     slices = tensor_slices(net)
     w0 = eng.read_weights()

@@ -120,3 +120,36 @@ def test_reference_kernel_set_matches_too():
     net = W.config("small_resnet")
     res = run_parity(_engine(), net, 60, engine_kwargs=dict(kernel_set=1))
     _check(res, 60, len(net["stages"]))
+
+
+@pytest.mark.parametrize("name", ["tiny_vgg", "tiny_resnet", "tiny_bottleneck"])
+def test_bf16_activation_mode(name):
+    """Tensors that cross a stage boundary are rounded to bf16 (both sides round
+    to nearest even).  A rounding boundary is one more decision taken on a
+    floating-point value, and there are thousands of them per tick: a value
+    that fp32 and fp64 arithmetic place on different sides of a boundary moves
+    one activation by 2^-8 relative, far above 1e-5.  The reference oracles are
+    therefore perturbed by 3e-6 and 1e-5 here (an order of magnitude above the
+    fp32-vs-fp64 difference), so that they meet such events at least as often
+    as the library does, and the tolerance is 4x their own disagreement from
+    the first tick on.  A dropped rounding site or a wrong rounding mode
+    shifts every element of a tensor by up to 2^-9 relative at every tick and
+    is far outside that."""
+    net = dict(W.config(name))
+    net["act_dtype"] = "bf16"
+    K = 60
+    res = run_parity(_engine(), net, K, mitigation=3, perturb=(3e-6, 1e-5))
+    _check(res, K, len(net["stages"]))
+    # and it is not the fp32 path: the trajectories differ from the fp32 run
+    PBEngine = _engine()
+    xs, ys = W.sample_pool(net)
+    outs = []
+    for dt in ("fp32", "bf16"):
+        n2 = dict(net); n2["act_dtype"] = dt
+        e = PBEngine(n2)
+        for t in range(30):
+            e.tick(xs[t % len(ys)], ys[t % len(ys)])
+        outs.append(e.read_weights())
+        e.close()
+    assert not np.array_equal(outs[0], outs[1])
+    assert np.abs(outs[0] - outs[1]).max() > 1e-4
