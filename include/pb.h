@@ -82,7 +82,8 @@ typedef struct {
   int32_t n_classes;
   int32_t mitigation;         /* 0 plain delayed SGDM, 1 SC_D, 2 LWP^v_D, 3 SC_D + LWP^v_D */
   int32_t bwd_weights;        /* 0 backward pass uses current weights (the paper's PB)      */
-  int32_t act_dtype;          /* 0 fp32 activations                                         */
+  int32_t act_dtype;          /* 0 fp32 activations; 1 bf16: tensors that cross a stage boundary are
+                                 rounded to bf16 (nearest even) by the step that writes them      */
   int32_t loss_capacity;      /* losses kept (most recent); 0 = 1<<20                       */
   int32_t kernel_set;         /* 0 tiled MFMA kernels (default), 1 plain direct kernels     */
   void* device_arena;         /* DEVICE memory owned by the caller (>= pb_arena_bytes, 256-byte
@@ -96,10 +97,14 @@ typedef struct {
 size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays);
 
 /* Build a context.  delays: n_stages entries or NULL for the pipeline's own
- * D^s = 2(S-1-s) (Eq. wf); other values are rejected with PB_E_UNSUPPORTED
- * (they cannot be produced by a pipeline that never stalls).  Weights are
- * initialised on the host from `seed` (Kaiming normal, std sqrt(2/fan_in),
- * biases 0, GroupNorm scale 1 / shift 0) and uploaded; velocity starts at 0.
+ * D^s = 2(S-1-s) (Eq. wf).  delays[s] > 2(S-1-s): the forward pass of stage s
+ * uses predicted weights that many updates old, read from a ring of
+ * delays[s] - 2(S-1-s) + 2 weight versions per stage (more device memory:
+ * ask pb_arena_bytes with the same delays), and SC / LWP use delays[s] as the
+ * stage's delay.  delays[s] < 2(S-1-s) is rejected with PB_E_UNSUPPORTED: a
+ * pipeline that never stalls cannot produce it.  Weights are initialised on
+ * the host from `seed` (Kaiming normal, std sqrt(2/fan_in), biases 0,
+ * GroupNorm scale 1 / shift 0) and uploaded; velocity starts at 0.
  * The descriptor is copied; the caller may free it afterwards. */
 int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float lr, float momentum,
             uint64_t seed);

@@ -67,6 +67,10 @@ struct GemmCfg {
   int32_t xoff;            // LDS column of logical patch column 0
 };
 
+// Pointer fields of a step that point into slot 0 of the stage's ring of predicted-weight versions;
+// k_phase moves them to the slot of the tick before the step runs.
+enum ParamField : int32_t { PF_W = 1, PF_B = 2, PF_WP = 4, PF_GAMMA = 8, PF_BETA = 16, PF_WHAT = 32 };
+
 enum StepFlags : int32_t {
   F_PRE_AFFINE = 1,   // input is sc[c]*x + sh[c] (GroupNorm folded into the load)
   F_PRE_RELU = 2,     // then max(.,0)
@@ -98,7 +102,8 @@ struct StepDesc {
   int32_t n;                // generic element count (CE: classes, COPY: floats)
   int32_t loss_cap, n_stages;
   float fa, fb, flrT, flr, fm;   // K_UPDATE: SC coefficients a, b, lr*T, lr, momentum
-  int32_t pad0_;
+  int32_t pmask;            // which pointer fields address the stage's ring of predicted weights (PF_* bits)
+  int32_t pdepth, plag, pstride, pad1_;   // that ring: slots, lag of the slot this step uses, floats per slot
   GemmCfg g;     // main operand set of a K_GEMM step
   GemmCfg gp;    // projection of the skip tensor accumulated into the same tile (forward only)
   TRef x;        // op input (forward) / saved input (backward)
@@ -140,8 +145,8 @@ struct Globals {
 };
 
 // ---- launch wrappers implemented in pb_kernels.hip ----
-void launch_phase(const StepDesc* recs_dev, int rec_stride, int total_tiles, const Globals* G, int k,
-                  const float* sample_override, int label_override, hipStream_t s);
+void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, const float* sample_override,
+                  int label_override, hipStream_t s);
 void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,
                    int n_stages, const Globals* G, int k, hipStream_t s);
 void launch_update_flat(float* w, float* v, const float* g, float* what, int64_t n, float lr, float m,

@@ -49,7 +49,8 @@ struct Stage {
   int Cout = 0, Hout = 0, Wout = 0;   // stage output
   int skip_from = -1, sstride = 1, sC = 0, sH = 0, sW = 0;
   int tap_dist = 0;                // >0: a later stage (this + tap_dist) adds this stage's input
-  int D = 0;
+  int D = 0;        // natural delay 2(S-1-s): ticks between the stage's forward and backward pass of a sample
+  int De = 0;       // delay the caller asks for (>= D): the forward pass uses weights that many updates old
   // parameter offsets in the padded flat arena (floats), -1 = absent
   int64_t off = 0, padded = 0, n_params = 0, n_head = 0;
   int64_t o_w = -1, o_b = -1, o_wp = -1, o_gamma = -1, o_beta = -1;
@@ -79,6 +80,7 @@ int parse_net(const pb_net_desc* net, std::vector<Stage>& out) {
     if (ps.n_ops <= 0 || !ps.ops) return fail(PB_E_INVALID, "stage %d has no ops", s);
     st.Cin = C; st.Hin = H; st.Win = W;
     st.D = 2 * (S - 1 - s);
+    st.De = st.D;
     int i = 0;
     const int n = ps.n_ops;
     auto kind = [&](int j) { return j < n ? ps.ops[j].kind : -1; };
@@ -189,12 +191,18 @@ int parse_net(const pb_net_desc* net, std::vector<Stage>& out) {
   return PB_OK;
 }
 
-int check_delays(const std::vector<Stage>& st, const int32_t* delays) {
+// delays[s] = the pipeline's own 2(S-1-s): depth-2 ring of predicted weights (one being read, one being
+// written).  Larger: the forward pass reads a version that many updates older, kept in a deeper ring.
+// Smaller: a pipeline that never stalls cannot produce it (stage s+1 would need stage s's output of the
+// same tick).
+int check_delays(std::vector<Stage>& st, const int32_t* delays) {
   if (!delays) return PB_OK;
   for (size_t s = 0; s < st.size(); ++s) {
     if (delays[s] < 0) return fail(PB_E_INVALID, "delay of stage %zu is negative", s);
-    if (delays[s] != st[s].D)
-      return fail(PB_E_UNSUPPORTED, "delay %d of stage %zu differs from the pipeline's 2(S-1-s)=%d", delays[s], s, st[s].D);
+    if (delays[s] < st[s].D)
+      return fail(PB_E_UNSUPPORTED, "delay %d of stage %zu is below the pipeline's 2(S-1-s)=%d", delays[s], s, st[s].D);
+    if (delays[s] - st[s].D > 4096) return fail(PB_E_UNSUPPORTED, "delay %d of stage %zu: more than 4096 extra weight versions", delays[s], s);
+    st[s].De = delays[s];
   }
   return PB_OK;
 }
@@ -218,7 +226,8 @@ struct StageBufs {
 
 struct Layout {
   int64_t P = 0;                      // padded parameter count
-  int64_t w = 0, v = 0, g = 0, what = -1;
+  int64_t w = 0, v = 0, g = 0;
+  std::vector<int64_t> what;          // per stage: ring [De - D + 2][padded] of predicted-weight versions
   std::vector<StageBufs> sb;
   int64_t staging = 0, labels = 0, loss = 0, globals = 0, zero = 0;
   int64_t total = 0;
@@ -230,13 +239,15 @@ void plan_arena(const std::vector<Stage>& st, bool lwp, int loss_cap, Layout& L,
   const int S = (int)st.size();
   L.P = 0;
   for (const Stage& s : st) L.P += s.padded;
-  // The forward (predicted) weights exist twice: copy p is read by the forward passes of ticks of
-  // parity p while the updates of that tick write the other copy, so an update may run beside
-  // forward work of its own tick.  Master weights and velocity are updated in place: their only
-  // readers in a tick (the stage's backward steps) come before the stage's update.  Without weight
-  // prediction the forward copy simply equals the master weights.
+  // The forward (predicted) weights are kept as a ring of versions per stage: the update of tick t
+  // writes slot (t+1) mod R, the forward pass of tick t reads slot (t - extra) mod R, extra = De - D,
+  // R = extra + 2.  With the pipeline's own delays that is two copies alternating by tick parity, which
+  // is what lets an update run beside forward work of its own tick.  Master weights and velocity are
+  // updated in place: their only readers in a tick (the stage's backward steps) come before the
+  // stage's update.  Without weight prediction the forward copy simply equals the master weights.
   L.w = pl.alloc(L.P); L.v = pl.alloc(L.P); L.g = pl.alloc(L.P);
-  L.what = pl.alloc(2 * L.P);
+  L.what.assign(S, 0);
+  for (int s = 0; s < S; ++s) L.what[s] = pl.alloc((int64_t)(st[s].De - st[s].D + 2) * st[s].padded);
   (void)lwp;
   L.sb.assign(S, StageBufs());
   for (int s = 0; s < S; ++s) {
@@ -292,10 +303,7 @@ struct pb_ctx {
   std::vector<int64_t> rec_first;      // per step: index of its first per-workgroup record
   Plan* plan = nullptr;                // arena allocator while the step table is compiled
   std::vector<std::pair<int64_t, std::vector<int32_t>>> tables;   // (arena offset, contents) of the GEMM offset tables
-  std::vector<std::pair<int64_t, int64_t>> table_offs;            // per gemm_tables call: offsets of its two tables
-  size_t table_cursor = 0;
   std::vector<Phase> phases;
-  int rec_stride = 0;   // records per step table (there are two, one per tick parity)
   // device views
   StepDesc* recs_dev = nullptr;        // one descriptor copy per workgroup, in launch order
   Globals* globals_dev = nullptr;
@@ -469,16 +477,9 @@ void gemm_tables(pb_ctx* c, const GemmCfg& g, int C, int H, int W, int K, int OH
     else if (g.gm == 2) { const int ih = i / W, iw = i % W; n[i] = ih * g.Wp + iw; }
     else { const int ci = i / kk, tap = i % kk, kh = tap / k, kw = tap % k; n[i] = ci * PRW + kh * g.Wp + kw; }
   }
-  int64_t oq, on;
-  if (c->table_cursor < c->table_offs.size()) {          // second record table: the tables exist already
-    oq = c->table_offs[c->table_cursor].first; on = c->table_offs[c->table_cursor].second;
-  } else {
-    oq = c->plan->alloc((int64_t)q.size()); on = c->plan->alloc((int64_t)n.size());
-    c->table_offs.push_back({oq, on});
-    c->tables.push_back({oq, std::move(q)});
-    c->tables.push_back({on, std::move(n)});
-  }
-  ++c->table_cursor;
+  const int64_t oq = c->plan->alloc((int64_t)q.size()), on = c->plan->alloc((int64_t)n.size());
+  c->tables.push_back({oq, std::move(q)});
+  c->tables.push_back({on, std::move(n)});
   *tq = (const int32_t*)c->f(oq);
   *tn = (const int32_t*)c->f(on);
   (void)C; (void)H; (void)K; (void)OH;
@@ -504,8 +505,8 @@ bool head_fits(int C, int HW, int K, bool gap, int G) {
 // Coefficients of the stage's update (Eqs. gscv, gscw, scd, lwp_v_form) by mitigation mode.
 void set_update_coeffs(const pb_ctx* c, const Stage& a, StepDesc* d) {
   double ca = 1.0, cb = 0.0;
-  if (c->mitigation == 1 || c->mitigation == 3) sc_coeffs((double)c->m, a.D, &ca, &cb);
-  const double T = (c->mitigation >= 2) ? (double)a.D : 0.0;
+  if (c->mitigation == 1 || c->mitigation == 3) sc_coeffs((double)c->m, a.De, &ca, &cb);
+  const double T = (c->mitigation >= 2) ? (double)a.De : 0.0;
   d->fa = (float)ca; d->fb = (float)cb; d->flrT = (float)((double)c->lr * T); d->flr = c->lr; d->fm = c->m;
 }
 
@@ -525,9 +526,8 @@ bool gn_bwd_fits(int C, int HW, int G) {
 // one stage are independent inside a tick (they work on different samples and
 // read the start-of-tick weights), except for the last stage whose backward
 // pass consumes the loss gradient of the same tick.
-void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int parity) {
+void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   const int S = c->S;
-  c->table_cursor = 0;
   // all stages run concurrently: aim at a few workgroups per compute unit over
   // the whole phase rather than per step
   g_tile_target = std::max(4, std::min(32, 1024 / (3 * S)));
@@ -537,10 +537,16 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
     const Stage& a = c->st[s];
     const StageBufs& b = L.sb[s];
     const int D = a.D;
-    // the copy of the forward parameters that ticks of this parity read, and the one their updates write
-    const int64_t rd = parity * L.P + a.off, wr = (1 - parity) * L.P + a.off;
-    const float* wf = c->f(L.what + rd);                    // forward (predicted) parameters
+    // slot 0 of the stage's ring of predicted weights; steps that read or write it carry a mask of the
+    // pointer fields that k_phase has to move to the slot of the tick
+    const float* wf = c->f(L.what[s]);                      // forward (predicted) parameters
     const float* wb = c->f(L.w + a.off);                    // backward (current) parameters
+    auto fwd_params = [&](StepDesc& d, int mask) {
+      d.pmask = mask; d.pdepth = a.De - a.D + 2; d.plag = a.De - a.D; d.pstride = (int)a.padded;
+    };
+    auto writes_what = [&](StepDesc& d) {
+      d.pmask = PF_WHAT; d.pdepth = a.De - a.D + 2; d.plag = -1; d.pstride = (int)a.padded;
+    };
     float* gr = c->f(L.g + a.off);
     const int t_f = s, t_b = 2 * (S - 1) - s;
     const TRef x_f = ring(c, b.xring, D + 2, a.in_elems(), 0);
@@ -578,6 +584,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
         d.skip.base = const_cast<float*>(wb + a.o_gamma);
         d.ggamma = gr + a.o_gamma; d.gbeta = gr + a.o_beta;
       }
+      fwd_params(d, PF_W | (a.has_bias ? PF_B : 0) | (a.pre_gn ? PF_GAMMA | PF_BETA : 0));   // d.wp: master weights
       d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
       d.loss_log = c->f(L.loss);
       d.labels = c->labels_dev;
@@ -592,6 +599,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
       d.C = a.Cin; d.H = a.Hin; d.W = a.Win; d.G = a.G;
       d.x = x_f; d.st = ring(c, b.prest, D + 1, b.st_stride, 0);
       d.gamma = wf + a.o_gamma; d.beta = wf + a.o_beta;
+      fwd_params(d, PF_GAMMA | PF_BETA);
       if (b.aring >= 0) {
         d.y = ring(c, b.aring, D + 1, a.in_elems(), 0);
         if (a.pre_relu) d.flags |= F_PRE_RELU;
@@ -637,6 +645,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
           if (a.proj) { d.flags |= F_PROJ; d.wp = wf + a.o_wp; }
         }
       }
+      fwd_params(d, PF_W | (a.has_bias ? PF_B : 0) | ((d.flags & F_PROJ) ? PF_WP : 0));
       d.ntiles = cdiv((int64_t)a.K * a.OH * a.OW, BLK);
       if (c->bf16 && !a.ce) d.flags |= F_BF16_OUT;   // the logits of the loss stage stay unrounded
       if (c->kernel_set == 0) {
@@ -659,6 +668,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
       d.x = ring(c, b.zring, D + 1, a.z_elems(), 0);
       d.st = ring(c, b.postst, D + 1, b.st_stride, 0);
       d.gamma = wf + a.o_gamma; d.beta = wf + a.o_beta;
+      fwd_params(d, PF_GAMMA | PF_BETA);
       d.ntiles = a.G;
       out.push_back({ph++, d});
       StepDesc e = blank(K_POST_FWD, s, t_f);
@@ -837,7 +847,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
         d.v = c->f(L.v + a.off + a.o_gamma);
         d.w = wb + a.o_gamma;                         // in place (d.gamma)
         d.b = d.v;
-        d.what = c->f(L.what + wr + a.o_gamma);
+        d.what = c->f(L.what[s] + a.o_gamma);
+        writes_what(d);
         d.ntiles = a.G;
         out.push_back({pb++, d});
       } else {
@@ -882,7 +893,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out, int pa
     set_update_coeffs(c, a, &d);
     d.w = c->f(L.w + a.off); d.v = c->f(L.v + a.off); d.gw = c->f(L.g + a.off);
     d.wp = d.w; d.b = d.v;                             // master weights and velocity in place
-    d.what = c->f(L.what + (1 - parity) * L.P + a.off);
+    d.what = c->f(L.what[s]);
+    d.pmask = PF_WHAT; d.pdepth = a.De - a.D + 2; d.plag = -1; d.pstride = (int)a.padded;
     d.n = (int)(gn_fused ? a.o_gamma : a.padded);      // o_gamma is a multiple of 4
     d.ntiles = (int)cdiv(d.n, UPD_TILE);
     if (d.n > 0) out.push_back({last_grad_phase + 1, d});
@@ -925,6 +937,14 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
   int idx = 0;
   for (const auto& pr : steps) {
     const StepDesc& d = pr.second;
+    if (d.pmask) {
+      // the ring of predicted-weight versions: every slot of every masked pointer inside the arena
+      const float* ps[6] = {d.w, d.b, d.wp, d.gamma, d.beta, d.what};
+      bool pok = d.pdepth >= 2 && d.pstride > 0 && d.plag >= -1 && d.plag <= d.pdepth - 2 && (d.pmask & ~63) == 0;
+      for (int f = 0; f < 6; ++f)
+        if ((d.pmask >> f) & 1) pok = pok && ps[f] && ptr_ok(ps[f] + (int64_t)(d.pdepth - 1) * d.pstride, 1);
+      if (!pok) return fail(PB_E_INVALID, "internal: step %d (kind %d, stage %d) has a bad weight-version ring", idx, d.kind, d.stage);
+    }
     if (c->bf16 && (d.kind == K_CONV_FWD || d.kind == K_CONV_BWD_X))
       return fail(PB_E_UNSUPPORTED, "bf16 activations: stage %d has a layer the GEMM tiling cannot place", d.stage);
     const int64_t in = (int64_t)d.C * d.H * d.W, outn = (int64_t)d.K * d.OH * d.OW;
@@ -1169,7 +1189,7 @@ int run_one_tick(pb_ctx* c, const float* staging, int label) {
   if (c->launch_mode == 0) {
     for (const Phase& p : c->phases) {
       ScopedEv ev(c, 0);
-      launch_phase(c->recs_dev + c->rec_first[p.first], c->rec_stride, p.tiles, c->globals_dev, k, staging, label, c->stream);
+      launch_phase(c->recs_dev + c->rec_first[p.first], p.tiles, c->globals_dev, k, staging, label, c->stream);
     }
   } else {
     // one launch per step (same records, same arithmetic); event classes: 1 = update steps, 2 = ingest
@@ -1177,7 +1197,7 @@ int run_one_tick(pb_ctx* c, const float* staging, int label) {
       for (int i = 0; i < p.count; ++i) {
         const StepDesc& sd = c->steps[p.first + i];
         ScopedEv ev(c, sd.kind == K_INGEST ? 2 : sd.kind == K_UPDATE ? 1 : 0);
-        launch_phase(c->recs_dev + c->rec_first[p.first + i], c->rec_stride, sd.ntiles, c->globals_dev, k, staging, label,
+        launch_phase(c->recs_dev + c->rec_first[p.first + i], sd.ntiles, c->globals_dev, k, staging, label,
                      c->stream);
       }
   }
@@ -1210,11 +1230,11 @@ size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays) {
   tmp.labels_dev = (int32_t*)tmp.f(L.labels);
   std::vector<std::pair<int, StepDesc>> steps;
   tmp.plan = &pl;
-  compile_steps(&tmp, steps, 0);
+  compile_steps(&tmp, steps);
   if (validate_steps(&tmp, steps, pl.total) != PB_OK) return 0;
   int64_t total_tiles = 0;
   for (auto& pr : steps) total_tiles += pr.second.ntiles;
-  pl.alloc(2 * total_tiles * (int64_t)sizeof(StepDesc) / 4 + 64);
+  pl.alloc(total_tiles * (int64_t)sizeof(StepDesc) / 4 + 64);
   return (size_t)pl.total * sizeof(float) + 256;
 }
 
@@ -1229,7 +1249,7 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   tmp.loss_cap = lcap;
   std::vector<std::pair<int, StepDesc>> steps;
   tmp.plan = &pl;
-  compile_steps(&tmp, steps, 0);
+  compile_steps(&tmp, steps);
   order_steps(steps);
   static const char* names[] = {"gn_stats", "gap_fwd", "conv_fwd", "post_fwd", "ce", "gnb_reduce", "gnb_apply",
                                 "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad", "ingest", "update", "head", "gn_bwd"};
@@ -1305,44 +1325,31 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   c->globals_dev = (Globals*)c->f(c->L.globals);
   c->zero_dev = (int32_t*)c->f(c->L.zero);
 
-  // two step tables that differ only in which copy of the parameters they read and write:
-  // ticks of parity p run table p
-  std::vector<std::pair<int, StepDesc>> tagged, tagged1;
+  std::vector<std::pair<int, StepDesc>> tagged;
   c->plan = &pl;
-  compile_steps(c, tagged, 0);
-  compile_steps(c, tagged1, 1);
-  if (validate_steps(c, tagged, pl.total) != PB_OK || validate_steps(c, tagged1, pl.total) != PB_OK) { pb_destroy(c); return PB_E_INVALID; }
+  compile_steps(c, tagged);
+  if (validate_steps(c, tagged, pl.total) != PB_OK) { pb_destroy(c); return PB_E_INVALID; }
   order_steps(tagged);
-  order_steps(tagged1);
   const int n_steps = (int)tagged.size();
-  if ((int)tagged1.size() != n_steps) { pb_destroy(c); return fail(PB_E_INVALID, "internal: step tables differ"); }
   c->steps.resize(n_steps);
   int n_ph = 0;
   for (auto& p : tagged) n_ph = std::max(n_ph, p.first + 1);
   c->phases.assign(n_ph, Phase());
   c->rec_first.assign(n_steps, 0);
-  std::vector<StepDesc> recs, recs1;
+  std::vector<StepDesc> recs;
   for (int i = 0, cur = -1, acc = 0; i < n_steps; ++i) {
     const int ph = tagged[i].first;
-    if (tagged1[i].first != ph || tagged1[i].second.kind != tagged[i].second.kind || tagged1[i].second.ntiles != tagged[i].second.ntiles) {
-      pb_destroy(c);
-      return fail(PB_E_INVALID, "internal: step tables differ");
-    }
     if (ph != cur) { cur = ph; acc = 0; c->phases[ph].first = i; }
     c->steps[i] = tagged[i].second;
     c->rec_first[i] = (int64_t)recs.size();
     for (int tl = 0; tl < tagged[i].second.ntiles; ++tl) {
       recs.push_back(tagged[i].second);
       recs.back().tile = tl;
-      recs1.push_back(tagged1[i].second);
-      recs1.back().tile = tl;
     }
     acc += tagged[i].second.ntiles;
     c->phases[ph].count++;
     c->phases[ph].tiles = acc;
   }
-  c->rec_stride = (int)recs.size();
-  recs.insert(recs.end(), recs1.begin(), recs1.end());
   const int64_t o_recs = pl.alloc((int64_t)recs.size() * sizeof(StepDesc) / 4 + 64);
   if ((size_t)pl.total * sizeof(float) > need) { pb_destroy(c); return fail(PB_E_NOMEM, "internal: arena plan mismatch"); }
   c->recs_dev = (StepDesc*)c->f(o_recs);
@@ -1353,7 +1360,8 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   memset(&g0, 0, sizeof g0);
   g0.n_pool = 1;
   INIT_TRY(hipMemcpyAsync(c->f(c->L.w), w.data(), sizeof(float) * c->L.P, hipMemcpyHostToDevice, c->stream));
-  INIT_TRY(hipMemcpyAsync(c->f(c->L.what), w.data(), sizeof(float) * c->L.P, hipMemcpyHostToDevice, c->stream));
+  for (int s = 0; s < c->S; ++s)     // slot 0 of every stage's ring of predicted weights: v = 0, so w_hat = w
+    INIT_TRY(hipMemcpyAsync(c->f(c->L.what[s]), w.data() + st[s].off, sizeof(float) * st[s].padded, hipMemcpyHostToDevice, c->stream));
   INIT_TRY(hipMemcpyAsync(c->recs_dev, recs.data(), sizeof(StepDesc) * recs.size(), hipMemcpyHostToDevice, c->stream));
   INIT_TRY(hipMemcpyAsync(c->globals_dev, &g0, sizeof g0, hipMemcpyHostToDevice, c->stream));
   for (auto& tb : c->tables)

@@ -1256,7 +1256,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
 // that a single burst of scalar loads (one memory round trip) delivers all a
 // workgroup needs to know.
 __global__ void __launch_bounds__(BLK)
-k_phase(const StepDesc* __restrict__ recs, int rec_stride, const Globals* __restrict__ G, int k,
+k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
         const float* __restrict__ sample_override, int label_override) {
   __shared__ float red_[8];
   __shared__ __attribute__((aligned(16))) float smem_[LDS_FLOATS];
@@ -1275,12 +1275,30 @@ k_phase(const StepDesc* __restrict__ recs, int rec_stride, const Globals* __rest
   static_assert(sizeof(StepDesc) % 4 == 0 && NW <= BLK, "descriptor must fit one word per thread");
   __shared__ StepDesc sd_;
   {
-    // two record tables: parameter pointers of even and of odd ticks
-    const gint* dp = (const gint*)(recs + (size_t)(t & 1) * rec_stride + blockIdx.x);
+    const gint* dp = (const gint*)(recs + blockIdx.x);
     if (threadIdx.x < NW) ((lint*)&sd_)[threadIdx.x] = dp[threadIdx.x];
   }
   __syncthreads();
   const LDesc& d = *(const LDesc*)&sd_;
+  // Predicted weights live in a ring of versions per stage (the update of tick t writes slot t+1, the
+  // forward pass of tick t reads slot t - extra delay): move the step's pointers to its slot.
+  if (UNI(d.pmask) != 0) {
+    const int depth = UNI(d.pdepth), u = t - UNI(d.plag);
+    const int slot = u < 0 ? 0 : u % depth;
+    const size_t off = (size_t)slot * (size_t)UNI(d.pstride);
+    const int f = threadIdx.x;
+    if (f < 6 && ((UNI(d.pmask) >> f) & 1)) {
+      switch (f) {
+        case 0: sd_.w += off; break;
+        case 1: sd_.b += off; break;
+        case 2: sd_.wp += off; break;
+        case 3: sd_.gamma += off; break;
+        case 4: sd_.beta += off; break;
+        default: sd_.what += off; break;
+      }
+    }
+    __syncthreads();
+  }
   const int tile = UNI(d.tile);
   const bool live = t >= UNI(d.first_tick);
   if (!live && !(UNI(d.flags) & F_ALWAYS)) return;
@@ -1379,11 +1397,10 @@ __global__ void k_advance(Globals* G, int dt, int didx) {
 }
 
 // --------------------------------------------------------- launch wrappers
-void launch_phase(const StepDesc* recs_dev, int rec_stride, int total_tiles, const Globals* G, int k,
-                  const float* sample_override, int label_override, hipStream_t s) {
+void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, const float* sample_override,
+                  int label_override, hipStream_t s) {
   if (total_tiles <= 0) return;
-  hipLaunchKernelGGL(k_phase, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, rec_stride, G, k, sample_override,
-                     label_override);
+  hipLaunchKernelGGL(k_phase, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, G, k, sample_override, label_override);
 }
 
 void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,

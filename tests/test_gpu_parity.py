@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 
 import pb_workloads as W
+from oracle import pb_oracle as O
 from tests.parity_util import TOL, run_parity
 
 pytestmark = pytest.mark.gpu
@@ -153,3 +154,57 @@ def test_bf16_activation_mode(name):
         e.close()
     assert not np.array_equal(outs[0], outs[1])
     assert np.abs(outs[0] - outs[1]).max() > 1e-4
+
+
+@pytest.mark.parametrize("name,extra", [("tiny_resnet", (3, 0, 2, 1, 0, 5)), ("tiny_vgg", (1, 4, 0, 2))])
+def test_delays_above_the_pipelines_own(name, extra):
+    """delays[s] larger than 2(S-1-s): the forward pass of stage s reads predicted weights that many
+    updates old from the stage's ring of weight versions; SC and LWP use the larger delay.  Reference:
+    the oracle's sample-indexed form (Eqs. wi, sgdpb, wf with forward index i - D^s), stage s compared
+    after the number of updates it has seen."""
+    PBEngine = _engine()
+    net = W.config(name)
+    S = len(net["stages"])
+    assert len(extra) == S
+    delays = [2 * (S - 1 - s) + extra[s] for s in range(S)]
+    xs, ys = W.sample_pool(net)
+    K = 45
+    eng = PBEngine(net, delays=delays)
+    for t in range(K):
+        eng.tick(xs[t % len(ys)], ys[t % len(ys)])
+    w_gpu, l_gpu = eng.read_weights(), eng.loss_history()
+    eng.close()
+    n = K - (S - 1)                       # samples that have reached the loss
+    hist, losses = O.run_sample_indexed(net, n, xs, ys, delays=delays, mitigation=3)
+    off = 0
+    worst = 0.0
+    for s, st in enumerate(net["stages"]):
+        n_upd = max(0, K - 2 * (S - 1) + s)
+        params, _ = hist[s][n_upd]
+        for pname, shape, _ in O.stage_param_specs(st):
+            cnt = int(np.prod(shape))
+            ref = params[pname].numpy().reshape(-1)
+            got = w_gpu[off:off + cnt].astype(np.float64)
+            mx = np.abs(ref).max()
+            err = np.abs(got - ref).max() / mx if mx > 0 else np.abs(got).max()
+            worst = max(worst, err)
+            assert err <= 1e-5, (s, pname, err)
+            off += cnt
+    assert off == w_gpu.size
+    assert np.allclose(l_gpu, np.asarray(losses[: len(l_gpu)]), rtol=1e-4, atol=1e-4)
+    # and the larger delays change the trajectory
+    e0 = PBEngine(net)
+    for t in range(K):
+        e0.tick(xs[t % len(ys)], ys[t % len(ys)])
+    assert np.abs(e0.read_weights() - w_gpu).max() > 1e-4
+    e0.close()
+    print(f"{name}: delays {delays}, worst tensor error {worst:.2e}", file=sys.stderr)
+
+
+def test_delays_below_the_pipelines_own_are_rejected():
+    from paper_2003_11666_amd.binding import PBError
+    PBEngine = _engine()
+    net = W.config("tiny_mlp")
+    S = len(net["stages"])
+    with pytest.raises(PBError):
+        PBEngine(net, delays=[0] * S)
