@@ -81,7 +81,9 @@ typedef struct {
   int32_t in_c, in_h, in_w;   /* one sample is in_c*in_h*in_w floats, CHW order */
   int32_t n_classes;
   int32_t mitigation;         /* 0 plain delayed SGDM, 1 SC_D, 2 LWP^v_D, 3 SC_D + LWP^v_D */
-  int32_t bwd_weights;        /* 0 backward pass uses current weights (the paper's PB)      */
+  int32_t bwd_weights;        /* 0 backward pass uses current weights (the paper's PB); 1 weight
+                                 stashing: it uses the predicted weights its forward pass read,
+                                 kept in a ring of delays[s] + 2 versions per stage            */
   int32_t act_dtype;          /* 0 fp32 activations; 1 bf16: tensors that cross a stage boundary are
                                  rounded to bf16 (nearest even) by the step that writes them      */
   int32_t loss_capacity;      /* losses kept (most recent); 0 = 1<<20                       */

@@ -69,7 +69,7 @@ struct GemmCfg {
 
 // Pointer fields of a step that point into slot 0 of the stage's ring of predicted-weight versions;
 // k_phase moves them to the slot of the tick before the step runs.
-enum ParamField : int32_t { PF_W = 1, PF_B = 2, PF_WP = 4, PF_GAMMA = 8, PF_BETA = 16, PF_WHAT = 32 };
+enum ParamField : int32_t { PF_W = 1, PF_B = 2, PF_WP = 4, PF_GAMMA = 8, PF_BETA = 16, PF_WHAT = 32, PF_SKIPBASE = 64 };
 
 enum StepFlags : int32_t {
   F_PRE_AFFINE = 1,   // input is sc[c]*x + sh[c] (GroupNorm folded into the load)

@@ -67,7 +67,7 @@ int parse_net(const pb_net_desc* net, std::vector<Stage>& out) {
   if (net->in_c <= 0 || net->in_h <= 0 || net->in_w <= 0 || net->n_classes <= 0)
     return fail(PB_E_INVALID, "bad input dimensions");
   if (net->mitigation < 0 || net->mitigation > 3) return fail(PB_E_INVALID, "mitigation must be 0..3");
-  if (net->bwd_weights != 0) return fail(PB_E_UNSUPPORTED, "bwd_weights=%d (weight stashing) not implemented", net->bwd_weights);
+  if (net->bwd_weights != 0 && net->bwd_weights != 1) return fail(PB_E_INVALID, "bwd_weights=%d", net->bwd_weights);
   if (net->act_dtype != 0 && net->act_dtype != 1) return fail(PB_E_INVALID, "act_dtype=%d", net->act_dtype);
   if (net->act_dtype == 1 && net->kernel_set != 0) return fail(PB_E_UNSUPPORTED, "bf16 activations need kernel_set 0");
   if (net->kernel_set < 0 || net->kernel_set > 1) return fail(PB_E_INVALID, "kernel_set must be 0 or 1");
@@ -235,7 +235,9 @@ struct Layout {
 
 int st_stride_of(const Stage& s) { return (2 * s.G + 2 * s.gnC() + 63) / 64 * 64; }
 
-void plan_arena(const std::vector<Stage>& st, bool lwp, int loss_cap, Layout& L, Plan& pl, bool use_aring) {
+int what_depth(const Stage& a, bool stash) { return stash ? a.De + 2 : a.De - a.D + 2; }
+
+void plan_arena(const std::vector<Stage>& st, bool stash, int loss_cap, Layout& L, Plan& pl, bool use_aring) {
   const int S = (int)st.size();
   L.P = 0;
   for (const Stage& s : st) L.P += s.padded;
@@ -247,8 +249,9 @@ void plan_arena(const std::vector<Stage>& st, bool lwp, int loss_cap, Layout& L,
   // stage's update.  Without weight prediction the forward copy simply equals the master weights.
   L.w = pl.alloc(L.P); L.v = pl.alloc(L.P); L.g = pl.alloc(L.P);
   L.what.assign(S, 0);
-  for (int s = 0; s < S; ++s) L.what[s] = pl.alloc((int64_t)(st[s].De - st[s].D + 2) * st[s].padded);
-  (void)lwp;
+  // Weight stashing (the backward pass uses the forward's predicted weights, Eq. sgdpb_weight_stash):
+  // the version the forward pass of a sample read has to survive until its backward pass, De + 2 slots.
+  for (int s = 0; s < S; ++s) L.what[s] = pl.alloc((int64_t)what_depth(st[s], stash) * st[s].padded);
   L.sb.assign(S, StageBufs());
   for (int s = 0; s < S; ++s) {
     const Stage& a = st[s];
@@ -298,6 +301,7 @@ struct pb_ctx {
   int64_t ticks = 0;
   int launch_mode = 0;
   int kernel_set = 0;
+  bool stash = false;  // weight stashing: the backward pass reads the predicted weights its forward pass used
   bool bf16 = false;   // bf16 activation mode: tensors that cross a stage boundary are rounded to bf16
   std::vector<StepDesc> steps;         // sorted by phase
   std::vector<int64_t> rec_first;      // per step: index of its first per-workgroup record
@@ -541,11 +545,19 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     // pointer fields that k_phase has to move to the slot of the tick
     const float* wf = c->f(L.what[s]);                      // forward (predicted) parameters
     const float* wb = c->f(L.w + a.off);                    // backward (current) parameters
+    const int wdepth = what_depth(a, c->stash);
     auto fwd_params = [&](StepDesc& d, int mask) {
-      d.pmask = mask; d.pdepth = a.De - a.D + 2; d.plag = a.De - a.D; d.pstride = (int)a.padded;
+      d.pmask = mask; d.pdepth = wdepth; d.plag = a.De - a.D; d.pstride = (int)a.padded;
     };
     auto writes_what = [&](StepDesc& d) {
-      d.pmask = PF_WHAT; d.pdepth = a.De - a.D + 2; d.plag = -1; d.pstride = (int)a.padded;
+      d.pmask = PF_WHAT; d.pdepth = wdepth; d.plag = -1; d.pstride = (int)a.padded;
+    };
+    // weights of a backward step: the current master weights, or with weight stashing the version the
+    // sample's forward pass read, De updates ago, from the same ring
+    const float* wbk = c->stash ? wf : wb;
+    auto bwd_params = [&](StepDesc& d, int mask) {
+      if (!c->stash) return;
+      d.pmask = mask; d.pdepth = wdepth; d.plag = a.De; d.pstride = (int)a.padded;
     };
     float* gr = c->f(L.g + a.off);
     const int t_f = s, t_b = 2 * (S - 1) - s;
@@ -578,13 +590,16 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       if (a.gap) d.flags |= F_DU_GAP;
       if (a.has_bias) { d.flags |= F_BIAS; d.b = wf + a.o_b; d.gb = gr + a.o_b; }
       d.x = x_f;
-      d.w = wf + a.o_w; d.wp = wb + a.o_w; d.gw = gr + a.o_w;
+      d.w = wf + a.o_w; d.wp = wbk + a.o_w; d.gw = gr + a.o_w;
       if (a.pre_gn) {
         d.gamma = wf + a.o_gamma; d.beta = wf + a.o_beta;
-        d.skip.base = const_cast<float*>(wb + a.o_gamma);
+        d.skip.base = const_cast<float*>(wbk + a.o_gamma);
         d.ggamma = gr + a.o_gamma; d.gbeta = gr + a.o_beta;
       }
-      fwd_params(d, PF_W | (a.has_bias ? PF_B : 0) | (a.pre_gn ? PF_GAMMA | PF_BETA : 0));   // d.wp: master weights
+      // d.wp, d.skip.base: the backward pass's weights (the last stage's own delay is 0, so with
+      // stashing they are the very slot the forward pass reads)
+      fwd_params(d, PF_W | (a.has_bias ? PF_B : 0) | (a.pre_gn ? PF_GAMMA | PF_BETA : 0) |
+                        (c->stash ? PF_WP | (a.pre_gn ? PF_SKIPBASE : 0) : 0));
       d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
       d.loss_log = c->f(L.loss);
       d.labels = c->labels_dev;
@@ -702,7 +717,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       d.x = ring(c, b.zring, D + 1, a.z_elems(), D);
       d.st = ring(c, b.postst, D + 1, b.st_stride, D);
       d.dy = dy_src;
-      d.gamma = wb + a.o_gamma;
+      d.gamma = wbk + a.o_gamma;
+      bwd_params(d, PF_GAMMA);
       d.ggamma = gr + a.o_gamma; d.gbeta = gr + a.o_beta;
       d.part = c->f(b.part);
       if (c->kernel_set == 0 && !a.pool && gn_bwd_fits(d.C, d.H * d.W, d.G)) {
@@ -764,7 +780,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       d.C = a.C; d.H = a.H; d.W = a.W; d.K = a.K; d.OH = a.OH; d.OW = a.OW;
       d.k = a.k; d.stride = a.stride; d.pad = a.pad;
       d.dy = dz_src;
-      d.w = wb + a.o_w;
+      d.w = wbk + a.o_w;
+      bwd_params(d, PF_W);
       if (a.pre_gn) {
         d.dx = ring(c, b.da, 1, a.gap ? a.C : a.in_elems(), 0);
       } else {
@@ -803,7 +820,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         e.C = a.sC; e.H = a.sH; e.W = a.sW; e.K = a.K; e.OH = a.OH; e.OW = a.OW;
         e.k = 1; e.stride = a.sstride; e.pad = 0;
         e.dy = dy_src;
-        e.w = wb + a.o_wp;
+        e.w = wbk + a.o_wp;
+        bwd_params(e, PF_W);
         e.dx = skg_w;
         if (c->bf16) e.flags |= F_BF16_OUT;
         e.ntiles = cdiv(ta.in_elems(), BLK);
@@ -829,7 +847,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       d.x = x_b;
       d.st = ring(c, b.prest, D + 1, b.st_stride, D);
       d.dy = ring(c, b.da, 1, a.gap ? a.C : a.in_elems(), 0);
-      d.gamma = wb + a.o_gamma;
+      d.gamma = wbk + a.o_gamma;
+      bwd_params(d, PF_GAMMA);
       d.ggamma = gr + a.o_gamma; d.gbeta = gr + a.o_beta;
       d.part = c->f(b.part);
       if (c->kernel_set == 0 && gn_bwd_fits(d.C, d.H * d.W, d.G)) {
@@ -842,13 +861,17 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         // this step ends the stage's backward chain and is the only producer of the scale / shift
         // gradients: it updates those two tensors itself, so that the rest of the stage can be
         // updated one phase earlier and no phase is left that holds nothing but updates
-        d.flags |= F_UPD_GN | F_ALWAYS;
-        set_update_coeffs(c, a, &d);
-        d.v = c->f(L.v + a.off + a.o_gamma);
-        d.w = wb + a.o_gamma;                         // in place (d.gamma)
-        d.b = d.v;
-        d.what = c->f(L.what[s] + a.o_gamma);
-        writes_what(d);
+        // (not with weight stashing: the step would need two slots of the ring, the stashed scale it
+        // reads and the new version it writes)
+        if (!c->stash) {
+          d.flags |= F_UPD_GN | F_ALWAYS;
+          set_update_coeffs(c, a, &d);
+          d.v = c->f(L.v + a.off + a.o_gamma);
+          d.w = wb + a.o_gamma;                       // master scale and shift, updated in place
+          d.b = d.v;
+          d.what = c->f(L.what[s] + a.o_gamma);
+          writes_what(d);
+        }
         d.ntiles = a.G;
         out.push_back({pb++, d});
       } else {
@@ -894,7 +917,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     d.w = c->f(L.w + a.off); d.v = c->f(L.v + a.off); d.gw = c->f(L.g + a.off);
     d.wp = d.w; d.b = d.v;                             // master weights and velocity in place
     d.what = c->f(L.what[s]);
-    d.pmask = PF_WHAT; d.pdepth = a.De - a.D + 2; d.plag = -1; d.pstride = (int)a.padded;
+    d.pmask = PF_WHAT; d.pdepth = what_depth(a, c->stash); d.plag = -1; d.pstride = (int)a.padded;
     d.n = (int)(gn_fused ? a.o_gamma : a.padded);      // o_gamma is a multiple of 4
     d.ntiles = (int)cdiv(d.n, UPD_TILE);
     if (d.n > 0) out.push_back({last_grad_phase + 1, d});
@@ -939,9 +962,9 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
     const StepDesc& d = pr.second;
     if (d.pmask) {
       // the ring of predicted-weight versions: every slot of every masked pointer inside the arena
-      const float* ps[6] = {d.w, d.b, d.wp, d.gamma, d.beta, d.what};
-      bool pok = d.pdepth >= 2 && d.pstride > 0 && d.plag >= -1 && d.plag <= d.pdepth - 2 && (d.pmask & ~63) == 0;
-      for (int f = 0; f < 6; ++f)
+      const float* ps[7] = {d.w, d.b, d.wp, d.gamma, d.beta, d.what, d.skip.base};
+      bool pok = d.pdepth >= 2 && d.pstride > 0 && d.plag >= -1 && d.plag <= d.pdepth - 2 && (d.pmask & ~127) == 0;
+      for (int f = 0; f < 7; ++f)
         if ((d.pmask >> f) & 1) pok = pok && ps[f] && ptr_ok(ps[f] + (int64_t)(d.pdepth - 1) * d.pstride, 1);
       if (!pok) return fail(PB_E_INVALID, "internal: step %d (kind %d, stage %d) has a bad weight-version ring", idx, d.kind, d.stage);
     }
@@ -1221,10 +1244,11 @@ size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays) {
   tmp.st = st; tmp.S = (int)st.size();
   tmp.kernel_set = net->kernel_set;
   tmp.bf16 = net->act_dtype == 1;
+  tmp.stash = net->bwd_weights == 1;
   const int cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   Plan pl;
   Layout L;
-  plan_arena(st, net->mitigation >= 2, cap, L, pl, net->kernel_set == 0);
+  plan_arena(st, net->bwd_weights == 1, cap, L, pl, net->kernel_set == 0);
   // step table, prefix, chunk map and segment table live in the arena too
   tmp.L = L; tmp.loss_cap = cap; tmp.arena = nullptr;
   tmp.labels_dev = (int32_t*)tmp.f(L.labels);
@@ -1242,10 +1266,10 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   std::vector<Stage> st;
   if (parse_net(net, st) != PB_OK) return PB_E_INVALID;
   pb_ctx tmp;
-  tmp.st = st; tmp.S = (int)st.size(); tmp.kernel_set = net->kernel_set; tmp.bf16 = net->act_dtype == 1;
+  tmp.st = st; tmp.S = (int)st.size(); tmp.kernel_set = net->kernel_set; tmp.bf16 = net->act_dtype == 1; tmp.stash = net->bwd_weights == 1;
   const int lcap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   Plan pl;
-  plan_arena(st, net->mitigation >= 2, lcap, tmp.L, pl, net->kernel_set == 0);
+  plan_arena(st, net->bwd_weights == 1, lcap, tmp.L, pl, net->kernel_set == 0);
   tmp.loss_cap = lcap;
   std::vector<std::pair<int, StepDesc>> steps;
   tmp.plan = &pl;
@@ -1296,6 +1320,7 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   c->mitigation = net->mitigation; c->lr = lr; c->m = momentum;
   c->kernel_set = net->kernel_set;
   c->bf16 = net->act_dtype == 1;
+  c->stash = net->bwd_weights == 1;
   c->loss_cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   c->stream = (hipStream_t)net->stream;
   for (const Stage& a : st) c->n_params += a.n_params;
@@ -1320,7 +1345,7 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   INIT_TRY(hipMemsetAsync(base, 0, need, c->stream));
 
   Plan pl;
-  plan_arena(st, net->mitigation >= 2, c->loss_cap, c->L, pl, net->kernel_set == 0);
+  plan_arena(st, net->bwd_weights == 1, c->loss_cap, c->L, pl, net->kernel_set == 0);
   c->labels_dev = (int32_t*)c->f(c->L.labels);
   c->globals_dev = (Globals*)c->f(c->L.globals);
   c->zero_dev = (int32_t*)c->f(c->L.zero);

@@ -459,7 +459,7 @@ __device__ void step_gnb_apply(const LDesc& d, int tile, int t) {
 // The same update for one parameter (GroupNorm scale or shift updated by the
 // step that produced its gradient): w, v at index i in place, w_hat into the other copy.
 __device__ __forceinline__ void update_one(const LDesc& d, int i, float g) {
-  float vv = GP(d.v)[i], wv = GP(d.gamma)[i];
+  float vv = GP(d.v)[i], wv = GP(d.w)[i];
   vv = fmaf(UNIF(d.fm), vv, g);
   wv = fmaf(-UNIF(d.flr), fmaf(UNIF(d.fa), vv, UNIF(d.fb) * g), wv);
   GP((float*)d.b)[i] = vv;
@@ -1287,14 +1287,15 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     const int slot = u < 0 ? 0 : u % depth;
     const size_t off = (size_t)slot * (size_t)UNI(d.pstride);
     const int f = threadIdx.x;
-    if (f < 6 && ((UNI(d.pmask) >> f) & 1)) {
+    if (f < 7 && ((UNI(d.pmask) >> f) & 1)) {
       switch (f) {
         case 0: sd_.w += off; break;
         case 1: sd_.b += off; break;
         case 2: sd_.wp += off; break;
         case 3: sd_.gamma += off; break;
         case 4: sd_.beta += off; break;
-        default: sd_.what += off; break;
+        case 5: sd_.what += off; break;
+        default: sd_.skip.base += off; break;
       }
     }
     __syncthreads();

@@ -62,9 +62,9 @@ def rel_errors(a, b, slices):
     return worst_inf, worst_l2, where
 
 
-def perturbed_oracle(net, seed, mitigation, eps, gen_seed=12345, lr=None):
+def perturbed_oracle(net, seed, mitigation, eps, gen_seed=12345, lr=None, bwd_weights=0):
     import torch
-    orc = O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr)
+    orc = O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr, bwd_weights=bwd_weights)
     g = torch.Generator().manual_seed(gen_seed)
     for p in orc.w:
         for k in p:
@@ -73,11 +73,11 @@ def perturbed_oracle(net, seed, mitigation, eps, gen_seed=12345, lr=None):
 
 
 def run_parity(engine_cls, net, K, mitigation=3, seed=42, every=1, engine_kwargs=None, verbose=False, lr=None,
-               perturb=PERTURB):
+               perturb=PERTURB, bwd_weights=0):
     xs, ys = W.sample_pool(net)
-    orc = O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr)
-    orcs = [perturbed_oracle(net, seed, mitigation, e, 12345 + i, lr=lr) for i, e in enumerate(perturb)]
-    eng = engine_cls(net, seed=seed, mitigation=mitigation, lr=lr, **(engine_kwargs or {}))
+    orc = O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr, bwd_weights=bwd_weights)
+    orcs = [perturbed_oracle(net, seed, mitigation, e, 12345 + i, lr=lr, bwd_weights=bwd_weights) for i, e in enumerate(perturb)]
+    eng = engine_cls(net, seed=seed, mitigation=mitigation, lr=lr, bwd_weights=bwd_weights, **(engine_kwargs or {}))
     slices = tensor_slices(net)
     w0 = eng.read_weights()
     assert w0.size == orc.read_weights().size

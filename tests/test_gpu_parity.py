@@ -208,3 +208,25 @@ def test_delays_below_the_pipelines_own_are_rejected():
     S = len(net["stages"])
     with pytest.raises(PBError):
         PBEngine(net, delays=[0] * S)
+
+
+@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_vgg", "tiny_resnet", "small_resnet", "tiny_bottleneck"])
+@pytest.mark.parametrize("mit", [3, 0])
+def test_weight_stashing(name, mit):
+    """bwd_weights=1 (Eq. sgdpb_weight_stash): the backward pass of a sample uses the predicted weights
+    its forward pass read, kept in the stage's ring of weight versions for D^s ticks."""
+    net = W.config(name)
+    K = 80
+    res = run_parity(_engine(), net, K, mitigation=mit, bwd_weights=1)
+    _check(res, K, len(net["stages"]))
+    # it differs from the default (current weights in the backward pass)
+    PBEngine = _engine()
+    xs, ys = W.sample_pool(net)
+    outs = []
+    for bw in (0, 1):
+        e = PBEngine(net, mitigation=mit, bwd_weights=bw)
+        for t in range(40):
+            e.tick(xs[t % len(ys)], ys[t % len(ys)])
+        outs.append(e.read_weights())
+        e.close()
+    assert np.abs(outs[0] - outs[1]).max() > 1e-5
