@@ -93,6 +93,10 @@ typedef struct {
                                  allocates and frees its own */
   size_t arena_bytes;
   void* stream;               /* hipStream_t to launch on, NULL = the null stream */
+  float sc_scale;             /* over-compensation: SC uses the coefficients of delay sc_scale * delays[s]  */
+  float lwp_scale;            /* ... and LWP the horizon T = lwp_scale * delays[s]; 0 means 1 for both     */
+  int32_t lwp_form;           /* 0 velocity form w_hat = w - lr T v (Eq. lwp_v_form); 1 weight-difference
+                                 form w_hat = w + T (w - w_prev) (Eq. lwp_w_form)                          */
 } pb_net_desc;
 
 /* Device bytes pb_init needs for this network (0 on an invalid descriptor). */

@@ -374,8 +374,11 @@ class PBOracle:
     """
 
     def __init__(self, net, delays=None, lr=None, momentum=None, seed=42, mitigation=3,
-                 bwd_weights=0):
+                 bwd_weights=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v"):
         self.net = net
+        if lwp_form not in ("v", "w"):
+            raise ValueError("lwp_form must be 'v' (velocity) or 'w' (weight difference)")
+        self.lwp_form = lwp_form
         self.stages = net["stages"]
         self.S = S = len(self.stages)
         self.lr = float(net["lr"] if lr is None else lr)
@@ -392,10 +395,13 @@ class PBOracle:
         self.bf16 = (net.get("act_dtype", "fp32") == "bf16")
         self.w = init_params(net, seed)
         self.v = [{k: torch.zeros_like(t) for k, t in p.items()} for p in self.w]
+        self.w_prev = [dict(p) for p in self.w]     # weights before the latest update (LWP weight-difference form)
+        # over-compensation (Section "Combined Mitigation", appendix on extended horizons):
+        # SC with the coefficients of delay sc_scale*D, LWP with horizon T = lwp_scale*D
         self.coef = []
         for D in self.delays:
-            a, b = sc_coefficients(self.m, D) if mitigation in (1, 3) else (1.0, 0.0)
-            T = float(D) if mitigation in (2, 3) else 0.0
+            a, b = sc_coefficients(self.m, sc_scale * D) if mitigation in (1, 3) else (1.0, 0.0)
+            T = float(lwp_scale * D) if mitigation in (2, 3) else 0.0
             self.coef.append((a, b, T))
         self.t = 0
         self.fwd_mail = {}      # stage -> activation produced for it last tick
@@ -408,6 +414,8 @@ class PBOracle:
 
     def predicted(self, s):
         a, b, T = self.coef[s]
+        if self.lwp_form == "w":      # Eq. lwp_w_form: w_hat = w + T (w - w_prev)
+            return {k: self.w[s][k] + T * (self.w[s][k] - self.w_prev[s][k]) for k in self.w[s]}
         return {k: lwp_predict(self.w[s][k], self.v[s][k], self.lr, T) for k in self.w[s]}
 
     def tick(self, sample, label):
@@ -461,6 +469,7 @@ class PBOracle:
         for s, grads in pending.items():
             a, b, T = self.coef[s]
             for k in self.w[s]:
+                self.w_prev[s][k] = self.w[s][k]
                 self.w[s][k], self.v[s][k] = gsc_update(self.w[s][k], self.v[s][k], grads[k],
                                                         self.lr, self.m, a, b)
             self.last_grads[s] = grads
@@ -484,7 +493,7 @@ class PBOracle:
 # cross-checks the tick form's bookkeeping
 # --------------------------------------------------------------------------
 def run_sample_indexed(net, n_samples, pool_x, pool_y, delays=None, lr=None, momentum=None,
-                       seed=42, mitigation=3, bwd_weights=0):
+                       seed=42, mitigation=3, bwd_weights=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v"):
     """Process samples one at a time.  Stage s's forward of sample i uses the
     stage's state after max(0, i - D^s) updates, the backward uses the state
     after i updates; then update i is applied to every stage.
@@ -502,8 +511,8 @@ def run_sample_indexed(net, n_samples, pool_x, pool_y, delays=None, lr=None, mom
     hist = [[(w0[s], {k: torch.zeros_like(t) for k, t in w0[s].items()})] for s in range(S)]
     coef = []
     for D in delays:
-        a, b = sc_coefficients(m, D) if mitigation in (1, 3) else (1.0, 0.0)
-        T = float(D) if mitigation in (2, 3) else 0.0
+        a, b = sc_coefficients(m, sc_scale * D) if mitigation in (1, 3) else (1.0, 0.0)
+        T = float(lwp_scale * D) if mitigation in (2, 3) else 0.0
         coef.append((a, b, T))
     losses = []
     n_pool = len(pool_y)
@@ -515,7 +524,11 @@ def run_sample_indexed(net, n_samples, pool_x, pool_y, delays=None, lr=None, mom
         saved, inputs, whats = [], [], []
         for s in range(S):
             wv, vv = hist[s][max(0, i - delays[s])]
-            what = {k: lwp_predict(wv[k], vv[k], lr, coef[s][2]) for k in wv}
+            if lwp_form == "w":
+                wp_, _ = hist[s][max(0, i - delays[s] - 1)]
+                what = {k: wv[k] + coef[s][2] * (wv[k] - wp_[k]) for k in wv}
+            else:
+                what = {k: lwp_predict(wv[k], vv[k], lr, coef[s][2]) for k in wv}
             src = skip_source(stages[s])
             inputs.append(x)
             y, loss, sv = stage_forward(stages[s], what, x, inputs[src] if src >= 0 else None,

@@ -37,7 +37,8 @@ class _NetDesc(C.Structure):
                 ("in_c", C.c_int32), ("in_h", C.c_int32), ("in_w", C.c_int32),
                 ("n_classes", C.c_int32), ("mitigation", C.c_int32), ("bwd_weights", C.c_int32),
                 ("act_dtype", C.c_int32), ("loss_capacity", C.c_int32), ("kernel_set", C.c_int32),
-                ("device_arena", C.c_void_p), ("arena_bytes", C.c_size_t), ("stream", C.c_void_p)]
+                ("device_arena", C.c_void_p), ("arena_bytes", C.c_size_t), ("stream", C.c_void_p),
+                ("sc_scale", C.c_float), ("lwp_scale", C.c_float), ("lwp_form", C.c_int32)]
 
 
 def lib_path():
@@ -101,7 +102,7 @@ def _check(lib, rc):
     return rc
 
 
-def marshal_net(net, mitigation=3, bwd_weights=0, loss_capacity=0, kernel_set=0):
+def marshal_net(net, mitigation=3, bwd_weights=0, loss_capacity=0, kernel_set=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v"):
     """dict descriptor (pb_workloads) -> pb_net_desc; returns (desc, keepalive)."""
     keep = []
     stages = (_Stage * len(net["stages"]))()
@@ -119,6 +120,8 @@ def marshal_net(net, mitigation=3, bwd_weights=0, loss_capacity=0, kernel_set=0)
     d.in_c, d.in_h, d.in_w = net["in_c"], net["in_h"], net["in_w"]
     d.n_classes = net["n_classes"]
     d.mitigation, d.bwd_weights = mitigation, bwd_weights
+    d.sc_scale, d.lwp_scale = sc_scale, lwp_scale
+    d.lwp_form = {"v": 0, "w": 1}[lwp_form]
     d.act_dtype = {"fp32": 0, "bf16": 1}[net.get("act_dtype", "fp32")]
     d.loss_capacity = loss_capacity
     d.kernel_set = kernel_set
@@ -140,10 +143,10 @@ class PBEngine:
     """pb_init / pb_tick / pb_run_resident / pb_read_weights / pb_loss_history."""
 
     def __init__(self, net, lr=None, momentum=None, seed=42, mitigation=3, delays=None,
-                 bwd_weights=0, loss_capacity=0, torch_arena=True, kernel_set=0):
+                 bwd_weights=0, loss_capacity=0, torch_arena=True, kernel_set=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v"):
         self.lib = load_library()
         self.net = net
-        desc, self._keep = marshal_net(net, mitigation, bwd_weights, loss_capacity, kernel_set)
+        desc, self._keep = marshal_net(net, mitigation, bwd_weights, loss_capacity, kernel_set, sc_scale, lwp_scale, lwp_form)
         dl = None
         if delays is not None:
             dl = (C.c_int32 * len(delays))(*delays)

@@ -86,7 +86,8 @@ enum StepFlags : int32_t {
   F_GN_RELU = 2048,   // GN backward: a ReLU follows the normalisation
   F_UPD_GN = 4096,    // K_GN_BWD also applies the update of the GroupNorm scale / shift it has the gradients of
   F_ALWAYS = 8192,    // the step runs before its first_tick too (then it only carries parameters over)
-  F_BF16_OUT = 16384  // the step's output crosses a stage boundary in bf16 mode: round it to bf16 (nearest even)
+  F_BF16_OUT = 16384, // the step's output crosses a stage boundary in bf16 mode: round it to bf16 (nearest even)
+  F_LWP_W = 32768     // update: weight-difference form of the prediction, w_hat = w' + T (w' - w); flrT then holds T
 };
 
 struct StepDesc {

@@ -134,7 +134,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
         if (rr >= M) rr = M - 1;                            // rows beyond M repeat the last one; never stored
         return Aglob + (size_t)rr * Q + q0 + c;
       };
-      constexpr int AU = 8;
+      constexpr int AU = 10;
       const int av = avec ? 4 : 1;                          // floats per request
       const int spr = avec ? (seg_pad + 3) >> 2 : seg_pad;  // requests per segment
       const float ispr = frcp(spr);

@@ -71,6 +71,8 @@ int parse_net(const pb_net_desc* net, std::vector<Stage>& out) {
   if (net->act_dtype != 0 && net->act_dtype != 1) return fail(PB_E_INVALID, "act_dtype=%d", net->act_dtype);
   if (net->act_dtype == 1 && net->kernel_set != 0) return fail(PB_E_UNSUPPORTED, "bf16 activations need kernel_set 0");
   if (net->kernel_set < 0 || net->kernel_set > 1) return fail(PB_E_INVALID, "kernel_set must be 0 or 1");
+  if (net->lwp_form != 0 && net->lwp_form != 1) return fail(PB_E_INVALID, "lwp_form must be 0 or 1");
+  if (!(net->sc_scale >= 0.f) || !(net->lwp_scale >= 0.f)) return fail(PB_E_INVALID, "sc_scale and lwp_scale must be >= 0");
   const int S = net->n_stages;
   out.assign(S, Stage());
   int C = net->in_c, H = net->in_h, W = net->in_w;
@@ -301,6 +303,8 @@ struct pb_ctx {
   int64_t ticks = 0;
   int launch_mode = 0;
   int kernel_set = 0;
+  bool lwp_w = false;  // LWP in its weight-difference form
+  double sc_scale = 1.0, lwp_scale = 1.0;   // over-compensation factors on the stage delay
   bool stash = false;  // weight stashing: the backward pass reads the predicted weights its forward pass used
   bool bf16 = false;   // bf16 activation mode: tensors that cross a stage boundary are rounded to bf16
   std::vector<StepDesc> steps;         // sorted by phase
@@ -351,9 +355,9 @@ int bwd_w_tiles(int K, int C, int k, int P, bool bias) {
   return cdiv(nW, per) + (bias ? cdiv(K, per) : 0);
 }
 
-void sc_coeffs(double m, int D, double* a, double* b) {
-  *a = (D == 0) ? 1.0 : pow(m, (double)D);
-  *b = (m == 1.0) ? (double)D : (1.0 - *a) / (1.0 - m);
+void sc_coeffs(double m, double D, double* a, double* b) {
+  *a = (D == 0.0) ? 1.0 : pow(m, D);
+  *b = (m == 1.0) ? D : (1.0 - *a) / (1.0 - m);
 }
 
 // ---------------------------------------------------------- GEMM tiling
@@ -509,9 +513,10 @@ bool head_fits(int C, int HW, int K, bool gap, int G) {
 // Coefficients of the stage's update (Eqs. gscv, gscw, scd, lwp_v_form) by mitigation mode.
 void set_update_coeffs(const pb_ctx* c, const Stage& a, StepDesc* d) {
   double ca = 1.0, cb = 0.0;
-  if (c->mitigation == 1 || c->mitigation == 3) sc_coeffs((double)c->m, a.De, &ca, &cb);
-  const double T = (c->mitigation >= 2) ? (double)a.De : 0.0;
+  if (c->mitigation == 1 || c->mitigation == 3) sc_coeffs((double)c->m, c->sc_scale * a.De, &ca, &cb);
+  const double T = (c->mitigation >= 2) ? c->lwp_scale * a.De : 0.0;
   d->fa = (float)ca; d->fb = (float)cb; d->flrT = (float)((double)c->lr * T); d->flr = c->lr; d->fm = c->m;
+  if (c->lwp_w) { d->flags |= F_LWP_W; d->flrT = (float)T; }   // w_hat = w' + T (w' - w)
 }
 
 // Whether the GroupNorm backward of a C x HW map in G groups can run as one
@@ -1321,6 +1326,9 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   c->kernel_set = net->kernel_set;
   c->bf16 = net->act_dtype == 1;
   c->stash = net->bwd_weights == 1;
+  c->lwp_w = net->lwp_form == 1;
+  c->sc_scale = net->sc_scale > 0.f ? net->sc_scale : 1.0;
+  c->lwp_scale = net->lwp_scale > 0.f ? net->lwp_scale : 1.0;
   c->loss_cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   c->stream = (hipStream_t)net->stream;
   for (const Stage& a : st) c->n_params += a.n_params;

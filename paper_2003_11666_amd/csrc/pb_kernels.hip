@@ -460,11 +460,12 @@ __device__ void step_gnb_apply(const LDesc& d, int tile, int t) {
 // step that produced its gradient): w, v at index i in place, w_hat into the other copy.
 __device__ __forceinline__ void update_one(const LDesc& d, int i, float g) {
   float vv = GP(d.v)[i], wv = GP(d.w)[i];
+  const float w_old = wv;
   vv = fmaf(UNIF(d.fm), vv, g);
   wv = fmaf(-UNIF(d.flr), fmaf(UNIF(d.fa), vv, UNIF(d.fb) * g), wv);
   GP((float*)d.b)[i] = vv;
   GP((float*)d.w)[i] = wv;
-  if (d.what) GP(d.what)[i] = fmaf(-UNIF(d.flrT), vv, wv);
+  if (d.what) GP(d.what)[i] = (UNI(d.flags) & F_LWP_W) ? fmaf(UNIF(d.flrT), wv - w_old, wv) : fmaf(-UNIF(d.flrT), vv, wv);
 }
 
 // Limit of the one-workgroup GroupNorm backward: elements of a group (they
@@ -709,6 +710,7 @@ __device__ void step_update(const LDesc& d, int tile) {
   const int n4 = UNI(d.n) >> 2;
   const int i0 = tile * (UPD_TILE / 4) + threadIdx.x;
   const float a = UNIF(d.fa), b = UNIF(d.fb), lrT = UNIF(d.flrT), lr = UNIF(d.flr), m = UNIF(d.fm);
+  const bool wform = UNI(d.flags) & F_LWP_W;
   const gv4* gp = (const gv4*)d.gw;
   const gv4* vp = (const gv4*)d.v;
   const gv4* wp = (const gv4*)d.w;
@@ -736,7 +738,7 @@ __device__ void step_update(const LDesc& d, int tile) {
       if (ho) {
         v4f p;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) p[e] = fmaf(-lrT, v2[e], w2[e]);
+        for (int e = 0; e < 4; ++e) p[e] = wform ? fmaf(lrT, w2[e] - wv[u][e], w2[e]) : fmaf(-lrT, v2[e], w2[e]);
         ho[i] = p;
       }
     }

@@ -230,3 +230,46 @@ def test_weight_stashing(name, mit):
         outs.append(e.read_weights())
         e.close()
     assert np.abs(outs[0] - outs[1]).max() > 1e-5
+
+
+@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_resnet"])
+def test_overcompensation(name):
+    """SC_2D + LWP_2D: the same kernels with the coefficients of twice the delay."""
+    net = W.config(name)
+    xs, ys = W.sample_pool(net)
+    K = 60
+    PBEngine = _engine()
+    eng = PBEngine(net, mitigation=3, sc_scale=2.0, lwp_scale=2.0)
+    orc = O.PBOracle(net, mitigation=3, sc_scale=2.0, lwp_scale=2.0)
+    for t in range(K):
+        eng.tick(xs[t % len(ys)], ys[t % len(ys)])
+        orc.tick(xs[t % len(ys)], ys[t % len(ys)])
+    from tests.parity_util import rel_errors, tensor_slices
+    e_inf, e_l2, where = rel_errors(eng.read_weights(), orc.read_weights(), tensor_slices(net))
+    assert max(e_inf, e_l2) <= TOL, (e_inf, e_l2, where)
+    assert np.allclose(eng.loss_history(), orc.loss_history(), rtol=1e-4, atol=1e-4)
+    eng.close()
+
+
+@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_resnet", "tiny_vgg"])
+def test_lwp_weight_difference_form(name):
+    """lwp_form='w' (Eq. lwp_w_form): w_hat = w + T (w - w_prev), built inside the fused update
+    from the weights before and after it."""
+    net = W.config(name)
+    xs, ys = W.sample_pool(net)
+    K = 60
+    PBEngine = _engine()
+    eng = PBEngine(net, mitigation=3, lwp_form="w")
+    orc = O.PBOracle(net, mitigation=3, lwp_form="w")
+    ref_v = O.PBOracle(net, mitigation=3)
+    for t in range(K):
+        eng.tick(xs[t % len(ys)], ys[t % len(ys)])
+        orc.tick(xs[t % len(ys)], ys[t % len(ys)])
+        ref_v.tick(xs[t % len(ys)], ys[t % len(ys)])
+    from tests.parity_util import rel_errors, tensor_slices
+    e_inf, e_l2, where = rel_errors(eng.read_weights(), orc.read_weights(), tensor_slices(net))
+    # w - w_prev is a difference of nearly equal fp32 numbers: its rounding error, times T, enters w_hat
+    assert max(e_inf, e_l2) <= 2e-5, (e_inf, e_l2, where)
+    assert np.abs(orc.read_weights() - ref_v.read_weights()).max() > 1e-4
+    assert np.allclose(eng.loss_history(), orc.loss_history(), rtol=1e-4, atol=1e-4)
+    eng.close()

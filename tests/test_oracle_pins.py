@@ -396,3 +396,75 @@ def test_bf16_rounding_points():
     for s, g in orc.grad_mail.items():
         assert torch.equal(g, g.float().bfloat16().double())
     assert np.isfinite(orc.loss_history()).all()
+
+
+# --------------------------------------------------------------------------
+# Over-compensation (Section "Combined Mitigation": LWP_2D, SC_2D and their combination)
+# --------------------------------------------------------------------------
+def test_overcompensation_coefficients_and_forms():
+    """The scaled variants are the same update with the coefficients of delay
+    scale*D: a = m^(2D), b = (1 - m^(2D))/(1 - m), T = 2D for the doubled forms;
+    the tick form and the sample-indexed form agree with them switched on."""
+    net = W.config("tiny_resnet")
+    S = len(net["stages"])
+    m = net["momentum"]
+    orc = O.PBOracle(net, mitigation=3, sc_scale=2.0, lwp_scale=2.0)
+    for s in range(S):
+        D = 2 * (S - 1 - s)
+        a, b, T = orc.coef[s]
+        assert a == pytest.approx(m ** (2 * D), rel=1e-14)
+        assert b == pytest.approx(sum(m ** i for i in range(2 * D)), rel=1e-12)   # geometric sum, Eq. scd
+        assert T == 2 * D
+    xs, ys = W.sample_pool(net)
+    K = 4 * S + 3
+    for t in range(K):
+        orc.tick(xs[t % len(ys)], ys[t % len(ys)])
+    hist, losses = O.run_sample_indexed(net, K - (S - 1), xs, ys, mitigation=3, sc_scale=2.0, lwp_scale=2.0)
+    assert np.allclose(orc.loss_history(), losses[:K - S + 1], rtol=1e-10)
+    plain = O.PBOracle(net, mitigation=3)
+    for t in range(K):
+        plain.tick(xs[t % len(ys)], ys[t % len(ys)])
+    differs = False
+    for s in range(S):
+        k = max(0, K - 2 * (S - 1) + s)
+        for name_, t_ in hist[s][k][0].items():
+            assert torch.allclose(orc.w[s][name_], t_, rtol=1e-10, atol=1e-13), (s, name_)
+            differs |= not torch.allclose(orc.w[s][name_], plain.w[s][name_], rtol=1e-6, atol=1e-9)
+    assert differs
+
+
+def test_overcompensated_lwp_on_the_quadratic():
+    """LWP with horizon T on the scalar quadratic: with constant velocity the
+    prediction lands exactly T steps ahead (Eq. lwp_v_form), whatever the delay."""
+    lr, m = 0.1, 0.0
+    # m = 0, lam = 0 would be static; use the predictor alone: w_t = w_0 - lr*v*t
+    w0, v = torch.tensor([1.0, -2.0], dtype=O.DT), torch.tensor([0.3, 0.7], dtype=O.DT)
+    for T in (0, 3, 8):
+        pred = O.lwp_predict(w0, v, lr, float(T))
+        assert torch.allclose(pred, w0 - lr * T * v, rtol=0, atol=1e-15)
+
+
+# --------------------------------------------------------------------------
+# LWP in its weight-difference form (Eq. lwp_w_form)
+# --------------------------------------------------------------------------
+def test_lwp_weight_form():
+    """w_hat = w + T (w - w_prev).  Without Spike Compensation w - w_prev = -lr v, so the form equals
+    the velocity form exactly (Section "Linear Weight Prediction"); with SC the two differ; the tick
+    form and the sample-indexed form agree on it."""
+    net = W.config("tiny_resnet")
+    xs, ys = W.sample_pool(net)
+    S = len(net["stages"])
+    K = 4 * S + 3
+    a, b = O.PBOracle(net, mitigation=2, lwp_form="w"), O.PBOracle(net, mitigation=2)
+    c, d = O.PBOracle(net, mitigation=3, lwp_form="w"), O.PBOracle(net, mitigation=3)
+    for t in range(K):
+        for o in (a, b, c, d):
+            o.tick(xs[t % len(ys)], ys[t % len(ys)])
+    assert np.abs(a.read_weights() - b.read_weights()).max() <= 1e-13
+    assert np.abs(c.read_weights() - d.read_weights()).max() > 1e-4
+    hist, losses = O.run_sample_indexed(net, K - (S - 1), xs, ys, mitigation=3, lwp_form="w")
+    assert np.allclose(c.loss_history(), losses[:K - S + 1], rtol=1e-10)
+    for s in range(S):
+        k = max(0, K - 2 * (S - 1) + s)
+        for name_, t_ in hist[s][k][0].items():
+            assert torch.allclose(c.w[s][name_], t_, rtol=1e-10, atol=1e-13), (s, name_)
