@@ -107,8 +107,14 @@ size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays);
  * uses predicted weights that many updates old, read from a ring of
  * delays[s] - 2(S-1-s) + 2 weight versions per stage (more device memory:
  * ask pb_arena_bytes with the same delays), and SC / LWP use delays[s] as the
- * stage's delay.  delays[s] < 2(S-1-s) is rejected with PB_E_UNSUPPORTED: a
- * pipeline that never stalls cannot produce it.  Weights are initialised on
+ * stage's delay.  If any delays[s] < 2(S-1-s) -- which a pipeline that never
+ * stalls cannot produce -- the context runs the sample-indexed form instead
+ * (Eqs. wi, sgdpb, wf): one pb_tick pushes one sample through all stages in
+ * dependency order, forward pass of stage s with the weights delays[s] updates
+ * old, backward pass with the current ones, then the update; pb_loss_history
+ * then has one entry per tick.  With all delays zero that is SGD with
+ * momentum.  A verification mode (several launches per stage and tick), not
+ * a performance path.  Negative delays are rejected.  Weights are initialised on
  * the host from `seed` (Kaiming normal, std sqrt(2/fan_in), biases 0,
  * GroupNorm scale 1 / shift 0) and uploaded; velocity starts at 0.
  * The descriptor is copied; the caller may free it afterwards. */

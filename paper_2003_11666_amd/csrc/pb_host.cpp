@@ -195,16 +195,22 @@ int parse_net(const pb_net_desc* net, std::vector<Stage>& out) {
 
 // delays[s] = the pipeline's own 2(S-1-s): depth-2 ring of predicted weights (one being read, one being
 // written).  Larger: the forward pass reads a version that many updates older, kept in a deeper ring.
-// Smaller: a pipeline that never stalls cannot produce it (stage s+1 would need stage s's output of the
-// same tick).
-int check_delays(std::vector<Stage>& st, const int32_t* delays) {
+// Any delay smaller than the pipeline's own: a pipeline that never stalls cannot produce it (stage s+1
+// would need stage s's output of the same tick), so the whole network switches to the sample-indexed
+// form (Eqs. wi, sgdpb, wf): one tick pushes one sample through all stages in dependency order, forward
+// pass of stage s with the weights delays[s] updates old, backward pass with the current ones, then the
+// update.  That is a verification mode (a few launches per stage and tick), not a performance path.
+int check_delays(std::vector<Stage>& st, const int32_t* delays, bool* sequential) {
+  *sequential = false;
   if (!delays) return PB_OK;
   for (size_t s = 0; s < st.size(); ++s) {
     if (delays[s] < 0) return fail(PB_E_INVALID, "delay of stage %zu is negative", s);
-    if (delays[s] < st[s].D)
-      return fail(PB_E_UNSUPPORTED, "delay %d of stage %zu is below the pipeline's 2(S-1-s)=%d", delays[s], s, st[s].D);
-    if (delays[s] - st[s].D > 4096) return fail(PB_E_UNSUPPORTED, "delay %d of stage %zu: more than 4096 extra weight versions", delays[s], s);
+    if (delays[s] < st[s].D) *sequential = true;
+    if (delays[s] > 4096 + st[s].D) return fail(PB_E_UNSUPPORTED, "delay %d of stage %zu: too many weight versions", delays[s], s);
+  }
+  for (size_t s = 0; s < st.size(); ++s) {
     st[s].De = delays[s];
+    if (*sequential) st[s].D = 0;      // nothing is in flight between a sample's forward and backward pass
   }
   return PB_OK;
 }
@@ -303,6 +309,7 @@ struct pb_ctx {
   int64_t ticks = 0;
   int launch_mode = 0;
   int kernel_set = 0;
+  bool sequential = false;   // sample-indexed form: one sample through all stages per tick (delays below the pipeline's own)
   bool lwp_w = false;  // LWP in its weight-difference form
   double sc_scale = 1.0, lwp_scale = 1.0;   // over-compensation factors on the stage delay
   bool stash = false;  // weight stashing: the backward pass reads the predicted weights its forward pass used
@@ -542,6 +549,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   g_tile_target = std::max(4, std::min(32, 1024 / (3 * S)));
   if (const char* e = getenv("PB_TILE_TARGET")) g_tile_target = std::max(1, atoi(e));
   const Layout& L = c->L;
+  std::vector<int> bwd0(S, 0);   // per stage: phase its backward chain starts in
   for (int s = 0; s < S; ++s) {
     const Stage& a = c->st[s];
     const StageBufs& b = L.sb[s];
@@ -565,17 +573,22 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       d.pmask = mask; d.pdepth = wdepth; d.plag = a.De; d.pstride = (int)a.padded;
     };
     float* gr = c->f(L.g + a.off);
-    const int t_f = s, t_b = 2 * (S - 1) - s;
+    const bool seq = c->sequential;
+    const int t_f = seq ? 0 : s, t_b = seq ? 0 : 2 * (S - 1) - s;
+    const int ML = seq ? 0 : -1;                       // lag of the mailbox slot a producer writes (next tick's, or this tick's)
+    auto SL = [&](int A) { return seq ? 0 : s - A; };   // lag of the skip tensor tapped at stage A
+    auto TL = [&](int dist) { return seq ? 0 : dist; }; // lag of a skip gradient
+    const int NS = seq ? 1 : S;                        // depth of the label ring / samples in flight before the loss
     const TRef x_f = ring(c, b.xring, D + 2, a.in_elems(), 0);
     const TRef x_b = ring(c, b.xring, D + 2, a.in_elems(), D);
     TRef y_out;   // where the stage output goes
-    if (s < S - 1) y_out = ring(c, L.sb[s + 1].xring, c->st[s + 1].D + 2, a.out_elems(), -1);
+    if (s < S - 1) y_out = ring(c, L.sb[s + 1].xring, c->st[s + 1].D + 2, a.out_elems(), ML);
     else y_out = ring(c, b.logits, 1, a.K, 0);
     int ph = 0;
     if (s == 0) {
       // the sample arrives in phase 0; the first stage's forward chain follows it
       StepDesc d = blank(K_INGEST, 0, 0);
-      d.n = a.in_elems(); d.n_stages = S;
+      d.n = a.in_elems(); d.n_stages = NS;
       d.dx = x_f;
       d.labels = c->labels_dev;
       d.ntiles = cdiv(d.n, BLK);
@@ -589,7 +602,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     if (fused_head) {
       StepDesc d = blank(K_HEAD, s, t_f);
       d.C = a.Cin; d.H = a.Hin; d.W = a.Win; d.K = a.K; d.G = a.pre_gn ? a.G : 1;
-      d.n_stages = S; d.loss_cap = c->loss_cap;
+      d.n_stages = NS; d.loss_cap = c->loss_cap;
       if (a.pre_gn) d.flags |= F_PRE_AFFINE;
       if (a.pre_relu) d.flags |= F_PRE_RELU;
       if (a.gap) d.flags |= F_DU_GAP;
@@ -605,7 +618,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       // stashing they are the very slot the forward pass reads)
       fwd_params(d, PF_W | (a.has_bias ? PF_B : 0) | (a.pre_gn ? PF_GAMMA | PF_BETA : 0) |
                         (c->stash ? PF_WP | (a.pre_gn ? PF_SKIPBASE : 0) : 0));
-      d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
+      d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), ML);
       d.loss_log = c->f(L.loss);
       d.labels = c->labels_dev;
       d.ntiles = 1;
@@ -660,7 +673,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         if (a.add) {
           const int A = a.skip_from;
           d.flags |= F_SKIP;
-          d.skip = ring(c, L.sb[A].xring, c->st[A].D + 2, c->st[A].in_elems(), s - A);
+          d.skip = ring(c, L.sb[A].xring, c->st[A].D + 2, c->st[A].in_elems(), SL(A));
           d.sC = a.sC; d.sH = a.sH; d.sW = a.sW; d.sstride = a.sstride;
           if (a.proj) { d.flags |= F_PROJ; d.wp = wf + a.o_wp; }
         }
@@ -701,7 +714,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     }
     if (a.ce) {
       StepDesc d = blank(K_CE, s, t_f);
-      d.n = a.K; d.n_stages = S; d.loss_cap = c->loss_cap;
+      d.n = a.K; d.n_stages = NS; d.loss_cap = c->loss_cap;
       d.x = ring(c, b.logits, 1, a.K, 0);
       d.dx = ring(c, b.dlogits, 1, a.K, 0);
       d.loss_log = c->f(L.loss);
@@ -711,6 +724,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     }
     // ----------------------------------------------------------- backward
     int pb = (s == S - 1) ? ph : 0;
+    bwd0[s] = pb;
     const TRef dy_src = (s == S - 1) ? ring(c, b.dlogits, 1, a.K, 0)
                                      : ring(c, b.gradbox, 2, a.out_elems(), 0);
     TRef dz_src = dy_src;
@@ -790,9 +804,9 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       if (a.pre_gn) {
         d.dx = ring(c, b.da, 1, a.gap ? a.C : a.in_elems(), 0);
       } else {
-        d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
+        d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), ML);
         if (a.pre_relu) { d.flags |= F_MASK_X; d.x = x_b; }
-        if (a.tap_dist) { d.flags |= F_ADD_SKG; d.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
+        if (a.tap_dist) { d.flags |= F_ADD_SKG; d.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), TL(a.tap_dist)); }
         if (c->bf16) d.flags |= F_BF16_OUT;          // this gradient leaves the stage
       }
       d.ntiles = cdiv((int64_t)a.C * a.H * a.W, BLK);
@@ -811,7 +825,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         StepDesc d = blank(K_CONV_BWD_W, s, t_b);
         d.C = a.sC; d.H = a.sH; d.W = a.sW; d.K = a.K; d.OH = a.OH; d.OW = a.OW;
         d.k = 1; d.stride = a.sstride; d.pad = 0;
-        d.x = ring(c, L.sb[A].xring, ta.D + 2, ta.in_elems(), D + (s - A));
+        d.x = ring(c, L.sb[A].xring, ta.D + 2, ta.in_elems(), D + SL(A));
         d.dy = dy_src;
         d.gw = gr + a.o_wp;
         d.ntiles = bwd_w_tiles(a.K, a.sC, 1, a.OH * a.OW, false);
@@ -860,8 +874,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         d.kind = K_GN_BWD;
         if (c->bf16) d.flags |= F_BF16_OUT;
         if (s > 0) {
-          d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
-          if (a.tap_dist) { d.flags |= F_ADD_SKG; d.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
+          d.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), ML);
+          if (a.tap_dist) { d.flags |= F_ADD_SKG; d.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), TL(a.tap_dist)); }
         }
         // this step ends the stage's backward chain and is the only producer of the scale / shift
         // gradients: it updates those two tensors itself, so that the rest of the stage can be
@@ -886,12 +900,33 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
           StepDesc e = d;
           e.kind = K_GNB_APPLY;
           if (c->bf16) e.flags |= F_BF16_OUT;
-          e.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), -1);
-          if (a.tap_dist) { e.flags |= F_ADD_SKG; e.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), a.tap_dist); }
+          e.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), ML);
+          if (a.tap_dist) { e.flags |= F_ADD_SKG; e.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), TL(a.tap_dist)); }
           e.ntiles = cdiv(a.in_elems(), BLK);
           out.push_back({pb++, e});
         }
       }
+    }
+  }
+  // Sample-indexed form: the chains run one after the other -- forward of stage 0, 1, ..., then backward
+  // of the last stage down to stage 0 -- instead of side by side.
+  if (c->sequential) {
+    auto is_bwd = [](const StepDesc& d) {
+      return d.kind == K_GNB_REDUCE || d.kind == K_GNB_APPLY || d.kind == K_GN_BWD || d.kind == K_CONV_BWD_X ||
+             d.kind == K_CONV_BWD_W || d.kind == K_BIAS_GRAD || d.kind == K_COPY || (d.kind == K_GEMM && d.g.gm != 1);
+    };
+    std::vector<int> lenF(S, 0), lenB(S, 0), baseF(S, 0), baseB(S, 0);
+    for (auto& pr : out) {
+      const int st_ = pr.second.stage;
+      if (is_bwd(pr.second)) lenB[st_] = std::max(lenB[st_], pr.first - bwd0[st_] + 1);
+      else lenF[st_] = std::max(lenF[st_], pr.first + 1);
+    }
+    for (int s = 1; s < S; ++s) baseF[s] = baseF[s - 1] + lenF[s - 1];
+    baseB[S - 1] = baseF[S - 1] + lenF[S - 1];
+    for (int s = S - 2; s >= 0; --s) baseB[s] = baseB[s + 1] + lenB[s + 1];
+    for (auto& pr : out) {
+      const int st_ = pr.second.stage;
+      pr.first = is_bwd(pr.second) ? baseB[st_] + (pr.first - bwd0[st_]) : baseF[st_] + pr.first;
     }
   }
   // 16-byte loads of the A operand need a 16-byte aligned operand (the arena is)
@@ -1244,12 +1279,14 @@ const char* pb_last_error(void) { return g_err.c_str(); }
 
 size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays) {
   std::vector<Stage> st;
-  if (parse_net(net, st) != PB_OK || check_delays(st, delays) != PB_OK) return 0;
+  bool sequential = false;
+  if (parse_net(net, st) != PB_OK || check_delays(st, delays, &sequential) != PB_OK) return 0;
   pb_ctx tmp;
   tmp.st = st; tmp.S = (int)st.size();
   tmp.kernel_set = net->kernel_set;
   tmp.bf16 = net->act_dtype == 1;
   tmp.stash = net->bwd_weights == 1;
+  tmp.sequential = sequential;
   const int cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   Plan pl;
   Layout L;
@@ -1313,7 +1350,8 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   std::vector<Stage> st;
   int rc = parse_net(net, st);
   if (rc != PB_OK) return rc;
-  rc = check_delays(st, delays);
+  bool sequential = false;
+  rc = check_delays(st, delays, &sequential);
   if (rc != PB_OK) return rc;
   if (!(momentum >= 0.f && momentum <= 1.f)) return fail(PB_E_INVALID, "momentum must be in [0,1]");
   if (!(lr >= 0.f)) return fail(PB_E_INVALID, "learning rate must be >= 0");
@@ -1327,6 +1365,7 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   c->bf16 = net->act_dtype == 1;
   c->stash = net->bwd_weights == 1;
   c->lwp_w = net->lwp_form == 1;
+  c->sequential = sequential;
   c->sc_scale = net->sc_scale > 0.f ? net->sc_scale : 1.0;
   c->lwp_scale = net->lwp_scale > 0.f ? net->lwp_scale : 1.0;
   c->loss_cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
@@ -1447,7 +1486,8 @@ int64_t pb_read_velocity(pb_ctx* c, float* dst, int64_t cap) {
 
 int64_t pb_loss_history(pb_ctx* c, float* dst, int64_t cap) {
   if (!c) return fail(PB_E_INVALID, "NULL context");
-  const int64_t count = std::max<int64_t>(0, c->ticks - c->S + 1);
+  // pipelined: the sample fed by tick i reaches the loss at tick i + S - 1; sample-indexed form: at tick i
+  const int64_t count = c->sequential ? c->ticks : std::max<int64_t>(0, c->ticks - c->S + 1);
   const int64_t avail = std::min<int64_t>(count, c->loss_cap);
   if (!dst) return avail;
   const int64_t n = std::min(avail, cap);

@@ -201,13 +201,49 @@ def test_delays_above_the_pipelines_own(name, extra):
     print(f"{name}: delays {delays}, worst tensor error {worst:.2e}", file=sys.stderr)
 
 
-def test_delays_below_the_pipelines_own_are_rejected():
-    from paper_2003_11666_amd.binding import PBError
+def _sample_indexed_case(name, delays, mit, K=40):
     PBEngine = _engine()
-    net = W.config("tiny_mlp")
+    net = W.config(name)
     S = len(net["stages"])
-    with pytest.raises(PBError):
-        PBEngine(net, delays=[0] * S)
+    xs, ys = W.sample_pool(net)
+    eng = PBEngine(net, delays=delays, mitigation=mit)
+    for t in range(K):
+        eng.tick(xs[t % len(ys)], ys[t % len(ys)])
+    w_gpu, l_gpu = eng.read_weights(), eng.loss_history()
+    eng.close()
+    hist, losses = O.run_sample_indexed(net, K, xs, ys, delays=delays, mitigation=mit)
+    assert len(l_gpu) == K                      # one loss per tick in this form
+    assert np.allclose(l_gpu, np.asarray(losses), rtol=1e-4, atol=1e-4)
+    off = 0
+    for s, st in enumerate(net["stages"]):
+        params, _ = hist[s][K]                  # every stage has seen K updates
+        for pname, shape, _ in O.stage_param_specs(st):
+            cnt = int(np.prod(shape))
+            ref = params[pname].numpy().reshape(-1)
+            got = w_gpu[off:off + cnt].astype(np.float64)
+            mx = np.abs(ref).max()
+            err = np.abs(got - ref).max() / mx if mx > 0 else np.abs(got).max()
+            assert err <= 2e-5, (s, pname, err)
+            off += cnt
+    assert off == w_gpu.size
+
+
+@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_vgg", "tiny_resnet", "tiny_bottleneck", "odd_resnet"])
+@pytest.mark.parametrize("mit", [3, 0])
+def test_zero_delays_run_the_sample_indexed_form(name, mit):
+    """All delays zero: no pipeline can produce that, the library switches to the sample-indexed form
+    (one sample through all stages per tick), which is then plain SGD with momentum -- the oracle's
+    form of it is pinned to torch.optim.SGD in tests/test_oracle_pins.py."""
+    S = len(W.config(name)["stages"])
+    _sample_indexed_case(name, [0] * S, mit)
+
+
+@pytest.mark.parametrize("name,delays", [("tiny_resnet", (3, 0, 1, 2, 0, 0)), ("tiny_vgg", (1, 7, 0, 0)),
+                                         ("tiny_bottleneck", (2, 2, 2, 1, 1, 1, 0, 0))])
+def test_small_delays_run_the_sample_indexed_form(name, delays):
+    """Delays below the pipeline's own for some stages (and above for others): forward pass of stage s
+    with the weights delays[s] updates old, SC and LWP with that delay."""
+    _sample_indexed_case(name, list(delays), 3)
 
 
 @pytest.mark.parametrize("name", ["tiny_mlp", "tiny_vgg", "tiny_resnet", "small_resnet", "tiny_bottleneck"])
@@ -273,3 +309,36 @@ def test_lwp_weight_difference_form(name):
     assert np.abs(orc.read_weights() - ref_v.read_weights()).max() > 1e-4
     assert np.allclose(eng.loss_history(), orc.loss_history(), rtol=1e-4, atol=1e-4)
     eng.close()
+
+
+@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_vgg", "tiny_resnet", "tiny_bottleneck"])
+def test_zero_delays_equal_torch_sgd_with_momentum(name):
+    """With every delay zero the library must be plain SGD with momentum for any mitigation (SC and LWP
+    with zero delay are the identity): checked against torch.optim.SGD on an autograd model of the net."""
+    import torch
+    from tests import torch_ref as R
+    PBEngine = _engine()
+    net = W.config(name)
+    S = len(net["stages"])
+    xs, ys = W.sample_pool(net)
+    n = 25
+    params = R.leaf_params(net, 42)
+    opt = torch.optim.SGD([t for p in params for t in p.values()], lr=net["lr"], momentum=net["momentum"])
+    ref_losses = []
+    for i in range(n):
+        opt.zero_grad()
+        loss = R.forward_loss(net, params, xs[i % len(ys)], ys[i % len(ys)])
+        loss.backward()
+        opt.step()
+        ref_losses.append(float(loss.detach()))
+    ref = R.flat(params).detach().numpy()
+    for mit in (0, 3):
+        eng = PBEngine(net, delays=[0] * S, mitigation=mit)
+        for i in range(n):
+            eng.tick(xs[i % len(ys)], ys[i % len(ys)])
+        w = eng.read_weights().astype(np.float64)
+        assert np.allclose(eng.loss_history(), ref_losses, rtol=1e-4, atol=1e-5)
+        from tests.parity_util import rel_errors, tensor_slices
+        e_inf, e_l2, where = rel_errors(w.astype(np.float32), ref, tensor_slices(net))
+        assert max(e_inf, e_l2) <= 2e-5, (mit, e_inf, e_l2, where)
+        eng.close()

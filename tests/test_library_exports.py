@@ -35,16 +35,18 @@ def test_descriptor_validation_on_host():
     for name in ("mlp", "vgg11", "resnet20", "wide"):
         d, keep = B.marshal_net(W.config(name))
         assert lib.pb_arena_bytes(ctypes.byref(d), None) > 0, name
-    # the pipeline's own delays and larger ones accepted (larger: deeper weight-version rings, more memory),
-    # smaller ones refused
+    # the pipeline's own delays, larger ones (deeper weight-version rings, more memory) and smaller ones
+    # (sample-indexed form) are all accepted; negative ones are refused
     net = W.config("tiny_resnet")
     S = len(net["stages"])
     d, keep = B.marshal_net(net)
     nat = (ctypes.c_int32 * S)(*[2 * (S - 1 - s) for s in range(S)])
     assert lib.pb_arena_bytes(ctypes.byref(d), nat) > 0
     zero = (ctypes.c_int32 * S)(*([0] * S))
-    assert lib.pb_arena_bytes(ctypes.byref(d), zero) == 0
-    assert b"below the pipeline" in lib.pb_last_error()
+    assert lib.pb_arena_bytes(ctypes.byref(d), zero) > 0
+    neg = (ctypes.c_int32 * S)(*([0] * (S - 1) + [-1]))
+    assert lib.pb_arena_bytes(ctypes.byref(d), neg) == 0
+    assert b"negative" in lib.pb_last_error()
     more = (ctypes.c_int32 * S)(*[2 * (S - 1 - s) + 3 for s in range(S)])
     assert lib.pb_arena_bytes(ctypes.byref(d), more) > lib.pb_arena_bytes(ctypes.byref(d), nat)
     # broken descriptor: loss op missing
