@@ -23,6 +23,7 @@
 
 namespace pb {
 
+template <int V> struct IConst { static constexpr int value = V; };
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) v4f gv4;
 typedef __attribute__((address_space(3))) v4f lv4;
@@ -47,8 +48,13 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
   const int wk_id = wv & (wk - 1), wn_id = (wv >> lg(wk)) & (wn - 1), wm_id = wv >> (lg(wk) + lg(wn));
   const int tiles_n = UNI(d.g.tiles_n);
   const int tm = UNI(fdiv(tile, frcp(tiles_n))), tn = tile - tm * tiles_n;
-  const int MT = UNI(d.g.MT);
-  const int m0 = tm * MT, n0 = tn * UNI(d.g.NT);
+  const int MT = UNI(d.g.MT), NT = UNI(d.g.NT);
+  // a workgroup runs nsub consecutive column tiles one after the other: the
+  // descriptor and the offset table are fetched once, an A block that is a single
+  // chunk stays in LDS, and the requests of the next column tile are in flight
+  // while this one is contracted and stored
+  const int nsub = UNI(d.g.nsub);
+  const int m0 = tm * MT, n0 = tn * nsub * NT;
   const int flags = UNI(d.flags);
   const int kq = lane >> 4;
   // with one or two subtiles per wave consecutive MFMAs would wait for each other's
@@ -57,6 +63,92 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
   v4f acc[NI], acc2[NI];
 #pragma unroll
   for (int j = 0; j < NI; ++j) { acc[j] = (v4f){0.f, 0.f, 0.f, 0.f}; acc2[j] = (v4f){0.f, 0.f, 0.f, 0.f}; }
+  // sums of a tile: split of the reduction across waves, epilogue, store
+  auto finish = [&](int n0s) {
+    if (DUAL) {
+#pragma unroll
+      for (int j = 0; j < NI; ++j) acc[j] += acc2[j];
+    }
+    PB_TS(7);
+    // ---- reduce the split of the reduction across waves (fixed order)
+    if (wk > 1) {
+      __syncthreads();
+      lfloat* red = smem;   // [wave][j][lane] float4
+      if (wk_id > 0) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) *(lv4*)(red + ((wv * 4 + j) * 64 + lane) * 4) = acc[j];
+      }
+      __syncthreads();
+      if (wk_id == 0) {
+        for (int w2 = 1; w2 < wk; ++w2)
+#pragma unroll
+          for (int j = 0; j < NI; ++j) {
+            const v4f r = *(const lv4*)(red + (((wv + w2) * 4 + j) * 64 + lane) * 4);
+            acc[j][0] += r[0]; acc[j][1] += r[1]; acc[j][2] += r[2]; acc[j][3] += r[3];
+          }
+      }
+    }
+    PB_TS(8);
+    if (wk_id != 0) return;
+    // ---- epilogue: lane holds C[i = 4*(lane/16) + r][j = lane%16]
+    const int M = UNI(d.g.M), N = UNI(d.g.N);
+    gfloat* out = (GM == 1) ? at(d.y, t) : (GM == 2) ? at(d.dx, t) : GP(d.gw);
+    const int mrow = m0 + wm_id * 16 + 4 * kq;
+    const bool extras = (GM == 1 && (flags & (F_BIAS | F_SKIP))) || (GM == 2 && (flags & (F_MASK_X | F_ADD_SKG))) ||
+                        (GM != 3 && (flags & F_BF16_OUT));
+    if (!extras) {
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        const int n = n0s + (wn_id * ni + j) * 16 + (lane & 15);
+        if (n < N) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (mrow + r < M) out[(size_t)(mrow + r) * N + n] = acc[j][r];
+        }
+      }
+      return;
+    }
+    const gfloat* skip = (GM == 1 && (flags & F_SKIP) && !(flags & F_PROJ)) ? (const gfloat*)at(d.skip, t) : nullptr;
+    const gfloat* xm = (GM == 2 && (flags & F_MASK_X)) ? (const gfloat*)at(d.x, t) : nullptr;
+    const gfloat* skg = (GM == 2 && (flags & F_ADD_SKG)) ? (const gfloat*)at(d.skg, t) : nullptr;
+    const gfloat* bias = (GM == 1 && (flags & F_BIAS)) ? GP(d.b) : nullptr;
+    // every operand of the epilogue is requested before the first one is used
+    PB_TS(18);
+    float add[NI][4], msk[NI][4];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      const int n = n0s + (wn_id * ni + j) * 16 + (lane & 15);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        add[j][r] = 0.f; msk[j][r] = 1.f;
+        if (n < N && mrow + r < M) {
+          const size_t o = (size_t)(mrow + r) * N + n;
+          if (bias) add[j][r] = bias[mrow + r];
+          if (skip) add[j][r] += skip[o];
+          if (skg) add[j][r] = skg[o];
+          if (xm) msk[j][r] = xm[o];
+        }
+      }
+    }
+    PB_TS(19);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      const int n = n0s + (wn_id * ni + j) * 16 + (lane & 15);
+      if (n >= N) continue;
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (mrow + r < M) {
+          float v = acc[j][r];
+          if (GM == 2 && !(msk[j][r] > 0.f)) v = 0.f;
+          out[(size_t)(mrow + r) * N + n] = rbf_if(GM != 3 && (flags & F_BF16_OUT), v + add[j][r]);
+        }
+      if (j == 0) PB_TS(21);
+      if (j == 1) PB_TS(22);
+      if (j == 2) PB_TS(23);
+    }
+    PB_TS(20);
+
+  };
   const int nops = (GM == 1 && (flags & F_PROJ)) ? 2 : 1;
 
   for (int op = 0; op < nops; ++op) {
@@ -87,25 +179,151 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
     const int border = gk - 1 - gpad;
 
     // first row (of the output map for forward / backward weights, of the input
-    // map for backward data) this tile touches; per-lane column offsets
-    int tile_row0 = 0, c_lo = 0, adj;
-    if (GM == 1) { tile_row0 = UNI(fdiv(n0, frcp(gOW))); adj = tile_row0 * gs * Wp; }
-    else if (GM == 2) { tile_row0 = UNI(fdiv(n0, frcp(gW))); adj = tile_row0 * Wp; }
-    else { c_lo = UNI(fdiv(n0, frcp(kk))); adj = c_lo * PRW; }
-    adj -= UNI(g.xoff);
-    int offn[NI];
+    // map for backward data) the current column tile touches; per-lane column offsets
+    int tile_row0 = 0, c_lo = 0, adj = 0;
+    auto tile_geometry = [&](int n0s) {
+      if (GM == 1) { tile_row0 = UNI(fdiv(n0s, frcp(gOW))); adj = tile_row0 * gs * Wp; }
+      else if (GM == 2) { tile_row0 = UNI(fdiv(n0s, frcp(gW))); adj = tile_row0 * Wp; }
+      else { c_lo = UNI(fdiv(n0s, frcp(kk))); adj = c_lo * PRW; }
+      adj -= UNI(g.xoff);
+    };
+    int tnv[NI], offn[NI];   // column offsets as the table has them, and relative to the patch of the column tile
+    auto tn_load = [&](int n0s) {
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-      const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
-      offn[j] = (n < N) ? tnb[n] - adj : 0;
-    }
+      for (int j = 0; j < NI; ++j) {
+        const int n = n0s + (wn_id * ni + j) * 16 + (lane & 15);
+        tnv[j] = (n < N) ? tnb[n] : -1;
+      }
+    };
+    tn_load(n0);
     if (!op) PB_TS(2);
-    __syncthreads();   // LDS may still be in use by the previous operand set
-    if (!op) PB_TS(9);
     const int patch_elems = CC * PRW;
     const int mte = (M - m0 < MT) ? M - m0 : MT;        // rows of the tile that exist
     const size_t co_stride = (size_t)gC * kk;           // GM 2: floats between the weights of consecutive output channels
     const int i_row = wm_id * 16 + (lane & 15);
+    const int lstride = (GM == 2) ? MT * kk : LDA;
+
+    // ---- A block as a 2-D copy: nseg segments of seg_pad floats, of which the first
+    // seg_len of the first nvalid segments come from memory and the rest is zero.
+    // Requests (a_issue) and the stores into LDS (a_commit) are separate so that the
+    // requests of chunk ch+1 can be in flight while chunk ch is contracted.
+    constexpr int AU = 10;
+    const int av = avec ? 4 : 1;                          // floats per request
+    struct APar { int nvalid, seg_len, spr, slots; float ispr; };
+    auto a_par = [&](int ch) {
+      const int q0 = ch * QC;
+      const int qe = (Q - q0 < QC) ? Q - q0 : QC, q4 = (qe + 3) & ~3;
+      int nseg, seg_pad;
+      APar p;
+      if (GM == 2) {
+        const float ikk = frcp(kk);
+        nseg = UNI(fdiv(q4 + kk - 1, ikk)); p.nvalid = UNI(fdiv(qe, ikk)); p.seg_len = mte * kk; seg_pad = MT * kk;
+      } else {
+        nseg = MT; p.nvalid = MT; p.seg_len = qe; seg_pad = q4;
+      }
+      p.spr = avec ? (seg_pad + 3) >> 2 : seg_pad;        // requests per segment
+      p.ispr = frcp(p.spr);
+      p.slots = nseg * p.spr;
+      return p;
+    };
+    auto a_src = [&](int ch, int r, int c) -> const gfloat* {
+      if (GM == 2) return Aglob + (size_t)(ch * CC + r) * co_stride + (size_t)m0 * kk + c;
+      int rr = m0 + r;
+      if (rr >= M) rr = M - 1;                            // rows beyond M repeat the last one; never stored
+      return Aglob + (size_t)rr * Q + ch * QC + c;
+    };
+    v4f ra[AU];
+    auto a_issue = [&](int ch, int first_slot) {
+      const APar p = a_par(ch);
+      const int a_dr = UNI(fdiv(BLK, p.ispr)), a_dc = BLK - a_dr * p.spr;
+      int r = fdiv(first_slot, p.ispr), c = first_slot - r * p.spr;
+#pragma unroll
+      for (int u = 0; u < AU; ++u) {
+        ra[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+        if (first_slot + u * BLK < p.slots && r < p.nvalid && c * av < p.seg_len) {
+          if (avec) ra[u] = *(const gv4*)a_src(ch, r, 4 * c);
+          else ra[u][0] = *a_src(ch, r, c);
+        }
+        c += a_dc; r += a_dr;
+        if (c >= p.spr) { c -= p.spr; ++r; }
+      }
+    };
+    auto a_commit = [&](int ch, int first_slot) {
+      const APar p = a_par(ch);
+      const int a_dr = UNI(fdiv(BLK, p.ispr)), a_dc = BLK - a_dr * p.spr;
+      int r = fdiv(first_slot, p.ispr), c = first_slot - r * p.spr;
+#pragma unroll
+      for (int u = 0; u < AU; ++u) {
+        if (first_slot + u * BLK < p.slots) {
+          if (avec) *(lv4*)(Alds + r * lstride + 4 * c) = ra[u];
+          else Alds[r * lstride + c] = ra[u][0];
+        }
+        c += a_dc; r += a_dr;
+        if (c >= p.spr) { c -= p.spr; ++r; }
+      }
+    };
+    // ---- patch origin of a chunk: first channel and first source row
+    auto p_origin = [&](int ch, int clo, int trow, int& chan0, int& row0) {
+      if (GM == 1) { chan0 = ch * CC; row0 = trow * gs - gpad; }
+      else if (GM == 2) { chan0 = ch * CC; row0 = trow; }
+      else { chan0 = clo; row0 = ch * rows_c * gs - gpad; }
+    };
+    // ---- patch staged with 16-byte copies (vec == 1): rows of the source map go to
+    // LDS as they are; the interior of a patch row starts at column 4, columns 0..3
+    // and Wsrc+4..Wsrc+7 are halo.  Requests and stores separate, as for the A block.
+    constexpr int VU = 8;
+    const int Wsrc = (GM == 2) ? gOW : gW, Hsrc = (GM == 2) ? gOH : gH, Cred = (GM == 2) ? gK : gC;
+    const int W4 = Wsrc >> 2, pv_nrow = CC * PR, pv_nslot = pv_nrow * W4;
+    v4f pv[VU];
+    int pdst[VU];
+    auto p_issue = [&](int ch, int base, int clo, int trow) {
+      int chan0, row0;
+      p_origin(ch, clo, trow, chan0, row0);
+      const int rshift = (GM == 2) ? border : 0;
+      const float iW4 = frcp(W4), iPR = frcp(PR);
+      int r = fdiv(base, iW4), xs = base - r * W4;
+      int c = fdiv(r, iPR), y = r - c * PR;
+      const int dr = UNI(fdiv(BLK, iW4)), dxs = BLK - dr * W4, dc = UNI(fdiv(dr, iPR)), dy = dr - dc * PR;
+#pragma unroll
+      for (int u = 0; u < VU; ++u) {
+        pv[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+        pdst[u] = -1;
+        if (base + u * BLK < pv_nslot) {
+          const int chn = chan0 + c, srow = row0 + y - rshift;
+          pdst[u] = c * PRW + y * Wp + 4 + 4 * xs;
+          if (chn < Cred && srow >= 0 && srow < Hsrc)
+            pv[u] = *(const gv4*)(src + ((size_t)chn * Hsrc + srow) * Wsrc + 4 * xs);
+        }
+        xs += dxs; y += dy; c += dc;
+        if (xs >= W4) { xs -= W4; ++y; }
+        if (y >= PR) { y -= PR; ++c; }
+        if (y >= PR) { y -= PR; ++c; }
+      }
+    };
+    auto p_commit = [&]() {
+#pragma unroll
+      for (int u = 0; u < VU; ++u)
+        if (pdst[u] >= 0) *(lv4*)(patch + pdst[u]) = pv[u];
+    };
+
+    // ---- requests of the first chunk: offset table, A block, patch
+    int tv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) tv[u] = (tid + u * BLK < QCpad) ? tq[tid + u * BLK] : 0;
+    a_issue(0, tid);
+    if (!op) PB_TS(10);
+    tile_geometry(n0);
+    if (vec == 1) p_issue(0, tid, c_lo, tile_row0);
+
+    for (int sub = 0; sub < nsub; ++sub) {
+    const int n0s = n0 + sub * NT;
+    if (sub && n0s >= N) break;
+    const bool more = sub + 1 < nsub && n0s + NT < N;   // another column tile follows
+    tile_geometry(n0s);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) offn[j] = (tnv[j] >= 0) ? tnv[j] - adj : 0;
+    __syncthreads();   // LDS may still be in use by the previous operand set / column tile
+    if (!op && !sub) PB_TS(9);
 
     for (int ch = 0; ch < n_chunks; ++ch) {
       const int q0 = ch * QC;
@@ -113,101 +331,12 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
       const int qc4 = (qc_eff + 3) & ~3;
       if (ch) __syncthreads();                              // the previous chunk has been contracted
       if (ch == 1 && !op) PB_TS(12);
-      // ---- requests: offset table (first chunk), A block, then the patch
-      int tv[4];
-      if (ch == 0) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) tv[u] = (tid + u * BLK < QCpad) ? tq[tid + u * BLK] : 0;
-      }
-      // A block as a 2-D copy: nseg segments of seg_pad floats, of which the first
-      // seg_len of the first nvalid segments come from memory and the rest is zero
-      int nseg, nvalid, seg_len, seg_pad, lstride;
-      if (GM == 2) {
-        const float ikk = frcp(kk);
-        nseg = UNI(fdiv(qc4 + kk - 1, ikk)); nvalid = UNI(fdiv(qc_eff, ikk)); seg_len = mte * kk; seg_pad = MT * kk; lstride = MT * kk;
-      } else {
-        nseg = MT; nvalid = MT; seg_len = qc_eff; seg_pad = qc4; lstride = LDA;
-      }
-      auto a_src = [&](int r, int c) -> const gfloat* {
-        if (GM == 2) return Aglob + (size_t)(ch * CC + r) * co_stride + (size_t)m0 * kk + c;
-        int rr = m0 + r;
-        if (rr >= M) rr = M - 1;                            // rows beyond M repeat the last one; never stored
-        return Aglob + (size_t)rr * Q + q0 + c;
-      };
-      constexpr int AU = 10;
-      const int av = avec ? 4 : 1;                          // floats per request
-      const int spr = avec ? (seg_pad + 3) >> 2 : seg_pad;  // requests per segment
-      const float ispr = frcp(spr);
-      const int a_slots = nseg * spr;
-      const int a_dr = UNI(fdiv(BLK, ispr)), a_dc = BLK - a_dr * spr;
-      int a_r = fdiv(tid, ispr), a_c = tid - a_r * spr;     // iterator over this thread's requests
-      v4f ra[AU];
-      auto a_issue = [&](int first_slot) {
-        int r = a_r, c = a_c;
-#pragma unroll
-        for (int u = 0; u < AU; ++u) {
-          ra[u] = (v4f){0.f, 0.f, 0.f, 0.f};
-          if (first_slot + u * BLK < a_slots && r < nvalid && c * av < seg_len) {
-            if (avec) ra[u] = *(const gv4*)a_src(r, 4 * c);
-            else ra[u][0] = *a_src(r, c);
-          }
-          c += a_dc; r += a_dr;
-          if (c >= spr) { c -= spr; ++r; }
-        }
-      };
-      auto a_commit = [&](int first_slot) {
-#pragma unroll
-        for (int u = 0; u < AU; ++u) {
-          if (first_slot + u * BLK < a_slots) {
-            if (avec) *(lv4*)(Alds + a_r * lstride + 4 * a_c) = ra[u];
-            else Alds[a_r * lstride + a_c] = ra[u][0];
-          }
-          a_c += a_dc; a_r += a_dr;
-          if (a_c >= spr) { a_c -= spr; ++a_r; }
-        }
-      };
-      a_issue(tid);
-      if (!ch && !op) PB_TS(10);
-      if (ch == 1 && !op) PB_TS(13);
-      // ---- patch
       int chan0, row0;
-      if (GM == 1) { chan0 = ch * CC; row0 = tile_row0 * gs - gpad; }
-      else if (GM == 2) { chan0 = ch * CC; row0 = tile_row0; }
-      else { chan0 = c_lo; row0 = ch * rows_c * gs - gpad; }
+      p_origin(ch, c_lo, tile_row0, chan0, row0);
       if (vec == 1) {
-        // rows of the source map go to LDS with 16-byte copies; the interior of a
-        // patch row starts at column 4, columns 0..3 and Wsrc+4..Wsrc+7 are halo
-        const int Wsrc = (GM == 2) ? gOW : gW, Hsrc = (GM == 2) ? gOH : gH, Cred = (GM == 2) ? gK : gC;
-        const int W4 = Wsrc >> 2, nrow = CC * PR, nslot = nrow * W4;
-        const int rshift = (GM == 2) ? border : 0;
-        constexpr int VU = 8;
-        const float iW4 = frcp(W4), iPR = frcp(PR);
-        int r = fdiv(tid, iW4), xs = tid - r * W4;
-        int c = fdiv(r, iPR), y = r - c * PR;
-        const int dr = UNI(fdiv(BLK, iW4)), dxs = BLK - dr * W4, dc = UNI(fdiv(dr, iPR)), dy = dr - dc * PR;
-        for (int base = tid; base < nslot; base += BLK * VU) {
-          v4f v[VU];
-          int dst[VU];
-#pragma unroll
-          for (int u = 0; u < VU; ++u) {
-            v[u] = (v4f){0.f, 0.f, 0.f, 0.f};
-            dst[u] = -1;
-            if (base + u * BLK < nslot) {
-              const int chn = chan0 + c, srow = row0 + y - rshift;
-              dst[u] = c * PRW + y * Wp + 4 + 4 * xs;
-              if (chn < Cred && srow >= 0 && srow < Hsrc)
-                v[u] = *(const gv4*)(src + ((size_t)chn * Hsrc + srow) * Wsrc + 4 * xs);
-            }
-            xs += dxs; y += dy; c += dc;
-            if (xs >= W4) { xs -= W4; ++y; }
-            if (y >= PR) { y -= PR; ++c; }
-            if (y >= PR) { y -= PR; ++c; }
-          }
-#pragma unroll
-          for (int u = 0; u < VU; ++u)
-            if (dst[u] >= 0) *(lv4*)(patch + dst[u]) = v[u];
-        }
-        for (int h = tid; h < 2 * nrow; h += BLK) {
+        p_commit();
+        for (int base = tid + BLK * VU; base < pv_nslot; base += BLK * VU) { p_issue(ch, base, c_lo, tile_row0); p_commit(); }
+        for (int h = tid; h < 2 * pv_nrow; h += BLK) {
           const int rr = h >> 1;
           *(lv4*)(patch + rr * Wp + ((h & 1) ? Wsrc + 4 : 0)) = (v4f){0.f, 0.f, 0.f, 0.f};
         }
@@ -299,19 +428,36 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
       if (!ch && !op) PB_TS(3);
       if (ch == 1 && !op) PB_TS(14);
       // ---- park the offset table and the A block
-      if (ch == 0) {
+      if (ch == 0 && sub == 0) {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
           if (tid + u * BLK < QCpad) offq[tid + u * BLK] = tv[u];
         for (int i = tid + 4 * BLK; i < QCpad; i += BLK) offq[i] = tq[i];
       }
-      a_commit(tid);
-      for (int s0 = tid + AU * BLK; s0 < a_slots; s0 += AU * BLK) { a_issue(s0); a_commit(s0); }
+      if (sub == 0 || n_chunks > 1) {   // a single chunk's A block serves every column tile
+        a_commit(ch, tid);
+        const int a_slots = a_par(ch).slots;
+        for (int s0 = tid + AU * BLK; s0 < a_slots; s0 += AU * BLK) { a_issue(ch, s0); a_commit(ch, s0); }
+      }
       if (!ch && !op) PB_TS(4);
       if (ch == 1 && !op) PB_TS(15);
       __syncthreads();
       if (!ch && !op) PB_TS(5);
       if (ch == 1 && !op) PB_TS(16);
+      // ---- requests of the next chunk (or of the first chunk of the next column
+      // tile): in flight while this one is contracted
+      if (ch + 1 < n_chunks) {
+        a_issue(ch + 1, tid);
+        if (vec == 1) p_issue(ch + 1, tid, c_lo, tile_row0);
+      } else if (more) {
+        if (n_chunks > 1) a_issue(0, tid);
+        if (vec == 1) {
+          const int nn = n0s + NT;
+          p_issue(0, tid, GM == 3 ? UNI(fdiv(nn, frcp(kk))) : 0,
+                  GM == 1 ? UNI(fdiv(nn, frcp(gOW))) : (GM == 2 ? UNI(fdiv(nn, frcp(gW))) : 0));
+        }
+        tn_load(n0s + NT);
+      }
       // ---- MFMA loop: lane holds A[i = lane%16][k = lane/16] and B[k = lane/16][j = lane%16];
       // the waves of a reduction split take k-steps wk_id, wk_id + wk, ...
       {
@@ -332,34 +478,80 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
         }
         const int a_adv = (GM == 2) ? dq_co * lstride + dq_tap : dq;
         const int a_wrap = (GM == 2) ? lstride - kk : 0;    // extra advance when the tap index wraps into the next channel
-        auto fetch = [&](float& a, int& oq) {
-          a = *ap; oq = *oqp;
-          ap += a_adv; oqp += dq;
-          if (GM == 2) { a_tap += dq_tap; if (a_tap >= kk) { a_tap -= kk; ap += a_wrap; } }
+        // Software pipeline over groups of G k-steps: while the MFMAs of group g
+        // run, the A and B values of group g+1 and the offsets of group g+2 (the
+        // addresses of the B reads) are on their way from LDS.  Two cursors: the A
+        // values, and the offset table one group ahead of them.  A load that would
+        // run past the last group (live = false) re-reads the first entries instead
+        // and leaves its cursor alone: the loop body has no branch around a load, so
+        // that the wait before an MFMA counts the loads behind it exactly.  The
+        // scheduling barriers keep the compiler from sinking reads to their first use.
+        constexpr int G = NI == 4 ? 4 : 8;
+        const int ng = nk / G;
+        const lfloat* const ap0 = ap;
+        const lint* const oqp0 = oqp;
+        const int a_tap0 = a_tap;
+        float av[2][G], bv[2][G][NI];
+        int oqv[G];
+        auto load_oq = [&](bool live) {
+          const lint* p = live ? oqp : oqp0;
+          const int st = live ? dq : 0;
+#pragma unroll
+          for (int u = 0; u < G; ++u) { oqv[u] = *p; p += st; }
+          oqp += G * st;
         };
-        int s = 0;
-        for (; s + 8 <= nk; s += 8) {
-          float a[8];
-          int oq[8];
+        auto load_ab = [&](auto NB, bool live) {
+          constexpr int nb = decltype(NB)::value;
+          const lfloat* p = live ? ap : ap0;
+          int tap = live ? a_tap : a_tap0;
+          const int adv = live ? a_adv : 0, dtap = live ? dq_tap : 0;
 #pragma unroll
-          for (int u = 0; u < 8; ++u) fetch(a[u], oq[u]);
-          float b[8][NI];
+          for (int u = 0; u < G; ++u) {
+            av[nb][u] = *p;
+            p += adv;
+            if (GM == 2) { tap += dtap; if (tap >= kk) { tap -= kk; p += a_wrap; } }
 #pragma unroll
-          for (int u = 0; u < 8; ++u)
+            for (int j = 0; j < NI; ++j) bv[nb][u][j] = patch[oqv[u] + offn[j]];
+          }
+          ap = live ? p : ap;
+          a_tap = live ? tap : a_tap;
+        };
+        auto mfmas = [&](auto CB) {
+          constexpr int cb = decltype(CB)::value;
 #pragma unroll
-            for (int j = 0; j < NI; ++j) b[u][j] = patch[oq[u] + offn[j]];
-#pragma unroll
-          for (int u = 0; u < 8; ++u)
+          for (int u = 0; u < G; ++u)
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
-              if (DUAL && (u & 1)) acc2[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u], b[u][j], acc2[j], 0, 0, 0);
-              else acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u], b[u][j], acc[j], 0, 0, 0);
+              if (DUAL && (u & 1)) acc2[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[cb][u], bv[cb][u][j], acc2[j], 0, 0, 0);
+              else acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[cb][u], bv[cb][u][j], acc[j], 0, 0, 0);
             }
+        };
+        using I0 = IConst<0>;
+        using I1 = IConst<1>;
+        int g = 0;
+        if (ng > 0) {
+          load_oq(true);
+          load_ab(I0(), true);
+          load_oq(ng > 1);
+          for (; g + 2 <= ng; g += 2) {
+            load_ab(I1(), true);
+            load_oq(g + 2 < ng);
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(I0());
+            __builtin_amdgcn_sched_barrier(0);
+            load_ab(I0(), g + 2 < ng);
+            load_oq(g + 3 < ng);
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(I1());
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if (g < ng) mfmas(I0());   // odd number of groups: the last one is in buffer 0
         }
-        for (; s < nk; ++s) {
-          float a;
-          int oq;
-          fetch(a, oq);
+        for (int s = ng * G; s < nk; ++s) {
+          const float a = *ap;
+          const int oq = *oqp;
+          ap += a_adv; oqp += dq;
+          if (GM == 2) { a_tap += dq_tap; if (a_tap >= kk) { a_tap -= kk; ap += a_wrap; } }
 #pragma unroll
           for (int j = 0; j < NI; ++j)
             acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, patch[oq + offn[j]], acc[j], 0, 0, 0);
@@ -368,79 +560,14 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
       if (!ch && !op) PB_TS(6);
       if (ch == 1 && !op) PB_TS(17);
     }
-  }
-
-  if (DUAL) {
+    if (nops == 1) {
+      finish(n0s);
 #pragma unroll
-    for (int j = 0; j < NI; ++j) acc[j] += acc2[j];
-  }
-  PB_TS(7);
-  // ---- reduce the split of the reduction across waves (fixed order)
-  if (wk > 1) {
-    __syncthreads();
-    lfloat* red = smem;   // [wave][j][lane] float4
-    if (wk_id > 0) {
-#pragma unroll
-      for (int j = 0; j < NI; ++j) *(lv4*)(red + ((wv * 4 + j) * 64 + lane) * 4) = acc[j];
+      for (int j = 0; j < NI; ++j) { acc[j] = (v4f){0.f, 0.f, 0.f, 0.f}; acc2[j] = (v4f){0.f, 0.f, 0.f, 0.f}; }
     }
-    __syncthreads();
-    if (wk_id == 0) {
-      for (int w2 = 1; w2 < wk; ++w2)
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-          const v4f r = *(const lv4*)(red + (((wv + w2) * 4 + j) * 64 + lane) * 4);
-          acc[j][0] += r[0]; acc[j][1] += r[1]; acc[j][2] += r[2]; acc[j][3] += r[3];
-        }
-    }
+    }   // column tiles
   }
-  PB_TS(8);
-  if (wk_id != 0) return;
-  // ---- epilogue: lane holds C[i = 4*(lane/16) + r][j = lane%16]
-  const int M = UNI(d.g.M), N = UNI(d.g.N);
-  gfloat* out = (GM == 1) ? at(d.y, t) : (GM == 2) ? at(d.dx, t) : GP(d.gw);
-  const int mrow = m0 + wm_id * 16 + 4 * kq;
-  const bool extras = (GM == 1 && (flags & (F_BIAS | F_SKIP))) || (GM == 2 && (flags & (F_MASK_X | F_ADD_SKG))) ||
-                      (GM != 3 && (flags & F_BF16_OUT));
-  if (!extras) {
-#pragma unroll
-    for (int j = 0; j < NI; ++j) {
-      const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
-      if (n < N) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (mrow + r < M) out[(size_t)(mrow + r) * N + n] = acc[j][r];
-      }
-    }
-    return;
-  }
-  const gfloat* skip = (GM == 1 && (flags & F_SKIP) && !(flags & F_PROJ)) ? (const gfloat*)at(d.skip, t) : nullptr;
-  const gfloat* xm = (GM == 2 && (flags & F_MASK_X)) ? (const gfloat*)at(d.x, t) : nullptr;
-  const gfloat* skg = (GM == 2 && (flags & F_ADD_SKG)) ? (const gfloat*)at(d.skg, t) : nullptr;
-  const gfloat* bias = (GM == 1 && (flags & F_BIAS)) ? GP(d.b) : nullptr;
-#pragma unroll
-  for (int j = 0; j < NI; ++j) {
-    const int n = n0 + (wn_id * ni + j) * 16 + (lane & 15);
-    if (n >= N) continue;
-    float add[4], msk[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      add[r] = 0.f; msk[r] = 1.f;
-      if (mrow + r < M) {
-        const size_t o = (size_t)(mrow + r) * N + n;
-        if (bias) add[r] = bias[mrow + r];
-        if (skip) add[r] += skip[o];
-        if (skg) add[r] = skg[o];
-        if (xm) msk[r] = xm[o];
-      }
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-      if (mrow + r < M) {
-        float v = acc[j][r];
-        if (GM == 2 && !(msk[r] > 0.f)) v = 0.f;
-        out[(size_t)(mrow + r) * N + n] = rbf_if(GM != 3 && (flags & F_BF16_OUT), v + add[r]);
-      }
-  }
+  if (nops != 1) finish(n0);   // both operand sets have been accumulated (one column tile per workgroup)
 }
 
 __device__ __forceinline__ void step_gemm(const LDesc& d, int tile, int t, lfloat* smem) {

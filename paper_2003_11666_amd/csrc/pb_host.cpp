@@ -370,39 +370,20 @@ void sc_coeffs(double m, double D, double* a, double* b) {
 // ---------------------------------------------------------- GEMM tiling
 int pow2_floor(int x) { int p = 1; while (p * 2 <= x) p *= 2; return p; }
 
-// Choose the tiling of one implicit-GEMM operand set.  mode 1 forward, 2
-// backward data, 3 backward weights.  `like` != nullptr forces the wave
-// arrangement of an existing configuration (projection accumulated into the
-// same tile).  Returns false if no chunking fits the LDS budget.
-int g_tile_target = 8;   // workgroups a step is split into at least, when its shape allows
+// Tiling of one implicit-GEMM operand set.  mode 1 forward, 2 backward data,
+// 3 backward weights.
+int g_tile_target = 8;     // latency policy: workgroups a step is split into at least, when its shape allows
+double g_tile_budget_us = 0;   // throughput policy (> 0): longest tile a step should have, microseconds (estimate)
 
-bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int s, int pad,
-               const GemmCfg* like, GemmCfg* out, bool allow_vec = false) {
-  const int target = g_tile_target;
-  GemmCfg g;
-  memset(&g, 0, sizeof g);
-  g.gm = mode;
-  const int kk = k * k, P = OH * OW, HWi = H * W;
-  if (mode == 1) { g.M = K; g.N = P; g.Q = C * kk; }
-  else if (mode == 2) { g.M = C; g.N = HWi; g.Q = K * kk; }
-  else { g.M = K; g.N = C * kk; g.Q = P; }
-  if (like) {
-    g.wm = like->wm; g.wn = like->wn; g.wk = like->wk; g.ni = like->ni;
-  } else {
-    const int mt = cdiv(g.M, 16), n16 = cdiv(g.N, 16);
-    g.wm = mt >= 4 ? 4 : mt >= 2 ? 2 : 1;
-    const int rest = 4 / g.wm;
-    if (mode == 3 && g.Q >= 256) { g.wk = rest; g.wn = 1; }
-    else { g.wn = std::min(rest, pow2_floor(n16)); g.wk = rest / g.wn; }
-    g.ni = std::min(4, cdiv(n16, g.wn));
-    auto tiles = [&]() { return cdiv(g.M, 16 * g.wm) * cdiv(g.N, 16 * g.ni * g.wn); };
-    if (g.ni == 3) g.ni = 4;   // the kernels are instantiated for 1, 2 and 4 subtiles
-    while (tiles() < target && g.ni > 1) g.ni /= 2;
-    while (tiles() < target && g.wm > 1 && g.Q >= 64 * g.wk * 2) { g.wm /= 2; g.wk *= 2; }
-    while (tiles() < target && g.wn > 1 && g.Q >= 64 * g.wk * 2) { g.wn /= 2; g.wk *= 2; }
-  }
+// Given the wave arrangement (wm, wn, wk, ni), choose the chunking of the
+// reduction that fits the LDS budget.  `fine`: search the channel count of a
+// chunk in steps of 4 (else by halving).  Returns false if nothing fits.
+bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int s, int pad, bool allow_vec, bool fine) {
+  const int mode = g.gm, kk = k * k;
   g.MT = 16 * g.wm; g.NT = 16 * g.ni * g.wn;
-  g.tiles_n = cdiv(g.N, g.NT);
+  if (g.nsub < 1 || g.wk != 1) g.nsub = 1;   // the split of the reduction reuses the A block's LDS
+  g.nsub = std::min(g.nsub, cdiv(g.N, g.NT));
+  g.tiles_n = cdiv(cdiv(g.N, g.NT), g.nsub);
   g.tiles = cdiv(g.M, g.MT) * g.tiles_n;
   // 16-byte row copies: source rows a multiple of 4 floats wide, no transform
   // while staging, and (backward data) unit stride so that no zeros interleave
@@ -433,9 +414,20 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
     if (g.vec == 1) g.Wp = (mode == 1 ? W : OW) + 8;
     const int nch = mode == 1 ? C : K;
     int CC = nch;
-    while (CC > 1 && !fits(CC * kk, CC, g.PR, g.Wp)) CC = (CC + 1) / 2;
-    if (CC > 4) CC = CC / 4 * 4;   // keeps the chunks of a row 16-byte aligned
-    if (!fits(CC * kk, CC, g.PR, g.Wp)) return false;
+    if (fine) {
+      while (CC > 1 && !fits(CC * kk, CC, g.PR, g.Wp)) CC = CC > 4 ? (CC - 1) / 4 * 4 : CC - 1;
+      if (CC >= 1 && fits(CC * kk, CC, g.PR, g.Wp) && CC < nch) {
+        // even out the chunks
+        const int n = cdiv(nch, CC);
+        int even = cdiv(nch, n);
+        if (even > 4) even = (even + 3) / 4 * 4;
+        if (even <= CC) CC = even;
+      }
+    } else {
+      while (CC > 1 && !fits(CC * kk, CC, g.PR, g.Wp)) CC = (CC + 1) / 2;
+      if (CC > 4) CC = CC / 4 * 4;   // keeps the chunks of a row 16-byte aligned
+    }
+    if (CC < 1 || !fits(CC * kk, CC, g.PR, g.Wp)) return false;
     g.CC = CC; g.QC = CC * kk; g.n_chunks = cdiv(nch, CC); g.rows_c = 0;
   } else {
     g.CC = std::min(C, (g.NT + kk - 2) / kk + 1);
@@ -469,6 +461,96 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
   g.o_A = g.QCpad;
   g.o_patch = (int)(g.o_A + a_size(g.QC));
   if (g.o_patch % 4 || g.o_patch + (g.CC * g.PR * g.Wp + 3) / 4 * 4 > LDS_FLOATS) return false;
+  return true;
+}
+
+// Estimated duration of one tile, microseconds: a fixed part (descriptor, offset
+// tables, epilogue), per chunk a fixed part, the staging of the A block and the
+// patch (instruction-bound: counted in 16-byte requests per thread, of which the
+// first 10 + 8 are prefetched while the previous chunk is contracted) and the
+// MFMA loop, whose cost per MFMA falls with the number of column subtiles a
+// wave keeps (one A fetch and one offset fetch per k-step whatever their number).
+double est_tile_us(const GemmCfg& g, int k) {
+  const int kk = k * k;
+  const double a_fl = g.gm == 2 ? (double)((g.QCpad + kk - 1) / kk + 1) * g.MT * kk : (double)g.MT * g.QCpad;
+  const double p_fl = (double)g.CC * g.PR * g.Wp;
+  const double a_sl = a_fl / (g.avec ? 4 : 1) / BLK, p_sl = p_fl / (g.vec == 1 ? 4 : 1) / BLK;
+  const double stage_a = 0.1 * std::min(a_sl, 10.0) + 0.3 * std::max(0.0, a_sl - 10.0);
+  const double stage_p = g.vec == 1 ? 0.1 * std::min(p_sl, 8.0) + 0.3 * std::max(0.0, p_sl - 8.0) : 0.3 * p_sl;
+  const double mf = (double)cdiv(cdiv(std::min(g.QC, g.Q), 4), g.wk) * g.ni;
+  const double t_mfma = mf * (32.0 + 70.0 / g.ni) / 2400.0;
+  const double t_chunk = 1.0 + stage_a + stage_p + t_mfma;
+  double t = 4.0 + g.n_chunks * t_chunk + (g.wk > 1 ? 0.5 : 0.0);
+  // further column tiles of a backward-weights workgroup: no descriptor, no tables,
+  // the patch already requested; the A block again only if the reduction is chunked
+  if (g.nsub > 1) t += (g.nsub - 1) * (g.n_chunks * (0.5 + (g.n_chunks > 1 ? stage_a : 0.0) + stage_p + t_mfma) + 1.0);
+  return t;
+}
+
+// Choose the wave arrangement and the chunking of one operand set.  `like` !=
+// nullptr forces the wave arrangement of an existing configuration (projection
+// accumulated into the same tile).  Returns false if no chunking fits the LDS
+// budget.
+//   Latency policy (small networks): at least g_tile_target tiles per step, rows
+//   first.  Throughput policy (g_tile_budget_us > 0): of all arrangements whose
+//   estimated tile duration stays within the budget, the one with the least total
+//   work (tiles x duration); if none does, the one with the shortest tile.
+bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int s, int pad,
+               const GemmCfg* like, GemmCfg* out, bool allow_vec = false, int max_sub = 16) {
+  const int target = g_tile_target;
+  GemmCfg g;
+  memset(&g, 0, sizeof g);
+  g.gm = mode;
+  const int kk = k * k, P = OH * OW, HWi = H * W;
+  if (mode == 1) { g.M = K; g.N = P; g.Q = C * kk; }
+  else if (mode == 2) { g.M = C; g.N = HWi; g.Q = K * kk; }
+  else { g.M = K; g.N = C * kk; g.Q = P; }
+  const int mt = cdiv(g.M, 16), n16 = cdiv(g.N, 16);
+  if (like) {
+    g.wm = like->wm; g.wn = like->wn; g.wk = like->wk; g.ni = like->ni;
+  } else if (g_tile_budget_us > 0) {
+    bool have = false;
+    double best_work = 0, best_tile = 0;
+    bool best_within = false;
+    GemmCfg bestg;
+    for (int wm = 1; wm <= 4; wm *= 2)
+      for (int wn = 1; wm * wn <= 4; wn *= 2) {
+        const int wk = 4 / (wm * wn);
+        if (wm > 1 && 16 * (wm / 2) >= 16 * mt) continue;            // waves without rows
+        if (wk > 1 && g.Q < 64 * wk) continue;
+        for (int ni = 1; ni <= 4; ni *= 2)
+        for (int nsub = 1; nsub <= (wk == 1 ? max_sub : 1); nsub *= 2) {
+          if (wn * ni > 1 && (wn * ni) / 2 >= n16) continue;         // subtiles without columns
+          if (nsub > 1 && 16 * ni * wn * (nsub / 2) >= g.N) continue; // column tiles beyond the last column
+          GemmCfg c = g;
+          c.wm = wm; c.wn = wn; c.wk = wk; c.ni = ni; c.nsub = nsub;
+          if (!fit_gemm(c, C, H, W, K, OH, OW, k, s, pad, allow_vec, true)) continue;
+          const double tt = est_tile_us(c, k), work = tt * c.tiles;
+          const bool within = tt <= g_tile_budget_us;
+          bool better;
+          if (!have) better = true;
+          else if (within != best_within) better = within;
+          else if (within) better = work < best_work || (work == best_work && tt < best_tile);
+          else better = tt < best_tile;
+          if (better) { have = true; bestg = c; best_work = work; best_tile = tt; best_within = within; }
+        }
+      }
+    if (!have) return false;
+    *out = bestg;
+    return true;
+  } else {
+    g.wm = mt >= 4 ? 4 : mt >= 2 ? 2 : 1;
+    const int rest = 4 / g.wm;
+    if (mode == 3 && g.Q >= 256) { g.wk = rest; g.wn = 1; }
+    else { g.wn = std::min(rest, pow2_floor(n16)); g.wk = rest / g.wn; }
+    g.ni = std::min(4, cdiv(n16, g.wn));
+    auto tiles = [&]() { return cdiv(g.M, 16 * g.wm) * cdiv(g.N, 16 * g.ni * g.wn); };
+    if (g.ni == 3) g.ni = 4;   // the kernels are instantiated for 1, 2 and 4 subtiles
+    while (tiles() < target && g.ni > 1) g.ni /= 2;
+    while (tiles() < target && g.wm > 1 && g.Q >= 64 * g.wk * 2) { g.wm /= 2; g.wk *= 2; }
+    while (tiles() < target && g.wn > 1 && g.Q >= 64 * g.wk * 2) { g.wn /= 2; g.wk *= 2; }
+  }
+  if (!fit_gemm(g, C, H, W, K, OH, OW, k, s, pad, allow_vec, like && g_tile_budget_us > 0)) return false;
   *out = g;
   return true;
 }
@@ -548,6 +630,20 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   // the whole phase rather than per step
   g_tile_target = std::max(4, std::min(32, 1024 / (3 * S)));
   if (const char* e = getenv("PB_TILE_TARGET")) g_tile_target = std::max(1, atoi(e));
+  // Networks whose tick is long compared with a launch are tiled for throughput:
+  // the budget for the longest tile is the duration of a GEMM phase if the tick's
+  // 6 flops per multiply-accumulate ran at a third of the fp32 MFMA peak, spread
+  // over the two GEMM phases of a tick.
+  {
+    double macs = 0;
+    for (const Stage& a : c->st) {
+      macs += (double)a.K * a.OH * a.OW * a.C * a.k * a.k;
+      if (a.proj) macs += (double)a.K * a.OH * a.OW * a.sC;
+    }
+    const double tick_us = 6.0 * macs / 50e6;
+    g_tile_budget_us = tick_us >= 10.0 ? std::max(12.0, tick_us / 2) : 0.0;
+    if (const char* e = getenv("PB_TILE_BUDGET_US")) g_tile_budget_us = atof(e);
+  }
   const Layout& L = c->L;
   std::vector<int> bwd0(S, 0);   // per stage: phase its backward chain starts in
   for (int s = 0; s < S; ++s) {
@@ -685,7 +781,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         GemmCfg g, gp;
         memset(&gp, 0, sizeof gp);
         const bool plain_src = !(d.flags & (F_PRE_AFFINE | F_PRE_RELU));
-        bool ok = make_gemm(1, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, plain_src);
+        bool ok = make_gemm(1, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, plain_src, (d.flags & F_PROJ) ? 1 : 16);
         if (ok && (d.flags & F_PROJ)) ok = make_gemm(1, d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, 0, &g, &gp, true);
         if (ok) {
           d.kind = K_GEMM; d.g = g; d.gp = gp; d.ntiles = g.tiles;
@@ -1103,7 +1199,8 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
         auto cfg_ok = [&](const GemmCfg& g, int C, int H, int W, int k, int s, int pad) {
           const int kk = k * k;
           bool o = g.wm * g.wn * g.wk == 4 && (g.ni == 1 || g.ni == 2 || g.ni == 4) && g.MT == 16 * g.wm && g.NT == 16 * g.ni * g.wn &&
-                   g.tiles_n == cdiv(g.N, g.NT) && g.tiles == cdiv(g.M, g.MT) * g.tiles_n && g.QCpad % 16 == 0 &&
+                   g.nsub >= 1 && (g.nsub == 1 || (g.wk == 1 && !(d.flags & F_PROJ && g.gm == 1))) && g.tiles_n == cdiv(cdiv(g.N, g.NT), g.nsub) &&
+                   g.tiles == cdiv(g.M, g.MT) * g.tiles_n && g.QCpad % 16 == 0 &&
                    g.QCpad >= g.QC && g.o_offq >= 0 && g.o_A >= g.o_offq + g.QCpad && g.o_A % 4 == 0 && g.o_patch % 4 == 0 &&
                    (int64_t)g.o_patch + ((int64_t)g.CC * g.PR * g.Wp + 3) / 4 * 4 <= LDS_FLOATS && LDS_FLOATS >= 4096 &&
                    (int64_t)g.n_chunks * g.QC >= g.Q;
@@ -1328,8 +1425,8 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
     o += line;
     if (d.kind == K_GEMM) {
       const GemmCfg& g = d.g;
-      snprintf(line, sizeof line, " | gm%d M%d N%d Q%d waves %dx%dx%d ni%d tile %dx%d chunks %d QC%d CC%d PR%d Wp%d lds %d",
-               g.gm, g.M, g.N, g.Q, g.wm, g.wn, g.wk, g.ni, g.MT, g.NT, g.n_chunks, g.QC, g.CC, g.PR, g.Wp,
+      snprintf(line, sizeof line, " | gm%d M%d N%d Q%d waves %dx%dx%d ni%d tile %dx%d x%d chunks %d QC%d CC%d PR%d Wp%d lds %d",
+               g.gm, g.M, g.N, g.Q, g.wm, g.wn, g.wk, g.ni, g.MT, g.NT, g.nsub, g.n_chunks, g.QC, g.CC, g.PR, g.Wp,
                g.o_patch + g.CC * g.PR * g.Wp);
       o += line;
     }

@@ -1257,7 +1257,7 @@ __device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
 // phase, a full copy of its step descriptor with the tile index filled in, so
 // that a single burst of scalar loads (one memory round trip) delivers all a
 // workgroup needs to know.
-__global__ void __launch_bounds__(BLK)
+__global__ void __launch_bounds__(BLK) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
         const float* __restrict__ sample_override, int label_override) {
   __shared__ float red_[8];
