@@ -105,7 +105,9 @@ struct StepDesc {
   int32_t loss_cap, n_stages;
   float fa, fb, flrT, flr, fm;   // K_UPDATE: SC coefficients a, b, lr*T, lr, momentum
   int32_t pmask;            // which pointer fields address the stage's ring of predicted weights (PF_* bits)
-  int32_t pdepth, plag, pstride, pad1_;   // that ring: slots, lag of the slot this step uses, floats per slot
+  int32_t pdepth, plag, pstride;   // that ring: slots, lag of the slot this step uses, floats per slot
+  int32_t grain;            // > 0: streaming form of an elementwise step, floats per workgroup (K_COPY, K_GNB_APPLY);
+                            // K_GNB_REDUCE: 1 = one wavefront per channel
   GemmCfg g;     // main operand set of a K_GEMM step
   GemmCfg gp;    // projection of the skip tensor accumulated into the same tile (forward only)
   TRef x;        // op input (forward) / saved input (backward)

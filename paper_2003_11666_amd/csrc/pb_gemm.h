@@ -207,7 +207,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
     // seg_len of the first nvalid segments come from memory and the rest is zero.
     // Requests (a_issue) and the stores into LDS (a_commit) are separate so that the
     // requests of chunk ch+1 can be in flight while chunk ch is contracted.
-    constexpr int AU = 10;
+    constexpr int AU = 6;
     const int av = avec ? 4 : 1;                          // floats per request
     struct APar { int nvalid, seg_len, spr, slots; float ispr; };
     auto a_par = [&](int ch) {
@@ -271,7 +271,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
     // ---- patch staged with 16-byte copies (vec == 1): rows of the source map go to
     // LDS as they are; the interior of a patch row starts at column 4, columns 0..3
     // and Wsrc+4..Wsrc+7 are halo.  Requests and stores separate, as for the A block.
-    constexpr int VU = 8;
+    constexpr int VU = 6;
     const int Wsrc = (GM == 2) ? gOW : gW, Hsrc = (GM == 2) ? gOH : gH, Cred = (GM == 2) ? gK : gC;
     const int W4 = Wsrc >> 2, pv_nrow = CC * PR, pv_nslot = pv_nrow * W4;
     v4f pv[VU];

@@ -356,6 +356,13 @@ StepDesc blank(int kind, int stage, int first_tick) {
 
 int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
+// Streaming forms of the elementwise steps (networks tiled for throughput):
+// floats per workgroup, and whether a ring can be read with 16-byte accesses.
+constexpr int STREAM_GRAIN = 4 * 4 * BLK;
+bool ref_vec4(const pb_ctx* c, const TRef& r) {
+  return r.base && (r.base - c->f(0)) % 4 == 0 && (r.depth == 1 || r.stride % 4 == 0);
+}
+
 int bwd_w_tiles(int K, int C, int k, int P, bool bias) {
   const int64_t nW = (int64_t)K * C * k * k;
   const int per = P > 16 ? BLK / 64 : BLK;
@@ -467,7 +474,7 @@ bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int
 // Estimated duration of one tile, microseconds: a fixed part (descriptor, offset
 // tables, epilogue), per chunk a fixed part, the staging of the A block and the
 // patch (instruction-bound: counted in 16-byte requests per thread, of which the
-// first 10 + 8 are prefetched while the previous chunk is contracted) and the
+// first 6 + 6 are prefetched while the previous chunk is contracted) and the
 // MFMA loop, whose cost per MFMA falls with the number of column subtiles a
 // wave keeps (one A fetch and one offset fetch per k-step whatever their number).
 double est_tile_us(const GemmCfg& g, int k) {
@@ -475,8 +482,8 @@ double est_tile_us(const GemmCfg& g, int k) {
   const double a_fl = g.gm == 2 ? (double)((g.QCpad + kk - 1) / kk + 1) * g.MT * kk : (double)g.MT * g.QCpad;
   const double p_fl = (double)g.CC * g.PR * g.Wp;
   const double a_sl = a_fl / (g.avec ? 4 : 1) / BLK, p_sl = p_fl / (g.vec == 1 ? 4 : 1) / BLK;
-  const double stage_a = 0.1 * std::min(a_sl, 10.0) + 0.3 * std::max(0.0, a_sl - 10.0);
-  const double stage_p = g.vec == 1 ? 0.1 * std::min(p_sl, 8.0) + 0.3 * std::max(0.0, p_sl - 8.0) : 0.3 * p_sl;
+  const double stage_a = 0.1 * std::min(a_sl, 6.0) + 0.3 * std::max(0.0, a_sl - 6.0);
+  const double stage_p = g.vec == 1 ? 0.1 * std::min(p_sl, 6.0) + 0.3 * std::max(0.0, p_sl - 6.0) : 0.3 * p_sl;
   const double mf = (double)cdiv(cdiv(std::min(g.QC, g.Q), 4), g.wk) * g.ni;
   const double t_mfma = mf * (32.0 + 70.0 / g.ni) / 2400.0;
   const double t_chunk = 1.0 + stage_a + stage_p + t_mfma;
@@ -616,6 +623,26 @@ bool gn_bwd_fits(int C, int HW, int G) {
   const int cpg = C / G;
   const int64_t n = (int64_t)cpg * HW;
   return n <= GNB_MAX_N && cpg <= BLK && n / 2 + 5 * cpg + 2 <= LDS_FLOATS;
+}
+
+// Streaming form of a K_GNB_APPLY step (see step_gnb_apply_stream): workgroups
+// aligned to groups, STREAM_GRAIN floats each.
+void stream_apply(const pb_ctx* c, StepDesc& e) {
+  const int HW = e.H * e.W;
+  if (g_tile_budget_us <= 0 || !(e.flags & F_DU_BUF) || HW % 4 || !ref_vec4(c, e.x) || !ref_vec4(c, e.dy) ||
+      !ref_vec4(c, e.dx) || ((e.flags & F_ADD_SKG) && !ref_vec4(c, e.skg)))
+    return;
+  const int64_t gsz = (int64_t)(e.C / e.G) * HW;
+  e.grain = STREAM_GRAIN;
+  e.n = cdiv(gsz, e.grain);
+  e.ntiles = e.G * e.n;
+}
+
+// One wavefront per channel for a K_GNB_REDUCE step over a small map.
+void wave_reduce(StepDesc& d) {
+  if (g_tile_budget_us <= 0 || !(d.flags & F_DU_BUF) || d.H * d.W > 1024) return;
+  d.grain = 1;
+  d.ntiles = cdiv(d.C, BLK / 64);
 }
 
 // Compile the network into the step table.  Every step carries the phase it
@@ -848,11 +875,13 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         dz_src = d.dx;
       } else {
         d.ntiles = a.K;
-        out.push_back({pb++, d});
         StepDesc e = d;
+        wave_reduce(d);
+        out.push_back({pb++, d});
         e.kind = K_GNB_APPLY;
         e.dx = ring(c, b.dz, 1, a.z_elems(), 0);
         e.ntiles = cdiv(a.z_elems(), BLK);
+        stream_apply(c, e);
         out.push_back({pb++, e});
         dz_src = e.dx;
       }
@@ -951,6 +980,10 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         d.n = ta.in_elems();
         d.dy = dy_src; d.dx = skg_w;
         d.ntiles = cdiv(d.n, BLK);
+        if (g_tile_budget_us > 0 && d.n % 4 == 0 && ref_vec4(c, d.dy) && ref_vec4(c, d.dx)) {
+          d.grain = STREAM_GRAIN;
+          d.ntiles = cdiv(d.n, d.grain);
+        }
         out.push_back({pb, d});
       }
     }
@@ -991,14 +1024,17 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         out.push_back({pb++, d});
       } else {
         d.ntiles = a.Cin;
+        const StepDesc d_plain = d;
+        wave_reduce(d);
         out.push_back({pb++, d});
         if (s > 0) {
-          StepDesc e = d;
+          StepDesc e = d_plain;
           e.kind = K_GNB_APPLY;
           if (c->bf16) e.flags |= F_BF16_OUT;
           e.dx = ring(c, L.sb[s - 1].gradbox, 2, a.in_elems(), ML);
           if (a.tap_dist) { e.flags |= F_ADD_SKG; e.skg = ring(c, b.skg, a.tap_dist + 1, a.in_elems(), TL(a.tap_dist)); }
           e.ntiles = cdiv(a.in_elems(), BLK);
+          stream_apply(c, e);
           out.push_back({pb++, e});
         }
       }
@@ -1143,8 +1179,18 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
         const int64_t dyn = (d.flags & F_DU_BUF) ? in : (d.flags & F_DU_GAP) ? d.C : (int64_t)d.C * d.PH * d.PW;
         ok = ok && d.G > 0 && d.C % d.G == 0 && ref_ok(d.x, in) && ref_ok(d.st, stn) && ref_ok(d.dy, dyn) &&
              ptr_ok(d.part, 3 * d.C) && ptr_ok(d.gamma, d.C);
-        if (d.kind == K_GNB_REDUCE) ok = ok && d.ntiles == d.C && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C);
-        else ok = ok && (int64_t)d.ntiles * BLK >= in && ref_ok(d.dx, in) && (!(d.flags & F_ADD_SKG) || ref_ok(d.skg, in));
+        if (d.kind == K_GNB_REDUCE) {
+          ok = ok && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C);
+          if (d.grain == 1) ok = ok && (d.flags & F_DU_BUF) && d.ntiles == cdiv(d.C, BLK / 64);
+          else ok = ok && d.grain == 0 && d.ntiles == d.C;
+        } else {
+          ok = ok && ref_ok(d.dx, in) && (!(d.flags & F_ADD_SKG) || ref_ok(d.skg, in));
+          if (d.grain > 0)
+            ok = ok && d.grain % (4 * BLK) == 0 && (d.flags & F_DU_BUF) && (d.H * d.W) % 4 == 0 && d.n > 0 &&
+                 (int64_t)d.n * d.grain >= (int64_t)(d.C / d.G) * d.H * d.W && d.ntiles == d.G * d.n && ref_vec4(c, d.x) &&
+                 ref_vec4(c, d.dy) && ref_vec4(c, d.dx) && (!(d.flags & F_ADD_SKG) || ref_vec4(c, d.skg));
+          else ok = ok && (int64_t)d.ntiles * BLK >= in;
+        }
         break;
       }
       case K_GN_BWD: {
@@ -1169,7 +1215,10 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
              (!(d.flags & F_BIAS) || ptr_ok(d.gb, d.K)) && (!(d.flags & F_PRE_AFFINE) || ref_ok(d.st, stn));
         break;
       case K_COPY:
-        ok = ok && (int64_t)d.ntiles * BLK >= d.n && ref_ok(d.dy, d.n) && ref_ok(d.dx, d.n);
+        ok = ok && ref_ok(d.dy, d.n) && ref_ok(d.dx, d.n);
+        if (d.grain > 0)
+          ok = ok && d.grain % (4 * BLK) == 0 && d.n % 4 == 0 && (int64_t)d.ntiles * d.grain >= d.n && ref_vec4(c, d.dy) && ref_vec4(c, d.dx);
+        else ok = ok && (int64_t)d.ntiles * BLK >= d.n;
         break;
       case K_INGEST:
         ok = ok && (int64_t)d.ntiles * BLK >= d.n && ref_ok(d.dx, d.n) && ptr_ok((const float*)d.labels, d.n_stages);

@@ -34,6 +34,7 @@ __shared__ long long ts_sh[4][24];
 __device__ long long pb_ts_out[16384 * 100];
 __device__ int pb_ts_n;
 __device__ int pb_ts_tick;
+__device__ int pb_ts_grid;   // 0: record every phase, else only the launch with this many workgroups
 #define PB_TS(i) do { if ((threadIdx.x & 63) == 0) ts_sh[threadIdx.x >> 6][i] = (long long)__builtin_amdgcn_s_memrealtime(); } while (0)
 #else
 #define PB_TS(i)
@@ -366,7 +367,59 @@ __device__ __forceinline__ float gn_du(const LDesc& d, const gfloat* dy, const g
 
 // Per channel: dgamma = sum dyv*xh, dbeta = sum dyv (dyv = gradient after the
 // ReLU mask); also gamma_b*dbeta and gamma_b*dgamma for the group sums.
+// One wavefront per channel (small maps: a workgroup per channel would leave
+// most of its lanes without an element).  Plain gradient buffers only.
+__device__ void step_gnb_reduce_wave(const LDesc& d, int tile, int t) {
+  const int lane = threadIdx.x & 63, c = tile * (BLK / 64) + UNI((int)(threadIdx.x >> 6));
+  const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W);
+  if (c >= C) return;
+  const int cpg = UNI(fdiv(C, frcp(G))), g = UNI(fdiv(c, frcp(cpg)));
+  const gfloat* st = at(d.st, t);
+  const gfloat* xc = at(d.x, t) + (size_t)c * HW;
+  const gfloat* dc = at(d.dy, t) + (size_t)c * HW;
+  const bool rl = UNI(d.flags) & F_GN_RELU;
+  constexpr int RU = 4;
+  float xv[RU], dv[RU];
+#pragma unroll
+  for (int u = 0; u < RU; ++u) {
+    const int i = lane + u * 64;
+    xv[u] = 0.f; dv[u] = 0.f;
+    if (i < HW) { xv[u] = xc[i]; dv[u] = dc[i]; }
+  }
+  const float mean = st[g], rstd = st[G + g], sc = st[2 * G + c], sh = st[2 * G + C + c];
+  const float gm = GP(d.gamma)[c];
+  float sg = 0.f, sb = 0.f;
+#pragma unroll
+  for (int u = 0; u < RU; ++u) {
+    if (lane + u * 64 < HW) {
+      const float yv = fmaf(sc, xv[u], sh);
+      float du = dv[u];
+      if (rl && !(yv > 0.f)) du = 0.f;
+      sg = fmaf(du, (xv[u] - mean) * rstd, sg);
+      sb += du;
+    }
+  }
+  for (int i = lane + RU * 64; i < HW; i += 64) {
+    const float x1 = xc[i];
+    const float yv = fmaf(sc, x1, sh);
+    float du = dc[i];
+    if (rl && !(yv > 0.f)) du = 0.f;
+    sg = fmaf(du, (x1 - mean) * rstd, sg);
+    sb += du;
+  }
+  sg = wave_sum(sg);
+  sb = wave_sum(sb);
+  if (lane == 0) {
+    GP(d.ggamma)[c] = sg;
+    GP(d.gbeta)[c] = sb;
+    GP(d.part)[c] = gm * sb;
+    GP(d.part)[C + c] = gm * sg;
+    GP(d.part)[2 * C + c] = gm;
+  }
+}
+
 __device__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red) {
+  if (UNI(d.grain) == 1) { step_gnb_reduce_wave(d, tile, t); return; }
   const int c = tile, HW = UNI(d.H) * UNI(d.W), cpg = UNI(fdiv(UNI(d.C), frcp(UNI(d.G)))), g = UNI(fdiv(c, frcp(cpg)));
   const gfloat* st = at(d.st, t);
   const float mean = st[g], rstd = st[d.G + g], sc = st[2 * d.G + c], sh = st[2 * d.G + d.C + c];
@@ -426,7 +479,69 @@ __device__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red) {
 }
 
 // dx = rstd * (dxh - mean(dxh) - xh * mean(dxh*xh)), dxh = dyv * gamma_b
+// Streaming form: a workgroup takes d.grain consecutive floats of ONE group
+// (d.n workgroups per group), 16 bytes per access, every operand of a thread
+// requested before the first is used.  Plain gradient buffers, H*W a multiple of 4.
+__device__ void step_gnb_apply_stream(const LDesc& d, int tile, int t) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W), grain = UNI(d.grain), tpg = UNI(d.n);
+  const int cpg = UNI(fdiv(C, frcp(G))), gsz = cpg * HW;
+  const int g = UNI(fdiv(tile, frcp(tpg))), k = tile - g * tpg;
+  const int lo = k * grain, hi = (gsz < lo + grain) ? gsz : lo + grain;
+  const size_t gbase = (size_t)g * gsz;
+  const gfloat* st = at(d.st, t);
+  const gfloat* x = at(d.x, t) + gbase;
+  const gfloat* dy = at(d.dy, t) + gbase;
+  gfloat* dx = at(d.dx, t) + gbase;
+  const int flags = UNI(d.flags);
+  const gfloat* skg = (flags & F_ADD_SKG) ? (const gfloat*)at(d.skg, t) + gbase : nullptr;
+  const gfloat* part = GP(d.part);
+  const float ihw = frcp(HW);
+  // group sums of the per-channel partial sums (fixed order: lanes, then the wave
+  // tree), taken while every lane is active
+  float p1 = 0.f, p2 = 0.f;
+  for (int j = lane; j < cpg; j += 64) { p1 += part[g * cpg + j]; p2 += part[C + g * cpg + j]; }
+  const float mean = st[g], rstd = st[G + g];
+  const float inv_n = 1.0f / (float)gsz;
+  const float m1 = wave_sum(p1) * inv_n, m2 = wave_sum(p2) * inv_n;
+  constexpr int U = 4;
+  for (int base = lo + tid * 4; base < hi; base += U * 4 * BLK) {
+    v4f xv[U], dv[U], sk[U];
+    float sc[U], sh[U], gm[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = base + u * 4 * BLK;
+      xv[u] = (v4f){0.f, 0.f, 0.f, 0.f}; dv[u] = xv[u]; sk[u] = xv[u];
+      sc[u] = 0.f; sh[u] = 0.f; gm[u] = 0.f;
+      if (i < hi) {
+        const int c = g * cpg + fdiv(i, ihw);
+        xv[u] = *(const gv4*)(x + i);
+        dv[u] = *(const gv4*)(dy + i);
+        if (skg) sk[u] = *(const gv4*)(skg + i);
+        sc[u] = st[2 * G + c]; sh[u] = st[2 * G + C + c]; gm[u] = part[2 * C + c];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = base + u * 4 * BLK;
+      if (i < hi) {
+        v4f r;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float yv = fmaf(sc[u], xv[u][e], sh[u]);
+          float du = dv[u][e];
+          if ((flags & F_GN_RELU) && !(yv > 0.f)) du = 0.f;
+          const float xh = (xv[u][e] - mean) * rstd;
+          r[e] = rbf_if(flags & F_BF16_OUT, rstd * (du * gm[u] - m1 - xh * m2) + sk[u][e]);
+        }
+        *(gv4*)(dx + i) = r;
+      }
+    }
+  }
+}
+
 __device__ void step_gnb_apply(const LDesc& d, int tile, int t) {
+  if (UNI(d.grain) > 0) { step_gnb_apply_stream(d, tile, t); return; }
   const int HW = UNI(d.H) * UNI(d.W), cpg = UNI(fdiv(UNI(d.C), frcp(UNI(d.G)))), n = cpg * HW;
   const int o = tile * BLK + threadIdx.x;
   if (o >= d.C * HW) return;
@@ -673,8 +788,30 @@ __device__ void step_conv_bwd_w(const LDesc& d, int tile, int t) {
 }
 
 __device__ void step_copy(const LDesc& d, int tile, int t) {
+  const int grain = UNI(d.grain), n = UNI(d.n);
+  if (grain > 0) {   // streaming form: grain floats per workgroup, 16 bytes per access (n a multiple of 4)
+    const gfloat* src = at(d.dy, t);
+    gfloat* dst = at(d.dx, t);
+    const int lo = tile * grain, hi = (n < lo + grain) ? n : lo + grain;
+    constexpr int U = 4;
+    for (int base = lo + (int)threadIdx.x * 4; base < hi; base += U * 4 * BLK) {
+      v4f v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = base + u * 4 * BLK;
+        v[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+        if (i < hi) v[u] = *(const gv4*)(src + i);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = base + u * 4 * BLK;
+        if (i < hi) *(gv4*)(dst + i) = v[u];
+      }
+    }
+    return;
+  }
   const int o = tile * BLK + threadIdx.x;
-  if (o < d.n) at(d.dx, t)[o] = at(d.dy, t)[o];
+  if (o < n) at(d.dx, t)[o] = at(d.dy, t)[o];
 }
 
 
@@ -1327,7 +1464,7 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
 #ifdef PB_TIMING
   PB_TS(11);
   __syncthreads();
-  if (t == pb_ts_tick) {
+  if (t == pb_ts_tick && (pb_ts_grid == 0 || pb_ts_grid == (int)gridDim.x)) {
     __shared__ int slot_;
     if (threadIdx.x == 0) slot_ = atomicAdd(&pb_ts_n, 1);
     __syncthreads();
@@ -1435,6 +1572,7 @@ extern "C" int pb_debug_set_tick(int t) {
   hipMemcpyToSymbol(HIP_SYMBOL(pb::pb_ts_n), &z, sizeof(int));
   return (int)hipMemcpyToSymbol(HIP_SYMBOL(pb::pb_ts_tick), &t, sizeof(int));
 }
+extern "C" int pb_debug_set_grid(int g) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(pb::pb_ts_grid), &g, sizeof(int)); }
 extern "C" int pb_debug_dump(long long* host, int max_recs) {
   int n = 0;
   hipDeviceSynchronize();
