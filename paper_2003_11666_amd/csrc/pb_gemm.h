@@ -65,6 +65,12 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
   for (int j = 0; j < NI; ++j) { acc[j] = (v4f){0.f, 0.f, 0.f, 0.f}; acc2[j] = (v4f){0.f, 0.f, 0.f, 0.f}; }
   // sums of a tile: split of the reduction across waves, epilogue, store
   auto finish = [&](int n0s) {
+    // the addresses the epilogue needs are worked out here, not before the
+    // contraction: an opaque copy of the tick index keeps the compiler from
+    // hoisting them to the top of the function, where they would have to be
+    // kept (in scratch memory) across the MFMA loop
+    int te = t;
+    asm volatile("" : "+s"(te));
     if (DUAL) {
 #pragma unroll
       for (int j = 0; j < NI; ++j) acc[j] += acc2[j];
@@ -92,37 +98,42 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
     if (wk_id != 0) return;
     // ---- epilogue: lane holds C[i = 4*(lane/16) + r][j = lane%16]
     const int M = UNI(d.g.M), N = UNI(d.g.N);
-    gfloat* out = (GM == 1) ? at(d.y, t) : (GM == 2) ? at(d.dx, t) : GP(d.gw);
-    const int mrow = m0 + wm_id * 16 + 4 * kq;
+    gfloat* out = (GM == 1) ? at(d.y, te) : (GM == 2) ? at(d.dx, te) : GP(d.gw);
+    const int zero = te - t;                              // 0, opaque to the compiler (see above)
+    const int mrow = m0 + wm_id * 16 + 4 * kq + zero;
+    const int ncol = n0s + wn_id * ni * 16 + (lane & 15) + zero;
+    int ro[4];                                            // element offset of the lane's four rows, -1 beyond M
+#pragma unroll
+    for (int r = 0; r < 4; ++r) ro[r] = (mrow + r < M) ? (mrow + r) * N : -1;
     const bool extras = (GM == 1 && (flags & (F_BIAS | F_SKIP))) || (GM == 2 && (flags & (F_MASK_X | F_ADD_SKG))) ||
                         (GM != 3 && (flags & F_BF16_OUT));
     if (!extras) {
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
-        const int n = n0s + (wn_id * ni + j) * 16 + (lane & 15);
+        const int n = ncol + j * 16;
         if (n < N) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            if (mrow + r < M) out[(size_t)(mrow + r) * N + n] = acc[j][r];
+            if (ro[r] >= 0) out[ro[r] + n] = acc[j][r];
         }
       }
       return;
     }
-    const gfloat* skip = (GM == 1 && (flags & F_SKIP) && !(flags & F_PROJ)) ? (const gfloat*)at(d.skip, t) : nullptr;
-    const gfloat* xm = (GM == 2 && (flags & F_MASK_X)) ? (const gfloat*)at(d.x, t) : nullptr;
-    const gfloat* skg = (GM == 2 && (flags & F_ADD_SKG)) ? (const gfloat*)at(d.skg, t) : nullptr;
+    const gfloat* skip = (GM == 1 && (flags & F_SKIP) && !(flags & F_PROJ)) ? (const gfloat*)at(d.skip, te) : nullptr;
+    const gfloat* xm = (GM == 2 && (flags & F_MASK_X)) ? (const gfloat*)at(d.x, te) : nullptr;
+    const gfloat* skg = (GM == 2 && (flags & F_ADD_SKG)) ? (const gfloat*)at(d.skg, te) : nullptr;
     const gfloat* bias = (GM == 1 && (flags & F_BIAS)) ? GP(d.b) : nullptr;
     // every operand of the epilogue is requested before the first one is used
     PB_TS(18);
     float add[NI][4], msk[NI][4];
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const int n = n0s + (wn_id * ni + j) * 16 + (lane & 15);
+      const int n = ncol + j * 16;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         add[j][r] = 0.f; msk[j][r] = 1.f;
-        if (n < N && mrow + r < M) {
-          const size_t o = (size_t)(mrow + r) * N + n;
+        if (n < N && ro[r] >= 0) {
+          const int o = ro[r] + n;
           if (bias) add[j][r] = bias[mrow + r];
           if (skip) add[j][r] += skip[o];
           if (skg) add[j][r] = skg[o];
@@ -133,14 +144,14 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
     PB_TS(19);
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const int n = n0s + (wn_id * ni + j) * 16 + (lane & 15);
+      const int n = ncol + j * 16;
       if (n >= N) continue;
 #pragma unroll
       for (int r = 0; r < 4; ++r)
-        if (mrow + r < M) {
+        if (ro[r] >= 0) {
           float v = acc[j][r];
           if (GM == 2 && !(msk[j][r] > 0.f)) v = 0.f;
-          out[(size_t)(mrow + r) * N + n] = rbf_if(GM != 3 && (flags & F_BF16_OUT), v + add[j][r]);
+          out[ro[r] + n] = rbf_if(GM != 3 && (flags & F_BF16_OUT), v + add[j][r]);
         }
       if (j == 0) PB_TS(21);
       if (j == 1) PB_TS(22);

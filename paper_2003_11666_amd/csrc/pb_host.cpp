@@ -1101,6 +1101,23 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
 void order_steps(std::vector<std::pair<int, StepDesc>>& tagged) {
   auto step_cost = [](const StepDesc& d) -> int64_t {
     if (d.kind == K_HEAD) return (int64_t)1 << 40;
+    if (g_tile_budget_us > 0) {
+      // networks tiled for throughput: estimated duration of one workgroup, nanoseconds
+      double us = 3.0;
+      if (d.kind == K_GEMM) {
+        us = est_tile_us(d.g, d.g.gm == 1 && d.gp.gm ? d.k : d.k);
+        if (d.gp.gm) us += est_tile_us(d.gp, 1);
+      } else if (d.kind == K_GN_STATS || d.kind == K_GN_BWD) {
+        us = 4.0 + (double)d.C / std::max(1, d.G) * d.H * d.W / BLK * 0.05;
+      } else if (d.kind == K_GNB_REDUCE) {
+        us = 4.0 + (d.grain == 1 ? 1.0 : (double)d.H * d.W / BLK * ((d.flags & F_DU_POOL) ? 0.8 : 0.05));
+      } else if (d.kind == K_UPDATE) {
+        us = 15.0;
+      } else if (d.kind == K_POST_FWD || d.kind == K_GNB_APPLY) {
+        us = (d.flags & (F_POOL | F_DU_POOL)) ? 8.0 : 5.0;
+      }
+      return (int64_t)(us * 1000.0);
+    }
     if (d.kind == K_GEMM) {
       const GemmCfg& g = d.g;
       return ((int64_t)1 << 20) + (int64_t)g.Q * g.ni / g.wk + ((int64_t)g.MT * g.Q + (int64_t)g.n_chunks * g.CC * g.PR * g.Wp) / 64;
