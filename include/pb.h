@@ -181,6 +181,19 @@ int pb_update_standalone(float* w_dev, float* v_dev, const float* g_dev, float* 
  * including the terminator; writes at most cap bytes into buf (may be NULL). */
 int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap);
 
+/* Learning rate and momentum for update size n from the values in use at a
+ * reference update size n_ref (Appendix "Small Batch Size Training",
+ * Eq. hpscale): the momentum's decay per sample stays the same,
+ * m = m_ref^(n/n_ref), and the effective learning rate lr/(1-m) grows
+ * linearly with the update size, lr = lr_ref (1-m) n / ((1-m_ref) n_ref).
+ * The paper trains at n = 1 with hyper-parameters published for n_ref = 128
+ * or 32; the results are what pb_init takes as lr and momentum.  Host
+ * arithmetic in double, results rounded once to float.  lr_out, momentum_out:
+ * host pointers, written on success.  PB_E_INVALID if a pointer is NULL,
+ * n or n_ref < 1, momentum_ref outside [0,1] or lr_ref < 0. */
+int pb_scale_hyperparameters(float lr_ref, float momentum_ref, int32_t n_ref, int32_t n, float* lr_out,
+                             float* momentum_out);
+
 int pb_sync(pb_ctx* ctx);
 void pb_destroy(pb_ctx* ctx);
 const char* pb_last_error(void);

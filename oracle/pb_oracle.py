@@ -174,6 +174,19 @@ def sc_coefficients(m, D):
     return a, b
 
 
+def scale_hyperparameters(lr_ref, m_ref, n_ref, n):
+    """Learning rate and momentum for update size n from those of a reference
+    update size n_ref (Appendix "Small Batch Size Training", Eq. hpscale):
+    m = m_ref^(n/n_ref), lr = lr_ref (1-m) n / ((1-m_ref) n_ref).  Double
+    arithmetic.  m_ref = 1 gives m = 1 and the limit of the ratio, (n/n_ref)^2."""
+    m = float(m_ref) ** (float(n) / float(n_ref))
+    if m_ref == 1.0:
+        lr = float(lr_ref) * (float(n) / float(n_ref)) ** 2
+    else:
+        lr = (1.0 - m) * float(n) / ((1.0 - float(m_ref)) * float(n_ref)) * float(lr_ref)
+    return lr, m
+
+
 def gsc_update(w, v, g, lr, m, a, b):
     """v' = m v + g ; w' = w - lr (a v' + b g)  (Eqs. gscv, gscw)."""
     v_new = m * v + g

@@ -16,6 +16,7 @@ OP_KIND = {"linear": 0, "conv": 1, "gn": 2, "relu": 3, "maxpool": 4, "gap": 5, "
 EXPORTS = ["pb_arena_bytes", "pb_init", "pb_tick", "pb_run_resident", "pb_read_weights",
            "pb_read_velocity", "pb_loss_history", "pb_num_params", "pb_num_ticks",
            "pb_set_launch_mode", "pb_plan_summary", "pb_profile_begin", "pb_profile_end", "pb_update_standalone",
+           "pb_scale_hyperparameters",
            "pb_sync", "pb_destroy", "pb_last_error"]
 
 
@@ -86,6 +87,8 @@ def load_library():
                                          C.c_float, C.c_float, C.c_float, C.c_float, C.c_float, C.c_void_p]
     lib.pb_plan_summary.restype = C.c_int64
     lib.pb_plan_summary.argtypes = [C.POINTER(_NetDesc), C.c_char_p, C.c_int64]
+    lib.pb_scale_hyperparameters.restype = C.c_int
+    lib.pb_scale_hyperparameters.argtypes = [C.c_float, C.c_float, C.c_int32, C.c_int32, fp, fp]
     lib.pb_sync.restype = C.c_int
     lib.pb_sync.argtypes = [C.c_void_p]
     lib.pb_destroy.restype = None
@@ -225,6 +228,14 @@ class PBEngine:
             self.close()
         except Exception:
             pass
+
+
+def scale_hyperparameters(lr_ref, momentum_ref, n_ref, n=1):
+    """(lr, momentum) for update size n from the reference values (pb_scale_hyperparameters)."""
+    lib = load_library()
+    lr, m = C.c_float(), C.c_float()
+    _check(lib, lib.pb_scale_hyperparameters(lr_ref, momentum_ref, n_ref, n, C.byref(lr), C.byref(m)))
+    return lr.value, m.value
 
 
 def update_standalone(w, v, g, what, lr, m, a, b, lrT):

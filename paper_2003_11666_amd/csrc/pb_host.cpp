@@ -1706,6 +1706,21 @@ int pb_update_standalone(float* w, float* v, const float* g, float* what, int64_
   return PB_OK;
 }
 
+int pb_scale_hyperparameters(float lr_ref, float momentum_ref, int32_t n_ref, int32_t n, float* lr_out,
+                             float* momentum_out) {
+  if (!lr_out || !momentum_out) return fail(PB_E_INVALID, "NULL output pointer");
+  if (n < 1 || n_ref < 1) return fail(PB_E_INVALID, "update sizes must be >= 1");
+  if (!(momentum_ref >= 0.f && momentum_ref <= 1.f) || !(lr_ref >= 0.f))
+    return fail(PB_E_INVALID, "reference momentum must be in [0,1] and reference learning rate >= 0");
+  const double ratio = (double)n / (double)n_ref, mr = (double)momentum_ref;
+  const double m = pow(mr, ratio);
+  // m_ref = 1: (1-m)/(1-m_ref) -> n/n_ref
+  const double lr = (mr == 1.0) ? (double)lr_ref * ratio * ratio : (1.0 - m) / (1.0 - mr) * ratio * (double)lr_ref;
+  *lr_out = (float)lr;
+  *momentum_out = (float)m;
+  return PB_OK;
+}
+
 int pb_sync(pb_ctx* c) {
   if (!c) return fail(PB_E_INVALID, "NULL context");
   HIP_TRY(hipStreamSynchronize(c->stream));

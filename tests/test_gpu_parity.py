@@ -287,6 +287,34 @@ def test_overcompensation(name):
     eng.close()
 
 
+@pytest.mark.parametrize("name", ["tiny_resnet", "small_resnet"])
+def test_paper_scaled_hyperparameters(name):
+    """Learning rate and momentum as the paper derives them for update size one from a reference
+    batch of 128 (Eq. hpscale): momentum 0.9^(1/128), so that a = m^D stays close to 1 and
+    b = (1 - m^D)/(1 - m) close to D -- the regime the paper's own experiments run in.  Weights move
+    little in 80 ticks at this learning rate; the velocities carry the comparison."""
+    from paper_2003_11666_amd import scale_hyperparameters
+    lr, m = scale_hyperparameters(0.1, 0.9, 128, 1)
+    lo, mo = O.scale_hyperparameters(0.1, 0.9, 128, 1)
+    assert abs(lr - lo) <= 1e-6 * lo and abs(m - mo) <= 1e-7
+    net = W.config(name)
+    xs, ys = W.sample_pool(net)
+    K = 80
+    PBEngine = _engine()
+    eng = PBEngine(net, mitigation=3, lr=lr, momentum=m)
+    orc = O.PBOracle(net, mitigation=3, lr=lr, momentum=m)
+    for t in range(K):
+        eng.tick(xs[t % len(ys)], ys[t % len(ys)])
+        orc.tick(xs[t % len(ys)], ys[t % len(ys)])
+    from tests.parity_util import rel_errors, tensor_slices
+    e_inf, e_l2, where = rel_errors(eng.read_weights(), orc.read_weights(), tensor_slices(net))
+    assert max(e_inf, e_l2) <= TOL, (e_inf, e_l2, where)
+    v_inf, v_l2, v_where = rel_errors(eng.read_velocity(), orc.read_velocity(), tensor_slices(net))
+    assert max(v_inf, v_l2) <= 10 * TOL, (v_inf, v_l2, v_where)
+    assert np.allclose(eng.loss_history(), orc.loss_history(), rtol=1e-4, atol=1e-4)
+    eng.close()
+
+
 @pytest.mark.parametrize("name", ["tiny_mlp", "tiny_resnet", "tiny_vgg"])
 def test_lwp_weight_difference_form(name):
     """lwp_form='w' (Eq. lwp_w_form): w_hat = w + T (w - w_prev), built inside the fused update

@@ -55,3 +55,19 @@ def test_descriptor_validation_on_host():
     bad["stages"][-1] = bad["stages"][-1][:-1]
     d, keep = B.marshal_net(bad)
     assert lib.pb_arena_bytes(ctypes.byref(d), None) == 0
+
+
+def test_hyperparameter_scaling_is_host_arithmetic():
+    """pb_scale_hyperparameters (Eq. hpscale) touches no device: checked here against the oracle's
+    routine and against the two invariants the appendix states."""
+    from paper_2003_11666_amd import binding as B
+    from oracle import pb_oracle as O
+    lib = B.load_library()
+    for lr_r, m_r, n_r, n in [(0.1, 0.9, 128, 1), (0.1, 0.9, 32, 1), (0.05, 0.95, 64, 8)]:
+        lr, m = B.scale_hyperparameters(lr_r, m_r, n_r, n)
+        lo, mo = O.scale_hyperparameters(lr_r, m_r, n_r, n)
+        assert abs(lr - lo) <= 1e-6 * lo and abs(m - mo) <= 1e-7
+    out = ctypes.c_float()
+    assert lib.pb_scale_hyperparameters(0.1, 0.9, 0, 1, ctypes.byref(out), ctypes.byref(out)) < 0
+    assert lib.pb_scale_hyperparameters(0.1, 1.5, 8, 1, ctypes.byref(out), ctypes.byref(out)) < 0
+    assert lib.pb_scale_hyperparameters(0.1, 0.9, 8, 1, None, ctypes.byref(out)) < 0

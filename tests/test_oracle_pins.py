@@ -468,3 +468,43 @@ def test_lwp_weight_form():
         k = max(0, K - 2 * (S - 1) + s)
         for name_, t_ in hist[s][k][0].items():
             assert torch.allclose(c.w[s][name_], t_, rtol=1e-10, atol=1e-13), (s, name_)
+
+
+# ---- hyper-parameter scaling with the update size (Appendix "Small Batch Size Training", Eq. hpscale)
+@pytest.mark.parametrize("lr_r,m_r,n_r,n", [(0.1, 0.9, 128, 1), (0.1, 0.9, 32, 1), (0.05, 0.95, 64, 8),
+                                            (0.2, 0.5, 4, 16), (0.1, 0.0, 8, 1)])
+def test_hyperparameter_scaling_invariants(lr_r, m_r, n_r, n):
+    """What the appendix states in words: the momentum's decay per SAMPLE is unchanged, and the
+    effective learning rate lr/(1-m) is proportional to the update size."""
+    lr, m = O.scale_hyperparameters(lr_r, m_r, n_r, n)
+    assert m ** (1.0 / n) == pytest.approx(m_r ** (1.0 / n_r), rel=1e-12, abs=1e-300)
+    assert lr / (1.0 - m) / n == pytest.approx(lr_r / (1.0 - m_r) / n_r, rel=1e-12)
+    # identity at the reference size, and scaling in two hops equals scaling in one
+    assert O.scale_hyperparameters(lr_r, m_r, n_r, n_r) == pytest.approx((lr_r, m_r), rel=1e-15)
+    lr1, m1 = O.scale_hyperparameters(lr_r, m_r, n_r, 4)
+    assert O.scale_hyperparameters(lr1, m1, 4, n) == pytest.approx((lr, m), rel=1e-12)
+
+
+def test_hyperparameter_scaling_keeps_the_trajectory_of_a_constant_gradient():
+    """Plain momentum SGD (the update routine with a = 1, b = 0) on a stream of samples that all
+    have gradient 1: with update size 128 (mean gradient per update) and with update size 1 at the
+    scaled values, the weight has moved by the same amount after the same number of samples --
+    total contribution per sample lr/((1-m) n) and decay per sample m^(1/n) are both kept."""
+    lr_r, m_r, n_r = 0.1, 0.9, 128
+    lr, m = O.scale_hyperparameters(lr_r, m_r, n_r, 1)
+    n_samples = n_r * 400
+    w_r = v_r = 0.0
+    for _ in range(n_samples // n_r):
+        w_r, v_r = O.gsc_update(w_r, v_r, 1.0, lr_r, m_r, 1.0, 0.0)
+    w = v = 0.0
+    for _ in range(n_samples):
+        w, v = O.gsc_update(w, v, 1.0, lr, m, 1.0, 0.0)
+    assert w == pytest.approx(w_r, rel=5e-3)
+    # a swapped ratio (n_ref/n instead of n/n_ref) would be off by orders of magnitude
+    assert abs(w) > 1.0
+
+
+def test_hyperparameter_scaling_limit_of_unit_momentum():
+    lr, m = O.scale_hyperparameters(0.1, 1.0, 8, 2)
+    lr_near, m_near = O.scale_hyperparameters(0.1, 1.0 - 1e-9, 8, 2)
+    assert m == 1.0 and lr == pytest.approx(lr_near, rel=1e-6)
