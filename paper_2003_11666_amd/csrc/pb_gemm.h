@@ -38,8 +38,13 @@ typedef __attribute__((address_space(3))) v4f lv4;
 //   A block, GM 2:       one segment of MT*k*k floats per output channel of the
 //                        chunk -- the layout the weights have in memory
 template <int GM, int NI>
-__device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfloat* smem) {
+__device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lfloat* smem) {
   PB_TS(1);
+  // an opaque copy of the tile index: what is derived from it is then worked out
+  // inside this instantiation, not once ahead of all of them and kept in scratch
+  // memory across the dispatch on (GM, NI)
+  int tile = tile_;
+  asm volatile("" : "+s"(tile));
   const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);   // wave index: scalar
   const int wk = UNI(d.g.wk), wn = UNI(d.g.wn);
   constexpr int ni = NI;
@@ -497,7 +502,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile, int t, lfl
         // and leaves its cursor alone: the loop body has no branch around a load, so
         // that the wait before an MFMA counts the loads behind it exactly.  The
         // scheduling barriers keep the compiler from sinking reads to their first use.
-        constexpr int G = NI == 4 ? 4 : 8;
+        constexpr int G = 4;
         const int ng = nk / G;
         const lfloat* const ap0 = ap;
         const lint* const oqp0 = oqp;
@@ -601,7 +606,7 @@ __device__ __forceinline__ void step_gemm(const LDesc& d, int tile, int t, lfloa
 }
 
 // db[co] = sum_p dZ[co,p], one wavefront per channel.
-__device__ void step_bias_grad(const LDesc& d, int tile, int t) {
+__device__ __forceinline__ void step_bias_grad(const LDesc& d, int tile, int t) {
   const int co = tile * (BLK / 64) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (co >= d.K) return;
   const int P = d.OH * d.OW;

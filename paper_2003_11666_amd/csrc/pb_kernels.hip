@@ -120,7 +120,7 @@ namespace pb {
 // GroupNorm statistics of one group (biased variance, two passes) and the
 // folded per-channel scale/shift built from the forward (predicted) affine
 // parameters; kept for the backward pass of the same sample.
-__device__ void step_gn_stats(const LDesc& d, int tile, int t, lfloat* red, lfloat* smem) {
+__device__ __forceinline__ void step_gn_stats(const LDesc& d, int tile, int t, lfloat* red, lfloat* smem) {
   const int tid = threadIdx.x;
   const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W);
   const int g = tile, cpg = UNI(fdiv(C, frcp(G))), n = cpg * HW;
@@ -211,7 +211,7 @@ __device__ void step_gn_stats(const LDesc& d, int tile, int t, lfloat* red, lflo
 }
 
 // pooled[c] = mean_hw relu(sc*x+sh)
-__device__ void step_gap_fwd(const LDesc& d, int tile, int t, lfloat* red) {
+__device__ __forceinline__ void step_gap_fwd(const LDesc& d, int tile, int t, lfloat* red) {
   const int c = tile, HW = d.H * d.W;
   const gfloat* xp = at(d.x, t) + (size_t)c * HW;
   const bool aff = d.flags & F_PRE_AFFINE, rl = d.flags & F_PRE_RELU;
@@ -228,7 +228,7 @@ __device__ void step_gap_fwd(const LDesc& d, int tile, int t, lfloat* red) {
 }
 
 // Direct convolution / linear forward, one thread per output element.
-__device__ void step_conv_fwd(const LDesc& d, int tile, int t) {
+__device__ __forceinline__ void step_conv_fwd(const LDesc& d, int tile, int t) {
   const int P = d.OH * d.OW;
   const int o = tile * BLK + threadIdx.x;
   if (o >= d.K * P) return;
@@ -271,7 +271,7 @@ __device__ void step_conv_fwd(const LDesc& d, int tile, int t) {
 }
 
 // y = [maxpool] relu(sc*z+sh), one thread per output element.
-__device__ void step_post_fwd(const LDesc& d, int tile, int t) {
+__device__ __forceinline__ void step_post_fwd(const LDesc& d, int tile, int t) {
   const gfloat* z = at(d.x, t);
   const gfloat* st = at(d.st, t);
   gfloat* y = at(d.y, t);
@@ -304,7 +304,7 @@ __device__ void step_post_fwd(const LDesc& d, int tile, int t) {
 
 // Softmax cross-entropy of the sample that reaches the last stage at tick t
 // (sample index t-(S-1)); writes dlogits = softmax - onehot.
-__device__ void step_ce(const LDesc& d, int tile, int t, lfloat* red) {
+__device__ __forceinline__ void step_ce(const LDesc& d, int tile, int t, lfloat* red) {
   const gfloat* z = at(d.x, t);
   gfloat* dz = at(d.dx, t);
   const int n = d.n;
@@ -369,7 +369,7 @@ __device__ __forceinline__ float gn_du(const LDesc& d, const gfloat* dy, const g
 // ReLU mask); also gamma_b*dbeta and gamma_b*dgamma for the group sums.
 // One wavefront per channel (small maps: a workgroup per channel would leave
 // most of its lanes without an element).  Plain gradient buffers only.
-__device__ void step_gnb_reduce_wave(const LDesc& d, int tile, int t) {
+__device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, int t) {
   const int lane = threadIdx.x & 63, c = tile * (BLK / 64) + UNI((int)(threadIdx.x >> 6));
   const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W);
   if (c >= C) return;
@@ -418,7 +418,7 @@ __device__ void step_gnb_reduce_wave(const LDesc& d, int tile, int t) {
   }
 }
 
-__device__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red) {
+__device__ __forceinline__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red) {
   if (UNI(d.grain) == 1) { step_gnb_reduce_wave(d, tile, t); return; }
   const int c = tile, HW = UNI(d.H) * UNI(d.W), cpg = UNI(fdiv(UNI(d.C), frcp(UNI(d.G)))), g = UNI(fdiv(c, frcp(cpg)));
   const gfloat* st = at(d.st, t);
@@ -482,7 +482,7 @@ __device__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red) {
 // Streaming form: a workgroup takes d.grain consecutive floats of ONE group
 // (d.n workgroups per group), 16 bytes per access, every operand of a thread
 // requested before the first is used.  Plain gradient buffers, H*W a multiple of 4.
-__device__ void step_gnb_apply_stream(const LDesc& d, int tile, int t) {
+__device__ __forceinline__ void step_gnb_apply_stream(const LDesc& d, int tile, int t) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W), grain = UNI(d.grain), tpg = UNI(d.n);
   const int cpg = UNI(fdiv(C, frcp(G))), gsz = cpg * HW;
@@ -540,7 +540,7 @@ __device__ void step_gnb_apply_stream(const LDesc& d, int tile, int t) {
   }
 }
 
-__device__ void step_gnb_apply(const LDesc& d, int tile, int t) {
+__device__ __forceinline__ void step_gnb_apply(const LDesc& d, int tile, int t) {
   if (UNI(d.grain) > 0) { step_gnb_apply_stream(d, tile, t); return; }
   const int HW = UNI(d.H) * UNI(d.W), cpg = UNI(fdiv(UNI(d.C), frcp(UNI(d.G)))), n = cpg * HW;
   const int o = tile * BLK + threadIdx.x;
@@ -593,7 +593,7 @@ constexpr int GNB_MAX_N = 4096;
 // slot lies inside one channel).  Per-channel sums (dgamma, dbeta) go through
 // per-slot partial sums in LDS, then the group sums, then dx.
 // LDS: psum[n/4] | psum2[n/4] | cs[2*cpg] | cs2[3*cpg] | grp[2]
-__device__ void step_gn_bwd(const LDesc& d, int tile, int t, bool live, lfloat* smem) {
+__device__ __forceinline__ void step_gn_bwd(const LDesc& d, int tile, int t, bool live, lfloat* smem) {
   const int tid = threadIdx.x;
   const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W), flags = UNI(d.flags);
   const int g = tile, cpg = UNI(fdiv(C, frcp(G))), n = cpg * HW, ns = n >> 2, HW4 = HW >> 2;
@@ -703,7 +703,7 @@ __device__ void step_gn_bwd(const LDesc& d, int tile, int t, bool live, lfloat* 
 
 // Backward data: dX = W^T dZ (transposed convolution), one thread per input
 // element, gathering.
-__device__ void step_conv_bwd_x(const LDesc& d, int tile, int t) {
+__device__ __forceinline__ void step_conv_bwd_x(const LDesc& d, int tile, int t) {
   const int HW = d.H * d.W, P = d.OH * d.OW, kk = d.k * d.k;
   const int o = tile * BLK + threadIdx.x;
   if (o >= d.C * HW) return;
@@ -733,7 +733,7 @@ __device__ void step_conv_bwd_x(const LDesc& d, int tile, int t) {
 // Backward weights: dW[co,ci,kh,kw] = sum_p dZ[co,p] * a[ci, p*s-pad+k],
 // a = the forward's transformed input recomputed from the saved input.
 // Large maps: one wavefront per weight element; small maps: one thread.
-__device__ void step_conv_bwd_w(const LDesc& d, int tile, int t) {
+__device__ __forceinline__ void step_conv_bwd_w(const LDesc& d, int tile, int t) {
   const int HW = d.H * d.W, P = d.OH * d.OW, kk = d.k * d.k;
   const int nW = d.K * d.C * kk;
   const bool wave_mode = P > 16;
@@ -787,7 +787,7 @@ __device__ void step_conv_bwd_w(const LDesc& d, int tile, int t) {
   }
 }
 
-__device__ void step_copy(const LDesc& d, int tile, int t) {
+__device__ __forceinline__ void step_copy(const LDesc& d, int tile, int t) {
   const int grain = UNI(d.grain), n = UNI(d.n);
   if (grain > 0) {   // streaming form: grain floats per workgroup, 16 bytes per access (n a multiple of 4)
     const gfloat* src = at(d.dy, t);
@@ -818,7 +818,7 @@ __device__ void step_copy(const LDesc& d, int tile, int t) {
 // The tick's sample into the first stage's input ring, its label into the
 // label ring.  src != nullptr: handed over by the host call; otherwise pool
 // item (idx_base + k) mod n_pool.
-__device__ void step_ingest(const LDesc& d, int tile, int t, const Globals* __restrict__ G, int k,
+__device__ __forceinline__ void step_ingest(const LDesc& d, int tile, int t, const Globals* __restrict__ G, int k,
                             const float* src_override, int label_override) {
   const gfloat* src = (const gfloat*)src_override;
   int lab = label_override;
@@ -840,7 +840,7 @@ __device__ void step_ingest(const LDesc& d, int tile, int t, const Globals* __re
 // other (d.what), so the update may run beside forward work of the same tick
 // as soon as the stage's gradients are complete.  Master weights and velocity
 // (read d.w, d.v; written d.wp, d.b) are updated in place.
-__device__ void step_update(const LDesc& d, int tile) {
+__device__ __forceinline__ void step_update(const LDesc& d, int tile) {
   // the step streams 24 bytes per parameter and nothing else: what it needs is bytes in
   // flight, so every thread requests its 8 vectors of all three arrays before using any
   constexpr int UU = UPD_TILE / (4 * BLK);
@@ -894,7 +894,7 @@ constexpr int HEAD_MAX_K = 16;      // classes
 // channel) and every reduction over a group or a channel goes through one
 // array of per-slot partial sums in LDS.
 // LDS: psum[n/4] | psum2[n/4] | vec[512] | dvec[512] | logit[16] | ebuf[16] | chan[9*C] | grp[2*G]
-__device__ void step_head_gap4(const LDesc& d, int t, lfloat* smem) {
+__device__ __forceinline__ void step_head_gap4(const LDesc& d, int t, lfloat* smem) {
   const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);
   const int C = UNI(d.C), HW = UNI(d.H) * UNI(d.W), K = UNI(d.K), G = UNI(d.G), flags = UNI(d.flags);
   const bool rl = flags & F_PRE_RELU, has_b = flags & F_BIAS;
@@ -1155,7 +1155,7 @@ __device__ void step_head_gap4(const LDesc& d, int t, lfloat* smem) {
 // goes to LDS, the weights stay in registers) and everything after that runs
 // out of LDS and registers.
 // LDS: xs[C*H*W] | vec[512] | dvec[512] | logit[16] | bias[16] | chan[9*C] | grp[2*G]
-__device__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
+__device__ __forceinline__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
   (void)red;
   if ((UNI(d.flags) & F_PRE_AFFINE) && (UNI(d.flags) & F_DU_GAP) && ((UNI(d.H) * UNI(d.W)) & 3) == 0) {
     step_head_gap4(d, t, smem);
