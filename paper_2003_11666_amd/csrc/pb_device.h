@@ -65,7 +65,9 @@ struct GemmCfg {
   int32_t vec;             // 1: patch rows are staged with 16-byte copies (source rows a multiple of 4 wide, no transform);
                            // 2: backward data of a strided layer: patch cleared, then the gradient scattered into it
   int32_t xoff;            // LDS column of logical patch column 0
-  int32_t nsub;            // backward weights: consecutive column tiles one workgroup runs (tiles_n counts groups of nsub)
+  int32_t nsub;            // consecutive column tiles one workgroup runs (tiles_n counts groups of nsub)
+  int32_t win;             // > 0: 1x1 layer seen as a plain matrix product (map flattened to one row of H*W pixels):
+                           // the patch holds only the win = NT columns of the current column tile
 };
 
 // Pointer fields of a step that point into slot 0 of the stage's ring of predicted-weight versions;

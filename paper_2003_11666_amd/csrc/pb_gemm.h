@@ -196,12 +196,14 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
 
     // first row (of the output map for forward / backward weights, of the input
     // map for backward data) the current column tile touches; per-lane column offsets
-    int tile_row0 = 0, c_lo = 0, adj = 0;
+    int tile_row0 = 0, c_lo = 0, adj = 0, col0 = 0;
+    const int win = (GM == 3) ? 0 : UNI(g.win);   // > 0: flattened 1x1 layer, the patch holds the tile's own columns only
     auto tile_geometry = [&](int n0s) {
       if (GM == 1) { tile_row0 = UNI(fdiv(n0s, frcp(gOW))); adj = tile_row0 * gs * Wp; }
       else if (GM == 2) { tile_row0 = UNI(fdiv(n0s, frcp(gW))); adj = tile_row0 * Wp; }
       else { c_lo = UNI(fdiv(n0s, frcp(kk))); adj = c_lo * PRW; }
-      adj -= UNI(g.xoff);
+      col0 = win ? n0s : 0;
+      adj += col0 - UNI(g.xoff);
     };
     int tnv[NI], offn[NI];   // column offsets as the table has them, and relative to the patch of the column tile
     auto tn_load = [&](int n0s) {
@@ -289,10 +291,11 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     // and Wsrc+4..Wsrc+7 are halo.  Requests and stores separate, as for the A block.
     constexpr int VU = 6;
     const int Wsrc = (GM == 2) ? gOW : gW, Hsrc = (GM == 2) ? gOH : gH, Cred = (GM == 2) ? gK : gC;
-    const int W4 = Wsrc >> 2, pv_nrow = CC * PR, pv_nslot = pv_nrow * W4;
+    const int Wwin = win ? win : Wsrc;                    // columns of a source row that go into the patch
+    const int W4 = Wwin >> 2, pv_nrow = CC * PR, pv_nslot = pv_nrow * W4;
     v4f pv[VU];
     int pdst[VU];
-    auto p_issue = [&](int ch, int base, int clo, int trow) {
+    auto p_issue = [&](int ch, int base, int clo, int trow, int pcol) {
       int chan0, row0;
       p_origin(ch, clo, trow, chan0, row0);
       const int rshift = (GM == 2) ? border : 0;
@@ -307,8 +310,8 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
         if (base + u * BLK < pv_nslot) {
           const int chn = chan0 + c, srow = row0 + y - rshift;
           pdst[u] = c * PRW + y * Wp + 4 + 4 * xs;
-          if (chn < Cred && srow >= 0 && srow < Hsrc)
-            pv[u] = *(const gv4*)(src + ((size_t)chn * Hsrc + srow) * Wsrc + 4 * xs);
+          if (chn < Cred && srow >= 0 && srow < Hsrc && pcol + 4 * xs < Wsrc)
+            pv[u] = *(const gv4*)(src + ((size_t)chn * Hsrc + srow) * Wsrc + pcol + 4 * xs);
         }
         xs += dxs; y += dy; c += dc;
         if (xs >= W4) { xs -= W4; ++y; }
@@ -329,7 +332,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     a_issue(0, tid);
     if (!op) PB_TS(10);
     tile_geometry(n0);
-    if (vec == 1) p_issue(0, tid, c_lo, tile_row0);
+    if (vec == 1) p_issue(0, tid, c_lo, tile_row0, col0);
 
     for (int sub = 0; sub < nsub; ++sub) {
     const int n0s = n0 + sub * NT;
@@ -351,10 +354,10 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
       p_origin(ch, c_lo, tile_row0, chan0, row0);
       if (vec == 1) {
         p_commit();
-        for (int base = tid + BLK * VU; base < pv_nslot; base += BLK * VU) { p_issue(ch, base, c_lo, tile_row0); p_commit(); }
+        for (int base = tid + BLK * VU; base < pv_nslot; base += BLK * VU) { p_issue(ch, base, c_lo, tile_row0, col0); p_commit(); }
         for (int h = tid; h < 2 * pv_nrow; h += BLK) {
           const int rr = h >> 1;
-          *(lv4*)(patch + rr * Wp + ((h & 1) ? Wsrc + 4 : 0)) = (v4f){0.f, 0.f, 0.f, 0.f};
+          *(lv4*)(patch + rr * Wp + ((h & 1) ? Wwin + 4 : 0)) = (v4f){0.f, 0.f, 0.f, 0.f};
         }
       } else if (GM == 2 && vec == 2) {
         // strided layer: the output gradient sits at stride spacing inside a patch
@@ -464,13 +467,13 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
       // tile): in flight while this one is contracted
       if (ch + 1 < n_chunks) {
         a_issue(ch + 1, tid);
-        if (vec == 1) p_issue(ch + 1, tid, c_lo, tile_row0);
+        if (vec == 1) p_issue(ch + 1, tid, c_lo, tile_row0, col0);
       } else if (more) {
         if (n_chunks > 1) a_issue(0, tid);
         if (vec == 1) {
           const int nn = n0s + NT;
           p_issue(0, tid, GM == 3 ? UNI(fdiv(nn, frcp(kk))) : 0,
-                  GM == 1 ? UNI(fdiv(nn, frcp(gOW))) : (GM == 2 ? UNI(fdiv(nn, frcp(gW))) : 0));
+                  GM == 1 ? UNI(fdiv(nn, frcp(gOW))) : (GM == 2 ? UNI(fdiv(nn, frcp(gW))) : 0), win ? nn : 0);
         }
         tn_load(n0s + NT);
       }

@@ -389,6 +389,7 @@ bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int
   const int mode = g.gm, kk = k * k;
   g.MT = 16 * g.wm; g.NT = 16 * g.ni * g.wn;
   if (g.nsub < 1 || g.wk != 1) g.nsub = 1;   // the split of the reduction reuses the A block's LDS
+  if (mode == 3) g.win = 0;
   g.nsub = std::min(g.nsub, cdiv(g.N, g.NT));
   g.tiles_n = cdiv(cdiv(g.N, g.NT), g.nsub);
   g.tiles = cdiv(g.M, g.MT) * g.tiles_n;
@@ -419,6 +420,10 @@ bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int
     g.PR = mode == 1 ? (rows_max - 1) * s + k : rows_max + k - 1;
     g.Wp = mode == 1 ? W + 2 * pad : W + k - 1;
     if (g.vec == 1) g.Wp = (mode == 1 ? W : OW) + 8;
+    if (g.win) {   // flattened 1x1 layer: one row, only the tile's own columns
+      if (g.vec != 1 || H != 1 || OH != 1 || k != 1 || s != 1 || pad != 0) return false;
+      g.win = g.NT; g.Wp = g.NT + 8;
+    }
     const int nch = mode == 1 ? C : K;
     int CC = nch;
     if (fine) {
@@ -503,11 +508,12 @@ double est_tile_us(const GemmCfg& g, int k) {
 //   estimated tile duration stays within the budget, the one with the least total
 //   work (tiles x duration); if none does, the one with the shortest tile.
 bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int s, int pad,
-               const GemmCfg* like, GemmCfg* out, bool allow_vec = false, int max_sub = 16) {
+               const GemmCfg* like, GemmCfg* out, bool allow_vec = false, int max_sub = 16, bool flat = false) {
   const int target = g_tile_target;
   GemmCfg g;
   memset(&g, 0, sizeof g);
   g.gm = mode;
+  g.win = flat ? 1 : 0;
   const int kk = k * k, P = OH * OW, HWi = H * W;
   if (mode == 1) { g.M = K; g.N = P; g.Q = C * kk; }
   else if (mode == 2) { g.M = C; g.N = HWi; g.Q = K * kk; }
@@ -808,7 +814,12 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         GemmCfg g, gp;
         memset(&gp, 0, sizeof gp);
         const bool plain_src = !(d.flags & (F_PRE_AFFINE | F_PRE_RELU));
-        bool ok = make_gemm(1, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, plain_src, (d.flags & F_PROJ) ? 1 : 16);
+        // a 1x1 layer of stride 1 is a plain matrix product over the pixels: seen as a map of one row,
+        // a column tile needs its own columns only, not whole rows of the map
+        const bool flat = g_tile_budget_us > 0 && plain_src && !(d.flags & F_PROJ) && d.k == 1 && d.stride == 1 && d.pad == 0 &&
+                          (d.H * d.W) % 4 == 0 && d.H > 1;
+        if (flat) { d.W *= d.H; d.H = 1; d.OW *= d.OH; d.OH = 1; }
+        bool ok = make_gemm(1, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, plain_src, (d.flags & F_PROJ) ? 1 : 16, flat);
         if (ok && (d.flags & F_PROJ)) ok = make_gemm(1, d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, 0, &g, &gp, true);
         if (ok) {
           d.kind = K_GEMM; d.g = g; d.gp = gp; d.ntiles = g.tiles;
@@ -936,7 +947,10 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       }
       d.ntiles = cdiv((int64_t)a.C * a.H * a.W, BLK);
       GemmCfg g;
-      if (c->kernel_set == 0 && make_gemm(2, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, true)) {
+      const bool flat = c->kernel_set == 0 && g_tile_budget_us > 0 && d.k == 1 && d.stride == 1 && d.pad == 0 &&
+                        (d.H * d.W) % 4 == 0 && d.H > 1;
+      if (flat) { d.W *= d.H; d.H = 1; d.OW *= d.OH; d.OH = 1; }
+      if (c->kernel_set == 0 && make_gemm(2, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, true, 16, flat)) {
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
         gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, &d.tq, &d.tn);
       }
@@ -980,7 +994,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         d.n = ta.in_elems();
         d.dy = dy_src; d.dx = skg_w;
         d.ntiles = cdiv(d.n, BLK);
-        if (g_tile_budget_us > 0 && d.n % 4 == 0 && ref_vec4(c, d.dy) && ref_vec4(c, d.dx)) {
+        if (d.n % 4 == 0 && ref_vec4(c, d.dy) && ref_vec4(c, d.dx)) {
           d.grain = STREAM_GRAIN;
           d.ntiles = cdiv(d.n, d.grain);
         }
@@ -1283,19 +1297,21 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
             o = o && g.gm == 2 && s > 1 && g.xoff == 0;
           } else if (g.vec) {
             const int wsrc = (g.gm == 2) ? d.OW : W;
-            o = o && wsrc % 4 == 0 && g.Wp == wsrc + 8 && g.xoff == 4 - hl_ && hl_ <= 4 && (g.gm != 2 || s == 1) &&
+            if (g.win) o = o && g.win == g.NT && g.Wp == g.NT + 8 && H == 1 && d.OH == 1 && k == 1 && s == 1 && pad == 0 && g.gm != 3;
+            else o = o && g.Wp == wsrc + 8;
+            o = o && wsrc % 4 == 0 && g.xoff == 4 - hl_ && hl_ <= 4 && (g.gm != 2 || s == 1) &&
                 (g.o_patch % 4) == 0 && !(d.flags & (F_PRE_AFFINE | F_PRE_RELU) && g.gm != 2);
           } else {
-            o = o && g.xoff == 0;
+            o = o && g.xoff == 0 && g.win == 0;
           }
           if (g.gm == 1) {
             const int rows_max = std::min(d.OH, (g.NT + d.OW - 2) / d.OW + 1);
             o = o && g.M == d.K && g.N == d.OH * d.OW && g.Q == C * kk && g.QC == g.CC * kk &&
-                g.PR >= (rows_max - 1) * s + k && g.Wp >= W + 2 * pad && g.Wp >= (d.OW - 1) * s + k + g.xoff;
+                g.PR >= (rows_max - 1) * s + k && (g.win || (g.Wp >= W + 2 * pad && g.Wp >= (d.OW - 1) * s + k + g.xoff));
           } else if (g.gm == 2) {
             const int rows_max = std::min(H, (g.NT + W - 2) / W + 1);
             o = o && g.M == C && g.N == H * W && g.Q == d.K * kk && g.QC == g.CC * kk && g.PR >= rows_max + k - 1 &&
-                g.Wp >= W + k - 1 + g.xoff && pad <= k - 1;
+                (g.win || g.Wp >= W + k - 1 + g.xoff) && pad <= k - 1;
           } else if (g.gm == 3) {
             o = o && g.M == d.K && g.N == C * kk && g.Q == d.OH * d.OW && g.QC == g.rows_c * d.OW &&
                 g.CC >= std::min(C, (g.NT + kk - 2) / kk + 1) && g.PR >= (g.rows_c - 1) * s + k && g.Wp >= W + 2 * pad &&
