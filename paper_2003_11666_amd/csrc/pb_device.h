@@ -11,6 +11,7 @@ constexpr int BLK = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int UPD_CHUNK = 1024;   // stages are padded to this many floats
 constexpr int UPD_TILE = 8192;    // floats per workgroup of an update step (8 float4 per thread and array in flight)
 constexpr float GN_EPS = 1e-5f;
+constexpr int GNB_WAVE_CH = 4;    // channels per wavefront in the one-wavefront-per-channel form of K_GNB_REDUCE
 
 // A tensor that lives in a ring of `depth` slots.  At tick t the slot in use
 // is (t - lag) mod depth: lag 0 = the slot of the sample handled now, lag D =

@@ -491,11 +491,11 @@ double est_tile_us(const GemmCfg& g, int k) {
   const double stage_p = g.vec == 1 ? 0.1 * std::min(p_sl, 6.0) + 0.3 * std::max(0.0, p_sl - 6.0) : 0.3 * p_sl;
   const double mf = (double)cdiv(cdiv(std::min(g.QC, g.Q), 4), g.wk) * g.ni;
   const double t_mfma = mf * (32.0 + 70.0 / g.ni) / 2400.0;
-  const double t_chunk = 1.0 + stage_a + stage_p + t_mfma;
+  const double t_chunk = 3.0 + stage_a + stage_p + t_mfma;   // fixed part: two barriers, the request code, fill and drain of the MFMA pipeline
   double t = 4.0 + g.n_chunks * t_chunk + (g.wk > 1 ? 0.5 : 0.0);
   // further column tiles of a backward-weights workgroup: no descriptor, no tables,
   // the patch already requested; the A block again only if the reduction is chunked
-  if (g.nsub > 1) t += (g.nsub - 1) * (g.n_chunks * (0.5 + (g.n_chunks > 1 ? stage_a : 0.0) + stage_p + t_mfma) + 1.0);
+  if (g.nsub > 1) t += (g.nsub - 1) * (g.n_chunks * (2.5 + (g.n_chunks > 1 ? stage_a : 0.0) + stage_p + t_mfma) + 1.0);
   return t;
 }
 
@@ -648,7 +648,7 @@ void stream_apply(const pb_ctx* c, StepDesc& e) {
 void wave_reduce(StepDesc& d) {
   if (g_tile_budget_us <= 0 || !(d.flags & F_DU_BUF) || d.H * d.W > 1024) return;
   d.grain = 1;
-  d.ntiles = cdiv(d.C, BLK / 64);
+  d.ntiles = cdiv(d.C, GNB_WAVE_CH * (BLK / 64));
 }
 
 // Compile the network into the step table.  Every step carries the phase it
@@ -674,7 +674,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       if (a.proj) macs += (double)a.K * a.OH * a.OW * a.sC;
     }
     const double tick_us = 6.0 * macs / 50e6;
-    g_tile_budget_us = tick_us >= 10.0 ? std::max(12.0, tick_us / 2) : 0.0;
+    g_tile_budget_us = tick_us >= 10.0 ? std::max(16.0, 0.65 * tick_us) : 0.0;
     if (const char* e = getenv("PB_TILE_BUDGET_US")) g_tile_budget_us = atof(e);
   }
   const Layout& L = c->L;
@@ -1212,7 +1212,7 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
              ptr_ok(d.part, 3 * d.C) && ptr_ok(d.gamma, d.C);
         if (d.kind == K_GNB_REDUCE) {
           ok = ok && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C);
-          if (d.grain == 1) ok = ok && (d.flags & F_DU_BUF) && d.ntiles == cdiv(d.C, BLK / 64);
+          if (d.grain == 1) ok = ok && (d.flags & F_DU_BUF) && d.ntiles == cdiv(d.C, GNB_WAVE_CH * (BLK / 64));
           else ok = ok && d.grain == 0 && d.ntiles == d.C;
         } else {
           ok = ok && ref_ok(d.dx, in) && (!(d.flags & F_ADD_SKG) || ref_ok(d.skg, in));

@@ -367,54 +367,73 @@ __device__ __forceinline__ float gn_du(const LDesc& d, const gfloat* dy, const g
 
 // Per channel: dgamma = sum dyv*xh, dbeta = sum dyv (dyv = gradient after the
 // ReLU mask); also gamma_b*dbeta and gamma_b*dgamma for the group sums.
-// One wavefront per channel (small maps: a workgroup per channel would leave
-// most of its lanes without an element).  Plain gradient buffers only.
+// One wavefront per channel, GNB_WAVE_CH channels per wavefront (small maps: a
+// workgroup per channel would leave most of its lanes without an element, and a
+// workgroup that lives for one memory round trip wastes its slot).  The loads of
+// all of a wavefront's channels are requested before the first sum.  Plain
+// gradient buffers only.
 __device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, int t) {
-  const int lane = threadIdx.x & 63, c = tile * (BLK / 64) + UNI((int)(threadIdx.x >> 6));
+  const int lane = threadIdx.x & 63;
+  const int c0 = (tile * (BLK / 64) + UNI((int)(threadIdx.x >> 6))) * GNB_WAVE_CH;
   const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W);
-  if (c >= C) return;
-  const int cpg = UNI(fdiv(C, frcp(G))), g = UNI(fdiv(c, frcp(cpg)));
+  if (c0 >= C) return;
+  const int cpg = UNI(fdiv(C, frcp(G)));
   const gfloat* st = at(d.st, t);
-  const gfloat* xc = at(d.x, t) + (size_t)c * HW;
-  const gfloat* dc = at(d.dy, t) + (size_t)c * HW;
+  const gfloat* x = at(d.x, t);
+  const gfloat* dy = at(d.dy, t);
   const bool rl = UNI(d.flags) & F_GN_RELU;
   constexpr int RU = 4;
-  float xv[RU], dv[RU];
+  float xv[GNB_WAVE_CH][RU], dv[GNB_WAVE_CH][RU], mean[GNB_WAVE_CH], rstd[GNB_WAVE_CH], sc[GNB_WAVE_CH], sh[GNB_WAVE_CH],
+      gm[GNB_WAVE_CH];
 #pragma unroll
-  for (int u = 0; u < RU; ++u) {
-    const int i = lane + u * 64;
-    xv[u] = 0.f; dv[u] = 0.f;
-    if (i < HW) { xv[u] = xc[i]; dv[u] = dc[i]; }
-  }
-  const float mean = st[g], rstd = st[G + g], sc = st[2 * G + c], sh = st[2 * G + C + c];
-  const float gm = GP(d.gamma)[c];
-  float sg = 0.f, sb = 0.f;
+  for (int q = 0; q < GNB_WAVE_CH; ++q) {
+    const int c = c0 + q;
+    mean[q] = rstd[q] = sc[q] = sh[q] = gm[q] = 0.f;
 #pragma unroll
-  for (int u = 0; u < RU; ++u) {
-    if (lane + u * 64 < HW) {
-      const float yv = fmaf(sc, xv[u], sh);
-      float du = dv[u];
-      if (rl && !(yv > 0.f)) du = 0.f;
-      sg = fmaf(du, (xv[u] - mean) * rstd, sg);
-      sb += du;
+    for (int u = 0; u < RU; ++u) { xv[q][u] = 0.f; dv[q][u] = 0.f; }
+    if (c < C) {
+      const int g = UNI(fdiv(c, frcp(cpg)));
+#pragma unroll
+      for (int u = 0; u < RU; ++u) {
+        const int i = lane + u * 64;
+        if (i < HW) { xv[q][u] = x[(size_t)c * HW + i]; dv[q][u] = dy[(size_t)c * HW + i]; }
+      }
+      mean[q] = st[g]; rstd[q] = st[G + g]; sc[q] = st[2 * G + c]; sh[q] = st[2 * G + C + c];
+      gm[q] = GP(d.gamma)[c];
     }
   }
-  for (int i = lane + RU * 64; i < HW; i += 64) {
-    const float x1 = xc[i];
-    const float yv = fmaf(sc, x1, sh);
-    float du = dc[i];
-    if (rl && !(yv > 0.f)) du = 0.f;
-    sg = fmaf(du, (x1 - mean) * rstd, sg);
-    sb += du;
-  }
-  sg = wave_sum(sg);
-  sb = wave_sum(sb);
-  if (lane == 0) {
-    GP(d.ggamma)[c] = sg;
-    GP(d.gbeta)[c] = sb;
-    GP(d.part)[c] = gm * sb;
-    GP(d.part)[C + c] = gm * sg;
-    GP(d.part)[2 * C + c] = gm;
+#pragma unroll
+  for (int q = 0; q < GNB_WAVE_CH; ++q) {
+    const int c = c0 + q;
+    if (c >= C) break;
+    float sg = 0.f, sb = 0.f;
+#pragma unroll
+    for (int u = 0; u < RU; ++u) {
+      if (lane + u * 64 < HW) {
+        const float yv = fmaf(sc[q], xv[q][u], sh[q]);
+        float du = dv[q][u];
+        if (rl && !(yv > 0.f)) du = 0.f;
+        sg = fmaf(du, (xv[q][u] - mean[q]) * rstd[q], sg);
+        sb += du;
+      }
+    }
+    for (int i = lane + RU * 64; i < HW; i += 64) {
+      const float x1 = x[(size_t)c * HW + i];
+      const float yv = fmaf(sc[q], x1, sh[q]);
+      float du = dy[(size_t)c * HW + i];
+      if (rl && !(yv > 0.f)) du = 0.f;
+      sg = fmaf(du, (x1 - mean[q]) * rstd[q], sg);
+      sb += du;
+    }
+    sg = wave_sum(sg);
+    sb = wave_sum(sb);
+    if (lane == 0) {
+      GP(d.ggamma)[c] = sg;
+      GP(d.gbeta)[c] = sb;
+      GP(d.part)[c] = gm[q] * sb;
+      GP(d.part)[C + c] = gm[q] * sg;
+      GP(d.part)[2 * C + c] = gm[q];
+    }
   }
 }
 
