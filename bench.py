@@ -20,6 +20,11 @@ sys.path.insert(0, ROOT)
 # measured HBM bytes per algorithmic byte of the update kernel (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)
 UPDATE_TRAFFIC_PER_ALGORITHMIC_BYTE = 1.0
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+# k_phase: bytes that crossed the L2 / fabric boundary per algorithmic byte of the launch, from
+# `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this script (FETCH_SIZE scaled by 2, WRITE_SIZE
+# by 1: what the counters read for a plain copy of known size): profiles/k_phase_hbm_traffic.md
+KPHASE_TRAFFIC_PER_ALGORITHMIC_BYTE = {"resnet20": 2.69, "mlp": 1.78, "vgg11": 1.13, "wide": 1.30,
+                                       "resnet50_fp32": 1.96}
 
 
 def tick_algorithmic_bytes(net, n_params, lwp=True):
@@ -141,7 +146,9 @@ def main():
                                f"pool of {len(ys)} resident samples"},
         "roofline": {"kernel": "k_phase (every step of a tick: forward, backward and update of all stages)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": (KPHASE_TRAFFIC_PER_ALGORITHMIC_BYTE[args.config] * tick_bytes / launches
+                                 if args.config in KPHASE_TRAFFIC_PER_ALGORITHMIC_BYTE else None),
                      "avg_launch_us": ph_us_tick / launches, "launches_per_tick": launches,
                      "algorithmic_bytes_per_launch": tick_bytes / launches},
         "update_in_tick": {"kernel": "k_phase, update steps only (one launch per stage)", "bound": "hbm",

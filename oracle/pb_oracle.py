@@ -21,6 +21,8 @@ What it follows (paper sections / equations, by name):
   form, w_hat = w - eta*T*v with T = D (Eq. lwp_v_form); combined update
   (Section "Combined Mitigation").
 * Weight stashing (Eq. sgdpb_weight_stash) is available as bwd_weights=1.
+* Learning rate and momentum for another update size (Appendix "Small
+  Batch Size Training", Eq. hpscale): scale_hyperparameters.
 
 Readings where the paper is silent or ambiguous (kept in step with the
 library's documentation):
@@ -52,6 +54,9 @@ library's documentation):
       that crosses a stage boundary or is kept for the backward pass
       (stage outputs, a conv output that feeds a GroupNorm in the same
       stage, every dX and skip gradient); all sums stay in high precision.
+  R13 Hyper-parameter scaling with the update size (Eq. hpscale) at a
+      reference momentum of exactly 1, where the printed ratio is 0/0: the
+      limit, lr = lr_ref (n/n_ref)^2.
   Canonical parameter order: stage-major; inside a stage: main weight
   [cout][cin][kh][kw], bias, projection weight, GroupNorm scale, shift.
 """
