@@ -116,6 +116,26 @@ def test_resnet50_structure_64px_120_ticks():
     _check(res, 120, len(net["stages"]))
 
 
+@pytest.mark.timeout(900)
+def test_resnet50_config_full_size_110_ticks():
+    """The ResNet-50 configuration at its full size (3x224x224, 50 stages, 25.5 M parameters, the
+    tiling bench.py times) with fp32 activations: 110 ticks, i.e. 12 updates of the first stage and
+    up to 110 of the last, checked every 22 ticks against the oracle."""
+    net = W.config("resnet50_fp32")
+    res = run_parity(_engine(), net, 110, every=22)
+    _check(res, 110, len(net["stages"]))
+
+
+@pytest.mark.timeout(900)
+def test_resnet50_config_full_size_bf16_activations():
+    """The same network as the benchmark runs it (bf16 activations): tolerance from the
+    perturbed oracles as in test_bf16_activation_mode."""
+    net = W.config("resnet50")
+    assert net.get("act_dtype") == "bf16"
+    res = run_parity(_engine(), net, 104, every=26, perturb=(3e-6, 1e-5))
+    _check(res, 104, len(net["stages"]))
+
+
 def test_reference_kernel_set_matches_too():
     """The plain direct kernels (kernel_set=1) are a second GPU implementation."""
     net = W.config("small_resnet")
