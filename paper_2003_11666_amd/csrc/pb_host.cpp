@@ -608,8 +608,12 @@ bool a_aligned(const pb_ctx* c, const StepDesc& d, bool second) {
 constexpr int HEAD_MAX_IN = 8192, HEAD_MAX_CV = 512, HEAD_MAX_K = 16;
 bool head_fits(int C, int HW, int K, bool gap, int G) {
   const int64_t n_in = (int64_t)C * HW, cv = gap ? C : n_in;
-  if (n_in > HEAD_MAX_IN || cv > HEAD_MAX_CV || K > HEAD_MAX_K || C > 2 * BLK || G > BLK || G < 1 || C % G) return false;
-  return (n_in + 3) / 4 * 4 + 2 * HEAD_MAX_CV + 2 * HEAD_MAX_K + 9 * (int64_t)C + 2 * G <= LDS_FLOATS;
+  if (cv > HEAD_MAX_CV || K > HEAD_MAX_K || C > 2 * BLK || G > BLK || G < 1 || C % G) return false;
+  const int64_t tail = 2 * HEAD_MAX_CV + 2 * HEAD_MAX_K + 9 * (int64_t)C + 2 * G;
+  // pooled form on maps of a multiple of 4 pixels (step_head_gap4): the input stays in registers
+  // (up to 16 vectors per thread), LDS holds two partial sums per 4 elements
+  if (gap && HW % 4 == 0) return n_in <= 2 * HEAD_MAX_IN && 2 * (n_in / 4) + tail <= LDS_FLOATS;
+  return n_in <= HEAD_MAX_IN && (n_in + 3) / 4 * 4 + tail <= LDS_FLOATS;
 }
 
 // Coefficients of the stage's update (Eqs. gscv, gscw, scd, lwp_v_form) by mitigation mode.

@@ -915,6 +915,7 @@ constexpr int HEAD_MAX_K = 16;      // classes
 // channel) and every reduction over a group or a channel goes through one
 // array of per-slot partial sums in LDS.
 // LDS: psum[n/4] | psum2[n/4] | vec[512] | dvec[512] | logit[16] | ebuf[16] | chan[9*C] | grp[2*G]
+template <int XU>   // 16-byte vectors of the input a thread keeps: 8 (up to 8192 inputs) or 16
 __device__ __forceinline__ void step_head_gap4(const LDesc& d, int t, lfloat* smem) {
   const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);
   const int C = UNI(d.C), HW = UNI(d.H) * UNI(d.W), K = UNI(d.K), G = UNI(d.G), flags = UNI(d.flags);
@@ -932,7 +933,6 @@ __device__ __forceinline__ void step_head_gap4(const LDesc& d, int t, lfloat* sm
   lfloat* grp = chan + 9 * C;
   const gfloat* x = at(d.x, t);
   // ---- all global reads in one burst
-  constexpr int XU = HEAD_MAX_IN / (4 * BLK);
   v4f xr[XU];
 #pragma unroll
   for (int u = 0; u < XU; ++u) {
@@ -1179,7 +1179,8 @@ __device__ __forceinline__ void step_head_gap4(const LDesc& d, int t, lfloat* sm
 __device__ __forceinline__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
   (void)red;
   if ((UNI(d.flags) & F_PRE_AFFINE) && (UNI(d.flags) & F_DU_GAP) && ((UNI(d.H) * UNI(d.W)) & 3) == 0) {
-    step_head_gap4(d, t, smem);
+    if (UNI(d.C) * UNI(d.H) * UNI(d.W) <= HEAD_MAX_IN) step_head_gap4<HEAD_MAX_IN / (4 * BLK)>(d, t, smem);
+    else step_head_gap4<2 * HEAD_MAX_IN / (4 * BLK)>(d, t, smem);
     return;
   }
   const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);
