@@ -87,6 +87,15 @@ __device__ __forceinline__ float wave_sum(float v) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// Sum over each row of 16 lanes, returned to every lane of the row (fixed order).
+__device__ __forceinline__ float row_sum(float v) {
+  v += dpp_src<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+  v += dpp_src<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+  v += dpp_src<0x141, 0xF>(v);   // row_half_mirror
+  v += dpp_src<0x140, 0xF>(v);   // row_mirror
+  return v;
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
@@ -1165,6 +1174,180 @@ __device__ __forceinline__ void step_head_gap4(const LDesc& d, int t, lfloat* sm
     }
 }
 
+// Pooled last stage with FOUR GroupNorm groups on an 8x8 map (the CIFAR ResNets): one group per
+// wavefront.  A group's 16 * C/4 vectors sit in the registers of one wavefront, slot lane + 64 u, so
+// that a channel (16 vectors) is one row of 16 lanes at a fixed u: group statistics are wavefront
+// sums, channel sums are row sums, and neither needs LDS or a barrier.  The workgroup meets three
+// times: pooled activations -> linear layer (rows dealt out to the wavefronts) -> logits -> loss and
+// gradient of the pooled activations -> GroupNorm backward, again inside the wavefront.  The general
+// form above needs fourteen barriers for the same work.  XW = vectors per lane = C / 16.
+template <int XW>
+__device__ __forceinline__ void step_head_wave(const LDesc& d, int t, lfloat* smem) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);
+  const int C = UNI(d.C), K = UNI(d.K), flags = UNI(d.flags);
+  constexpr int HW = 64;
+  const int cpg = C >> 2, n = cpg * HW, nu = cpg >> 2;       // per group: channels, elements, vectors per lane
+  const bool rl = flags & F_PRE_RELU, has_b = flags & F_BIAS;
+  lfloat* vec = smem;                  // [256] pooled activations
+  lfloat* dvec = vec + 256;            // [256] gradient of an element under the pool
+  lfloat* logit = dvec + 256;          // [HEAD_MAX_K]
+  const int c0 = wv * cpg + (lane >> 4);                     // channel of the lane's vector u: c0 + 4 u
+  const gfloat* xg = at(d.x, t) + (size_t)wv * n;
+  // ---- all global reads in one burst
+  v4f xr[XW];
+  float gf[XW], bfw[XW], gbk[XW];
+#pragma unroll
+  for (int u = 0; u < XW; ++u) {
+    xr[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+    gf[u] = bfw[u] = gbk[u] = 0.f;
+    if (u < nu) {
+      xr[u] = *(const gv4*)(xg + 4 * (lane + 64 * u));
+      const int c = c0 + 4 * u;
+      gf[u] = GP(d.gamma)[c]; bfw[u] = GP(d.beta)[c]; gbk[u] = ((const gfloat*)d.skip.base)[c];
+    }
+  }
+  constexpr int KU = HEAD_MAX_K / 4, IU = 4;
+  float wf[KU][IU];        // forward weights: wavefront wv holds rows wv, wv + 4, ..., lane holds columns lane + 64 i
+#pragma unroll
+  for (int ku = 0; ku < KU; ++ku)
+#pragma unroll
+    for (int iu = 0; iu < IU; ++iu) {
+      const int k = wv + 4 * ku, i = lane + 64 * iu;
+      wf[ku][iu] = 0.f;
+      if (4 * ku < K && 64 * iu < C) {
+        if (k < K && i < C) wf[ku][iu] = GP(d.w)[k * C + i];
+      }
+    }
+  float wb[HEAD_MAX_K];    // backward (current) weights: thread holds column tid
+#pragma unroll
+  for (int k = 0; k < HEAD_MAX_K; ++k) {
+    wb[k] = 0.f;
+    if (k < K && tid < C) wb[k] = GP(d.wp)[k * C + tid];
+  }
+  const float bz = (has_b && tid < K) ? GP(d.b)[tid] : 0.f;
+  const int sample = t - (UNI(d.n_stages) - 1);
+  const int label = ((const gint*)d.labels)[sample % UNI(d.n_stages)];
+  // ---- GroupNorm statistics of the wavefront's group (two passes over registers)
+  float sm = 0.f;
+#pragma unroll
+  for (int u = 0; u < XW; ++u) sm += (xr[u][0] + xr[u][1]) + (xr[u][2] + xr[u][3]);
+  const float mean = wave_sum(sm) / (float)n;
+  float q = 0.f;
+#pragma unroll
+  for (int u = 0; u < XW; ++u)
+    if (u < nu) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { const float dl = xr[u][e] - mean; q = fmaf(dl, dl, q); }
+    }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)n + GN_EPS);
+  // ---- normalise, ReLU, average pool: a channel is a row of 16 lanes
+  float sc[XW], sh[XW];
+#pragma unroll
+  for (int u = 0; u < XW; ++u) {
+    sc[u] = gf[u] * rstd;
+    sh[u] = fmaf(-mean, sc[u], bfw[u]);
+    float ps = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { float v = fmaf(sc[u], xr[u][e], sh[u]); if (rl) v = fmaxf(v, 0.f); ps += v; }
+    ps = row_sum(ps);
+    if (u < nu && (lane & 15) == 0) vec[c0 + 4 * u] = ps / (float)HW;
+  }
+  __syncthreads();
+  // ---- linear layer: wavefront wv computes rows wv, wv + 4, ...
+#pragma unroll
+  for (int ku = 0; ku < KU; ++ku) {
+    const int k = wv + 4 * ku;
+    if (k < K) {
+      float a = 0.f;
+#pragma unroll
+      for (int iu = 0; iu < IU; ++iu) {
+        const int i = lane + 64 * iu;
+        if (64 * iu < C && i < C) a = fmaf(wf[ku][iu], vec[i], a);
+      }
+      a = wave_sum(a);
+      if (lane == 0) logit[k] = a;
+    }
+  }
+  if (tid < K) dvec[tid] = bz;           // the bias rides in dvec[0..K) until the next barrier
+  __syncthreads();
+  // ---- loss and dlogits (every thread, from LDS)
+  float dl[HEAD_MAX_K];
+  float mx = -3.0e38f;
+#pragma unroll
+  for (int k = 0; k < HEAD_MAX_K; ++k) {
+    dl[k] = (k < K) ? logit[k] + dvec[k] : -3.0e38f;
+    mx = fmaxf(mx, dl[k]);
+  }
+  const float zl = logit[label] + dvec[label];
+  float se = 0.f;
+#pragma unroll
+  for (int k = 0; k < HEAD_MAX_K; ++k) { dl[k] = (k < K) ? expf(dl[k] - mx) : 0.f; se += dl[k]; }
+  if (tid == 0) GP(d.loss_log)[sample % UNI(d.loss_cap)] = logf(se) + mx - zl;
+#pragma unroll
+  for (int k = 0; k < HEAD_MAX_K; ++k) dl[k] = dl[k] / se - (k == label ? 1.f : 0.f);
+  __syncthreads();                       // every thread has read the bias out of dvec
+  // ---- backward of the linear layer: dW = dl (x) vec, db = dl, dvec = W_cur^T dl / HW
+  if (tid < C) {
+    const float vi = vec[tid];
+    float a = 0.f;
+#pragma unroll
+    for (int k = 0; k < HEAD_MAX_K; ++k)
+      if (k < K) {
+        GP(d.gw)[k * C + tid] = dl[k] * vi;
+        a = fmaf(wb[k], dl[k], a);
+      }
+    dvec[tid] = a / (float)HW;
+  }
+  if (has_b) {
+#pragma unroll
+    for (int k = 0; k < HEAD_MAX_K; ++k)
+      if (k < K && tid == k) GP(d.gb)[k] = dl[k];
+  }
+  __syncthreads();
+  // ---- GroupNorm backward inside the wavefront
+  float s1 = 0.f, s2 = 0.f;              // group sums of gamma_b * (channel sums), taken from one lane per row
+  float dug[XW];
+#pragma unroll
+  for (int u = 0; u < XW; ++u) {
+    dug[u] = 0.f;
+    if (u < nu) {
+      const int c = c0 + 4 * u;
+      const float du0 = dvec[c];
+      float sg = 0.f, sb = 0.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float du = du0;
+        if (rl && !(fmaf(sc[u], xr[u][e], sh[u]) > 0.f)) du = 0.f;
+        sg = fmaf(du, (xr[u][e] - mean) * rstd, sg);
+        sb += du;
+      }
+      sg = row_sum(sg); sb = row_sum(sb);
+      if ((lane & 15) == 0) {
+        GP(d.ggamma)[c] = sg; GP(d.gbeta)[c] = sb;
+        s1 = fmaf(gbk[u], sb, s1); s2 = fmaf(gbk[u], sg, s2);
+      }
+      dug[u] = du0 * gbk[u];
+    }
+  }
+  if (d.dx.base == nullptr) return;
+  const float inv_n = 1.0f / (float)n;
+  const float m1 = wave_sum(s1) * inv_n, m2 = wave_sum(s2) * inv_n;
+  gfloat* dx = at(d.dx, t) + (size_t)wv * n;
+#pragma unroll
+  for (int u = 0; u < XW; ++u)
+    if (u < nu) {
+      v4f o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float du = dug[u];
+        if (rl && !(fmaf(sc[u], xr[u][e], sh[u]) > 0.f)) du = 0.f;
+        const float xh = (xr[u][e] - mean) * rstd;
+        o[e] = rbf_if(flags & F_BF16_OUT, rstd * (du - m1 - xh * m2));
+      }
+      *(gv4*)(dx + 4 * (lane + 64 * u)) = o;
+    }
+}
+
 // The whole last stage in one workgroup: [GroupNorm, ReLU, global average
 // pool |  ReLU | nothing] -> linear -> softmax cross-entropy -> backward of all
 // of it.  Forward parameters: d.w / d.b / d.gamma / d.beta point into the
@@ -1178,6 +1361,12 @@ __device__ __forceinline__ void step_head_gap4(const LDesc& d, int t, lfloat* sm
 // LDS: xs[C*H*W] | vec[512] | dvec[512] | logit[16] | bias[16] | chan[9*C] | grp[2*G]
 __device__ __forceinline__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
   (void)red;
+  if ((UNI(d.flags) & F_PRE_AFFINE) && (UNI(d.flags) & F_DU_GAP) && UNI(d.H) * UNI(d.W) == 64 && UNI(d.G) == 4 &&
+      (UNI(d.C) & 15) == 0 && UNI(d.C) <= 256) {
+    if (UNI(d.C) <= 64) step_head_wave<4>(d, t, smem);
+    else step_head_wave<16>(d, t, smem);
+    return;
+  }
   if ((UNI(d.flags) & F_PRE_AFFINE) && (UNI(d.flags) & F_DU_GAP) && ((UNI(d.H) * UNI(d.W)) & 3) == 0) {
     if (UNI(d.C) * UNI(d.H) * UNI(d.W) <= HEAD_MAX_IN) step_head_gap4<HEAD_MAX_IN / (4 * BLK)>(d, t, smem);
     else step_head_gap4<2 * HEAD_MAX_IN / (4 * BLK)>(d, t, smem);
