@@ -379,6 +379,7 @@ int pow2_floor(int x) { int p = 1; while (p * 2 <= x) p *= 2; return p; }
 
 // Tiling of one implicit-GEMM operand set.  mode 1 forward, 2 backward data,
 // 3 backward weights.
+int g_tile_target_bwd = 8; // ... of a backward step (a stage has two of them in the same phase)
 int g_tile_target = 8;     // latency policy: workgroups a step is split into at least, when its shape allows
 double g_tile_budget_us = 0;   // throughput policy (> 0): longest tile a step should have, microseconds (estimate)
 
@@ -509,7 +510,7 @@ double est_tile_us(const GemmCfg& g, int k) {
 //   work (tiles x duration); if none does, the one with the shortest tile.
 bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int s, int pad,
                const GemmCfg* like, GemmCfg* out, bool allow_vec = false, int max_sub = 16, bool flat = false) {
-  const int target = g_tile_target;
+  const int target = (mode == 1) ? g_tile_target : g_tile_target_bwd;
   GemmCfg g;
   memset(&g, 0, sizeof g);
   g.gm = mode;
@@ -665,8 +666,13 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   const int S = c->S;
   // all stages run concurrently: aim at a few workgroups per compute unit over
   // the whole phase rather than per step
-  g_tile_target = std::max(4, std::min(32, 1024 / (3 * S)));
+  g_tile_target = std::max(4, std::min(32, 960 / (3 * S)));
   if (const char* e = getenv("PB_TILE_TARGET")) g_tile_target = std::max(1, atoi(e));
+  // the backward phase holds two GEMM steps per stage: fewer tiles each, so that the phase's workgroups
+  // fit the 512 a chip holds at a time (ResNet-20: 16 / 9 measured 33.4 k ticks/s, 16 / 12 30.0 k, 16 / 8 27.0 k)
+  g_tile_target_bwd = std::max(4, std::min(32, 540 / (3 * S)));
+  if (getenv("PB_TILE_TARGET")) g_tile_target_bwd = g_tile_target;
+  if (const char* e = getenv("PB_TILE_TARGET_BWD")) g_tile_target_bwd = std::max(1, atoi(e));
   // Networks whose tick is long compared with a launch are tiled for throughput:
   // the budget for the longest tile is the duration of a GEMM phase if the tick's
   // 6 flops per multiply-accumulate ran at a third of the fp32 MFMA peak, spread
