@@ -68,6 +68,41 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
   v4f acc[NI], acc2[NI];
 #pragma unroll
   for (int j = 0; j < NI; ++j) { acc[j] = (v4f){0.f, 0.f, 0.f, 0.f}; acc2[j] = (v4f){0.f, 0.f, 0.f, 0.f}; }
+  // Operands of the epilogue (bias, skip tensor, ReLU mask source, skip-path gradient).  With
+  // one or two column subtiles per wave they are few enough to be requested before the
+  // contraction and kept in registers, so that the epilogue does not pay a memory round
+  // trip of its own; with four subtiles they are requested in the epilogue.
+  constexpr bool EARLY = NI <= 2 && GM != 3;
+  float ea[EARLY ? NI : 1][4], em[EARLY ? NI : 1][4];
+#pragma unroll
+  for (int j = 0; j < (EARLY ? NI : 1); ++j)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { ea[j][r] = 0.f; em[j][r] = 1.f; }
+  auto epi_operands = [&](int n0s, int tt, float (*add)[4], float (*msk)[4]) {
+    const int M = UNI(d.g.M), N = UNI(d.g.N);
+    const int mrow = m0 + wm_id * 16 + 4 * kq;
+    const int ncol = n0s + wn_id * ni * 16 + (lane & 15);
+    const gfloat* skip = (GM == 1 && (flags & F_SKIP) && !(flags & F_PROJ)) ? (const gfloat*)at(d.skip, tt) : nullptr;
+    const gfloat* xm = (GM == 2 && (flags & F_MASK_X)) ? (const gfloat*)at(d.x, tt) : nullptr;
+    const gfloat* skg = (GM == 2 && (flags & F_ADD_SKG)) ? (const gfloat*)at(d.skg, tt) : nullptr;
+    const gfloat* bias = (GM == 1 && (flags & F_BIAS)) ? GP(d.b) : nullptr;
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      const int n = ncol + j * 16;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        add[j][r] = 0.f; msk[j][r] = 1.f;
+        if (n < N && mrow + r < M) {
+          const int o = (mrow + r) * N + n;
+          if (bias) add[j][r] = bias[mrow + r];
+          if (skip) add[j][r] += skip[o];
+          if (skg) add[j][r] = skg[o];
+          if (xm) msk[j][r] = xm[o];
+        }
+      }
+    }
+  };
+  const bool extras_any = (GM == 1 && (flags & (F_BIAS | F_SKIP))) || (GM == 2 && (flags & (F_MASK_X | F_ADD_SKG)));
   // sums of a tile: split of the reduction across waves, epilogue, store
   auto finish = [&](int n0s) {
     // the addresses the epilogue needs are worked out here, not before the
@@ -124,27 +159,16 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
       }
       return;
     }
-    const gfloat* skip = (GM == 1 && (flags & F_SKIP) && !(flags & F_PROJ)) ? (const gfloat*)at(d.skip, te) : nullptr;
-    const gfloat* xm = (GM == 2 && (flags & F_MASK_X)) ? (const gfloat*)at(d.x, te) : nullptr;
-    const gfloat* skg = (GM == 2 && (flags & F_ADD_SKG)) ? (const gfloat*)at(d.skg, te) : nullptr;
-    const gfloat* bias = (GM == 1 && (flags & F_BIAS)) ? GP(d.b) : nullptr;
     // every operand of the epilogue is requested before the first one is used
     PB_TS(18);
     float add[NI][4], msk[NI][4];
+    if (EARLY) {
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-      const int n = ncol + j * 16;
+      for (int j = 0; j < NI; ++j)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        add[j][r] = 0.f; msk[j][r] = 1.f;
-        if (n < N && ro[r] >= 0) {
-          const int o = ro[r] + n;
-          if (bias) add[j][r] = bias[mrow + r];
-          if (skip) add[j][r] += skip[o];
-          if (skg) add[j][r] = skg[o];
-          if (xm) msk[j][r] = xm[o];
-        }
-      }
+        for (int r = 0; r < 4; ++r) { add[j][r] = ea[EARLY ? j : 0][r]; msk[j][r] = em[EARLY ? j : 0][r]; }
+    } else {
+      epi_operands(n0s, te, add, msk);
     }
     PB_TS(19);
 #pragma unroll
@@ -339,6 +363,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     if (sub && n0s >= N) break;
     const bool more = sub + 1 < nsub && n0s + NT < N;   // another column tile follows
     tile_geometry(n0s);
+    if (EARLY && !op && wk_id == 0 && extras_any) epi_operands(n0s, t, ea, em);
 #pragma unroll
     for (int j = 0; j < NI; ++j) offn[j] = (tnv[j] >= 0) ? tnv[j] - adj : 0;
     __syncthreads();   // LDS may still be in use by the previous operand set / column tile
