@@ -653,7 +653,8 @@ void stream_apply(const pb_ctx* c, StepDesc& e) {
 
 // One wavefront per channel for a K_GNB_REDUCE step over a small map.
 void wave_reduce(StepDesc& d) {
-  if (g_tile_budget_us <= 0 || !(d.flags & F_DU_BUF) || d.H * d.W > 1024) return;
+  // (a gradient routed back through a max-pool costs a window search per element: small maps only)
+  if (g_tile_budget_us <= 0 || !(d.flags & (F_DU_BUF | F_DU_POOL)) || d.H * d.W > ((d.flags & F_DU_POOL) ? 64 : 1024)) return;
   d.grain = 1;
   d.ntiles = cdiv(d.C, GNB_WAVE_CH * (BLK / 64));
 }
@@ -1249,7 +1250,7 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
              ptr_ok(d.part, 3 * d.C) && ptr_ok(d.gamma, d.C);
         if (d.kind == K_GNB_REDUCE) {
           ok = ok && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C);
-          if (d.grain == 1) ok = ok && (d.flags & F_DU_BUF) && d.ntiles == cdiv(d.C, GNB_WAVE_CH * (BLK / 64));
+          if (d.grain == 1) ok = ok && (d.flags & (F_DU_BUF | F_DU_POOL)) && d.ntiles == cdiv(d.C, GNB_WAVE_CH * (BLK / 64));
           else ok = ok && d.grain == 0 && d.ntiles == d.C;
         } else {
           ok = ok && ref_ok(d.dx, in) && (!(d.flags & F_ADD_SKG) || ref_ok(d.skg, in));

@@ -380,7 +380,7 @@ __device__ __forceinline__ float gn_du(const LDesc& d, const gfloat* dy, const g
 // workgroup per channel would leave most of its lanes without an element, and a
 // workgroup that lives for one memory round trip wastes its slot).  The loads of
 // all of a wavefront's channels are requested before the first sum.  Plain
-// gradient buffers only.
+// gradient buffers, or gradients routed back through a max-pool.
 __device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, int t) {
   const int lane = threadIdx.x & 63;
   const int c0 = (tile * (BLK / 64) + UNI((int)(threadIdx.x >> 6))) * GNB_WAVE_CH;
@@ -390,7 +390,7 @@ __device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, i
   const gfloat* st = at(d.st, t);
   const gfloat* x = at(d.x, t);
   const gfloat* dy = at(d.dy, t);
-  const bool rl = UNI(d.flags) & F_GN_RELU;
+  const bool rl = UNI(d.flags) & F_GN_RELU, pooled = UNI(d.flags) & F_DU_POOL;
   constexpr int RU = 4;
   float xv[GNB_WAVE_CH][RU], dv[GNB_WAVE_CH][RU], mean[GNB_WAVE_CH], rstd[GNB_WAVE_CH], sc[GNB_WAVE_CH], sh[GNB_WAVE_CH],
       gm[GNB_WAVE_CH];
@@ -405,10 +405,17 @@ __device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, i
 #pragma unroll
       for (int u = 0; u < RU; ++u) {
         const int i = lane + u * 64;
-        if (i < HW) { xv[q][u] = x[(size_t)c * HW + i]; dv[q][u] = dy[(size_t)c * HW + i]; }
+        if (i < HW) { xv[q][u] = x[(size_t)c * HW + i]; if (!pooled) dv[q][u] = dy[(size_t)c * HW + i]; }
       }
       mean[q] = st[g]; rstd[q] = st[G + g]; sc[q] = st[2 * G + c]; sh[q] = st[2 * G + C + c];
       gm[q] = GP(d.gamma)[c];
+      if (pooled) {   // gradient routed back through the max-pool (needs the channel's scale and shift)
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+          const int i = lane + u * 64;
+          if (i < HW) dv[q][u] = gn_du(d, dy, x + (size_t)c * HW, sc[q], sh[q], c, i, HW);
+        }
+      }
     }
   }
 #pragma unroll
@@ -429,7 +436,7 @@ __device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, i
     for (int i = lane + RU * 64; i < HW; i += 64) {
       const float x1 = x[(size_t)c * HW + i];
       const float yv = fmaf(sc[q], x1, sh[q]);
-      float du = dy[(size_t)c * HW + i];
+      float du = pooled ? gn_du(d, dy, x + (size_t)c * HW, sc[q], sh[q], c, i, HW) : dy[(size_t)c * HW + i];
       if (rl && !(yv > 0.f)) du = 0.f;
       sg = fmaf(du, (x1 - mean[q]) * rstd[q], sg);
       sb += du;
