@@ -26,6 +26,8 @@ namespace pb {
 template <int V> struct IConst { static constexpr int value = V; };
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) v4f gv4;
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(1))) v2f gv2;
 typedef __attribute__((address_space(3))) v4f lv4;
 
 // One tile of a K_GEMM step, GM = 1 forward, 2 backward data, 3 backward
@@ -383,6 +385,34 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
         for (int h = tid; h < 2 * pv_nrow; h += BLK) {
           const int rr = h >> 1;
           *(lv4*)(patch + rr * Wp + ((h & 1) ? Wwin + 4 : 0)) = (v4f){0.f, 0.f, 0.f, 0.f};
+        }
+      } else if (GM == 2 && vec == 3) {
+        // layer of stride 2 (border 0 or 1, even gradient width, patch width a multiple
+        // of 4): a 16-byte vector of a patch row holds two neighbouring gradient values
+        // with zeros between them, or zeros only: one 8-byte request and one 16-byte
+        // store per vector, no clearing pass.
+        const int W4p = Wp >> 2, rows4 = PR * W4p, nslot = CC * rows4;
+        constexpr int DU = 6;
+        const float ir4 = frcp(rows4), iw4 = frcp(W4p);
+        v2f v[DU];
+        for (int base = tid; base < nslot; base += DU * BLK) {
+#pragma unroll
+          for (int u = 0; u < DU; ++u) {
+            const int sl = base + u * BLK;
+            v[u] = (v2f){0.f, 0.f};
+            if (sl < nslot) {
+              const int c = fdiv(sl, ir4), rem = sl - c * rows4, y = fdiv(rem, iw4), j = rem - y * W4p;
+              const int chn = chan0 + c, ty = row0 + y - border, oh = ty >> 1;
+              if (chn < gK && ty >= 0 && !(ty & 1) && oh < gOH && 2 * j < gOW)
+                v[u] = *(const gv2*)(src + (size_t)chn * P + oh * gOW + 2 * j);
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < DU; ++u) {
+            const int sl = base + u * BLK;
+            if (sl < nslot)
+              *(lv4*)(patch + 4 * sl) = border ? (v4f){0.f, v[u][0], 0.f, v[u][1]} : (v4f){v[u][0], 0.f, v[u][1], 0.f};
+          }
         }
       } else if (GM == 2 && vec == 2) {
         // strided layer: the output gradient sits at stride spacing inside a patch

@@ -388,6 +388,15 @@ double g_tile_budget_us = 0;   // throughput policy (> 0): longest tile a step s
 // Given the wave arrangement (wm, wn, wk, ni), choose the chunking of the
 // reduction that fits the LDS budget.  `fine`: search the channel count of a
 // chunk in steps of 4 (else by halving).  Returns false if nothing fits.
+// Rows of a map of row length `rowlen` that NT consecutive pixels starting at a
+// multiple of NT can touch.
+static int tile_rows(int NT, int rowlen, int nrows) {
+  int r = (NT + rowlen - 2) / rowlen + 1;
+  if (rowlen % NT == 0) r = 1;
+  else if (NT % rowlen == 0) r = NT / rowlen;
+  return std::min(nrows, r);
+}
+
 bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int s, int pad, bool allow_vec, bool fine) {
   const int mode = g.gm, kk = k * k;
   g.MT = 16 * g.wm; g.NT = 16 * g.ni * g.wn;
@@ -404,7 +413,7 @@ bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int
     if (mode == 2) g.vec = (s == 1 && OW % 4 == 0) ? 1 : 0;
     else g.vec = (W % 4 == 0) ? 1 : 0;
   }
-  if (mode == 2 && s > 1) g.vec = 2;
+  if (mode == 2 && s > 1) g.vec = (s == 2 && hl <= 1 && OW % 2 == 0) ? 3 : 2;   // 3: pairs of gradient values per 16-byte vector
   g.xoff = g.vec == 1 ? 4 - hl : 0;
   // LDS per chunk: offset table, A block, patch
   auto a_size = [&](int QC) -> int64_t {
@@ -419,10 +428,11 @@ bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int
   };
   if (mode == 1 || mode == 2) {
     const int rowlen = mode == 1 ? OW : W, nrows = mode == 1 ? OH : H;
-    const int rows_max = std::min(nrows, (g.NT + rowlen - 2) / rowlen + 1);
+    const int rows_max = tile_rows(g.NT, rowlen, nrows);
     g.PR = mode == 1 ? (rows_max - 1) * s + k : rows_max + k - 1;
     g.Wp = mode == 1 ? W + 2 * pad : W + k - 1;
     if (g.vec == 1) g.Wp = (mode == 1 ? W : OW) + 8;
+    if (g.vec == 3) g.Wp = (g.Wp + 3) / 4 * 4;
     if (g.win) {   // flattened 1x1 layer: one row, only the tile's own columns
       if (g.vec != 1 || H != 1 || OH != 1 || k != 1 || s != 1 || pad != 0) return false;
       g.win = g.NT; g.Wp = g.NT + 8;
@@ -489,7 +499,7 @@ double est_tile_us(const GemmCfg& g, int k) {
   const int kk = k * k;
   const double a_fl = g.gm == 2 ? (double)((g.QCpad + kk - 1) / kk + 1) * g.MT * kk : (double)g.MT * g.QCpad;
   const double p_fl = (double)g.CC * g.PR * g.Wp;
-  const double a_sl = a_fl / (g.avec ? 4 : 1) / BLK, p_sl = p_fl / (g.vec == 1 ? 4 : 1) / BLK;
+  const double a_sl = a_fl / (g.avec ? 4 : 1) / BLK, p_sl = p_fl / ((g.vec == 1 || g.vec == 3) ? 4 : 1) / BLK;
   const double stage_a = 0.1 * std::min(a_sl, 6.0) + 0.3 * std::max(0.0, a_sl - 6.0);
   const double stage_p = g.vec == 1 ? 0.1 * std::min(p_sl, 6.0) + 0.3 * std::max(0.0, p_sl - 6.0) : 0.3 * p_sl;
   const double mf = (double)cdiv(cdiv(std::min(g.QC, g.Q), 4), g.wk) * g.ni;
@@ -1333,6 +1343,9 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
           const int hl_ = (g.gm == 2) ? k - 1 - pad : pad;
           if (g.vec == 2) {
             o = o && g.gm == 2 && s > 1 && g.xoff == 0;
+          } else if (g.vec == 3) {
+            o = o && g.gm == 2 && s == 2 && hl_ >= 0 && hl_ <= 1 && d.OW % 2 == 0 && g.Wp % 4 == 0 && g.xoff == 0 &&
+                (g.o_patch % 4) == 0 && g.win == 0;
           } else if (g.vec) {
             const int wsrc = (g.gm == 2) ? d.OW : W;
             if (g.win) o = o && g.win == g.NT && g.Wp == g.NT + 8 && H == 1 && d.OH == 1 && k == 1 && s == 1 && pad == 0 && g.gm != 3;
@@ -1343,11 +1356,11 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
             o = o && g.xoff == 0 && g.win == 0;
           }
           if (g.gm == 1) {
-            const int rows_max = std::min(d.OH, (g.NT + d.OW - 2) / d.OW + 1);
+            const int rows_max = tile_rows(g.NT, d.OW, d.OH);
             o = o && g.M == d.K && g.N == d.OH * d.OW && g.Q == C * kk && g.QC == g.CC * kk &&
                 g.PR >= (rows_max - 1) * s + k && (g.win || (g.Wp >= W + 2 * pad && g.Wp >= (d.OW - 1) * s + k + g.xoff));
           } else if (g.gm == 2) {
-            const int rows_max = std::min(H, (g.NT + W - 2) / W + 1);
+            const int rows_max = tile_rows(g.NT, W, H);
             o = o && g.M == C && g.N == H * W && g.Q == d.K * kk && g.QC == g.CC * kk && g.PR >= rows_max + k - 1 &&
                 (g.win || g.Wp >= W + k - 1 + g.xoff) && pad <= k - 1;
           } else if (g.gm == 3) {
