@@ -39,6 +39,30 @@ typedef __attribute__((address_space(3))) v4f lv4;
 //   A block, GM 1 and 3: MT rows of the chunk's reduction range, row stride LDA
 //   A block, GM 2:       one segment of MT*k*k floats per output channel of the
 //                        chunk -- the layout the weights have in memory
+#ifndef PB_SCHED
+#define PB_SCHED 0
+#endif
+#if PB_SCHED == 0
+#define PB_SCHED_MID() __builtin_amdgcn_sched_barrier(0)
+#define PB_SCHED_END()
+#elif PB_SCHED == 1
+#define PB_SCHED_MID()
+#define PB_SCHED_END()
+#else
+#define PB_SCHED_MID()
+#define PB_SCHED_END() sched_interleave<G * NI, (GM == 2 ? 8 : 3)>()
+#endif
+// one MFMA, then up to three LDS reads and V other vector instructions, N times
+template <int N, int V>
+__device__ __forceinline__ void sched_interleave() {
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, V, 0);
+  }
+}
+
 template <int GM, int NI>
 __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lfloat* smem) {
   PB_TS(1);
@@ -610,13 +634,15 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
           for (; g + 2 <= ng; g += 2) {
             load_ab(I1(), true);
             load_oq(g + 2 < ng);
-            __builtin_amdgcn_sched_barrier(0);
+            PB_SCHED_MID();
             mfmas(I0());
+            PB_SCHED_END();
             __builtin_amdgcn_sched_barrier(0);
             load_ab(I0(), g + 2 < ng);
             load_oq(g + 3 < ng);
-            __builtin_amdgcn_sched_barrier(0);
+            PB_SCHED_MID();
             mfmas(I1());
+            PB_SCHED_END();
             __builtin_amdgcn_sched_barrier(0);
           }
           if (g < ng) mfmas(I0());   // odd number of groups: the last one is in buffer 0

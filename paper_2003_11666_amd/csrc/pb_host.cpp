@@ -661,6 +661,15 @@ void stream_apply(const pb_ctx* c, StepDesc& e) {
   e.ntiles = e.G * e.n;
 }
 
+// Networks tiled for latency: the GroupNorm statistics of a layer of four small groups
+// in one workgroup, a wavefront per group.
+void gn_stats_wave(StepDesc& d) {
+  const int64_t n = d.G > 0 ? (int64_t)(d.C / d.G) * d.H * d.W : 0;
+  if (g_tile_budget_us > 0 || d.G < 1 || d.G > BLK / 64 || d.C / d.G > 64 || (d.H * d.W) % 4 || n > 4096) return;
+  d.grain = 1;
+  d.ntiles = 1;
+}
+
 // One wavefront per channel for a K_GNB_REDUCE step over a small map.
 void wave_reduce(StepDesc& d) {
   // (a gradient routed back through a max-pool costs a window search per element: small maps only)
@@ -743,7 +752,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       d.n = a.in_elems(); d.n_stages = NS;
       d.dx = x_f;
       d.labels = c->labels_dev;
-      d.ntiles = cdiv(d.n, BLK);
+      d.ntiles = cdiv(d.n, 4 * BLK);
       if (c->bf16) d.flags |= F_BF16_OUT;
       out.push_back({0, d});
       ph = 1;
@@ -790,6 +799,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         if (a.pre_relu) d.flags |= F_PRE_RELU;
       }
       d.ntiles = a.G;
+      gn_stats_wave(d);
       out.push_back({ph++, d});
     }
     if (a.gap) {
@@ -885,6 +895,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       d.gamma = wf + a.o_gamma; d.beta = wf + a.o_beta;
       fwd_params(d, PF_GAMMA | PF_BETA);
       d.ntiles = a.G;
+      gn_stats_wave(d);
       out.push_back({ph++, d});
       StepDesc e = blank(K_POST_FWD, s, t_f);
       e.C = a.K; e.H = a.OH; e.W = a.OW; e.G = a.G;
@@ -1043,7 +1054,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         d.dy = dy_src; d.dx = skg_w;
         d.ntiles = cdiv(d.n, BLK);
         if (d.n % 4 == 0 && ref_vec4(c, d.dy) && ref_vec4(c, d.dx)) {
-          d.grain = STREAM_GRAIN;
+          d.grain = g_tile_budget_us > 0 ? STREAM_GRAIN : 2 * STREAM_GRAIN;   // fewer workgroups for a network tiled for latency
           d.ntiles = cdiv(d.n, d.grain);
         }
         out.push_back({pb, d});
@@ -1189,9 +1200,24 @@ void order_steps(std::vector<std::pair<int, StepDesc>>& tagged) {
     if (d.kind == K_GN_BWD) return (int64_t)d.C / std::max(1, d.G) * d.H * d.W / 32 + 1000;
     return 0;
   };
+  // Networks tiled for latency: a phase may have somewhat more workgroups than the chip
+  // holds at once (512: two per compute unit).  Workgroups are handed to the 32 shader
+  // engines round robin and in order, so workgroup 512 + j waits for a slot in the engine
+  // that took workgroups j, j + 32, ... (seen in per-workgroup start and end times).  The
+  // shortest steps (copies, the sample, statistics) therefore go to the front, shortest
+  // first, where they free a slot early in the engines the surplus workgroups will be
+  // sent to; the surplus itself is the cheapest GEMM tiles, the longer of them first.
+  auto rank = [](const StepDesc& d) {
+    if (g_tile_budget_us > 0) return d.kind == K_HEAD ? 0 : 1;
+    if (d.kind == K_HEAD) return 1;
+    return (d.kind == K_GEMM || d.kind == K_GN_BWD) ? 2 : 0;
+  };
   std::stable_sort(tagged.begin(), tagged.end(),
                    [&](const std::pair<int, StepDesc>& x, const std::pair<int, StepDesc>& y) {
                      if (x.first != y.first) return x.first < y.first;
+                     const int rx = rank(x.second), ry = rank(y.second);
+                     if (rx != ry) return rx < ry;
+                     if (rx == 0 && g_tile_budget_us <= 0) return step_cost(x.second) < step_cost(y.second);
                      return step_cost(x.second) > step_cost(y.second);
                    });
 }
@@ -1226,7 +1252,12 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
     bool ok = d.ntiles > 0;
     switch (d.kind) {
       case K_GN_STATS:
-        ok = ok && d.G > 0 && d.C % d.G == 0 && d.ntiles == d.G && ref_ok(d.x, in) && ref_ok(d.st, stn) &&
+        if (d.grain == 1)   // one wavefront per group, one workgroup
+          ok = ok && d.G > 0 && d.G <= BLK / 64 && d.C % d.G == 0 && d.ntiles == 1 && d.C / d.G <= 64 && (d.H * d.W) % 4 == 0 &&
+               d.C / d.G * d.H * d.W <= 4096;
+        else
+          ok = ok && d.ntiles == d.G;
+        ok = ok && d.G > 0 && d.C % d.G == 0 && ref_ok(d.x, in) && ref_ok(d.st, stn) &&
              ptr_ok(d.gamma, d.C) && ptr_ok(d.beta, d.C) && (!d.y.base || ref_ok(d.y, in));
         break;
       case K_GAP_FWD:
@@ -1300,7 +1331,7 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
         else ok = ok && (int64_t)d.ntiles * BLK >= d.n;
         break;
       case K_INGEST:
-        ok = ok && (int64_t)d.ntiles * BLK >= d.n && ref_ok(d.dx, d.n) && ptr_ok((const float*)d.labels, d.n_stages);
+        ok = ok && (int64_t)d.ntiles * 4 * BLK >= d.n && ref_ok(d.dx, d.n) && ptr_ok((const float*)d.labels, d.n_stages);
         break;
       case K_UPDATE:
         ok = ok && d.n > 0 && d.n % 4 == 0 && d.ntiles == cdiv(d.n, UPD_TILE) && ptr_ok(d.w, d.n) && ptr_ok(d.v, d.n) &&

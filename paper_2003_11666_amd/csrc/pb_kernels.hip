@@ -35,7 +35,11 @@ __device__ long long pb_ts_out[16384 * 100];
 __device__ int pb_ts_n;
 __device__ int pb_ts_tick;
 __device__ int pb_ts_grid;   // 0: record every phase, else only the launch with this many workgroups
+#if PB_TIMING == 2   /* light form: start and end of a workgroup only, no atomics */
+#define PB_TS(i) do { if ((i) == 0 || (i) == 11) { if ((threadIdx.x & 63) == 0) ts_sh[threadIdx.x >> 6][i] = (long long)__builtin_amdgcn_s_memrealtime(); } } while (0)
+#else
 #define PB_TS(i) do { if ((threadIdx.x & 63) == 0) ts_sh[threadIdx.x >> 6][i] = (long long)__builtin_amdgcn_s_memrealtime(); } while (0)
+#endif
 #else
 #define PB_TS(i)
 #endif
@@ -215,6 +219,79 @@ __device__ __forceinline__ void step_gn_stats(const LDesc& d, int tile, int t, l
       float v = fmaf(sc, xp[i], fmaf(-mean, sc, GP(d.beta)[ch]));
       if (rl) v = fmaxf(v, 0.f);
       yo[i] = v;
+    }
+  }
+}
+
+// The same with one wavefront per group and all four groups of the layer in one
+// workgroup (grain = 1; groups of at most 4096 elements, at most 64 channels per
+// group): sums across lanes only, no barrier, and a quarter of the workgroups.
+// LDS: per wavefront sc[64] | sh[64].
+constexpr int GNS_WAVE_MAX_N = 4096;
+__device__ __forceinline__ void step_gn_stats_wave(const LDesc& d, int t, lfloat* smem) {
+  const int lane = threadIdx.x & 63, g = UNI(threadIdx.x >> 6);
+  const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W);
+  const int cpg = UNI(fdiv(C, frcp(G))), n = cpg * HW;
+  if (g >= G) return;
+  const gfloat* xp = at(d.x, t) + (size_t)g * n;
+  gfloat* st = at(d.st, t);
+  const bool rl = UNI(d.flags) & F_PRE_RELU;
+  constexpr int WU = GNS_WAVE_MAX_N / (4 * 64);
+  v4f xr[WU];
+#pragma unroll
+  for (int u = 0; u < WU; ++u) {
+    const int i = (lane + u * 64) * 4;
+    xr[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+    if (u * 256 < n) {
+      if (i < n) xr[u] = *(const gv4*)(xp + i);
+    }
+  }
+  float gam = 0.f, bet = 0.f;
+  if (lane < cpg) { gam = GP(d.gamma)[g * cpg + lane]; bet = GP(d.beta)[g * cpg + lane]; }
+  float s = 0.f;
+#pragma unroll
+  for (int u = 0; u < WU; ++u) s += (xr[u][0] + xr[u][1]) + (xr[u][2] + xr[u][3]);
+  const float mean = wave_sum(s) / (float)n;
+  float q = 0.f;
+#pragma unroll
+  for (int u = 0; u < WU; ++u)
+    if ((lane + u * 64) * 4 < n) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { const float dl = xr[u][e] - mean; q = fmaf(dl, dl, q); }
+    }
+  const float var = wave_sum(q) / (float)n;
+  const float rstd = 1.0f / sqrtf(var + GN_EPS);
+  if (lane == 0) { st[g] = mean; st[G + g] = rstd; }
+  lfloat* sc_l = smem + g * 128;
+  lfloat* sh_l = sc_l + 64;
+  if (lane < cpg) {
+    const int ch = g * cpg + lane;
+    const float sc = gam * rstd, sh = fmaf(-mean, sc, bet);
+    st[2 * G + ch] = sc;
+    st[2 * G + C + ch] = sh;
+    sc_l[lane] = sc; sh_l[lane] = sh;
+  }
+  if (!d.y.base) return;
+  // (LDS operations of one wavefront complete in order: the values are there)
+  __builtin_amdgcn_wave_barrier();
+  gfloat* yo = at(d.y, t) + (size_t)g * n;
+  const float ihw = frcp(HW);
+#pragma unroll
+  for (int u = 0; u < WU; ++u) {
+    const int i = (lane + u * 64) * 4;
+    if (u * 256 < n) {
+      if (i < n) {
+        const int c = fdiv(i, ihw);   // H*W is a multiple of 4: the four elements share a channel
+        const float sc = sc_l[c], sh = sh_l[c];
+        v4f o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float v = fmaf(sc, xr[u][e], sh);
+          if (rl) v = fmaxf(v, 0.f);
+          o[e] = v;
+        }
+        *(gv4*)(yo + i) = o;
+      }
     }
   }
 }
@@ -672,16 +749,20 @@ __device__ __forceinline__ void step_gn_bwd(const LDesc& d, int tile, int t, boo
   }
   if (tid < cpg) { cs[tid] = sc_c; cs[cpg + tid] = sh_c; }
   __syncthreads();
-  // ---- mask by the ReLU, per-slot partial sums of du*xh and du
+  // ---- mask by the ReLU, per-slot partial sums of du*xh and du.  When a channel is a
+  // whole number of rows of 16 slots (H*W a multiple of 64) the 16 lanes of a row add
+  // their partial sums up across lanes first and LDS holds one pair per row.
+  const bool rows16 = (HW4 & 15) == 0;
+  const int per_c = rows16 ? HW4 >> 4 : HW4;          // partial sums per channel in LDS
 #pragma unroll
   for (int u = 0; u < GU; ++u)
     if (u * BLK < ns) {
       const int sl = tid + u * BLK;
+      float sg = 0.f, sb = 0.f;
       if (sl < ns) {
         const int c = fdiv(sl, ihw4);
         const float sc = cs[c], sh = cs[cpg + c];
         const float dpool = gapd ? du[u][0] / (float)HW : 0.f;   // gradient of every element under an average pool
-        float sg = 0.f, sb = 0.f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           float dv = gapd ? dpool : du[u][e];
@@ -690,6 +771,11 @@ __device__ __forceinline__ void step_gn_bwd(const LDesc& d, int tile, int t, boo
           sg = fmaf(dv, (xr[u][e] - mean) * rstd, sg);
           sb += dv;
         }
+      }
+      if (rows16) {
+        sg = row_sum(sg); sb = row_sum(sb);
+        if (sl < ns && (tid & 15) == 0) { psum[sl >> 4] = sg; psum2[sl >> 4] = sb; }
+      } else if (sl < ns) {
         psum[sl] = sg; psum2[sl] = sb;
       }
     }
@@ -697,7 +783,7 @@ __device__ __forceinline__ void step_gn_bwd(const LDesc& d, int tile, int t, boo
   for (int j = tid; j < 4 * cpg; j += BLK) {          // lanes 4c..4c+3 share channel c
     const int c = j >> 2, p = j & 3;
     float sg = 0.f, sb = 0.f;
-    for (int i = p; i < HW4; i += 4) { sg += psum[c * HW4 + i]; sb += psum2[c * HW4 + i]; }
+    for (int i = p; i < per_c; i += 4) { sg += psum[c * per_c + i]; sb += psum2[c * per_c + i]; }
     sg += dpp_src<0xB1, 0xF>(sg); sb += dpp_src<0xB1, 0xF>(sb);
     sg += dpp_src<0x4E, 0xF>(sg); sb += dpp_src<0x4E, 0xF>(sb);
     if (p == 0) {
@@ -863,9 +949,15 @@ __device__ __forceinline__ void step_ingest(const LDesc& d, int tile, int t, con
     lab = ((const gint*)G->pool_labels)[item];
   }
   gfloat* dst = at(d.dx, t);
-  const int i = tile * BLK + threadIdx.x;
-  if (i < d.n) dst[i] = rbf_if(d.flags & F_BF16_OUT, src[i]);
-  if (i == 0) ((gint*)d.labels)[t % d.n_stages] = lab;
+  constexpr int U = 4;   // elements per thread
+  const int i0 = tile * U * BLK + threadIdx.x;
+  float v[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) v[u] = (i0 + u * BLK < d.n) ? src[i0 + u * BLK] : 0.f;
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (i0 + u * BLK < d.n) dst[i0 + u * BLK] = rbf_if(d.flags & F_BF16_OUT, v[u]);
+  if (i0 == 0) ((gint*)d.labels)[t % d.n_stages] = lab;
 }
 
 // Fused Spike-Compensated momentum update with Linear Weight Prediction of one
@@ -1661,7 +1753,9 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
   const bool live = t >= UNI(d.first_tick);
   if (!live && !(UNI(d.flags) & F_ALWAYS)) return;
   switch (UNI(d.kind)) {
-    case K_GN_STATS: step_gn_stats(d, tile, t, red, smem); break;
+    case K_GN_STATS:
+      if (UNI(d.grain) == 1) step_gn_stats_wave(d, t, smem); else step_gn_stats(d, tile, t, red, smem);
+      break;
     case K_GAP_FWD: step_gap_fwd(d, tile, t, red); break;
     case K_CONV_FWD: step_conv_fwd(d, tile, t); break;
     case K_POST_FWD: step_post_fwd(d, tile, t); break;
@@ -1681,6 +1775,22 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
   }
 #ifdef PB_TIMING
   PB_TS(11);
+#if PB_TIMING == 2
+  if (t == pb_ts_tick && (threadIdx.x & 63) == 0) {
+    // slot = workgroup index; launches of another grid size than pb_ts_grid go to the upper half
+    const int slot = (int)blockIdx.x + ((int)gridDim.x == pb_ts_grid ? 0 : 8192);
+    const int w = threadIdx.x >> 6;
+    if (slot < 16384) {
+      pb_ts_out[slot * 100 + 4 + w * 24 + 0] = ts_sh[w][0];
+      pb_ts_out[slot * 100 + 4 + w * 24 + 11] = ts_sh[w][11];
+      if (w == 0) {
+        pb_ts_out[slot * 100 + 0] = d.kind; pb_ts_out[slot * 100 + 1] = d.stage;
+        pb_ts_out[slot * 100 + 2] = d.g.gm; pb_ts_out[slot * 100 + 3] = tile;
+      }
+    }
+  }
+  return;
+#endif
   __syncthreads();
   if (t == pb_ts_tick && (pb_ts_grid == 0 || pb_ts_grid == (int)gridDim.x)) {
     __shared__ int slot_;
@@ -1810,6 +1920,9 @@ extern "C" int pb_debug_dump(long long* host, int max_recs) {
   int n = 0;
   hipDeviceSynchronize();
   hipMemcpyFromSymbol(&n, HIP_SYMBOL(pb::pb_ts_n), sizeof(int));
+#if PB_TIMING == 2
+  n = 16384;
+#endif
   if (n > max_recs) n = max_recs;
   if (n > 16384) n = 16384;
   hipMemcpyFromSymbol(host, HIP_SYMBOL(pb::pb_ts_out), (size_t)n * 100 * sizeof(long long));
