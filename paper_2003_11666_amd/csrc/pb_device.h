@@ -69,6 +69,9 @@ struct GemmCfg {
   int32_t nsub;            // consecutive column tiles one workgroup runs (tiles_n counts groups of nsub)
   int32_t win;             // > 0: 1x1 layer seen as a plain matrix product (map flattened to one row of H*W pixels):
                            // the patch holds only the win = NT columns of the current column tile
+  int32_t parts;           // backward weights: the reduction is split over `parts` groups of workgroups, each taking
+  int32_t cpp;             // cpp consecutive chunks and writing a partial gradient of its own (summed by the update step);
+  int32_t tpp;             // tiles per part (tiles = parts * tpp)
 };
 
 // Pointer fields of a step that point into slot 0 of the stage's ring of predicted-weight versions;
@@ -109,6 +112,8 @@ struct StepDesc {
   float fa, fb, flrT, flr, fm;   // K_UPDATE: SC coefficients a, b, lr*T, lr, momentum
   int32_t pmask;            // which pointer fields address the stage's ring of predicted weights (PF_* bits)
   int32_t pdepth, plag, pstride;   // that ring: slots, lag of the slot this step uses, floats per slot
+  int32_t gparts, gpstride; // partial weight gradients of the stage: their number, floats between two of them
+                            // (K_GEMM backward weights writes one of them, K_UPDATE sums them in order)
   int32_t grain;            // > 0: streaming form of an elementwise step, floats per workgroup (K_COPY, K_GNB_APPLY);
                             // K_GNB_REDUCE: 1 = one wavefront per channel
   GemmCfg g;     // main operand set of a K_GEMM step

@@ -78,6 +78,13 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
   auto lg = [](int x) { return x == 1 ? 0 : (x == 2 ? 1 : 2); };
   const int wk_id = wv & (wk - 1), wn_id = (wv >> lg(wk)) & (wn - 1), wm_id = wv >> (lg(wk) + lg(wn));
   const int tiles_n = UNI(d.g.tiles_n);
+  // backward weights: part of the reduction (a range of chunks) this workgroup takes
+  int qpart = 0;
+  if (GM == 3) {
+    const int tpp = UNI(d.g.tpp);
+    qpart = UNI(fdiv(tile, frcp(tpp)));
+    tile -= qpart * tpp;
+  }
   const int tm = UNI(fdiv(tile, frcp(tiles_n))), tn = tile - tm * tiles_n;
   const int MT = UNI(d.g.MT), NT = UNI(d.g.NT);
   // a workgroup runs nsub consecutive column tiles one after the other: the
@@ -164,7 +171,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     if (wk_id != 0) return;
     // ---- epilogue: lane holds C[i = 4*(lane/16) + r][j = lane%16]
     const int M = UNI(d.g.M), N = UNI(d.g.N);
-    gfloat* out = (GM == 1) ? at(d.y, te) : (GM == 2) ? at(d.dx, te) : GP(d.gw);
+    gfloat* out = (GM == 1) ? at(d.y, te) : (GM == 2) ? at(d.dx, te) : GP(d.gw) + (size_t)qpart * (size_t)UNI(d.gpstride);
     const int zero = te - t;                              // 0, opaque to the compiler (see above)
     const int mrow = m0 + wm_id * 16 + 4 * kq + zero;
     const int ncol = n0s + wn_id * ni * 16 + (lane & 15) + zero;
@@ -241,6 +248,10 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     const int HW = gH * gW, P = gOH * gOW;
     const int QC = UNI(g.QC), QCpad = UNI(g.QCpad), CC = UNI(g.CC), M = UNI(g.M), N = UNI(g.N), Q = UNI(g.Q);
     const int n_chunks = UNI(g.n_chunks), rows_c = UNI(g.rows_c), LDA = UNI(g.LDA);
+    // chunks this workgroup contracts (all of them except for a split backward-weights step)
+    const int ch0 = (GM == 3) ? qpart * UNI(g.cpp) : 0;
+    const int ch_end = (GM == 3 && ch0 + UNI(g.cpp) < n_chunks) ? ch0 + UNI(g.cpp) : n_chunks;
+    const int nch = ch_end - ch0;
     const int vec = UNI(g.vec), avec = UNI(g.avec);
     const int border = gk - 1 - gpad;
 
@@ -379,10 +390,10 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     int tv[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) tv[u] = (tid + u * BLK < QCpad) ? tq[tid + u * BLK] : 0;
-    a_issue(0, tid);
+    a_issue(ch0, tid);
     if (!op) PB_TS(10);
     tile_geometry(n0);
-    if (vec == 1) p_issue(0, tid, c_lo, tile_row0, col0);
+    if (vec == 1) p_issue(ch0, tid, c_lo, tile_row0, col0);
 
     for (int sub = 0; sub < nsub; ++sub) {
     const int n0s = n0 + sub * NT;
@@ -395,12 +406,12 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     __syncthreads();   // LDS may still be in use by the previous operand set / column tile
     if (!op && !sub) PB_TS(9);
 
-    for (int ch = 0; ch < n_chunks; ++ch) {
+    for (int ch = ch0; ch < ch_end; ++ch) {
       const int q0 = ch * QC;
       const int qc_eff = (Q - q0 < QC) ? Q - q0 : QC;       // valid reduction entries in this chunk
       const int qc4 = (qc_eff + 3) & ~3;
-      if (ch) __syncthreads();                              // the previous chunk has been contracted
-      if (ch == 1 && !op) PB_TS(12);
+      if (ch != ch0) __syncthreads();                       // the previous chunk has been contracted
+      if (ch == ch0 + 1 && !op) PB_TS(12);
       int chan0, row0;
       p_origin(ch, c_lo, tile_row0, chan0, row0);
       if (vec == 1) {
@@ -523,35 +534,35 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
           }
         }
       }
-      if (!ch && !op) PB_TS(3);
-      if (ch == 1 && !op) PB_TS(14);
+      if (ch == ch0 && !op) PB_TS(3);
+      if (ch == ch0 + 1 && !op) PB_TS(14);
       // ---- park the offset table and the A block
-      if (ch == 0 && sub == 0) {
+      if (ch == ch0 && sub == 0) {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
           if (tid + u * BLK < QCpad) offq[tid + u * BLK] = tv[u];
         for (int i = tid + 4 * BLK; i < QCpad; i += BLK) offq[i] = tq[i];
       }
-      if (sub == 0 || n_chunks > 1) {   // a single chunk's A block serves every column tile
+      if (sub == 0 || nch > 1) {   // a single chunk's A block serves every column tile
         a_commit(ch, tid);
         const int a_slots = a_par(ch).slots;
         for (int s0 = tid + AU * BLK; s0 < a_slots; s0 += AU * BLK) { a_issue(ch, s0); a_commit(ch, s0); }
       }
-      if (!ch && !op) PB_TS(4);
-      if (ch == 1 && !op) PB_TS(15);
+      if (ch == ch0 && !op) PB_TS(4);
+      if (ch == ch0 + 1 && !op) PB_TS(15);
       __syncthreads();
-      if (!ch && !op) PB_TS(5);
-      if (ch == 1 && !op) PB_TS(16);
+      if (ch == ch0 && !op) PB_TS(5);
+      if (ch == ch0 + 1 && !op) PB_TS(16);
       // ---- requests of the next chunk (or of the first chunk of the next column
       // tile): in flight while this one is contracted
-      if (ch + 1 < n_chunks) {
+      if (ch + 1 < ch_end) {
         a_issue(ch + 1, tid);
         if (vec == 1) p_issue(ch + 1, tid, c_lo, tile_row0, col0);
       } else if (more) {
-        if (n_chunks > 1) a_issue(0, tid);
+        if (nch > 1) a_issue(ch0, tid);
         if (vec == 1) {
           const int nn = n0s + NT;
-          p_issue(0, tid, GM == 3 ? UNI(fdiv(nn, frcp(kk))) : 0,
+          p_issue(ch0, tid, GM == 3 ? UNI(fdiv(nn, frcp(kk))) : 0,
                   GM == 1 ? UNI(fdiv(nn, frcp(gOW))) : (GM == 2 ? UNI(fdiv(nn, frcp(gW))) : 0), win ? nn : 0);
         }
         tn_load(n0s + NT);
@@ -657,8 +668,8 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
             acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, patch[oq + offn[j]], acc[j], 0, 0, 0);
         }
       }
-      if (!ch && !op) PB_TS(6);
-      if (ch == 1 && !op) PB_TS(17);
+      if (ch == ch0 && !op) PB_TS(6);
+      if (ch == ch0 + 1 && !op) PB_TS(17);
     }
     if (nops == 1) {
       finish(n0s);

@@ -229,7 +229,9 @@ struct StageBufs {
   int64_t aring = -1;   // normalised + rectified stage input (pre-norm conv stages)
   int64_t xring = -1, prest = -1, pooled = -1, zring = -1, postst = -1, gradbox = -1, skg = -1,
           da = -1, dz = -1, part = -1, logits = -1, dlogits = -1,
-          projy = -1;   // output of the skip projection of the tick's forward sample (computed one phase ahead of the sum)
+          projy = -1,   // output of the skip projection of the tick's forward sample (computed one phase ahead of the sum)
+          gparts = -1;  // GRAD_PARTS copies of the stage's gradient block, the first one complete, the others partial
+                        // weight gradients of a backward-weights GEMM whose reduction is split over workgroups
   int st_stride = 0;
 };
 
@@ -241,6 +243,11 @@ struct Layout {
   int64_t staging = 0, labels = 0, loss = 0, globals = 0, zero = 0;
   int64_t total = 0;
 };
+
+// A convolution over a large map with few weights has a weight gradient that is a long
+// reduction with few output tiles: such a stage gets room for partial gradients.
+constexpr int GRAD_PARTS = 16;
+bool split_candidate(const Stage& a) { return a.is_conv && (int64_t)a.OH * a.OW >= 256 && a.padded <= 16384; }
 
 int st_stride_of(const Stage& s) { return (2 * s.G + 2 * s.gnC() + 63) / 64 * 64; }
 
@@ -280,6 +287,7 @@ void plan_arena(const std::vector<Stage>& st, bool stash, int loss_cap, Layout& 
     if (s < S - 1) b.gradbox = pl.alloc(2 * (int64_t)a.out_elems());
     if (a.tap_dist) b.skg = pl.alloc((int64_t)(a.tap_dist + 1) * a.in_elems());
     if (a.proj) b.projy = pl.alloc(a.out_elems());
+    if (split_candidate(a)) b.gparts = pl.alloc((int64_t)GRAD_PARTS * a.padded);
     if (a.ce) { b.logits = pl.alloc(a.K); b.dlogits = pl.alloc(a.K); }
   }
   L.staging = pl.alloc(st[0].in_elems());
@@ -397,7 +405,8 @@ static int tile_rows(int NT, int rowlen, int nrows) {
   return std::min(nrows, r);
 }
 
-bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int s, int pad, bool allow_vec, bool fine) {
+bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int s, int pad, bool allow_vec, bool fine,
+              int rows_cap = 0) {
   const int mode = g.gm, kk = k * k;
   g.MT = 16 * g.wm; g.NT = 16 * g.ni * g.wn;
   if (g.nsub < 1 || g.wk != 1) g.nsub = 1;   // the split of the reduction reuses the A block's LDS
@@ -460,13 +469,15 @@ bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int
     auto pr = [&](int r) { return (r - 1) * s + k; };
     // one chunk holding every output row, else the largest row count whose
     // pixel count is a multiple of 4 (chunks in the middle must not be padded)
+    // (rows_cap > 0: at most that many rows per chunk, for a reduction split over workgroups)
     int rows = 0;
-    if (fits(OH * OW, g.CC, pr(OH), g.Wp)) {
+    const int cap = rows_cap > 0 ? std::min(OH, rows_cap) : OH;
+    if (cap == OH && fits(OH * OW, g.CC, pr(OH), g.Wp)) {
       rows = OH;
     } else {
       int step = 1;
       while ((step * OW) % 4) ++step;
-      for (int r = step; r < OH; r += step) {
+      for (int r = step; r < OH && r <= std::max(cap, step); r += step) {
         if (!fits(r * OW, g.CC, pr(r), g.Wp)) break;
         rows = r;
       }
@@ -475,6 +486,7 @@ bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int
     g.rows_c = rows; g.QC = rows * OW; g.PR = pr(rows); g.n_chunks = cdiv(OH, rows);
   }
   g.QCpad = (g.QC + 15) / 16 * 16;
+  g.parts = 1; g.cpp = g.n_chunks; g.tpp = g.tiles;
   // 16-byte fetches of the A block: every segment starts on a 16-byte boundary and
   // has a length that is a multiple of 4 (the caller withdraws this if the operand's
   // address does not allow it).  Forward / backward weights: segments are rows of the
@@ -521,7 +533,8 @@ double est_tile_us(const GemmCfg& g, int k) {
 //   estimated tile duration stays within the budget, the one with the least total
 //   work (tiles x duration); if none does, the one with the shortest tile.
 bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int s, int pad,
-               const GemmCfg* like, GemmCfg* out, bool allow_vec = false, int max_sub = 16, bool flat = false) {
+               const GemmCfg* like, GemmCfg* out, bool allow_vec = false, int max_sub = 16, bool flat = false,
+               int max_parts = 1) {
   const int target = (mode == 1) ? g_tile_target : g_tile_target_bwd;
   GemmCfg g;
   memset(&g, 0, sizeof g);
@@ -532,6 +545,30 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
   else if (mode == 2) { g.M = C; g.N = HWi; g.Q = K * kk; }
   else { g.M = K; g.N = C * kk; g.Q = P; }
   const int mt = cdiv(g.M, 16), n16 = cdiv(g.N, 16);
+  if (!like && g_tile_budget_us <= 0 && mode == 3 && max_parts > 1 && g.Q >= 256) {
+    // Latency policy, weight gradient over a large map: split the reduction (the output
+    // rows) over 4 or 8 groups of workgroups, each small enough that one burst of requests
+    // (about 8 per thread) brings in its rows of dZ and of the input; every group covers
+    // all columns with as few tiles as the wave arrangement allows.
+    GemmCfg t = g;
+    t.wm = mt >= 4 ? 4 : mt >= 2 ? 2 : 1;
+    const int rest = 4 / t.wm;
+    t.wn = std::min(rest, pow2_floor(n16)); t.wk = rest / t.wn;
+    t.ni = std::min(4, cdiv(n16, t.wn));
+    if (t.ni == 3) t.ni = 4;
+    const int NT = 16 * t.ni * t.wn, CC = std::min(C, (NT + kk - 2) / kk + 1), Wp = W + 8;
+    int rows = OH;
+    while (rows > 1 && cdiv(OH, rows) < std::min(max_parts, 8) &&
+           (int64_t)16 * t.wm * rows * OW + (int64_t)CC * ((rows - 1) * s + k) * Wp > 8192) rows = (rows + 1) / 2;
+    if (cdiv(OH, rows) >= 4 && fit_gemm(t, C, H, W, K, OH, OW, k, s, pad, allow_vec, false, rows) && t.n_chunks >= 4) {
+      t.cpp = cdiv(t.n_chunks, std::min(max_parts, t.n_chunks));
+      t.parts = cdiv(t.n_chunks, t.cpp);
+      t.tpp = t.tiles;
+      t.tiles = t.parts * t.tpp;
+      *out = t;
+      return true;
+    }
+  }
   if (like) {
     g.wm = like->wm; g.wn = like->wn; g.wk = like->wk; g.ni = like->ni;
   } else if (g_tile_budget_us > 0) {
@@ -733,7 +770,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       if (!c->stash) return;
       d.pmask = mask; d.pdepth = wdepth; d.plag = a.De; d.pstride = (int)a.padded;
     };
-    float* gr = c->f(L.g + a.off);
+    float* gr = c->f(b.gparts >= 0 ? b.gparts : L.g + a.off);
     const bool seq = c->sequential;
     const int t_f = seq ? 0 : s, t_b = seq ? 0 : 2 * (S - 1) - s;
     const int ML = seq ? 0 : -1;                       // lag of the mailbox slot a producer writes (next tick's, or this tick's)
@@ -977,7 +1014,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       d.ntiles = bwd_w_tiles(a.K, a.C, a.k, a.OH * a.OW, a.has_bias);
       GemmCfg g;
       if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g,
-                                          !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)))) {
+                                          !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)), 16, false, b.gparts >= 0 ? GRAD_PARTS : 1)) {
         if (a.has_bias) {
           StepDesc e = blank(K_BIAS_GRAD, s, t_b);
           e.K = a.K; e.OH = a.OH; e.OW = a.OW; e.dy = dz_src; e.gb = gr + a.o_b;
@@ -985,6 +1022,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
           out.push_back({pb, e});
         }
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles; d.flags &= ~F_BIAS;
+        d.gparts = g.parts; d.gpstride = (int)a.padded;
         gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, &d.tq, &d.tn);
       }
       out.push_back({pb, d});
@@ -1028,8 +1066,10 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         d.gw = gr + a.o_wp;
         d.ntiles = bwd_w_tiles(a.K, a.sC, 1, a.OH * a.OW, false);
         GemmCfg g;
-        if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, 1, d.stride, 0, nullptr, &g, true)) {
+        if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, 1, d.stride, 0, nullptr, &g, true, 16, false,
+                                            b.gparts >= 0 ? GRAD_PARTS : 1)) {
           d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
+          d.gparts = g.parts; d.gpstride = (int)a.padded;
           gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, 1, d.stride, &d.tq, &d.tn);
         }
         out.push_back({pb, d});
@@ -1149,6 +1189,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     const Stage& a = c->st[s];
     int last_grad_phase = 0;
     bool gn_fused = false;
+    int gparts = 1;   // partial weight gradients the stage's backward-weights steps leave
     for (auto& pr : out) {
       const StepDesc& e = pr.second;
       if (e.stage != s) continue;
@@ -1156,10 +1197,13 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       const bool writes_grad = (e.kind == K_GEMM && e.g.gm == 3) || e.kind == K_CONV_BWD_W || e.kind == K_BIAS_GRAD ||
                                e.kind == K_GNB_REDUCE || e.kind == K_GN_BWD || e.kind == K_HEAD;
       if (writes_grad) last_grad_phase = std::max(last_grad_phase, pr.first);
+      if (e.kind == K_GEMM && e.g.gm == 3) gparts = std::max(gparts, e.g.parts);
     }
     StepDesc d = blank(K_UPDATE, s, 0);
     set_update_coeffs(c, a, &d);
-    d.w = c->f(L.w + a.off); d.v = c->f(L.v + a.off); d.gw = c->f(L.g + a.off);
+    d.w = c->f(L.w + a.off); d.v = c->f(L.v + a.off);
+    d.gw = c->f(L.sb[s].gparts >= 0 ? L.sb[s].gparts : L.g + a.off);
+    d.gparts = gparts; d.gpstride = (int)a.padded;
     d.wp = d.w; d.b = d.v;                             // master weights and velocity in place
     d.what = c->f(L.what[s]);
     d.pmask = PF_WHAT; d.pdepth = what_depth(a, c->stash); d.plag = -1; d.pstride = (int)a.padded;
@@ -1337,6 +1381,8 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
         ok = ok && d.n > 0 && d.n % 4 == 0 && d.ntiles == cdiv(d.n, UPD_TILE) && ptr_ok(d.w, d.n) && ptr_ok(d.v, d.n) &&
              ptr_ok(d.gw, d.n) && ptr_ok(d.wp, d.n) && ptr_ok(d.b, d.n) && (!d.what || ptr_ok(d.what, d.n)) &&
              d.what != nullptr;
+        if (d.gparts > 1)
+          ok = ok && d.gpstride >= d.n && d.gpstride % 4 == 0 && ptr_ok(d.gw, (int64_t)(d.gparts - 1) * d.gpstride + d.n);
         break;
       case K_HEAD: {
         const int64_t cv = (d.flags & F_DU_GAP) ? d.C : in;
@@ -1359,7 +1405,9 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
           const int kk = k * k;
           bool o = g.wm * g.wn * g.wk == 4 && (g.ni == 1 || g.ni == 2 || g.ni == 4) && g.MT == 16 * g.wm && g.NT == 16 * g.ni * g.wn &&
                    g.nsub >= 1 && (g.nsub == 1 || (g.wk == 1 && !(d.flags & F_PROJ && g.gm == 1))) && g.tiles_n == cdiv(cdiv(g.N, g.NT), g.nsub) &&
-                   g.tiles == cdiv(g.M, g.MT) * g.tiles_n && g.QCpad % 16 == 0 &&
+                   g.parts >= 1 && g.cpp >= 1 && g.tpp == cdiv(g.M, g.MT) * g.tiles_n && g.tiles == g.parts * g.tpp &&
+                   (int64_t)g.parts * g.cpp >= g.n_chunks && (int64_t)(g.parts - 1) * g.cpp < g.n_chunks &&
+                   (g.parts == 1 || (g.gm == 3 && g.nsub == 1)) && g.QCpad % 16 == 0 &&
                    g.QCpad >= g.QC && g.o_offq >= 0 && g.o_A >= g.o_offq + g.QCpad && g.o_A % 4 == 0 && g.o_patch % 4 == 0 &&
                    (int64_t)g.o_patch + ((int64_t)g.CC * g.PR * g.Wp + 3) / 4 * 4 <= LDS_FLOATS && LDS_FLOATS >= 4096 &&
                    (int64_t)g.n_chunks * g.QC >= g.Q;
@@ -1425,6 +1473,10 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
         } else {
           ok = ok && ref_ok(d.x, in) && ref_ok(d.dy, outn) && ptr_ok(d.gw, wn_) &&
                (!(d.flags & F_PRE_AFFINE) || ref_ok(d.st, stn)) && !(d.flags & F_BIAS);
+          // a split reduction writes partial gradients gpstride floats apart
+          if (d.g.parts > 1)
+            ok = ok && d.gparts == d.g.parts && d.gpstride >= wn_ && d.gpstride % 4 == 0 &&
+                 ptr_ok(d.gw, (int64_t)(d.g.parts - 1) * d.gpstride + wn_);
         }
         break;
       }
@@ -1589,8 +1641,8 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
     o += line;
     if (d.kind == K_GEMM) {
       const GemmCfg& g = d.g;
-      snprintf(line, sizeof line, " | gm%d M%d N%d Q%d waves %dx%dx%d ni%d tile %dx%d x%d chunks %d QC%d CC%d PR%d Wp%d lds %d",
-               g.gm, g.M, g.N, g.Q, g.wm, g.wn, g.wk, g.ni, g.MT, g.NT, g.nsub, g.n_chunks, g.QC, g.CC, g.PR, g.Wp,
+      snprintf(line, sizeof line, " | gm%d M%d N%d Q%d waves %dx%dx%d ni%d tile %dx%d x%d chunks %d/%d QC%d CC%d PR%d Wp%d lds %d",
+               g.gm, g.M, g.N, g.Q, g.wm, g.wn, g.wk, g.ni, g.MT, g.NT, g.nsub, g.n_chunks, g.parts, g.QC, g.CC, g.PR, g.Wp,
                g.o_patch + g.CC * g.PR * g.Wp);
       o += line;
     }

@@ -986,6 +986,24 @@ __device__ __forceinline__ void step_update(const LDesc& d, int tile) {
     const int i = i0 + u * BLK;
     if (i < n4) { gv[u] = gp[i]; vv[u] = vp[i]; wv[u] = wp[i]; }
   }
+  // a stage whose weight gradient was computed in parts (split reduction of the
+  // backward-weights GEMM): add the other parts, in order
+  const int gparts = UNI(d.gparts);
+  if (gparts > 1) {
+    const int ps4 = UNI(d.gpstride) >> 2;
+    for (int p = 1; p < gparts; ++p) {
+      v4f pv[UU];
+#pragma unroll
+      for (int u = 0; u < UU; ++u) {
+        const int i = i0 + u * BLK;
+        pv[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+        if (i < n4) pv[u] = gp[(size_t)p * ps4 + i];
+      }
+#pragma unroll
+      for (int u = 0; u < UU; ++u)
+        if (i0 + u * BLK < n4) gv[u] += pv[u];
+    }
+  }
   gv4* vo = (gv4*)(float*)d.b;
   gv4* wo = (gv4*)(float*)d.wp;
   gv4* ho = (gv4*)d.what;
