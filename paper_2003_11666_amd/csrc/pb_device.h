@@ -94,7 +94,8 @@ enum StepFlags : int32_t {
   F_UPD_GN = 4096,    // K_GN_BWD also applies the update of the GroupNorm scale / shift it has the gradients of
   F_ALWAYS = 8192,    // the step runs before its first_tick too (then it only carries parameters over)
   F_BF16_OUT = 16384, // the step's output crosses a stage boundary in bf16 mode: round it to bf16 (nearest even)
-  F_LWP_W = 32768     // update: weight-difference form of the prediction, w_hat = w' + T (w' - w); flrT then holds T
+  F_LWP_W = 32768,    // update: weight-difference form of the prediction, w_hat = w' + T (w' - w); flrT then holds T
+  F_NT = 65536        // K_UPDATE, in a kernel built for non-temporal output stores: this step uses them too
 };
 
 struct StepDesc {
@@ -158,7 +159,7 @@ struct Globals {
 
 // ---- launch wrappers implemented in pb_kernels.hip ----
 void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, const float* sample_override,
-                  int label_override, hipStream_t s);
+                  int label_override, bool nt, hipStream_t s);
 void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,
                    int n_stages, const Globals* G, int k, hipStream_t s);
 void launch_update_flat(float* w, float* v, const float* g, float* what, int64_t n, float lr, float m,

@@ -39,6 +39,15 @@ typedef __attribute__((address_space(3))) v4f lv4;
 //   A block, GM 1 and 3: MT rows of the chunk's reduction range, row stride LDA
 //   A block, GM 2:       one segment of MT*k*k floats per output channel of the
 //                        chunk -- the layout the weights have in memory
+// Store of a step's bulk output.  What a phase writes is read by the next launch, from
+// any XCD, so nothing is gained by keeping it in the writer's L2; lines left dirty there
+// are written back when the kernel ends, which a short tick feels (ResNet-20: 1 us of 26).
+// With the non-temporal hint they leave while the other workgroups still run.  Larger
+// networks, whose parameters and activations are re-read from the caches, are quicker
+// without it: nt is a compile-time constant of the kernel instantiation (k_phase<NT>).
+// (The hinted store goes through an opaque copy of the address: otherwise the compiler
+// may merge the two stores of the branch into one plain store.)
+#define PB_ST(nt, p, v) do { if (nt) { auto q_ = (p); asm volatile("" : "+v"(q_)); __builtin_nontemporal_store((v), q_); } else *(p) = (v); } while (0)
 #ifndef PB_SCHED
 #define PB_SCHED 0
 #endif
@@ -64,7 +73,7 @@ __device__ __forceinline__ void sched_interleave() {
 }
 
 template <int GM, int NI>
-__device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lfloat* smem) {
+__device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lfloat* smem, const bool nt) {
   PB_TS(1);
   // an opaque copy of the tile index: what is derived from it is then worked out
   // inside this instantiation, not once ahead of all of them and kept in scratch
@@ -187,7 +196,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
         if (n < N) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            if (ro[r] >= 0) out[ro[r] + n] = acc[j][r];
+            if (ro[r] >= 0) PB_ST(nt, out + ro[r] + n, acc[j][r]);
         }
       }
       return;
@@ -213,7 +222,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
         if (ro[r] >= 0) {
           float v = acc[j][r];
           if (GM == 2 && !(msk[j][r] > 0.f)) v = 0.f;
-          out[ro[r] + n] = rbf_if(GM != 3 && (flags & F_BF16_OUT), v + add[j][r]);
+          PB_ST(nt, out + ro[r] + n, rbf_if(GM != 3 && (flags & F_BF16_OUT), v + add[j][r]));
         }
       if (j == 0) PB_TS(21);
       if (j == 1) PB_TS(22);
@@ -681,22 +690,22 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
   if (nops != 1) finish(n0);   // both operand sets have been accumulated (one column tile per workgroup)
 }
 
-__device__ __forceinline__ void step_gemm(const LDesc& d, int tile, int t, lfloat* smem) {
+__device__ __forceinline__ void step_gemm(const LDesc& d, int tile, int t, lfloat* smem, const bool nt) {
   // the number of column subtiles per wave (1, 2 or 4) is a compile-time
   // constant so that the accumulators stay in fixed registers
   const int gm = UNI(d.g.gm), ni = UNI(d.g.ni);
   if (gm == 1) {
-    if (ni == 1) step_gemm_t<1, 1>(d, tile, t, smem);
-    else if (ni == 2) step_gemm_t<1, 2>(d, tile, t, smem);
-    else step_gemm_t<1, 4>(d, tile, t, smem);
+    if (ni == 1) step_gemm_t<1, 1>(d, tile, t, smem, nt);
+    else if (ni == 2) step_gemm_t<1, 2>(d, tile, t, smem, nt);
+    else step_gemm_t<1, 4>(d, tile, t, smem, nt);
   } else if (gm == 2) {
-    if (ni == 1) step_gemm_t<2, 1>(d, tile, t, smem);
-    else if (ni == 2) step_gemm_t<2, 2>(d, tile, t, smem);
-    else step_gemm_t<2, 4>(d, tile, t, smem);
+    if (ni == 1) step_gemm_t<2, 1>(d, tile, t, smem, nt);
+    else if (ni == 2) step_gemm_t<2, 2>(d, tile, t, smem, nt);
+    else step_gemm_t<2, 4>(d, tile, t, smem, nt);
   } else {
-    if (ni == 1) step_gemm_t<3, 1>(d, tile, t, smem);
-    else if (ni == 2) step_gemm_t<3, 2>(d, tile, t, smem);
-    else step_gemm_t<3, 4>(d, tile, t, smem);
+    if (ni == 1) step_gemm_t<3, 1>(d, tile, t, smem, nt);
+    else if (ni == 2) step_gemm_t<3, 2>(d, tile, t, smem, nt);
+    else step_gemm_t<3, 4>(d, tile, t, smem, nt);
   }
 }
 

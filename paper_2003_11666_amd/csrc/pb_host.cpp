@@ -319,6 +319,7 @@ struct pb_ctx {
   int64_t ticks = 0;
   int launch_mode = 0;
   int kernel_set = 0;
+  bool nt_stores = false;   // launch the kernel instantiation with non-temporal output stores
   bool sequential = false;   // sample-indexed form: one sample through all stages per tick (delays below the pipeline's own)
   bool lwp_w = false;  // LWP in its weight-difference form
   double sc_scale = 1.0, lwp_scale = 1.0;   // over-compensation factors on the stage delay
@@ -1211,6 +1212,21 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     d.ntiles = (int)cdiv(d.n, UPD_TILE);
     if (d.n > 0) out.push_back({last_grad_phase + 1, d});
   }
+  // Networks tiled for latency run the kernel instantiation whose bulk outputs leave the L2
+  // while the phase still runs instead of at its end (see PB_ST).  The update joins in only
+  // where it retires long before its phase does, i.e. beside GEMM steps with a long
+  // reduction; as the last thing a phase waits for it is quicker with plain stores (the
+  // 4-stage MLP).
+  c->nt_stores = g_tile_budget_us <= 0 && c->kernel_set == 0;
+  if (c->nt_stores) {
+    std::vector<char> long_gemm;
+    for (auto& pr : out) {
+      if ((int)long_gemm.size() <= pr.first) long_gemm.resize(pr.first + 1, 0);
+      if (pr.second.kind == K_GEMM && pr.second.g.Q >= 256) long_gemm[pr.first] = 1;
+    }
+    for (auto& pr : out)
+      if (pr.second.kind == K_UPDATE && long_gemm[pr.first]) pr.second.flags |= F_NT;
+  }
 }
 
 // Launch order: by phase; inside a phase the steps are independent of each
@@ -1565,7 +1581,7 @@ int run_one_tick(pb_ctx* c, const float* staging, int label) {
   if (c->launch_mode == 0) {
     for (const Phase& p : c->phases) {
       ScopedEv ev(c, 0);
-      launch_phase(c->recs_dev + c->rec_first[p.first], p.tiles, c->globals_dev, k, staging, label, c->stream);
+      launch_phase(c->recs_dev + c->rec_first[p.first], p.tiles, c->globals_dev, k, staging, label, c->nt_stores, c->stream);
     }
   } else {
     // one launch per step (same records, same arithmetic); event classes: 1 = update steps, 2 = ingest
@@ -1574,7 +1590,7 @@ int run_one_tick(pb_ctx* c, const float* staging, int label) {
         const StepDesc& sd = c->steps[p.first + i];
         ScopedEv ev(c, sd.kind == K_INGEST ? 2 : sd.kind == K_UPDATE ? 1 : 0);
         launch_phase(c->recs_dev + c->rec_first[p.first + i], sd.ntiles, c->globals_dev, k, staging, label,
-                     c->stream);
+                     c->nt_stores, c->stream);
       }
   }
   hipError_t e = hipGetLastError();

@@ -133,7 +133,7 @@ namespace pb {
 // GroupNorm statistics of one group (biased variance, two passes) and the
 // folded per-channel scale/shift built from the forward (predicted) affine
 // parameters; kept for the backward pass of the same sample.
-__device__ __forceinline__ void step_gn_stats(const LDesc& d, int tile, int t, lfloat* red, lfloat* smem) {
+__device__ __forceinline__ void step_gn_stats(const LDesc& d, int tile, int t, lfloat* red, lfloat* smem, const bool nt) {
   const int tid = threadIdx.x;
   const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W);
   const int g = tile, cpg = UNI(fdiv(C, frcp(G))), n = cpg * HW;
@@ -191,7 +191,7 @@ __device__ __forceinline__ void step_gn_stats(const LDesc& d, int tile, int t, l
             if (rl) v = fmaxf(v, 0.f);
             o[e] = v;
           }
-          *(gv4*)(yo + i) = o;
+          PB_ST(nt, (gv4*)(yo + i), o);
         }
       }
     }
@@ -228,7 +228,7 @@ __device__ __forceinline__ void step_gn_stats(const LDesc& d, int tile, int t, l
 // group): sums across lanes only, no barrier, and a quarter of the workgroups.
 // LDS: per wavefront sc[64] | sh[64].
 constexpr int GNS_WAVE_MAX_N = 4096;
-__device__ __forceinline__ void step_gn_stats_wave(const LDesc& d, int t, lfloat* smem) {
+__device__ __forceinline__ void step_gn_stats_wave(const LDesc& d, int t, lfloat* smem, const bool nt) {
   const int lane = threadIdx.x & 63, g = UNI(threadIdx.x >> 6);
   const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W);
   const int cpg = UNI(fdiv(C, frcp(G))), n = cpg * HW;
@@ -290,7 +290,7 @@ __device__ __forceinline__ void step_gn_stats_wave(const LDesc& d, int t, lfloat
           if (rl) v = fmaxf(v, 0.f);
           o[e] = v;
         }
-        *(gv4*)(yo + i) = o;
+        PB_ST(nt, (gv4*)(yo + i), o);
       }
     }
   }
@@ -705,7 +705,7 @@ constexpr int GNB_MAX_N = 4096;
 // slot lies inside one channel).  Per-channel sums (dgamma, dbeta) go through
 // per-slot partial sums in LDS, then the group sums, then dx.
 // LDS: psum[n/4] | psum2[n/4] | cs[2*cpg] | cs2[3*cpg] | grp[2]
-__device__ __forceinline__ void step_gn_bwd(const LDesc& d, int tile, int t, bool live, lfloat* smem) {
+__device__ __forceinline__ void step_gn_bwd(const LDesc& d, int tile, int t, bool live, lfloat* smem, const bool nt) {
   const int tid = threadIdx.x;
   const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W), flags = UNI(d.flags);
   const int g = tile, cpg = UNI(fdiv(C, frcp(G))), n = cpg * HW, ns = n >> 2, HW4 = HW >> 2;
@@ -817,7 +817,7 @@ __device__ __forceinline__ void step_gn_bwd(const LDesc& d, int tile, int t, boo
           const float xh = (xr[u][e] - mean) * rstd;
           o[e] = rbf_if(flags & F_BF16_OUT, rstd * (du[u][e] * gm - m1 - xh * m2) + sk[u][e]);
         }
-        *(gv4*)(dx + 4 * sl) = o;
+        PB_ST(nt, (gv4*)(dx + 4 * sl), o);
       }
     }
 }
@@ -908,7 +908,7 @@ __device__ __forceinline__ void step_conv_bwd_w(const LDesc& d, int tile, int t)
   }
 }
 
-__device__ __forceinline__ void step_copy(const LDesc& d, int tile, int t) {
+__device__ __forceinline__ void step_copy(const LDesc& d, int tile, int t, const bool nt) {
   const int grain = UNI(d.grain), n = UNI(d.n);
   if (grain > 0) {   // streaming form: grain floats per workgroup, 16 bytes per access (n a multiple of 4)
     const gfloat* src = at(d.dy, t);
@@ -926,7 +926,7 @@ __device__ __forceinline__ void step_copy(const LDesc& d, int tile, int t) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int i = base + u * 4 * BLK;
-        if (i < hi) *(gv4*)(dst + i) = v[u];
+        if (i < hi) PB_ST(nt, (gv4*)(dst + i), v[u]);
       }
     }
     return;
@@ -967,7 +967,7 @@ __device__ __forceinline__ void step_ingest(const LDesc& d, int tile, int t, con
 // other (d.what), so the update may run beside forward work of the same tick
 // as soon as the stage's gradients are complete.  Master weights and velocity
 // (read d.w, d.v; written d.wp, d.b) are updated in place.
-__device__ __forceinline__ void step_update(const LDesc& d, int tile) {
+__device__ __forceinline__ void step_update(const LDesc& d, int tile, const bool nt_kernel) {
   // the step streams 24 bytes per parameter and nothing else: what it needs is bytes in
   // flight, so every thread requests its 8 vectors of all three arrays before using any.
   // Plain accesses: the parameter arrays of the VGG-11 and wide configurations fit the
@@ -976,7 +976,7 @@ __device__ __forceinline__ void step_update(const LDesc& d, int tile) {
   const int n4 = UNI(d.n) >> 2;
   const int i0 = tile * (UPD_TILE / 4) + threadIdx.x;
   const float a = UNIF(d.fa), b = UNIF(d.fb), lrT = UNIF(d.flrT), lr = UNIF(d.flr), m = UNIF(d.fm);
-  const bool wform = UNI(d.flags) & F_LWP_W;
+  const bool wform = UNI(d.flags) & F_LWP_W, nt = nt_kernel && (UNI(d.flags) & F_NT);
   const gv4* gp = (const gv4*)d.gw;
   const gv4* vp = (const gv4*)d.v;
   const gv4* wp = (const gv4*)d.w;
@@ -1017,13 +1017,13 @@ __device__ __forceinline__ void step_update(const LDesc& d, int tile) {
         v2[e] = fmaf(m, vv[u][e], gv[u][e]);
         w2[e] = fmaf(-lr, fmaf(a, v2[e], b * gv[u][e]), wv[u][e]);
       }
-      vo[i] = v2;
-      wo[i] = w2;
+      PB_ST(nt, vo + i, v2);
+      PB_ST(nt, wo + i, w2);
       if (ho) {
         v4f p;
 #pragma unroll
         for (int e = 0; e < 4; ++e) p[e] = wform ? fmaf(lrT, w2[e] - wv[u][e], w2[e]) : fmaf(-lrT, v2[e], w2[e]);
-        ho[i] = p;
+        PB_ST(nt, ho + i, p);
       }
     }
   }
@@ -1042,7 +1042,7 @@ constexpr int HEAD_MAX_K = 16;      // classes
 // array of per-slot partial sums in LDS.
 // LDS: psum[n/4] | psum2[n/4] | vec[512] | dvec[512] | logit[16] | ebuf[16] | chan[9*C] | grp[2*G]
 template <int XU>   // 16-byte vectors of the input a thread keeps: 8 (up to 8192 inputs) or 16
-__device__ __forceinline__ void step_head_gap4(const LDesc& d, int t, lfloat* smem) {
+__device__ __forceinline__ void step_head_gap4(const LDesc& d, int t, lfloat* smem, const bool nt) {
   const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);
   const int C = UNI(d.C), HW = UNI(d.H) * UNI(d.W), K = UNI(d.K), G = UNI(d.G), flags = UNI(d.flags);
   const bool rl = flags & F_PRE_RELU, has_b = flags & F_BIAS;
@@ -1286,7 +1286,7 @@ __device__ __forceinline__ void step_head_gap4(const LDesc& d, int t, lfloat* sm
           const float xh = (xr[u][e] - mean) * rstd;
           o[e] = rbf_if(flags & F_BF16_OUT, rstd * (du - m1 - xh * m2));
         }
-        *(gv4*)(dx + 4 * sl) = o;
+        PB_ST(nt, (gv4*)(dx + 4 * sl), o);
       }
     }
 }
@@ -1476,7 +1476,7 @@ __device__ __forceinline__ void step_head_wave(const LDesc& d, int t, lfloat* sm
 // goes to LDS, the weights stay in registers) and everything after that runs
 // out of LDS and registers.
 // LDS: xs[C*H*W] | vec[512] | dvec[512] | logit[16] | bias[16] | chan[9*C] | grp[2*G]
-__device__ __forceinline__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem) {
+__device__ __forceinline__ void step_head(const LDesc& d, int t, lfloat* red, lfloat* smem, const bool nt) {
   (void)red;
   if ((UNI(d.flags) & F_PRE_AFFINE) && (UNI(d.flags) & F_DU_GAP) && UNI(d.H) * UNI(d.W) == 64 && UNI(d.G) == 4 &&
       (UNI(d.C) & 15) == 0 && UNI(d.C) <= 256) {
@@ -1485,8 +1485,8 @@ __device__ __forceinline__ void step_head(const LDesc& d, int t, lfloat* red, lf
     return;
   }
   if ((UNI(d.flags) & F_PRE_AFFINE) && (UNI(d.flags) & F_DU_GAP) && ((UNI(d.H) * UNI(d.W)) & 3) == 0) {
-    if (UNI(d.C) * UNI(d.H) * UNI(d.W) <= HEAD_MAX_IN) step_head_gap4<HEAD_MAX_IN / (4 * BLK)>(d, t, smem);
-    else step_head_gap4<2 * HEAD_MAX_IN / (4 * BLK)>(d, t, smem);
+    if (UNI(d.C) * UNI(d.H) * UNI(d.W) <= HEAD_MAX_IN) step_head_gap4<HEAD_MAX_IN / (4 * BLK)>(d, t, smem, nt);
+    else step_head_gap4<2 * HEAD_MAX_IN / (4 * BLK)>(d, t, smem, nt);
     return;
   }
   const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);
@@ -1722,6 +1722,8 @@ __device__ __forceinline__ void step_head(const LDesc& d, int t, lfloat* red, lf
 // phase, a full copy of its step descriptor with the tile index filled in, so
 // that a single burst of scalar loads (one memory round trip) delivers all a
 // workgroup needs to know.
+// NT: bulk outputs are stored with the non-temporal hint (networks tiled for latency, see PB_ST).
+template <bool NT>
 __global__ void __launch_bounds__(BLK) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
         const float* __restrict__ sample_override, int label_override) {
@@ -1772,7 +1774,7 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
   if (!live && !(UNI(d.flags) & F_ALWAYS)) return;
   switch (UNI(d.kind)) {
     case K_GN_STATS:
-      if (UNI(d.grain) == 1) step_gn_stats_wave(d, t, smem); else step_gn_stats(d, tile, t, red, smem);
+      if (UNI(d.grain) == 1) step_gn_stats_wave(d, t, smem, NT); else step_gn_stats(d, tile, t, red, smem, NT);
       break;
     case K_GAP_FWD: step_gap_fwd(d, tile, t, red); break;
     case K_CONV_FWD: step_conv_fwd(d, tile, t); break;
@@ -1782,13 +1784,13 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     case K_GNB_APPLY: step_gnb_apply(d, tile, t); break;
     case K_CONV_BWD_X: step_conv_bwd_x(d, tile, t); break;
     case K_CONV_BWD_W: step_conv_bwd_w(d, tile, t); break;
-    case K_COPY: step_copy(d, tile, t); break;
-    case K_GEMM: step_gemm(d, tile, t, smem); break;
+    case K_COPY: step_copy(d, tile, t, NT); break;
+    case K_GEMM: step_gemm(d, tile, t, smem, NT); break;
     case K_BIAS_GRAD: step_bias_grad(d, tile, t); break;
     case K_INGEST: step_ingest(d, tile, t, G, k, sample_override, label_override); break;
-    case K_UPDATE: step_update(d, tile); break;
-    case K_HEAD: step_head(d, t, red, smem); break;
-    case K_GN_BWD: step_gn_bwd(d, tile, t, live, smem); break;
+    case K_UPDATE: step_update(d, tile, NT); break;
+    case K_HEAD: step_head(d, t, red, smem, NT); break;
+    case K_GN_BWD: step_gn_bwd(d, tile, t, live, smem, NT); break;
     default: break;
   }
 #ifdef PB_TIMING
@@ -1894,9 +1896,10 @@ __global__ void k_advance(Globals* G, int dt, int didx) {
 
 // --------------------------------------------------------- launch wrappers
 void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, const float* sample_override,
-                  int label_override, hipStream_t s) {
+                  int label_override, bool nt, hipStream_t s) {
   if (total_tiles <= 0) return;
-  hipLaunchKernelGGL(k_phase, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, G, k, sample_override, label_override);
+  if (nt) hipLaunchKernelGGL(k_phase<true>, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, G, k, sample_override, label_override);
+  else hipLaunchKernelGGL(k_phase<false>, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, G, k, sample_override, label_override);
 }
 
 void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,
