@@ -39,7 +39,7 @@ def top_kernels(cur, limit=8):
 
 
 def phases(cur):
-    rows = list(cur.execute("select grid_x, workgroup_x, (end-start)/1000.0 from kernels where name like 'pb::k_phase%'"))
+    rows = list(cur.execute("select grid_x, workgroup_x, (end-start)/1000.0 from kernels where name like '%pb::k_phase%'"))
     agg = collections.OrderedDict()
     for gx, wx, d in rows:
         agg.setdefault(gx // max(wx, 1), []).append(d)
@@ -53,7 +53,7 @@ def steps(cur, config):
     import pb_workloads as W
     from paper_2003_11666_amd import binding as B
     plan = B.plan_summary(W.config(config)).strip().split("\n")
-    rows = list(cur.execute("select start, end from kernels where name like 'pb::k_phase%' order by start"))
+    rows = list(cur.execute("select start, end from kernels where name like '%pb::k_phase%' order by start"))
     n = len(plan)
     ticks = [rows[i:i + n] for i in range(0, len(rows) - n + 1, n)]
     ticks = ticks[len(ticks) // 2:]            # steady state: every stage busy
