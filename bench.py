@@ -23,8 +23,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 # k_phase: bytes that crossed the L2 / fabric boundary per algorithmic byte of the launch, from
 # `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this script (FETCH_SIZE scaled by 2, WRITE_SIZE
 # by 1: what the counters read for a plain copy of known size): profiles/k_phase_hbm_traffic.md
-KPHASE_TRAFFIC_PER_ALGORITHMIC_BYTE = {"resnet20": 2.69, "mlp": 1.78, "vgg11": 1.13, "wide": 1.29,
-                                       "resnet50_fp32": 1.96}
+KPHASE_TRAFFIC_PER_ALGORITHMIC_BYTE = {"resnet20": 2.55, "mlp": 1.84, "vgg11": 1.13, "wide": 1.27, "resnet50_fp32": 1.98}
 
 
 def tick_algorithmic_bytes(net, n_params, lwp=True):

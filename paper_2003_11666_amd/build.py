@@ -14,15 +14,20 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950", "-x",
          "-ffp-contract=off", "-Wall", "-Wno-unused-function"]
 
 
-def build(verbose=True):
+TIMING_LIB = os.path.join(HERE, "libpb_hip_timing.so")
+
+
+def build(verbose=True, timing=False):
+    """timing=True: the development build with a time stamp at the start and the end of every
+    workgroup (libpb_hip_timing.so, read by wg_timeline.py); the shipped library has none."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+    out = TIMING_LIB if timing else LIB
+    cmd = [hipcc] + FLAGS + (["-DPB_TIMING=2"] if timing else []) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    build()
-    print("built", LIB)
+    print("built", build(timing="--timing" in sys.argv[1:]))

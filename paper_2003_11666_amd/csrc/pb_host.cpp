@@ -1903,3 +1903,16 @@ void pb_destroy(pb_ctx* c) {
 }
 
 }  // extern "C"
+
+#ifdef PB_TIMING
+// Development build only: workgroups per launch of a tick, in launch order.
+extern "C" int pb_debug_phase_grids(pb_ctx* c, int32_t* out, int cap) {
+  if (!c || !out) return -1;
+  int n = 0;
+  for (const Phase& p : c->phases) {
+    if (n < cap) out[n] = p.tiles;
+    ++n;
+  }
+  return n;
+}
+#endif

@@ -1937,6 +1937,13 @@ extern "C" int pb_debug_set_tick(int t) {
   return (int)hipMemcpyToSymbol(HIP_SYMBOL(pb::pb_ts_tick), &t, sizeof(int));
 }
 extern "C" int pb_debug_set_grid(int g) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(pb::pb_ts_grid), &g, sizeof(int)); }
+extern "C" int pb_debug_clear(void) {
+  void* p = nullptr;
+  hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(pb::pb_ts_out));
+  if (e != hipSuccess) return (int)e;
+  hipDeviceSynchronize();
+  return (int)hipMemset(p, 0, sizeof(long long) * 16384 * 100);
+}
 extern "C" int pb_debug_dump(long long* host, int max_recs) {
   int n = 0;
   hipDeviceSynchronize();
