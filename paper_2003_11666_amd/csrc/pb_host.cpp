@@ -589,14 +589,28 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
           GemmCfg c = g;
           c.wm = wm; c.wn = wn; c.wk = wk; c.ni = ni; c.nsub = nsub;
           if (!fit_gemm(c, C, H, W, K, OH, OW, k, s, pad, allow_vec, true)) continue;
-          const double tt = est_tile_us(c, k), work = tt * c.tiles;
+          // backward weights of a stage with room for partial gradients: the chunks of the
+          // reduction are dealt out to as many groups of workgroups (up to max_parts) as it
+          // takes to bring one workgroup's share under 30 us
+          GemmCfg e = c;
+          double tt = est_tile_us(c, k);
+          for (int want = 2; mode == 3 && nsub == 1 && want <= max_parts && want <= c.n_chunks && tt > 30.0; want *= 2) {
+            e = c;
+            e.cpp = cdiv(c.n_chunks, want);
+            e.parts = cdiv(c.n_chunks, e.cpp);
+            e.tiles = e.parts * e.tpp;
+            GemmCfg one = e;
+            one.n_chunks = e.cpp;   // what one workgroup contracts
+            tt = est_tile_us(one, k);
+          }
+          const double work = tt * e.tiles;
           const bool within = tt <= g_tile_budget_us;
           bool better;
           if (!have) better = true;
           else if (within != best_within) better = within;
           else if (within) better = work < best_work || (work == best_work && tt < best_tile);
           else better = tt < best_tile;
-          if (better) { have = true; bestg = c; best_work = work; best_tile = tt; best_within = within; }
+          if (better) { have = true; bestg = e; best_work = work; best_tile = tt; best_within = within; }
         }
       }
     if (!have) return false;
@@ -1243,7 +1257,8 @@ void order_steps(std::vector<std::pair<int, StepDesc>>& tagged) {
       } else if (d.kind == K_GN_STATS || d.kind == K_GN_BWD) {
         us = 4.0 + (double)d.C / std::max(1, d.G) * d.H * d.W / BLK * 0.05;
       } else if (d.kind == K_GNB_REDUCE) {
-        us = 4.0 + (d.grain == 1 ? 1.0 : (double)d.H * d.W / BLK * ((d.flags & F_DU_POOL) ? 0.8 : 0.05));
+        // (routing the gradient back through a max-pool costs a window search per element: 7 us per 256 of them)
+        us = 4.0 + (d.grain == 1 ? 1.0 : (double)d.H * d.W / BLK * ((d.flags & F_DU_POOL) ? 7.0 : 0.05));
       } else if (d.kind == K_UPDATE) {
         us = 15.0;
       } else if (d.kind == K_POST_FWD || d.kind == K_GNB_APPLY) {
