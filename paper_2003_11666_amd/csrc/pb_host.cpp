@@ -247,7 +247,7 @@ struct Layout {
 // A convolution over a large map with few weights has a weight gradient that is a long
 // reduction with few output tiles: such a stage gets room for partial gradients.
 constexpr int GRAD_PARTS = 16;
-bool split_candidate(const Stage& a) { return a.is_conv && (int64_t)a.OH * a.OW >= 256 && a.padded <= 16384; }
+bool split_candidate(const Stage& a) { return a.is_conv && (int64_t)a.OH * a.OW >= 256 && a.padded <= 65536; }
 
 int st_stride_of(const Stage& s) { return (2 * s.G + 2 * s.gnC() + 63) / 64 * 64; }
 
@@ -1255,7 +1255,9 @@ void order_steps(std::vector<std::pair<int, StepDesc>>& tagged) {
         us = est_tile_us(d.g, d.g.gm == 1 && d.gp.gm ? d.k : d.k);
         if (d.gp.gm) us += est_tile_us(d.gp, 1);
       } else if (d.kind == K_GN_STATS || d.kind == K_GN_BWD) {
-        us = 4.0 + (double)d.C / std::max(1, d.G) * d.H * d.W / BLK * 0.05;
+        // (a group beyond the registers of a workgroup, 8192 elements, takes three passes over memory)
+        const double n = (double)d.C / std::max(1, d.G) * d.H * d.W;
+        us = 4.0 + n / BLK * (d.kind == K_GN_STATS && n > 8192 ? 1.0 : 0.05);
       } else if (d.kind == K_GNB_REDUCE) {
         // (routing the gradient back through a max-pool costs a window search per element: 7 us per 256 of them)
         us = 4.0 + (d.grain == 1 ? 1.0 : (double)d.H * d.W / BLK * ((d.flags & F_DU_POOL) ? 7.0 : 0.05));

@@ -1796,9 +1796,9 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
 #ifdef PB_TIMING
   PB_TS(11);
 #if PB_TIMING == 2
-  if (t == pb_ts_tick && (threadIdx.x & 63) == 0) {
-    // slot = workgroup index; launches of another grid size than pb_ts_grid go to the upper half
-    const int slot = (int)blockIdx.x + ((int)gridDim.x == pb_ts_grid ? 0 : 8192);
+  if (t == pb_ts_tick && (threadIdx.x & 63) == 0 && (int)gridDim.x == pb_ts_grid) {
+    // slot = workgroup index; only the launch with pb_ts_grid workgroups is recorded
+    const int slot = (int)blockIdx.x;
     const int w = threadIdx.x >> 6;
     if (slot < 16384) {
       pb_ts_out[slot * 100 + 4 + w * 24 + 0] = ts_sh[w][0];

@@ -47,8 +47,8 @@ def main():
     warm = 2 * len(net["stages"]) + 8 if "stages" in net else 120
     t = 0
     for ph, grid in enumerate(grids):
-        if grids.count(grid) > 1 or grid > 8192:
-            print(f"launch {ph}: grid {grid} not unique in the tick or above 8192 workgroups, skipped")
+        if grids.count(grid) > 1 or grid > SLOTS:
+            print(f"launch {ph}: grid {grid} not unique in the tick or above {SLOTS} workgroups, skipped")
             continue
         lib.pb_debug_clear()
         lib.pb_debug_set_grid(C.c_int(grid))
@@ -59,7 +59,7 @@ def main():
         eng.sync()
         buf = np.zeros(SLOTS * REC, dtype=np.int64)
         lib.pb_debug_dump(buf.ctypes.data_as(C.POINTER(C.c_longlong)), C.c_int(SLOTS))
-        r = buf.reshape(SLOTS, REC)[:8192]
+        r = buf.reshape(SLOTS, REC)
         rows = []
         for i in range(grid):
             ts = r[i, 4:].reshape(4, 24)
