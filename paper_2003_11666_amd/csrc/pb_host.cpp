@@ -1255,9 +1255,9 @@ void order_steps(std::vector<std::pair<int, StepDesc>>& tagged) {
         us = est_tile_us(d.g, d.g.gm == 1 && d.gp.gm ? d.k : d.k);
         if (d.gp.gm) us += est_tile_us(d.gp, 1);
       } else if (d.kind == K_GN_STATS || d.kind == K_GN_BWD) {
-        // (a group beyond the registers of a workgroup, 8192 elements, takes three passes over memory)
+        // (a group beyond the registers of a workgroup, 32768 elements, takes three passes over memory)
         const double n = (double)d.C / std::max(1, d.G) * d.H * d.W;
-        us = 4.0 + n / BLK * (d.kind == K_GN_STATS && n > 8192 ? 1.0 : 0.05);
+        us = 4.0 + n / BLK * (d.kind == K_GN_STATS && n > 32768 ? 1.0 : 0.05);
       } else if (d.kind == K_GNB_REDUCE) {
         // (routing the gradient back through a max-pool costs a window search per element: 7 us per 256 of them)
         us = 4.0 + (d.grain == 1 ? 1.0 : (double)d.H * d.W / BLK * ((d.flags & F_DU_POOL) ? 7.0 : 0.05));

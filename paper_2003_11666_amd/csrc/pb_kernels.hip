@@ -133,15 +133,16 @@ namespace pb {
 // GroupNorm statistics of one group (biased variance, two passes) and the
 // folded per-channel scale/shift built from the forward (predicted) affine
 // parameters; kept for the backward pass of the same sample.
-__device__ __forceinline__ void step_gn_stats(const LDesc& d, int tile, int t, lfloat* red, lfloat* smem, const bool nt) {
+// GU: 16-byte registers per thread; a group of up to GU * 1024 elements stays in registers
+template <int GU>
+__device__ __forceinline__ bool step_gn_stats_reg(const LDesc& d, int tile, int t, lfloat* red, lfloat* smem, const bool nt) {
   const int tid = threadIdx.x;
   const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W);
   const int g = tile, cpg = UNI(fdiv(C, frcp(G))), n = cpg * HW;
   const gfloat* xp = at(d.x, t) + (size_t)g * n;
   gfloat* st = at(d.st, t);
   const bool rl = UNI(d.flags) & F_PRE_RELU;
-  constexpr int GU = 8;   // 16-byte registers per thread: groups of up to 8192 elements stay in registers
-  if ((n & 3) == 0 && n <= GU * 4 * BLK && cpg <= BLK) {
+  {
     // one burst of reads: the group, and its channels' affine parameters
     v4f xr[GU];
 #pragma unroll
@@ -195,7 +196,20 @@ __device__ __forceinline__ void step_gn_stats(const LDesc& d, int tile, int t, l
         }
       }
     }
-    return;
+    return true;
+  }
+}
+
+__device__ __forceinline__ void step_gn_stats(const LDesc& d, int tile, int t, lfloat* red, lfloat* smem, const bool nt) {
+  const int tid = threadIdx.x;
+  const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W);
+  const int g = tile, cpg = UNI(fdiv(C, frcp(G))), n = cpg * HW;
+  const gfloat* xp = at(d.x, t) + (size_t)g * n;
+  gfloat* st = at(d.st, t);
+  const bool rl = UNI(d.flags) & F_PRE_RELU;
+  if ((n & 3) == 0 && cpg <= BLK) {
+    if (n <= 8 * 4 * BLK) { step_gn_stats_reg<8>(d, tile, t, red, smem, nt); return; }
+    if (n <= 32 * 4 * BLK) { step_gn_stats_reg<32>(d, tile, t, red, smem, nt); return; }
   }
   float s = 0.f;
   for (int i = tid; i < n; i += BLK) s += xp[i];
