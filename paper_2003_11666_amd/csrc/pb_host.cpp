@@ -1232,6 +1232,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   // reduction; as the last thing a phase waits for it is quicker with plain stores (the
   // 4-stage MLP).
   c->nt_stores = g_tile_budget_us <= 0 && c->kernel_set == 0;
+  if (const char* e = getenv("PB_NT_STORES")) c->nt_stores = atoi(e) != 0;   // (tests: both instantiations, same arithmetic)
   if (c->nt_stores) {
     std::vector<char> long_gemm;
     for (auto& pr : out) {

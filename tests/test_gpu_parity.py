@@ -60,6 +60,23 @@ def test_per_step_launch_mode_is_bit_identical():
     assert np.array_equal(outs[0][1], outs[1][1])
 
 
+def test_both_kernel_instantiations_are_bit_identical(monkeypatch):
+    """k_phase<true> (non-temporal output stores) and k_phase<false> differ in a store hint only."""
+    PBEngine = _engine()
+    net = W.config("small_resnet")
+    xs, ys = W.sample_pool(net)
+    outs = []
+    for nt in ("0", "1"):
+        monkeypatch.setenv("PB_NT_STORES", nt)
+        e = PBEngine(net)
+        for t in range(40):
+            e.tick(xs[t % len(ys)], ys[t % len(ys)])
+        outs.append((e.read_weights(), e.loss_history()))
+        e.close()
+    assert np.array_equal(outs[0][0], outs[1][0])
+    assert np.array_equal(outs[0][1], outs[1][1])
+
+
 def test_resident_pool_equals_host_ticks():
     import torch
     PBEngine = _engine()

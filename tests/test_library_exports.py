@@ -71,3 +71,42 @@ def test_hyperparameter_scaling_is_host_arithmetic():
     assert lib.pb_scale_hyperparameters(0.1, 0.9, 0, 1, ctypes.byref(out), ctypes.byref(out)) < 0
     assert lib.pb_scale_hyperparameters(0.1, 1.5, 8, 1, ctypes.byref(out), ctypes.byref(out)) < 0
     assert lib.pb_scale_hyperparameters(0.1, 0.9, 8, 1, None, ctypes.byref(out)) < 0
+
+
+def _plan(name):
+    from paper_2003_11666_amd import binding
+    rows = []
+    for line in binding.plan_summary(W.config(name)).splitlines():
+        m = re.match(r"stage\s+(\d+) phase (\d+) (\S+)\s+tiles\s+(\d+)", line)
+        assert m, line
+        rows.append((int(m.group(1)), int(m.group(2)), m.group(3), int(m.group(4)), line))
+    return rows
+
+
+def test_resnet20_plan_two_phases_split_weight_gradients_short_steps_first():
+    """Host-side planning of the headline configuration: two launches per tick; the weight
+    gradients of the 32x32 layers are split over workgroups; a phase begins with its short steps."""
+    rows = _plan("resnet20")
+    assert {r[1] for r in rows} == {0, 1}
+    split = [r for r in rows if "gm3" in r[4] and "C16x32x32 K16x32x32 k3" in r[4]]
+    assert len(split) == 6
+    for r in split:
+        m = re.search(r"chunks (\d+)/(\d+)", r[4])
+        assert int(m.group(2)) >= 4 and int(m.group(1)) >= int(m.group(2))
+    phase0 = [r for r in rows if r[1] == 0]
+    kinds = [r[2] for r in phase0]
+    first_gemm = kinds.index("gemm")
+    assert set(kinds[:first_gemm]) <= {"ingest", "copy", "gn_stats", "head"}
+    assert "gn_stats" not in kinds[first_gemm:] and "ingest" not in kinds[first_gemm:]
+    # GroupNorm statistics of a layer of four groups: one workgroup
+    assert all(r[3] == 1 for r in phase0 if r[2] == "gn_stats")
+
+
+def test_throughput_plans_keep_every_tile_count_consistent():
+    for name in ("vgg11", "wide"):
+        for r in _plan(name):
+            if r[2] != "gemm":
+                continue
+            m = re.search(r"chunks (\d+)/(\d+)", r[4])
+            chunks, parts = int(m.group(1)), int(m.group(2))
+            assert 1 <= parts <= chunks and r[3] % parts == 0, r[4]
