@@ -1260,8 +1260,10 @@ void order_steps(std::vector<std::pair<int, StepDesc>>& tagged) {
         const double n = (double)d.C / std::max(1, d.G) * d.H * d.W;
         us = 4.0 + n / BLK * (d.kind == K_GN_STATS && n > 32768 ? 1.0 : 0.05);
       } else if (d.kind == K_GNB_REDUCE) {
-        // (routing the gradient back through a max-pool costs a window search per element: 7 us per 256 of them)
-        us = 4.0 + (d.grain == 1 ? 1.0 : (double)d.H * d.W / BLK * ((d.flags & F_DU_POOL) ? 7.0 : 0.05));
+        // (routing the gradient back through a max-pool costs a window search per element: about 2 us per
+        // 256 of them when the channel fits LDS, 7 us from global memory)
+        const bool in_lds = (int64_t)d.H * d.W + (int64_t)d.PH * d.PW <= LDS_FLOATS;
+        us = 4.0 + (d.grain == 1 ? 1.0 : (double)d.H * d.W / BLK * ((d.flags & F_DU_POOL) ? (in_lds ? 2.0 : 7.0) : 0.05));
       } else if (d.kind == K_UPDATE) {
         us = 15.0;
       } else if (d.kind == K_POST_FWD || d.kind == K_GNB_APPLY) {

@@ -427,34 +427,70 @@ __device__ __forceinline__ void step_ce(const LDesc& d, int tile, int t, lfloat*
 // Gradient arriving at element (h,w) of channel c of the tensor u = relu(affine(z))
 // that feeds a max-pool: the sum of dY over the windows whose first maximum
 // (row-major scan, strict >) sits at (h,w).
-__device__ __forceinline__ float pool_routed(const LDesc& d, const gfloat* zc, float sc, float sh,
-                                             int h, int w, const gfloat* dyc) {
+// PK > 0: window size known at compile time (the nine reads of a 3x3 window are then
+// requested together instead of one by one)
+template <int PK, class PZ, class PD>   // pointers to the channel's map and to its pooled gradient: global memory or LDS
+__device__ __forceinline__ float pool_routed_k(const LDesc& d, PZ zc, float sc, float sh,
+                                               int h, int w, PD dyc) {
+  // window geometry in scalar registers; divisions by the pooling stride through a reciprocal
+  const int pk = PK > 0 ? PK : UNI(d.pk);
+  const int ps = UNI(d.ps), pp = UNI(d.pp), H = UNI(d.H), W = UNI(d.W), PH = UNI(d.PH), PW = UNI(d.PW);
+  const float ips = frcp(ps);
   float sum = 0.f;
-  int ph_lo = h + d.pp - d.pk + 1;
-  ph_lo = ph_lo <= 0 ? 0 : (ph_lo + d.ps - 1) / d.ps;
-  int ph_hi = (h + d.pp) / d.ps;
-  if (ph_hi >= d.PH) ph_hi = d.PH - 1;
-  int pw_lo = w + d.pp - d.pk + 1;
-  pw_lo = pw_lo <= 0 ? 0 : (pw_lo + d.ps - 1) / d.ps;
-  int pw_hi = (w + d.pp) / d.ps;
-  if (pw_hi >= d.PW) pw_hi = d.PW - 1;
+  int ph_lo = h + pp - pk + 1;
+  ph_lo = ph_lo <= 0 ? 0 : fdiv(ph_lo + ps - 1, ips);
+  int ph_hi = fdiv(h + pp, ips);
+  if (ph_hi >= PH) ph_hi = PH - 1;
+  int pw_lo = w + pp - pk + 1;
+  pw_lo = pw_lo <= 0 ? 0 : fdiv(pw_lo + ps - 1, ips);
+  int pw_hi = fdiv(w + pp, ips);
+  if (pw_hi >= PW) pw_hi = PW - 1;
   for (int ph = ph_lo; ph <= ph_hi; ++ph)
     for (int pw = pw_lo; pw <= pw_hi; ++pw) {
       float best = -1.f;
-      int bh = -1, bw = -1;
-      for (int kh = 0; kh < d.pk; ++kh) {
-        const int ih = ph * d.ps - d.pp + kh;
-        if (ih < 0 || ih >= d.H) continue;
-        for (int kw = 0; kw < d.pk; ++kw) {
-          const int iw = pw * d.ps - d.pp + kw;
-          if (iw < 0 || iw >= d.W) continue;
-          const float v = fmaxf(fmaf(sc, zc[ih * d.W + iw], sh), 0.f);
-          if (v > best) { best = v; bh = ih; bw = iw; }
+      int bi = -1;
+      const int ih0 = ph * ps - pp, iw0 = pw * ps - pp;
+      if (PK > 0) {
+        float zv[PK > 0 ? PK * PK : 1];
+#pragma unroll
+        for (int kh = 0; kh < PK; ++kh)
+#pragma unroll
+          for (int kw = 0; kw < PK; ++kw) {
+            const int ih = ih0 + kh, iw = iw0 + kw;
+            const bool in = ih >= 0 && ih < H && iw >= 0 && iw < W;
+            zv[kh * PK + kw] = zc[in ? ih * W + iw : 0];
+          }
+#pragma unroll
+        for (int kh = 0; kh < PK; ++kh)
+#pragma unroll
+          for (int kw = 0; kw < PK; ++kw) {
+            const int ih = ih0 + kh, iw = iw0 + kw;
+            const bool in = ih >= 0 && ih < H && iw >= 0 && iw < W;
+            const float v = fmaxf(fmaf(sc, zv[kh * PK + kw], sh), 0.f);
+            if (in && v > best) { best = v; bi = ih * W + iw; }
+          }
+      } else {
+        for (int kh = 0; kh < pk; ++kh) {
+          const int ih = ih0 + kh;
+          if (ih < 0 || ih >= H) continue;
+          for (int kw = 0; kw < pk; ++kw) {
+            const int iw = iw0 + kw;
+            if (iw < 0 || iw >= W) continue;
+            const float v = fmaxf(fmaf(sc, zc[ih * W + iw], sh), 0.f);
+            if (v > best) { best = v; bi = ih * W + iw; }
+          }
         }
       }
-      if (bh == h && bw == w) sum += dyc[ph * d.PW + pw];
+      if (bi == h * W + w) sum += dyc[ph * PW + pw];
     }
   return sum;
+}
+
+template <class PZ, class PD>
+__device__ __forceinline__ float pool_routed(const LDesc& d, PZ zc, float sc, float sh, int h, int w, PD dyc) {
+  if (UNI(d.pk) == 3) return pool_routed_k<3>(d, zc, sc, sh, h, w, dyc);
+  if (UNI(d.pk) == 2) return pool_routed_k<2>(d, zc, sc, sh, h, w, dyc);
+  return pool_routed_k<0>(d, zc, sc, sh, h, w, dyc);
 }
 
 __device__ __forceinline__ float gn_du(const LDesc& d, const gfloat* dy, const gfloat* xc, float sc,
@@ -544,7 +580,7 @@ __device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, i
   }
 }
 
-__device__ __forceinline__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red) {
+__device__ __forceinline__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red, lfloat* smem) {
   if (UNI(d.grain) == 1) { step_gnb_reduce_wave(d, tile, t); return; }
   const int c = tile, HW = UNI(d.H) * UNI(d.W), cpg = UNI(fdiv(UNI(d.C), frcp(UNI(d.G)))), g = UNI(fdiv(c, frcp(cpg)));
   const gfloat* st = at(d.st, t);
@@ -581,6 +617,31 @@ __device__ __forceinline__ void step_gnb_reduce(const LDesc& d, int tile, int t,
             sb += du;
           }
         }
+    }
+  } else if ((d.flags & F_DU_POOL) && HW + UNI(d.PH) * UNI(d.PW) <= LDS_FLOATS) {
+    // gradient routed back through a max-pool: every element looks at up to four pooling
+    // windows of nine inputs.  The channel's map and its pooled gradient are fetched once,
+    // with coalesced loads, and the window searches read LDS.
+    const int PHW = UNI(d.PH) * UNI(d.PW), W = UNI(d.W);
+    lfloat* zs = smem;
+    lfloat* ds = smem + HW;
+    const gfloat* dyc = dy + (size_t)c * PHW;
+    if ((HW & 3) == 0) {
+      for (int i = threadIdx.x * 4; i < HW; i += 4 * BLK) *(lv4*)(zs + i) = *(const gv4*)(xc + i);
+    } else {
+      for (int i = threadIdx.x; i < HW; i += BLK) zs[i] = xc[i];
+    }
+    for (int i = threadIdx.x; i < PHW; i += BLK) ds[i] = dyc[i];
+    __syncthreads();
+    const float iw = frcp(W);
+    for (int i = threadIdx.x; i < HW; i += BLK) {
+      const float xv = zs[i];
+      const float yv = fmaf(sc, xv, sh);
+      const int h = fdiv(i, iw), w = i - h * W;
+      float du = pool_routed(d, (const lfloat*)zs, sc, sh, h, w, (const lfloat*)ds);
+      if (rl && !(yv > 0.f)) du = 0.f;
+      sg = fmaf(du, (xv - mean) * rstd, sg);
+      sb += du;
     }
   } else {
     for (int i = threadIdx.x; i < HW; i += BLK) {
@@ -1794,7 +1855,7 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     case K_CONV_FWD: step_conv_fwd(d, tile, t); break;
     case K_POST_FWD: step_post_fwd(d, tile, t); break;
     case K_CE: step_ce(d, tile, t, red); break;
-    case K_GNB_REDUCE: step_gnb_reduce(d, tile, t, red); break;
+    case K_GNB_REDUCE: step_gnb_reduce(d, tile, t, red, smem); break;
     case K_GNB_APPLY: step_gnb_apply(d, tile, t); break;
     case K_CONV_BWD_X: step_conv_bwd_x(d, tile, t); break;
     case K_CONV_BWD_W: step_conv_bwd_w(d, tile, t); break;
