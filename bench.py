@@ -77,7 +77,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the pipeline on ONE GPU only; --gpus must be 1 "
-              "(see DESIGN.md, 'How the path would shard')", file=sys.stderr)
+              "(sharding the pipeline's stages over several GPUs is described in the design notes, not built)", file=sys.stderr)
         sys.exit(2)
 
     import torch
