@@ -26,6 +26,8 @@ namespace pb {
 template <int V> struct IConst { static constexpr int value = V; };
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) v4f gv4;
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i lvi4;
 typedef float v2f __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(1))) v2f gv2;
 typedef __attribute__((address_space(3))) v4f lv4;
@@ -300,7 +302,9 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     struct APar { int nvalid, seg_len, spr, slots; float ispr; };
     auto a_par = [&](int ch) {
       const int q0 = ch * QC;
-      const int qe = (Q - q0 < QC) ? Q - q0 : QC, q4 = (qe + 3) & ~3;
+      // rows of the A block are zero beyond the chunk's reduction entries up to the next multiple
+      // of 16 (forward, backward weights: the MFMA loop walks the reduction in blocks of 16) or of 4
+      const int qe = (Q - q0 < QC) ? Q - q0 : QC, q4 = (GM == 2) ? (qe + 3) & ~3 : (qe + 15) & ~15;
       int nseg, seg_pad;
       APar p;
       if (GM == 2) {
@@ -579,10 +583,18 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
       // ---- MFMA loop: lane holds A[i = lane%16][k = lane/16] and B[k = lane/16][j = lane%16];
       // the waves of a reduction split take k-steps wk_id, wk_id + wk, ...
       {
-        const int nsteps = qc4 >> 2;
-        const int nk = (nsteps > wk_id) ? (nsteps - wk_id + wk - 1) >> lg(wk) : 0;
-        const int dq = 4 * wk;
-        const lint* oqp = offq + 4 * wk_id + kq;
+        // Forward and backward weights (K16): the reduction is walked in blocks of 16 entries;
+        // in a block's four MFMAs lane group kq = lane / 16 supplies entries 4 kq .. 4 kq + 3, so
+        // that its four A values and its four patch offsets are one 16-byte LDS read each.  The
+        // waves of a reduction split take blocks wk_id, wk_id + wk, ...  Backward data (A block
+        // in the weights' own layout): k-steps of 4 entries, lane group kq supplies entry kq.
+        constexpr bool K16 = GM != 2;
+        const int nsteps = K16 ? 4 * ((qc_eff + 15) >> 4) : qc4 >> 2;
+        const int nunit = K16 ? nsteps >> 2 : nsteps;      // blocks / k-steps dealt out to the waves
+        const int nmine = (nunit > wk_id) ? (nunit - wk_id + wk - 1) >> lg(wk) : 0;
+        const int nk = K16 ? 4 * nmine : nmine;            // MFMA steps of this wave
+        const int dq = K16 ? 16 * wk : 4 * wk;             // K16: advance per block; else per k-step
+        const lint* oqp = offq + (K16 ? 16 * wk_id + 4 * kq : 4 * wk_id + kq);
         const lfloat* ap;
         int a_tap = 0, dq_co = 0, dq_tap = 0;
         if (GM == 2) {
@@ -592,7 +604,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
           ap = Alds + co * lstride + i_row * kk + a_tap;
           dq_co = UNI(fdiv(dq, ikk)); dq_tap = dq - dq_co * kk;
         } else {
-          ap = Alds + i_row * LDA + 4 * wk_id + kq;
+          ap = Alds + i_row * LDA + (K16 ? 16 * wk_id + 4 * kq : 4 * wk_id + kq);
         }
         const int a_adv = (GM == 2) ? dq_co * lstride + dq_tap : dq;
         const int a_wrap = (GM == 2) ? lstride - kk : 0;    // extra advance when the tap index wraps into the next channel
@@ -614,15 +626,32 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
         auto load_oq = [&](bool live) {
           const lint* p = live ? oqp : oqp0;
           const int st = live ? dq : 0;
+          if (K16) {
+            const v4i o = *(const lvi4*)p;
 #pragma unroll
-          for (int u = 0; u < G; ++u) { oqv[u] = *p; p += st; }
-          oqp += G * st;
+            for (int u = 0; u < G; ++u) oqv[u] = o[u];
+            oqp += st;
+          } else {
+#pragma unroll
+            for (int u = 0; u < G; ++u) { oqv[u] = *p; p += st; }
+            oqp += G * st;
+          }
         };
         auto load_ab = [&](auto NB, bool live) {
           constexpr int nb = decltype(NB)::value;
           const lfloat* p = live ? ap : ap0;
           int tap = live ? a_tap : a_tap0;
           const int adv = live ? a_adv : 0, dtap = live ? dq_tap : 0;
+          if (K16) {
+            const v4f a4 = *(const lv4*)p;
+            p += adv;
+#pragma unroll
+            for (int u = 0; u < G; ++u) {
+              av[nb][u] = a4[u];
+#pragma unroll
+              for (int j = 0; j < NI; ++j) bv[nb][u][j] = patch[oqv[u] + offn[j]];
+            }
+          } else {
 #pragma unroll
           for (int u = 0; u < G; ++u) {
             av[nb][u] = *p;
@@ -630,6 +659,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
             if (GM == 2) { tap += dtap; if (tap >= kk) { tap -= kk; p += a_wrap; } }
 #pragma unroll
             for (int j = 0; j < NI; ++j) bv[nb][u][j] = patch[oqv[u] + offn[j]];
+          }
           }
           ap = live ? p : ap;
           a_tap = live ? tap : a_tap;
