@@ -190,6 +190,11 @@ def config(name):
         # ragged sizes: spans several tiles with tails in every kernel
         st = preact_resnet_basic((12, 20), 2, 4, in_c=3, n_classes=7)
         return _net("small_resnet", st, 3, 20, 20, 7, 0.01, 0.9, 32, 15, 200)
+    if name == "split_resnet":
+        # 32x32 and 16x16 maps with few channels: the weight gradients of these layers are
+        # long reductions with few output tiles, which the engine splits over workgroups
+        st = preact_resnet_basic((8, 16), 1, 4, in_c=3, n_classes=5)
+        return _net("split_resnet", st, 3, 32, 32, 5, 0.01, 0.9, 16, 17, 100)
     if name == "odd_resnet":
         # odd map sizes (6x6, then 3x3): no row or map is a multiple of 4 wide, so the
         # scalar staging paths and the generic fused last stage run

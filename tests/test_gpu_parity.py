@@ -27,7 +27,8 @@ def _check(res, K, S):
     assert res["v_err"] <= res["v_tol"], (res["v_err"], res["v_tol"])
 
 
-@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_vgg", "tiny_resnet", "small_resnet", "odd_resnet", "tiny_bottleneck"])
+@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_vgg", "tiny_resnet", "small_resnet", "odd_resnet", "tiny_bottleneck",
+                                  "split_resnet"])
 @pytest.mark.parametrize("mit", [3, 0])
 def test_small_nets_100_ticks(name, mit):
     net = W.config(name)
@@ -160,7 +161,7 @@ def test_reference_kernel_set_matches_too():
     _check(res, 60, len(net["stages"]))
 
 
-@pytest.mark.parametrize("name", ["tiny_vgg", "tiny_resnet", "tiny_bottleneck"])
+@pytest.mark.parametrize("name", ["tiny_vgg", "tiny_resnet", "tiny_bottleneck", "split_resnet"])
 def test_bf16_activation_mode(name):
     """Tensors that cross a stage boundary are rounded to bf16 (both sides round
     to nearest even).  A rounding boundary is one more decision taken on a
@@ -283,7 +284,7 @@ def test_small_delays_run_the_sample_indexed_form(name, delays):
     _sample_indexed_case(name, list(delays), 3)
 
 
-@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_vgg", "tiny_resnet", "small_resnet", "tiny_bottleneck"])
+@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_vgg", "tiny_resnet", "small_resnet", "tiny_bottleneck", "split_resnet"])
 @pytest.mark.parametrize("mit", [3, 0])
 def test_weight_stashing(name, mit):
     """bwd_weights=1 (Eq. sgdpb_weight_stash): the backward pass of a sample uses the predicted weights
@@ -352,7 +353,7 @@ def test_paper_scaled_hyperparameters(name):
     eng.close()
 
 
-@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_resnet", "tiny_vgg"])
+@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_resnet", "tiny_vgg", "split_resnet"])
 def test_lwp_weight_difference_form(name):
     """lwp_form='w' (Eq. lwp_w_form): w_hat = w + T (w - w_prev), built inside the fused update
     from the weights before and after it."""

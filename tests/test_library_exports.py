@@ -110,3 +110,11 @@ def test_throughput_plans_keep_every_tile_count_consistent():
             m = re.search(r"chunks (\d+)/(\d+)", r[4])
             chunks, parts = int(m.group(1)), int(m.group(2))
             assert 1 <= parts <= chunks and r[3] % parts == 0, r[4]
+
+
+def test_split_test_network_really_splits():
+    """The small network the GPU tests use for the split weight-gradient reduction is planned that way."""
+    rows = [r for r in _plan("split_resnet") if "gm3" in r[4]]
+    parts = [int(re.search(r"chunks (\d+)/(\d+)", r[4]).group(2)) for r in rows]
+    assert max(parts) >= 4
+
