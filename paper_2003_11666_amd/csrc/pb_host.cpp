@@ -230,6 +230,7 @@ struct StageBufs {
   int64_t xring = -1, prest = -1, pooled = -1, zring = -1, postst = -1, gradbox = -1, skg = -1,
           da = -1, dz = -1, part = -1, logits = -1, dlogits = -1,
           projy = -1,   // output of the skip projection of the tick's forward sample (computed one phase ahead of the sum)
+          zparts = -1,  // FWD_PARTS partial outputs of a thin layer's forward GEMM split over its reduction (summed by its statistics step)
           gparts = -1;  // GRAD_PARTS copies of the stage's gradient block, the first one complete, the others partial
                         // weight gradients of a backward-weights GEMM whose reduction is split over workgroups
   int st_stride = 0;
@@ -247,6 +248,14 @@ struct Layout {
 // A convolution over a large map with few weights has a weight gradient that is a long
 // reduction with few output tiles: such a stage gets room for partial gradients.
 constexpr int GRAD_PARTS = 16;
+// A layer on a map of at most 16 pixels with a long reduction is a matrix-vector product: its
+// forward GEMM has as many tiles as it has blocks of 16 output channels, each streaming its rows of
+// the weight matrix.  Followed by a GroupNorm (whose statistics step reads the whole output anyway),
+// its reduction is split over workgroups that write partial outputs.
+constexpr int FWD_PARTS = 8;
+bool fwd_split_candidate(const Stage& a) {
+  return a.is_conv && a.post_gn && !a.add && (int64_t)a.OH * a.OW <= 16 && (int64_t)a.C * a.k * a.k >= 2048;
+}
 bool split_candidate(const Stage& a) { return a.is_conv && (int64_t)a.OH * a.OW >= 256 && a.padded <= 65536; }
 
 int st_stride_of(const Stage& s) { return (2 * s.G + 2 * s.gnC() + 63) / 64 * 64; }
@@ -288,6 +297,7 @@ void plan_arena(const std::vector<Stage>& st, bool stash, int loss_cap, Layout& 
     if (a.tap_dist) b.skg = pl.alloc((int64_t)(a.tap_dist + 1) * a.in_elems());
     if (a.proj) b.projy = pl.alloc(a.out_elems());
     if (split_candidate(a)) b.gparts = pl.alloc((int64_t)GRAD_PARTS * a.padded);
+    if (fwd_split_candidate(a)) b.zparts = pl.alloc((int64_t)FWD_PARTS * a.z_elems());
     if (a.ce) { b.logits = pl.alloc(a.K); b.dlogits = pl.alloc(a.K); }
   }
   L.staging = pl.alloc(st[0].in_elems());
@@ -594,7 +604,8 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
           // takes to bring one workgroup's share under 30 us
           GemmCfg e = c;
           double tt = est_tile_us(c, k);
-          for (int want = 2; mode == 3 && nsub == 1 && want <= max_parts && want <= c.n_chunks && tt > 30.0; want *= 2) {
+          for (int want = 2; (mode == 3 || mode == 1) && nsub == 1 && want <= max_parts && want <= c.n_chunks &&
+                             tt > (mode == 3 ? 30.0 : 12.0); want *= 2) {
             e = c;
             e.cpp = cdiv(c.n_chunks, want);
             e.parts = cdiv(c.n_chunks, e.cpp);
@@ -840,6 +851,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       continue;
     }
     // ------------------------------------------------------------ forward
+    int fwd_parts = 1;   // > 1: the layer's forward GEMM leaves partial outputs (see fwd_split_candidate)
     if (a.pre_gn) {
       StepDesc d = blank(K_GN_STATS, s, t_f);
       d.C = a.Cin; d.H = a.Hin; d.W = a.Win; d.G = a.G;
@@ -929,10 +941,14 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         const bool flat = g_tile_budget_us > 0 && plain_src && !(d.flags & F_PROJ) && d.k == 1 && d.stride == 1 && d.pad == 0 &&
                           (d.H * d.W) % 4 == 0 && d.H > 1;
         if (flat) { d.W *= d.H; d.H = 1; d.OW *= d.OH; d.OH = 1; }
-        bool ok = make_gemm(1, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, plain_src, (d.flags & F_PROJ) ? 1 : 16, flat);
+        const bool zsplit = a.post_gn && b.zparts >= 0 && !c->bf16 && g_tile_budget_us > 0 && !(d.flags & (F_SKIP | F_PROJ)) &&
+                            (a.K / a.G) * a.OH * a.OW % 4 == 0 && (int64_t)(a.K / a.G) * a.OH * a.OW <= 32768 && a.K / a.G <= BLK;
+        bool ok = make_gemm(1, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, plain_src, (d.flags & F_PROJ) ? 1 : 16, flat,
+                            zsplit ? FWD_PARTS : 1);
         if (ok && (d.flags & F_PROJ)) ok = make_gemm(1, d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, 0, &g, &gp, true);
         if (ok) {
           d.kind = K_GEMM; d.g = g; d.gp = gp; d.ntiles = g.tiles;
+          if (g.parts > 1) { d.gw = c->f(b.zparts); d.gparts = g.parts; d.gpstride = (int)a.z_elems(); fwd_parts = g.parts; }
           gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, &d.tq, &d.tn);
           if (d.flags & F_PROJ) gemm_tables(c, gp, d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, &d.tq2, &d.tn2);
         }
@@ -947,7 +963,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       d.gamma = wf + a.o_gamma; d.beta = wf + a.o_beta;
       fwd_params(d, PF_GAMMA | PF_BETA);
       d.ntiles = a.G;
-      gn_stats_wave(d);
+      if (fwd_parts > 1) { d.gw = c->f(b.zparts); d.gparts = fwd_parts; d.gpstride = (int)a.z_elems(); }
+      else gn_stats_wave(d);
       out.push_back({ph++, d});
       StepDesc e = blank(K_POST_FWD, s, t_f);
       e.C = a.K; e.H = a.OH; e.W = a.OW; e.G = a.G;
@@ -1253,7 +1270,9 @@ void order_steps(std::vector<std::pair<int, StepDesc>>& tagged) {
       // networks tiled for throughput: estimated duration of one workgroup, nanoseconds
       double us = 3.0;
       if (d.kind == K_GEMM) {
-        us = est_tile_us(d.g, d.g.gm == 1 && d.gp.gm ? d.k : d.k);
+        GemmCfg one = d.g;
+        one.n_chunks = d.g.cpp;   // what one workgroup contracts (a split reduction: its share of the chunks)
+        us = est_tile_us(one, d.k);
         if (d.gp.gm) us += est_tile_us(d.gp, 1);
       } else if (d.kind == K_GN_STATS || d.kind == K_GN_BWD) {
         // (a group beyond the registers of a workgroup, 32768 elements, takes three passes over memory)
@@ -1337,6 +1356,9 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
                d.C / d.G * d.H * d.W <= 4096;
         else
           ok = ok && d.ntiles == d.G;
+        if (d.gparts > 1)   // sums the partial outputs of a split forward GEMM: register form only
+          ok = ok && d.grain != 1 && d.G > 0 && (int64_t)(d.C / d.G) * d.H * d.W <= 32768 && ((d.C / d.G) * d.H * d.W) % 4 == 0 && d.C / d.G <= BLK &&
+               d.gpstride >= in && d.gpstride % 4 == 0 && ptr_ok(d.gw, (int64_t)(d.gparts - 1) * d.gpstride + in);
         ok = ok && d.G > 0 && d.C % d.G == 0 && ref_ok(d.x, in) && ref_ok(d.st, stn) &&
              ptr_ok(d.gamma, d.C) && ptr_ok(d.beta, d.C) && (!d.y.base || ref_ok(d.y, in));
         break;
@@ -1443,7 +1465,7 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
                    g.nsub >= 1 && (g.nsub == 1 || (g.wk == 1 && !(d.flags & F_PROJ && g.gm == 1))) && g.tiles_n == cdiv(cdiv(g.N, g.NT), g.nsub) &&
                    g.parts >= 1 && g.cpp >= 1 && g.tpp == cdiv(g.M, g.MT) * g.tiles_n && g.tiles == g.parts * g.tpp &&
                    (int64_t)g.parts * g.cpp >= g.n_chunks && (int64_t)(g.parts - 1) * g.cpp < g.n_chunks &&
-                   (g.parts == 1 || (g.gm == 3 && g.nsub == 1)) && g.QCpad % 16 == 0 &&
+                   (g.parts == 1 || ((g.gm == 3 || g.gm == 1) && g.nsub == 1)) && g.QCpad % 16 == 0 &&
                    g.QCpad >= g.QC && g.o_offq >= 0 && g.o_A >= g.o_offq + g.QCpad && g.o_A % 4 == 0 && g.o_patch % 4 == 0 &&
                    (int64_t)g.o_patch + ((int64_t)g.CC * g.PR * g.Wp + 3) / 4 * 4 <= LDS_FLOATS && LDS_FLOATS >= 4096 &&
                    (int64_t)g.n_chunks * g.QC >= g.Q;
@@ -1493,6 +1515,10 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
              (!(d.flags & F_PROJ) || d.g.gm != 1 || (ptr_ok((const float*)d.tq2, d.gp.QCpad) && ptr_ok((const float*)d.tn2, d.gp.N)));
         const int64_t wn_ = (int64_t)d.K * d.C * d.k * d.k;
         if (d.g.gm == 1) {
+          // a forward pass split over its reduction writes partial outputs gpstride floats apart
+          if (d.g.parts > 1)
+            ok = ok && d.gparts == d.g.parts && d.gpstride >= outn && d.gpstride % 4 == 0 && !(d.flags & (F_SKIP | F_PROJ | F_BF16_OUT)) &&
+                 ptr_ok(d.gw, (int64_t)(d.g.parts - 1) * d.gpstride + outn);
           ok = ok && ref_ok(d.x, in) && ref_ok(d.y, outn) && ptr_ok(d.w, wn_) &&
                (!(d.flags & F_PRE_AFFINE) || ref_ok(d.st, stn)) && (!(d.flags & F_BIAS) || ptr_ok(d.b, d.K));
           if (d.flags & F_SKIP) {

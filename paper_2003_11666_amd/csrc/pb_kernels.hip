@@ -151,6 +151,24 @@ __device__ __forceinline__ bool step_gn_stats_reg(const LDesc& d, int tile, int 
       xr[u] = (v4f){0.f, 0.f, 0.f, 0.f};
       if (i < n) xr[u] = *(const gv4*)(xp + i);
     }
+    // The layer's forward GEMM was split over its reduction and left partial sums: the
+    // statistics step adds them up in order (the first part stands in for the tensor read
+    // above) and writes the tensor for the steps that read it after this one.
+    const int gparts = UNI(d.gparts);
+    if (gparts > 1) {
+      const gfloat* part = GP(d.gw) + (size_t)g * n;
+      const size_t ps = (size_t)UNI(d.gpstride);
+#pragma unroll
+      for (int u = 0; u < GU; ++u) {
+        const int i = (tid + u * BLK) * 4;
+        if (i < n) {
+          v4f a = *(const gv4*)(part + i);
+          for (int p = 1; p < gparts; ++p) a += *(const gv4*)(part + p * ps + i);
+          xr[u] = a;
+          *(gv4*)((gfloat*)xp + i) = a;
+        }
+      }
+    }
     float gam = 0.f, bet = 0.f;
     if (tid < cpg) { gam = GP(d.gamma)[g * cpg + tid]; bet = GP(d.beta)[g * cpg + tid]; }
     float s = 0.f;
