@@ -76,10 +76,12 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
   auto lg = [](int x) { return x == 1 ? 0 : (x == 2 ? 1 : 2); };
   const int wk_id = wv & (wk - 1), wn_id = (wv >> lg(wk)) & (wn - 1), wm_id = wv >> (lg(wk) + lg(wn));
   const int tiles_n = UNI(d.g.tiles_n);
-  // backward weights, and the forward pass of a thin layer whose consumer adds the parts up:
-  // part of the reduction (a range of chunks) this workgroup takes
+  // backward weights, and the forward or backward-data pass of a thin layer whose consumer
+  // adds the parts up: part of the reduction (a range of chunks) this workgroup takes
+  // (forward and backward data are split only in networks tiled for throughput, which run the
+  // kernel instantiation without the non-temporal hint: the other one carries no code for it)
   int qpart = 0;
-  if (GM != 2) {
+  if (GM == 3 || !nt) {
     const int tpp = UNI(d.g.tpp);
     qpart = UNI(fdiv(tile, frcp(tpp)));
     tile -= qpart * tpp;
@@ -170,8 +172,8 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     if (wk_id != 0) return;
     // ---- epilogue: lane holds C[i = 4*(lane/16) + r][j = lane%16]
     const int M = UNI(d.g.M), N = UNI(d.g.N);
-    gfloat* out = (GM == 2) ? at(d.dx, te)
-                  : (GM == 3 || UNI(d.g.parts) > 1) ? GP(d.gw) + (size_t)qpart * (size_t)UNI(d.gpstride) : at(d.y, te);
+    gfloat* out = (GM == 3 || (!nt && UNI(d.g.parts) > 1)) ? GP(d.gw) + (size_t)qpart * (size_t)UNI(d.gpstride)
+                  : (GM == 2) ? at(d.dx, te) : at(d.y, te);
     const int zero = te - t;                              // 0, opaque to the compiler (see above)
     const int mrow = m0 + wm_id * 16 + 4 * kq + zero;
     const int ncol = n0s + wn_id * ni * 16 + (lane & 15) + zero;
@@ -249,8 +251,8 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     const int QC = UNI(g.QC), QCpad = UNI(g.QCpad), CC = UNI(g.CC), M = UNI(g.M), N = UNI(g.N), Q = UNI(g.Q);
     const int n_chunks = UNI(g.n_chunks), rows_c = UNI(g.rows_c), LDA = UNI(g.LDA);
     // chunks this workgroup contracts (all of them except for a split backward-weights step)
-    const int ch0 = (GM != 2) ? qpart * UNI(g.cpp) : 0;
-    const int ch_end = (GM != 2 && ch0 + UNI(g.cpp) < n_chunks) ? ch0 + UNI(g.cpp) : n_chunks;
+    const int ch0 = (GM == 3 || !nt) ? qpart * UNI(g.cpp) : 0;
+    const int ch_end = ((GM == 3 || !nt) && ch0 + UNI(g.cpp) < n_chunks) ? ch0 + UNI(g.cpp) : n_chunks;
     const int nch = ch_end - ch0;
     const int vec = UNI(g.vec), avec = UNI(g.avec);
     const int border = gk - 1 - gpad;

@@ -230,6 +230,8 @@ struct StageBufs {
   int64_t xring = -1, prest = -1, pooled = -1, zring = -1, postst = -1, gradbox = -1, skg = -1,
           da = -1, dz = -1, part = -1, logits = -1, dlogits = -1,
           projy = -1,   // output of the skip projection of the tick's forward sample (computed one phase ahead of the sum)
+          dxparts = -1, // FWD_PARTS partial gradients with respect to the stage's output, left by the backward-data GEMM of
+                        // the next stage (a thin layer) split over its reduction; summed by the stage's GroupNorm channel sums
           zparts = -1,  // FWD_PARTS partial outputs of a thin layer's forward GEMM split over its reduction (summed by its statistics step)
           gparts = -1;  // GRAD_PARTS copies of the stage's gradient block, the first one complete, the others partial
                         // weight gradients of a backward-weights GEMM whose reduction is split over workgroups
@@ -257,6 +259,22 @@ bool fwd_split_candidate(const Stage& a) {
   return a.is_conv && a.post_gn && !a.add && (int64_t)a.OH * a.OW <= 16 && (int64_t)a.C * a.k * a.k >= 2048;
 }
 bool split_candidate(const Stage& a) { return a.is_conv && (int64_t)a.OH * a.OW >= 256 && a.padded <= 65536; }
+
+// The same for the backward-data GEMM of a thin layer: it writes the gradient with respect to the
+// previous stage's output.  Where that stage ends in a GroupNorm whose channel sums run in the
+// one-wavefront-per-channel form over at most 64 gradient values per channel, they add the parts up.
+bool bwd_split_consumer(const std::vector<Stage>& st, int s) {
+  if (s + 1 >= (int)st.size()) return false;
+  const Stage& a = st[s];
+  const Stage& n = st[s + 1];
+  if (!a.post_gn || !n.is_conv || n.pre_gn || n.pre_relu || n.tap_dist || n.add) return false;
+  if ((int64_t)n.H * n.W > 16 || (int64_t)n.K * n.k * n.k < 2048) return false;
+  // consumer: the channel sums behind a max-pool in their one-wavefront-per-channel form, or the fused
+  // GroupNorm backward (one workgroup per group, gradient in registers)
+  const int64_t per_channel = a.out_elems() / std::max(1, a.K);
+  if (a.pool) return per_channel <= 64 && a.OH * a.OW <= 64;
+  return a.G > 0 && (int64_t)(a.K / a.G) * a.OH * a.OW <= 4096 && (a.OH * a.OW) % 4 == 0;
+}
 
 int st_stride_of(const Stage& s) { return (2 * s.G + 2 * s.gnC() + 63) / 64 * 64; }
 
@@ -298,6 +316,7 @@ void plan_arena(const std::vector<Stage>& st, bool stash, int loss_cap, Layout& 
     if (a.proj) b.projy = pl.alloc(a.out_elems());
     if (split_candidate(a)) b.gparts = pl.alloc((int64_t)GRAD_PARTS * a.padded);
     if (fwd_split_candidate(a)) b.zparts = pl.alloc((int64_t)FWD_PARTS * a.z_elems());
+    if (bwd_split_consumer(st, s)) b.dxparts = pl.alloc((int64_t)FWD_PARTS * a.out_elems());
     if (a.ce) { b.logits = pl.alloc(a.K); b.dlogits = pl.alloc(a.K); }
   }
   L.staging = pl.alloc(st[0].in_elems());
@@ -604,8 +623,7 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
           // takes to bring one workgroup's share under 30 us
           GemmCfg e = c;
           double tt = est_tile_us(c, k);
-          for (int want = 2; (mode == 3 || mode == 1) && nsub == 1 && want <= max_parts && want <= c.n_chunks &&
-                             tt > (mode == 3 ? 30.0 : 12.0); want *= 2) {
+          for (int want = 2; nsub == 1 && want <= max_parts && want <= c.n_chunks && tt > (mode == 3 ? 30.0 : 12.0); want *= 2) {
             e = c;
             e.cpp = cdiv(c.n_chunks, want);
             e.parts = cdiv(c.n_chunks, e.cpp);
@@ -1079,8 +1097,12 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       const bool flat = c->kernel_set == 0 && g_tile_budget_us > 0 && d.k == 1 && d.stride == 1 && d.pad == 0 &&
                         (d.H * d.W) % 4 == 0 && d.H > 1;
       if (flat) { d.W *= d.H; d.H = 1; d.OW *= d.OH; d.OH = 1; }
-      if (c->kernel_set == 0 && make_gemm(2, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, true, 16, flat)) {
+      const bool dxsplit = !a.pre_gn && s > 0 && L.sb[s - 1].dxparts >= 0 && !c->bf16 && g_tile_budget_us > 0 &&
+                           !(d.flags & (F_MASK_X | F_ADD_SKG | F_BF16_OUT)) && !flat;
+      if (c->kernel_set == 0 && make_gemm(2, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, true, 16, flat,
+                                          dxsplit ? FWD_PARTS : 1)) {
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
+        if (g.parts > 1) { d.gw = c->f(L.sb[s - 1].dxparts); d.gparts = g.parts; d.gpstride = (int)a.in_elems(); }
         gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, &d.tq, &d.tn);
       }
       out.push_back({pb, d});
@@ -1213,6 +1235,18 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     if (d.g.avec && !a_aligned(c, d, false)) d.g.avec = 0;
     if (d.gp.gm && d.gp.avec && !a_aligned(c, d, true)) d.gp.avec = 0;
   }
+  // ---- a backward-data GEMM that leaves partial gradients: its consumer, the channel sums of the
+  // previous stage's GroupNorm (same gradient buffer), adds them up
+  for (auto& pr : out) {
+    const StepDesc& p = pr.second;
+    if (p.kind != K_GEMM || p.g.gm != 2 || p.g.parts <= 1) continue;
+    for (auto& qr : out) {
+      StepDesc& q = qr.second;
+      if ((q.kind == K_GNB_REDUCE || q.kind == K_GN_BWD) && q.stage == p.stage - 1 && q.dy.base == p.dx.base) {
+        q.gw = p.gw; q.gparts = p.g.parts; q.gpstride = p.gpstride;
+      }
+    }
+  }
   // ---- fused update: one step per stage, in the phase after the last one that writes a gradient
   // of the stage (its readers use the other copy of the parameters, so they need not be waited for).
   // It runs from the first tick on: before the stage's first backward pass its gradient and
@@ -1250,6 +1284,9 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   // 4-stage MLP).
   c->nt_stores = g_tile_budget_us <= 0 && c->kernel_set == 0;
   if (const char* e = getenv("PB_NT_STORES")) c->nt_stores = atoi(e) != 0;   // (tests: both instantiations, same arithmetic)
+  // (forward and backward-data GEMMs split over their reduction exist only in the other instantiation)
+  for (auto& pr : out)
+    if (pr.second.kind == K_GEMM && pr.second.g.gm != 3 && pr.second.g.parts > 1) c->nt_stores = false;
   if (c->nt_stores) {
     std::vector<char> long_gemm;
     for (auto& pr : out) {
@@ -1395,6 +1432,8 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
           ok = ok && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C);
           if (d.grain == 1) ok = ok && (d.flags & (F_DU_BUF | F_DU_POOL)) && d.ntiles == cdiv(d.C, GNB_WAVE_CH * (BLK / 64));
           else ok = ok && d.grain == 0 && d.ntiles == d.C;
+          if (d.gparts > 1)   // sums partial gradients: wave form, at most 64 values per channel
+            ok = ok && d.grain == 1 && dyn / d.C <= 64 && d.gpstride >= dyn && ptr_ok(d.gw, (int64_t)(d.gparts - 1) * d.gpstride + dyn);
         } else {
           ok = ok && ref_ok(d.dx, in) && (!(d.flags & F_ADD_SKG) || ref_ok(d.skg, in));
           if (d.grain > 0)
@@ -1411,6 +1450,8 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
              ((d.flags & F_DU_BUF) || (d.flags & F_DU_GAP)) && ref_ok(d.x, in) && ref_ok(d.st, stn) && ref_ok(d.dy, dyn) &&
              ptr_ok(d.gamma, d.C) && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C) && (!d.dx.base || ref_ok(d.dx, in)) &&
              (!(d.flags & F_ADD_SKG) || (d.dx.base && ref_ok(d.skg, in)));
+        if (d.gparts > 1)   // sums partial gradients (see bwd_split_consumer)
+          ok = ok && (d.flags & F_DU_BUF) && d.gpstride >= in && d.gpstride % 4 == 0 && ptr_ok(d.gw, (int64_t)(d.gparts - 1) * d.gpstride + in);
         if (d.flags & F_UPD_GN)
           ok = ok && ptr_ok(d.v, 2 * d.C) && ptr_ok(d.w, 2 * d.C) && ptr_ok(d.b, 2 * d.C) && ptr_ok(d.gamma, 2 * d.C) &&
                d.what && ptr_ok(d.what, 2 * d.C);
@@ -1465,7 +1506,7 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
                    g.nsub >= 1 && (g.nsub == 1 || (g.wk == 1 && !(d.flags & F_PROJ && g.gm == 1))) && g.tiles_n == cdiv(cdiv(g.N, g.NT), g.nsub) &&
                    g.parts >= 1 && g.cpp >= 1 && g.tpp == cdiv(g.M, g.MT) * g.tiles_n && g.tiles == g.parts * g.tpp &&
                    (int64_t)g.parts * g.cpp >= g.n_chunks && (int64_t)(g.parts - 1) * g.cpp < g.n_chunks &&
-                   (g.parts == 1 || ((g.gm == 3 || g.gm == 1) && g.nsub == 1)) && g.QCpad % 16 == 0 &&
+                   (g.parts == 1 || g.nsub == 1) && g.QCpad % 16 == 0 &&
                    g.QCpad >= g.QC && g.o_offq >= 0 && g.o_A >= g.o_offq + g.QCpad && g.o_A % 4 == 0 && g.o_patch % 4 == 0 &&
                    (int64_t)g.o_patch + ((int64_t)g.CC * g.PR * g.Wp + 3) / 4 * 4 <= LDS_FLOATS && LDS_FLOATS >= 4096 &&
                    (int64_t)g.n_chunks * g.QC >= g.Q;
@@ -1530,6 +1571,16 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
               ok = ok && ref_ok(d.skip, outn);
           }
         } else if (d.g.gm == 2) {
+          if (d.g.parts > 1) {   // partial gradients, summed by the previous stage's channel sums
+            ok = ok && d.gparts == d.g.parts && d.gpstride >= in && !(d.flags & (F_MASK_X | F_ADD_SKG | F_BF16_OUT)) &&
+                 ptr_ok(d.gw, (int64_t)(d.g.parts - 1) * d.gpstride + in);
+            bool consumed = false;
+            for (auto& qr : steps)
+              consumed = consumed || (((qr.second.kind == K_GNB_REDUCE && qr.second.grain == 1) ||
+                                       (qr.second.kind == K_GN_BWD && !(qr.second.flags & F_DU_GAP))) &&
+                                      qr.second.gparts == d.gparts && qr.second.gw == d.gw && qr.second.dy.base == d.dx.base);
+            ok = ok && consumed;
+          }
           ok = ok && ref_ok(d.dy, outn) && ref_ok(d.dx, in) && ptr_ok(d.w, wn_) &&
                (!(d.flags & F_MASK_X) || ref_ok(d.x, in)) && (!(d.flags & F_ADD_SKG) || ref_ok(d.skg, in));
         } else {

@@ -154,7 +154,7 @@ __device__ __forceinline__ bool step_gn_stats_reg(const LDesc& d, int tile, int 
     // The layer's forward GEMM was split over its reduction and left partial sums: the
     // statistics step adds them up in order (the first part stands in for the tensor read
     // above) and writes the tensor for the steps that read it after this one.
-    const int gparts = UNI(d.gparts);
+    const int gparts = nt ? 1 : UNI(d.gparts);   // (only in the instantiation for networks tiled for throughput)
     if (gparts > 1) {
       const gfloat* part = GP(d.gw) + (size_t)g * n;
       const size_t ps = (size_t)UNI(d.gpstride);
@@ -526,7 +526,7 @@ __device__ __forceinline__ float gn_du(const LDesc& d, const gfloat* dy, const g
 // workgroup that lives for one memory round trip wastes its slot).  The loads of
 // all of a wavefront's channels are requested before the first sum.  Plain
 // gradient buffers, or gradients routed back through a max-pool.
-__device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, int t) {
+__device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, int t, lfloat* smem, const bool nt) {
   const int lane = threadIdx.x & 63;
   const int c0 = (tile * (BLK / 64) + UNI((int)(threadIdx.x >> 6))) * GNB_WAVE_CH;
   const int C = UNI(d.C), G = UNI(d.G), HW = UNI(d.H) * UNI(d.W);
@@ -537,6 +537,28 @@ __device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, i
   const gfloat* dy = at(d.dy, t);
   const bool rl = UNI(d.flags) & F_GN_RELU, pooled = UNI(d.flags) & F_DU_POOL;
   constexpr int RU = 4;
+  // The incoming gradient was left as partial sums by a backward-data GEMM split over its
+  // reduction (at most 64 values per channel): add them up in order, write the gradient for
+  // the elementwise pass that reads it in a later launch, and keep it in LDS for this step.
+  const int gparts = nt ? 1 : UNI(d.gparts);   // (only in the instantiation for networks tiled for throughput)
+  lfloat* ls = smem + UNI((int)(threadIdx.x >> 6)) * (GNB_WAVE_CH * 64);
+  if (gparts > 1) {
+    const int n_dy = pooled ? UNI(d.PH) * UNI(d.PW) : HW;
+    const gfloat* part = GP(d.gw);
+    const size_t ps = (size_t)UNI(d.gpstride);
+#pragma unroll
+    for (int q = 0; q < GNB_WAVE_CH; ++q) {
+      const int c = c0 + q;
+      if (c < C && lane < n_dy) {
+        const size_t o = (size_t)c * n_dy + lane;
+        float s = part[o];
+        for (int p = 1; p < gparts; ++p) s += part[p * ps + o];
+        ((gfloat*)dy)[o] = s;
+        ls[q * 64 + lane] = s;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
   float xv[GNB_WAVE_CH][RU], dv[GNB_WAVE_CH][RU], mean[GNB_WAVE_CH], rstd[GNB_WAVE_CH], sc[GNB_WAVE_CH], sh[GNB_WAVE_CH],
       gm[GNB_WAVE_CH];
 #pragma unroll
@@ -558,9 +580,18 @@ __device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, i
 #pragma unroll
         for (int u = 0; u < RU; ++u) {
           const int i = lane + u * 64;
-          if (i < HW) dv[q][u] = gn_du(d, dy, x + (size_t)c * HW, sc[q], sh[q], c, i, HW);
+          if (i < HW && gparts <= 1) dv[q][u] = gn_du(d, dy, x + (size_t)c * HW, sc[q], sh[q], c, i, HW);
         }
       }
+    }
+  }
+  if (gparts > 1) {   // (maps of at most 64 pixels: u = 0 only) the summed gradient from LDS
+    const int W = UNI(d.W), h = fdiv(lane, frcp(W)), w = lane - h * W;
+#pragma unroll
+    for (int q = 0; q < GNB_WAVE_CH; ++q) {
+      const int c = c0 + q;
+      if (c < C && lane < HW)
+        dv[q][0] = pooled ? pool_routed(d, x + (size_t)c * HW, sc[q], sh[q], h, w, (const lfloat*)(ls + q * 64)) : ls[q * 64 + lane];
     }
   }
 #pragma unroll
@@ -598,8 +629,8 @@ __device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, i
   }
 }
 
-__device__ __forceinline__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red, lfloat* smem) {
-  if (UNI(d.grain) == 1) { step_gnb_reduce_wave(d, tile, t); return; }
+__device__ __forceinline__ void step_gnb_reduce(const LDesc& d, int tile, int t, lfloat* red, lfloat* smem, const bool nt) {
+  if (UNI(d.grain) == 1) { step_gnb_reduce_wave(d, tile, t, smem, nt); return; }
   const int c = tile, HW = UNI(d.H) * UNI(d.W), cpg = UNI(fdiv(UNI(d.C), frcp(UNI(d.G)))), g = UNI(fdiv(c, frcp(cpg)));
   const gfloat* st = at(d.st, t);
   const float mean = st[g], rstd = st[d.G + g], sc = st[2 * d.G + c], sh = st[2 * d.G + d.C + c];
@@ -832,6 +863,21 @@ __device__ __forceinline__ void step_gn_bwd(const LDesc& d, int tile, int t, boo
         if (gapd) { const float v = dy[g * cpg + fdiv(sl, ihw4)]; du[u] = (v4f){v, v, v, v}; }
         else du[u] = *(const gv4*)(dy + (size_t)g * n + 4 * sl);
         if (skg) sk[u] = *(const gv4*)(skg + 4 * sl);
+      }
+    }
+  }
+  if (!nt && UNI(d.gparts) > 1 && !gapd) {
+    // the gradient was left as partial sums by a backward-data GEMM split over its reduction
+    // (the buffer read above holds nothing yet): add them up in order
+    const int gparts = UNI(d.gparts);
+    const size_t ps = (size_t)UNI(d.gpstride);
+    for (int u = 0; u < GU; ++u) {
+      const int sl = tid + u * BLK;
+      if (sl < ns) {
+        const gfloat* part = GP(d.gw) + (size_t)g * n + 4 * sl;
+        v4f a = *(const gv4*)part;
+        for (int p = 1; p < gparts; ++p) a += *(const gv4*)(part + p * ps);
+        du[u] = a;
       }
     }
   }
@@ -1873,7 +1919,7 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     case K_CONV_FWD: step_conv_fwd(d, tile, t); break;
     case K_POST_FWD: step_post_fwd(d, tile, t); break;
     case K_CE: step_ce(d, tile, t, red); break;
-    case K_GNB_REDUCE: step_gnb_reduce(d, tile, t, red, smem); break;
+    case K_GNB_REDUCE: step_gnb_reduce(d, tile, t, red, smem, NT); break;
     case K_GNB_APPLY: step_gnb_apply(d, tile, t); break;
     case K_CONV_BWD_X: step_conv_bwd_x(d, tile, t); break;
     case K_CONV_BWD_W: step_conv_bwd_w(d, tile, t); break;
