@@ -92,7 +92,9 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
   // descriptor and the offset table are fetched once, an A block that is a single
   // chunk stays in LDS, and the requests of the next column tile are in flight
   // while this one is contracted and stored
-  const int nsub = UNI(d.g.nsub);
+  // (several column tiles per workgroup and flattened 1x1 layers are planned only for networks
+  // tiled for throughput: the instantiation for the others carries no code for them)
+  const int nsub = nt ? 1 : UNI(d.g.nsub);
   const int m0 = tm * MT, n0 = tn * nsub * NT;
   const int flags = UNI(d.flags);
   const int kq = lane >> 4;
@@ -260,7 +262,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     // first row (of the output map for forward / backward weights, of the input
     // map for backward data) the current column tile touches; per-lane column offsets
     int tile_row0 = 0, c_lo = 0, adj = 0, col0 = 0;
-    const int win = (GM == 3) ? 0 : UNI(g.win);   // > 0: flattened 1x1 layer, the patch holds the tile's own columns only
+    const int win = (GM == 3 || nt) ? 0 : UNI(g.win);   // > 0: flattened 1x1 layer, the patch holds the tile's own columns only
     auto tile_geometry = [&](int n0s) {
       if (GM == 1) { tile_row0 = UNI(fdiv(n0s, frcp(gOW))); adj = tile_row0 * gs * Wp; }
       else if (GM == 2) { tile_row0 = UNI(fdiv(n0s, frcp(gW))); adj = tile_row0 * Wp; }

@@ -1284,9 +1284,11 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   // 4-stage MLP).
   c->nt_stores = g_tile_budget_us <= 0 && c->kernel_set == 0;
   if (const char* e = getenv("PB_NT_STORES")) c->nt_stores = atoi(e) != 0;   // (tests: both instantiations, same arithmetic)
-  // (forward and backward-data GEMMs split over their reduction exist only in the other instantiation)
+  // (forward and backward-data GEMMs split over their reduction, several column tiles per workgroup and
+  // flattened 1x1 layers exist only in the other instantiation)
   for (auto& pr : out)
-    if (pr.second.kind == K_GEMM && pr.second.g.gm != 3 && pr.second.g.parts > 1) c->nt_stores = false;
+    if (pr.second.kind == K_GEMM && ((pr.second.g.gm != 3 && pr.second.g.parts > 1) || pr.second.g.nsub > 1 || pr.second.g.win > 0 ||
+                                    pr.second.gp.nsub > 1 || pr.second.gp.win > 0)) c->nt_stores = false;
   if (c->nt_stores) {
     std::vector<char> long_gemm;
     for (auto& pr : out) {
