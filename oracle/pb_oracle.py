@@ -57,6 +57,15 @@ library's documentation):
   R13 Hyper-parameter scaling with the update size (Eq. hpscale) at a
       reference momentum of exactly 1, where the printed ratio is 0/0: the
       limit, lr = lr_ref (n/n_ref)^2.
+  R14 Update size N above one (Appendix "Small Batch Size Training" defines it as
+      the number of samples that contribute to the gradient of one update and
+      sets it to one): the per-worker batch stays one sample per stage and
+      tick; a stage adds up the gradients of N consecutive samples (samples
+      kN .. kN+N-1 form update k) and applies ONE update with their mean when
+      the last of them has passed its backward pass.  Delays are counted in
+      updates: SC and LWP use D^s / N for the stage's delay (not rounded).
+      Forward of sample i at stage s therefore sees floor((i - D^s) / N)
+      updates, its backward floor(i / N).
   Canonical parameter order: stage-major; inside a stage: main weight
   [cout][cin][kh][kw], bias, projection weight, GroupNorm scale, shift.
 """
@@ -268,9 +277,16 @@ def softmax_ce(logits, label):
     return loss, dz.reshape(logits.shape)
 
 
-def stage_forward(stage, P, x, skip_x, label, bf16=False):
+def stage_forward(stage, P, x, skip_x, label, bf16=False, relu_shift=0.0):
     """Run one stage's op list.  P: parameters to use (predicted weights).
-    Returns (output or None for the loss stage, loss or None, saved list)."""
+    Returns (output or None for the loss stage, loss or None, saved list).
+
+    relu_shift is a conditioning probe for the tests, 0 everywhere else: the
+    ReLU then passes x > relu_shift * rms(x) instead of x > 0, i.e. it takes
+    the other decision for every element that lies within |relu_shift| * rms
+    of zero on one side.  How far the trajectory of such a run departs from
+    the reference run bounds what an implementation in lower precision may
+    legitimately differ by when it rounds such an element to the other side."""
     saved = []
     loss = None
     n_ops = len(stage)
@@ -279,7 +295,10 @@ def stage_forward(stage, P, x, skip_x, label, bf16=False):
         if kind == "gn":
             x, sv = gn_forward(x, P["gamma"], P["beta"], op["groups"])
         elif kind == "relu":
-            sv = dict(mask=(x > 0))
+            if relu_shift == 0.0:
+                sv = dict(mask=(x > 0))
+            else:
+                sv = dict(mask=(x > relu_shift * torch.sqrt((x * x).mean())))
             x = torch.where(sv["mask"], x, torch.zeros_like(x))
         elif kind == "conv":
             sv = dict(x=x)
@@ -392,8 +411,11 @@ class PBOracle:
     """
 
     def __init__(self, net, delays=None, lr=None, momentum=None, seed=42, mitigation=3,
-                 bwd_weights=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v"):
+                 bwd_weights=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v", update_size=1):
         self.net = net
+        if int(update_size) < 1:
+            raise ValueError("update_size must be >= 1")
+        self.N = int(update_size)
         if lwp_form not in ("v", "w"):
             raise ValueError("lwp_form must be 'v' (velocity) or 'w' (weight difference)")
         self.lwp_form = lwp_form
@@ -418,9 +440,12 @@ class PBOracle:
         # SC with the coefficients of delay sc_scale*D, LWP with horizon T = lwp_scale*D
         self.coef = []
         for D in self.delays:
-            a, b = sc_coefficients(self.m, sc_scale * D) if mitigation in (1, 3) else (1.0, 0.0)
-            T = float(lwp_scale * D) if mitigation in (2, 3) else 0.0
+            Du = D / self.N if self.N > 1 else D        # the stage's delay counted in updates (reading R14)
+            a, b = sc_coefficients(self.m, sc_scale * Du) if mitigation in (1, 3) else (1.0, 0.0)
+            T = float(lwp_scale * Du) if mitigation in (2, 3) else 0.0
             self.coef.append((a, b, T))
+        self.gsum = [None] * S         # gradients added up since the stage's latest update
+        self.gcount = [0] * S
         self.t = 0
         self.fwd_mail = {}      # stage -> activation produced for it last tick
         self.grad_mail = {}     # stage -> dY for its output, produced last tick
@@ -429,6 +454,7 @@ class PBOracle:
         self.labels = {}
         self.losses = []
         self.last_grads = [None] * S   # gradients applied in the latest tick (for tests)
+        self.relu_shift = 0.0          # conditioning probe for the tests, see stage_forward
 
     def predicted(self, s):
         a, b, T = self.coef[s]
@@ -455,7 +481,7 @@ class PBOracle:
                 src = skip_source(stage)
                 skip_x = self.saved[src][i]["x_in"] if src >= 0 else None
                 y, loss, sv = stage_forward(stage, what, xin, skip_x,
-                                            self.labels[i] if s == S - 1 else None, self.bf16)
+                                            self.labels[i] if s == S - 1 else None, self.bf16, self.relu_shift)
                 self.saved[s][i] = dict(ops=sv, x_in=xin, what=what)
                 if s < S - 1:
                     new_fwd[s + 1] = y
@@ -486,6 +512,15 @@ class PBOracle:
         # all reads done: apply the updates (reading R1)
         for s, grads in pending.items():
             a, b, T = self.coef[s]
+            if self.N > 1:
+                # update size N: one update with the mean gradient of N consecutive samples (reading R14)
+                self.gsum[s] = grads if self.gsum[s] is None else {k: self.gsum[s][k] + grads[k] for k in grads}
+                self.gcount[s] += 1
+                self.last_grads[s] = grads
+                if self.gcount[s] < self.N:
+                    continue
+                grads = {k: t_ / self.N for k, t_ in self.gsum[s].items()}
+                self.gsum[s], self.gcount[s] = None, 0
             for k in self.w[s]:
                 self.w_prev[s][k] = self.w[s][k]
                 self.w[s][k], self.v[s][k] = gsc_update(self.w[s][k], self.v[s][k], grads[k],
@@ -511,14 +546,20 @@ class PBOracle:
 # cross-checks the tick form's bookkeeping
 # --------------------------------------------------------------------------
 def run_sample_indexed(net, n_samples, pool_x, pool_y, delays=None, lr=None, momentum=None,
-                       seed=42, mitigation=3, bwd_weights=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v"):
+                       seed=42, mitigation=3, bwd_weights=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v",
+                       update_size=1):
     """Process samples one at a time.  Stage s's forward of sample i uses the
     stage's state after max(0, i - D^s) updates, the backward uses the state
     after i updates; then update i is applied to every stage.
 
+    update_size N > 1 (reading R14): update k is applied after sample kN+N-1
+    with the mean gradient of samples kN..kN+N-1; the forward pass of sample i
+    sees floor(max(0, i - D^s) / N) updates, the backward pass floor(i / N).
+
     Returns (history, losses): history[s][k] = (params, velocity) of stage s
-    after k updates, k = 0..n_samples.
+    after k updates, k = 0..n_samples // N.
     """
+    N = int(update_size)
     stages = net["stages"]
     S = len(stages)
     lr = float(net["lr"] if lr is None else lr)
@@ -529,10 +570,12 @@ def run_sample_indexed(net, n_samples, pool_x, pool_y, delays=None, lr=None, mom
     hist = [[(w0[s], {k: torch.zeros_like(t) for k, t in w0[s].items()})] for s in range(S)]
     coef = []
     for D in delays:
-        a, b = sc_coefficients(m, sc_scale * D) if mitigation in (1, 3) else (1.0, 0.0)
-        T = float(lwp_scale * D) if mitigation in (2, 3) else 0.0
+        Du = D / N if N > 1 else D
+        a, b = sc_coefficients(m, sc_scale * Du) if mitigation in (1, 3) else (1.0, 0.0)
+        T = float(lwp_scale * Du) if mitigation in (2, 3) else 0.0
         coef.append((a, b, T))
     losses = []
+    gsum = [None] * S
     n_pool = len(pool_y)
     for i in range(n_samples):
         x = torch.as_tensor(pool_x[i % n_pool], dtype=DT).reshape(net["in_c"], net["in_h"], net["in_w"])
@@ -541,9 +584,10 @@ def run_sample_indexed(net, n_samples, pool_x, pool_y, delays=None, lr=None, mom
         label = int(pool_y[i % n_pool])
         saved, inputs, whats = [], [], []
         for s in range(S):
-            wv, vv = hist[s][max(0, i - delays[s])]
+            kf = max(0, i - delays[s]) // N            # updates the forward pass sees
+            wv, vv = hist[s][kf]
             if lwp_form == "w":
-                wp_, _ = hist[s][max(0, i - delays[s] - 1)]
+                wp_, _ = hist[s][max(0, kf - 1)]
                 what = {k: wv[k] + coef[s][2] * (wv[k] - wp_[k]) for k in wv}
             else:
                 what = {k: lwp_predict(wv[k], vv[k], lr, coef[s][2]) for k in wv}
@@ -559,7 +603,7 @@ def run_sample_indexed(net, n_samples, pool_x, pool_y, delays=None, lr=None, mom
         skipgrad = {}
         grads_all = [None] * S
         for s in range(S - 1, -1, -1):
-            wcur, _ = hist[s][i]
+            wcur, _ = hist[s][i // N]
             W = whats[s] if bwd_weights == 1 else wcur
             dx, grads, dskip = stage_backward(stages[s], W, saved[s], dy, need_dx=(s > 0), bf16=bf16)
             if s > 0:
@@ -573,20 +617,28 @@ def run_sample_indexed(net, n_samples, pool_x, pool_y, delays=None, lr=None, mom
             grads_all[s] = grads
             dy = dx
         for s in range(S):
-            wcur, vcur = hist[s][i]
+            g_upd = grads_all[s]
+            if N > 1:
+                gsum[s] = g_upd if gsum[s] is None else {k: gsum[s][k] + g_upd[k] for k in g_upd}
+                if (i + 1) % N:
+                    continue
+                g_upd = {k: t_ / N for k, t_ in gsum[s].items()}
+                gsum[s] = None
+            wcur, vcur = hist[s][i // N]
             a, b, T = coef[s]
             wn, vn = {}, {}
             for k in wcur:
-                wn[k], vn[k] = gsc_update(wcur[k], vcur[k], grads_all[s][k], lr, m, a, b)
+                wn[k], vn[k] = gsc_update(wcur[k], vcur[k], g_upd[k], lr, m, a, b)
             hist[s].append((wn, vn))
     return hist, np.asarray(losses)
 
 
 def scalar_quadratic_run(lam, lr, m, D, a, b, T, steps, w_form=False, phi0=1.0):
     """Delayed optimisation of the scalar loss with gradient lam*phi
-    (Section "Analysis for a Convex Quadratic").  g_t = lam * pred_t with
-    pred_t built from the state D steps back (state before step 0 is
-    constant phi0, zero velocity).  Velocity form: pred = phi - lr*T*v;
+    (Section "Analysis for a Convex Quadratic"), driven through this module's
+    own update and prediction routines.  g_t = lam * pred_t with pred_t built
+    from the state D steps back (the state before step 0 is constant phi0 with
+    zero velocity).  Velocity form: pred = lwp_predict(phi, v, lr, T);
     weight-difference form: pred = phi + T (phi - phi_prev).  Returns the
     trajectory phi_0..phi_steps."""
     phi = [phi0]
@@ -598,10 +650,8 @@ def scalar_quadratic_run(lam, lr, m, D, a, b, T, steps, w_form=False, phi0=1.0):
             ph_prev = phi[k - 1] if k - 1 >= 0 else phi0
             pred = ph + T * (ph - ph_prev)
         else:
-            vv = v[k] if k >= 0 else 0.0
-            pred = ph - lr * T * vv
-        g = lam * pred
-        v_new = m * v[-1] + g
-        phi.append(phi[-1] - lr * (a * v_new + b * g))
+            pred = lwp_predict(ph, v[k] if k >= 0 else 0.0, lr, T)
+        w_new, v_new = gsc_update(phi[-1], v[-1], lam * pred, lr, m, a, b)
+        phi.append(w_new)
         v.append(v_new)
     return np.asarray(phi)

@@ -508,3 +508,344 @@ def test_hyperparameter_scaling_limit_of_unit_momentum():
     lr, m = O.scale_hyperparameters(0.1, 1.0, 8, 2)
     lr_near, m_near = O.scale_hyperparameters(0.1, 1.0 - 1e-9, 8, 2)
     assert m == 1.0 and lr == pytest.approx(lr_near, rel=1e-6)
+
+
+# --------------------------------------------------------------------------
+# The analysis of the convex quadratic, driven through the oracle's own
+# per-sample pipeline routine (delay bookkeeping, coefficients, prediction,
+# update) instead of a scalar helper
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("kind,D", [("gdm", 1), ("gdm", 3), ("gsc", 1), ("gsc", 4), ("lwp", 2), ("lwp", 5),
+                                    ("cmb", 1), ("cmb", 3)])
+def test_sample_indexed_pipeline_on_a_quadratic_follows_characteristic_polynomial(kind, D, monkeypatch):
+    """run_sample_indexed with a one-stage "network" whose layer math is replaced by the scalar
+    quadratic loss lam/2 phi^2 (forward gradient lam * phi_hat, phi_hat the predicted weight the
+    forward pass was handed): the weight history it keeps must satisfy the linear recurrence whose
+    characteristic polynomial the paper prints for that method (Section "Analysis for a Convex
+    Quadratic": plain delayed momentum, SC_D, LWP_D, LWP^w_D + SC_D).  A wrong version index in the
+    forward pass, a prediction from the wrong velocity, swapped a / b or a wrong horizon all break
+    the recurrence."""
+    lam = 1.7
+    m, lr = 0.8, 0.02
+
+    def fwd(stage, P, x, skip_x, label, bf16=False, relu_shift=0.0):
+        phi_hat = P["w"].reshape(())
+        return None, 0.5 * lam * phi_hat * phi_hat, [dict(phi=phi_hat)]
+
+    def bwd(stage, Wb, saved, dy, need_dx=True, bf16=False):
+        return None, {"w": (lam * saved[0]["phi"]).reshape(1, 1)}, None
+
+    monkeypatch.setattr(O, "stage_forward", fwd)
+    monkeypatch.setattr(O, "stage_backward", bwd)
+    net = dict(name="quad", stages=[[W.linear(1, 1, bias=0), W.ce()]], in_c=1, in_h=1, in_w=1, n_classes=1,
+               lr=lr, momentum=m, n_pool=1, seed_data=1, ticks=0, act_dtype="fp32")
+    mit = {"gdm": 0, "gsc": 1, "lwp": 2, "cmb": 3}[kind]
+    n = 400
+    hist, _ = O.run_sample_indexed(net, n, np.zeros((1, 1, 1, 1), np.float32), np.zeros(1, np.int32), delays=[D],
+                                   mitigation=mit, lwp_form="w" if kind == "cmb" else "v")
+    phi = np.array([float(hist[0][k][0]["w"]) for k in range(n + 1)])
+    assert phi[0] != 0.0
+    a, b = O.sc_coefficients(m, D) if kind in ("gsc", "cmb") else (1.0, 0.0)
+    T = float(D) if kind in ("lwp", "cmb") else 0.0
+    c = _poly(kind, D, m, lr * lam, a, b, T)
+    nn = len(c) - 1
+    t0 = D + 4
+    res = [sum(c[j] * phi[t + nn - j] for j in range(nn + 1)) for t in range(t0, 380 - nn)]
+    assert max(abs(r) for r in res) < 1e-12 * abs(phi[t0:]).max() + 1e-15
+    # and the helper on the same problem gives the same trajectory
+    ref = O.scalar_quadratic_run(lam, lr, m, D, a, b, T, n, w_form=(kind == "cmb"), phi0=phi[0])
+    assert np.allclose(phi, ref, rtol=1e-12, atol=1e-15)
+
+
+# --------------------------------------------------------------------------
+# Layer routines against plain loops written from the definitions
+# --------------------------------------------------------------------------
+def _naive_conv(x, w, b, stride, pad):
+    C, H, Wd = x.shape
+    K, _, k, _ = w.shape
+    OH, OW = (H + 2 * pad - k) // stride + 1, (Wd + 2 * pad - k) // stride + 1
+    y = np.zeros((K, OH, OW))
+    for co in range(K):
+        for oh in range(OH):
+            for ow in range(OW):
+                acc = 0.0 if b is None else b[co]
+                for ci in range(C):
+                    for kh in range(k):
+                        for kw in range(k):
+                            ih, iw = oh * stride - pad + kh, ow * stride - pad + kw
+                            if 0 <= ih < H and 0 <= iw < Wd:
+                                acc += w[co, ci, kh, kw] * x[ci, ih, iw]
+                y[co, oh, ow] = acc
+    return y
+
+
+@pytest.mark.parametrize("C,H,Wd,K,k,stride,pad", [(3, 7, 6, 4, 3, 2, 1), (2, 5, 5, 3, 1, 2, 0), (2, 6, 7, 2, 3, 1, 1),
+                                                  (1, 9, 8, 2, 5, 2, 2)])
+def test_conv_routines_against_plain_loops(C, H, Wd, K, k, stride, pad):
+    rng = np.random.default_rng(5)
+    x, w, b = rng.standard_normal((C, H, Wd)), rng.standard_normal((K, C, k, k)), rng.standard_normal(K)
+    y = O.conv_forward(torch.from_numpy(x), torch.from_numpy(w), torch.from_numpy(b), stride, pad).numpy()
+    y_ref = _naive_conv(x, w, b, stride, pad)
+    assert y.shape == y_ref.shape and np.allclose(y, y_ref, rtol=1e-12, atol=1e-12)
+    # backward: dW[co,ci,kh,kw] = sum dy[co,oh,ow] x[ci,oh*s-p+kh,ow*s-p+kw]; dX = the transposed map
+    dy = rng.standard_normal(y_ref.shape)
+    dx, dw = O.conv_backward(torch.from_numpy(dy), torch.from_numpy(x), torch.from_numpy(w), stride, pad)
+    dw_ref, dx_ref = np.zeros_like(w), np.zeros_like(x)
+    OH, OW = y_ref.shape[1:]
+    for co in range(K):
+        for oh in range(OH):
+            for ow in range(OW):
+                for ci in range(C):
+                    for kh in range(k):
+                        for kw in range(k):
+                            ih, iw = oh * stride - pad + kh, ow * stride - pad + kw
+                            if 0 <= ih < H and 0 <= iw < Wd:
+                                dw_ref[co, ci, kh, kw] += dy[co, oh, ow] * x[ci, ih, iw]
+                                dx_ref[ci, ih, iw] += dy[co, oh, ow] * w[co, ci, kh, kw]
+    assert np.allclose(dw.numpy(), dw_ref, rtol=1e-12, atol=1e-12)
+    assert np.allclose(dx.numpy(), dx_ref, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("k,stride,pad,H,Wd", [(2, 2, 0, 6, 6), (3, 2, 1, 7, 8), (3, 2, 1, 5, 5)])
+def test_maxpool_forward_and_gradient_routing_against_plain_loops(k, stride, pad, H, Wd):
+    """Through the oracle's stage routines: the pooled value is the window maximum and the gradient
+    goes to the FIRST maximum in row-major window order (ties are planted: post-ReLU zeros and
+    repeated values)."""
+    rng = np.random.default_rng(9)
+    C = 3
+    x = np.round(rng.standard_normal((C, H, Wd)) * 2) / 2      # many repeated values
+    x[x < 0] = 0.0                                              # as after a ReLU
+    # a 1x1 convolution with identity weights in front, so that the stage has its weight layer and the
+    # oracle's own backward routine routes the gradient
+    stage = [W.conv(C, C, 1, 1, 0), W.maxpool(k, stride, pad)]
+    Wid = {"w": torch.eye(C, dtype=O.DT).reshape(C, C, 1, 1)}
+    y, _, saved = O.stage_forward(stage, Wid, torch.from_numpy(x), None, None)
+    PH, PW = (H + 2 * pad - k) // stride + 1, (Wd + 2 * pad - k) // stride + 1
+    dy = rng.standard_normal((C, PH, PW))
+    y_ref, dx_ref = np.zeros((C, PH, PW)), np.zeros_like(x)
+    for c in range(C):
+        for ph in range(PH):
+            for pw in range(PW):
+                best, arg = -np.inf, None
+                for kh in range(k):
+                    for kw in range(k):
+                        ih, iw = ph * stride - pad + kh, pw * stride - pad + kw
+                        if 0 <= ih < H and 0 <= iw < Wd and x[c, ih, iw] > best:
+                            best, arg = x[c, ih, iw], (ih, iw)
+                y_ref[c, ph, pw] = best
+                dx_ref[c, arg[0], arg[1]] += dy[c, ph, pw]
+    assert np.array_equal(y.numpy(), y_ref)
+    dx, _, _ = O.stage_backward(stage, Wid, saved, torch.from_numpy(dy), need_dx=True)
+    assert np.array_equal(dx.numpy(), dx_ref)
+
+
+def test_groupnorm_and_cross_entropy_against_plain_loops():
+    rng = np.random.default_rng(11)
+    C, H, Wd, G = 6, 3, 4, 3
+    x, gamma, beta = rng.standard_normal((C, H, Wd)), rng.standard_normal(C), rng.standard_normal(C)
+    y, sv = O.gn_forward(torch.from_numpy(x), torch.from_numpy(gamma), torch.from_numpy(beta), G)
+    cpg = C // G
+    y_ref = np.zeros_like(x)
+    for g in range(G):
+        blk = x[g * cpg:(g + 1) * cpg]
+        n = blk.size
+        mean = sum(blk.reshape(-1)) / n
+        var = sum((v - mean) ** 2 for v in blk.reshape(-1)) / n       # biased
+        for c in range(g * cpg, (g + 1) * cpg):
+            y_ref[c] = (x[c] - mean) / math.sqrt(var + 1e-5) * gamma[c] + beta[c]
+    assert np.allclose(y.numpy(), y_ref, rtol=1e-12, atol=1e-12)
+    z = rng.standard_normal(7)
+    loss, dz = O.softmax_ce(torch.from_numpy(z), 4)
+    p = np.exp(z) / np.exp(z).sum()
+    assert float(loss) == pytest.approx(-math.log(p[4]), rel=1e-12)
+    onehot = np.zeros(7); onehot[4] = 1.0
+    assert np.allclose(dz.numpy(), p - onehot, rtol=1e-12, atol=1e-15)
+
+
+# --------------------------------------------------------------------------
+# bf16 activation mode: the rounding itself and the places it is applied
+# --------------------------------------------------------------------------
+def _bf16_rne_bits(x32):
+    """Round-to-nearest-even to bfloat16 by integer arithmetic on the float32 bit pattern."""
+    u = np.asarray(x32, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = u + 0x7FFF + ((u >> 16) & 1)
+    return ((u & 0xFFFF0000).astype(np.uint32)).view(np.float32)
+
+
+def test_round_bf16_fixed_vectors():
+    # 1 + 2^-8 lies exactly between 1 and 1 + 2^-7: ties go to the even mantissa (1.0);
+    # 1 + 3*2^-8 lies between 1 + 2^-7 (odd) and 1 + 2^-6 (even): goes up.  Truncation gets the
+    # second and fourth wrong, round-half-up the first.
+    cases = [(1.0 + 2.0 ** -8, 1.0), (1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -6), (-(1.0 + 2.0 ** -8), -1.0),
+             (1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0 + 2.0 ** -7), (1.0 + 2.0 ** -7, 1.0 + 2.0 ** -7),
+             (3.0e-3, float(_bf16_rne_bits([3.0e-3])[0])), (0.0, 0.0), (-2.5, -2.5),
+             (255.0 + 0.5, 256.0), (1.0 - 2.0 ** -9, 1.0)]
+    for x, want in cases:
+        got = float(O._round_bf16(torch.tensor([x], dtype=O.DT))[0])
+        assert got == want, (x, got, want)
+    rng = np.random.default_rng(3)
+    v = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))).astype(np.float32)
+    got = O._round_bf16(torch.from_numpy(v.astype(np.float64))).numpy()
+    assert np.array_equal(got.astype(np.float32), _bf16_rne_bits(v))
+    # a float64 value is first taken to float32 (what the library holds), then to bf16
+    assert float(O._round_bf16(torch.tensor([1.0 + 2.0 ** -8 + 2.0 ** -40], dtype=O.DT))[0]) == 1.0
+
+
+def _is_bf16(t):
+    return torch.equal(t, t.float().bfloat16().double())
+
+
+def test_bf16_rounding_sites_of_one_tick():
+    """Every tensor that crosses a stage boundary or is kept for the backward pass is bf16 (network
+    input, a conv output that feeds a GroupNorm of its own stage, stage outputs, every dX and skip
+    gradient) and equals the nearest-even rounding of what the fp32-activation computation gives
+    from the same inputs; statistics, normalised values, gradients, weights and velocities are not
+    rounded."""
+    net = dict(W.config("tiny_bottleneck"))
+    net["act_dtype"] = "bf16"
+    stages = net["stages"]
+    S = len(stages)
+    xs, ys = W.sample_pool(net)
+    orc = O.PBOracle(net)
+    for t in range(2 * S + 1):
+        orc.tick(xs[t % len(ys)], ys[t % len(ys)])
+    # state kept for the backward pass
+    for s in range(S):
+        for i, entry in orc.saved[s].items():
+            assert _is_bf16(entry["x_in"]), (s, "stage input")
+            for op, sv in zip(stages[s], entry["ops"]):
+                if op["kind"] == "conv":
+                    assert _is_bf16(sv["x"]) or any(o["kind"] == "gn" for o in stages[s][:stages[s].index(op)])
+                if op["kind"] == "gn":
+                    assert not _is_bf16(sv["xh"]) and not _is_bf16(sv["rstd"])
+    for s, y in orc.fwd_mail.items():
+        assert _is_bf16(y)
+    for s, g in orc.grad_mail.items():
+        assert _is_bf16(g)
+    for s in range(S):
+        for d in orc.skipgrad[s].values():
+            assert _is_bf16(d)
+    assert any(len(d) for d in orc.skipgrad)
+    for s in range(S):
+        for k in orc.w[s]:
+            assert not _is_bf16(orc.last_grads[s][k]) or orc.last_grads[s][k].numel() < 3, (s, k)
+        assert not _is_bf16(orc.w[s]["w"]) and not _is_bf16(orc.v[s]["w"])
+    # values: stage forward in bf16 mode = rounding of the fp32-mode result at exactly the listed places
+    x0 = O._round_bf16(torch.as_tensor(xs[0], dtype=O.DT))
+    assert np.array_equal(x0.numpy().astype(np.float32), _bf16_rne_bits(xs[0]))
+    P = orc.predicted(0)
+    y_b, _, sv_b = O.stage_forward(stages[0], P, x0, None, None, bf16=True)      # conv, gn, relu, maxpool
+    z = O.conv_forward(x0, P["w"], None, stages[0][0]["stride"], stages[0][0]["pad"])
+    z_r = torch.from_numpy(_bf16_rne_bits(z.numpy().astype(np.float32)).astype(np.float64))
+    rest, _, _ = O.stage_forward(stages[0][1:], P, z_r, None, None, bf16=False)
+    want = _bf16_rne_bits(rest.numpy().astype(np.float32)).astype(np.float64)
+    assert np.array_equal(y_b.numpy(), want)
+    # a pre-norm stage: only the stage output is rounded
+    P1 = orc.predicted(1)
+    y1_b, _, _ = O.stage_forward(stages[1], P1, y_b, None, None, bf16=True)
+    y1_f, _, sv1 = O.stage_forward(stages[1], P1, y_b, None, None, bf16=False)
+    assert np.array_equal(y1_b.numpy(), _bf16_rne_bits(y1_f.numpy().astype(np.float32)).astype(np.float64))
+    assert not _is_bf16(y1_f)
+    # backward of that stage: the caller rounds dX, the stage routine itself leaves it alone
+    dy = O._round_bf16(torch.randn(y1_f.shape, dtype=O.DT, generator=torch.Generator().manual_seed(4)))
+    dx, grads, _ = O.stage_backward(stages[1], orc.w[1], sv1, dy, need_dx=True, bf16=True)
+    assert not _is_bf16(dx) and not _is_bf16(grads["w"])
+
+
+# --------------------------------------------------------------------------
+# Update size above one (Appendix "Small Batch Size Training")
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_resnet"])
+def test_update_size_one_is_the_default_path(name):
+    net = W.config(name)
+    xs, ys = W.sample_pool(net)
+    a, b = O.PBOracle(net), O.PBOracle(net, update_size=1)
+    for t in range(40):
+        a.tick(xs[t % len(ys)], ys[t % len(ys)])
+        b.tick(xs[t % len(ys)], ys[t % len(ys)])
+    assert np.array_equal(a.read_weights(), b.read_weights()) and np.array_equal(a.loss_history(), b.loss_history())
+
+
+@pytest.mark.parametrize("name", NETS)
+@pytest.mark.parametrize("N", [2, 3])
+def test_zero_delay_with_update_size_n_is_minibatch_sgdm(name, N):
+    """All delays zero and update size N: plain minibatch SGD with momentum on the mean loss of N
+    samples (a library optimizer on an autograd model; the networks normalise per sample, so a batch
+    is N independent samples), whatever the mitigation."""
+    net = W.config(name)
+    xs, ys = W.sample_pool(net)
+    S = len(net["stages"])
+    n_upd = 5
+    params = R.leaf_params(net, 42)
+    opt = torch.optim.SGD([t for p in params for t in p.values()], lr=net["lr"], momentum=net["momentum"])
+    for u in range(n_upd):
+        opt.zero_grad()
+        loss = sum(R.forward_loss(net, params, xs[u * N + j], ys[u * N + j]) for j in range(N)) / N
+        loss.backward()
+        opt.step()
+    ref = R.flat(params)
+    for mit in (0, 3):
+        hist, _ = O.run_sample_indexed(net, n_upd * N, xs, ys, delays=[0] * S, mitigation=mit, update_size=N)
+        assert all(len(hist[s]) == n_upd + 1 for s in range(S))
+        got = torch.cat([t.reshape(-1) for s in range(S) for t in hist[s][n_upd][0].values()])
+        assert torch.allclose(got, ref, rtol=1e-8, atol=1e-11)
+
+
+@pytest.mark.parametrize("name", ["tiny_vgg", "tiny_resnet", "tiny_bottleneck"])
+@pytest.mark.parametrize("N,mit", [(2, 3), (3, 3), (4, 0), (3, 1)])
+def test_update_size_tick_form_equals_sample_indexed_form(name, N, mit):
+    """Two independent book-keepings of the same rule: gradients added up per stage across ticks with
+    an update every N-th backward pass, against versions indexed by floor(i / N)."""
+    net = W.config(name)
+    xs, ys = W.sample_pool(net)
+    S = len(net["stages"])
+    K = 5 * S + 7
+    orc = O.PBOracle(net, mitigation=mit, update_size=N)
+    for t in range(K):
+        orc.tick(xs[t % len(ys)], ys[t % len(ys)])
+    n = K - (S - 1)
+    hist, losses = O.run_sample_indexed(net, n, xs, ys, mitigation=mit, update_size=N)
+    assert np.allclose(orc.loss_history(), losses[:K - S + 1], rtol=1e-10)
+    moved = False
+    for s in range(S):
+        n_bwd = max(0, K - 2 * (S - 1) + s)          # backward passes stage s has done
+        wv, vv = hist[s][n_bwd // N]
+        for name_, t_ in wv.items():
+            assert torch.allclose(orc.w[s][name_], t_, rtol=1e-10, atol=1e-13), (s, name_)
+            assert torch.allclose(orc.v[s][name_], vv[name_], rtol=1e-10, atol=1e-13)
+        moved |= n_bwd // N > 0
+    assert moved
+    # the coefficients count the delay in updates
+    for s in range(S):
+        D = 2 * (S - 1 - s)
+        a, b, T = orc.coef[s]
+        if mit in (1, 3):
+            assert a == pytest.approx(net["momentum"] ** (D / N), rel=1e-14)
+        if mit in (2, 3):
+            assert T == pytest.approx(D / N, rel=1e-15)
+
+
+def test_update_size_with_scaled_hyperparameters_keeps_a_constant_gradient_trajectory(monkeypatch):
+    """Eq. hpscale through the per-sample pipeline routine: a stream of samples that all have gradient
+    1, plain momentum; update size 32 at the reference values and update size 1 at the scaled values
+    move the weight by the same amount over the same number of samples."""
+    def fwd(stage, P, x, skip_x, label, bf16=False, relu_shift=0.0):
+        return None, P["w"].reshape(()), [dict()]
+
+    def bwd(stage, Wb, saved, dy, need_dx=True, bf16=False):
+        return None, {"w": torch.ones(1, 1, dtype=O.DT)}, None
+
+    monkeypatch.setattr(O, "stage_forward", fwd)
+    monkeypatch.setattr(O, "stage_backward", bwd)
+    lr_r, m_r, n_r = 0.1, 0.9, 32
+    lr, m = O.scale_hyperparameters(lr_r, m_r, n_r, 1)
+    net = dict(name="const", stages=[[W.linear(1, 1, bias=0), W.ce()]], in_c=1, in_h=1, in_w=1, n_classes=1,
+               lr=lr_r, momentum=m_r, n_pool=1, seed_data=1, ticks=0, act_dtype="fp32")
+    x, y = np.zeros((1, 1, 1, 1), np.float32), np.zeros(1, np.int32)
+    n_samples = n_r * 200
+    h_r, _ = O.run_sample_indexed(net, n_samples, x, y, delays=[0], lr=lr_r, momentum=m_r, mitigation=0, update_size=n_r)
+    h_1, _ = O.run_sample_indexed(net, n_samples, x, y, delays=[0], lr=lr, momentum=m, mitigation=0, update_size=1)
+    assert len(h_r[0]) == 201 and len(h_1[0]) == n_samples + 1
+    d_r = float(h_r[0][-1][0]["w"] - h_r[0][0][0]["w"])
+    d_1 = float(h_1[0][-1][0]["w"] - h_1[0][0][0]["w"])
+    assert d_1 == pytest.approx(d_r, rel=5e-3) and abs(d_r) > 1.0
