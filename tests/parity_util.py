@@ -6,19 +6,26 @@ import pb_workloads as W
 from oracle import pb_oracle as O
 
 TOL = 1e-5   # per-tick relative weight tolerance for fp32 (stated by the benchmark spec)
-# A ReLU mask is an integer decision taken on a floating-point value.  When a
-# pre-activation lands within rounding error of zero, fp32 and fp64 arithmetic
-# may legitimately decide differently, and the gradient of that sample then
-# differs by a finite amount (one element's contribution).  The oracle's own
-# conditioning tells when that happens: a second oracle whose initial weights
-# are perturbed by PERTURB (about the rounding error of an fp32 forward pass)
-# is run alongside (two of them, with different perturbations); while the
-# oracles agree to WELL_CONDITIONED the trajectory is well conditioned and the
-# strict tolerance applies, after a tie event the tolerance for the remaining
-# ticks is SENS_FACTOR times the oracles' own disagreement.
-PERTURB = (3e-7, 1e-6)
+# The tolerance is taken PER TENSOR and is TOL unless one of three conditioning probes says that
+# this very tensor cannot be pinned that tightly at this tick.  The probes are three more runs of the
+# oracle on the same inputs:
+#   * RELU_BAND: a ReLU mask is an integer decision taken on a floating-point value.  An fp32
+#     evaluation of a stage places a pre-activation within about RELU_BAND * rms of where fp64
+#     places it (measured on these networks: up to 4.1e-6 * rms), so an element that close to zero may
+#     legitimately land on the other side, and the gradient of that sample then differs by a finite
+#     amount -- one element's contribution -- in the parameters of its own stage and of the stages
+#     before it.  Two probes take the other decision for EVERY element within the band, one for the
+#     positive side, one for the negative side (PBOracle.relu_shift): whatever subset of those
+#     decisions an fp32 implementation flips, the tensors it can touch are those the probes touch.
+#   * PERTURB: fp32 master weights are rounded at every update (2^-24 relative each, about 2e-7
+#     after 100 updates); a probe whose initial weights are perturbed by that much shows how far the
+#     training dynamics amplify rounding-size differences in each tensor.
+# A tensor's tolerance at a tick is max(TOL, SENS_FACTOR * largest departure of any probe from the
+# reference oracle on that tensor up to that tick).  A tie in one tensor never loosens the bound of
+# another, and the tests assert how much of the window stays at TOL.
+RELU_BAND = 2e-6
+PERTURB = (2e-7,)
 SENS_FACTOR = 4.0
-WELL_CONDITIONED = 1e-5   # oracle-vs-perturbed-oracle disagreement up to which TOL applies (the perturbation itself reaches ~5e-6 on large tensors)
 
 
 def tensor_slices(net):
@@ -32,16 +39,19 @@ def tensor_slices(net):
     return out
 
 
-def median_rel_error(a, b, slices):
-    """Median over tensors of max|d|/max|ref|: robust against the few tensors a
-    ReLU-mask tie touches."""
-    errs = []
-    for s, name, lo, hi in slices:
-        r = b[lo:hi]
+def per_tensor_errors(a, b, slices):
+    """Per tensor max(max|d|/max|ref|, ||d||2/||ref||2) with ref = b; a tensor whose reference is all zero
+    must be all zero in a as well (reported as 0 or inf)."""
+    out = np.zeros(len(slices))
+    for k, (s, name, lo, hi) in enumerate(slices):
+        x, r = np.asarray(a[lo:hi], dtype=np.float64), b[lo:hi]
+        d = x - r
         mx = np.abs(r).max()
-        if mx > 0:
-            errs.append(np.abs(a[lo:hi].astype(np.float64) - r).max() / mx)
-    return float(np.median(errs)) if errs else 0.0
+        if mx == 0.0:
+            out[k] = 0.0 if np.abs(d).max() == 0.0 else np.inf
+            continue
+        out[k] = max(np.abs(d).max() / mx, np.linalg.norm(d) / np.linalg.norm(r))
+    return out
 
 
 def rel_errors(a, b, slices):
@@ -62,9 +72,9 @@ def rel_errors(a, b, slices):
     return worst_inf, worst_l2, where
 
 
-def perturbed_oracle(net, seed, mitigation, eps, gen_seed=12345, lr=None, bwd_weights=0):
+def perturbed_oracle(net, seed, mitigation, eps, gen_seed=12345, lr=None, bwd_weights=0, **okw):
     import torch
-    orc = O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr, bwd_weights=bwd_weights)
+    orc = O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr, bwd_weights=bwd_weights, **okw)
     g = torch.Generator().manual_seed(gen_seed)
     for p in orc.w:
         for k in p:
@@ -72,19 +82,64 @@ def perturbed_oracle(net, seed, mitigation, eps, gen_seed=12345, lr=None, bwd_we
     return orc
 
 
+class _OracleAsEngine:
+    def __init__(self, orc):
+        self.o = orc
+
+    def tick(self, x, y):
+        self.o.tick(x, y)
+
+    def read_weights(self):
+        return self.o.read_weights()
+
+    def read_velocity(self):
+        return self.o.read_velocity()
+
+    def loss_history(self):
+        return self.o.loss_history()
+
+    def close(self):
+        pass
+
+
 def run_parity(engine_cls, net, K, mitigation=3, seed=42, every=1, engine_kwargs=None, verbose=False, lr=None,
-               perturb=PERTURB, bwd_weights=0):
+               perturb=PERTURB, bwd_weights=0, oracle_kwargs=None, relu_band=RELU_BAND):
+    """K ticks of engine and oracle on the same pool; every `every`-th tick every parameter tensor is
+    compared under its own tolerance (see the head of this file).  Returns the violations and the
+    coverage of the strict tolerance: per (tensor, checked tick) pair, and per stage the number of
+    updates the stage had received at the last checked tick up to which all of its tensors had been
+    held to TOL without interruption."""
+    okw = oracle_kwargs or {}
     xs, ys = W.sample_pool(net)
-    orc = O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr, bwd_weights=bwd_weights)
-    orcs = [perturbed_oracle(net, seed, mitigation, e, 12345 + i, lr=lr, bwd_weights=bwd_weights) for i, e in enumerate(perturb)]
-    eng = engine_cls(net, seed=seed, mitigation=mitigation, lr=lr, bwd_weights=bwd_weights, **(engine_kwargs or {}))
+    orc = O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr, bwd_weights=bwd_weights, **okw)
+    orcs = [perturbed_oracle(net, seed, mitigation, e, 12345 + i, lr=lr, bwd_weights=bwd_weights, **okw)
+            for i, e in enumerate(perturb)]
+    for shift in (relu_band, -relu_band):
+        o2 = O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr, bwd_weights=bwd_weights, **okw)
+        o2.relu_shift = shift
+        orcs.append(o2)
+    if engine_cls is None:
+        # coverage run: how much of the window the probes leave at TOL is a property of the oracle alone
+        eng = _OracleAsEngine(O.PBOracle(net, seed=seed, mitigation=mitigation, lr=lr, bwd_weights=bwd_weights, **okw))
+    else:
+        eng = engine_cls(net, seed=seed, mitigation=mitigation, lr=lr, bwd_weights=bwd_weights, **(engine_kwargs or {}))
     slices = tensor_slices(net)
+    S = len(net["stages"])
+    nT = len(slices)
     w0 = eng.read_weights()
     assert w0.size == orc.read_weights().size
     # same initial weights (both sides implement the same counter-based generator)
-    assert np.abs(w0.astype(np.float64) - orc.read_weights()).max() <= 1e-7
-    worst = (0.0, 0.0, None, -1)
-    violations, strict_ticks, checked = [], 0, 0
+    assert np.abs(np.asarray(w0, dtype=np.float64) - orc.read_weights()).max() <= 1e-7
+    worst = (0.0, None, -1)
+    violations = []
+    strict_pairs = pairs = 0
+    still_strict = np.ones(nT, dtype=bool)        # tensor has been under TOL at every check so far
+    strict_until = np.full(nT, -1)                # last checked tick of that unbroken run
+    checked = 0
+    worst_median = 0.0
+    within_tol_pairs = 0                          # pairs on which the engine actually agreed to TOL
+    tol_log = []                                  # every tolerance applied, for the coverage report
+    sens_run = np.zeros(nT)                       # largest departure of a probe so far, per tensor
     for t in range(K):
         i = t % len(ys)
         orc.tick(xs[i], ys[i])
@@ -93,24 +148,56 @@ def run_parity(engine_cls, net, K, mitigation=3, seed=42, every=1, engine_kwargs
         eng.tick(xs[i], ys[i])
         if (t + 1) % every == 0 or t == K - 1:
             ref = orc.read_weights()
-            e_inf, e_l2, where = rel_errors(eng.read_weights(), ref, slices)
-            s_inf = max(max(rel_errors(o2.read_weights(), ref, slices)[:2]) for o2 in orcs)
-            tol = TOL if s_inf <= WELL_CONDITIONED else max(TOL, SENS_FACTOR * s_inf)
+            err = per_tensor_errors(eng.read_weights(), ref, slices)
+            sens = np.max([per_tensor_errors(o2.read_weights(), ref, slices) for o2 in orcs], axis=0)
+            sens_run = np.maximum(sens_run, sens)
+            tol = np.maximum(TOL, SENS_FACTOR * sens_run)
+            strict = tol == TOL
+            tol_log.append(tol.copy())
+            within_tol_pairs += int((err <= TOL).sum())
             checked += 1
-            strict_ticks += tol == TOL
+            pairs += nT
+            strict_pairs += int(strict.sum())
+            still_strict &= strict
+            strict_until[still_strict] = t
+            bad = np.nonzero(err > tol)[0]
+            for k in bad:
+                violations.append((t, slices[k][0], slices[k][1], float(err[k]), float(tol[k])))
+            # the median over tensors: the few tensors a tie touches cannot move it, an error common to
+            # all tensors (a wrong constant, a dropped term) does
+            med_err, med_tol = float(np.median(err)), max(TOL, SENS_FACTOR * float(np.median(sens_run)))
+            if med_err > med_tol:
+                violations.append((t, -1, "median over tensors", med_err, med_tol))
+            worst_median = max(worst_median, med_err)
+            kmax = int(np.argmax(err))
             if verbose:
-                print(f"tick {t}: inf {e_inf:.2e} l2 {e_l2:.2e} at {where} (oracle sens {s_inf:.1e})", flush=True)
-            if max(e_inf, e_l2) > tol:
-                violations.append((t, e_inf, e_l2, where, tol))
-            if e_inf > worst[0]:
-                worst = (e_inf, max(e_l2, worst[1]), where, t)
-    med = median_rel_error(eng.read_weights(), orc.read_weights(), slices)
-    lg, lo = eng.loss_history(), orc.loss_history()
-    ev, ov = eng.read_velocity(), orc.read_velocity()
-    l_sens = max(np.abs(o2.loss_history() - lo).max() for o2 in orcs) if len(lo) else 0.0
-    v_sens = max(np.abs(o2.read_velocity() - ov).max() for o2 in orcs) / np.abs(ov).max()
-    v_err = np.abs(ev - ov).max() / np.abs(ov).max()
+                print(f"tick {t}: worst {err[kmax]:.2e} at {slices[kmax][:2]} (its oracle sens {sens[kmax]:.1e}), "
+                      f"{int(strict.sum())}/{nT} tensors strict", flush=True)
+            if err[kmax] > worst[0]:
+                worst = (float(err[kmax]), slices[kmax][:2], t)
+    # updates each stage had received while all of its tensors were still under the strict tolerance
+    upd_strict = []
+    for s in range(S):
+        ks = [k for k, sl in enumerate(slices) if sl[0] == s]
+        last = min(strict_until[k] for k in ks)
+        first_update_tick = 2 * (S - 1) - s           # the tick that applies the stage's first update
+        upd_strict.append(max(0, int(last) - first_update_tick + 1))
+    ref = orc.read_weights()
+    final_err = per_tensor_errors(eng.read_weights(), ref, slices)
+    med = float(np.median(final_err))
+    # loss history: per sample, tolerance from the oracles' disagreement on that sample's loss
+    lg, lo = np.asarray(eng.loss_history(), dtype=np.float64), orc.loss_history()
+    l_sens = np.max([np.abs(o2.loss_history() - lo) for o2 in orcs], axis=0) if len(lo) else np.zeros(0)
+    l_tol = np.maximum(1e-4 * np.maximum(1.0, np.abs(lo)), SENS_FACTOR * l_sens)
+    # velocity: per tensor, like the weights
+    ov = orc.read_velocity()
+    v_err = per_tensor_errors(eng.read_velocity(), ov, slices)
+    v_sens = np.max([per_tensor_errors(o2.read_velocity(), ov, slices) for o2 in orcs], axis=0)
+    v_tol = np.maximum(10 * TOL, SENS_FACTOR * v_sens)
     eng.close()
-    return dict(worst_inf=worst[0], worst_l2=worst[1], where=worst[2], tick=worst[3],
-                violations=violations, strict_ticks=strict_ticks, checked=checked, median_final=med,
-                loss_gpu=lg, loss_cpu=lo, loss_tol=max(1e-4, SENS_FACTOR * l_sens), v_err=v_err, v_tol=max(10 * TOL, SENS_FACTOR * v_sens))
+    return dict(worst=worst[0], where=worst[1], tick=worst[2], violations=violations,
+                strict_pairs=strict_pairs, pairs=pairs, checked=checked, strict_frac=strict_pairs / max(1, pairs),
+                upd_strict=upd_strict, within_tol_pairs=within_tol_pairs, median_final=med, worst_median=worst_median, tol_quantiles=np.quantile(np.concatenate(tol_log), [0.5, 0.9, 1.0]),
+                loss_gpu=lg, loss_cpu=lo, loss_tol=l_tol,
+                v_bad=[(slices[k][0], slices[k][1], float(v_err[k]), float(v_tol[k])) for k in np.nonzero(v_err > v_tol)[0]],
+                v_worst=float(v_err.max()), v_strict=int((v_tol == 10 * TOL).sum()), n_tensors=nT)

@@ -1,4 +1,5 @@
 """HIP engine vs CPU oracle, element by element, through the C ABI."""
+import os
 import sys
 
 import numpy as np
@@ -16,15 +17,86 @@ def _engine():
     return PBEngine
 
 
-def _check(res, K, S):
-    print(f"worst inf {res['worst_inf']:.3e} l2 {res['worst_l2']:.3e} at {res['where']} tick {res['tick']}; "
-          f"strict 1e-5 tolerance in force on {res['strict_ticks']}/{res['checked']} checked ticks; "
-          f"median tensor error at the last tick {res['median_final']:.2e}",
-          file=sys.stderr, flush=True)
+# Share of (tensor, checked tick) pairs held to the strict 1e-5 and, per stage, the updates received while every tensor
+# of the stage was still held to it.  Both are properties of the oracle and its conditioning probes alone (see
+# tests/parity_util.py; the values below are what the probes give for each case, less a margin for a different
+# summation order of the float64 library routines on another host) -- the engine cannot influence them, and a test
+# fails if the probes stop leaving that much of the window at 1e-5.
+# case key -> (min strict share, min updates under the strict tolerance of the least covered stage)
+COVERAGE = {
+    "tiny_mlp/mit3": (0.95, 94),   # probes give 1.000, 96
+    "tiny_mlp/mit0": (0.84, 67),   # probes give 0.893, 69
+    "tiny_vgg/mit3": (0.95, 92),   # probes give 1.000, 94
+    "tiny_vgg/mit0": (0.95, 92),   # probes give 1.000, 94
+    "tiny_resnet/mit3": (0.95, 88),   # probes give 1.000, 90
+    "tiny_resnet/mit0": (0.95, 88),   # probes give 1.000, 90
+    "small_resnet/mit3": (0.34, 15),   # probes give 0.399, 17
+    "small_resnet/mit0": (0.37, 22),   # probes give 0.429, 24
+    "odd_resnet/mit3": (0.92, 45),   # probes give 0.974, 47
+    "odd_resnet/mit0": (0.95, 88),   # probes give 1.000, 90
+    "tiny_bottleneck/mit3": (0.83, 18),   # probes give 0.882, 20
+    "tiny_bottleneck/mit0": (0.89, 51),   # probes give 0.944, 53
+    "split_resnet/mit3": (0.73, 56),   # probes give 0.781, 58
+    "split_resnet/mit0": (0.34, 24),   # probes give 0.397, 26
+    "tiny_resnet/mit1/60": (0.95, 48),   # probes give 1.000, 50
+    "tiny_resnet/mit2/60": (0.95, 48),   # probes give 1.000, 50
+    "mlp": (0.95, 92),   # probes give 1.000, 94
+    "small_resnet/kernel_set1/60": (0.61, 15),   # probes give 0.664, 17
+    "tiny_vgg/bf16/60": (0.00, 0),   # probes give 0.027, 0
+    "tiny_resnet/bf16/60": (0.00, 0),   # probes give 0.037, 0
+    "tiny_bottleneck/bf16/60": (0.00, 0),   # probes give 0.056, 0
+    "split_resnet/bf16/60": (0.00, 0),   # probes give 0.037, 0
+    "tiny_mlp/mit3/stash/80": (0.94, 70),   # probes give 0.990, 72
+    "tiny_mlp/mit0/stash/80": (0.95, 74),   # probes give 1.000, 76
+    "tiny_vgg/mit3/stash/80": (0.95, 72),   # probes give 1.000, 74
+    "tiny_vgg/mit0/stash/80": (0.95, 72),   # probes give 1.000, 74
+    "tiny_resnet/mit3/stash/80": (0.95, 68),   # probes give 1.000, 70
+    "tiny_resnet/mit0/stash/80": (0.95, 68),   # probes give 1.000, 70
+    "small_resnet/mit3/stash/80": (0.42, 11),   # probes give 0.473, 13
+    "small_resnet/mit0/stash/80": (0.52, 16),   # probes give 0.578, 18
+    "tiny_bottleneck/mit3/stash/80": (0.52, 16),   # probes give 0.577, 18
+    "tiny_bottleneck/mit0/stash/80": (0.94, 52),   # probes give 0.992, 54
+    "split_resnet/mit3/stash/80": (0.34, 17),   # probes give 0.390, 19
+    "split_resnet/mit0/stash/80": (0.33, 6),   # probes give 0.383, 8
+    "resnet20/mit3": (0.33, 1),   # probes give 0.388, 3
+    "resnet20/mit0": (0.38, 1),   # probes give 0.435, 3
+    "vgg11": (0.14, 0),   # probes give 0.192, 0
+    "tiny_resnet/mit3/N2": (0.95, 88),   # probes give 1.000, 90
+    "tiny_resnet/mit0/N3": (0.95, 88),   # probes give 1.000, 90
+    "small_resnet/mit3/N4": (0.63, 37),   # probes give 0.689, 39
+    "tiny_vgg/mit3/N3": (0.95, 92),   # probes give 1.000, 94
+    "tiny_mlp/mit1/N2": (0.95, 94),   # probes give 1.000, 96
+    "split_resnet/mit3/N2": (0.64, 35),   # probes give 0.697, 37
+    "tiny_resnet/mit3/stash/N2/80": (0.84, 57),   # probes give 0.897, 59
+    "wide/lrNone": (0.38, 0),   # probes give 0.431, 0
+    "wide/lr0.0005": (0.44, 0),   # probes give 0.491, 0
+    "resnet50_64": (0.61, 0),   # probes give 0.660, 0
+    "resnet50_fp32": (0.00, 0),
+    "resnet50/bf16": (0.00, 0),
+}
+SUMMARY = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "parity_summary.txt")
+
+
+def _check(res, K, S, key=None):
+    line = (f"{key or '?'}: strict 1e-5 on {res['strict_pairs']}/{res['pairs']} (tensor, tick) pairs = {res['strict_frac']:.3f}; "
+            f"measured error <= 1e-5 on {res['within_tol_pairs']}/{res['pairs']}; "
+            f"updates under the strict tolerance per stage min {min(res['upd_strict'])} max {max(res['upd_strict'])}; "
+            f"worst tensor error {res['worst']:.3e} at {res['where']} tick {res['tick']}; worst median-over-tensors "
+            f"{res['worst_median']:.2e}; tolerance in force median {res['tol_quantiles'][0]:.1e} 90% {res['tol_quantiles'][1]:.1e} "
+            f"max {res['tol_quantiles'][2]:.1e}; velocity worst {res['v_worst']:.2e}; violations {len(res['violations'])}")
+    print(line, file=sys.stderr, flush=True)
+    if os.path.isdir(os.path.dirname(SUMMARY)):
+        with open(SUMMARY, "a") as f:
+            f.write(line + "\n")
     assert not res["violations"], res["violations"][:3]
     assert len(res["loss_gpu"]) == len(res["loss_cpu"]) == max(0, K - S + 1)
-    assert np.allclose(res["loss_gpu"], res["loss_cpu"], rtol=res["loss_tol"], atol=res["loss_tol"])
-    assert res["v_err"] <= res["v_tol"], (res["v_err"], res["v_tol"])
+    bad = np.nonzero(np.abs(res["loss_gpu"] - res["loss_cpu"]) > res["loss_tol"])[0]
+    assert bad.size == 0, (bad[:5], res["loss_gpu"][bad[:5]], res["loss_cpu"][bad[:5]], res["loss_tol"][bad[:5]])
+    assert not res["v_bad"], res["v_bad"][:3]
+    if key is not None:
+        min_frac, min_upd = COVERAGE[key]
+        assert res["strict_frac"] >= min_frac, (res["strict_frac"], min_frac)
+        assert min(res["upd_strict"]) >= min_upd, (res["upd_strict"], min_upd)
 
 
 @pytest.mark.parametrize("name", ["tiny_mlp", "tiny_vgg", "tiny_resnet", "small_resnet", "odd_resnet", "tiny_bottleneck",
@@ -34,14 +106,14 @@ def test_small_nets_100_ticks(name, mit):
     net = W.config(name)
     K = 100
     res = run_parity(_engine(), net, K, mitigation=mit)
-    _check(res, K, len(net["stages"]))
+    _check(res, K, len(net["stages"]), f"{name}/mit{mit}")
 
 
 @pytest.mark.parametrize("mit", [1, 2])
 def test_single_mitigations(mit):
     net = W.config("tiny_resnet")
     res = run_parity(_engine(), net, 60, mitigation=mit)
-    _check(res, 60, len(net["stages"]))
+    _check(res, 60, len(net["stages"]), f"tiny_resnet/mit{mit}/60")
 
 
 def test_per_step_launch_mode_is_bit_identical():
@@ -61,15 +133,14 @@ def test_per_step_launch_mode_is_bit_identical():
     assert np.array_equal(outs[0][1], outs[1][1])
 
 
-def test_both_kernel_instantiations_are_bit_identical(monkeypatch):
+def test_both_kernel_instantiations_are_bit_identical():
     """k_phase<true> (non-temporal output stores) and k_phase<false> differ in a store hint only."""
     PBEngine = _engine()
     net = W.config("small_resnet")
     xs, ys = W.sample_pool(net)
     outs = []
-    for nt in ("0", "1"):
-        monkeypatch.setenv("PB_NT_STORES", nt)
-        e = PBEngine(net)
+    for nt in (-1, 1):
+        e = PBEngine(net, tuning=dict(nt_stores=nt))
         for t in range(40):
             e.tick(xs[t % len(ys)], ys[t % len(ys)])
         outs.append((e.read_weights(), e.loss_history()))
@@ -98,40 +169,39 @@ def test_resident_pool_equals_host_ticks():
 def test_mlp_config_100_ticks():
     net = W.config("mlp")
     res = run_parity(_engine(), net, 100)
-    _check(res, 100, len(net["stages"]))
+    _check(res, 100, len(net["stages"]), "mlp")
 
 
-def test_resnet20_config_100_ticks():
+@pytest.mark.parametrize("mit", [3, 0])
+def test_resnet20_config_100_ticks(mit):
+    """The headline configuration, every tensor after every tick, with the combined mitigation and as
+    plain delayed SGD with momentum (the ablation the configuration names)."""
     net = W.config("resnet20")
-    res = run_parity(_engine(), net, 100, every=5)
-    _check(res, 100, len(net["stages"]))
+    res = run_parity(_engine(), net, 100, mitigation=mit)
+    _check(res, 100, len(net["stages"]), f"resnet20/mit{mit}")
 
 
 def test_vgg11_config_100_ticks():
     net = W.config("vgg11")
     res = run_parity(_engine(), net, 100, every=5)
-    _check(res, 100, len(net["stages"]))
+    _check(res, 100, len(net["stages"]), "vgg11")
 
 
-def test_wide_config_100_ticks():
-    # 256-channel stages on 8x8 maps: a single ReLU-mask tie moves a GroupNorm-shift
-    # gradient by ~1/64 of a channel's sum and about one tie per sample occurs, so
-    # oracles perturbed by 1e-6 already disagree by ~5e-3 on a few `beta` tensors
-    # from the first update on (and at the configuration's lr the first 100 ticks
-    # are chaotic: loss spikes to ~9).  Checked here at a tenth of the lr: the
-    # tie-aware tolerance on every tensor, plus the median over tensors, which the
-    # few tie-affected tensors cannot move.
+@pytest.mark.parametrize("lr", [None, 0.0005])
+def test_wide_config_100_ticks(lr):
+    """The wide network at its configured learning rate (the one bench.py times) and at a fifth of it.
+    256-channel stages on 8x8 maps: one ReLU decision moves a GroupNorm-shift gradient by ~1/64 of a
+    channel's sum, and with 1.1 M decisions per sample several fall inside the band every tick, so few
+    tensors stay at 1e-5 for long; the per-tensor bounds and the median over tensors carry the test."""
     net = W.config("wide")
-    res = run_parity(_engine(), net, 100, every=5, lr=0.0005)
-    assert res["strict_ticks"] >= 5
-    assert res["median_final"] <= 10 * TOL, res["median_final"]
-    _check(res, 100, len(net["stages"]))
+    res = run_parity(_engine(), net, 100, every=5, lr=lr)
+    _check(res, 100, len(net["stages"]), f"wide/lr{lr}")
 
 
 def test_resnet50_structure_64px_120_ticks():
     net = W.config("resnet50_64")
     res = run_parity(_engine(), net, 120, every=10)
-    _check(res, 120, len(net["stages"]))
+    _check(res, 120, len(net["stages"]), "resnet50_64")
 
 
 @pytest.mark.timeout(900)
@@ -141,7 +211,7 @@ def test_resnet50_config_full_size_110_ticks():
     up to 110 of the last, checked every 22 ticks against the oracle."""
     net = W.config("resnet50_fp32")
     res = run_parity(_engine(), net, 110, every=22)
-    _check(res, 110, len(net["stages"]))
+    _check(res, 110, len(net["stages"]), "resnet50_fp32")
 
 
 @pytest.mark.timeout(900)
@@ -151,14 +221,14 @@ def test_resnet50_config_full_size_bf16_activations():
     net = W.config("resnet50")
     assert net.get("act_dtype") == "bf16"
     res = run_parity(_engine(), net, 104, every=26, perturb=(3e-6, 1e-5))
-    _check(res, 104, len(net["stages"]))
+    _check(res, 104, len(net["stages"]), "resnet50/bf16")
 
 
 def test_reference_kernel_set_matches_too():
     """The plain direct kernels (kernel_set=1) are a second GPU implementation."""
     net = W.config("small_resnet")
     res = run_parity(_engine(), net, 60, engine_kwargs=dict(kernel_set=1))
-    _check(res, 60, len(net["stages"]))
+    _check(res, 60, len(net["stages"]), "small_resnet/kernel_set1/60")
 
 
 @pytest.mark.parametrize("name", ["tiny_vgg", "tiny_resnet", "tiny_bottleneck", "split_resnet"])
@@ -178,7 +248,7 @@ def test_bf16_activation_mode(name):
     net["act_dtype"] = "bf16"
     K = 60
     res = run_parity(_engine(), net, K, mitigation=3, perturb=(3e-6, 1e-5))
-    _check(res, K, len(net["stages"]))
+    _check(res, K, len(net["stages"]), f"{name}/bf16/60")
     # and it is not the fp32 path: the trajectories differ from the fp32 run
     PBEngine = _engine()
     xs, ys = W.sample_pool(net)
@@ -292,7 +362,7 @@ def test_weight_stashing(name, mit):
     net = W.config(name)
     K = 80
     res = run_parity(_engine(), net, K, mitigation=mit, bwd_weights=1)
-    _check(res, K, len(net["stages"]))
+    _check(res, K, len(net["stages"]), f"{name}/mit{mit}/stash/80")
     # it differs from the default (current weights in the backward pass)
     PBEngine = _engine()
     xs, ys = W.sample_pool(net)
@@ -408,3 +478,49 @@ def test_zero_delays_equal_torch_sgd_with_momentum(name):
         e_inf, e_l2, where = rel_errors(w.astype(np.float32), ref, tensor_slices(net))
         assert max(e_inf, e_l2) <= 2e-5, (mit, e_inf, e_l2, where)
         eng.close()
+
+
+@pytest.mark.parametrize("name,N,mit", [("tiny_resnet", 2, 3), ("tiny_resnet", 3, 0), ("small_resnet", 4, 3), ("tiny_vgg", 3, 3),
+                                        ("tiny_mlp", 2, 1), ("split_resnet", 2, 3)])
+def test_update_size_above_one(name, N, mit):
+    """Update size N (Appendix "Small Batch Size Training"): gradients of N consecutive samples added up
+    across ticks, one SC / LWP update with their mean every N-th backward pass, delays counted in updates."""
+    net = W.config(name)
+    K = 100
+    res = run_parity(_engine(), net, K, mitigation=mit, engine_kwargs=dict(update_size=N), oracle_kwargs=dict(update_size=N))
+    _check(res, K, len(net["stages"]), f"{name}/mit{mit}/N{N}")
+    # and it is not the update-size-one trajectory
+    PBEngine = _engine()
+    xs, ys = W.sample_pool(net)
+    outs = []
+    for n in (1, N):
+        e = PBEngine(net, mitigation=mit, update_size=n)
+        for t in range(50):
+            e.tick(xs[t % len(ys)], ys[t % len(ys)])
+        outs.append(e.read_weights())
+        e.close()
+    assert np.abs(outs[0] - outs[1]).max() > 1e-5
+
+
+def test_update_size_in_the_sample_indexed_form_and_with_stashing():
+    """Update size 3 with all delays zero is minibatch SGD with momentum: the library against the oracle's
+    per-sample form (itself pinned to torch.optim.SGD on the mean loss of 3 samples); and with weight
+    stashing in the pipeline."""
+    PBEngine = _engine()
+    net = W.config("tiny_resnet")
+    S = len(net["stages"])
+    xs, ys = W.sample_pool(net)
+    K, N = 36, 3
+    eng = PBEngine(net, delays=[0] * S, update_size=N)
+    for t in range(K):
+        eng.tick(xs[t % len(ys)], ys[t % len(ys)])
+    w_gpu, l_gpu = eng.read_weights(), eng.loss_history()
+    eng.close()
+    hist, losses = O.run_sample_indexed(net, K, xs, ys, delays=[0] * S, update_size=N)
+    assert np.allclose(l_gpu, np.asarray(losses), rtol=1e-4, atol=1e-4)
+    ref = np.concatenate([t.numpy().reshape(-1) for s in range(S) for t in hist[s][K // N][0].values()])
+    from tests.parity_util import rel_errors, tensor_slices
+    e_inf, e_l2, where = rel_errors(w_gpu, ref, tensor_slices(net))
+    assert max(e_inf, e_l2) <= 2e-5, (e_inf, e_l2, where)
+    res = run_parity(PBEngine, net, 80, bwd_weights=1, engine_kwargs=dict(update_size=2), oracle_kwargs=dict(update_size=2))
+    _check(res, 80, S, "tiny_resnet/mit3/stash/N2/80")
