@@ -75,6 +75,15 @@ typedef struct {
   const pb_op* ops;
 } pb_stage;
 
+/* Planner settings a caller may override (all zero = the library's own choices). */
+typedef struct {
+  int32_t tile_target;      /* latency-tiled networks: workgroups a forward GEMM step is split into at least   */
+  int32_t tile_target_bwd;  /* ... and a backward GEMM step                                                     */
+  float tile_budget_us;     /* > 0: tile for throughput with this budget for the longest tile (microseconds,
+                               estimate); < 0: tile for latency whatever the network's size; 0: by size       */
+  int32_t nt_stores;        /* kernel instantiation with non-temporal output stores: 1 on, -1 off, 0 by policy  */
+} pb_tuning;
+
 typedef struct {
   int32_t n_stages;
   const pb_stage* stages;
@@ -97,6 +106,12 @@ typedef struct {
   float lwp_scale;            /* ... and LWP the horizon T = lwp_scale * delays[s]; 0 means 1 for both     */
   int32_t lwp_form;           /* 0 velocity form w_hat = w - lr T v (Eq. lwp_v_form); 1 weight-difference
                                  form w_hat = w + T (w - w_prev) (Eq. lwp_w_form)                          */
+  int32_t update_size;        /* samples per update (Appendix "Small Batch Size Training"; the paper uses 1 = 0
+                                 here).  N > 1: still one sample per stage and tick; a stage adds up the
+                                 gradients of N consecutive samples and applies one update with their mean
+                                 after the last one's backward pass; SC and LWP count the stage's delay in
+                                 updates, delays[s] / N                                                     */
+  const pb_tuning* tuning;    /* NULL = defaults */
 } pb_net_desc;
 
 /* Device bytes pb_init needs for this network (0 on an invalid descriptor). */
@@ -170,7 +185,8 @@ int pb_profile_begin(pb_ctx* ctx, int32_t max_events);
 int pb_profile_end(pb_ctx* ctx, int32_t which, int64_t* n_launches, double* total_ms);
 
 /* Stand-alone launch of the fused update kernel over caller-provided DEVICE
- * arrays of n floats (n a multiple of 1024) with one set of coefficients:
+ * arrays of n floats (n a multiple of 1024, every array 16-byte aligned:
+ * PB_E_INVALID otherwise) with one set of coefficients:
  * v <- m v + g; w <- w - lr (a v + b g); w_hat <- w - lrT v (skipped when
  * w_hat == NULL).  Used to measure the kernel at sizes beyond the caches. */
 int pb_update_standalone(float* w_dev, float* v_dev, const float* g_dev, float* what_dev, int64_t n,

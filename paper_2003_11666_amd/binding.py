@@ -33,13 +33,19 @@ class _Stage(C.Structure):
     _fields_ = [("n_ops", C.c_int32), ("ops", C.POINTER(_Op))]
 
 
+class _Tuning(C.Structure):
+    _fields_ = [("tile_target", C.c_int32), ("tile_target_bwd", C.c_int32), ("tile_budget_us", C.c_float),
+                ("nt_stores", C.c_int32)]
+
+
 class _NetDesc(C.Structure):
     _fields_ = [("n_stages", C.c_int32), ("stages", C.POINTER(_Stage)),
                 ("in_c", C.c_int32), ("in_h", C.c_int32), ("in_w", C.c_int32),
                 ("n_classes", C.c_int32), ("mitigation", C.c_int32), ("bwd_weights", C.c_int32),
                 ("act_dtype", C.c_int32), ("loss_capacity", C.c_int32), ("kernel_set", C.c_int32),
                 ("device_arena", C.c_void_p), ("arena_bytes", C.c_size_t), ("stream", C.c_void_p),
-                ("sc_scale", C.c_float), ("lwp_scale", C.c_float), ("lwp_form", C.c_int32)]
+                ("sc_scale", C.c_float), ("lwp_scale", C.c_float), ("lwp_form", C.c_int32),
+                ("update_size", C.c_int32), ("tuning", C.POINTER(_Tuning))]
 
 
 def lib_path():
@@ -105,7 +111,8 @@ def _check(lib, rc):
     return rc
 
 
-def marshal_net(net, mitigation=3, bwd_weights=0, loss_capacity=0, kernel_set=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v"):
+def marshal_net(net, mitigation=3, bwd_weights=0, loss_capacity=0, kernel_set=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v",
+                update_size=1, tuning=None):
     """dict descriptor (pb_workloads) -> pb_net_desc; returns (desc, keepalive)."""
     keep = []
     stages = (_Stage * len(net["stages"]))()
@@ -128,6 +135,11 @@ def marshal_net(net, mitigation=3, bwd_weights=0, loss_capacity=0, kernel_set=0,
     d.act_dtype = {"fp32": 0, "bf16": 1}[net.get("act_dtype", "fp32")]
     d.loss_capacity = loss_capacity
     d.kernel_set = kernel_set
+    d.update_size = update_size
+    if tuning:
+        tn = _Tuning(**tuning)
+        keep.append(tn)
+        d.tuning = C.pointer(tn)
     return d, keep
 
 
@@ -146,10 +158,12 @@ class PBEngine:
     """pb_init / pb_tick / pb_run_resident / pb_read_weights / pb_loss_history."""
 
     def __init__(self, net, lr=None, momentum=None, seed=42, mitigation=3, delays=None,
-                 bwd_weights=0, loss_capacity=0, torch_arena=True, kernel_set=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v"):
+                 bwd_weights=0, loss_capacity=0, torch_arena=True, kernel_set=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v",
+                 update_size=1, tuning=None):
         self.lib = load_library()
         self.net = net
-        desc, self._keep = marshal_net(net, mitigation, bwd_weights, loss_capacity, kernel_set, sc_scale, lwp_scale, lwp_form)
+        desc, self._keep = marshal_net(net, mitigation, bwd_weights, loss_capacity, kernel_set, sc_scale, lwp_scale, lwp_form,
+                                       update_size, tuning)
         dl = None
         if delays is not None:
             dl = (C.c_int32 * len(delays))(*delays)

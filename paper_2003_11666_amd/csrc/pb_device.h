@@ -115,6 +115,8 @@ struct StepDesc {
   int32_t pdepth, plag, pstride;   // that ring: slots, lag of the slot this step uses, floats per slot
   int32_t gparts, gpstride; // partial weight gradients of the stage: their number, floats between two of them
                             // (K_GEMM backward weights writes one of them, K_UPDATE sums them in order)
+  int32_t upd_n, upd_t0;    // K_UPDATE: update size N (gradients of N consecutive samples per update) and the tick of the
+                            // stage's first backward pass
   int32_t grain;            // > 0: streaming form of an elementwise step, floats per workgroup (K_COPY, K_GNB_APPLY);
                             // K_GNB_REDUCE: 1 = one wavefront per channel
   GemmCfg g;     // main operand set of a K_GEMM step
@@ -137,6 +139,8 @@ struct StepDesc {
   float* gb;
   float* ggamma;
   float* gbeta;
+  float* gacc;         // K_UPDATE with an update size above one: gradients added up since the stage's latest update
+  const float* what0;  // ... and slot 0 of the stage's ring of predicted weights (never moved to the tick's slot)
   float* part;         // per-channel partial sums of the GN backward
   float* loss_log;
   int32_t* labels;     // label ring [n_stages]

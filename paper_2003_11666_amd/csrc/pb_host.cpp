@@ -73,6 +73,7 @@ int parse_net(const pb_net_desc* net, std::vector<Stage>& out) {
   if (net->kernel_set < 0 || net->kernel_set > 1) return fail(PB_E_INVALID, "kernel_set must be 0 or 1");
   if (net->lwp_form != 0 && net->lwp_form != 1) return fail(PB_E_INVALID, "lwp_form must be 0 or 1");
   if (!(net->sc_scale >= 0.f) || !(net->lwp_scale >= 0.f)) return fail(PB_E_INVALID, "sc_scale and lwp_scale must be >= 0");
+  if (net->update_size < 0 || net->update_size > 65536) return fail(PB_E_INVALID, "update_size must be 0 (= 1) .. 65536");
   const int S = net->n_stages;
   out.assign(S, Stage());
   int C = net->in_c, H = net->in_h, W = net->in_w;
@@ -241,6 +242,7 @@ struct StageBufs {
 struct Layout {
   int64_t P = 0;                      // padded parameter count
   int64_t w = 0, v = 0, g = 0;
+  int64_t gacc = -1;                  // update size above one: gradients added up since each stage's latest update
   std::vector<int64_t> what;          // per stage: ring [De - D + 2][padded] of predicted-weight versions
   std::vector<StageBufs> sb;
   int64_t staging = 0, labels = 0, loss = 0, globals = 0, zero = 0;
@@ -280,7 +282,7 @@ int st_stride_of(const Stage& s) { return (2 * s.G + 2 * s.gnC() + 63) / 64 * 64
 
 int what_depth(const Stage& a, bool stash) { return stash ? a.De + 2 : a.De - a.D + 2; }
 
-void plan_arena(const std::vector<Stage>& st, bool stash, int loss_cap, Layout& L, Plan& pl, bool use_aring) {
+void plan_arena(const std::vector<Stage>& st, bool stash, int loss_cap, Layout& L, Plan& pl, bool use_aring, int update_size) {
   const int S = (int)st.size();
   L.P = 0;
   for (const Stage& s : st) L.P += s.padded;
@@ -291,6 +293,7 @@ void plan_arena(const std::vector<Stage>& st, bool stash, int loss_cap, Layout& 
   // updated in place: their only readers in a tick (the stage's backward steps) come before the
   // stage's update.  Without weight prediction the forward copy simply equals the master weights.
   L.w = pl.alloc(L.P); L.v = pl.alloc(L.P); L.g = pl.alloc(L.P);
+  if (update_size > 1) L.gacc = pl.alloc(L.P);
   L.what.assign(S, 0);
   // Weight stashing (the backward pass uses the forward's predicted weights, Eq. sgdpb_weight_stash):
   // the version the forward pass of a sample read has to survive until its backward pass, De + 2 slots.
@@ -354,6 +357,8 @@ struct pb_ctx {
   double sc_scale = 1.0, lwp_scale = 1.0;   // over-compensation factors on the stage delay
   bool stash = false;  // weight stashing: the backward pass reads the predicted weights its forward pass used
   bool bf16 = false;   // bf16 activation mode: tensors that cross a stage boundary are rounded to bf16
+  int N = 1;           // update size: samples per update
+  pb_tuning tune = {0, 0, 0.f, 0};
   std::vector<StepDesc> steps;         // sorted by phase
   std::vector<int64_t> rec_first;      // per step: index of its first per-workgroup record
   Plan* plan = nullptr;                // arena allocator while the step table is compiled
@@ -369,6 +374,13 @@ struct pb_ctx {
   const int32_t* pool_labels = nullptr;
   int n_pool = 0;
   int idx_base = 0;
+  // host-fed ticks: the sample goes through a ring of pinned host buffers, so that the copy to the
+  // device is asynchronous and the caller's buffer is free again when pb_tick returns
+  static constexpr int N_PINNED = 8;
+  float* pinned[N_PINNED] = {};
+  hipEvent_t pinned_done[N_PINNED] = {};
+  bool pinned_used[N_PINNED] = {};
+  int pinned_next = 0;
   // profiling
   bool profiling = false;
   int max_events = 0;
@@ -379,6 +391,15 @@ struct pb_ctx {
 };
 
 namespace {
+
+// the settings of the descriptor that shape the plan
+void take_settings(pb_ctx* c, const pb_net_desc* net) {
+  c->kernel_set = net->kernel_set;
+  c->bf16 = net->act_dtype == 1;
+  c->stash = net->bwd_weights == 1;
+  c->N = net->update_size > 1 ? net->update_size : 1;
+  if (net->tuning) c->tune = *net->tuning;
+}
 
 TRef ring(const pb_ctx* c, int64_t off, int depth, int stride, int lag) {
   TRef r;
@@ -713,8 +734,9 @@ bool head_fits(int C, int HW, int K, bool gap, int G) {
 // Coefficients of the stage's update (Eqs. gscv, gscw, scd, lwp_v_form) by mitigation mode.
 void set_update_coeffs(const pb_ctx* c, const Stage& a, StepDesc* d) {
   double ca = 1.0, cb = 0.0;
-  if (c->mitigation == 1 || c->mitigation == 3) sc_coeffs((double)c->m, c->sc_scale * a.De, &ca, &cb);
-  const double T = (c->mitigation >= 2) ? c->lwp_scale * a.De : 0.0;
+  const double Du = c->N > 1 ? (double)a.De / c->N : (double)a.De;   // the stage's delay counted in updates
+  if (c->mitigation == 1 || c->mitigation == 3) sc_coeffs((double)c->m, c->sc_scale * Du, &ca, &cb);
+  const double T = (c->mitigation >= 2) ? c->lwp_scale * Du : 0.0;
   d->fa = (float)ca; d->fb = (float)cb; d->flrT = (float)((double)c->lr * T); d->flr = c->lr; d->fm = c->m;
   if (c->lwp_w) { d->flags |= F_LWP_W; d->flrT = (float)T; }   // w_hat = w' + T (w' - w)
 }
@@ -770,12 +792,11 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   // all stages run concurrently: aim at a few workgroups per compute unit over
   // the whole phase rather than per step
   g_tile_target = std::max(4, std::min(32, 960 / (3 * S)));
-  if (const char* e = getenv("PB_TILE_TARGET")) g_tile_target = std::max(1, atoi(e));
+  if (c->tune.tile_target > 0) g_tile_target = c->tune.tile_target;
   // the backward phase holds two GEMM steps per stage: fewer tiles each, so that the phase's workgroups
   // fit the 512 a chip holds at a time (ResNet-20: 16 / 9 measured 33.4 k ticks/s, 16 / 12 30.0 k, 16 / 8 27.0 k)
   g_tile_target_bwd = std::max(4, std::min(32, 540 / (3 * S)));
-  if (getenv("PB_TILE_TARGET")) g_tile_target_bwd = g_tile_target;
-  if (const char* e = getenv("PB_TILE_TARGET_BWD")) g_tile_target_bwd = std::max(1, atoi(e));
+  if (c->tune.tile_target_bwd > 0) g_tile_target_bwd = c->tune.tile_target_bwd;
   // Networks whose tick is long compared with a launch are tiled for throughput:
   // the budget for the longest tile is the duration of a GEMM phase if the tick's
   // 6 flops per multiply-accumulate ran at a third of the fp32 MFMA peak, spread
@@ -788,7 +809,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     }
     const double tick_us = 6.0 * macs / 50e6;
     g_tile_budget_us = tick_us >= 10.0 ? std::max(16.0, 0.65 * tick_us) : 0.0;
-    if (const char* e = getenv("PB_TILE_BUDGET_US")) g_tile_budget_us = atof(e);
+    if (c->tune.tile_budget_us > 0.f) g_tile_budget_us = c->tune.tile_budget_us;
+    else if (c->tune.tile_budget_us < 0.f) g_tile_budget_us = 0.0;
   }
   const Layout& L = c->L;
   std::vector<int> bwd0(S, 0);   // per stage: phase its backward chain starts in
@@ -1178,7 +1200,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         // updated one phase earlier and no phase is left that holds nothing but updates
         // (not with weight stashing: the step would need two slots of the ring, the stashed scale it
         // reads and the new version it writes)
-        if (!c->stash) {
+        // (nor with an update size above one: the gradients are then added up across ticks by the update step)
+        if (!c->stash && c->N == 1) {
           d.flags |= F_UPD_GN | F_ALWAYS;
           set_update_coeffs(c, a, &d);
           d.v = c->f(L.v + a.off + a.o_gamma);
@@ -1273,6 +1296,12 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     d.wp = d.w; d.b = d.v;                             // master weights and velocity in place
     d.what = c->f(L.what[s]);
     d.pmask = PF_WHAT; d.pdepth = what_depth(a, c->stash); d.plag = -1; d.pstride = (int)a.padded;
+    if (c->N > 1) {
+      d.upd_n = c->N;
+      d.upd_t0 = c->sequential ? 0 : 2 * (S - 1) - s;
+      d.gacc = c->f(L.gacc + a.off);
+      d.what0 = c->f(L.what[s]);
+    }
     d.n = (int)(gn_fused ? a.o_gamma : a.padded);      // o_gamma is a multiple of 4
     d.ntiles = (int)cdiv(d.n, UPD_TILE);
     if (d.n > 0) out.push_back({last_grad_phase + 1, d});
@@ -1283,7 +1312,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   // reduction; as the last thing a phase waits for it is quicker with plain stores (the
   // 4-stage MLP).
   c->nt_stores = g_tile_budget_us <= 0 && c->kernel_set == 0;
-  if (const char* e = getenv("PB_NT_STORES")) c->nt_stores = atoi(e) != 0;   // (tests: both instantiations, same arithmetic)
+  if (c->tune.nt_stores) c->nt_stores = c->tune.nt_stores > 0;   // (tests: both instantiations, same arithmetic)
   // (forward and backward-data GEMMs split over their reduction, several column tiles per workgroup and
   // flattened 1x1 layers exist only in the other instantiation)
   for (auto& pr : out)
@@ -1484,6 +1513,11 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
              d.what != nullptr;
         if (d.gparts > 1)
           ok = ok && d.gpstride >= d.n && d.gpstride % 4 == 0 && ptr_ok(d.gw, (int64_t)(d.gparts - 1) * d.gpstride + d.n);
+        if (d.upd_n > 1)
+          ok = ok && d.upd_t0 >= 0 && ptr_ok(d.gacc, d.n) && d.pmask == PF_WHAT && d.plag == -1 &&
+               ptr_ok(d.what0 + (int64_t)(d.pdepth - 1) * d.pstride, d.n) && d.what0 == d.what;
+        else
+          ok = ok && d.upd_n <= 1;
         break;
       case K_HEAD: {
         const int64_t cv = (d.flags & F_DU_GAP) ? d.C : in;
@@ -1676,6 +1710,8 @@ struct ScopedEv {
 };
 
 int run_one_tick(pb_ctx* c, const float* staging, int label) {
+  // the kernels index every ring with a 32-bit tick counter
+  if (c->ticks >= (int64_t)0x7fffff00) return fail(PB_E_UNSUPPORTED, "tick counter exhausted (2^31 ticks): start a new context");
   const int k = (int)c->ticks;   // t_base stays 0 on this path
   if (c->launch_mode == 0) {
     for (const Phase& p : c->phases) {
@@ -1711,14 +1747,12 @@ size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays) {
   if (parse_net(net, st) != PB_OK || check_delays(st, delays, &sequential) != PB_OK) return 0;
   pb_ctx tmp;
   tmp.st = st; tmp.S = (int)st.size();
-  tmp.kernel_set = net->kernel_set;
-  tmp.bf16 = net->act_dtype == 1;
-  tmp.stash = net->bwd_weights == 1;
+  take_settings(&tmp, net);
   tmp.sequential = sequential;
   const int cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   Plan pl;
   Layout L;
-  plan_arena(st, net->bwd_weights == 1, cap, L, pl, net->kernel_set == 0);
+  plan_arena(st, net->bwd_weights == 1, cap, L, pl, net->kernel_set == 0, tmp.N);
   // step table, prefix, chunk map and segment table live in the arena too
   tmp.L = L; tmp.loss_cap = cap; tmp.arena = nullptr;
   tmp.labels_dev = (int32_t*)tmp.f(L.labels);
@@ -1736,10 +1770,11 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   std::vector<Stage> st;
   if (parse_net(net, st) != PB_OK) return PB_E_INVALID;
   pb_ctx tmp;
-  tmp.st = st; tmp.S = (int)st.size(); tmp.kernel_set = net->kernel_set; tmp.bf16 = net->act_dtype == 1; tmp.stash = net->bwd_weights == 1;
+  tmp.st = st; tmp.S = (int)st.size();
+  take_settings(&tmp, net);
   const int lcap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   Plan pl;
-  plan_arena(st, net->bwd_weights == 1, lcap, tmp.L, pl, net->kernel_set == 0);
+  plan_arena(st, net->bwd_weights == 1, lcap, tmp.L, pl, net->kernel_set == 0, tmp.N);
   tmp.loss_cap = lcap;
   std::vector<std::pair<int, StepDesc>> steps;
   tmp.plan = &pl;
@@ -1789,9 +1824,7 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   pb_ctx* c = new pb_ctx();
   c->st = st; c->S = (int)st.size();
   c->mitigation = net->mitigation; c->lr = lr; c->m = momentum;
-  c->kernel_set = net->kernel_set;
-  c->bf16 = net->act_dtype == 1;
-  c->stash = net->bwd_weights == 1;
+  take_settings(c, net);
   c->lwp_w = net->lwp_form == 1;
   c->sequential = sequential;
   c->sc_scale = net->sc_scale > 0.f ? net->sc_scale : 1.0;
@@ -1820,7 +1853,7 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   INIT_TRY(hipMemsetAsync(base, 0, need, c->stream));
 
   Plan pl;
-  plan_arena(st, net->bwd_weights == 1, c->loss_cap, c->L, pl, net->kernel_set == 0);
+  plan_arena(st, net->bwd_weights == 1, c->loss_cap, c->L, pl, net->kernel_set == 0, c->N);
   c->labels_dev = (int32_t*)c->f(c->L.labels);
   c->globals_dev = (Globals*)c->f(c->L.globals);
   c->zero_dev = (int32_t*)c->f(c->L.zero);
@@ -1867,6 +1900,13 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   for (auto& tb : c->tables)
     INIT_TRY(hipMemcpyAsync(c->f(tb.first), tb.second.data(), sizeof(int32_t) * tb.second.size(), hipMemcpyHostToDevice, c->stream));
   INIT_TRY(hipStreamSynchronize(c->stream));
+  {
+    const size_t bytes = sizeof(float) * st[0].in_elems();
+    for (int i = 0; i < pb_ctx::N_PINNED; ++i) {
+      INIT_TRY(hipHostMalloc((void**)&c->pinned[i], bytes, hipHostMallocDefault));
+      INIT_TRY(hipEventCreateWithFlags(&c->pinned_done[i], hipEventDisableTiming));
+    }
+  }
 #undef INIT_TRY
   *out = c;
   return PB_OK;
@@ -1876,7 +1916,18 @@ int pb_tick(pb_ctx* c, const float* sample, int32_t label) {
   if (!c || !sample) return fail(PB_E_INVALID, "NULL argument");
   if (label < 0 || label >= c->st.back().K) return fail(PB_E_INVALID, "label %d out of range", label);
   float* staging = c->f(c->L.staging);
-  HIP_TRY(hipMemcpyAsync(staging, sample, sizeof(float) * c->st[0].in_elems(), hipMemcpyHostToDevice, c->stream));
+  const size_t bytes = sizeof(float) * c->st[0].in_elems();
+  if (c->pinned[0]) {
+    const int i = c->pinned_next;
+    c->pinned_next = (i + 1) % pb_ctx::N_PINNED;
+    if (c->pinned_used[i]) HIP_TRY(hipEventSynchronize(c->pinned_done[i]));   // its copy of N_PINNED ticks ago has landed
+    memcpy(c->pinned[i], sample, bytes);
+    HIP_TRY(hipMemcpyAsync(staging, c->pinned[i], bytes, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipEventRecord(c->pinned_done[i], c->stream));
+    c->pinned_used[i] = true;
+  } else {
+    HIP_TRY(hipMemcpyAsync(staging, sample, bytes, hipMemcpyHostToDevice, c->stream));
+  }
   return run_one_tick(c, staging, label);
 }
 
@@ -1965,6 +2016,8 @@ int pb_update_standalone(float* w, float* v, const float* g, float* what, int64_
                          float a, float b, float lrT, void* stream) {
   if (!w || !v || !g || n <= 0 || n % UPD_CHUNK) return fail(PB_E_INVALID, "n must be a positive multiple of %d", UPD_CHUNK);
   if (n / UPD_CHUNK > 0x7fffffff) return fail(PB_E_INVALID, "n too large");
+  // the kernel moves 16 bytes per access
+  if (((uintptr_t)w | (uintptr_t)v | (uintptr_t)g | (uintptr_t)what) % 16) return fail(PB_E_INVALID, "arrays must be 16-byte aligned");
   launch_update_flat(w, v, g, what, n, lr, m, a, b, lrT, (hipStream_t)stream);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PB_E_HIP, "kernel launch failed: %s", hipGetErrorString(e));
@@ -1997,6 +2050,10 @@ void pb_destroy(pb_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   for (auto& e : c->evs) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
   for (auto& e : c->ev_pool) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+  for (int i = 0; i < pb_ctx::N_PINNED; ++i) {
+    if (c->pinned[i]) (void)hipHostFree(c->pinned[i]);
+    if (c->pinned_done[i]) (void)hipEventDestroy(c->pinned_done[i]);
+  }
   if (c->own_arena && c->arena) (void)hipFree(c->arena);
   delete c;
 }

@@ -1106,7 +1106,7 @@ __device__ __forceinline__ void step_ingest(const LDesc& d, int tile, int t, con
 // other (d.what), so the update may run beside forward work of the same tick
 // as soon as the stage's gradients are complete.  Master weights and velocity
 // (read d.w, d.v; written d.wp, d.b) are updated in place.
-__device__ __forceinline__ void step_update(const LDesc& d, int tile, const bool nt_kernel) {
+__device__ __forceinline__ void step_update(const LDesc& d, int tile, int t, const bool nt_kernel) {
   // the step streams 24 bytes per parameter and nothing else: what it needs is bytes in
   // flight, so every thread requests its 8 vectors of all three arrays before using any.
   // Plain accesses: the parameter arrays of the VGG-11 and wide configurations fit the
@@ -1146,6 +1146,38 @@ __device__ __forceinline__ void step_update(const LDesc& d, int tile, const bool
   gv4* vo = (gv4*)(float*)d.b;
   gv4* wo = (gv4*)(float*)d.wp;
   gv4* ho = (gv4*)d.what;
+  // Update size N above one: the gradients of N consecutive samples are added up (d.gacc) and one
+  // update with their mean is applied after the backward pass of the last of them.  On every other
+  // tick the parameters stand still and the predicted weights are carried over from the slot of this
+  // tick to the slot of the next one.
+  const int N = UNI(d.upd_n);
+  if (N > 1) {
+    const int j = t - UNI(d.upd_t0);                    // sample whose gradient arrived in this tick
+    const int pos = j >= 0 ? j % N : -1;
+    gv4* ap = (gv4*)d.gacc;
+    if (pos > 0) {
+#pragma unroll
+      for (int u = 0; u < UU; ++u) {
+        const int i = i0 + u * BLK;
+        if (i < n4) gv[u] += ap[i];
+      }
+    }
+    if (pos != N - 1) {
+      const gv4* hs = (const gv4*)(d.what0 + (size_t)(t % UNI(d.pdepth)) * (size_t)UNI(d.pstride));
+#pragma unroll
+      for (int u = 0; u < UU; ++u) {
+        const int i = i0 + u * BLK;
+        if (i < n4) {
+          if (pos >= 0) ap[i] = gv[u];
+          if (ho) ho[i] = hs[i];
+        }
+      }
+      return;
+    }
+    const float inv = 1.0f / (float)N;
+#pragma unroll
+    for (int u = 0; u < UU; ++u) gv[u] *= inv;
+  }
 #pragma unroll
   for (int u = 0; u < UU; ++u) {
     const int i = i0 + u * BLK;
@@ -1927,7 +1959,7 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     case K_GEMM: step_gemm(d, tile, t, smem, NT); break;
     case K_BIAS_GRAD: step_bias_grad(d, tile, t); break;
     case K_INGEST: step_ingest(d, tile, t, G, k, sample_override, label_override); break;
-    case K_UPDATE: step_update(d, tile, NT); break;
+    case K_UPDATE: step_update(d, tile, t, NT); break;
     case K_HEAD: step_head(d, t, red, smem, NT); break;
     case K_GN_BWD: step_gn_bwd(d, tile, t, live, smem, NT); break;
     default: break;
