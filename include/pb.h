@@ -136,6 +136,25 @@ size_t pb_arena_bytes(const pb_net_desc* net, const int32_t* delays);
 int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float lr, float momentum,
             uint64_t seed);
 
+/* pb_init for callers that cannot allocate device memory (code under HIP graph
+ * capture set-up, tight serving loops, harnesses that forbid hipMalloc): the
+ * same context, the same kernels, but the arena -- weights, velocities,
+ * gradients, activation rings, partial sums, step tables -- lies in a device
+ * array that is part of the library itself, pb_static_arena_bytes() = 64 MiB
+ * per GPU, held by every GPU the library runs on until the process ends.
+ * Calls no hipMalloc / hipFree and no allocating library routine; the array
+ * is cleared by a kernel.  net->device_arena must be NULL.  A network whose
+ * pb_arena_bytes exceeds the array is refused with PB_E_NOMEM (ResNet-20 at
+ * 32x32 needs 55 MiB with the default loss_capacity; VGG-11 and larger do not
+ * fit: use pb_init).  All contexts built by this call on one GPU would share
+ * that GPU's array -- overlapping use would race --, so a second call on the
+ * same GPU is refused with PB_E_UNSUPPORTED until pb_destroy has released the
+ * first context.  The array keeps the previous context's contents until the
+ * next call clears it.  Everything else is as for pb_init. */
+int pb_init_static(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float lr, float momentum,
+                   uint64_t seed);
+size_t pb_static_arena_bytes(void);
+
 /* One pipeline time step: feeds `sample` (host, in_c*in_h*in_w floats) with
  * its class label, runs every stage's forward and backward work and the fused
  * update.  The sample is copied before the call returns; GPU work is

@@ -13,7 +13,7 @@ _LIB = None
 
 OP_KIND = {"linear": 0, "conv": 1, "gn": 2, "relu": 3, "maxpool": 4, "gap": 5, "add": 6, "ce": 7}
 
-EXPORTS = ["pb_arena_bytes", "pb_init", "pb_tick", "pb_run_resident", "pb_read_weights",
+EXPORTS = ["pb_arena_bytes", "pb_init", "pb_init_static", "pb_static_arena_bytes", "pb_tick", "pb_run_resident", "pb_read_weights",
            "pb_read_velocity", "pb_loss_history", "pb_num_params", "pb_num_ticks",
            "pb_set_launch_mode", "pb_plan_summary", "pb_profile_begin", "pb_profile_end", "pb_update_standalone",
            "pb_scale_hyperparameters",
@@ -70,6 +70,10 @@ def load_library():
     lib.pb_arena_bytes.argtypes = [C.POINTER(_NetDesc), ip]
     lib.pb_init.restype = C.c_int
     lib.pb_init.argtypes = [C.POINTER(C.c_void_p), C.POINTER(_NetDesc), ip, C.c_float, C.c_float, C.c_uint64]
+    lib.pb_init_static.restype = C.c_int
+    lib.pb_init_static.argtypes = lib.pb_init.argtypes
+    lib.pb_static_arena_bytes.restype = C.c_size_t
+    lib.pb_static_arena_bytes.argtypes = []
     lib.pb_tick.restype = C.c_int
     lib.pb_tick.argtypes = [C.c_void_p, fp, C.c_int32]
     lib.pb_run_resident.restype = C.c_int
@@ -159,7 +163,7 @@ class PBEngine:
 
     def __init__(self, net, lr=None, momentum=None, seed=42, mitigation=3, delays=None,
                  bwd_weights=0, loss_capacity=0, torch_arena=True, kernel_set=0, sc_scale=1.0, lwp_scale=1.0, lwp_form="v",
-                 update_size=1, tuning=None):
+                 static_arena=False, update_size=1, tuning=None):
         self.lib = load_library()
         self.net = net
         desc, self._keep = marshal_net(net, mitigation, bwd_weights, loss_capacity, kernel_set, sc_scale, lwp_scale, lwp_form,
@@ -168,7 +172,10 @@ class PBEngine:
         if delays is not None:
             dl = (C.c_int32 * len(delays))(*delays)
         self._arena = None
-        if torch_arena:
+        if static_arena:
+            import torch
+            desc.stream = torch.cuda.current_stream().cuda_stream
+        elif torch_arena:
             import torch
             need = self.lib.pb_arena_bytes(C.byref(desc), dl)
             if need == 0:
@@ -181,7 +188,8 @@ class PBEngine:
         self.ctx = C.c_void_p()
         lr = net["lr"] if lr is None else lr
         momentum = net["momentum"] if momentum is None else momentum
-        _check(self.lib, self.lib.pb_init(C.byref(self.ctx), C.byref(desc), dl, lr, momentum, seed))
+        init = self.lib.pb_init_static if static_arena else self.lib.pb_init
+        _check(self.lib, init(C.byref(self.ctx), C.byref(desc), dl, lr, momentum, seed))
         self.n_params = self.lib.pb_num_params(self.ctx)
         self._in_elems = net["in_c"] * net["in_h"] * net["in_w"]
 

@@ -170,5 +170,11 @@ void launch_update_flat(float* w, float* v, const float* g, float* what, int64_t
                         float a, float b, float lrT, hipStream_t s);
 void launch_advance(Globals* G, int dt, int didx, hipStream_t s);
 void launch_set_globals(Globals* G, Globals val, hipStream_t s);
+void launch_fill_zero(void* p, size_t bytes, hipStream_t s);   // bytes a multiple of 16, p 16-byte aligned
+
+// The library's own device array for contexts that must not allocate (pb_init_static): its
+// address on the current device (looked up once per device) and that device's ordinal.
+constexpr size_t STATIC_ARENA_BYTES = (size_t)64 << 20;
+hipError_t static_arena(void** ptr, int* device);
 
 }  // namespace pb

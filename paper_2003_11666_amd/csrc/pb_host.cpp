@@ -19,6 +19,11 @@ namespace {
 
 thread_local std::string g_err;
 
+// contexts built by pb_init_static share one static device array per GPU: one at a time
+constexpr int MAX_STATIC_DEVS = 64;
+bool g_static_busy[MAX_STATIC_DEVS] = {};
+int g_static_dev = -1;   // device of the pb_init_static call in progress
+
 int fail(int code, const char* fmt, ...) {
   char buf[512];
   va_list ap;
@@ -347,6 +352,7 @@ struct pb_ctx {
   Layout L;
   float* arena = nullptr;
   bool own_arena = false;
+  int static_dev = -1;       // >= 0: the context lives in the library's static arena of that device
   hipStream_t stream = nullptr;
   int64_t ticks = 0;
   int launch_mode = 0;
@@ -1806,8 +1812,14 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   return (int64_t)o.size() + 1;
 }
 
-int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float lr, float momentum,
-            uint64_t seed) {
+}  // extern "C"
+
+namespace {
+
+// pb_init and pb_init_static.  static_arena: the context lives in the library's own
+// device array (handed in as base / base_bytes) and nothing is allocated or freed on the device.
+int init_common(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float lr, float momentum,
+                uint64_t seed, void* base, size_t base_bytes, bool static_arena) {
   if (!out) return fail(PB_E_INVALID, "out is NULL");
   *out = nullptr;
   std::vector<Stage> st;
@@ -1832,9 +1844,15 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   c->loss_cap = net->loss_capacity > 0 ? net->loss_capacity : (1 << 20);
   c->stream = (hipStream_t)net->stream;
   for (const Stage& a : st) c->n_params += a.n_params;
-  void* base = net->device_arena;
-  if (base) {
-    if (net->arena_bytes < need) { delete c; return fail(PB_E_NOMEM, "arena has %zu bytes, %zu needed", net->arena_bytes, need); }
+  if (static_arena) {
+    if (need > base_bytes) {
+      delete c;
+      return fail(PB_E_NOMEM, "this network needs %zu bytes of device memory, the library's static arena holds %zu: use pb_init",
+                  need, base_bytes);
+    }
+    c->static_dev = g_static_dev;
+  } else if (base) {
+    if (base_bytes < need) { delete c; return fail(PB_E_NOMEM, "arena has %zu bytes, %zu needed", base_bytes, need); }
     if ((uintptr_t)base % 256) { delete c; return fail(PB_E_INVALID, "arena must be 256-byte aligned"); }
   } else {
     if (hipMalloc(&base, need) != hipSuccess) { delete c; return fail(PB_E_NOMEM, "hipMalloc of %zu bytes failed", need); }
@@ -1850,7 +1868,14 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
       return PB_E_HIP;                                                                  \
     }                                                                                   \
   } while (0)
-  INIT_TRY(hipMemsetAsync(base, 0, need, c->stream));
+  if (static_arena) {
+    // the array keeps the previous context's contents: everything must start at zero (a fill kernel,
+    // so that the call stays free of runtime memory operations that may allocate)
+    launch_fill_zero(base, (need + 15) / 16 * 16, c->stream);
+    INIT_TRY(hipGetLastError());
+  } else {
+    INIT_TRY(hipMemsetAsync(base, 0, need, c->stream));
+  }
 
   Plan pl;
   plan_arena(st, net->bwd_weights == 1, c->loss_cap, c->L, pl, net->kernel_set == 0, c->N);
@@ -1900,7 +1925,7 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
   for (auto& tb : c->tables)
     INIT_TRY(hipMemcpyAsync(c->f(tb.first), tb.second.data(), sizeof(int32_t) * tb.second.size(), hipMemcpyHostToDevice, c->stream));
   INIT_TRY(hipStreamSynchronize(c->stream));
-  {
+  if (!static_arena) {
     const size_t bytes = sizeof(float) * st[0].in_elems();
     for (int i = 0; i < pb_ctx::N_PINNED; ++i) {
       INIT_TRY(hipHostMalloc((void**)&c->pinned[i], bytes, hipHostMallocDefault));
@@ -1910,6 +1935,35 @@ int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float l
 #undef INIT_TRY
   *out = c;
   return PB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pb_init(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float lr, float momentum,
+            uint64_t seed) {
+  if (!net) return fail(PB_E_INVALID, "empty network");
+  return init_common(out, net, delays, lr, momentum, seed, net->device_arena, net->arena_bytes, false);
+}
+
+size_t pb_static_arena_bytes(void) { return STATIC_ARENA_BYTES; }
+
+int pb_init_static(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, float lr, float momentum,
+                   uint64_t seed) {
+  if (!net) return fail(PB_E_INVALID, "empty network");
+  if (net->device_arena) return fail(PB_E_INVALID, "pb_init_static takes no device_arena: it uses the library's own");
+  void* base = nullptr;
+  int dev = -1;
+  const hipError_t e = static_arena(&base, &dev);
+  if (e != hipSuccess) return fail(PB_E_HIP, "static arena: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= MAX_STATIC_DEVS) return fail(PB_E_UNSUPPORTED, "device ordinal %d", dev);
+  if (g_static_busy[dev])
+    return fail(PB_E_UNSUPPORTED, "the static arena of device %d is held by another context: destroy it first", dev);
+  g_static_dev = dev;
+  const int rc = init_common(out, net, delays, lr, momentum, seed, base, STATIC_ARENA_BYTES, true);
+  if (rc == PB_OK) g_static_busy[dev] = true;
+  return rc;
 }
 
 int pb_tick(pb_ctx* c, const float* sample, int32_t label) {
@@ -1926,6 +1980,7 @@ int pb_tick(pb_ctx* c, const float* sample, int32_t label) {
     HIP_TRY(hipEventRecord(c->pinned_done[i], c->stream));
     c->pinned_used[i] = true;
   } else {
+    // (a context that must not allocate has no pinned buffers: the runtime stages the pageable copy itself)
     HIP_TRY(hipMemcpyAsync(staging, sample, bytes, hipMemcpyHostToDevice, c->stream));
   }
   return run_one_tick(c, staging, label);
@@ -2055,6 +2110,7 @@ void pb_destroy(pb_ctx* c) {
     if (c->pinned_done[i]) (void)hipEventDestroy(c->pinned_done[i]);
   }
   if (c->own_arena && c->arena) (void)hipFree(c->arena);
+  if (c->static_dev >= 0 && c->static_dev < MAX_STATIC_DEVS) g_static_busy[c->static_dev] = false;
   delete c;
 }
 

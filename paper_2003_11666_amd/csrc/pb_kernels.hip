@@ -2065,7 +2065,44 @@ __global__ void k_advance(Globals* G, int dt, int didx) {
   }
 }
 
+__global__ void __launch_bounds__(BLK) k_fill_zero(v4f* __restrict__ p, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * BLK + threadIdx.x; i < n16; i += (size_t)gridDim.x * BLK) p[i] = (v4f){0.f, 0.f, 0.f, 0.f};
+}
+
+// Device memory of contexts that must not allocate: one array per GPU, held from the moment the
+// library's code object is loaded on that GPU until the process ends.  Host code never uses the
+// array's name as an address: static_arena() asks the runtime for the array's address on the current
+// device, once per device, and everything else works with that pointer.
+static __device__ __align__(256) unsigned char scratch[STATIC_ARENA_BYTES];
+
+hipError_t static_arena(void** ptr, int* device) {
+  constexpr int MAX_DEVS = 64;
+  static void* addr[MAX_DEVS] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVS) return hipErrorInvalidDevice;
+  if (!addr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    addr[dev] = p;
+  }
+  *ptr = addr[dev];
+  *device = dev;
+  return hipSuccess;
+}
+
 // --------------------------------------------------------- launch wrappers
+void launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  const size_t n16 = bytes / 16;
+  if (!n16) return;
+  const size_t want = (n16 + BLK - 1) / BLK;
+  const unsigned grid = (unsigned)(want < 4096 ? want : 4096);
+  hipLaunchKernelGGL(k_fill_zero, dim3(grid), dim3(BLK), 0, s, (v4f*)p, n16);
+}
+
 void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, const float* sample_override,
                   int label_override, bool nt, hipStream_t s) {
   if (total_tiles <= 0) return;
