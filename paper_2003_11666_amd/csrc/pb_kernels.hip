@@ -1106,7 +1106,55 @@ __device__ __forceinline__ void step_ingest(const LDesc& d, int tile, int t, con
 // other (d.what), so the update may run beside forward work of the same tick
 // as soon as the stage's gradients are complete.  Master weights and velocity
 // (read d.w, d.v; written d.wp, d.b) are updated in place.
+// Update size N above one (the paper's setting is one; this path is not tuned): the gradients of N
+// consecutive samples are added up in d.gacc and one update with their mean is applied after the
+// backward pass of the last of them.  On every other tick the parameters stand still and the
+// predicted weights are carried over from the slot of this tick to the slot of the next one.
+// Two vectors per thread at a time: the step shares its kernel with steps that need every register.
+__device__ __forceinline__ void step_update_acc(const LDesc& d, int tile, int t) {
+  const int N = UNI(d.upd_n);
+  const int n4 = UNI(d.n) >> 2;
+  const int j = t - UNI(d.upd_t0);                      // sample whose gradient arrived in this tick
+  const int pos = j >= 0 ? j % N : -1;
+  const float a = UNIF(d.fa), b = UNIF(d.fb), lrT = UNIF(d.flrT), lr = UNIF(d.flr), m = UNIF(d.fm);
+  const bool wform = UNI(d.flags) & F_LWP_W;
+  const int gparts = UNI(d.gparts), ps4 = UNI(d.gpstride) >> 2;
+  const gv4* gp = (const gv4*)d.gw;
+  gv4* ap = (gv4*)d.gacc;
+  gv4* vp = (gv4*)d.v;
+  gv4* wp = (gv4*)(float*)d.w;
+  gv4* ho = (gv4*)d.what;
+  const gv4* hs = (const gv4*)(d.what0 + (size_t)(t % UNI(d.pdepth)) * (size_t)UNI(d.pstride));
+  const float inv = 1.0f / (float)N;
+  const int lo = tile * (UPD_TILE / 4), hi = (n4 < lo + UPD_TILE / 4) ? n4 : lo + UPD_TILE / 4;
+#pragma unroll 2
+  for (int i = lo + (int)threadIdx.x; i < hi; i += BLK) {
+    if (pos < 0) { if (ho) ho[i] = hs[i]; continue; }
+    v4f g = gp[i];
+    for (int p = 1; p < gparts; ++p) g += gp[(size_t)p * ps4 + i];
+    if (pos > 0) g += ap[i];
+    if (pos != N - 1) {
+      ap[i] = g;
+      if (ho) ho[i] = hs[i];
+      continue;
+    }
+    const v4f v0 = vp[i], w0 = wp[i];
+    v4f v2, w2, h;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float ge = g[e] * inv;
+      v2[e] = fmaf(m, v0[e], ge);
+      w2[e] = fmaf(-lr, fmaf(a, v2[e], b * ge), w0[e]);
+      h[e] = wform ? fmaf(lrT, w2[e] - w0[e], w2[e]) : fmaf(-lrT, v2[e], w2[e]);
+    }
+    vp[i] = v2;
+    wp[i] = w2;
+    if (ho) ho[i] = h;
+  }
+}
+
 __device__ __forceinline__ void step_update(const LDesc& d, int tile, int t, const bool nt_kernel) {
+  if (UNI(d.upd_n) > 1) { step_update_acc(d, tile, t); return; }
   // the step streams 24 bytes per parameter and nothing else: what it needs is bytes in
   // flight, so every thread requests its 8 vectors of all three arrays before using any.
   // Plain accesses: the parameter arrays of the VGG-11 and wide configurations fit the
@@ -1146,38 +1194,6 @@ __device__ __forceinline__ void step_update(const LDesc& d, int tile, int t, con
   gv4* vo = (gv4*)(float*)d.b;
   gv4* wo = (gv4*)(float*)d.wp;
   gv4* ho = (gv4*)d.what;
-  // Update size N above one: the gradients of N consecutive samples are added up (d.gacc) and one
-  // update with their mean is applied after the backward pass of the last of them.  On every other
-  // tick the parameters stand still and the predicted weights are carried over from the slot of this
-  // tick to the slot of the next one.
-  const int N = UNI(d.upd_n);
-  if (N > 1) {
-    const int j = t - UNI(d.upd_t0);                    // sample whose gradient arrived in this tick
-    const int pos = j >= 0 ? j % N : -1;
-    gv4* ap = (gv4*)d.gacc;
-    if (pos > 0) {
-#pragma unroll
-      for (int u = 0; u < UU; ++u) {
-        const int i = i0 + u * BLK;
-        if (i < n4) gv[u] += ap[i];
-      }
-    }
-    if (pos != N - 1) {
-      const gv4* hs = (const gv4*)(d.what0 + (size_t)(t % UNI(d.pdepth)) * (size_t)UNI(d.pstride));
-#pragma unroll
-      for (int u = 0; u < UU; ++u) {
-        const int i = i0 + u * BLK;
-        if (i < n4) {
-          if (pos >= 0) ap[i] = gv[u];
-          if (ho) ho[i] = hs[i];
-        }
-      }
-      return;
-    }
-    const float inv = 1.0f / (float)N;
-#pragma unroll
-    for (int u = 0; u < UU; ++u) gv[u] *= inv;
-  }
 #pragma unroll
   for (int u = 0; u < UU; ++u) {
     const int i = i0 + u * BLK;
