@@ -189,6 +189,11 @@ def run_parity(engine_cls, net, K, mitigation=3, seed=42, every=1, engine_kwargs
     lg, lo = np.asarray(eng.loss_history(), dtype=np.float64), orc.loss_history()
     l_sens = np.max([np.abs(o2.loss_history() - lo) for o2 in orcs], axis=0) if len(lo) else np.zeros(0)
     l_tol = np.maximum(1e-4 * np.maximum(1.0, np.abs(lo)), SENS_FACTOR * l_sens)
+    if net.get("act_dtype", "fp32") == "bf16" and len(lo):
+        # bf16 activations: thousands of roundings per tick sit on a floating-point boundary, and which
+        # sample's loss a flipped rounding moves is a matter of chance: the probes bound the size of such
+        # a move over the window, not the sample it hits
+        l_tol = np.maximum(l_tol, SENS_FACTOR * l_sens.max())
     # velocity: per tensor, like the weights
     ov = orc.read_velocity()
     v_err = per_tensor_errors(eng.read_velocity(), ov, slices)

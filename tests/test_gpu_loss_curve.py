@@ -36,7 +36,7 @@ def _read(name):
     return ticks, win, pool, np.asarray(vals)
 
 
-@pytest.mark.parametrize("name", ["mlp", "tiny_vgg", "small_resnet", "resnet20"])
+@pytest.mark.parametrize("name", ["mlp", "tiny_vgg", "small_resnet", "resnet20", "vgg11"])
 def test_loss_curve_matches_oracle(name):
     import torch
     from paper_2003_11666_amd import PBEngine
