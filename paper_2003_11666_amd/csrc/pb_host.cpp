@@ -1802,6 +1802,22 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
                g.o_patch + g.CC * g.PR * g.Wp);
       o += line;
     }
+    {
+      // algorithmic bytes of the streaming steps (each operand read or written once, 4 bytes per element)
+      const int64_t in = (int64_t)d.C * d.H * d.W;
+      int64_t el = -1;
+      if (d.kind == K_GN_STATS) el = (d.gparts > 1 ? (int64_t)d.gparts * in + in : in) + (d.y.base ? in : 0);
+      else if (d.kind == K_GN_BWD) el = in + ((d.flags & F_DU_GAP) ? d.C : in) + (d.dx.base ? in : 0) + ((d.flags & F_ADD_SKG) ? in : 0);
+      else if (d.kind == K_GNB_REDUCE) el = in + ((d.flags & F_DU_BUF) ? in : (d.flags & F_DU_GAP) ? d.C : (int64_t)d.C * d.PH * d.PW);
+      else if (d.kind == K_GNB_APPLY) el = 3 * in + ((d.flags & F_ADD_SKG) ? in : 0);
+      else if (d.kind == K_POST_FWD) el = in + ((d.flags & F_POOL) ? (int64_t)d.C * d.PH * d.PW : in);
+      else if (d.kind == K_COPY) el = 2 * (int64_t)d.n;
+      else if (d.kind == K_UPDATE) el = 6 * (int64_t)d.n + (int64_t)(d.gparts - 1) * d.n;
+      if (el >= 0) {
+        snprintf(line, sizeof line, " | bytes %lld", (long long)(4 * el));
+        o += line;
+      }
+    }
     o += "\n";
   }
   if (buf && cap > 0) {

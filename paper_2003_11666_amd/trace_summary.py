@@ -7,7 +7,7 @@
 Reads the .db file rocprofv3 leaves under OUT (its rocpd SQLite output) and prints
   * the kernels by total time (the `top_kernels` view),
   * the `k_phase` launches grouped by grid size, i.e. by phase of the tick,
-  * with --steps CONFIG, for a run made with `bench.py --launch-mode 1 --no-step-profile`
+  * with --steps CONFIG, for a run made with `bench.py --launch-mode 1`
     (one launch per step, in step-table order): the mean duration of every step of the tick,
   * with --counters, for a `--pmc` run: the mean counter value per kernel.
 """
@@ -67,6 +67,20 @@ def steps(cur, config):
         agg.setdefault(key, []).append(d)
     for k, v in sorted(agg.items(), key=lambda kv: -max(kv[1])):
         print(f"{sum(v) / len(v):6.2f} ({max(v):6.2f}) x{len(v):2d} | {k[:170]}")
+    # streaming steps (the plan gives their algorithmic bytes): achieved bandwidth per step class
+    cls = collections.OrderedDict()
+    for si, line in enumerate(plan):
+        m = re.search(r"phase \d+ (\w+) .*\| bytes (\d+)", line)
+        if not m:
+            continue
+        d = sum((t[si][1] - t[si][0]) / 1000.0 for t in ticks) / len(ticks)
+        c = cls.setdefault(m.group(1), [0, 0.0, 0, 0.0])
+        c[0] += int(m.group(2)); c[1] += d; c[2] += 1
+        c[3] = max(c[3], int(m.group(2)) / d / 1e3)
+    print("step class | steps per tick | algorithmic MB per tick | us per tick (one launch per step) | GB/s over the class | "
+          "best single step GB/s | % of 8 TB/s (class, best step)")
+    for k, (b, us, n, best) in cls.items():
+        print(f"{k} | {n} | {b / 1e6:.2f} | {us:.1f} | {b / us / 1e3:.0f} | {best:.0f} | {b / us / 1e3 / 80:.1f}, {best / 80:.1f}")
     print("slowest step per phase (us):", {k: round(v, 2) for k, v in sorted(phmax.items())})
 
 
