@@ -23,7 +23,7 @@ from oracle import pb_oracle as O            # noqa: E402
 # cannot memorise: while a net falls into a 32-sample pool the loss drops off a cliff at a moment that
 # rounding errors move by hundreds of ticks, and window means of two correct runs then differ
 CASES = {"mlp": (10000, 500, None), "tiny_vgg": (10000, 500, None), "small_resnet": (10000, 500, 1024),
-         "resnet20": (10000, 500, None), "vgg11": (10000, 500, None), "wide": (10000, 500, None)}
+         "resnet20": (10000, 500, None), "vgg11": (10000, 500, None), "wide": (5000, 500, None)}
 
 
 def main():

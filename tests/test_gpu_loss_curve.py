@@ -1,4 +1,4 @@
-"""Loss-curve agreement of the HIP path with the CPU oracle over 10 000 ticks.
+"""Loss-curve agreement of the HIP path with the CPU oracle over 10 000 ticks (5 000 for the wide network).
 
 The oracle's window means are stored under tests/golden/ (written by
 tests/golden/make_loss_curves.py, which runs the oracle only).  Individual
@@ -36,7 +36,7 @@ def _read(name):
     return ticks, win, pool, np.asarray(vals)
 
 
-@pytest.mark.parametrize("name", ["mlp", "tiny_vgg", "small_resnet", "resnet20", "vgg11"])
+@pytest.mark.parametrize("name", ["mlp", "tiny_vgg", "small_resnet", "resnet20", "vgg11", "wide"])
 def test_loss_curve_matches_oracle(name):
     import torch
     from paper_2003_11666_amd import PBEngine
