@@ -95,7 +95,9 @@ enum StepFlags : int32_t {
   F_ALWAYS = 8192,    // the step runs before its first_tick too (then it only carries parameters over)
   F_BF16_OUT = 16384, // the step's output crosses a stage boundary in bf16 mode: round it to bf16 (nearest even)
   F_LWP_W = 32768,    // update: weight-difference form of the prediction, w_hat = w' + T (w' - w); flrT then holds T
-  F_NT = 65536        // K_UPDATE, in a kernel built for non-temporal output stores: this step uses them too
+  F_NT = 65536,       // K_UPDATE, in a kernel built for non-temporal output stores: this step uses them too
+  F_WGRAD = 131072    // K_UPDATE of a 3x3 layer on a 2x2 or 4x4 map: the weight gradient is not read from memory but
+                      // computed inside the step from the layer's saved input (x) and output gradient (dy)
 };
 
 struct StepDesc {

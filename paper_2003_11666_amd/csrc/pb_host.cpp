@@ -262,8 +262,9 @@ constexpr int GRAD_PARTS = 16;
 // the weight matrix.  Followed by a GroupNorm (whose statistics step reads the whole output anyway),
 // its reduction is split over workgroups that write partial outputs.
 constexpr int FWD_PARTS = 8;
+constexpr int THIN_MAX_PIXELS = 64;
 bool fwd_split_candidate(const Stage& a) {
-  return a.is_conv && a.post_gn && !a.add && (int64_t)a.OH * a.OW <= 16 && (int64_t)a.C * a.k * a.k >= 2048;
+  return a.is_conv && a.post_gn && !a.add && (int64_t)a.OH * a.OW <= THIN_MAX_PIXELS && (int64_t)a.C * a.k * a.k >= 2048;
 }
 bool split_candidate(const Stage& a) { return a.is_conv && (int64_t)a.OH * a.OW >= 256 && a.padded <= 65536; }
 
@@ -275,7 +276,7 @@ bool bwd_split_consumer(const std::vector<Stage>& st, int s) {
   const Stage& a = st[s];
   const Stage& n = st[s + 1];
   if (!a.post_gn || !n.is_conv || n.pre_gn || n.pre_relu || n.tap_dist || n.add) return false;
-  if ((int64_t)n.H * n.W > 16 || (int64_t)n.K * n.k * n.k < 2048) return false;
+  if ((int64_t)n.H * n.W > THIN_MAX_PIXELS || (int64_t)n.K * n.k * n.k < 2048) return false;
   // consumer: the channel sums behind a max-pool in their one-wavefront-per-channel form, or the fused
   // GroupNorm backward (one workgroup per group, gradient in registers)
   const int64_t per_channel = a.out_elems() / std::max(1, a.K);
@@ -820,6 +821,10 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   }
   const Layout& L = c->L;
   std::vector<int> bwd0(S, 0);   // per stage: phase its backward chain starts in
+  // stages whose weight gradient is computed inside the update step (see F_WGRAD): the phase the
+  // gradient's operands are complete in, and the operands
+  struct FusedW { int phase = -1; TRef x, dy; };
+  std::vector<FusedW> fusedw(S);
   for (int s = 0; s < S; ++s) {
     const Stage& a = c->st[s];
     const StageBufs& b = L.sb[s];
@@ -1091,6 +1096,15 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       if (a.has_bias) { d.flags |= F_BIAS; d.gb = gr + a.o_b; }
       d.ntiles = bwd_w_tiles(a.K, a.C, a.k, a.OH * a.OW, a.has_bias);
       GemmCfg g;
+      // A 3x3 layer on a 2x2 or 4x4 map (the 512-channel layers of VGG-11): its weight gradient is an outer
+      // product of two tiny maps per weight; the update step computes it while it streams the parameters.
+      const bool fuse_w = c->kernel_set == 0 && g_tile_budget_us > 0 && c->N == 1 && a.is_conv && a.k == 3 && a.stride == 1 &&
+                          a.pad == 1 && a.H == a.W && (a.H == 2 || a.H == 4) && a.OH == a.H && a.OW == a.W && !a.gap &&
+                          !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)) && !a.has_bias && a.C * 9 >= 1171 && a.C * a.H * a.W <= 8192 &&
+                          a.n_w % 4 == 0 && a.n_w >= 65536 && b.gparts < 0 && ref_vec4(c, d.x) && ref_vec4(c, d.dy);
+      if (fuse_w) {
+        fusedw[s].phase = pb; fusedw[s].x = d.x; fusedw[s].dy = d.dy;
+      } else
       if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g,
                                           !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)), 16, false, b.gparts >= 0 ? GRAD_PARTS : 1)) {
         if (a.has_bias) {
@@ -1103,7 +1117,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         d.gparts = g.parts; d.gpstride = (int)a.padded;
         gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, &d.tq, &d.tn);
       }
-      out.push_back({pb, d});
+      if (!fuse_w) out.push_back({pb, d});
     }
     if (s > 0) {   // data gradient of the main layer
       StepDesc d = blank(K_CONV_BWD_X, s, t_b);
@@ -1295,6 +1309,14 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       if (e.kind == K_GEMM && e.g.gm == 3) gparts = std::max(gparts, e.g.parts);
     }
     StepDesc d = blank(K_UPDATE, s, 0);
+    if (fusedw[s].phase >= 0) {
+      // (its operands are complete at the start of that phase; the stage's backward-data step, which
+      // reads the weights this step overwrites, runs in it)
+      last_grad_phase = std::max(last_grad_phase, fusedw[s].phase);
+      d.flags |= F_WGRAD;
+      d.x = fusedw[s].x; d.dy = fusedw[s].dy;
+      d.C = a.C; d.H = a.H; d.W = a.W; d.K = a.K; d.OH = a.OH; d.OW = a.OW; d.k = 3; d.stride = 1; d.pad = 1;
+    }
     set_update_coeffs(c, a, &d);
     d.w = c->f(L.w + a.off); d.v = c->f(L.v + a.off);
     d.gw = c->f(L.sb[s].gparts >= 0 ? L.sb[s].gparts : L.g + a.off);
@@ -1324,6 +1346,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   for (auto& pr : out)
     if (pr.second.kind == K_GEMM && ((pr.second.g.gm != 3 && pr.second.g.parts > 1) || pr.second.g.nsub > 1 || pr.second.g.win > 0 ||
                                     pr.second.gp.nsub > 1 || pr.second.gp.win > 0)) c->nt_stores = false;
+  for (auto& pr : out)
+    if (pr.second.kind == K_UPDATE && (pr.second.flags & F_WGRAD)) c->nt_stores = false;
   if (c->nt_stores) {
     std::vector<char> long_gemm;
     for (auto& pr : out) {
@@ -1519,6 +1543,11 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
              d.what != nullptr;
         if (d.gparts > 1)
           ok = ok && d.gpstride >= d.n && d.gpstride % 4 == 0 && ptr_ok(d.gw, (int64_t)(d.gparts - 1) * d.gpstride + d.n);
+        if (d.flags & F_WGRAD)
+          ok = ok && !c->nt_stores && d.k == 3 && d.stride == 1 && d.pad == 1 && d.H == d.W && (d.H == 2 || d.H == 4) && d.OH == d.H &&
+               d.OW == d.W && d.C * 9 >= 1171 && (int64_t)d.C * d.H * d.W + 8 * 16 + UPD_TILE / 2 <= LDS_FLOATS &&
+               ((int64_t)d.K * d.C * 9) % 4 == 0 && (int64_t)d.K * d.C * 9 <= d.n && d.gparts <= 1 && d.upd_n <= 1 &&
+               ref_ok(d.x, (int64_t)d.C * d.H * d.W) && ref_ok(d.dy, (int64_t)d.K * d.H * d.W) && ref_vec4(c, d.x) && ref_vec4(c, d.dy);
         if (d.upd_n > 1)
           ok = ok && d.upd_t0 >= 0 && ptr_ok(d.gacc, d.n) && d.pmask == PF_WHAT && d.plag == -1 &&
                ptr_ok(d.what0 + (int64_t)(d.pdepth - 1) * d.pstride, d.n) && d.what0 == d.what;
@@ -1812,7 +1841,7 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
       else if (d.kind == K_GNB_APPLY) el = 3 * in + ((d.flags & F_ADD_SKG) ? in : 0);
       else if (d.kind == K_POST_FWD) el = in + ((d.flags & F_POOL) ? (int64_t)d.C * d.PH * d.PW : in);
       else if (d.kind == K_COPY) el = 2 * (int64_t)d.n;
-      else if (d.kind == K_UPDATE) el = 6 * (int64_t)d.n + (int64_t)(d.gparts - 1) * d.n;
+      else if (d.kind == K_UPDATE) el = 6 * (int64_t)d.n + (int64_t)(d.gparts - 1) * d.n - ((d.flags & F_WGRAD) ? (int64_t)d.K * d.C * 9 : 0);
       if (el >= 0) {
         snprintf(line, sizeof line, " | bytes %lld", (long long)(4 * el));
         o += line;

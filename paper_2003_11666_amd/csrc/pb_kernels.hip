@@ -1153,7 +1153,50 @@ __device__ __forceinline__ void step_update_acc(const LDesc& d, int tile, int t)
   }
 }
 
-__device__ __forceinline__ void step_update(const LDesc& d, int tile, int t, const bool nt_kernel) {
+// Weight gradient of a 3x3 convolution (stride 1, padding 1) on an S x S map, S = 2 or 4, for the
+// parameters [p0, p0 + cnt) of the layer's weight tensor [K][C][3][3], written to LDS (gl[idx - p0]).
+// g[k][c][kh][kw] = sum_{oh,ow} dz[k][oh][ow] * x[c][oh-1+kh][ow-1+kw]: with at most 16 pixels this is an
+// outer product, not a contraction -- 2.4 M outputs of 4-11 multiply-adds each for a 512x512 layer --,
+// so it is not worth a GEMM step of its own, and not worth 8 bytes per parameter of memory traffic
+// (gradient written, then read by the update): the update step that streams the parameters anyway
+// computes it on the fly.  A thread takes (k, c) pairs: the pair's two maps sit in registers (read from
+// LDS with 16-byte loads) and its nine sums are fully unrolled.
+// xs: the layer's input [C][S*S]; dzs: the rows k_lo.. of the output gradient [rows][S*S].
+template <int S>
+__device__ __forceinline__ void wgrad_small_map(const lfloat* xs, const lfloat* dzs, lfloat* gl, int C, int k_lo, int p0, int cnt) {
+  constexpr int HW = S * S;
+  const int pc0 = p0 / 9, pc1 = (p0 + cnt - 1) / 9;        // (k, c) pairs, flattened, that the range touches
+  const float iC = frcp(C);
+  for (int pc = pc0 + (int)threadIdx.x; pc <= pc1; pc += BLK) {
+    const int rel = pc - k_lo * C;                          // < 8 * C: small enough for the reciprocal division
+    const int kr = fdiv(rel, iC), c = rel - kr * C;
+    float xv[HW], dv[HW];
+#pragma unroll
+    for (int q = 0; q < HW / 4; ++q) {
+      const v4f a = *(const lv4*)(xs + c * HW + 4 * q), b = *(const lv4*)(dzs + kr * HW + 4 * q);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { xv[4 * q + e] = a[e]; dv[4 * q + e] = b[e]; }
+    }
+    const int base = pc * 9 - p0;
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+      for (int kw = 0; kw < 3; ++kw) {
+        float acc = 0.f;
+#pragma unroll
+        for (int oh = 0; oh < S; ++oh)
+#pragma unroll
+          for (int ow = 0; ow < S; ++ow) {
+            const int ih = oh - 1 + kh, iw = ow - 1 + kw;   // compile-time after unrolling
+            if (ih >= 0 && ih < S && iw >= 0 && iw < S) acc = fmaf(dv[oh * S + ow], xv[ih * S + iw], acc);
+          }
+        const int o = base + kh * 3 + kw;
+        if (o >= 0 && o < cnt) gl[o] = acc;
+      }
+  }
+}
+
+__device__ __forceinline__ void step_update(const LDesc& d, int tile, int t, lfloat* smem, const bool nt_kernel) {
   if (UNI(d.upd_n) > 1) { step_update_acc(d, tile, t); return; }
   // the step streams 24 bytes per parameter and nothing else: what it needs is bytes in
   // flight, so every thread requests its 8 vectors of all three arrays before using any.
@@ -1168,10 +1211,49 @@ __device__ __forceinline__ void step_update(const LDesc& d, int tile, int t, con
   const gv4* vp = (const gv4*)d.v;
   const gv4* wp = (const gv4*)d.w;
   v4f gv[UU], vv[UU], wv[UU];
+  // (nt kernels serve the networks tiled for latency, which have no layer this pays for)
+  const bool fused = !nt_kernel && (UNI(d.flags) & F_WGRAD);
+  const int nwg4 = fused ? (UNI(d.K) * UNI(d.C) * 9) >> 2 : 0;     // vectors of the weight tensor: gradient computed here
 #pragma unroll
   for (int u = 0; u < UU; ++u) {
     const int i = i0 + u * BLK;
-    if (i < n4) { gv[u] = gp[i]; vv[u] = vp[i]; wv[u] = wp[i]; }
+    if (i < n4) {
+      if (i >= nwg4) gv[u] = gp[i];
+      vv[u] = vp[i]; wv[u] = wp[i];
+    }
+  }
+  if (fused && tile * (UPD_TILE / 4) < nwg4) {
+    // the layer's input and the rows of dz this tile's parameters belong to, into LDS; then the tile's
+    // gradient in two halves of 4096 parameters (LDS: xs[C*S*S] | dzs[8*S*S] | gl[4096])
+    const int C = UNI(d.C), K = UNI(d.K), S = UNI(d.H), HW = S * S, CKK = C * 9;
+    const int p_lo = tile * UPD_TILE, k_lo = p_lo / CKK;
+    lfloat* xs = smem;
+    lfloat* dzs = xs + C * HW;
+    lfloat* gl = dzs + 8 * 16;
+    const gfloat* xg = at(d.x, t);
+    const gfloat* dzg = at(d.dy, t) + (size_t)k_lo * HW;
+    for (int i = threadIdx.x * 4; i < C * HW; i += 4 * BLK) *(lv4*)(xs + i) = *(const gv4*)(xg + i);
+    const int rows = (K - k_lo < 8) ? K - k_lo : 8;
+    if ((int)threadIdx.x * 4 < rows * HW) *(lv4*)(dzs + threadIdx.x * 4) = *(const gv4*)(dzg + threadIdx.x * 4);
+    const int n_w = nwg4 << 2;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int p0 = p_lo + h * (UPD_TILE / 2);
+      int cnt = n_w - p0;
+      if (cnt > UPD_TILE / 2) cnt = UPD_TILE / 2;
+      __syncthreads();                 // operands staged (h = 0) / previous half consumed (h = 1)
+      if (cnt > 0) {
+        if (S == 4) wgrad_small_map<4>(xs, dzs, gl, C, k_lo, p0, cnt);
+        else wgrad_small_map<2>(xs, dzs, gl, C, k_lo, p0, cnt);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < UU / 2; ++u) {
+        const int uu = h * (UU / 2) + u;
+        const int i = i0 + uu * BLK;
+        if (i < nwg4) gv[uu] = *(const lv4*)(gl + 4 * ((int)threadIdx.x + u * BLK));
+      }
+    }
   }
   // a stage whose weight gradient was computed in parts (split reduction of the
   // backward-weights GEMM): add the other parts, in order
@@ -1975,7 +2057,7 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     case K_GEMM: step_gemm(d, tile, t, smem, NT); break;
     case K_BIAS_GRAD: step_bias_grad(d, tile, t); break;
     case K_INGEST: step_ingest(d, tile, t, G, k, sample_override, label_override); break;
-    case K_UPDATE: step_update(d, tile, t, NT); break;
+    case K_UPDATE: step_update(d, tile, t, smem, NT); break;
     case K_HEAD: step_head(d, t, red, smem, NT); break;
     case K_GN_BWD: step_gn_bwd(d, tile, t, live, smem, NT); break;
     default: break;
