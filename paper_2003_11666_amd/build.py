@@ -43,6 +43,7 @@ def build(verbose=True, timing=False):
         # every step of a tick is inlined into k_phase; a change that makes it spill slows every step down
         # (a spilling build measured 32 us instead of 12 us for a ResNet-20 launch)
         if "k_phase" in name and not timing and int(u.get("ScratchSize [bytes/lane]", 0)) > MAX_SCRATCH_BYTES:
+            os.remove(out)      # a library that spills must not be the one that gets loaded
             raise RuntimeError(f"{name} uses {u['ScratchSize [bytes/lane]']} bytes of scratch memory per lane "
                                f"(limit {MAX_SCRATCH_BYTES}): a step spills registers")
     return out

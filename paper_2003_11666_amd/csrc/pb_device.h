@@ -41,7 +41,11 @@ enum StepKind : int32_t {
   K_INGEST = 12,     // the tick's sample and label into the first stage's ring
   K_UPDATE = 13,     // fused SC+LWP update of one stage's parameter block (reads one copy of w, v; writes the other)
   K_HEAD = 14,       // whole last stage (forward, loss, backward) in one workgroup
-  K_GN_BWD = 15      // GroupNorm backward of one group in one workgroup: channel sums and dx together
+  K_GN_BWD = 15,     // GroupNorm backward of one group in one workgroup: channel sums and dx together
+  K_DOT_FWD = 16,    // forward of a 3x3 layer (stride 1, padding 1) on a 2x2 or 4x4 map as dot products: d.n output
+                     // channels per workgroup, the weights streamed once, no MFMA, no LDS tiles
+  K_DOT_BWD_X = 17   // backward data of such a layer: 64 input channels per workgroup and a d.n-th of the output
+                     // channels (d.gparts parts, summed by the consumer of the gradient when there are several)
 };
 
 constexpr int LDS_FLOATS = 15872;   // 62 KB of LDS per workgroup for the GEMM steps (two workgroups per compute unit)

@@ -280,8 +280,18 @@ bool bwd_split_consumer(const std::vector<Stage>& st, int s) {
   // consumer: the channel sums behind a max-pool in their one-wavefront-per-channel form, or the fused
   // GroupNorm backward (one workgroup per group, gradient in registers)
   const int64_t per_channel = a.out_elems() / std::max(1, a.K);
-  if (a.pool) return per_channel <= 64 && a.OH * a.OW <= 64;
+  // (behind a max-pool: the wave form for maps of up to 64 pixels, else the form that stages the channel's map and its
+  // pooled gradient in LDS)
+  if (a.pool) return (per_channel <= 64 && a.OH * a.OW <= 64) || (int64_t)a.OH * a.OW + per_channel <= LDS_FLOATS;
   return a.G > 0 && (int64_t)(a.K / a.G) * a.OH * a.OW <= 4096 && (a.OH * a.OW) % 4 == 0;
+}
+
+// A 3x3 layer of stride 1 and padding 1 on a 2x2 or 4x4 map with many channels is a matrix-vector product:
+// its forward and backward-data passes run as dot-product steps (K_DOT_FWD, K_DOT_BWD_X) in networks tiled
+// for throughput.
+bool dot_layer(const Stage& a) {
+  return a.is_conv && a.k == 3 && a.stride == 1 && a.pad == 1 && a.H == a.W && (a.H == 2 || a.H == 4) && a.OH == a.H && a.OW == a.W &&
+         !a.gap && !a.has_bias && !a.add && !a.pre_gn && !a.pre_relu && a.C % 64 == 0 && a.K % 8 == 0 && (int64_t)a.C * a.K >= 32768;
 }
 
 int st_stride_of(const Stage& s) { return (2 * s.G + 2 * s.gnC() + 63) / 64 * 64; }
@@ -983,6 +993,12 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       fwd_params(d, PF_W | (a.has_bias ? PF_B : 0) | ((d.flags & F_PROJ) ? PF_WP : 0));
       d.ntiles = cdiv((int64_t)a.K * a.OH * a.OW, BLK);
       if (c->bf16 && !a.ce) d.flags |= F_BF16_OUT;   // the logits of the loss stage stay unrounded
+      const bool dot_fwd = c->kernel_set == 0 && g_tile_budget_us > 0 && !c->bf16 && dot_layer(a) && !a.ce && ref_vec4(c, d.x);
+      if (dot_fwd) {
+        d.kind = K_DOT_FWD;
+        d.n = a.H == 4 ? 4 : 8;            // output channels per workgroup
+        d.ntiles = a.K / d.n;
+      } else
       if (c->kernel_set == 0) {
         GemmCfg g, gp;
         memset(&gp, 0, sizeof gp);
@@ -1141,6 +1157,17 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       if (flat) { d.W *= d.H; d.H = 1; d.OW *= d.OH; d.OH = 1; }
       const bool dxsplit = !a.pre_gn && s > 0 && L.sb[s - 1].dxparts >= 0 && !c->bf16 && g_tile_budget_us > 0 &&
                            !(d.flags & (F_MASK_X | F_ADD_SKG | F_BF16_OUT)) && !flat;
+      const bool dot_bwd = c->kernel_set == 0 && g_tile_budget_us > 0 && !c->bf16 && dot_layer(a) && !(d.flags & (F_MASK_X | F_ADD_SKG | F_BF16_OUT)) &&
+                           ref_vec4(c, d.dy) && ref_vec4(c, d.dx);
+      if (dot_bwd) {
+        // 64 input channels per workgroup; the output channels in as many parts as the gradient's consumer can
+        // add up, so that the layer's weights are spread over C/64 x parts workgroups
+        d.kind = K_DOT_BWD_X;
+        const int parts = dxsplit ? FWD_PARTS : 1;
+        d.n = cdiv(a.K, parts);
+        d.ntiles = (a.C / 64) * parts;
+        if (parts > 1) { d.gw = c->f(L.sb[s - 1].dxparts); d.gparts = parts; d.gpstride = (int)a.in_elems(); }
+      } else
       if (c->kernel_set == 0 && make_gemm(2, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, true, 16, flat,
                                           dxsplit ? FWD_PARTS : 1)) {
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
@@ -1255,7 +1282,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   if (c->sequential) {
     auto is_bwd = [](const StepDesc& d) {
       return d.kind == K_GNB_REDUCE || d.kind == K_GNB_APPLY || d.kind == K_GN_BWD || d.kind == K_CONV_BWD_X ||
-             d.kind == K_CONV_BWD_W || d.kind == K_BIAS_GRAD || d.kind == K_COPY || (d.kind == K_GEMM && d.g.gm != 1);
+             d.kind == K_CONV_BWD_W || d.kind == K_BIAS_GRAD || d.kind == K_COPY || d.kind == K_DOT_BWD_X || (d.kind == K_GEMM && d.g.gm != 1);
     };
     std::vector<int> lenF(S, 0), lenB(S, 0), baseF(S, 0), baseB(S, 0);
     for (auto& pr : out) {
@@ -1282,11 +1309,12 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   // previous stage's GroupNorm (same gradient buffer), adds them up
   for (auto& pr : out) {
     const StepDesc& p = pr.second;
-    if (p.kind != K_GEMM || p.g.gm != 2 || p.g.parts <= 1) continue;
+    const bool split_gemm = p.kind == K_GEMM && p.g.gm == 2 && p.g.parts > 1, split_dot = p.kind == K_DOT_BWD_X && p.gparts > 1;
+    if (!split_gemm && !split_dot) continue;
     for (auto& qr : out) {
       StepDesc& q = qr.second;
       if ((q.kind == K_GNB_REDUCE || q.kind == K_GN_BWD) && q.stage == p.stage - 1 && q.dy.base == p.dx.base) {
-        q.gw = p.gw; q.gparts = p.g.parts; q.gpstride = p.gpstride;
+        q.gw = p.gw; q.gparts = p.gparts; q.gpstride = p.gpstride;
       }
     }
   }
@@ -1347,7 +1375,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     if (pr.second.kind == K_GEMM && ((pr.second.g.gm != 3 && pr.second.g.parts > 1) || pr.second.g.nsub > 1 || pr.second.g.win > 0 ||
                                     pr.second.gp.nsub > 1 || pr.second.gp.win > 0)) c->nt_stores = false;
   for (auto& pr : out)
-    if (pr.second.kind == K_UPDATE && (pr.second.flags & F_WGRAD)) c->nt_stores = false;
+    if ((pr.second.kind == K_UPDATE && (pr.second.flags & F_WGRAD)) || pr.second.kind == K_DOT_FWD || pr.second.kind == K_DOT_BWD_X)
+      c->nt_stores = false;
   if (c->nt_stores) {
     std::vector<char> long_gemm;
     for (auto& pr : out) {
@@ -1381,6 +1410,8 @@ void order_steps(std::vector<std::pair<int, StepDesc>>& tagged) {
         // 256 of them when the channel fits LDS, 7 us from global memory)
         const bool in_lds = (int64_t)d.H * d.W + (int64_t)d.PH * d.PW <= LDS_FLOATS;
         us = 4.0 + (d.grain == 1 ? 1.0 : (double)d.H * d.W / BLK * ((d.flags & F_DU_POOL) ? (in_lds ? 2.0 : 7.0) : 0.05));
+      } else if (d.kind == K_DOT_FWD || d.kind == K_DOT_BWD_X) {
+        us = 8.0;
       } else if (d.kind == K_UPDATE) {
         us = 15.0;
       } else if (d.kind == K_POST_FWD || d.kind == K_GNB_APPLY) {
@@ -1455,7 +1486,7 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
         else
           ok = ok && d.ntiles == d.G;
         if (d.gparts > 1)   // sums the partial outputs of a split forward GEMM: register form only
-          ok = ok && d.grain != 1 && d.G > 0 && (int64_t)(d.C / d.G) * d.H * d.W <= 32768 && ((d.C / d.G) * d.H * d.W) % 4 == 0 && d.C / d.G <= BLK &&
+          ok = ok && d.gparts <= FWD_PARTS && d.grain != 1 && d.G > 0 && (int64_t)(d.C / d.G) * d.H * d.W <= 32768 && ((d.C / d.G) * d.H * d.W) % 4 == 0 && d.C / d.G <= BLK &&
                d.gpstride >= in && d.gpstride % 4 == 0 && ptr_ok(d.gw, (int64_t)(d.gparts - 1) * d.gpstride + in);
         ok = ok && d.G > 0 && d.C % d.G == 0 && ref_ok(d.x, in) && ref_ok(d.st, stn) &&
              ptr_ok(d.gamma, d.C) && ptr_ok(d.beta, d.C) && (!d.y.base || ref_ok(d.y, in));
@@ -1493,8 +1524,12 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
           ok = ok && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C);
           if (d.grain == 1) ok = ok && (d.flags & (F_DU_BUF | F_DU_POOL)) && d.ntiles == cdiv(d.C, GNB_WAVE_CH * (BLK / 64));
           else ok = ok && d.grain == 0 && d.ntiles == d.C;
-          if (d.gparts > 1)   // sums partial gradients: wave form, at most 64 values per channel
-            ok = ok && d.grain == 1 && dyn / d.C <= 64 && d.gpstride >= dyn && ptr_ok(d.gw, (int64_t)(d.gparts - 1) * d.gpstride + dyn);
+          if (d.gparts > 1) {   // sums partial gradients: wave form with at most 64 values per channel, or the form that
+                                // stages a channel's pooled gradient in LDS
+            ok = ok && d.gparts <= FWD_PARTS && d.gpstride >= dyn && ptr_ok(d.gw, (int64_t)(d.gparts - 1) * d.gpstride + dyn);
+            if (d.grain == 1) ok = ok && dyn / d.C <= 64;
+            else ok = ok && (d.flags & F_DU_POOL) && (int64_t)d.H * d.W + (int64_t)d.PH * d.PW <= LDS_FLOATS;
+          }
         } else {
           ok = ok && ref_ok(d.dx, in) && (!(d.flags & F_ADD_SKG) || ref_ok(d.skg, in));
           if (d.grain > 0)
@@ -1512,7 +1547,7 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
              ptr_ok(d.gamma, d.C) && ptr_ok(d.ggamma, d.C) && ptr_ok(d.gbeta, d.C) && (!d.dx.base || ref_ok(d.dx, in)) &&
              (!(d.flags & F_ADD_SKG) || (d.dx.base && ref_ok(d.skg, in)));
         if (d.gparts > 1)   // sums partial gradients (see bwd_split_consumer)
-          ok = ok && (d.flags & F_DU_BUF) && d.gpstride >= in && d.gpstride % 4 == 0 && ptr_ok(d.gw, (int64_t)(d.gparts - 1) * d.gpstride + in);
+          ok = ok && d.gparts <= FWD_PARTS && (d.flags & F_DU_BUF) && d.gpstride >= in && d.gpstride % 4 == 0 && ptr_ok(d.gw, (int64_t)(d.gparts - 1) * d.gpstride + in);
         if (d.flags & F_UPD_GN)
           ok = ok && ptr_ok(d.v, 2 * d.C) && ptr_ok(d.w, 2 * d.C) && ptr_ok(d.b, 2 * d.C) && ptr_ok(d.gamma, 2 * d.C) &&
                d.what && ptr_ok(d.what, 2 * d.C);
@@ -1570,6 +1605,30 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
       case K_BIAS_GRAD:
         ok = ok && d.ntiles * (BLK / 64) >= d.K && ref_ok(d.dy, outn) && ptr_ok(d.gb, d.K);
         break;
+      case K_DOT_FWD: {
+        const int R = d.H == 4 ? 4 : 8;
+        ok = ok && !c->nt_stores && d.k == 3 && d.stride == 1 && d.pad == 1 && d.H == d.W && (d.H == 2 || d.H == 4) && d.OH == d.H && d.OW == d.W &&
+             d.n == R && d.K % R == 0 && d.ntiles == d.K / R && !(d.flags & ~F_ALWAYS) && ref_ok(d.x, in) && ref_vec4(c, d.x) &&
+             ref_ok(d.y, outn) && ptr_ok(d.w, (int64_t)d.K * d.C * 9);
+        break;
+      }
+      case K_DOT_BWD_X: {
+        const int parts = d.gparts > 1 ? d.gparts : 1;
+        ok = ok && !c->nt_stores && d.k == 3 && d.stride == 1 && d.pad == 1 && d.H == d.W && (d.H == 2 || d.H == 4) && d.OH == d.H && d.OW == d.W &&
+             d.C % 64 == 0 && d.n >= 1 && (int64_t)d.n * parts >= d.K && (int64_t)d.n * (parts - 1) < d.K && d.ntiles == (d.C / 64) * parts &&
+             !(d.flags & ~F_ALWAYS) && (int64_t)d.n * d.H * d.W + 4 * 64 * d.H * d.W <= LDS_FLOATS && ref_ok(d.dy, outn) && ref_vec4(c, d.dy) &&
+             ref_ok(d.dx, in) && ref_vec4(c, d.dx) && ptr_ok(d.w, (int64_t)d.K * d.C * 9);
+        if (parts > 1) {
+          ok = ok && parts <= FWD_PARTS && d.gpstride >= in && d.gpstride % 4 == 0 && ptr_ok(d.gw, (int64_t)(parts - 1) * d.gpstride + in);
+          bool consumed = false;
+          for (auto& qr : steps)
+            consumed = consumed || (((qr.second.kind == K_GNB_REDUCE && (qr.second.grain == 1 || (qr.second.flags & F_DU_POOL))) ||
+                                     (qr.second.kind == K_GN_BWD && !(qr.second.flags & F_DU_GAP))) &&
+                                    qr.second.gparts == d.gparts && qr.second.gw == d.gw && qr.second.dy.base == d.dx.base);
+          ok = ok && consumed;
+        }
+        break;
+      }
       case K_GEMM: {
         auto cfg_ok = [&](const GemmCfg& g, int C, int H, int W, int k, int s, int pad) {
           const int kk = k * k;
@@ -1647,7 +1706,7 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
                  ptr_ok(d.gw, (int64_t)(d.g.parts - 1) * d.gpstride + in);
             bool consumed = false;
             for (auto& qr : steps)
-              consumed = consumed || (((qr.second.kind == K_GNB_REDUCE && qr.second.grain == 1) ||
+              consumed = consumed || (((qr.second.kind == K_GNB_REDUCE && (qr.second.grain == 1 || (qr.second.flags & F_DU_POOL))) ||
                                        (qr.second.kind == K_GN_BWD && !(qr.second.flags & F_DU_GAP))) &&
                                       qr.second.gparts == d.gparts && qr.second.gw == d.gw && qr.second.dy.base == d.dx.base);
             ok = ok && consumed;
@@ -1816,7 +1875,7 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   compile_steps(&tmp, steps);
   order_steps(steps);
   static const char* names[] = {"gn_stats", "gap_fwd", "conv_fwd", "post_fwd", "ce", "gnb_reduce", "gnb_apply",
-                                "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad", "ingest", "update", "head", "gn_bwd"};
+                                "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad", "ingest", "update", "head", "gn_bwd", "dot_fwd", "dot_bwd_x"};
   std::string o;
   char line[400];
   for (auto& pr : steps) {

@@ -129,6 +129,28 @@ __device__ __forceinline__ float block_max(float v, lfloat* red) {
 #include "pb_gemm.h"
 namespace pb {
 
+// Sum of the `parts` partial results p[0], p[stride], ... (at most MAX_PARTS of them) in order, BATCH
+// loads requested before the first of them is added: a loop of load-then-add pays a memory round
+// trip per part.
+constexpr int MAX_PARTS = 8;
+template <class T, int BATCH, class P>
+__device__ __forceinline__ T sum_parts(const P* p, size_t stride, int parts) {
+  T a;
+#pragma unroll
+  for (int q0 = 0; q0 < MAX_PARTS; q0 += BATCH) {
+    if (q0 < parts) {
+      T v[BATCH];
+#pragma unroll
+      for (int q = 0; q < BATCH; ++q)
+        if (q0 + q < parts) v[q] = p[(q0 + q) * stride];
+#pragma unroll
+      for (int q = 0; q < BATCH; ++q)
+        if (q0 + q < parts) a = (q0 + q == 0) ? v[q] : a + v[q];
+    }
+  }
+  return a;
+}
+
 // ------------------------------------------------------------ forward steps
 // GroupNorm statistics of one group (biased variance, two passes) and the
 // folded per-channel scale/shift built from the forward (predicted) affine
@@ -162,8 +184,7 @@ __device__ __forceinline__ bool step_gn_stats_reg(const LDesc& d, int tile, int 
       for (int u = 0; u < GU; ++u) {
         const int i = (tid + u * BLK) * 4;
         if (i < n) {
-          v4f a = *(const gv4*)(part + i);
-          for (int p = 1; p < gparts; ++p) a += *(const gv4*)(part + p * ps + i);
+          const v4f a = sum_parts<v4f, 2>((const gv4*)(part + i), ps >> 2, gparts);
           xr[u] = a;
           *(gv4*)((gfloat*)xp + i) = a;
         }
@@ -551,8 +572,7 @@ __device__ __forceinline__ void step_gnb_reduce_wave(const LDesc& d, int tile, i
       const int c = c0 + q;
       if (c < C && lane < n_dy) {
         const size_t o = (size_t)c * n_dy + lane;
-        float s = part[o];
-        for (int p = 1; p < gparts; ++p) s += part[p * ps + o];
+        const float s = sum_parts<float, 8>(part + o, ps, gparts);
         ((gfloat*)dy)[o] = s;
         ls[q * 64 + lane] = s;
       }
@@ -680,7 +700,19 @@ __device__ __forceinline__ void step_gnb_reduce(const LDesc& d, int tile, int t,
     } else {
       for (int i = threadIdx.x; i < HW; i += BLK) zs[i] = xc[i];
     }
-    for (int i = threadIdx.x; i < PHW; i += BLK) ds[i] = dyc[i];
+    // (the pooled gradient may have been left as partial sums by a backward-data GEMM split over its reduction:
+    // add them up in order and write the gradient for the elementwise pass of a later launch)
+    const int gparts = nt ? 1 : UNI(d.gparts);
+    if (gparts > 1) {
+      const gfloat* part = GP(d.gw) + (size_t)c * PHW;
+      for (int i = threadIdx.x; i < PHW; i += BLK) {
+        const float sv = sum_parts<float, 8>(part + i, (size_t)UNI(d.gpstride), gparts);
+        ds[i] = sv;
+        ((gfloat*)dyc)[i] = sv;
+      }
+    } else {
+      for (int i = threadIdx.x; i < PHW; i += BLK) ds[i] = dyc[i];
+    }
     __syncthreads();
     const float iw = frcp(W);
     for (int i = threadIdx.x; i < HW; i += BLK) {
@@ -875,9 +907,7 @@ __device__ __forceinline__ void step_gn_bwd(const LDesc& d, int tile, int t, boo
       const int sl = tid + u * BLK;
       if (sl < ns) {
         const gfloat* part = GP(d.gw) + (size_t)g * n + 4 * sl;
-        v4f a = *(const gv4*)part;
-        for (int p = 1; p < gparts; ++p) a += *(const gv4*)(part + p * ps);
-        du[u] = a;
+        du[u] = sum_parts<v4f, 2>((const gv4*)part, ps >> 2, gparts);
       }
     }
   }
@@ -1296,6 +1326,159 @@ __device__ __forceinline__ void step_update(const LDesc& d, int tile, int t, lfl
       }
     }
   }
+}
+
+// ---- 3x3 layers on 2x2 and 4x4 maps (the 512-channel layers of VGG-11): matrix-vector products.
+// With 4 or 16 output pixels a 16-row MFMA tile is mostly padding and what matters is that the 9.4 MB of
+// weights go by once, in few workgroups.  A thread works on (output channel, input channel) pairs: the
+// pair's nine weights (36 contiguous bytes; consecutive lanes take consecutive input channels, so a
+// wavefront reads 2304 contiguous bytes) against the pair's two S x S maps, all index arithmetic of the
+// nine taps resolved at compile time.
+template <int S>
+__device__ __forceinline__ void corr_fwd(float (&acc)[S * S], const float (&w)[9], const float (&x)[S * S]) {
+#pragma unroll
+  for (int oh = 0; oh < S; ++oh)
+#pragma unroll
+    for (int ow = 0; ow < S; ++ow)
+#pragma unroll
+      for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+          const int ih = oh - 1 + kh, iw = ow - 1 + kw;
+          if (ih >= 0 && ih < S && iw >= 0 && iw < S) acc[oh * S + ow] = fmaf(w[kh * 3 + kw], x[ih * S + iw], acc[oh * S + ow]);
+        }
+}
+// dx[ih][iw] += sum_taps w[kh][kw] * dz[ih+1-kh][iw+1-kw]
+template <int S>
+__device__ __forceinline__ void corr_bwd(float (&acc)[S * S], const float (&w)[9], const float (&dz)[S * S]) {
+#pragma unroll
+  for (int ih = 0; ih < S; ++ih)
+#pragma unroll
+    for (int iw = 0; iw < S; ++iw)
+#pragma unroll
+      for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+          const int oh = ih + 1 - kh, ow = iw + 1 - kw;
+          if (oh >= 0 && oh < S && ow >= 0 && ow < S) acc[ih * S + iw] = fmaf(w[kh * 3 + kw], dz[oh * S + ow], acc[ih * S + iw]);
+        }
+}
+
+// Forward: workgroup `tile` computes output channels tile*R .. tile*R+R-1 (R = d.n).  Thread tid takes input
+// channels tid, tid+256, ...; per channel it holds the channel's map in registers and runs through the R rows,
+// RB rows of weights in flight at a time.  The R*S*S sums are then added up across the workgroup (lanes by DPP,
+// wavefronts through LDS, fixed order).
+template <int S, int R>
+__device__ __forceinline__ void step_dot_fwd_t(const LDesc& d, int tile, int t, lfloat* smem) {
+  constexpr int HW = S * S;
+  const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);
+  const int C = UNI(d.C), k0 = tile * R;
+  const gfloat* x = at(d.x, t);
+  const gfloat* w = GP(d.w) + (size_t)k0 * C * 9;
+  float acc[R][HW];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int i = 0; i < HW; ++i) acc[r][i] = 0.f;
+  for (int c = tid; c < C; c += BLK) {
+    float xv[HW];
+#pragma unroll
+    for (int q = 0; q < HW / 4; ++q) {
+      const v4f a = *(const gv4*)(x + c * HW + 4 * q);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) xv[4 * q + e] = a[e];
+    }
+    float wr[R][9];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int j = 0; j < 9; ++j) wr[r][j] = w[((size_t)r * C + c) * 9 + j];
+#pragma unroll
+    for (int r = 0; r < R; ++r) corr_fwd<S>(acc[r], wr[r], xv);
+  }
+  lfloat* red = smem;   // [4 wavefronts][R*HW]
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int i = 0; i < HW; ++i) {
+      const float sv = wave_sum(acc[r][i]);
+      if (lane == 0) red[wv * (R * HW) + r * HW + i] = sv;
+    }
+  __syncthreads();
+  if (tid < R * HW) {
+    const float sv = (red[tid] + red[R * HW + tid]) + (red[2 * R * HW + tid] + red[3 * R * HW + tid]);
+    at(d.y, t)[(size_t)k0 * HW + tid] = sv;
+  }
+}
+
+// Backward data: workgroup (cb, part) = (tile / parts, tile % parts) computes, for input channels cb*64 ..
+// cb*64+63, the sum over the part's output channels; wavefront wv takes every fourth of them.  dz of the
+// part sits in LDS.  The four wavefronts' sums are added through LDS in fixed order and written to the
+// gradient buffer (one part) or to the part's own copy, which the consumer of the gradient adds up.
+template <int S>
+__device__ __forceinline__ void step_dot_bwd_t(const LDesc& d, int tile, int t, lfloat* smem) {
+  constexpr int HW = S * S;
+  const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);
+  const int C = UNI(d.C), K = UNI(d.K), parts = UNI(d.gparts) > 1 ? UNI(d.gparts) : 1;
+  const int cb = UNI(fdiv(tile, frcp(parts))), part = tile - cb * parts;
+  const int kn = UNI(d.n), kbeg = part * kn, kcnt = (K - kbeg < kn) ? K - kbeg : kn;
+  const int c = cb * 64 + lane;
+  lfloat* dzs = smem;                     // [kn][HW]
+  lfloat* red = smem + kn * HW;           // [4][64][HW]
+  const gfloat* dz = at(d.dy, t) + (size_t)kbeg * HW;
+  for (int i = tid * 4; i < kcnt * HW; i += 4 * BLK) *(lv4*)(dzs + i) = *(const gv4*)(dz + i);
+  __syncthreads();
+  float acc[HW];
+#pragma unroll
+  for (int i = 0; i < HW; ++i) acc[i] = 0.f;
+  const gfloat* w = GP(d.w) + ((size_t)kbeg * C + c) * 9;
+  constexpr int KB = 4;                   // output channels whose weights are in flight together
+  for (int kk0 = wv; kk0 < kcnt; kk0 += 4 * KB) {
+    float wr[KB][9];
+#pragma unroll
+    for (int b = 0; b < KB; ++b) {
+      const int kk = kk0 + 4 * b;
+#pragma unroll
+      for (int j = 0; j < 9; ++j) wr[b][j] = (kk < kcnt && c < C) ? w[(size_t)kk * C * 9 + j] : 0.f;
+    }
+#pragma unroll
+    for (int b = 0; b < KB; ++b) {
+      const int kk = kk0 + 4 * b;
+      if (kk < kcnt) {
+        float dv[HW];
+#pragma unroll
+        for (int q = 0; q < HW / 4; ++q) {
+          const v4f a = *(const lv4*)(dzs + kk * HW + 4 * q);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dv[4 * q + e] = a[e];
+        }
+        corr_bwd<S>(acc, wr[b], dv);
+      }
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < HW / 4; ++q)
+    *(lv4*)(red + (wv * 64 + lane) * HW + 4 * q) = (v4f){acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+  __syncthreads();
+  if (wv == 0 && c < C) {
+    gfloat* out = (parts > 1) ? GP(d.gw) + (size_t)part * (size_t)UNI(d.gpstride) : at(d.dx, t);
+#pragma unroll
+    for (int q = 0; q < HW / 4; ++q) {
+      v4f a = *(const lv4*)(red + lane * HW + 4 * q);
+#pragma unroll
+      for (int w2 = 1; w2 < 4; ++w2) a += *(const lv4*)(red + (w2 * 64 + lane) * HW + 4 * q);
+      *(gv4*)(out + (size_t)c * HW + 4 * q) = a;
+    }
+  }
+}
+
+__device__ __forceinline__ void step_dot_fwd(const LDesc& d, int tile, int t, lfloat* smem) {
+  if (UNI(d.H) == 4) step_dot_fwd_t<4, 4>(d, tile, t, smem);
+  else step_dot_fwd_t<2, 8>(d, tile, t, smem);
+}
+__device__ __forceinline__ void step_dot_bwd_x(const LDesc& d, int tile, int t, lfloat* smem) {
+  if (UNI(d.H) == 4) step_dot_bwd_t<4>(d, tile, t, smem);
+  else step_dot_bwd_t<2>(d, tile, t, smem);
 }
 
 // Limits of the fused last stage (checked on the host): its input, the vector
@@ -2060,6 +2243,9 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     case K_UPDATE: step_update(d, tile, t, smem, NT); break;
     case K_HEAD: step_head(d, t, red, smem, NT); break;
     case K_GN_BWD: step_gn_bwd(d, tile, t, live, smem, NT); break;
+    // (planned only for networks tiled for throughput: the other instantiation carries no code for them)
+    case K_DOT_FWD: if (!NT) step_dot_fwd(d, tile, t, smem); break;
+    case K_DOT_BWD_X: if (!NT) step_dot_bwd_x(d, tile, t, smem); break;
     default: break;
   }
 #ifdef PB_TIMING

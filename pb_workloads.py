@@ -203,9 +203,9 @@ def config(name):
         st = preact_resnet_basic((6, 10), 1, 2, in_c=3, n_classes=5)
         return _net("odd_resnet", st, 3, 6, 6, 5, 0.02, 0.9, 16, 16, 100)
     if name == "thin_vgg":
-        # 144-channel 3x3 layers on 4x4 and 2x2 maps: matrix-vector-like layers whose weight gradient the
-        # engine computes inside the update step (as for the 512-channel layers of VGG-11)
-        st = vgg((16, 144, 144, 144), (0, 2, 3), 8, in_c=3, n_classes=5, in_hw=8)
+        # 192-channel 3x3 layers on 4x4 and 2x2 maps: matrix-vector-like layers that the engine runs as dot-product steps and whose weight gradient it
+        # computes inside the update step (as for the 512-channel layers of VGG-11)
+        st = vgg((16, 192, 192, 192), (0, 2, 3), 8, in_c=3, n_classes=5, in_hw=8)
         return _net("thin_vgg", st, 3, 8, 8, 5, 0.01, 0.9, 32, 18, 100)
     raise KeyError(name)
 
