@@ -82,6 +82,11 @@ typedef struct {
   float tile_budget_us;     /* > 0: tile for throughput with this budget for the longest tile (microseconds,
                                estimate); < 0: tile for latency whatever the network's size; 0: by size       */
   int32_t nt_stores;        /* kernel instantiation with non-temporal output stores: 1 on, -1 off, 0 by policy  */
+  int32_t one_launch;       /* one kernel launch per tick -- the workgroups of a later phase wait inside the launch
+                               for the stage's workgroups of the earlier phases --: 1 on, -1 off, 0 by policy
+                               (on where a tick has no more workgroups than the GPU has compute units)             */
+  int32_t spin_limit;       /* bound of such a wait, in polls (0 = default, 65536: a fraction of a second); when it expires the
+                               step is skipped and the next synchronising call returns PB_E_HIP                    */
 } pb_tuning;
 
 typedef struct {

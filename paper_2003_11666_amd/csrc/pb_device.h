@@ -123,6 +123,11 @@ struct StepDesc {
                             // (K_GEMM backward weights writes one of them, K_UPDATE sums them in order)
   int32_t upd_n, upd_t0;    // K_UPDATE: update size N (gradients of N consecutive samples per update) and the tick of the
                             // stage's first backward pass
+  // One launch per tick (all phases in one grid): a workgroup of a later phase waits until the counters
+  // wait_idx[i] have reached wait_n[i] x (ticks so far), i.e. until the stage's workgroups of the earlier
+  // phases are done, and every workgroup adds one to counter sig_idx when it is done
+  int32_t sig_idx, nwait;
+  int32_t wait_idx[3], wait_n[3];
   int32_t grain;            // > 0: streaming form of an elementwise step, floats per workgroup (K_COPY, K_GNB_APPLY);
                             // K_GNB_REDUCE: 1 = one wavefront per channel
   GemmCfg g;     // main operand set of a K_GEMM step
@@ -168,8 +173,12 @@ struct Globals {
 };
 
 // ---- launch wrappers implemented in pb_kernels.hip ----
+// sync != nullptr: the grid holds every phase of the tick; sync[SYNC_ERR] collects errors, sync[SYNC_SPIN] is the
+// bound of a dependency wait (iterations), sync[SYNC_CNT + i] are the completion counters; tick_ordinal counts the
+// ticks launched in this form since the counters were cleared, starting at 1
+constexpr int SYNC_ERR = 0, SYNC_SPIN = 1, SYNC_CNT = 16;
 void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, const float* sample_override,
-                  int label_override, bool nt, hipStream_t s);
+                  int label_override, bool nt, hipStream_t s, int32_t* sync = nullptr, uint32_t tick_ordinal = 0);
 void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,
                    int n_stages, const Globals* G, int k, hipStream_t s);
 void launch_update_flat(float* w, float* v, const float* g, float* what, int64_t n, float lr, float m,

@@ -2178,7 +2178,7 @@ __device__ __forceinline__ void step_head(const LDesc& d, int t, lfloat* red, lf
 template <bool NT>
 __global__ void __launch_bounds__(BLK) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
-        const float* __restrict__ sample_override, int label_override) {
+        const float* __restrict__ sample_override, int label_override, int32_t* __restrict__ sync, uint32_t tick_ordinal) {
   __shared__ float red_[8];
   __shared__ __attribute__((aligned(16))) float smem_[LDS_FLOATS];
   lfloat* red = (lfloat*)red_;
@@ -2223,7 +2223,36 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
   }
   const int tile = UNI(d.tile);
   const bool live = t >= UNI(d.first_tick);
-  if (!live && !(UNI(d.flags) & F_ALWAYS)) return;
+  bool run = live || (UNI(d.flags) & F_ALWAYS);
+  // One launch per tick: the grid holds the workgroups of every phase, in phase order.  Workgroups are handed
+  // out in index order, so when a workgroup of a later phase runs, the workgroups it depends on (lower
+  // indices: the same stage's steps of the earlier phases) are running or done; it waits for their completion
+  // counters.  The wait is bounded: on expiry the error word is set and the step is skipped, so that the grid
+  // always drains.
+  if (sync != nullptr && UNI(d.nwait) > 0) {
+    __shared__ int wait_ok_;
+    if (threadIdx.x == 0) {
+      const int limit = ((const gint*)sync)[SYNC_SPIN];
+      // (once a wait has expired anywhere, nobody waits any more: the rest of the work drains at once)
+      int ok = __hip_atomic_load(sync + SYNC_ERR, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0, it = 0;
+      for (int q = 0; q < d.nwait && ok; ++q) {
+        const uint32_t target = tick_ordinal * (uint32_t)d.wait_n[q];
+        while ((int32_t)((uint32_t)__hip_atomic_load(sync + SYNC_CNT + d.wait_idx[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+          if (++it > limit) { ok = 0; break; }
+          __builtin_amdgcn_s_sleep(2);
+        }
+      }
+      if (!ok) __hip_atomic_fetch_or(sync + SYNC_ERR, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // what the producers wrote before they counted themselves done is visible from here on: one wavefront's
+      // acquire drops the stale lines of this compute unit's vector cache and of this XCD's L2 for all four,
+      // which read nothing of it before the barrier
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      wait_ok_ = ok;
+    }
+    __syncthreads();
+    if (!wait_ok_) run = false;
+  }
+  if (run) {
   switch (UNI(d.kind)) {
     case K_GN_STATS:
       if (UNI(d.grain) == 1) step_gn_stats_wave(d, t, smem, NT); else step_gn_stats(d, tile, t, red, smem, NT);
@@ -2247,6 +2276,17 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     case K_DOT_FWD: if (!NT) step_dot_fwd(d, tile, t, smem); break;
     case K_DOT_BWD_X: if (!NT) step_dot_bwd_x(d, tile, t, smem); break;
     default: break;
+  }
+  }
+  if (sync != nullptr && UNI(d.sig_idx) >= 0) {
+    // every wavefront waits until its own stores have reached the L2, then the barrier; the release by one
+    // thread then writes that L2's dirty lines back, so that the other XCDs see them before the counter says so
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      __hip_atomic_fetch_add(sync + SYNC_CNT + d.sig_idx, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
 #ifdef PB_TIMING
   PB_TS(11);
@@ -2388,10 +2428,10 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
 }
 
 void launch_phase(const StepDesc* recs_dev, int total_tiles, const Globals* G, int k, const float* sample_override,
-                  int label_override, bool nt, hipStream_t s) {
+                  int label_override, bool nt, hipStream_t s, int32_t* sync, uint32_t tick_ordinal) {
   if (total_tiles <= 0) return;
-  if (nt) hipLaunchKernelGGL(k_phase<true>, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, G, k, sample_override, label_override);
-  else hipLaunchKernelGGL(k_phase<false>, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, G, k, sample_override, label_override);
+  if (nt) hipLaunchKernelGGL(k_phase<true>, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, G, k, sample_override, label_override, sync, tick_ordinal);
+  else hipLaunchKernelGGL(k_phase<false>, dim3(total_tiles), dim3(BLK), 0, s, recs_dev, G, k, sample_override, label_override, sync, tick_ordinal);
 }
 
 void launch_ingest(TRef ring0, int n_elems, const float* staging, int label, int32_t* label_ring,

@@ -546,3 +546,44 @@ def test_weight_gradient_inside_the_update_step():
     # the same network tiled for latency runs the GEMM form of the same gradient: both against the oracle
     res = run_parity(_engine(), net, K)
     _check(res, K, len(net["stages"]), "thin_vgg/gemm_wgrad/80")
+
+
+@pytest.mark.parametrize("name", ["tiny_mlp", "tiny_vgg", "small_resnet", "tiny_bottleneck", "resnet20"])
+def test_one_launch_per_tick_is_bit_identical(name):
+    """All phases of a tick in one launch, a later phase's workgroups waiting on completion counters for their
+    stage's earlier steps: same records, same arithmetic as one launch per phase."""
+    import torch
+    PBEngine = _engine()
+    net = W.config(name)
+    xs, ys = W.sample_pool(net)
+    xd, yd = torch.from_numpy(xs).cuda(), torch.from_numpy(ys).cuda()
+    outs = []
+    for one in (-1, 1):
+        e = PBEngine(net, tuning=dict(one_launch=one))
+        for t in range(30):
+            e.tick(xs[t % len(ys)], ys[t % len(ys)])
+        e.run_resident(xd, yd, 30, 170)
+        outs.append((e.read_weights(), e.read_velocity(), e.loss_history()))
+        e.close()
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    assert np.all(np.isfinite(outs[1][0])) and len(outs[1][2]) == 200 - len(net["stages"]) + 1
+
+
+def test_one_launch_per_tick_wait_expires_cleanly():
+    """The wait is bounded: with a bound of a single poll the workgroups of the second phase give up, the
+    launch drains, and the next synchronising call reports the failure instead of returning numbers."""
+    from paper_2003_11666_amd.binding import PBError
+    PBEngine = _engine()
+    net = W.config("small_resnet")
+    xs, ys = W.sample_pool(net)
+    e = PBEngine(net, tuning=dict(one_launch=1, spin_limit=1))
+    for t in range(20):
+        e.tick(xs[t % len(ys)], ys[t % len(ys)])
+    with pytest.raises(PBError, match="expired"):
+        e.read_weights()
+    e.close()
+    # the sample-indexed form has dependencies between stages inside a tick: refused
+    S = len(net["stages"])
+    with pytest.raises(PBError, match="one launch per tick"):
+        PBEngine(net, delays=[0] * S, tuning=dict(one_launch=1))
