@@ -85,6 +85,9 @@ typedef struct {
   int32_t one_launch;       /* one kernel launch per tick -- the workgroups of a later phase wait inside the launch
                                for the stage's workgroups of the earlier phases --: 1 on, -1 off, 0 by policy
                                (on where a tick has no more workgroups than the GPU has compute units)             */
+  int32_t tail_merge;       /* n > 0: the phases from phase n on share one launch in the same way (n = 0 with
+                               one_launch = 1); 0 or -1: off (measured slower on every configuration); -2: the
+                               longest run of last phases that hold steps of at most two stages                    */
   int32_t spin_limit;       /* bound of such a wait, in polls (0 = default, 65536: a fraction of a second); when it expires the
                                step is skipped and the next synchronising call returns PB_E_HIP                    */
 } pb_tuning;

@@ -256,7 +256,7 @@ struct Layout {
 
 // A convolution over a large map with few weights has a weight gradient that is a long
 // reduction with few output tiles: such a stage gets room for partial gradients.
-constexpr int MAX_SYNC_PHASES = 4;   // one launch per tick: phases a tick may have (a step waits for at most three earlier ones)
+constexpr int MAX_SYNC_PHASES = 8;   // phases that may share one launch (completion counters per stage and phase)
 constexpr int GRAD_PARTS = 16;
 // A layer on a map of at most 16 pixels with a long reduction is a matrix-vector product: its
 // forward GEMM has as many tiles as it has blocks of 16 output channels, each streaming its rows of
@@ -351,6 +351,7 @@ void plan_arena(const std::vector<Stage>& st, bool stash, int loss_cap, Layout& 
 struct Phase {
   std::vector<int> step_idx;       // indices into steps, in launch order
   int first = 0, count = 0, tiles = 0;
+  bool fused = false;              // holds several phases: its workgroups wait for each other through completion counters
 };
 
 }  // namespace
@@ -378,7 +379,8 @@ struct pb_ctx {
   bool bf16 = false;   // bf16 activation mode: tensors that cross a stage boundary are rounded to bf16
   int N = 1;           // update size: samples per update
   pb_tuning tune = {0, 0, 0.f, 0, 0, 0};
-  bool one_launch = false;     // every phase of a tick in one launch, dependencies through completion counters
+  int fuse_from = -1;          // >= 0: the phases from this one on share one launch, dependencies through completion
+                               // counters (0: one launch per tick)
   uint32_t fused_ticks = 0;    // ticks launched in that form so far
   int32_t* sync_dev = nullptr; // error word, wait bound, counters
   std::vector<StepDesc> steps;         // sorted by phase
@@ -1395,7 +1397,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
 
 // Launch order: by phase; inside a phase the steps are independent of each
 // other, and as its longest workgroups bound the phase they go first in the grid.
-void order_steps(std::vector<std::pair<int, StepDesc>>& tagged, bool one_launch = false) {
+void order_steps(std::vector<std::pair<int, StepDesc>>& tagged, bool one_launch = false) {   // one_launch: every phase in one launch
   auto step_cost = [](const StepDesc& d) -> int64_t {
     if (d.kind == K_HEAD) return (int64_t)1 << 40;
     if (g_tile_budget_us > 0) {
@@ -1786,11 +1788,11 @@ void init_weights_host(const std::vector<Stage>& st, uint64_t seed, std::vector<
 
 // After the stream has been synchronised: did a dependency wait of a one-launch tick expire?
 int check_device_error(pb_ctx* c) {
-  if (!c->one_launch) return PB_OK;
+  if (c->fuse_from < 0) return PB_OK;
   int32_t err = 0;
   if (hipMemcpy(&err, c->sync_dev + SYNC_ERR, sizeof err, hipMemcpyDeviceToHost) != hipSuccess)
     return fail(PB_E_HIP, "device to host copy failed");
-  if (err) return fail(PB_E_HIP, "a workgroup's wait for the steps it depends on expired (one launch per tick): results are invalid");
+  if (err) return fail(PB_E_HIP, "a workgroup's wait for the steps it depends on expired (phases sharing a launch): results are invalid");
   return PB_OK;
 }
 
@@ -1832,14 +1834,13 @@ int run_one_tick(pb_ctx* c, const float* staging, int label) {
   // the kernels index every ring with a 32-bit tick counter
   if (c->ticks >= (int64_t)0x7fffff00) return fail(PB_E_UNSUPPORTED, "tick counter exhausted (2^31 ticks): start a new context");
   const int k = (int)c->ticks;   // t_base stays 0 on this path
-  if (c->launch_mode == 0 && c->one_launch) {
-    const Phase& p = c->phases[0];
-    ScopedEv ev(c, 0);
-    launch_phase(c->recs_dev, p.tiles, c->globals_dev, k, staging, label, c->nt_stores, c->stream, c->sync_dev, ++c->fused_ticks);
-  } else if (c->launch_mode == 0) {
+  if (c->launch_mode == 0) {
+    bool counted = false;
     for (const Phase& p : c->phases) {
       ScopedEv ev(c, 0);
-      launch_phase(c->recs_dev + c->rec_first[p.first], p.tiles, c->globals_dev, k, staging, label, c->nt_stores, c->stream);
+      if (p.fused && !counted) { ++c->fused_ticks; counted = true; }
+      launch_phase(c->recs_dev + c->rec_first[p.first], p.tiles, c->globals_dev, k, staging, label, c->nt_stores, c->stream,
+                   p.fused ? c->sync_dev : nullptr, p.fused ? c->fused_ticks : 0u);
     }
   } else {
     // one launch per step (same records, same arithmetic); event classes: 1 = update steps, 2 = ingest
@@ -2023,42 +2024,80 @@ int init_common(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, flo
   if (validate_steps(c, tagged, pl.total) != PB_OK) { pb_destroy(c); return PB_E_INVALID; }
   int n_ph_all = 0;
   for (auto& p : tagged) n_ph_all = std::max(n_ph_all, p.first + 1);
-  // one launch per tick: pipelined form only (in the sample-indexed form steps of different stages depend on each
-  // other inside a tick), at most MAX_SYNC_PHASES phases.  By policy only where the tick's workgroups number no
-  // more than the compute units: then all of them are resident at once, no waiting workgroup can hold a
-  // producer's place, and the launch boundary saved outweighs what the per-workgroup release and acquire cost
-  // (measured: a tick of 165 workgroups gains 7 %, one of 944 workgroups takes twice as long).
+  // Phases sharing a launch: pipelined form only (in the sample-indexed form steps of different stages depend on
+  // each other inside a tick).
+  //  * One launch per tick.  By policy only where the tick's workgroups number no more than the compute units:
+  //    then all of them are resident at once, no waiting workgroup can hold a producer's place, and the launch
+  //    boundary saved outweighs what the per-workgroup release and acquire cost (measured: a tick of 165
+  //    workgroups gains 7 %, one of 944 workgroups takes twice as long).
+  //  * The last phases in one launch.  A deep network's last phases hold the dependency chains of one or two
+  //    stages only (the loss stage runs forward and backward in the same tick, the first stage's weight
+  //    gradient is split and summed): a few hundred workgroups each, a launch each.  On request (tail_merge n)
+  //    the phases from n on share a launch; only the workgroups of stages with a dependency inside it signal
+  //    and wait.  Not chosen by policy: measured on the 50-stage network (phases 2-6 in one launch, about 3000
+  //    of 9000 workgroups signalling or waiting) the tick takes 1215 us instead of 1125 -- a workgroup's release
+  //    and acquire write back and invalidate its XCD's L2, which costs the other workgroups more than the four
+  //    launch boundaries did -- and VGG-11 and the wide network lose as well (tail_merge -2 selects the
+  //    candidate rule: the longest run of last phases with steps of at most two stages).
+  std::vector<int64_t> wg_of(n_ph_all, 0);
+  for (auto& p : tagged) wg_of[p.first] += p.second.ntiles;
+  int n_cu = 0, cur_dev = 0;
+  INIT_TRY(hipGetDevice(&cur_dev));
+  INIT_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, cur_dev));
   const bool can_fuse = !c->sequential && n_ph_all >= 2 && n_ph_all <= MAX_SYNC_PHASES;
   if (c->tune.one_launch > 0 && !can_fuse) {
     pb_destroy(c);
     return fail(PB_E_UNSUPPORTED, "one launch per tick needs the pipelined form and 2..%d phases (this network has %d)", MAX_SYNC_PHASES, n_ph_all);
   }
-  if (c->tune.one_launch != 0) {
-    c->one_launch = c->tune.one_launch > 0;
-  } else {
+  c->fuse_from = -1;
+  if (c->tune.one_launch > 0) {
+    c->fuse_from = 0;
+  } else if (c->tune.one_launch == 0) {
     int64_t n_wg = 0;
-    for (auto& p : tagged) n_wg += p.second.ntiles;
-    int n_cu = 0, cur_dev = 0;
-    INIT_TRY(hipGetDevice(&cur_dev));
-    INIT_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, cur_dev));
-    c->one_launch = can_fuse && n_wg <= n_cu;
+    for (int64_t n : wg_of) n_wg += n;
+    if (can_fuse && n_wg <= n_cu) c->fuse_from = 0;
   }
-  order_steps(tagged, c->one_launch);
-  if (c->one_launch) {
-    // completion counter (stage, phase): workgroups of that stage in that phase
-    std::vector<int> cnt((size_t)c->S * MAX_SYNC_PHASES, 0);
-    for (auto& p : tagged) cnt[(size_t)p.second.stage * MAX_SYNC_PHASES + p.first] += p.second.ntiles;
-    for (auto& p : tagged) {
-      StepDesc& d = p.second;
-      d.sig_idx = p.first + 1 < n_ph_all ? d.stage * MAX_SYNC_PHASES + p.first : -1;
-      d.nwait = 0;
-      for (int q = 0; q < p.first; ++q) {
-        const int n = cnt[(size_t)d.stage * MAX_SYNC_PHASES + q];
-        if (n > 0) { d.wait_idx[d.nwait] = d.stage * MAX_SYNC_PHASES + q; d.wait_n[d.nwait] = n; ++d.nwait; }
-      }
+  if (c->fuse_from < 0 && c->tune.tail_merge > 0) {
+    if (c->sequential || c->tune.tail_merge > n_ph_all - 2 || n_ph_all - c->tune.tail_merge > MAX_SYNC_PHASES) {
+      pb_destroy(c);
+      return fail(PB_E_UNSUPPORTED, "tail_merge %d: needs the pipelined form, at least two phases from there on and at most %d (this network has %d phases)",
+                  c->tune.tail_merge, MAX_SYNC_PHASES, n_ph_all);
     }
-  } else {
-    for (auto& p : tagged) { p.second.sig_idx = -1; p.second.nwait = 0; }
+    c->fuse_from = c->tune.tail_merge;
+  } else if (c->fuse_from < 0 && c->tune.tail_merge == -2 && !c->sequential) {
+    // the longest run of last phases that have at most 8 workgroups per compute unit each and, together, steps
+    // of at most two stages; it joins the phase before it
+    int first_light = n_ph_all;
+    for (int ph = n_ph_all - 1; ph >= 2; --ph) {
+      std::vector<int> stages;
+      for (auto& p : tagged)
+        if (p.first >= ph && std::find(stages.begin(), stages.end(), p.second.stage) == stages.end()) stages.push_back(p.second.stage);
+      if (wg_of[ph] > 8 * (int64_t)n_cu || stages.size() > 2) break;
+      first_light = ph;
+    }
+    if (first_light < n_ph_all && n_ph_all - (first_light - 1) <= MAX_SYNC_PHASES) c->fuse_from = first_light - 1;
+  }
+  order_steps(tagged, c->fuse_from == 0);
+  for (auto& p : tagged) { p.second.sig_idx = -1; p.second.nwait = 0; }
+  if (c->fuse_from >= 0) {
+    // completion counter (stage, phase): workgroups of that stage in that phase.  A step waits for the nearest
+    // earlier phase of the launch that holds work of its stage (whose workgroups waited for the one before in
+    // their turn); a step signals if a later phase holds work of its stage.
+    const int f0 = c->fuse_from, nf = n_ph_all - f0;
+    std::vector<int> cnt((size_t)c->S * MAX_SYNC_PHASES, 0);
+    for (auto& p : tagged)
+      if (p.first >= f0) cnt[(size_t)p.second.stage * MAX_SYNC_PHASES + (p.first - f0)] += p.second.ntiles;
+    for (auto& p : tagged) {
+      if (p.first < f0) continue;
+      StepDesc& d = p.second;
+      const int me = p.first - f0;
+      for (int q = me - 1; q >= 0; --q) {
+        const int n = cnt[(size_t)d.stage * MAX_SYNC_PHASES + q];
+        if (n > 0) { d.wait_idx[0] = d.stage * MAX_SYNC_PHASES + q; d.wait_n[0] = n; d.nwait = 1; break; }
+      }
+      for (int q = me + 1; q < nf; ++q)
+        if (cnt[(size_t)d.stage * MAX_SYNC_PHASES + q] > 0) { d.sig_idx = d.stage * MAX_SYNC_PHASES + me; break; }
+    }
   }
   const int n_steps = (int)tagged.size();
   c->steps.resize(n_steps);
@@ -2080,11 +2119,13 @@ int init_common(pb_ctx** out, const pb_net_desc* net, const int32_t* delays, flo
     c->phases[ph].count++;
     c->phases[ph].tiles = acc;
   }
-  if (c->one_launch) {
+  if (c->fuse_from >= 0) {
     // (launch mode 1 still walks the steps one by one, in this same order: phase by phase)
-    Phase all;
-    all.first = 0; all.count = n_steps; all.tiles = (int)recs.size();
-    c->phases.assign(1, all);
+    Phase& m = c->phases[c->fuse_from];
+    m.fused = true;
+    m.count = n_steps - m.first;
+    m.tiles = (int)(recs.size() - (size_t)c->rec_first[m.first]);
+    c->phases.resize(c->fuse_from + 1);
   }
   const int64_t o_recs = pl.alloc((int64_t)recs.size() * sizeof(StepDesc) / 4 + 64);
   if ((size_t)pl.total * sizeof(float) > need) { pb_destroy(c); return fail(PB_E_NOMEM, "internal: arena plan mismatch"); }

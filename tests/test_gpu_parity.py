@@ -587,3 +587,25 @@ def test_one_launch_per_tick_wait_expires_cleanly():
     S = len(net["stages"])
     with pytest.raises(PBError, match="one launch per tick"):
         PBEngine(net, delays=[0] * S, tuning=dict(one_launch=1))
+
+
+@pytest.mark.parametrize("name,first", [("tiny_vgg", 1), ("tiny_vgg", 2), ("tiny_bottleneck", 1), ("resnet50", -2)])
+def test_last_phases_in_one_launch_are_bit_identical(name, first):
+    """The phases from `first` on share one launch (-2: the last phases that hold steps of at most two stages,
+    which for the deep network are the dependency chains of the loss stage and of the first stage): same records,
+    same arithmetic as one launch per phase."""
+    import torch
+    PBEngine = _engine()
+    net = W.config(name)
+    xs, ys = W.sample_pool(net)
+    xd, yd = torch.from_numpy(xs).cuda(), torch.from_numpy(ys).cuda()
+    n = 2 * len(net["stages"]) + 30
+    outs = []
+    for tail in (-1, first):
+        e = PBEngine(net, tuning=dict(one_launch=-1, tail_merge=tail))
+        e.run_resident(xd, yd, 0, n)
+        outs.append((e.read_weights(), e.read_velocity(), e.loss_history()))
+        e.close()
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    assert np.all(np.isfinite(outs[1][0])) and len(outs[1][2]) == n - len(net["stages"]) + 1
