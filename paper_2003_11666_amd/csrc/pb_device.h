@@ -44,8 +44,13 @@ enum StepKind : int32_t {
   K_GN_BWD = 15,     // GroupNorm backward of one group in one workgroup: channel sums and dx together
   K_DOT_FWD = 16,    // forward of a 3x3 layer (stride 1, padding 1) on a 2x2 or 4x4 map as dot products: d.n output
                      // channels per workgroup, the weights streamed once, no MFMA, no LDS tiles
-  K_DOT_BWD_X = 17   // backward data of such a layer: 64 input channels per workgroup and a d.n-th of the output
+  K_DOT_BWD_X = 17,  // backward data of such a layer: 64 input channels per workgroup and a d.n-th of the output
                      // channels (d.gparts parts, summed by the consumer of the gradient when there are several)
+  // A dense layer on one sample is a matrix-vector product (networks tiled for throughput, input length a multiple
+  // of 4): nothing for the matrix cores, a stream of the weight matrix.
+  K_FC_FWD = 18,     // y = W x + b: a wavefront per output, four outputs per workgroup
+  K_FC_BWD_X = 19,   // dx = W^T dy: 64 inputs per workgroup, the outputs dealt out to 16 groups of 16 lanes
+  K_FC_BWD_W = 20    // gW = dy x^T: 4096 consecutive weights per workgroup
 };
 
 constexpr int LDS_FLOATS = 15872;   // 62 KB of LDS per workgroup for the GEMM steps (two workgroups per compute unit)

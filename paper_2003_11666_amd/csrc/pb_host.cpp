@@ -734,6 +734,16 @@ void gemm_tables(pb_ctx* c, const GemmCfg& g, int C, int H, int W, int K, int OH
   (void)C; (void)H; (void)K; (void)OH;
 }
 
+// A dense layer on one sample (1x1 maps on both sides) whose operands allow 16-byte accesses: its three passes
+// run as matrix-vector steps (K_FC_*) in networks tiled for throughput.
+// (Kept out of line: inlined into the planner, hipcc 7.2 -O3 evaluated it to false at the weight-gradient call site
+// with every one of its terms true; out of line it is right at all three.)
+__attribute__((noinline)) bool fc_layer(const pb_ctx* c, const StepDesc& d, const float* w) {
+  return c->kernel_set == 0 && g_tile_budget_us > 0 && d.H == 1 && d.W == 1 && d.OH == 1 && d.OW == 1 && d.k == 1 && d.stride == 1 &&
+         d.pad == 0 && d.C % 4 == 0 && d.C >= 256 && d.K >= 1 && d.K <= 8192 && (int64_t)d.K * d.C < ((int64_t)1 << 30) &&
+         w && ((uintptr_t)w - (uintptr_t)c->f(0)) % 16 == 0 && ((d.pmask & PF_W) == 0 || d.pstride % 4 == 0);
+}
+
 // Whether the A operand of a GEMM step (of its projection operand set if
 // `second`) starts on a 16-byte boundary in every ring slot.
 bool a_aligned(const pb_ctx* c, const StepDesc& d, bool second) {
@@ -1006,6 +1016,10 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         d.n = a.H == 4 ? 4 : 8;            // output channels per workgroup
         d.ntiles = a.K / d.n;
       } else
+      if (fc_layer(c, d, d.w) && !(d.flags & (F_PRE_AFFINE | F_PRE_RELU | F_SKIP | F_PROJ)) && ref_vec4(c, d.x)) {
+        d.kind = K_FC_FWD;
+        d.ntiles = cdiv(d.K, BLK / 64);
+      } else
       if (c->kernel_set == 0) {
         GemmCfg g, gp;
         memset(&gp, 0, sizeof gp);
@@ -1125,8 +1139,18 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
                           a.pad == 1 && a.H == a.W && (a.H == 2 || a.H == 4) && a.OH == a.H && a.OW == a.W && !a.gap &&
                           !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)) && !a.has_bias && a.C * 9 >= 1171 && a.C * a.H * a.W <= 8192 &&
                           a.n_w % 4 == 0 && a.n_w >= 65536 && b.gparts < 0 && ref_vec4(c, d.x) && ref_vec4(c, d.dy);
+      const bool fc_w = fc_layer(c, d, d.gw) && !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)) && ref_vec4(c, d.x);
       if (fuse_w) {
         fusedw[s].phase = pb; fusedw[s].x = d.x; fusedw[s].dy = d.dy;
+      } else if (fc_w) {
+        if (a.has_bias) {
+          StepDesc e = blank(K_BIAS_GRAD, s, t_b);
+          e.K = a.K; e.OH = a.OH; e.OW = a.OW; e.dy = dz_src; e.gb = gr + a.o_b;
+          e.ntiles = cdiv(a.K, BLK / 64);
+          out.push_back({pb, e});
+        }
+        d.kind = K_FC_BWD_W; d.flags &= ~F_BIAS;
+        d.ntiles = cdiv((int64_t)d.K * d.C, 4096);
       } else
       if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g,
                                           !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)), 16, false, b.gparts >= 0 ? GRAD_PARTS : 1)) {
@@ -1166,6 +1190,10 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
                            !(d.flags & (F_MASK_X | F_ADD_SKG | F_BF16_OUT)) && !flat;
       const bool dot_bwd = c->kernel_set == 0 && g_tile_budget_us > 0 && !c->bf16 && dot_layer(a) && !(d.flags & (F_MASK_X | F_ADD_SKG | F_BF16_OUT)) &&
                            ref_vec4(c, d.dy) && ref_vec4(c, d.dx);
+      if (fc_layer(c, d, d.w) && !(d.flags & (F_MASK_X | F_ADD_SKG)) && ref_vec4(c, d.dx)) {
+        d.kind = K_FC_BWD_X;
+        d.ntiles = cdiv(d.C, 64);
+      } else
       if (dot_bwd) {
         // 64 input channels per workgroup; the output channels in as many parts as the gradient's consumer can
         // add up, so that the layer's weights are spread over C/64 x parts workgroups
@@ -1289,7 +1317,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   if (c->sequential) {
     auto is_bwd = [](const StepDesc& d) {
       return d.kind == K_GNB_REDUCE || d.kind == K_GNB_APPLY || d.kind == K_GN_BWD || d.kind == K_CONV_BWD_X ||
-             d.kind == K_CONV_BWD_W || d.kind == K_BIAS_GRAD || d.kind == K_COPY || d.kind == K_DOT_BWD_X || (d.kind == K_GEMM && d.g.gm != 1);
+             d.kind == K_CONV_BWD_W || d.kind == K_BIAS_GRAD || d.kind == K_COPY || d.kind == K_DOT_BWD_X || d.kind == K_FC_BWD_X || d.kind == K_FC_BWD_W || (d.kind == K_GEMM && d.g.gm != 1);
     };
     std::vector<int> lenF(S, 0), lenB(S, 0), baseF(S, 0), baseB(S, 0);
     for (auto& pr : out) {
@@ -1382,7 +1410,8 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     if (pr.second.kind == K_GEMM && ((pr.second.g.gm != 3 && pr.second.g.parts > 1) || pr.second.g.nsub > 1 || pr.second.g.win > 0 ||
                                     pr.second.gp.nsub > 1 || pr.second.gp.win > 0)) c->nt_stores = false;
   for (auto& pr : out)
-    if ((pr.second.kind == K_UPDATE && (pr.second.flags & F_WGRAD)) || pr.second.kind == K_DOT_FWD || pr.second.kind == K_DOT_BWD_X)
+    if ((pr.second.kind == K_UPDATE && (pr.second.flags & F_WGRAD)) || pr.second.kind == K_DOT_FWD || pr.second.kind == K_DOT_BWD_X ||
+        pr.second.kind == K_FC_FWD || pr.second.kind == K_FC_BWD_X || pr.second.kind == K_FC_BWD_W)
       c->nt_stores = false;
   if (c->nt_stores) {
     std::vector<char> long_gemm;
@@ -1620,6 +1649,18 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
       }
       case K_BIAS_GRAD:
         ok = ok && d.ntiles * (BLK / 64) >= d.K && ref_ok(d.dy, outn) && ptr_ok(d.gb, d.K);
+        break;
+      case K_FC_FWD:
+        ok = ok && !c->nt_stores && fc_layer(c, d, d.w) && !(d.flags & ~(F_ALWAYS | F_BIAS | F_BF16_OUT)) && d.ntiles == cdiv(d.K, BLK / 64) &&
+             ref_ok(d.x, d.C) && ref_vec4(c, d.x) && ref_ok(d.y, d.K) && ptr_ok(d.w, (int64_t)d.K * d.C) && (!(d.flags & F_BIAS) || ptr_ok(d.b, d.K));
+        break;
+      case K_FC_BWD_X:
+        ok = ok && !c->nt_stores && fc_layer(c, d, d.w) && !(d.flags & ~(F_ALWAYS | F_BF16_OUT)) && d.ntiles == cdiv(d.C, 64) &&
+             (d.K + 3) / 4 * 4 + 16 * 64 <= LDS_FLOATS && ref_ok(d.dy, d.K) && ref_ok(d.dx, d.C) && ptr_ok(d.w, (int64_t)d.K * d.C);
+        break;
+      case K_FC_BWD_W:
+        ok = ok && !c->nt_stores && fc_layer(c, d, d.gw) && !(d.flags & ~F_ALWAYS) && d.ntiles == cdiv((int64_t)d.K * d.C, 4096) &&
+             ref_ok(d.x, d.C) && ref_vec4(c, d.x) && ref_ok(d.dy, d.K) && ptr_ok(d.gw, (int64_t)d.K * d.C);
         break;
       case K_DOT_FWD: {
         const int R = d.H == 4 ? 4 : 8;
@@ -1905,7 +1946,7 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
   compile_steps(&tmp, steps);
   order_steps(steps);
   static const char* names[] = {"gn_stats", "gap_fwd", "conv_fwd", "post_fwd", "ce", "gnb_reduce", "gnb_apply",
-                                "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad", "ingest", "update", "head", "gn_bwd", "dot_fwd", "dot_bwd_x"};
+                                "conv_bwd_x", "conv_bwd_w", "copy", "gemm", "bias_grad", "ingest", "update", "head", "gn_bwd", "dot_fwd", "dot_bwd_x", "fc_fwd", "fc_bwd_x", "fc_bwd_w"};
   std::string o;
   char line[400];
   for (auto& pr : steps) {

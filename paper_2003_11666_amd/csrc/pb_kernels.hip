@@ -1481,6 +1481,94 @@ __device__ __forceinline__ void step_dot_bwd_x(const LDesc& d, int tile, int t, 
   else step_dot_bwd_t<2>(d, tile, t, smem);
 }
 
+// ---- Dense layer on one sample (a matrix-vector product): the weight matrix is streamed once, with 16-byte
+// loads; C (inputs) is a multiple of 4, the operands are 16-byte aligned.
+// Forward, y[k] = b[k] + sum_c w[k][c] x[c]: a wavefront per output k.
+__device__ __forceinline__ void step_fc_fwd(const LDesc& d, int tile, int t) {
+  const int lane = threadIdx.x & 63, k = tile * (BLK / 64) + UNI((int)(threadIdx.x >> 6));
+  const int C = UNI(d.C);
+  if (k >= UNI(d.K)) return;
+  const gfloat* x = at(d.x, t);
+  const gfloat* w = GP(d.w) + (size_t)k * C;
+  float s0 = 0.f, s1 = 0.f;
+  int c = 4 * lane;
+  for (; c + 256 < C; c += 512) {
+    const v4f a0 = *(const gv4*)(w + c), b0 = *(const gv4*)(x + c);
+    const v4f a1 = *(const gv4*)(w + c + 256), b1 = *(const gv4*)(x + c + 256);
+    s0 = fmaf(a0[3], b0[3], fmaf(a0[2], b0[2], fmaf(a0[1], b0[1], fmaf(a0[0], b0[0], s0))));
+    s1 = fmaf(a1[3], b1[3], fmaf(a1[2], b1[2], fmaf(a1[1], b1[1], fmaf(a1[0], b1[0], s1))));
+  }
+  if (c < C) {
+    const v4f a0 = *(const gv4*)(w + c), b0 = *(const gv4*)(x + c);
+    s0 = fmaf(a0[3], b0[3], fmaf(a0[2], b0[2], fmaf(a0[1], b0[1], fmaf(a0[0], b0[0], s0))));
+  }
+  const float s = wave_sum(s0 + s1);
+  if (lane == 0) {
+    const float v = s + ((UNI(d.flags) & F_BIAS) ? GP(d.b)[k] : 0.f);
+    at(d.y, t)[k] = rbf_if(UNI(d.flags) & F_BF16_OUT, v);
+  }
+}
+
+// Backward data, dx[c] = sum_k w[k][c] dy[k]: a workgroup takes 64 inputs c (16 lanes x 4) and deals the outputs
+// k out to its 16 groups of 16 lanes, group g taking k = g, g + 16, ...; the 16 partial sums of an input are
+// added in the order of the groups.  LDS: dy[K] | part[16][64].
+__device__ __forceinline__ void step_fc_bwd_x(const LDesc& d, int tile, int t, lfloat* smem) {
+  const int tid = threadIdx.x, l = tid & 15, g = tid >> 4;
+  const int C = UNI(d.C), K = UNI(d.K);
+  const int Kp = (K + 3) & ~3;
+  lfloat* dyl = smem;
+  lfloat* part = smem + Kp;
+  const gfloat* dy = at(d.dy, t);
+  for (int i = tid; i < K; i += BLK) dyl[i] = dy[i];
+  __syncthreads();
+  const int c = tile * 64 + 4 * l;
+  v4f acc = (v4f){0.f, 0.f, 0.f, 0.f};
+  if (c < C) {
+    const gfloat* w = GP(d.w) + c;
+    int k = g;
+    for (; k + 48 < K; k += 64) {
+      const v4f a0 = *(const gv4*)(w + (size_t)k * C), a1 = *(const gv4*)(w + (size_t)(k + 16) * C);
+      const v4f a2 = *(const gv4*)(w + (size_t)(k + 32) * C), a3 = *(const gv4*)(w + (size_t)(k + 48) * C);
+      const float e0 = dyl[k], e1 = dyl[k + 16], e2 = dyl[k + 32], e3 = dyl[k + 48];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] = fmaf(a3[j], e3, fmaf(a2[j], e2, fmaf(a1[j], e1, fmaf(a0[j], e0, acc[j]))));
+    }
+    for (; k < K; k += 16) {
+      const v4f a0 = *(const gv4*)(w + (size_t)k * C);
+      const float e0 = dyl[k];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] = fmaf(a0[j], e0, acc[j]);
+    }
+  }
+  *(lv4*)(part + g * 64 + 4 * l) = acc;
+  __syncthreads();
+  if (tid < 64 && tile * 64 + tid < C) {
+    float s = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) s += part[q * 64 + tid];
+    at(d.dx, t)[tile * 64 + tid] = rbf_if(UNI(d.flags) & F_BF16_OUT, s);
+  }
+}
+
+// Backward weights, gW[k][c] = dy[k] x[c] (an outer product): 4096 consecutive weights per workgroup.
+__device__ __forceinline__ void step_fc_bwd_w(const LDesc& d, int tile, int t) {
+  const int C = UNI(d.C);
+  const int64_t n = (int64_t)UNI(d.K) * C;
+  const gfloat* x = at(d.x, t);
+  const gfloat* dy = at(d.dy, t);
+  gfloat* gw = GP(d.gw);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int e = tile * 4096 + j * 1024 + 4 * (int)threadIdx.x;
+    if (e < n) {
+      const int k = e / C, c = e - k * C;
+      const v4f xv = *(const gv4*)(x + c);
+      const float s = dy[k];
+      *(gv4*)(gw + e) = (v4f){s * xv[0], s * xv[1], s * xv[2], s * xv[3]};
+    }
+  }
+}
+
 // Limits of the fused last stage (checked on the host): its input, the vector
 // the linear layer sees and the logits live in LDS / registers of one workgroup.
 constexpr int HEAD_MAX_IN = 8192;   // C*H*W
@@ -2275,6 +2363,9 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     // (planned only for networks tiled for throughput: the other instantiation carries no code for them)
     case K_DOT_FWD: if (!NT) step_dot_fwd(d, tile, t, smem); break;
     case K_DOT_BWD_X: if (!NT) step_dot_bwd_x(d, tile, t, smem); break;
+    case K_FC_FWD: if (!NT) step_fc_fwd(d, tile, t); break;
+    case K_FC_BWD_X: if (!NT) step_fc_bwd_x(d, tile, t, smem); break;
+    case K_FC_BWD_W: if (!NT) step_fc_bwd_w(d, tile, t); break;
     default: break;
   }
   }

@@ -23,7 +23,7 @@ sys.path.insert(0, os.path.dirname(_HERE))
 
 KINDS = {0: "gn_stats", 1: "gap_fwd", 2: "conv_fwd", 3: "post_fwd", 4: "ce", 5: "gnb_reduce", 6: "gnb_apply",
          7: "conv_bwd_x", 8: "conv_bwd_w", 9: "copy", 10: "gemm", 11: "bias_grad", 12: "ingest", 13: "update",
-         14: "head", 15: "gn_bwd"}
+         14: "head", 15: "gn_bwd", 16: "dot_fwd", 17: "dot_bwd_x", 18: "fc_fwd", 19: "fc_bwd_x", 20: "fc_bwd_w"}
 SLOTS, REC = 16384, 100
 
 

@@ -609,3 +609,15 @@ def test_last_phases_in_one_launch_are_bit_identical(name, first):
     for a, b in zip(*outs):
         assert np.array_equal(a, b)
     assert np.all(np.isfinite(outs[1][0])) and len(outs[1][2]) == n - len(net["stages"]) + 1
+
+
+def test_dense_layer_of_the_deep_network_runs_as_matrix_vector_steps():
+    """The 2048 -> 1000 linear layer of the ResNet-50 head on one sample: forward, backward data and the outer
+    product of the weight gradient are planned as streaming steps, not as MFMA tiles with one column; parity of
+    these steps with the oracle is that of the three ResNet-50 tests above."""
+    from paper_2003_11666_amd import binding
+    plan = binding.plan_summary(W.config("resnet50_64"))
+    for kind in ("fc_fwd", "fc_bwd_x", "fc_bwd_w"):
+        rows = [l for l in plan.splitlines() if f" {kind} " in l]
+        assert len(rows) == 1 and "stage 49" in rows[0] and "C2048x1x1 K1000x1x1" in rows[0], (kind, rows)
+    assert not [l for l in plan.splitlines() if "stage 49" in l and " gemm " in l]
