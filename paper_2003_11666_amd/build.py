@@ -17,12 +17,13 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950", "-x",
 TIMING_LIB = os.path.join(HERE, "libpb_hip_timing.so")
 
 
-def build(verbose=True, timing=False):
+def build(verbose=True, timing=False, stamps=False):
     """timing=True: the development build with a time stamp at the start and the end of every
-    workgroup (libpb_hip_timing.so, read by wg_timeline.py); the shipped library has none."""
+    workgroup (libpb_hip_timing.so, read by wg_timeline.py); stamps=True: the same library with the
+    stamps inside the GEMM step as well (read by gemm_stamps.py; the stamps cost time themselves); the shipped library has none."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    out = TIMING_LIB if timing else LIB
-    cmd = [hipcc] + FLAGS + (["-DPB_TIMING=2"] if timing else []) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out]
+    out = TIMING_LIB if (timing or stamps) else LIB
+    cmd = [hipcc] + FLAGS + (["-DPB_TIMING=1"] if stamps else ["-DPB_TIMING=2"] if timing else []) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out]
     cmd += ["-Rpass-analysis=kernel-resource-usage"]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -42,7 +43,7 @@ def build(verbose=True, timing=False):
     for name, u in usage.items():
         # every step of a tick is inlined into k_phase; a change that makes it spill slows every step down
         # (a spilling build measured 32 us instead of 12 us for a ResNet-20 launch)
-        if "k_phase" in name and not timing and int(u.get("ScratchSize [bytes/lane]", 0)) > MAX_SCRATCH_BYTES:
+        if "k_phase" in name and not (timing or stamps) and int(u.get("ScratchSize [bytes/lane]", 0)) > MAX_SCRATCH_BYTES:
             os.remove(out)      # a library that spills must not be the one that gets loaded
             raise RuntimeError(f"{name} uses {u['ScratchSize [bytes/lane]']} bytes of scratch memory per lane "
                                f"(limit {MAX_SCRATCH_BYTES}): a step spills registers")
@@ -68,4 +69,4 @@ def check_resources(stderr_text):
 
 
 if __name__ == "__main__":
-    print("built", build(timing="--timing" in sys.argv[1:]))
+    print("built", build(timing="--timing" in sys.argv[1:], stamps="--stamps" in sys.argv[1:]))

@@ -573,6 +573,7 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
         }
         tn_load(n0s + NT);
       }
+      if (ch == ch0 + 1 && !op) PB_TS(13);
       // ---- MFMA loop: lane holds A[i = lane%16][k = lane/16] and B[k = lane/16][j = lane%16];
       // the waves of a reduction split take k-steps wk_id, wk_id + wk, ...
       {

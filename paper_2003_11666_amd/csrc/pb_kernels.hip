@@ -2391,7 +2391,7 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
       pb_ts_out[slot * 100 + 4 + w * 24 + 11] = ts_sh[w][11];
       if (w == 0) {
         pb_ts_out[slot * 100 + 0] = d.kind; pb_ts_out[slot * 100 + 1] = d.stage;
-        pb_ts_out[slot * 100 + 2] = d.g.gm; pb_ts_out[slot * 100 + 3] = tile;
+        pb_ts_out[slot * 100 + 2] = d.g.gm + 8 * d.g.M; pb_ts_out[slot * 100 + 3] = tile;
       }
     }
   }
@@ -2407,7 +2407,7 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
       if (threadIdx.x < 96) pb_ts_out[slot * 100 + 4 + threadIdx.x] = ts_sh[threadIdx.x / 24][threadIdx.x % 24];
       if (threadIdx.x == 0) {
         pb_ts_out[slot * 100 + 0] = d.kind; pb_ts_out[slot * 100 + 1] = d.stage;
-        pb_ts_out[slot * 100 + 2] = d.g.gm; pb_ts_out[slot * 100 + 3] = tile;
+        pb_ts_out[slot * 100 + 2] = d.g.gm + 8 * d.g.M; pb_ts_out[slot * 100 + 3] = tile;
       }
     }
   }

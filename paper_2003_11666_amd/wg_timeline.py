@@ -65,7 +65,7 @@ def main():
             ts = r[i, 4:].reshape(4, 24)
             st, en = ts[:, 0], ts[:, 11]
             if (st > 0).any():
-                rows.append((i, KINDS.get(int(r[i, 0]), "?"), int(r[i, 1]), int(r[i, 2]), int(r[i, 3]),
+                rows.append((i, KINDS.get(int(r[i, 0]), "?"), int(r[i, 1]), int(r[i, 2]) & 7, int(r[i, 3]),
                              st[st > 0].min() / 100.0, en.max() / 100.0))
         if not rows:
             print(f"launch {ph}: no records")
