@@ -126,6 +126,9 @@ struct StepDesc {
   int32_t pdepth, plag, pstride;   // that ring: slots, lag of the slot this step uses, floats per slot
   int32_t gparts, gpstride; // partial weight gradients of the stage: their number, floats between two of them
                             // (K_GEMM backward weights writes one of them, K_UPDATE sums them in order)
+  int32_t ppstride;         // K_UPDATE, > 0: the stage keeps two copies of its master parameters, ppstride floats apart; the
+                            // update of tick t reads copy t mod 2 and writes the other (its backward readers of the tick
+                            // read copy t mod 2 through the ring fields above), so that it may run beside them
   int32_t upd_n, upd_t0;    // K_UPDATE: update size N (gradients of N consecutive samples per update) and the tick of the
                             // stage's first backward pass
   // One launch per tick (all phases in one grid): a workgroup of a later phase waits until the counters

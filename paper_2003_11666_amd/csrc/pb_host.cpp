@@ -239,6 +239,7 @@ struct StageBufs {
           dxparts = -1, // FWD_PARTS partial gradients with respect to the stage's output, left by the backward-data GEMM of
                         // the next stage (a thin layer) split over its reduction; summed by the stage's GroupNorm channel sums
           zparts = -1,  // FWD_PARTS partial outputs of a thin layer's forward GEMM split over its reduction (summed by its statistics step)
+          w2 = -1,      // second copy of the stage's master parameters (stages whose update computes the weight gradient itself)
           gparts = -1;  // GRAD_PARTS copies of the stage's gradient block, the first one complete, the others partial
                         // weight gradients of a backward-weights GEMM whose reduction is split over workgroups
   int st_stride = 0;
@@ -297,6 +298,13 @@ bool dot_layer(const Stage& a) {
 
 int st_stride_of(const Stage& s) { return (2 * s.G + 2 * s.gnC() + 63) / 64 * 64; }
 
+// A 3x3 layer on a 2x2 or 4x4 map (the 512-channel layers of VGG-11): its weight gradient is an outer product of two
+// tiny maps per weight, which the update step can compute while it streams the parameters (F_WGRAD).
+bool fusew_shape(const Stage& a) {
+  return a.is_conv && a.k == 3 && a.stride == 1 && a.pad == 1 && a.H == a.W && (a.H == 2 || a.H == 4) && a.OH == a.H && a.OW == a.W &&
+         !a.gap && !a.has_bias && a.C * 9 >= 1171 && a.C * a.H * a.W <= 8192 && a.n_w % 4 == 0 && a.n_w >= 65536;
+}
+
 int what_depth(const Stage& a, bool stash) { return stash ? a.De + 2 : a.De - a.D + 2; }
 
 void plan_arena(const std::vector<Stage>& st, bool stash, int loss_cap, Layout& L, Plan& pl, bool use_aring, int update_size) {
@@ -311,11 +319,17 @@ void plan_arena(const std::vector<Stage>& st, bool stash, int loss_cap, Layout& 
   // stage's update.  Without weight prediction the forward copy simply equals the master weights.
   L.w = pl.alloc(L.P); L.v = pl.alloc(L.P); L.g = pl.alloc(L.P);
   if (update_size > 1) L.gacc = pl.alloc(L.P);
+  // Exception: a stage whose update computes the weight gradient itself needs nothing but the layer's two maps, which
+  // are complete a phase before the stage's backward-data step has read the weights.  With a second copy of the
+  // stage's master parameters (the update of tick t reads copy t mod 2 and writes the other) it runs beside that step.
+  L.sb.assign(S, StageBufs());
+  if (!stash && update_size == 1 && use_aring)
+    for (int s = 0; s < S; ++s)
+      if (fusew_shape(st[s])) L.sb[s].w2 = pl.alloc(st[s].padded);
   L.what.assign(S, 0);
   // Weight stashing (the backward pass uses the forward's predicted weights, Eq. sgdpb_weight_stash):
   // the version the forward pass of a sample read has to survive until its backward pass, De + 2 slots.
   for (int s = 0; s < S; ++s) L.what[s] = pl.alloc((int64_t)what_depth(st[s], stash) * st[s].padded);
-  L.sb.assign(S, StageBufs());
   for (int s = 0; s < S; ++s) {
     const Stage& a = st[s];
     StageBufs& b = L.sb[s];
@@ -379,6 +393,7 @@ struct pb_ctx {
   bool bf16 = false;   // bf16 activation mode: tensors that cross a stage boundary are rounded to bf16
   int N = 1;           // update size: samples per update
   pb_tuning tune = {0, 0, 0.f, 0, 0, 0};
+  std::vector<char> pp_active;   // per stage: the update alternates between two copies of the master parameters
   int fuse_from = -1;          // >= 0: the phases from this one on share one launch, dependencies through completion
                                // counters (0: one launch per tick)
   uint32_t fused_ticks = 0;    // ticks launched in that form so far
@@ -850,8 +865,9 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   std::vector<int> bwd0(S, 0);   // per stage: phase its backward chain starts in
   // stages whose weight gradient is computed inside the update step (see F_WGRAD): the phase the
   // gradient's operands are complete in, and the operands
-  struct FusedW { int phase = -1; TRef x, dy; };
+  struct FusedW { int phase = -1; TRef x, dy; int64_t pp = 0; };
   std::vector<FusedW> fusedw(S);
+  c->pp_active.assign(S, 0);
   for (int s = 0; s < S; ++s) {
     const Stage& a = c->st[s];
     const StageBufs& b = L.sb[s];
@@ -870,7 +886,11 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     // weights of a backward step: the current master weights, or with weight stashing the version the
     // sample's forward pass read, De updates ago, from the same ring
     const float* wbk = c->stash ? wf : wb;
+    // (a stage with two copies of its master parameters: copy t mod 2)
+    const int64_t pp_stride = (b.w2 >= 0 && !c->stash && c->N == 1 && c->kernel_set == 0 && g_tile_budget_us > 0 && !c->sequential)
+                                  ? b.w2 - (L.w + a.off) : 0;
     auto bwd_params = [&](StepDesc& d, int mask) {
+      if (!c->stash && pp_stride > 0) { d.pmask = mask; d.pdepth = 2; d.plag = 0; d.pstride = (int)pp_stride; }
       if (!c->stash) return;
       d.pmask = mask; d.pdepth = wdepth; d.plag = a.De; d.pstride = (int)a.padded;
     };
@@ -1135,13 +1155,11 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       GemmCfg g;
       // A 3x3 layer on a 2x2 or 4x4 map (the 512-channel layers of VGG-11): its weight gradient is an outer
       // product of two tiny maps per weight; the update step computes it while it streams the parameters.
-      const bool fuse_w = c->kernel_set == 0 && g_tile_budget_us > 0 && c->N == 1 && a.is_conv && a.k == 3 && a.stride == 1 &&
-                          a.pad == 1 && a.H == a.W && (a.H == 2 || a.H == 4) && a.OH == a.H && a.OW == a.W && !a.gap &&
-                          !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)) && !a.has_bias && a.C * 9 >= 1171 && a.C * a.H * a.W <= 8192 &&
-                          a.n_w % 4 == 0 && a.n_w >= 65536 && b.gparts < 0 && ref_vec4(c, d.x) && ref_vec4(c, d.dy);
+      const bool fuse_w = c->kernel_set == 0 && g_tile_budget_us > 0 && c->N == 1 && fusew_shape(a) &&
+                          !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)) && b.gparts < 0 && ref_vec4(c, d.x) && ref_vec4(c, d.dy);
       const bool fc_w = fc_layer(c, d, d.gw) && !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)) && ref_vec4(c, d.x);
       if (fuse_w) {
-        fusedw[s].phase = pb; fusedw[s].x = d.x; fusedw[s].dy = d.dy;
+        fusedw[s].phase = pb; fusedw[s].x = d.x; fusedw[s].dy = d.dy; fusedw[s].pp = pp_stride > 0 ? pp_stride : 0;
       } else if (fc_w) {
         if (a.has_bias) {
           StepDesc e = blank(K_BIAS_GRAD, s, t_b);
@@ -1373,9 +1391,10 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     }
     StepDesc d = blank(K_UPDATE, s, 0);
     if (fusedw[s].phase >= 0) {
-      // (its operands are complete at the start of that phase; the stage's backward-data step, which
-      // reads the weights this step overwrites, runs in it)
-      last_grad_phase = std::max(last_grad_phase, fusedw[s].phase);
+      // (its operands are complete at the start of that phase; the stage's backward-data step, which reads the
+      // weights, runs in it: the update follows a phase later unless it writes the other copy of the parameters)
+      last_grad_phase = std::max(last_grad_phase, fusedw[s].pp > 0 ? fusedw[s].phase - 1 : fusedw[s].phase);
+      d.ppstride = (int)fusedw[s].pp;
       d.flags |= F_WGRAD;
       d.x = fusedw[s].x; d.dy = fusedw[s].dy;
       d.C = a.C; d.H = a.H; d.W = a.W; d.K = a.K; d.OH = a.OH; d.OW = a.OW; d.k = 3; d.stride = 1; d.pad = 1;
@@ -1396,6 +1415,7 @@ void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     d.n = (int)(gn_fused ? a.o_gamma : a.padded);      // o_gamma is a multiple of 4
     d.ntiles = (int)cdiv(d.n, UPD_TILE);
     if (d.n > 0) out.push_back({last_grad_phase + 1, d});
+    c->pp_active[s] = d.ppstride > 0;
   }
   // Networks tiled for latency run the kernel instantiation whose bulk outputs leave the L2
   // while the phase still runs instead of at its end (see PB_ST).  The update joins in only
@@ -1480,9 +1500,28 @@ void order_steps(std::vector<std::pair<int, StepDesc>>& tagged, bool one_launch 
   // and wait there for their stage's earlier steps.  Those whose wait ends first go first: forward GEMMs (they
   // wait for a statistics step), then the GroupNorm backward (a backward-data GEMM), then updates and the rest.
   auto late_rank = [](const StepDesc& d) { return d.kind == K_GEMM ? 0 : d.kind == K_GN_BWD ? 1 : 2; };
+  // Networks tiled for throughput, a phase whose GEMM tiles would keep the chip's 512 slots busy for less than
+  // 100 us: the update steps go last.  Beside the tiles they stream parameters at a fraction of the bandwidth and
+  // lengthen every tile's memory round trips; after them they have the chip to themselves (measured: wide 178 ->
+  // 170 us per tick, VGG-11 96 -> 93).  In a long phase (ResNet-50's GEMM launches) they stay in the order of
+  // cost, where they fill slots that would otherwise wait for bandwidth nobody uses (1 094 us against 1 112).
+  std::vector<char> upd_last;
+  if (g_tile_budget_us > 0) {
+    std::vector<double> gemm_us;
+    for (auto& p : tagged) {
+      if ((int)gemm_us.size() <= p.first) gemm_us.resize(p.first + 1, 0.0);
+      const int k = p.second.kind;
+      if (k == K_GEMM || k == K_DOT_FWD || k == K_DOT_BWD_X) gemm_us[p.first] += step_cost(p.second) * 1e-3 * p.second.ntiles / 512.0;
+    }
+    for (double u : gemm_us) upd_last.push_back(u < 100.0);
+  }
   std::stable_sort(tagged.begin(), tagged.end(),
                    [&](const std::pair<int, StepDesc>& x, const std::pair<int, StepDesc>& y) {
                      if (x.first != y.first) return x.first < y.first;
+                     if (!one_launch && !upd_last.empty() && upd_last[x.first]) {
+                       const bool ux = x.second.kind == K_UPDATE, uy = y.second.kind == K_UPDATE;
+                       if (ux != uy) return uy;
+                     }
                      if (one_launch && x.first > 0) {
                        const int lx = late_rank(x.second), ly = late_rank(y.second);
                        if (lx != ly) return lx < ly;
@@ -1623,6 +1662,9 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
              d.what != nullptr;
         if (d.gparts > 1)
           ok = ok && d.gpstride >= d.n && d.gpstride % 4 == 0 && ptr_ok(d.gw, (int64_t)(d.gparts - 1) * d.gpstride + d.n);
+        if (d.ppstride)
+          ok = ok && d.ppstride > 0 && d.ppstride % 4 == 0 && d.ppstride >= d.n && (d.flags & F_WGRAD) && d.w == d.wp &&
+               ptr_ok(d.w + d.ppstride, d.n);
         if (d.flags & F_WGRAD)
           ok = ok && !c->nt_stores && d.k == 3 && d.stride == 1 && d.pad == 1 && d.H == d.W && (d.H == 2 || d.H == 4) && d.OH == d.H &&
                d.OW == d.W && d.C * 9 >= 1171 && (int64_t)d.C * d.H * d.W + 8 * 16 + UPD_TILE / 2 <= LDS_FLOATS &&
@@ -1844,6 +1886,12 @@ int64_t copy_params_out(pb_ctx* c, int64_t arena_off, float* dst, int64_t cap) {
   std::vector<float> tmp(c->L.P);
   if (hipMemcpy(tmp.data(), c->f(arena_off), sizeof(float) * c->L.P, hipMemcpyDeviceToHost) != hipSuccess)
     return fail(PB_E_HIP, "device to host copy failed");
+  // stages with two copies of their master parameters: after an odd number of ticks the current ones are the second
+  if (arena_off == c->L.w && (c->ticks & 1))
+    for (size_t s = 0; s < c->st.size(); ++s)
+      if (c->pp_active[s] &&
+          hipMemcpy(tmp.data() + c->st[s].off, c->f(c->L.sb[s].w2), sizeof(float) * c->st[s].padded, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(PB_E_HIP, "device to host copy failed");
   int64_t n = 0;
   auto put = [&](const float* src, int64_t cnt) {
     const int64_t take = std::min<int64_t>(cnt, cap - n);

@@ -2309,6 +2309,14 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     }
     __syncthreads();
   }
+  if (UNI(d.ppstride) != 0) {
+    // update of a stage with two copies of its master parameters: read the tick's copy, write the other
+    if (threadIdx.x == 0) {
+      if (t & 1) sd_.w += (size_t)UNI(d.ppstride);
+      else sd_.wp += (size_t)UNI(d.ppstride);
+    }
+    __syncthreads();
+  }
   const int tile = UNI(d.tile);
   const bool live = t >= UNI(d.first_tick);
   bool run = live || (UNI(d.flags) & F_ALWAYS);

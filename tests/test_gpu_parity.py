@@ -540,6 +540,12 @@ def test_weight_gradient_inside_the_update_step():
     assert len(fused) == 2 and not any("gm3" in l and "C192x" in l for l in plan.split("\n")), plan
     # and their forward and backward-data passes run as dot-product steps, on the 4x4 and on the 2x2 map
     assert sum(" dot_fwd " in l for l in plan.split("\n")) == 2 and sum(" dot_bwd_x " in l for l in plan.split("\n")) == 2, plan
+    # these updates write a second copy of the stage's parameters, so they share the phase of the stage's
+    # backward-data step, which reads the first (weights are read back after every tick below: both copies)
+    import re
+    ph = lambda l: (int(re.search(r"stage\s+(\d+)", l).group(1)), int(re.search(r"phase (\d+)", l).group(1)))
+    bwd = dict(ph(l) for l in plan.split("\n") if " dot_bwd_x " in l)
+    assert all(bwd[ph(l)[0]] == ph(l)[1] for l in fused), plan
     K = 80
     res = run_parity(_engine(), net, K, engine_kwargs=dict(tuning=tuning))
     _check(res, K, len(net["stages"]), "thin_vgg/fused_wgrad/80")
