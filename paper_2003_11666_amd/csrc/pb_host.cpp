@@ -482,6 +482,7 @@ int pow2_floor(int x) { int p = 1; while (p * 2 <= x) p *= 2; return p; }
 int g_tile_target_bwd = 8; // ... of a backward step (a stage has two of them in the same phase)
 int g_tile_target = 8;     // latency policy: workgroups a step is split into at least, when its shape allows
 double g_tile_budget_us = 0;   // throughput policy (> 0): longest tile a step should have, microseconds (estimate)
+double g_budget_scale[4] = {1.0, 1.0, 1.0, 1.0};   // ... times this factor for the steps of a pass (index: GEMM mode), see compile_steps
 
 // Given the wave arrangement (wm, wn, wk, ni), choose the chunking of the
 // reduction that fits the LDS budget.  `fine`: search the channel count of a
@@ -693,7 +694,7 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
             tt = est_tile_us(one, k);
           }
           const double work = tt * e.tiles;
-          const bool within = tt <= g_tile_budget_us;
+          const bool within = tt <= g_tile_budget_us * g_budget_scale[mode];
           bool better;
           if (!have) better = true;
           else if (within != best_within) better = within;
@@ -836,7 +837,57 @@ void wave_reduce(StepDesc& d) {
 // one stage are independent inside a tick (they work on different samples and
 // read the start-of-tick weights), except for the last stage whose backward
 // pass consumes the loss gradient of the same tick.
+void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out);
+
+// The step table of a tick.  Networks tiled for throughput are planned twice when the first plan leaves the chip
+// partly empty: the tile budget makes tiles as large as it allows (least total work), which is right for a phase with
+// more GEMM workgroups than the chip's 512 places and wrong for one with fewer -- there the phase lasts as long as its
+// longest tile while places stay free.  The GEMM steps of such a pass get a budget smaller in the proportion of the
+// places they fill (wide network, forward pass: 205 tiles of 57 us -> launch 71 us).
 void compile_steps(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
+  for (double& f : g_budget_scale) f = 1.0;
+  compile_steps_once(c, out);
+  if (g_tile_budget_us <= 0 || c->tune.tile_budget_us != 0.f || c->kernel_set != 0) return;
+  std::vector<int> all, fwd, bwd;
+  for (auto& p : out) {
+    const StepDesc& d = p.second;
+    if ((int)all.size() <= p.first) { all.resize(p.first + 1, 0); fwd.resize(p.first + 1, 0); bwd.resize(p.first + 1, 0); }
+    const bool f = (d.kind == K_GEMM && d.g.gm == 1) || d.kind == K_DOT_FWD, b = (d.kind == K_GEMM && d.g.gm != 1) || d.kind == K_DOT_BWD_X;
+    if (f || b) all[p.first] += d.ntiles;
+    if (f) fwd[p.first] += d.ntiles;
+    if (b) bwd[p.first] += d.ntiles;
+  }
+  if (all.empty()) return;
+  const int pf = (int)(std::max_element(fwd.begin(), fwd.end()) - fwd.begin());
+  const int pb = (int)(std::max_element(bwd.begin(), bwd.end()) - bwd.begin());
+  const bool try_f = fwd[pf] > 0 && all[pf] < 300, try_b = bwd[pb] > 0 && pb != pf && all[pb] < 300;
+  if (!try_f && !try_b) return;
+  // smaller budgets in turn; the plan that fills the most places without exceeding them is kept
+  auto count = [&](const std::vector<std::pair<int, StepDesc>>& v, int ph) {
+    int n = 0;
+    for (auto& p : v)
+      if (p.first == ph && (p.second.kind == K_GEMM || p.second.kind == K_DOT_FWD || p.second.kind == K_DOT_BWD_X)) n += p.second.ntiles;
+    return n;
+  };
+  double best_f = 1.0, best_b = 1.0;
+  for (double f : {0.8, 0.65, 0.5, 0.4}) {
+    std::vector<std::pair<int, StepDesc>> trial;
+    if (try_f) g_budget_scale[1] = f;
+    if (try_b) g_budget_scale[2] = g_budget_scale[3] = f;
+    c->tables.clear();
+    compile_steps_once(c, trial);
+    if (try_f && count(trial, pf) <= 512) best_f = f;
+    if (try_b && count(trial, pb) <= 512) best_b = f;
+  }
+  g_budget_scale[1] = best_f;
+  g_budget_scale[2] = g_budget_scale[3] = best_b;
+  out.clear();
+  c->tables.clear();
+  compile_steps_once(c, out);
+  for (double& f : g_budget_scale) f = 1.0;
+}
+
+void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   const int S = c->S;
   // all stages run concurrently: aim at a few workgroups per compute unit over
   // the whole phase rather than per step
