@@ -53,7 +53,8 @@ enum StepKind : int32_t {
   K_FC_BWD_W = 20    // gW = dy x^T: 4096 consecutive weights per workgroup
 };
 
-constexpr int LDS_FLOATS = 15872;   // 62 KB of LDS per workgroup for the GEMM steps (two workgroups per compute unit)
+constexpr int LDS_FLOATS = 19456;   // 76 KB of LDS per workgroup (a compute unit has 160 KB and holds two workgroups); the
+                                    // planner gives GEMM tiles all of it or 62 KB (pb_tuning.gemm_lds_kb)
 
 // Tiling of one implicit-GEMM operand set: C[M x N] += A[M x Q] * B[Q x N] with
 // B[q][n] = patch[offq(q) + offn(n)], the patch being a zero-padded window of
@@ -81,6 +82,8 @@ struct GemmCfg {
   int32_t parts;           // backward weights: the reduction is split over `parts` groups of workgroups, each taking
   int32_t cpp;             // cpp consecutive chunks and writing a partial gradient of its own (summed by the update step);
   int32_t tpp;             // tiles per part (tiles = parts * tpp)
+  int32_t a_req;           // requests per thread that the A block of a full chunk takes (the kernel built for latency keeps
+                           // nine of them in flight when there are more than six, six otherwise)
 };
 
 // Pointer fields of a step that point into slot 0 of the stage's ring of predicted-weight versions;

@@ -61,8 +61,9 @@ __device__ __forceinline__ void sched_interleave() {
   }
 }
 
-template <int GM, int NI>
-__device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lfloat* smem, const bool nt) {
+template <int GM, int NI, bool NTK, int AU>
+__device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lfloat* smem) {
+  constexpr bool nt = NTK;
   PB_TS(1);
   // an opaque copy of the tile index: what is derived from it is then worked out
   // inside this instantiation, not once ahead of all of them and kept in scratch
@@ -290,7 +291,6 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     // seg_len of the first nvalid segments come from memory and the rest is zero.
     // Requests (a_issue) and the stores into LDS (a_commit) are separate so that the
     // requests of chunk ch+1 can be in flight while chunk ch is contracted.
-    constexpr int AU = 6;
     const int av = avec ? 4 : 1;                          // floats per request
     struct APar { int nvalid, seg_len, spr, slots; float ispr; };
     auto a_par = [&](int ch) {
@@ -718,22 +718,23 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
   if (nops != 1) finish(n0);   // both operand sets have been accumulated (one column tile per workgroup)
 }
 
-__device__ __forceinline__ void step_gemm(const LDesc& d, int tile, int t, lfloat* smem, const bool nt) {
+template <bool NTK>
+__device__ __forceinline__ void step_gemm(const LDesc& d, int tile, int t, lfloat* smem) {
   // the number of column subtiles per wave (1, 2 or 4) is a compile-time
   // constant so that the accumulators stay in fixed registers
   const int gm = UNI(d.g.gm), ni = UNI(d.g.ni);
   if (gm == 1) {
-    if (ni == 1) step_gemm_t<1, 1>(d, tile, t, smem, nt);
-    else if (ni == 2) step_gemm_t<1, 2>(d, tile, t, smem, nt);
-    else step_gemm_t<1, 4>(d, tile, t, smem, nt);
+    if (ni == 1) step_gemm_t<1, 1, NTK, (NTK ? 9 : 6)>(d, tile, t, smem);
+    else if (ni == 2) step_gemm_t<1, 2, NTK, 6>(d, tile, t, smem);
+    else step_gemm_t<1, 4, NTK, 6>(d, tile, t, smem);
   } else if (gm == 2) {
-    if (ni == 1) step_gemm_t<2, 1>(d, tile, t, smem, nt);
-    else if (ni == 2) step_gemm_t<2, 2>(d, tile, t, smem, nt);
-    else step_gemm_t<2, 4>(d, tile, t, smem, nt);
+    if (ni == 1) step_gemm_t<2, 1, NTK, (NTK ? 9 : 6)>(d, tile, t, smem);
+    else if (ni == 2) step_gemm_t<2, 2, NTK, 6>(d, tile, t, smem);
+    else step_gemm_t<2, 4, NTK, 6>(d, tile, t, smem);
   } else {
-    if (ni == 1) step_gemm_t<3, 1>(d, tile, t, smem, nt);
-    else if (ni == 2) step_gemm_t<3, 2>(d, tile, t, smem, nt);
-    else step_gemm_t<3, 4>(d, tile, t, smem, nt);
+    if (ni == 1) step_gemm_t<3, 1, NTK, 6>(d, tile, t, smem);
+    else if (ni == 2) step_gemm_t<3, 2, NTK, 6>(d, tile, t, smem);
+    else step_gemm_t<3, 4, NTK, 6>(d, tile, t, smem);
   }
 }
 

@@ -79,6 +79,8 @@ int parse_net(const pb_net_desc* net, std::vector<Stage>& out) {
   if (net->lwp_form != 0 && net->lwp_form != 1) return fail(PB_E_INVALID, "lwp_form must be 0 or 1");
   if (!(net->sc_scale >= 0.f) || !(net->lwp_scale >= 0.f)) return fail(PB_E_INVALID, "sc_scale and lwp_scale must be >= 0");
   if (net->update_size < 0 || net->update_size > 65536) return fail(PB_E_INVALID, "update_size must be 0 (= 1) .. 65536");
+  if (net->tuning && net->tuning->gemm_lds_kb != 0 && net->tuning->gemm_lds_kb != 62 && net->tuning->gemm_lds_kb != 76)
+    return fail(PB_E_INVALID, "tuning.gemm_lds_kb must be 0, 62 or 76");
   const int S = net->n_stages;
   out.assign(S, Stage());
   int C = net->in_c, H = net->in_h, W = net->in_w;
@@ -392,7 +394,7 @@ struct pb_ctx {
   bool stash = false;  // weight stashing: the backward pass reads the predicted weights its forward pass used
   bool bf16 = false;   // bf16 activation mode: tensors that cross a stage boundary are rounded to bf16
   int N = 1;           // update size: samples per update
-  pb_tuning tune = {0, 0, 0.f, 0, 0, 0};
+  pb_tuning tune = {0, 0, 0.f, 0, 0, 0, 0, 0};
   std::vector<char> pp_active;   // per stage: the update alternates between two copies of the master parameters
   int fuse_from = -1;          // >= 0: the phases from this one on share one launch, dependencies through completion
                                // counters (0: one launch per tick)
@@ -481,6 +483,7 @@ int pow2_floor(int x) { int p = 1; while (p * 2 <= x) p *= 2; return p; }
 // 3 backward weights.
 int g_tile_target_bwd = 8; // ... of a backward step (a stage has two of them in the same phase)
 int g_tile_target = 8;     // latency policy: workgroups a step is split into at least, when its shape allows
+int g_gemm_lds = 15872;        // floats of LDS a GEMM tile is planned with (the kernel's array holds LDS_FLOATS)
 double g_tile_budget_us = 0;   // throughput policy (> 0): longest tile a step should have, microseconds (estimate)
 double g_budget_scale[4] = {1.0, 1.0, 1.0, 1.0};   // ... times this factor for the steps of a pass (index: GEMM mode), see compile_steps
 
@@ -524,7 +527,7 @@ bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int
   auto fits = [&](int QC, int CC, int PR, int Wp) {
     const int QCpad = (QC + 15) / 16 * 16;
     const int64_t need = QCpad + a_size(QC) + ((int64_t)CC * PR * Wp + 3) / 4 * 4 + 16;
-    return need <= LDS_FLOATS;
+    return need <= g_gemm_lds;
   };
   if (mode == 1 || mode == 2) {
     const int rowlen = mode == 1 ? OW : W, nrows = mode == 1 ? OH : H;
@@ -584,11 +587,16 @@ bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int
   // reduction range; backward data: the MT x k x k weights of one output channel.
   if (mode == 2) g.avec = (C % 4 == 0) ? 1 : 0;
   else g.avec = (g.Q % 4 == 0 && (g.n_chunks == 1 || g.QC % 4 == 0)) ? 1 : 0;
+  {
+    const int q4 = (mode == 2) ? (g.QC + 3) / 4 * 4 : g.QCpad;
+    const int64_t nseg = (mode == 2) ? (q4 + kk - 1) / kk : g.MT, seg = (mode == 2) ? g.MT * kk : q4;
+    g.a_req = (int)cdiv(nseg * (g.avec ? (seg + 3) / 4 : seg), BLK);
+  }
   g.LDA = (mode == 2) ? g.MT * kk : g.QCpad + 4;   // QCpad + 4 = 4 * odd: the 16 rows of a wave fall into different banks
   g.o_offq = 0;
   g.o_A = g.QCpad;
   g.o_patch = (int)(g.o_A + a_size(g.QC));
-  if (g.o_patch % 4 || g.o_patch + (g.CC * g.PR * g.Wp + 3) / 4 * 4 > LDS_FLOATS) return false;
+  if (g.o_patch % 4 || g.o_patch + (g.CC * g.PR * g.Wp + 3) / 4 * 4 > g_gemm_lds) return false;
   return true;
 }
 
@@ -940,6 +948,11 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
     g_tile_budget_us = tick_us >= 10.0 ? std::max(16.0, 0.65 * tick_us) : 0.0;
     if (c->tune.tile_budget_us > 0.f) g_tile_budget_us = c->tune.tile_budget_us;
     else if (c->tune.tile_budget_us < 0.f) g_tile_budget_us = 0.0;
+    // A compute unit has 160 KB of LDS and holds two workgroups: a tile may use up to 76 KB.  Planning with all of it
+    // pays where the reductions are long (fewer chunks, each with its fixed costs: ResNet-50 +2.3 %, the wide ResNet
+    // +0.7 % measured); for shorter ticks the planner's estimate favours arrangements that measure slower (VGG-11
+    // -7.8 %), so those plan with 62 KB.
+    g_gemm_lds = (c->tune.gemm_lds_kb == 76 || (c->tune.gemm_lds_kb == 0 && tick_us >= 60.0)) ? LDS_FLOATS : 15872;
   }
   const Layout& L = c->L;
   std::vector<int> bwd0(S, 0);   // per stage: phase its backward chain starts in
@@ -1435,8 +1448,8 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   for (auto& pr : out) {
     StepDesc& d = pr.second;
     if (d.kind != K_GEMM) continue;
-    if (d.g.avec && !a_aligned(c, d, false)) d.g.avec = 0;
-    if (d.gp.gm && d.gp.avec && !a_aligned(c, d, true)) d.gp.avec = 0;
+    if (d.g.avec && !a_aligned(c, d, false)) { d.g.avec = 0; d.g.a_req *= 4; }
+    if (d.gp.gm && d.gp.avec && !a_aligned(c, d, true)) { d.gp.avec = 0; d.gp.a_req *= 4; }
   }
   // ---- a backward-data GEMM that leaves partial gradients: its consumer, the channel sums of the
   // previous stage's GroupNorm (same gradient buffer), adds them up

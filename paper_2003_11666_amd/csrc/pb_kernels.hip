@@ -2362,7 +2362,7 @@ k_phase(const StepDesc* __restrict__ recs, const Globals* __restrict__ G, int k,
     case K_CONV_BWD_X: step_conv_bwd_x(d, tile, t); break;
     case K_CONV_BWD_W: step_conv_bwd_w(d, tile, t); break;
     case K_COPY: step_copy(d, tile, t, NT); break;
-    case K_GEMM: step_gemm(d, tile, t, smem, NT); break;
+    case K_GEMM: step_gemm<NT>(d, tile, t, smem); break;
     case K_BIAS_GRAD: step_bias_grad(d, tile, t); break;
     case K_INGEST: step_ingest(d, tile, t, G, k, sample_override, label_override); break;
     case K_UPDATE: step_update(d, tile, t, smem, NT); break;
