@@ -36,7 +36,7 @@ class _Stage(C.Structure):
 class _Tuning(C.Structure):
     _fields_ = [("tile_target", C.c_int32), ("tile_target_bwd", C.c_int32), ("tile_budget_us", C.c_float),
                 ("nt_stores", C.c_int32), ("one_launch", C.c_int32), ("tail_merge", C.c_int32), ("spin_limit", C.c_int32),
-                ("gemm_lds_kb", C.c_int32)]
+                ("dense_1x1", C.c_int32), ("gemm_lds_kb", C.c_int32)]
 
 
 class _NetDesc(C.Structure):

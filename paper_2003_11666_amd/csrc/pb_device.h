@@ -82,9 +82,20 @@ struct GemmCfg {
   int32_t parts;           // backward weights: the reduction is split over `parts` groups of workgroups, each taking
   int32_t cpp;             // cpp consecutive chunks and writing a partial gradient of its own (summed by the update step);
   int32_t tpp;             // tiles per part (tiles = parts * tpp)
+  int32_t mm;              // 1: dense matrix-product form of a 1x1 layer of stride 1 (no patch, no offset tables): a workgroup of
+  int32_t mi;              // 2 x 2 waves, each with mi x ni accumulators (tile 32 mi x 32 ni), chunks of 32 reduction entries
   int32_t a_req;           // requests per thread that the A block of a full chunk takes (the kernel built for latency keeps
                            // nine of them in flight when there are more than six, six otherwise)
 };
+
+// Dense matrix-product form of a 1x1 layer (GemmCfg::mm)
+constexpr int MM_QC = 32;            // reduction entries per chunk
+constexpr int MM_LDK = MM_QC + 4;    // row stride of an operand stored [row][reduction]: 4 * odd, 16 rows on distinct banks
+
+// LDS floats of one chunk (both operands); the step needs twice that
+__host__ __device__ constexpr int mm_chunk_floats(int mode, int MT, int NT) {
+  return (mode == 2 ? MM_QC * (MT + 4) : MT * MM_LDK) + (mode == 3 ? NT * MM_LDK : MM_QC * (NT + 16));
+}
 
 // Pointer fields of a step that point into slot 0 of the stage's ring of predicted-weight versions;
 // k_phase moves them to the slot of the tick before the step runs.

@@ -123,20 +123,49 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
     const gfloat* xm = (GM == 2 && (flags & F_MASK_X)) ? (const gfloat*)at(d.x, tt) : nullptr;
     const gfloat* skg = (GM == 2 && (flags & F_ADD_SKG)) ? (const gfloat*)at(d.skg, tt) : nullptr;
     const gfloat* bias = (GM == 1 && (flags & F_BIAS) && qpart == 0) ? GP(d.b) : nullptr;   // (a split forward pass: once)
+    // straight-line loads from clamped positions (what lies beyond the matrix is never stored): with a branch per
+    // element every load would wait for the one before it
+    int o[NI][4];
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const int n = ncol + j * 16;
+      const int n = ncol + j * 16, nc = n < N ? n : N - 1;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
+        const int rr = mrow + r < M ? mrow + r : M - 1;
+        o[j][r] = rr * N + nc;
         add[j][r] = 0.f; msk[j][r] = 1.f;
-        if (n < N && mrow + r < M) {
-          const int o = (mrow + r) * N + n;
-          if (bias) add[j][r] = bias[mrow + r];
-          if (skip) add[j][r] += skip[o];
-          if (skg) add[j][r] = skg[o];
-          if (xm) msk[j][r] = xm[o];
-        }
       }
+    }
+    if (bias) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float bv = bias[mrow + r < M ? mrow + r : M - 1];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) add[j][r] = bv;
+      }
+    }
+    if (skip) {
+      float sv[NI][4];
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sv[j][r] = skip[o[j][r]];
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) add[j][r] += sv[j][r];
+    }
+    if (skg) {
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) add[j][r] = skg[o[j][r]];
+    }
+    if (xm) {
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) msk[j][r] = xm[o[j][r]];
     }
   };
   const bool extras_any = (GM == 1 && (flags & (F_BIAS | F_SKIP))) || (GM == 2 && (flags & (F_MASK_X | F_ADD_SKG)));
@@ -718,10 +747,15 @@ __device__ __forceinline__ void step_gemm_t(const LDesc& d, int tile_, int t, lf
   if (nops != 1) finish(n0);   // both operand sets have been accumulated (one column tile per workgroup)
 }
 
+}  // namespace pb
+#include "pb_mm.h"
+namespace pb {
+
 template <bool NTK>
 __device__ __forceinline__ void step_gemm(const LDesc& d, int tile, int t, lfloat* smem) {
   // the number of column subtiles per wave (1, 2 or 4) is a compile-time
   // constant so that the accumulators stay in fixed registers
+  if (!NTK && UNI(d.g.mm)) { step_mm(d, tile, t, smem); return; }   // (planned only for networks tiled for throughput)
   const int gm = UNI(d.g.gm), ni = UNI(d.g.ni);
   if (gm == 1) {
     if (ni == 1) step_gemm_t<1, 1, NTK, (NTK ? 9 : 6)>(d, tile, t, smem);

@@ -394,7 +394,7 @@ struct pb_ctx {
   bool stash = false;  // weight stashing: the backward pass reads the predicted weights its forward pass used
   bool bf16 = false;   // bf16 activation mode: tensors that cross a stage boundary are rounded to bf16
   int N = 1;           // update size: samples per update
-  pb_tuning tune = {0, 0, 0.f, 0, 0, 0, 0, 0};
+  pb_tuning tune = {0, 0, 0.f, 0, 0, 0, 0, 0, 0};
   std::vector<char> pp_active;   // per stage: the update alternates between two copies of the master parameters
   int fuse_from = -1;          // >= 0: the phases from this one on share one launch, dependencies through completion
                                // counters (0: one launch per tick)
@@ -607,6 +607,12 @@ bool fit_gemm(GemmCfg& g, int C, int H, int W, int K, int OH, int OW, int k, int
 // MFMA loop, whose cost per MFMA falls with the number of column subtiles a
 // wave keeps (one A fetch and one offset fetch per k-step whatever their number).
 double est_tile_us(const GemmCfg& g, int k) {
+  if (g.mm) {
+    // dense form: per chunk of 32 reduction entries 8 mi ni MFMAs per wave, two workgroups sharing the matrix pipes,
+    // and never less than the round trip of the next chunk's requests
+    const double t_mfma = 2.0 * 8.0 * g.mi * g.ni * 32.0 / 2400.0;
+    return 5.0 + g.n_chunks * std::max(2.2, t_mfma);
+  }
   const int kk = k * k;
   const double a_fl = g.gm == 2 ? (double)((g.QCpad + kk - 1) / kk + 1) * g.MT * kk : (double)g.MT * g.QCpad;
   const double p_fl = (double)g.CC * g.PR * g.Wp;
@@ -621,6 +627,40 @@ double est_tile_us(const GemmCfg& g, int k) {
   // the patch already requested; the A block again only if the reduction is chunked
   if (g.nsub > 1) t += (g.nsub - 1) * (g.n_chunks * (2.5 + (g.n_chunks > 1 ? stage_a : 0.0) + stage_p + t_mfma) + 1.0);
   return t;
+}
+
+// Dense matrix-product form of a 1x1 layer of stride 1 (pb_mm.h) in a network tiled for throughput: M x N result,
+// reduction Q, every matrix row-major as it lies in memory.  Forward and backward data: M = output rows (a multiple
+// of 64), N = pixels (a multiple of 4), Q = channels contracted (a multiple of 32).  Backward weights: M x N = cout x
+// cin (multiples of 64), Q = pixels (a multiple of 4), its chunks dealt out to up to max_parts groups of workgroups.
+bool make_mm(const pb_ctx* c, int mode, int M, int N, int Q, int max_parts, GemmCfg* out) {
+  if (g_tile_budget_us <= 0 || c->kernel_set != 0 || c->tune.dense_1x1 < 0) return false;
+  if (M % 64 || M < 64 || Q < 4 || Q % 4) return false;
+  if (mode == 3 ? (N % 64 || N < 64) : (N % 4 || N < 16 || Q % MM_QC)) return false;
+  GemmCfg g;
+  memset(&g, 0, sizeof g);
+  g.gm = mode; g.mm = 1; g.M = M; g.N = N; g.Q = Q;
+  g.mi = M % 128 == 0 ? 4 : 2;
+  if (mode != 3 && N <= 64) return false;   // (the kernel is built with 128-column tiles for these two passes)
+  g.ni = mode == 3 ? (N % 128 == 0 ? 4 : 2) : 4;
+  g.wm = 2; g.wn = 2; g.wk = 1; g.nsub = 1;
+  g.MT = 32 * g.mi; g.NT = 32 * g.ni;
+  if (2 * mm_chunk_floats(mode, g.MT, g.NT) > LDS_FLOATS) return false;
+  g.tiles_n = cdiv(N, g.NT);
+  g.tpp = (M / g.MT) * g.tiles_n;
+  g.QC = g.QCpad = MM_QC; g.n_chunks = cdiv(Q, MM_QC);
+  g.parts = 1; g.cpp = g.n_chunks;
+  if (mode == 3) {
+    GemmCfg one = g;
+    for (int want = 2; want <= max_parts && want <= g.n_chunks && est_tile_us(one, 1) > 30.0; want *= 2) {
+      g.cpp = cdiv(g.n_chunks, want);
+      g.parts = cdiv(g.n_chunks, g.cpp);
+      one.n_chunks = g.cpp;
+    }
+  }
+  g.tiles = g.parts * g.tpp;
+  *out = g;
+  return true;
 }
 
 // Choose the wave arrangement and the chunking of one operand set.  `like` !=
@@ -1147,6 +1187,11 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         bool ok = make_gemm(1, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, plain_src, (d.flags & F_PROJ) ? 1 : 16, flat,
                             zsplit ? FWD_PARTS : 1);
         if (ok && (d.flags & F_PROJ)) ok = make_gemm(1, d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, 0, &g, &gp, true);
+        GemmCfg gd;
+        if (ok && plain_src && !(d.flags & F_PROJ) && d.k == 1 && d.stride == 1 && d.pad == 0 && d.w && (d.w - c->f(0)) % 4 == 0 &&
+            ref_vec4(c, d.x) && make_mm(c, 1, d.K, d.OH * d.OW, d.C, 1, &gd)) {
+          d.kind = K_GEMM; d.g = gd; d.gp = gp; d.ntiles = gd.tiles;
+        } else
         if (ok) {
           d.kind = K_GEMM; d.g = g; d.gp = gp; d.ntiles = g.tiles;
           if (g.parts > 1) { d.gw = c->f(b.zparts); d.gparts = g.parts; d.gpstride = (int)a.z_elems(); fwd_parts = g.parts; }
@@ -1271,9 +1316,13 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
           e.ntiles = cdiv(a.K, BLK / 64);
           out.push_back({pb, e});
         }
+        GemmCfg gd;
+        const bool dense = !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)) && d.k == 1 && d.stride == 1 && d.pad == 0 && ref_vec4(c, d.x) &&
+                           ref_vec4(c, d.dy) && make_mm(c, 3, d.K, d.C, d.OH * d.OW, b.gparts >= 0 ? GRAD_PARTS : 1, &gd);
+        if (dense) g = gd;
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles; d.flags &= ~F_BIAS;
         d.gparts = g.parts; d.gpstride = (int)a.padded;
-        gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, &d.tq, &d.tn);
+        if (!dense) gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, &d.tq, &d.tn);
       }
       if (!fuse_w) out.push_back({pb, d});
     }
@@ -1316,9 +1365,13 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       } else
       if (c->kernel_set == 0 && make_gemm(2, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, true, 16, flat,
                                           dxsplit ? FWD_PARTS : 1)) {
+        GemmCfg gd;
+        const bool dense = d.k == 1 && d.stride == 1 && d.pad == 0 && d.w && (d.w - c->f(0)) % 4 == 0 && ref_vec4(c, d.dy) &&
+                           make_mm(c, 2, d.C, d.H * d.W, d.K, 1, &gd);
+        if (dense) g = gd;
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
         if (g.parts > 1) { d.gw = c->f(L.sb[s - 1].dxparts); d.gparts = g.parts; d.gpstride = (int)a.in_elems(); }
-        gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, &d.tq, &d.tn);
+        if (!dense) gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, &d.tq, &d.tn);
       }
       out.push_back({pb, d});
     }
@@ -1520,7 +1573,7 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   // (forward and backward-data GEMMs split over their reduction, several column tiles per workgroup and
   // flattened 1x1 layers exist only in the other instantiation)
   for (auto& pr : out)
-    if (pr.second.kind == K_GEMM && ((pr.second.g.gm != 3 && pr.second.g.parts > 1) || pr.second.g.nsub > 1 || pr.second.g.win > 0 ||
+    if (pr.second.kind == K_GEMM && ((pr.second.g.gm != 3 && pr.second.g.parts > 1) || pr.second.g.nsub > 1 || pr.second.g.win > 0 || pr.second.g.mm ||
                                     pr.second.gp.nsub > 1 || pr.second.gp.win > 0)) c->nt_stores = false;
   for (auto& pr : out)
     if ((pr.second.kind == K_UPDATE && (pr.second.flags & F_WGRAD)) || pr.second.kind == K_DOT_FWD || pr.second.kind == K_DOT_BWD_X ||
@@ -1872,10 +1925,29 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
           }
           return o;
         };
+        // dense matrix-product form of a 1x1 layer: tile and operand shapes the kernel assumes without checking
+        auto mm_ok = [&](const GemmCfg& g) {
+          const int P = d.OH * d.OW;
+          bool o = !c->nt_stores && d.k == 1 && d.stride == 1 && d.pad == 0 && d.H * d.W == P && !(d.flags & (F_PROJ | F_PRE_AFFINE | F_PRE_RELU)) &&
+                   (g.mi == 2 || g.mi == 4) && (g.ni == 4 || (g.ni == 2 && g.gm == 3)) && g.MT == 32 * g.mi && g.NT == 32 * g.ni &&
+                   2 * mm_chunk_floats(g.gm, g.MT, g.NT) <= LDS_FLOATS && g.M % g.MT == 0 && g.tiles_n == cdiv(g.N, g.NT) &&
+                   g.tpp == (g.M / g.MT) * g.tiles_n && g.n_chunks == cdiv(g.Q, MM_QC) && g.parts >= 1 && g.cpp >= 1 &&
+                   g.tiles == g.parts * g.tpp && (int64_t)g.parts * g.cpp >= g.n_chunks && (int64_t)(g.parts - 1) * g.cpp < g.n_chunks &&
+                   (g.gm == 3 || (d.w && (d.w - c->f(0)) % 4 == 0 && (d.pmask == 0 || d.pstride % 4 == 0)));
+          if (g.gm == 1) o = o && g.M == d.K && g.N == P && g.Q == d.C && g.Q % MM_QC == 0 && g.N % 4 == 0 && g.parts == 1 && ref_vec4(c, d.x);
+          else if (g.gm == 2) o = o && g.M == d.C && g.N == P && g.Q == d.K && g.Q % MM_QC == 0 && g.N % 4 == 0 && g.parts == 1 && ref_vec4(c, d.dy);
+          else if (g.gm == 3) o = o && g.M == d.K && g.N == d.C && g.Q == P && g.Q % 4 == 0 && g.N % g.NT == 0 && ref_vec4(c, d.x) && ref_vec4(c, d.dy);
+          else o = false;
+          return o;
+        };
+        if (d.g.mm) {
+          ok = ok && d.ntiles == d.g.tiles && mm_ok(d.g) && d.gp.gm == 0;
+        } else {
         ok = ok && (!d.g.avec || a_aligned(c, d, false)) && (!(d.flags & F_PROJ) || !d.gp.avec || a_aligned(c, d, true));
         ok = ok && d.ntiles == d.g.tiles && cfg_ok(d.g, d.C, d.H, d.W, d.k, d.stride, d.pad) &&
              ptr_ok((const float*)d.tq, d.g.QCpad) && ptr_ok((const float*)d.tn, d.g.N) &&
              (!(d.flags & F_PROJ) || d.g.gm != 1 || (ptr_ok((const float*)d.tq2, d.gp.QCpad) && ptr_ok((const float*)d.tn2, d.gp.N)));
+        }
         const int64_t wn_ = (int64_t)d.K * d.C * d.k * d.k;
         if (d.g.gm == 1) {
           // a forward pass split over its reduction writes partial outputs gpstride floats apart
@@ -2097,6 +2169,10 @@ int64_t pb_plan_summary(const pb_net_desc* net, char* buf, int64_t cap) {
     o += line;
     if (d.kind == K_GEMM) {
       const GemmCfg& g = d.g;
+      if (g.mm)
+        snprintf(line, sizeof line, " | gm%d M%d N%d Q%d dense mi%d ni%d tile %dx%d chunks %d/%d QC%d lds %d", g.gm, g.M, g.N, g.Q, g.mi, g.ni,
+                 g.MT, g.NT, g.n_chunks, g.parts, g.QC, 2 * mm_chunk_floats(g.gm, g.MT, g.NT));
+      else
       snprintf(line, sizeof line, " | gm%d M%d N%d Q%d waves %dx%dx%d ni%d tile %dx%d x%d chunks %d/%d QC%d CC%d PR%d Wp%d lds %d",
                g.gm, g.M, g.N, g.Q, g.wm, g.wn, g.wk, g.ni, g.MT, g.NT, g.nsub, g.n_chunks, g.parts, g.QC, g.CC, g.PR, g.Wp,
                g.o_patch + g.CC * g.PR * g.Wp);

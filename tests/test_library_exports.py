@@ -32,7 +32,7 @@ def test_every_declared_symbol_is_exported():
 def test_descriptor_validation_on_host():
     from paper_2003_11666_amd import binding as B
     lib = B.load_library()
-    for name in ("mlp", "vgg11", "resnet20", "wide"):
+    for name in ("mlp", "vgg11", "resnet20", "wide", "resnet50", "resnet50_64", "tiny_bottleneck"):
         d, keep = B.marshal_net(W.config(name))
         assert lib.pb_arena_bytes(ctypes.byref(d), None) > 0, name
     # the pipeline's own delays, larger ones (deeper weight-version rings, more memory) and smaller ones
