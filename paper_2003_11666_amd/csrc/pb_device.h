@@ -84,6 +84,9 @@ struct GemmCfg {
   int32_t tpp;             // tiles per part (tiles = parts * tpp)
   int32_t mm;              // 1: dense matrix-product form of a 1x1 layer of stride 1 (no patch, no offset tables): a workgroup of
   int32_t mi;              // 2 x 2 waves, each with mi x ni accumulators (tile 32 mi x 32 ni), chunks of 32 reduction entries
+  int32_t gather;          // dense form: pixel-indexed operands are fetched element by element (rows not a multiple of 4 pixels,
+  int32_t ps, pw;          // or a layer of stride ps = 2): dense pixel p = (oy, ox) of a pw-wide map lies at ps (oy sw + ox) in its
+  int32_t sw, shw;         // channel's map, whose rows are sw floats and whose channels are shw floats apart
   int32_t a_req;           // requests per thread that the A block of a full chunk takes (the kernel built for latency keeps
                            // nine of them in flight when there are more than six, six otherwise)
 };

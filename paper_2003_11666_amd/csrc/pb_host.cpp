@@ -461,8 +461,9 @@ int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 // Streaming forms of the elementwise steps (networks tiled for throughput):
 // floats per workgroup, and whether a ring can be read with 16-byte accesses.
 constexpr int STREAM_GRAIN = 4 * 4 * BLK;
-bool ref_vec4(const pb_ctx* c, const TRef& r) {
-  return r.base && (r.base - c->f(0)) % 4 == 0 && (r.depth == 1 || r.stride % 4 == 0);
+// (out of line, on integers: see arena_aligned16)
+__attribute__((noinline)) bool ref_vec4(const pb_ctx* c, const TRef& r) {
+  return (uintptr_t)r.base != 0 && ((uintptr_t)r.base - (uintptr_t)c->f(0)) % 16 == 0 && (r.depth == 1 || r.stride % 4 == 0);
 }
 
 int bwd_w_tiles(int K, int C, int k, int P, bool bias) {
@@ -629,20 +630,33 @@ double est_tile_us(const GemmCfg& g, int k) {
   return t;
 }
 
-// Dense matrix-product form of a 1x1 layer of stride 1 (pb_mm.h) in a network tiled for throughput: M x N result,
-// reduction Q, every matrix row-major as it lies in memory.  Forward and backward data: M = output rows (a multiple
-// of 64), N = pixels (a multiple of 4), Q = channels contracted (a multiple of 32).  Backward weights: M x N = cout x
-// cin (multiples of 64), Q = pixels (a multiple of 4), its chunks dealt out to up to max_parts groups of workgroups.
-bool make_mm(const pb_ctx* c, int mode, int M, int N, int Q, int max_parts, GemmCfg* out) {
+// Whether p lies a multiple of 16 bytes into the arena.  (Out of line and on integers: while a plan is only being
+// sized the arena's base is null, and comparisons on pointers derived from it are not reliable after optimisation.)
+__attribute__((noinline)) bool arena_aligned16(const pb_ctx* c, const float* p) {
+  return ((uintptr_t)p - (uintptr_t)c->f(0)) % 16 == 0;
+}
+
+// Dense matrix-product form of a 1x1 layer (pb_mm.h) in a network tiled for throughput: M x N result, reduction Q,
+// every matrix row-major as it lies in memory.  Forward and backward data: M = output rows (a multiple of 64), N =
+// pixels of the layer's output map (forward) or of its gradient (backward data), Q = channels contracted (a multiple
+// of 32).  Backward weights: M x N = cout x cin (multiples of 64), Q = pixels, its chunks dealt out to up to max_parts
+// groups of workgroups.  A layer of stride 2 (OH x OW output pixels of an H x W map, H = 2 OH, W = 2 OW) contracts over
+// its output pixels only; operands indexed by pixels are then gathered element by element, as are rows whose length
+// is not a multiple of 4.
+bool make_mm(const pb_ctx* c, int mode, int M, int N, int Q, int stride, int H, int W, int OH, int OW, int max_parts, GemmCfg* out) {
   if (g_tile_budget_us <= 0 || c->kernel_set != 0 || c->tune.dense_1x1 < 0) return false;
-  if (M % 64 || M < 64 || Q < 4 || Q % 4) return false;
-  if (mode == 3 ? (N % 64 || N < 64) : (N % 4 || N < 16 || Q % MM_QC)) return false;
+  if (stride != 1 && !(stride == 2 && H == 2 * OH && W == 2 * OW)) return false;
+  const int P = OH * OW;
+  if (M % 64 || M < 64 || (int64_t)M * std::max(N, Q) >= ((int64_t)1 << 30) || (int64_t)std::max(M, N) * H * W >= ((int64_t)1 << 30)) return false;
+  if (mode == 3 ? (N % 64 || N < 64 || Q != P || Q < 4) : (N != P || N < 16 || Q % MM_QC || Q < MM_QC)) return false;
   GemmCfg g;
   memset(&g, 0, sizeof g);
   g.gm = mode; g.mm = 1; g.M = M; g.N = N; g.Q = Q;
+  g.ps = stride; g.pw = stride == 1 ? P : OW; g.sw = stride == 1 ? H * W : W; g.shw = H * W;   // (stride 1: the map as one row)
+  g.gather = mode == 2 ? (P % 4 != 0) : (stride == 2 || P % 4 != 0);
   g.mi = M % 128 == 0 ? 4 : 2;
-  if (mode != 3 && N <= 64) return false;   // (the kernel is built with 128-column tiles for these two passes)
-  g.ni = mode == 3 ? (N % 128 == 0 ? 4 : 2) : 4;
+  g.ni = mode == 3 ? (N % 128 == 0 ? 4 : 2) : (N > 64 ? 4 : 2);
+  if (mode != 3 && g.mi == 2 && g.ni == 2) return false;   // (no 64 x 64 tiles for these two passes)
   g.wm = 2; g.wn = 2; g.wk = 1; g.nsub = 1;
   g.MT = 32 * g.mi; g.NT = 32 * g.ni;
   if (2 * mm_chunk_floats(mode, g.MT, g.NT) > LDS_FLOATS) return false;
@@ -1148,10 +1162,13 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
             fwd_params(e, PF_W);
             e.y = ring(c, b.projy, 1, a.out_elems(), 0);
             e.ntiles = cdiv((int64_t)a.K * a.OH * a.OW, BLK);
-            GemmCfg ge;
-            if (make_gemm(1, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, 0, nullptr, &ge, true)) {
+            GemmCfg ge, gd;
+            const bool dense = arena_aligned16(c, e.w) && ref_vec4(c, e.x) &&
+                               make_mm(c, 1, e.K, e.OH * e.OW, e.C, e.stride, e.H, e.W, e.OH, e.OW, 1, &gd);
+            if (dense || make_gemm(1, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, 0, nullptr, &ge, true)) {
+              if (dense) ge = gd;
               e.kind = K_GEMM; e.g = ge; e.ntiles = ge.tiles;
-              gemm_tables(c, ge, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, &e.tq, &e.tn);
+              if (!dense) gemm_tables(c, ge, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, &e.tq, &e.tn);
               out.push_back({ph - 1, e});
               d.flags &= ~F_PROJ;
               d.wp = nullptr;
@@ -1188,8 +1205,8 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
                             zsplit ? FWD_PARTS : 1);
         if (ok && (d.flags & F_PROJ)) ok = make_gemm(1, d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, 0, &g, &gp, true);
         GemmCfg gd;
-        if (ok && plain_src && !(d.flags & F_PROJ) && d.k == 1 && d.stride == 1 && d.pad == 0 && d.w && (d.w - c->f(0)) % 4 == 0 &&
-            ref_vec4(c, d.x) && make_mm(c, 1, d.K, d.OH * d.OW, d.C, 1, &gd)) {
+        if (ok && plain_src && !(d.flags & F_PROJ) && d.k == 1 && d.stride == 1 && d.pad == 0 && arena_aligned16(c, d.w) &&
+            ref_vec4(c, d.x) && make_mm(c, 1, d.K, d.OH * d.OW, d.C, 1, a.H, a.W, a.OH, a.OW, 1, &gd)) {
           d.kind = K_GEMM; d.g = gd; d.gp = gp; d.ntiles = gd.tiles;
         } else
         if (ok) {
@@ -1318,7 +1335,7 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         }
         GemmCfg gd;
         const bool dense = !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)) && d.k == 1 && d.stride == 1 && d.pad == 0 && ref_vec4(c, d.x) &&
-                           ref_vec4(c, d.dy) && make_mm(c, 3, d.K, d.C, d.OH * d.OW, b.gparts >= 0 ? GRAD_PARTS : 1, &gd);
+                           ref_vec4(c, d.dy) && make_mm(c, 3, d.K, d.C, d.OH * d.OW, 1, a.H, a.W, a.OH, a.OW, b.gparts >= 0 ? GRAD_PARTS : 1, &gd);
         if (dense) g = gd;
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles; d.flags &= ~F_BIAS;
         d.gparts = g.parts; d.gpstride = (int)a.padded;
@@ -1366,8 +1383,8 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       if (c->kernel_set == 0 && make_gemm(2, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, true, 16, flat,
                                           dxsplit ? FWD_PARTS : 1)) {
         GemmCfg gd;
-        const bool dense = d.k == 1 && d.stride == 1 && d.pad == 0 && d.w && (d.w - c->f(0)) % 4 == 0 && ref_vec4(c, d.dy) &&
-                           make_mm(c, 2, d.C, d.H * d.W, d.K, 1, &gd);
+        const bool dense = d.k == 1 && d.stride == 1 && d.pad == 0 && arena_aligned16(c, d.w) && ref_vec4(c, d.dy) &&
+                           make_mm(c, 2, d.C, d.H * d.W, d.K, 1, a.H, a.W, a.OH, a.OW, 1, &gd);
         if (dense) g = gd;
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
         if (g.parts > 1) { d.gw = c->f(L.sb[s - 1].dxparts); d.gparts = g.parts; d.gpstride = (int)a.in_elems(); }
@@ -1390,9 +1407,13 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         GemmCfg g;
         if (c->kernel_set == 0 && make_gemm(3, d.C, d.H, d.W, d.K, d.OH, d.OW, 1, d.stride, 0, nullptr, &g, true, 16, false,
                                             b.gparts >= 0 ? GRAD_PARTS : 1)) {
+          GemmCfg gd;
+          const bool dense = ref_vec4(c, d.x) && ref_vec4(c, d.dy) &&
+                             make_mm(c, 3, d.K, d.C, d.OH * d.OW, d.stride, d.H, d.W, d.OH, d.OW, b.gparts >= 0 ? GRAD_PARTS : 1, &gd);
+          if (dense) g = gd;
           d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
           d.gparts = g.parts; d.gpstride = (int)a.padded;
-          gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, 1, d.stride, &d.tq, &d.tn);
+          if (!dense) gemm_tables(c, g, d.C, d.H, d.W, d.K, d.OH, d.OW, 1, d.stride, &d.tq, &d.tn);
         }
         out.push_back({pb, d});
         StepDesc e = blank(K_CONV_BWD_X, s, t_b);
@@ -1406,8 +1427,12 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         e.ntiles = cdiv(ta.in_elems(), BLK);
         GemmCfg g2;
         if (c->kernel_set == 0 && make_gemm(2, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, 0, nullptr, &g2, true)) {
+          GemmCfg gd;
+          const bool dense = arena_aligned16(c, e.w) && ref_vec4(c, e.dy) && ref_vec4(c, e.dx) && ta.in_elems() % 2 == 0 &&
+                             make_mm(c, 2, e.C, e.OH * e.OW, e.K, e.stride, e.H, e.W, e.OH, e.OW, 1, &gd);
+          if (dense) g2 = gd;
           e.kind = K_GEMM; e.g = g2; e.ntiles = g2.tiles;
-          gemm_tables(c, g2, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, &e.tq, &e.tn);
+          if (!dense) gemm_tables(c, g2, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, &e.tq, &e.tn);
         }
         out.push_back({pb, e});
       } else {
@@ -1928,15 +1953,26 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
         // dense matrix-product form of a 1x1 layer: tile and operand shapes the kernel assumes without checking
         auto mm_ok = [&](const GemmCfg& g) {
           const int P = d.OH * d.OW;
-          bool o = !c->nt_stores && d.k == 1 && d.stride == 1 && d.pad == 0 && d.H * d.W == P && !(d.flags & (F_PROJ | F_PRE_AFFINE | F_PRE_RELU)) &&
-                   (g.mi == 2 || g.mi == 4) && (g.ni == 4 || (g.ni == 2 && g.gm == 3)) && g.MT == 32 * g.mi && g.NT == 32 * g.ni &&
+          bool o = !c->nt_stores && d.k == 1 && d.pad == 0 && !(d.flags & (F_PROJ | F_PRE_AFFINE | F_PRE_RELU)) &&
+                   (d.stride == 1 ? (d.H * d.W == P) : (d.stride == 2 && d.H == 2 * d.OH && d.W == 2 * d.OW)) &&
+                   g.ps == d.stride && g.pw == (d.stride == 1 ? P : d.OW) && g.sw == (d.stride == 1 ? P : d.W) && g.shw == d.H * d.W && P >= 1 &&
+                   (g.mi == 2 || g.mi == 4) && (g.ni == 2 || g.ni == 4) && (g.gm == 3 || g.mi == 4 || g.ni == 4) &&
+                   g.MT == 32 * g.mi && g.NT == 32 * g.ni &&
                    2 * mm_chunk_floats(g.gm, g.MT, g.NT) <= LDS_FLOATS && g.M % g.MT == 0 && g.tiles_n == cdiv(g.N, g.NT) &&
                    g.tpp == (g.M / g.MT) * g.tiles_n && g.n_chunks == cdiv(g.Q, MM_QC) && g.parts >= 1 && g.cpp >= 1 &&
                    g.tiles == g.parts * g.tpp && (int64_t)g.parts * g.cpp >= g.n_chunks && (int64_t)(g.parts - 1) * g.cpp < g.n_chunks &&
-                   (g.gm == 3 || (d.w && (d.w - c->f(0)) % 4 == 0 && (d.pmask == 0 || d.pstride % 4 == 0)));
-          if (g.gm == 1) o = o && g.M == d.K && g.N == P && g.Q == d.C && g.Q % MM_QC == 0 && g.N % 4 == 0 && g.parts == 1 && ref_vec4(c, d.x);
-          else if (g.gm == 2) o = o && g.M == d.C && g.N == P && g.Q == d.K && g.Q % MM_QC == 0 && g.N % 4 == 0 && g.parts == 1 && ref_vec4(c, d.dy);
-          else if (g.gm == 3) o = o && g.M == d.K && g.N == d.C && g.Q == P && g.Q % 4 == 0 && g.N % g.NT == 0 && ref_vec4(c, d.x) && ref_vec4(c, d.dy);
+                   (g.gm == 3 || (arena_aligned16(c, d.w) && (d.pmask == 0 || d.pstride % 4 == 0)));
+          // 16-byte fetches of pixel-indexed operands need unit stride and rows that are a multiple of 4 pixels
+          if (g.gm == 1)
+            o = o && g.M == d.K && g.N == P && g.Q == d.C && g.Q % MM_QC == 0 && g.parts == 1 && ref_vec4(c, d.x) &&
+                (g.gather || (d.stride == 1 && P % 4 == 0));
+          else if (g.gm == 2)
+            o = o && g.M == d.C && g.N == P && g.Q == d.K && g.Q % MM_QC == 0 && g.parts == 1 && ref_vec4(c, d.dy) &&
+                (g.gather || P % 4 == 0) &&
+                (d.stride == 1 || (!(d.flags & (F_MASK_X | F_ADD_SKG)) && ref_vec4(c, d.dx) && (d.H * d.W) % 2 == 0 && d.W % 2 == 0));
+          else if (g.gm == 3)
+            o = o && g.M == d.K && g.N == d.C && g.Q == P && g.N % g.NT == 0 && ref_vec4(c, d.x) && ref_vec4(c, d.dy) &&
+                (g.gather || (d.stride == 1 && P % 4 == 0));
           else o = false;
           return o;
         };

@@ -58,10 +58,65 @@ __device__ __forceinline__ void step_mm_t(const LDesc& d, int tile_, int t, lflo
   // forward: A = W[M][Q] rows m0.., B = X[Q][N] columns n0..
   // backward data: A^T = W[Q][M] columns m0.., B = dY[Q][N] columns n0..
   // backward weights: A = dY[M][Q] rows m0.., B^T = X[N][Q] rows n0..
+  // Pixel-indexed operands that cannot be fetched 16 bytes at a time (rows of 49 pixels; the input of a 1x1 layer of
+  // stride 2, of which every second pixel of every second row takes part) are fetched element by element: dense pixel
+  // p lies at poff(p) inside its channel's map, channels shw floats apart.
+  const int gather = UNI(d.g.gather), ps = UNI(d.g.ps), pw = UNI(d.g.pw), sw = UNI(d.g.sw), shw = UNI(d.g.shw);
+  const float ipw = frcp(pw);
+  auto poff = [&](int p) {
+    if (ps == 1) return p;
+    const int oy = fdiv(p, ipw);
+    return (oy * sw + (p - oy * pw)) * ps;
+  };
   constexpr int AV = MT * MM_QC / 4 / BLK;     // 16-byte requests per thread and chunk: A
   constexpr int BV = NT * MM_QC / 4 / BLK;     //                                        B
   v4f ra[AV], rb[BV];
+  auto issue_gather = [&](int ch) {
+    const int q0 = ch * MM_QC;
+    // (loads from clamped positions, zeros selected afterwards: no branch between two loads)
+#pragma unroll
+    for (int u = 0; u < AV; ++u) {
+      const int v = tid + u * BLK;
+      if (MODE == 2) {
+        const int q = v / (MT / 4), c4 = v % (MT / 4);
+        ra[u] = *(const gv4*)(Ag + (size_t)(q0 + q) * M + m0 + 4 * c4);
+      } else if (MODE == 1) {
+        const int r = v >> 3, c4 = v & 7;
+        ra[u] = *(const gv4*)(Ag + (size_t)(m0 + r) * Q + q0 + 4 * c4);
+      } else {
+        const int r = v >> 3, c4 = v & 7;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int p = q0 + 4 * c4 + e, pc = p < Q ? p : Q - 1;
+          const float x = Ag[(size_t)(m0 + r) * Q + pc];
+          ra[u][e] = p < Q ? x : 0.f;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < BV; ++u) {
+      const int v = tid + u * BLK;
+      if (MODE == 3) {
+        const int r = v >> 3, c4 = v & 7;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int p = q0 + 4 * c4 + e, pc = p < Q ? p : Q - 1;
+          const float x = Bg[(size_t)(n0 + r) * shw + poff(pc)];
+          rb[u][e] = p < Q ? x : 0.f;
+        }
+      } else {
+        const int q = v / (NT / 4), c4 = v % (NT / 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int p = n0 + 4 * c4 + e, pc = p < N ? p : N - 1;
+          const float x = Bg[(size_t)(q0 + q) * (MODE == 2 ? N : shw) + (MODE == 2 ? pc : poff(pc))];
+          rb[u][e] = p < N ? x : 0.f;
+        }
+      }
+    }
+  };
   auto issue = [&](int ch) {
+    if (gather) { issue_gather(ch); return; }
     const int q0 = ch * MM_QC;
 #pragma unroll
     for (int u = 0; u < AV; ++u) {
@@ -186,7 +241,7 @@ __device__ __forceinline__ void step_mm_t(const LDesc& d, int tile_, int t, lflo
 #pragma unroll
       for (int r = 0; r < 4; ++r) { add[i][j][r] = 0.f; msk[i][j][r] = 1.f; }
   // (straight-line loads from clamped addresses: a branch per element would make every load wait for the one before)
-  auto gather = [&](const gfloat* src, float (&dst)[MI][NI][4]) {
+  auto epi_fetch = [&](const gfloat* src, float (&dst)[MI][NI][4]) {
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
       const int row = m0 + wr * 16 * MI + 16 * i + 4 * kq;
@@ -199,9 +254,9 @@ __device__ __forceinline__ void step_mm_t(const LDesc& d, int tile_, int t, lflo
       }
     }
   };
-  if (MODE == 1 && skip) gather(skip, add);
-  if (MODE == 2 && skg) gather(skg, add);
-  if (MODE == 2 && xm) gather(xm, msk);
+  if (MODE == 1 && skip) epi_fetch(skip, add);
+  if (MODE == 2 && skg) epi_fetch(skg, add);
+  if (MODE == 2 && xm) epi_fetch(xm, msk);
   if (MODE == 1 && bias) {
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
@@ -221,6 +276,18 @@ __device__ __forceinline__ void step_mm_t(const LDesc& d, int tile_, int t, lflo
     for (int j = 0; j < NI; ++j) {
       const int col = n0 + wc * 16 * NI + 16 * j + li;
       if (col >= N) continue;
+      if (MODE == 2 && ps == 2) {
+        // backward data of a layer of stride 2: the gradient of dense pixel (oy, ox) belongs to input pixel (2 oy, 2 ox);
+        // its three neighbours in the 2 x 2 block took no part in the forward pass
+        const int o = poff(col);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          gfloat* q = out + (size_t)(row + r) * shw + o;
+          *(gv2*)q = (v2f){rbf_if(round, acc[i][j][r]), 0.f};
+          *(gv2*)(q + sw) = (v2f){0.f, 0.f};
+        }
+        continue;
+      }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         float v = acc[i][j][r];
@@ -232,13 +299,15 @@ __device__ __forceinline__ void step_mm_t(const LDesc& d, int tile_, int t, lflo
 }
 
 __device__ __forceinline__ void step_mm(const LDesc& d, int tile, int t, lfloat* smem) {
-  // forward and backward data: 128-column tiles; the rows of a tile 64 or 128 as the layer's channel count allows
+  // forward and backward data: tiles of 128 x 128, 64 x 128 (layers of 64 channels) or 128 x 64 (maps of at most 64 pixels)
   const int gm = UNI(d.g.gm), mi = UNI(d.g.mi), ni = UNI(d.g.ni);
   if (gm == 1) {
-    if (mi == 4) step_mm_t<1, 4, 4>(d, tile, t, smem);
+    if (mi == 4 && ni == 4) step_mm_t<1, 4, 4>(d, tile, t, smem);
+    else if (mi == 4) step_mm_t<1, 4, 2>(d, tile, t, smem);
     else step_mm_t<1, 2, 4>(d, tile, t, smem);
   } else if (gm == 2) {
-    if (mi == 4) step_mm_t<2, 4, 4>(d, tile, t, smem);
+    if (mi == 4 && ni == 4) step_mm_t<2, 4, 4>(d, tile, t, smem);
+    else if (mi == 4) step_mm_t<2, 4, 2>(d, tile, t, smem);
     else step_mm_t<2, 2, 4>(d, tile, t, smem);
   } else {
     if (mi == 4 && ni == 4) step_mm_t<3, 4, 4>(d, tile, t, smem);
