@@ -90,8 +90,9 @@ typedef struct {
                                longest run of last phases that hold steps of at most two stages                    */
   int32_t spin_limit;       /* bound of such a wait, in polls (0 = default, 65536: a fraction of a second); when it expires the
                                step is skipped and the next synchronising call returns PB_E_HIP                    */
-  int32_t dense_1x1;        /* 1x1 layers of stride 1 in throughput-tiled networks as dense matrix products with register
-                               tiles: -1 off, 0 or 1 on where the shapes allow                                      */
+  int32_t dense_1x1;        /* 1x1 layers in throughput-tiled networks as dense matrix products with register tiles:
+                               -1 off, 0 or 1 on where the shapes allow, 2 also forward and backward weights of k x k
+                               layers (their operands gathered tap by tap: measured slower, never chosen by policy)  */
   int32_t gemm_lds_kb;      /* LDS a GEMM tile may plan with, KB: 62 or 76 (two workgroups share a compute unit's 160 KB);
                                0: by policy (76 where a tick holds long reductions, 62 elsewhere)                  */
 } pb_tuning;

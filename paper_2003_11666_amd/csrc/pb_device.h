@@ -87,6 +87,8 @@ struct GemmCfg {
   int32_t gather;          // dense form: pixel-indexed operands are fetched element by element (rows not a multiple of 4 pixels,
   int32_t ps, pw;          // or a layer of stride ps = 2): dense pixel p = (oy, ox) of a pw-wide map lies at ps (oy sw + ox) in its
   int32_t sw, shw;         // channel's map, whose rows are sw floats and whose channels are shw floats apart
+  int32_t ck, cpad, sh;    // dense form of a k x k layer (ck = k, its padding, rows of the source map): the reduction or the
+                           // columns run over (channel, tap), see pb_mm.h
   int32_t a_req;           // requests per thread that the A block of a full chunk takes (the kernel built for latency keeps
                            // nine of them in flight when there are more than six, six otherwise)
 };

@@ -636,24 +636,39 @@ __attribute__((noinline)) bool arena_aligned16(const pb_ctx* c, const float* p) 
   return ((uintptr_t)p - (uintptr_t)c->f(0)) % 16 == 0;
 }
 
-// Dense matrix-product form of a 1x1 layer (pb_mm.h) in a network tiled for throughput: M x N result, reduction Q,
-// every matrix row-major as it lies in memory.  Forward and backward data: M = output rows (a multiple of 64), N =
-// pixels of the layer's output map (forward) or of its gradient (backward data), Q = channels contracted (a multiple
-// of 32).  Backward weights: M x N = cout x cin (multiples of 64), Q = pixels, its chunks dealt out to up to max_parts
-// groups of workgroups.  A layer of stride 2 (OH x OW output pixels of an H x W map, H = 2 OH, W = 2 OW) contracts over
-// its output pixels only; operands indexed by pixels are then gathered element by element, as are rows whose length
-// is not a multiple of 4.
-bool make_mm(const pb_ctx* c, int mode, int M, int N, int Q, int stride, int H, int W, int OH, int OW, int max_parts, GemmCfg* out) {
+// Dense matrix-product form of a layer (pb_mm.h) in a network tiled for throughput: M x N result, reduction Q.
+//   forward           M = cout, N = output pixels,  Q = cin k k   (a multiple of 32)
+//   backward data     M = cin,  N = input pixels,   Q = cout k k  (a multiple of 32); k > 1: stride 1 only
+//   backward weights  M = cout, N = cin k k (a multiple of 64), Q = output pixels, its chunks dealt out to up to
+//                     max_parts groups of workgroups
+// M is a multiple of 64.  A 1x1 layer of stride 1 whose map has a multiple of 4 pixels is a plain product of matrices
+// as they lie in memory; every other shape gathers its pixel-indexed operand element by element (a 1x1 layer of
+// stride 2, H = 2 OH, W = 2 OW, runs its backward data over the output pixels and scatters).
+bool make_mm(const pb_ctx* c, int mode, int C, int H, int W, int K, int OH, int OW, int k, int stride, int pad, int max_parts,
+             GemmCfg* out) {
   if (g_tile_budget_us <= 0 || c->kernel_set != 0 || c->tune.dense_1x1 < 0) return false;
-  if (stride != 1 && !(stride == 2 && H == 2 * OH && W == 2 * OW)) return false;
-  const int P = OH * OW;
-  if (M % 64 || M < 64 || (int64_t)M * std::max(N, Q) >= ((int64_t)1 << 30) || (int64_t)std::max(M, N) * H * W >= ((int64_t)1 << 30)) return false;
-  if (mode == 3 ? (N % 64 || N < 64 || Q != P || Q < 4) : (N != P || N < 16 || Q % MM_QC || Q < MM_QC)) return false;
+  if (k < 1 || k > 7 || pad < 0 || pad >= k || (stride != 1 && stride != 2)) return false;
+  if (k == 1 && stride == 2 && !(H == 2 * OH && W == 2 * OW)) return false;
+  // k x k layers: their pixel-indexed operand would be gathered tap by tap, nine requests for what the patch-based tiles
+  // fetch once and reuse from LDS -- measured 1.3 (ResNet-50) to 2.8 (VGG-11) times the tick of the patch-based tiles.
+  // Planned only on request (pb_tuning.dense_1x1 = 2: forward and backward weights), which keeps the geometry tested.
+  if (k > 1 && (mode == 2 || c->tune.dense_1x1 != 2)) return false;
+  if (k == 1 && stride == 1 && (H != OH || W != OW || pad != 0)) return false;
+  const int kk = k * k, P = OH * OW, HW = H * W;
+  const int M = mode == 2 ? C : K;
+  const int N = mode == 1 ? P : mode == 2 ? (k == 1 ? P : HW) : C * kk;
+  const int Q = mode == 1 ? C * kk : mode == 2 ? K * kk : P;
+  if (M % 64 || M < 64 || (int64_t)K * C * kk >= ((int64_t)1 << 30) || (int64_t)std::max(C, K) * std::max(HW, P) >= ((int64_t)1 << 30)) return false;
+  if (mode == 3 ? (N % 64 || N < 64 || Q < 4) : (N < 16 || Q % MM_QC || Q < MM_QC)) return false;
+  if (std::max(N, Q) >= (1 << 20)) return false;   // (index divisions in the kernel are exact below 2^21)
   GemmCfg g;
   memset(&g, 0, sizeof g);
   g.gm = mode; g.mm = 1; g.M = M; g.N = N; g.Q = Q;
-  g.ps = stride; g.pw = stride == 1 ? P : OW; g.sw = stride == 1 ? H * W : W; g.shw = H * W;   // (stride 1: the map as one row)
-  g.gather = mode == 2 ? (P % 4 != 0) : (stride == 2 || P % 4 != 0);
+  g.ps = stride; g.ck = k; g.cpad = pad;
+  if (k == 1 && stride == 1) { g.pw = P; g.sw = HW; g.sh = 1; g.shw = HW; }          // the map as one row
+  else if (mode == 2 && k > 1) { g.pw = W; g.sw = OW; g.sh = OH; g.shw = P; }          // pixel space: the input map; source: dY
+  else { g.pw = OW; g.sw = W; g.sh = H; g.shw = HW; }                                  // pixel space: the output map; source: the input
+  g.gather = k > 1 ? 1 : mode == 2 ? (P % 4 != 0) : (stride == 2 || P % 4 != 0);
   g.mi = M % 128 == 0 ? 4 : 2;
   g.ni = mode == 3 ? (N % 128 == 0 ? 4 : 2) : (N > 64 ? 4 : 2);
   if (mode != 3 && g.mi == 2 && g.ni == 2) return false;   // (no 64 x 64 tiles for these two passes)
@@ -993,10 +1008,12 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
   // 6 flops per multiply-accumulate ran at a third of the fp32 MFMA peak, spread
   // over the two GEMM phases of a tick.
   {
+    // (1x1 layers run as dense matrix products at about twice the rate of the patch-based tiles: counted half)
     double macs = 0;
+    const bool dense = c->kernel_set == 0 && c->tune.dense_1x1 >= 0;
     for (const Stage& a : c->st) {
-      macs += (double)a.K * a.OH * a.OW * a.C * a.k * a.k;
-      if (a.proj) macs += (double)a.K * a.OH * a.OW * a.sC;
+      macs += (double)a.K * a.OH * a.OW * a.C * a.k * a.k * (dense && a.k == 1 && a.K % 64 == 0 && a.C % 64 == 0 ? 0.5 : 1.0);
+      if (a.proj) macs += (double)a.K * a.OH * a.OW * a.sC * (dense && a.K % 64 == 0 && a.sC % 64 == 0 ? 0.5 : 1.0);
     }
     const double tick_us = 6.0 * macs / 50e6;
     g_tile_budget_us = tick_us >= 10.0 ? std::max(16.0, 0.65 * tick_us) : 0.0;
@@ -1164,7 +1181,7 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
             e.ntiles = cdiv((int64_t)a.K * a.OH * a.OW, BLK);
             GemmCfg ge, gd;
             const bool dense = arena_aligned16(c, e.w) && ref_vec4(c, e.x) &&
-                               make_mm(c, 1, e.K, e.OH * e.OW, e.C, e.stride, e.H, e.W, e.OH, e.OW, 1, &gd);
+                               make_mm(c, 1, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, 0, 1, &gd);
             if (dense || make_gemm(1, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, 0, nullptr, &ge, true)) {
               if (dense) ge = gd;
               e.kind = K_GEMM; e.g = ge; e.ntiles = ge.tiles;
@@ -1205,8 +1222,8 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
                             zsplit ? FWD_PARTS : 1);
         if (ok && (d.flags & F_PROJ)) ok = make_gemm(1, d.sC, d.sH, d.sW, d.K, d.OH, d.OW, 1, d.sstride, 0, &g, &gp, true);
         GemmCfg gd;
-        if (ok && plain_src && !(d.flags & F_PROJ) && d.k == 1 && d.stride == 1 && d.pad == 0 && arena_aligned16(c, d.w) &&
-            ref_vec4(c, d.x) && make_mm(c, 1, d.K, d.OH * d.OW, d.C, 1, a.H, a.W, a.OH, a.OW, 1, &gd)) {
+        if (ok && plain_src && !(d.flags & F_PROJ) && arena_aligned16(c, d.w) &&
+            ref_vec4(c, d.x) && make_mm(c, 1, a.C, a.H, a.W, a.K, a.OH, a.OW, a.k, a.stride, a.pad, 1, &gd)) {
           d.kind = K_GEMM; d.g = gd; d.gp = gp; d.ntiles = gd.tiles;
         } else
         if (ok) {
@@ -1334,8 +1351,8 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
           out.push_back({pb, e});
         }
         GemmCfg gd;
-        const bool dense = !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)) && d.k == 1 && d.stride == 1 && d.pad == 0 && ref_vec4(c, d.x) &&
-                           ref_vec4(c, d.dy) && make_mm(c, 3, d.K, d.C, d.OH * d.OW, 1, a.H, a.W, a.OH, a.OW, b.gparts >= 0 ? GRAD_PARTS : 1, &gd);
+        const bool dense = !(d.flags & (F_PRE_AFFINE | F_PRE_RELU)) && ref_vec4(c, d.x) && ref_vec4(c, d.dy) &&
+                           make_mm(c, 3, a.C, a.H, a.W, a.K, a.OH, a.OW, a.k, a.stride, a.pad, b.gparts >= 0 ? GRAD_PARTS : 1, &gd);
         if (dense) g = gd;
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles; d.flags &= ~F_BIAS;
         d.gparts = g.parts; d.gpstride = (int)a.padded;
@@ -1383,8 +1400,8 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
       if (c->kernel_set == 0 && make_gemm(2, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, nullptr, &g, true, 16, flat,
                                           dxsplit ? FWD_PARTS : 1)) {
         GemmCfg gd;
-        const bool dense = d.k == 1 && d.stride == 1 && d.pad == 0 && arena_aligned16(c, d.w) && ref_vec4(c, d.dy) &&
-                           make_mm(c, 2, d.C, d.H * d.W, d.K, 1, a.H, a.W, a.OH, a.OW, 1, &gd);
+        const bool dense = arena_aligned16(c, d.w) && ref_vec4(c, d.dy) &&
+                           make_mm(c, 2, a.C, a.H, a.W, a.K, a.OH, a.OW, a.k, a.stride, a.pad, 1, &gd);
         if (dense) g = gd;
         d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
         if (g.parts > 1) { d.gw = c->f(L.sb[s - 1].dxparts); d.gparts = g.parts; d.gpstride = (int)a.in_elems(); }
@@ -1409,7 +1426,7 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
                                             b.gparts >= 0 ? GRAD_PARTS : 1)) {
           GemmCfg gd;
           const bool dense = ref_vec4(c, d.x) && ref_vec4(c, d.dy) &&
-                             make_mm(c, 3, d.K, d.C, d.OH * d.OW, d.stride, d.H, d.W, d.OH, d.OW, b.gparts >= 0 ? GRAD_PARTS : 1, &gd);
+                             make_mm(c, 3, d.C, d.H, d.W, d.K, d.OH, d.OW, 1, d.stride, 0, b.gparts >= 0 ? GRAD_PARTS : 1, &gd);
           if (dense) g = gd;
           d.kind = K_GEMM; d.g = g; d.ntiles = g.tiles;
           d.gparts = g.parts; d.gpstride = (int)a.padded;
@@ -1429,7 +1446,7 @@ void compile_steps_once(pb_ctx* c, std::vector<std::pair<int, StepDesc>>& out) {
         if (c->kernel_set == 0 && make_gemm(2, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, 0, nullptr, &g2, true)) {
           GemmCfg gd;
           const bool dense = arena_aligned16(c, e.w) && ref_vec4(c, e.dy) && ref_vec4(c, e.dx) && ta.in_elems() % 2 == 0 &&
-                             make_mm(c, 2, e.C, e.OH * e.OW, e.K, e.stride, e.H, e.W, e.OH, e.OW, 1, &gd);
+                             make_mm(c, 2, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, 0, 1, &gd);
           if (dense) g2 = gd;
           e.kind = K_GEMM; e.g = g2; e.ntiles = g2.tiles;
           if (!dense) gemm_tables(c, g2, e.C, e.H, e.W, e.K, e.OH, e.OW, 1, e.stride, &e.tq, &e.tn);
@@ -1952,28 +1969,19 @@ int validate_steps(const pb_ctx* c, const std::vector<std::pair<int, StepDesc>>&
         };
         // dense matrix-product form of a 1x1 layer: tile and operand shapes the kernel assumes without checking
         auto mm_ok = [&](const GemmCfg& g) {
-          const int P = d.OH * d.OW;
-          bool o = !c->nt_stores && d.k == 1 && d.pad == 0 && !(d.flags & (F_PROJ | F_PRE_AFFINE | F_PRE_RELU)) &&
-                   (d.stride == 1 ? (d.H * d.W == P) : (d.stride == 2 && d.H == 2 * d.OH && d.W == 2 * d.OW)) &&
-                   g.ps == d.stride && g.pw == (d.stride == 1 ? P : d.OW) && g.sw == (d.stride == 1 ? P : d.W) && g.shw == d.H * d.W && P >= 1 &&
-                   (g.mi == 2 || g.mi == 4) && (g.ni == 2 || g.ni == 4) && (g.gm == 3 || g.mi == 4 || g.ni == 4) &&
-                   g.MT == 32 * g.mi && g.NT == 32 * g.ni &&
-                   2 * mm_chunk_floats(g.gm, g.MT, g.NT) <= LDS_FLOATS && g.M % g.MT == 0 && g.tiles_n == cdiv(g.N, g.NT) &&
-                   g.tpp == (g.M / g.MT) * g.tiles_n && g.n_chunks == cdiv(g.Q, MM_QC) && g.parts >= 1 && g.cpp >= 1 &&
-                   g.tiles == g.parts * g.tpp && (int64_t)g.parts * g.cpp >= g.n_chunks && (int64_t)(g.parts - 1) * g.cpp < g.n_chunks &&
-                   (g.gm == 3 || (arena_aligned16(c, d.w) && (d.pmask == 0 || d.pstride % 4 == 0)));
-          // 16-byte fetches of pixel-indexed operands need unit stride and rows that are a multiple of 4 pixels
-          if (g.gm == 1)
-            o = o && g.M == d.K && g.N == P && g.Q == d.C && g.Q % MM_QC == 0 && g.parts == 1 && ref_vec4(c, d.x) &&
-                (g.gather || (d.stride == 1 && P % 4 == 0));
+          // the configuration is exactly what the planner makes of the step's own geometry (make_mm holds the shape
+          // rules the kernel relies on); beyond that, the operands' alignment and the flags the dense form knows
+          GemmCfg want;
+          if (c->nt_stores || (d.flags & (F_PROJ | F_PRE_AFFINE | F_PRE_RELU)) || g.gm < 1 || g.gm > 3 ||
+              !make_mm(c, g.gm, d.C, d.H, d.W, d.K, d.OH, d.OW, d.k, d.stride, d.pad, g.parts > 1 ? GRAD_PARTS : 1, &want) ||
+              memcmp(&want, &g, sizeof g) != 0)
+            return false;
+          bool o = g.gm == 3 || (arena_aligned16(c, d.w) && (d.pmask == 0 || d.pstride % 4 == 0));
+          if (g.gm == 1) o = o && ref_vec4(c, d.x);
           else if (g.gm == 2)
-            o = o && g.M == d.C && g.N == P && g.Q == d.K && g.Q % MM_QC == 0 && g.parts == 1 && ref_vec4(c, d.dy) &&
-                (g.gather || P % 4 == 0) &&
-                (d.stride == 1 || (!(d.flags & (F_MASK_X | F_ADD_SKG)) && ref_vec4(c, d.dx) && (d.H * d.W) % 2 == 0 && d.W % 2 == 0));
-          else if (g.gm == 3)
-            o = o && g.M == d.K && g.N == d.C && g.Q == P && g.N % g.NT == 0 && ref_vec4(c, d.x) && ref_vec4(c, d.dy) &&
-                (g.gather || (d.stride == 1 && P % 4 == 0));
-          else o = false;
+            o = o && ref_vec4(c, d.dy) &&
+                (g.ps == 1 || (!(d.flags & (F_MASK_X | F_ADD_SKG)) && ref_vec4(c, d.dx) && (d.H * d.W) % 2 == 0 && d.W % 2 == 0));
+          else o = o && ref_vec4(c, d.x) && ref_vec4(c, d.dy);
           return o;
         };
         if (d.g.mm) {

@@ -71,47 +71,95 @@ __device__ __forceinline__ void step_mm_t(const LDesc& d, int tile_, int t, lflo
   constexpr int AV = MT * MM_QC / 4 / BLK;     // 16-byte requests per thread and chunk: A
   constexpr int BV = NT * MM_QC / 4 / BLK;     //                                        B
   v4f ra[AV], rb[BV];
+  // Convolution geometry of the gathered operands.  A k x k layer is the same product with the reduction (forward,
+  // backward data) or the columns (backward weights) running over (channel, tap): the element for tap (kh, kw) and
+  // pixel (y, x) of the step's pixel space lies at row ps y + dy, column ps x + dx of the source map (dy = kh - pad
+  // forward and backward weights, pad - kh backward data), and is zero outside the map.
+  const int ck = UNI(d.g.ck), kk = ck * ck, cpad = UNI(d.g.cpad), srcH = UNI(d.g.sh);
+  const float ikk = frcp(kk), ick = frcp(ck);
+  auto tap_of = [&](int q, int& c, int& dy, int& dx) {
+    c = fdiv(q, ikk);
+    const int tap = q - c * kk, kh = fdiv(tap, ick), kw = tap - kh * ck;
+    dy = MODE == 2 ? cpad - kh : kh - cpad;
+    dx = MODE == 2 ? cpad - kw : kw - cpad;
+  };
+  auto pix_of = [&](int p, int& y, int& x) {
+    y = fdiv(p, ipw);
+    x = (p - y * pw) * ps;
+    y *= ps;
+  };
+  // (a load from a clamped position and a select: no branch between two loads)
+  auto src_at = [&](const gfloat* base, int c, int y, int x, bool ok) -> float {
+    const bool in = ok && y >= 0 && y < srcH && x >= 0 && x < sw;
+    const float v = base[(unsigned)(in ? c * shw + y * sw + x : 0)];   // (unsigned: a 32-bit offset from a scalar base)
+    return in ? v : 0.f;
+  };
+  // Gathered operands are dealt out so that the lanes of a wavefront read neighbouring addresses (a request that
+  // touches 64 scattered lines costs the memory pipeline many times one that touches two): element i of a thread is
+  // entry tid + 256 i of the operand's chunk in its LDS order, [reduction][column] (forward, backward data) or
+  // [row][reduction] (backward weights), so a thread keeps one column (one reduction entry) for all its elements.
+  const bool a_gather = MODE == 3 && (Q & 3) != 0;       // rows of dY that cannot be fetched 16 bytes at a time
+  int gy = 0, gx = 0;
+  bool gok = false;
+  if (gather && MODE != 3) {
+    const int p = n0 + tid % NT;
+    gok = p < N;
+    pix_of(gok ? p : 0, gy, gx);
+  }
   auto issue_gather = [&](int ch) {
     const int q0 = ch * MM_QC;
-    // (loads from clamped positions, zeros selected afterwards: no branch between two loads)
+    if (a_gather) {
 #pragma unroll
-    for (int u = 0; u < AV; ++u) {
-      const int v = tid + u * BLK;
-      if (MODE == 2) {
-        const int q = v / (MT / 4), c4 = v % (MT / 4);
-        ra[u] = *(const gv4*)(Ag + (size_t)(q0 + q) * M + m0 + 4 * c4);
-      } else if (MODE == 1) {
-        const int r = v >> 3, c4 = v & 7;
-        ra[u] = *(const gv4*)(Ag + (size_t)(m0 + r) * Q + q0 + 4 * c4);
-      } else {
-        const int r = v >> 3, c4 = v & 7;
+      for (int i = 0; i < 4 * AV; ++i) {
+        const int idx = tid + i * BLK, r = idx >> 5, p = q0 + (idx & 31), pc = p < Q ? p : Q - 1;
+        const float x = Ag[(unsigned)((m0 + r) * Q + pc)];
+        ra[i >> 2][i & 3] = p < Q ? x : 0.f;
+      }
+    } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int p = q0 + 4 * c4 + e, pc = p < Q ? p : Q - 1;
-          const float x = Ag[(size_t)(m0 + r) * Q + pc];
-          ra[u][e] = p < Q ? x : 0.f;
+      for (int u = 0; u < AV; ++u) {
+        const int v = tid + u * BLK;
+        if (MODE == 2) {
+          const int q = v / (MT / 4), c4 = v % (MT / 4);
+          ra[u] = *(const gv4*)(Ag + (size_t)(q0 + q) * M + m0 + 4 * c4);
+        } else {
+          const int r = v >> 3, c4 = v & 7;
+          ra[u] = (v4f){0.f, 0.f, 0.f, 0.f};
+          if (q0 + 4 * c4 < Q) ra[u] = *(const gv4*)(Ag + (size_t)(m0 + r) * Q + q0 + 4 * c4);
         }
       }
     }
+    if (MODE == 3) {
+      const int p = q0 + (tid & 31);
+      int y, x;
+      pix_of(p < Q ? p : 0, y, x);
+      // (an opaque copy of the first column: its rows' taps are worked out again for every chunk instead of being
+      // kept, 48 registers of them, across the whole contraction)
+      int nb = n0;
+      asm volatile("" : "+v"(nb));
 #pragma unroll
-    for (int u = 0; u < BV; ++u) {
-      const int v = tid + u * BLK;
-      if (MODE == 3) {
-        const int r = v >> 3, c4 = v & 7;
+      for (int i = 0; i < 4 * BV; ++i) {
+        const int r = (tid >> 5) + i * (BLK / 32);
+        int c, dy, dx;
+        tap_of(nb + r, c, dy, dx);
+        rb[i >> 2][i & 3] = src_at(Bg, c, y + dy, x + dx, p < Q);
+      }
+    } else if (MODE == 2) {
+      // (a 1x1 layer: the gradient as it lies, also for stride 2, where the product runs over the output pixels)
+      const int p = n0 + tid % NT, pc = p < N ? p : N - 1;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int p = q0 + 4 * c4 + e, pc = p < Q ? p : Q - 1;
-          const float x = Bg[(size_t)(n0 + r) * shw + poff(pc)];
-          rb[u][e] = p < Q ? x : 0.f;
-        }
-      } else {
-        const int q = v / (NT / 4), c4 = v % (NT / 4);
+      for (int i = 0; i < 4 * BV; ++i) {
+        const int q = tid / NT + i * (BLK / NT);
+        const float x = Bg[(unsigned)((q0 + q) * N + pc)];
+        rb[i >> 2][i & 3] = p < N ? x : 0.f;
+      }
+    } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int p = n0 + 4 * c4 + e, pc = p < N ? p : N - 1;
-          const float x = Bg[(size_t)(q0 + q) * (MODE == 2 ? N : shw) + (MODE == 2 ? pc : poff(pc))];
-          rb[u][e] = p < N ? x : 0.f;
-        }
+      for (int i = 0; i < 4 * BV; ++i) {
+        const int q = tid / NT + i * (BLK / NT);
+        int c, dy, dx;
+        tap_of(q0 + q, c, dy, dx);
+        rb[i >> 2][i & 3] = src_at(Bg, c, gy + dy, gx + dx, gok);
       }
     }
   };
@@ -146,17 +194,34 @@ __device__ __forceinline__ void step_mm_t(const LDesc& d, int tile_, int t, lflo
   auto commit = [&](lfloat* buf) {
     lfloat* Al = buf;
     lfloat* Bl = buf + A_FLOATS;
+    if (a_gather) {
 #pragma unroll
-    for (int u = 0; u < AV; ++u) {
-      const int v = tid + u * BLK;
-      if (MODE == 2) *(lv4*)(Al + (v / (MT / 4)) * LDAT + 4 * (v % (MT / 4))) = ra[u];
-      else *(lv4*)(Al + (v >> 3) * MM_LDK + 4 * (v & 7)) = ra[u];
+      for (int i = 0; i < 4 * AV; ++i) {
+        const int idx = tid + i * BLK;
+        Al[(idx >> 5) * MM_LDK + (idx & 31)] = ra[i >> 2][i & 3];
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < AV; ++u) {
+        const int v = tid + u * BLK;
+        if (MODE == 2) *(lv4*)(Al + (v / (MT / 4)) * LDAT + 4 * (v % (MT / 4))) = ra[u];
+        else *(lv4*)(Al + (v >> 3) * MM_LDK + 4 * (v & 7)) = ra[u];
+      }
     }
+    if (gather) {
 #pragma unroll
-    for (int u = 0; u < BV; ++u) {
-      const int v = tid + u * BLK;
-      if (MODE == 3) *(lv4*)(Bl + (v >> 3) * MM_LDK + 4 * (v & 7)) = rb[u];
-      else *(lv4*)(Bl + (v / (NT / 4)) * LDB + 4 * (v % (NT / 4))) = rb[u];
+      for (int i = 0; i < 4 * BV; ++i) {
+        const int idx = tid + i * BLK;
+        if (MODE == 3) Bl[(idx >> 5) * MM_LDK + (idx & 31)] = rb[i >> 2][i & 3];
+        else Bl[(idx / NT) * LDB + idx % NT] = rb[i >> 2][i & 3];
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < BV; ++u) {
+        const int v = tid + u * BLK;
+        if (MODE == 3) *(lv4*)(Bl + (v >> 3) * MM_LDK + 4 * (v & 7)) = rb[u];
+        else *(lv4*)(Bl + (v / (NT / 4)) * LDB + 4 * (v % (NT / 4))) = rb[u];
+      }
     }
   };
 

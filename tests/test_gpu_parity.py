@@ -206,6 +206,30 @@ def test_resnet50_structure_64px_120_ticks():
     _check(res, 120, len(net["stages"]), "resnet50_64")
 
 
+def test_kxk_layers_in_the_dense_form_on_request():
+    """Forward and backward weights of the 3x3 layers through the dense matrix-product steps as well (operands
+    gathered tap by tap; slower than the patch-based tiles, so only planned on request): the same network, the
+    same bounds."""
+    from paper_2003_11666_amd import binding
+    net = W.config("resnet50_64")
+    plan = binding.plan_summary(net, tuning=dict(dense_1x1=2))
+    assert [l for l in plan.splitlines() if " k3 s1 " in l and "dense" in l and "gm1" in l]
+    assert [l for l in plan.splitlines() if " k3 s2 " in l and "dense" in l and "gm3" in l]
+    res = run_parity(_engine(), net, 120, every=10, engine_kwargs=dict(tuning=dict(dense_1x1=2)))
+    _check(res, 120, len(net["stages"]), "resnet50_64")
+
+
+def test_1x1_layers_of_the_deep_network_run_as_dense_matrix_products():
+    """Every 1x1 layer of the ResNet-50 configuration -- stride 1 and the stride-2 projections, 56x56 down to 7x7 maps,
+    all three passes -- is planned as a dense step; parity of these steps with the oracle is that of the ResNet-50
+    tests around this one."""
+    from paper_2003_11666_amd import binding
+    plan = binding.plan_summary(W.config("resnet50"))
+    rows = [l for l in plan.splitlines() if " gemm " in l and " k1 " in l]
+    assert len(rows) > 90 and all("dense" in l for l in rows), [l for l in rows if "dense" not in l][:3]
+    assert not [l for l in plan.splitlines() if " gemm " in l and " k3 " in l and "dense" in l]
+
+
 @pytest.mark.timeout(900)
 def test_resnet50_config_full_size_110_ticks():
     """The ResNet-50 configuration at its full size (3x224x224, 50 stages, 25.5 M parameters, the
