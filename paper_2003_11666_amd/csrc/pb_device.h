@@ -99,7 +99,7 @@ constexpr int MM_LDK = MM_QC + 4;    // row stride of an operand stored [row][re
 
 // LDS floats of one chunk (both operands); the step needs twice that
 __host__ __device__ constexpr int mm_chunk_floats(int mode, int MT, int NT) {
-  return (mode == 2 ? MM_QC * (MT + 4) : MT * MM_LDK) + (mode == 3 ? NT * MM_LDK : MM_QC * (NT + 16));
+  return (mode == 2 ? MM_QC * (MT + 4) : MT * MM_LDK) + (mode == 3 ? NT * MM_LDK : MM_QC * (NT + 4));
 }
 
 // Pointer fields of a step that point into slot 0 of the stage's ring of predicted-weight versions;

@@ -32,7 +32,8 @@ __device__ __forceinline__ void step_mm_t(const LDesc& d, int tile_, int t, lflo
   asm volatile("" : "+s"(tile));
   constexpr int MT = 32 * MI, NT = 32 * NI;
   constexpr int LDAT = MT + 4;       // backward data: A stored [reduction][row]
-  constexpr int LDB = NT + 16;       // forward, backward data: B stored [reduction][column]
+  constexpr int LDB = NT + 4;        // forward, backward data: B stored [reduction][column]; the four lane groups of a
+                                     // wave read rows 4 apart: 4 LDB = 16 (mod 32) keeps them on different banks
   constexpr int A_FLOATS = MODE == 2 ? MM_QC * LDAT : MT * MM_LDK;
   constexpr int CHUNK = mm_chunk_floats(MODE, MT, NT);
   const int tid = threadIdx.x, lane = tid & 63, wv = UNI(tid >> 6);
