@@ -794,6 +794,9 @@ bool make_gemm(int mode, int C, int H, int W, int K, int OH, int OW, int k, int 
     while (tiles() < target && g.ni > 1) g.ni /= 2;
     while (tiles() < target && g.wm > 1 && g.Q >= 64 * g.wk * 2) { g.wm /= 2; g.wk *= 2; }
     while (tiles() < target && g.wn > 1 && g.Q >= 64 * g.wk * 2) { g.wn /= 2; g.wk *= 2; }
+    // the same tile with two column subtiles per wave and the reduction split once more: the A values and patch offsets
+    // a wave fetches per k-step then feed two MFMAs (ResNet-20 23.4 -> 23.2 us per tick)
+    if (g.wn >= 2 && g.ni == 1 && g.Q >= 64 * g.wk * 2) { g.wn /= 2; g.ni = 2; g.wk *= 2; }
   }
   if (!fit_gemm(g, C, H, W, K, OH, OW, k, s, pad, allow_vec, like && g_tile_budget_us > 0)) return false;
   *out = g;
