@@ -841,6 +841,16 @@ __device__ __forceinline__ void step_gnb_apply(const LDesc& d, int tile, int t) 
 
 // The same update for one parameter (GroupNorm scale or shift updated by the
 // step that produced its gradient): w, v at index i in place, w_hat into the other copy.
+// (the same with the parameter and its velocity already in registers)
+__device__ __forceinline__ void update_loaded(const LDesc& d, int i, float g, float vv, float wv) {
+  const float w_old = wv;
+  vv = fmaf(UNIF(d.fm), vv, g);
+  wv = fmaf(-UNIF(d.flr), fmaf(UNIF(d.fa), vv, UNIF(d.fb) * g), wv);
+  GP((float*)d.b)[i] = vv;
+  GP((float*)d.w)[i] = wv;
+  if (d.what) GP(d.what)[i] = (UNI(d.flags) & F_LWP_W) ? fmaf(UNIF(d.flrT), wv - w_old, wv) : fmaf(-UNIF(d.flrT), vv, wv);
+}
+
 __device__ __forceinline__ void update_one(const LDesc& d, int i, float g) {
   float vv = GP(d.v)[i], wv = GP(d.w)[i];
   const float w_old = wv;
@@ -897,6 +907,15 @@ __device__ __forceinline__ void step_gn_bwd(const LDesc& d, int tile, int t, boo
         if (skg) sk[u] = *(const gv4*)(skg + 4 * sl);
       }
     }
+  }
+  // Scale and shift of the group's channels are updated by lane 4c of channel c once their gradients are summed: their
+  // master values and velocities are requested here, with the step's other reads, not after the sums (a memory round
+  // trip in the middle of the step, with the whole workgroup waiting at the next barrier).
+  const bool upd_pre = (flags & F_UPD_GN) && 4 * cpg <= BLK;
+  float uv0 = 0.f, uw0 = 0.f, uv1 = 0.f, uw1 = 0.f;
+  if (upd_pre && tid < 4 * cpg && (tid & 3) == 0) {
+    const int i0 = g * cpg + (tid >> 2), i1 = C + i0;
+    uv0 = GP(d.v)[i0]; uw0 = GP(d.w)[i0]; uv1 = GP(d.v)[i1]; uw1 = GP(d.w)[i1];
   }
   if (!nt && UNI(d.gparts) > 1 && !gapd) {
     // the gradient was left as partial sums by a backward-data GEMM split over its reduction
@@ -958,7 +977,8 @@ __device__ __forceinline__ void step_gn_bwd(const LDesc& d, int tile, int t, boo
     if (p == 0) {
       GP(d.ggamma)[g * cpg + c] = sg; GP(d.gbeta)[g * cpg + c] = sb;
       cs2[c] = sb; cs2[cpg + c] = sg;
-      if (flags & F_UPD_GN) { update_one(d, g * cpg + c, sg); update_one(d, C + g * cpg + c, sb); }
+      if (upd_pre) { update_loaded(d, g * cpg + c, sg, uv0, uw0); update_loaded(d, C + g * cpg + c, sb, uv1, uw1); }
+      else if (flags & F_UPD_GN) { update_one(d, g * cpg + c, sg); update_one(d, C + g * cpg + c, sb); }
     }
   }
   __syncthreads();
