@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 # Bytes that crossed the L2 / fabric boundary per algorithmic byte of a k_phase launch, from `rocprofv3 --pmc
 # FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this script (each scaled by what the counter reads for a plain copy of
 # known size): profiles/k_phase_counters_all_configs.md.  A figure from those runs, not a measurement of this run.
-KPHASE_TRAFFIC_PER_ALGORITHMIC_BYTE = {"resnet20": 2.53, "mlp": 1.78, "vgg11": 0.88, "wide": 1.26, "resnet50": 1.64}
+KPHASE_TRAFFIC_PER_ALGORITHMIC_BYTE = {"resnet20": 2.59, "mlp": 1.76, "vgg11": 0.88, "wide": 1.26, "resnet50": 1.64}
 TRAFFIC_SOURCE = "profiles/k_phase_counters_all_configs.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over this command; not measured by this run)"
 UPDATE_TRAFFIC_PER_ALGORITHMIC_BYTE = 1.0   # profiles/k_update_flat_1GiB_arrays.md
 
