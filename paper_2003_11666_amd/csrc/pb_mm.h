@@ -1,7 +1,7 @@
-// Dense matrix-product core for 1x1 layers of stride 1 in networks tiled for
+// Dense matrix-product core for the 1x1 layers of networks tiled for
 // throughput (fp32, v_mfma_f32_16x16x4_f32).
 //
-// A 1x1 layer on one sample is a plain matrix product over the flattened map:
+// A 1x1 layer of stride 1 on one sample is a plain matrix product over the flattened map:
 //   forward           Y[K x P]  = W[K x C] * X[C x P]
 //   backward data     dX[C x P] = W^T[C x K] * dY[K x P]
 //   backward weights  gW[K x C] = dY[K x P] * X^T[P x C]
@@ -19,6 +19,13 @@
 // supply entry 4 kq + u.  An operand whose rows run along the reduction (W
 // forward, dY and X backward weights) then gives a lane its values for all four
 // MFMAs of a block in one 16-byte LDS read.
+//
+// Operands that cannot be copied 16 bytes at a time -- maps whose pixel count
+// is not a multiple of 4, the input of a projection of stride 2 -- are
+// gathered element by element with the same tiles; the geometry is that of a
+// general k x k layer (reduction or columns over (channel, tap)), which the
+// planner uses for k > 1 only on request: a tap-by-tap gather fetches nine
+// times what a patch in LDS serves once.
 //
 // Included by pb_gemm.h.
 #pragma once
