@@ -285,10 +285,14 @@ __device__ __forceinline__ void step_mm_t(const LDesc& d, int tile_, int t, lflo
           for (int j = 0; j < NI; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[sb][i][u], b[sb][j][u], acc[i][j], 0, 0, 0);
     };
+    // the second block's operands come from LDS while the first block's MFMAs run (each MFMA is followed by a share
+    // of the reads)
     fetch(IConst<0>(), 0);
-    fetch(IConst<1>(), 1);
     __builtin_amdgcn_sched_barrier(0);
+    fetch(IConst<1>(), 1);
     mfmas(IConst<0>());
+    sched_interleave<4 * MI * NI, 0>();
+    __builtin_amdgcn_sched_barrier(0);
     mfmas(IConst<1>());
     __builtin_amdgcn_sched_barrier(0);
     if (more) commit(nxt);
