@@ -118,3 +118,17 @@ def test_split_test_network_really_splits():
     parts = [int(re.search(r"chunks (\d+)/(\d+)", r[4]).group(2)) for r in rows]
     assert max(parts) >= 4
 
+
+
+def test_planner_settings_struct_matches_the_header():
+    """The binding's copy of pb_tuning has the header's fields, in the header's order."""
+    from paper_2003_11666_amd import binding as B
+    text = open(os.path.join(ROOT, "include", "pb.h")).read()
+    body = re.search(r"typedef struct \{([^}]*)\} pb_tuning;", text, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if decl:
+            names += [n.strip() for n in decl.split(None, 1)[1].split(",")]
+    assert names == [f[0] for f in B._Tuning._fields_]
