@@ -1704,7 +1704,7 @@ void order_steps(std::vector<std::pair<int, StepDesc>>& tagged, bool one_launch 
       const int k = p.second.kind;
       if (k == K_GEMM || k == K_DOT_FWD || k == K_DOT_BWD_X) gemm_us[p.first] += step_cost(p.second) * 1e-3 * p.second.ntiles / 512.0;
     }
-    for (double u : gemm_us) upd_last.push_back(u < 100.0);
+    for (double u : gemm_us) upd_last.push_back(u > 0.0 && u < 100.0);   // (a phase without tiles: in the order of cost)
   }
   std::stable_sort(tagged.begin(), tagged.end(),
                    [&](const std::pair<int, StepDesc>& x, const std::pair<int, StepDesc>& y) {
